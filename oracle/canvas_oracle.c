@@ -1,0 +1,689 @@
+/*
+ * canvas_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, fp64 CPU interpreter of micro-DAG kernels built from the
+ * fine-grained primitives of "Canvas: End-to-End Kernel Architecture Search"
+ * (Section 5, Table "Three classes of fine-grained primitives").  It exists
+ * only so that tests, the smoke check and the benchmark's CPU-baseline leg can
+ * compare the GPU library against the primitive definitions written out
+ * directly.  It shares no code, header, table or helper with the GPU library
+ * and must never be called from the product path.
+ *
+ * Every tensor is fully materialised per image as [C, T, H, W] (T = number of
+ * unfolded taps, 1 when none), every primitive is its definition as a loop
+ * nest, every backward rule is the exact vector-Jacobian product of that
+ * definition.  Images of a batch are independent (the paper's shapes are
+ * per-image, Section 4); only the FC weight gradients sum over the batch.
+ * The only parallelism is an OpenMP loop over the batch index.
+ *
+ * Parity pins (see tests/test_oracle_*.py): brute-force direct (grouped)
+ * convolution and its gradients, adjoint dot-product identities, central
+ * finite differences, closed forms and invariants.  No function here is
+ * "parity unpinned".
+ *
+ * Serialized DAG ("blob"), UTF-8 text, one node per line, topological order:
+ *     canvas-dag 1
+ *     %1 = unfold %0 kh=3 kw=3
+ *     %2 = fc %1 groups=8 out=64
+ *     %3 = unary %2 op=gelu            (relu | abs | gelu | expclip lo=.. hi=..)
+ *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
+ *     %5 = binary %0 %4 op=mul         (first operand LHS, second RHS; add | mul)
+ *     %6 = fold %5 op=avg              (sum | avg | max)
+ *     %7 = softmax %6 axis=C           (C | T)
+ *     output %7
+ * %0 is the input [N, C, H, W].
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define MAX_NODES 64
+
+enum { OP_INPUT = 0, OP_UNFOLD, OP_SHIFT, OP_FC, OP_UNARY, OP_BINARY, OP_SOFTMAX, OP_FOLD };
+enum { UN_RELU = 0, UN_ABS, UN_GELU, UN_EXPCLIP };
+enum { BIN_ADD = 0, BIN_MUL };
+enum { AXIS_C = 0, AXIS_T };
+enum { FOLD_SUM = 0, FOLD_AVG, FOLD_MAX };
+
+typedef struct {
+    int op;
+    int a, b;           /* operand node ids (binary: a = LHS, b = RHS) */
+    int kh, kw;         /* unfold */
+    int dh, dw, c0, c1; /* shift */
+    int groups, out;    /* fc */
+    int kind;           /* unary / binary / fold kind, softmax axis */
+    double lo, hi;      /* expclip */
+    int C, T;           /* inferred shape [C, T, H, W] */
+    int widx;           /* fc: index into the weight list */
+} Node;
+
+typedef struct {
+    int n_nodes;        /* including node 0 (the input) */
+    int out;            /* output node id */
+    int n_weights;
+    int H, W;
+    Node node[MAX_NODES];
+} Dag;
+
+static void set_err(char *err, size_t errlen, const char *msg, int line) {
+    if (err && errlen) snprintf(err, errlen, "line %d: %s", line, msg);
+}
+
+/* ---------------------------------------------------------------- parsing */
+
+static int parse_ref(const char *tok, int *id) {
+    char *end;
+    long v;
+    if (tok[0] != '%') return 0;
+    v = strtol(tok + 1, &end, 10);
+    if (end == tok + 1 || *end) return 0;
+    *id = (int)v;
+    return 1;
+}
+
+static const char *find_attr(char **tok, int ntok, const char *key) {
+    size_t kl = strlen(key);
+    int i;
+    for (i = 0; i < ntok; i++)
+        if (!strncmp(tok[i], key, kl) && tok[i][kl] == '=') return tok[i] + kl + 1;
+    return NULL;
+}
+
+static int attr_int(char **tok, int ntok, const char *key, int *out) {
+    const char *v = find_attr(tok, ntok, key);
+    char *end;
+    long x;
+    if (!v) return 0;
+    x = strtol(v, &end, 10);
+    if (end == v || *end) return -1;
+    *out = (int)x;
+    return 1;
+}
+
+static int attr_dbl(char **tok, int ntok, const char *key, double *out) {
+    const char *v = find_attr(tok, ntok, key);
+    char *end;
+    double x;
+    if (!v) return 0;
+    x = strtod(v, &end);
+    if (end == v || *end) return -1;
+    *out = x;
+    return 1;
+}
+
+/* Shape rule of the Broadcast primitive (Section 5, "Blending primitives"):
+ * the dim lists [C, (T)] of both sides (H, W always common, batch outside) are
+ * stripped of a common prefix, then of a common suffix; the product of what is
+ * left of the LHS must divide the product of what is left of the RHS.  A tap
+ * dim of size 1 is the same as no tap dim.  Returns 1 when legal. */
+static int broadcast_legal(int CL, int TL, int CR, int TR) {
+    if (CL == CR) return TR % TL == 0;
+    return ((long)CR * TR) % ((long)CL * TL) == 0;
+}
+
+/* Index map of the Broadcast primitive: which LHS element (cl, tl) is applied
+ * to RHS element (c, t).  The LHS is replicated ("tiled") along the flattened
+ * non-common dims with its innermost dims aligned to those of the RHS, which is
+ * what the Involution example of Section 5 requires ([K*K] onto [C/G, K, K]). */
+static void broadcast_index(int CL, int TL, int CR, int TR, int c, int t, int *cl, int *tl) {
+    if (CL == CR) {
+        *cl = c;
+        *tl = t % TL;
+    } else {
+        long j = ((long)c * TR + t) % ((long)CL * TL);
+        *cl = (int)(j / TL);
+        *tl = (int)(j % TL);
+    }
+    (void)CR;
+}
+
+static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d, char *err, size_t errlen) {
+    char *buf = (char *)malloc(len + 1), *save1 = NULL, *line;
+    int lineno = 0, seen_header = 0, seen_output = 0, rc = -1;
+    if (!buf) return -1;
+    memcpy(buf, blob, len);
+    buf[len] = 0;
+    memset(d, 0, sizeof *d);
+    d->H = H;
+    d->W = W;
+    d->n_nodes = 1;
+    d->node[0].op = OP_INPUT;
+    d->node[0].C = C0;
+    d->node[0].T = 1;
+    d->out = -1;
+    for (line = strtok_r(buf, "\n", &save1); line; line = strtok_r(NULL, "\n", &save1)) {
+        char *tok[32], *save2 = NULL, *t;
+        int ntok = 0, id;
+        Node *nd;
+        lineno++;
+        for (t = strtok_r(line, " \t\r", &save2); t && ntok < 32; t = strtok_r(NULL, " \t\r", &save2)) tok[ntok++] = t;
+        if (ntok == 0 || tok[0][0] == '#') continue;
+        if (!seen_header) {
+            if (ntok != 2 || strcmp(tok[0], "canvas-dag") || strcmp(tok[1], "1")) {
+                set_err(err, errlen, "missing header 'canvas-dag 1'", lineno);
+                goto done;
+            }
+            seen_header = 1;
+            continue;
+        }
+        if (seen_output) { set_err(err, errlen, "text after output", lineno); goto done; }
+        if (!strcmp(tok[0], "output")) {
+            if (ntok != 2 || !parse_ref(tok[1], &id) || id < 0 || id >= d->n_nodes) {
+                set_err(err, errlen, "bad output", lineno);
+                goto done;
+            }
+            d->out = id;
+            seen_output = 1;
+            continue;
+        }
+        if (ntok < 4 || !parse_ref(tok[0], &id) || strcmp(tok[1], "=")) {
+            set_err(err, errlen, "expected '%k = op ...'", lineno);
+            goto done;
+        }
+        if (id != d->n_nodes || id >= MAX_NODES) { set_err(err, errlen, "node ids must be 1,2,3,...", lineno); goto done; }
+        nd = &d->node[id];
+        memset(nd, 0, sizeof *nd);
+        nd->widx = -1;
+        if (!parse_ref(tok[3], &nd->a) || nd->a < 0 || nd->a >= id) { set_err(err, errlen, "bad operand", lineno); goto done; }
+        {
+            const Node *A = &d->node[nd->a];
+            const char *opn = tok[2];
+            if (!strcmp(opn, "unfold")) {
+                nd->op = OP_UNFOLD;
+                if (attr_int(tok, ntok, "kh", &nd->kh) != 1 || attr_int(tok, ntok, "kw", &nd->kw) != 1 ||
+                    nd->kh < 1 || nd->kw < 1 || nd->kh % 2 == 0 || nd->kw % 2 == 0) {
+                    set_err(err, errlen, "unfold needs odd kh, kw >= 1", lineno);
+                    goto done;
+                }
+                nd->C = A->C;
+                nd->T = A->T * nd->kh * nd->kw;
+            } else if (!strcmp(opn, "shift")) {
+                nd->op = OP_SHIFT;
+                nd->c0 = 0;
+                nd->c1 = A->C;
+                if (attr_int(tok, ntok, "dh", &nd->dh) != 1 || attr_int(tok, ntok, "dw", &nd->dw) != 1 ||
+                    attr_int(tok, ntok, "c0", &nd->c0) < 0 || attr_int(tok, ntok, "c1", &nd->c1) < 0 ||
+                    nd->c0 < 0 || nd->c1 > A->C || nd->c0 > nd->c1) {
+                    set_err(err, errlen, "bad shift attributes", lineno);
+                    goto done;
+                }
+                nd->C = A->C;
+                nd->T = A->T;
+            } else if (!strcmp(opn, "fc")) {
+                nd->op = OP_FC;
+                if (attr_int(tok, ntok, "groups", &nd->groups) != 1 || attr_int(tok, ntok, "out", &nd->out) != 1 ||
+                    nd->groups < 1 || nd->out < 1 || A->C % nd->groups || nd->out % nd->groups) {
+                    set_err(err, errlen, "fc needs groups | C and groups | out", lineno);
+                    goto done;
+                }
+                nd->C = nd->out;
+                nd->T = 1;
+                nd->widx = d->n_weights++;
+            } else if (!strcmp(opn, "unary")) {
+                const char *k2 = find_attr(tok, ntok, "op");
+                nd->op = OP_UNARY;
+                if (!k2) { set_err(err, errlen, "unary needs op=", lineno); goto done; }
+                if (!strcmp(k2, "relu")) nd->kind = UN_RELU;
+                else if (!strcmp(k2, "abs")) nd->kind = UN_ABS;
+                else if (!strcmp(k2, "gelu")) nd->kind = UN_GELU;
+                else if (!strcmp(k2, "expclip")) {
+                    nd->kind = UN_EXPCLIP;
+                    if (attr_dbl(tok, ntok, "lo", &nd->lo) != 1 || attr_dbl(tok, ntok, "hi", &nd->hi) != 1 || !(nd->lo < nd->hi)) {
+                        set_err(err, errlen, "expclip needs lo < hi", lineno);
+                        goto done;
+                    }
+                } else { set_err(err, errlen, "unknown unary op", lineno); goto done; }
+                nd->C = A->C;
+                nd->T = A->T;
+            } else if (!strcmp(opn, "binary")) {
+                const char *k2 = find_attr(tok, ntok, "op");
+                const Node *B;
+                nd->op = OP_BINARY;
+                if (ntok < 5 || !parse_ref(tok[4], &nd->b) || nd->b < 0 || nd->b >= id || !k2) {
+                    set_err(err, errlen, "binary needs two operands and op=", lineno);
+                    goto done;
+                }
+                if (!strcmp(k2, "add")) nd->kind = BIN_ADD;
+                else if (!strcmp(k2, "mul")) nd->kind = BIN_MUL;
+                else { set_err(err, errlen, "unknown binary op", lineno); goto done; }
+                B = &d->node[nd->b];
+                if (!broadcast_legal(A->C, A->T, B->C, B->T)) {
+                    set_err(err, errlen, "broadcast: LHS size does not divide RHS size", lineno);
+                    goto done;
+                }
+                nd->C = B->C;
+                nd->T = B->T;
+            } else if (!strcmp(opn, "softmax")) {
+                const char *k2 = find_attr(tok, ntok, "axis");
+                nd->op = OP_SOFTMAX;
+                if (k2 && !strcmp(k2, "C")) nd->kind = AXIS_C;
+                else if (k2 && !strcmp(k2, "T")) nd->kind = AXIS_T;
+                else { set_err(err, errlen, "softmax needs axis=C|T", lineno); goto done; }
+                nd->C = A->C;
+                nd->T = A->T;
+            } else if (!strcmp(opn, "fold")) {
+                const char *k2 = find_attr(tok, ntok, "op");
+                nd->op = OP_FOLD;
+                if (k2 && !strcmp(k2, "sum")) nd->kind = FOLD_SUM;
+                else if (k2 && !strcmp(k2, "avg")) nd->kind = FOLD_AVG;
+                else if (k2 && !strcmp(k2, "max")) nd->kind = FOLD_MAX;
+                else { set_err(err, errlen, "fold needs op=sum|avg|max", lineno); goto done; }
+                nd->C = A->C;
+                nd->T = 1;
+            } else {
+                set_err(err, errlen, "unknown op", lineno);
+                goto done;
+            }
+        }
+        d->n_nodes++;
+    }
+    if (!seen_header) { set_err(err, errlen, "empty blob", lineno); goto done; }
+    if (d->out < 0) { set_err(err, errlen, "missing output", lineno); goto done; }
+    rc = 0;
+done:
+    free(buf);
+    return rc;
+}
+
+/* ------------------------------------------------------- forward, one image */
+
+static size_t node_numel(const Dag *d, int k) { return (size_t)d->node[k].C * d->node[k].T * d->H * d->W; }
+
+/* Unfold (Section 5): U(c, kh, kw, h, w) = I(c, h + kh, w + kw) with the window
+ * centred on the pixel (kh, kw run over [-K/2, K/2]) and zeros outside the
+ * image, the reading under which Unfold followed by FC is a same-size
+ * convolution.  New taps are the innermost channel dim: t = t_in*KH*KW + kh*KW + kw. */
+static void fwd_unfold(const Dag *d, const Node *nd, const double *in, double *out) {
+    const Node *A = &d->node[nd->a];
+    int H = d->H, W = d->W, K = nd->kh * nd->kw;
+    int c, ti, kh, kw, h, w;
+    for (c = 0; c < A->C; c++)
+        for (ti = 0; ti < A->T; ti++)
+            for (kh = 0; kh < nd->kh; kh++)
+                for (kw = 0; kw < nd->kw; kw++) {
+                    int t = ti * K + kh * nd->kw + kw;
+                    for (h = 0; h < H; h++)
+                        for (w = 0; w < W; w++) {
+                            int hs = h + kh - nd->kh / 2, ws = w + kw - nd->kw / 2;
+                            double v = 0.0;
+                            if (hs >= 0 && hs < H && ws >= 0 && ws < W) v = in[(((size_t)c * A->T + ti) * H + hs) * W + ws];
+                            out[(((size_t)c * nd->T + t) * H + h) * W + w] = v;
+                        }
+                }
+}
+
+/* Shift (Section 5): S(c, h, w) = I(c, h + dh, w + dw) on channels [c0, c1),
+ * zeros where the source pixel is outside; other channels pass through. */
+static void fwd_shift(const Dag *d, const Node *nd, const double *in, double *out) {
+    int H = d->H, W = d->W, c, t, h, w;
+    for (c = 0; c < nd->C; c++)
+        for (t = 0; t < nd->T; t++)
+            for (h = 0; h < H; h++)
+                for (w = 0; w < W; w++) {
+                    size_t base = ((size_t)c * nd->T + t) * H;
+                    double v;
+                    if (c >= nd->c0 && c < nd->c1) {
+                        int hs = h + nd->dh, ws = w + nd->dw;
+                        v = (hs >= 0 && hs < H && ws >= 0 && ws < W) ? in[(base + hs) * W + ws] : 0.0;
+                    } else {
+                        v = in[(base + h) * W + w];
+                    }
+                    out[(base + h) * W + w] = v;
+                }
+}
+
+/* Fully-connected (Section 5): every channel dim (channels of the group and all
+ * taps) is contracted into a new channel dim; groups are kept apart; no bias.
+ * y[g*Og + o, p] = sum_{c', t} Wt[g, o, c'*T + t] * x[g*Cg + c', t, p]. */
+static void fwd_fc(const Dag *d, const Node *nd, const double *in, const double *wt, double *out) {
+    const Node *A = &d->node[nd->a];
+    int P = d->H * d->W, G = nd->groups, Cg = A->C / G, Og = nd->out / G, K = Cg * A->T;
+    int g, o, i, p;
+    for (g = 0; g < G; g++)
+        for (o = 0; o < Og; o++) {
+            double *yrow = out + ((size_t)g * Og + o) * P;
+            for (p = 0; p < P; p++) yrow[p] = 0.0;
+            for (i = 0; i < K; i++) {
+                double wv = wt[((size_t)g * Og + o) * K + i];
+                const double *xrow = in + ((size_t)g * K + i) * P; /* (g*Cg + c')*T + t == g*K + i */
+                for (p = 0; p < P; p++) yrow[p] += wv * xrow[p];
+            }
+        }
+}
+
+static double gelu_cdf(double x) { return 0.5 * (1.0 + erf(x * 0.70710678118654752440)); }
+static double gelu_pdf(double x) { return 0.39894228040143267794 * exp(-0.5 * x * x); }
+
+static void fwd_unary(const Dag *d, const Node *nd, int k, const double *in, double *out) {
+    size_t n = node_numel(d, k), j;
+    for (j = 0; j < n; j++) {
+        double x = in[j], y = 0.0;
+        switch (nd->kind) {
+        case UN_RELU: y = x > 0.0 ? x : 0.0; break;
+        case UN_ABS: y = fabs(x); break;
+        case UN_GELU: y = x * gelu_cdf(x); break;
+        case UN_EXPCLIP: y = exp(x < nd->lo ? nd->lo : (x > nd->hi ? nd->hi : x)); break;
+        }
+        out[j] = y;
+    }
+}
+
+static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const double *rhs, double *out) {
+    const Node *L = &d->node[nd->a];
+    int P = d->H * d->W, c, t, p, cl, tl;
+    for (c = 0; c < nd->C; c++)
+        for (t = 0; t < nd->T; t++) {
+            const double *lrow, *rrow = rhs + ((size_t)c * nd->T + t) * P;
+            double *orow = out + ((size_t)c * nd->T + t) * P;
+            broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
+            lrow = lhs + ((size_t)cl * L->T + tl) * P;
+            for (p = 0; p < P; p++) orow[p] = nd->kind == BIN_ADD ? lrow[p] + rrow[p] : lrow[p] * rrow[p];
+        }
+}
+
+/* Softmax along one axis (channels or taps), every other index fixed. */
+static void fwd_softmax(const Dag *d, const Node *nd, const double *in, double *out) {
+    int P = d->H * d->W, C = nd->C, T = nd->T;
+    int len = nd->kind == AXIS_C ? C : T, outer = nd->kind == AXIS_C ? T : C;
+    int o, p, k;
+    for (o = 0; o < outer; o++)
+        for (p = 0; p < P; p++) {
+            double m = -INFINITY, s = 0.0;
+            for (k = 0; k < len; k++) {
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                if (in[idx] > m) m = in[idx];
+            }
+            for (k = 0; k < len; k++) {
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                out[idx] = exp(in[idx] - m);
+                s += out[idx];
+            }
+            for (k = 0; k < len; k++) {
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                out[idx] /= s;
+            }
+        }
+}
+
+/* Folding over the tap dim: sum, average or max; the tap dim disappears. */
+static void fwd_fold(const Dag *d, const Node *nd, const double *in, double *out) {
+    const Node *A = &d->node[nd->a];
+    int P = d->H * d->W, T = A->T, c, t, p;
+    for (c = 0; c < nd->C; c++)
+        for (p = 0; p < P; p++) {
+            double acc = in[((size_t)c * T) * P + p];
+            for (t = 1; t < T; t++) {
+                double v = in[((size_t)c * T + t) * P + p];
+                if (nd->kind == FOLD_MAX) { if (v > acc) acc = v; }
+                else acc += v;
+            }
+            if (nd->kind == FOLD_AVG) acc /= T;
+            out[(size_t)c * P + p] = acc;
+        }
+}
+
+/* ------------------------------------------------------ backward, one image */
+/* Each routine ADDS the contribution of node nd to the gradient(s) of its
+ * operand(s); a tensor consumed several times thus receives the sum. */
+
+static void bwd_unfold(const Dag *d, const Node *nd, const double *gout, double *gin) {
+    const Node *A = &d->node[nd->a];
+    int H = d->H, W = d->W, K = nd->kh * nd->kw;
+    int c, ti, kh, kw, h, w;
+    for (c = 0; c < A->C; c++)
+        for (ti = 0; ti < A->T; ti++)
+            for (kh = 0; kh < nd->kh; kh++)
+                for (kw = 0; kw < nd->kw; kw++) {
+                    int t = ti * K + kh * nd->kw + kw;
+                    for (h = 0; h < H; h++)
+                        for (w = 0; w < W; w++) {
+                            int hs = h + kh - nd->kh / 2, ws = w + kw - nd->kw / 2;
+                            if (hs >= 0 && hs < H && ws >= 0 && ws < W)
+                                gin[(((size_t)c * A->T + ti) * H + hs) * W + ws] += gout[(((size_t)c * nd->T + t) * H + h) * W + w];
+                        }
+                }
+}
+
+static void bwd_shift(const Dag *d, const Node *nd, const double *gout, double *gin) {
+    int H = d->H, W = d->W, c, t, h, w;
+    for (c = 0; c < nd->C; c++)
+        for (t = 0; t < nd->T; t++)
+            for (h = 0; h < H; h++)
+                for (w = 0; w < W; w++) {
+                    size_t base = ((size_t)c * nd->T + t) * H;
+                    if (c >= nd->c0 && c < nd->c1) {
+                        int hs = h + nd->dh, ws = w + nd->dw;
+                        if (hs >= 0 && hs < H && ws >= 0 && ws < W) gin[(base + hs) * W + ws] += gout[(base + h) * W + w];
+                    } else {
+                        gin[(base + h) * W + w] += gout[(base + h) * W + w];
+                    }
+                }
+}
+
+static void bwd_fc(const Dag *d, const Node *nd, const double *in, const double *wt, const double *gout, double *gin, double *gw) {
+    const Node *A = &d->node[nd->a];
+    int P = d->H * d->W, G = nd->groups, Cg = A->C / G, Og = nd->out / G, K = Cg * A->T;
+    int g, o, i, p;
+    for (g = 0; g < G; g++)
+        for (o = 0; o < Og; o++) {
+            const double *grow = gout + ((size_t)g * Og + o) * P;
+            for (i = 0; i < K; i++) {
+                size_t wi = ((size_t)g * Og + o) * K + i;
+                const double *xrow = in + ((size_t)g * K + i) * P;
+                double *girow = gin + ((size_t)g * K + i) * P;
+                double wv = wt[wi], acc = 0.0;
+                for (p = 0; p < P; p++) {
+                    girow[p] += wv * grow[p];
+                    acc += grow[p] * xrow[p];
+                }
+                gw[wi] += acc;
+            }
+        }
+}
+
+static void bwd_unary(const Dag *d, const Node *nd, int k, const double *in, const double *out, const double *gout, double *gin) {
+    size_t n = node_numel(d, k), j;
+    for (j = 0; j < n; j++) {
+        double x = in[j], dv = 0.0;
+        switch (nd->kind) {
+        case UN_RELU: dv = x > 0.0 ? 1.0 : 0.0; break;
+        case UN_ABS: dv = x > 0.0 ? 1.0 : (x < 0.0 ? -1.0 : 0.0); break;
+        case UN_GELU: dv = gelu_cdf(x) + x * gelu_pdf(x); break;
+        case UN_EXPCLIP: dv = (x > nd->lo && x < nd->hi) ? out[j] : 0.0; break;
+        }
+        gin[j] += gout[j] * dv;
+    }
+}
+
+static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const double *rhs, const double *gout, double *glhs, double *grhs) {
+    const Node *L = &d->node[nd->a];
+    int P = d->H * d->W, c, t, p, cl, tl;
+    for (c = 0; c < nd->C; c++)
+        for (t = 0; t < nd->T; t++) {
+            size_t ro = ((size_t)c * nd->T + t) * P, lo;
+            broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
+            lo = ((size_t)cl * L->T + tl) * P;
+            for (p = 0; p < P; p++) {
+                if (nd->kind == BIN_ADD) {
+                    glhs[lo + p] += gout[ro + p];
+                    grhs[ro + p] += gout[ro + p];
+                } else {
+                    glhs[lo + p] += gout[ro + p] * rhs[ro + p];
+                    grhs[ro + p] += gout[ro + p] * lhs[lo + p];
+                }
+            }
+        }
+}
+
+static void bwd_softmax(const Dag *d, const Node *nd, const double *out, const double *gout, double *gin) {
+    int P = d->H * d->W, C = nd->C, T = nd->T;
+    int len = nd->kind == AXIS_C ? C : T, outer = nd->kind == AXIS_C ? T : C;
+    int o, p, k;
+    for (o = 0; o < outer; o++)
+        for (p = 0; p < P; p++) {
+            double dot = 0.0;
+            for (k = 0; k < len; k++) {
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                dot += gout[idx] * out[idx];
+            }
+            for (k = 0; k < len; k++) {
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                gin[idx] += out[idx] * (gout[idx] - dot);
+            }
+        }
+}
+
+/* Max takes the gradient to the first maximal tap (lowest t) only. */
+static void bwd_fold(const Dag *d, const Node *nd, const double *in, const double *gout, double *gin) {
+    const Node *A = &d->node[nd->a];
+    int P = d->H * d->W, T = A->T, c, t, p;
+    for (c = 0; c < nd->C; c++)
+        for (p = 0; p < P; p++) {
+            double g = gout[(size_t)c * P + p];
+            if (nd->kind == FOLD_MAX) {
+                int best = 0;
+                for (t = 1; t < T; t++)
+                    if (in[((size_t)c * T + t) * P + p] > in[((size_t)c * T + best) * P + p]) best = t;
+                gin[((size_t)c * T + best) * P + p] += g;
+            } else {
+                if (nd->kind == FOLD_AVG) g /= T;
+                for (t = 0; t < T; t++) gin[((size_t)c * T + t) * P + p] += g;
+            }
+        }
+}
+
+/* ------------------------------------------------------------- entry points */
+
+/* Shape inference only.  shapes: n_nodes rows of [C, T, H, W]; wshapes:
+ * n_weights rows of [G, C_out/G, (C_in/G)*T].  Returns 0, or -1 with err set. */
+int canvas_oracle_infer(const char *blob, size_t len, const int64_t in_shape[4], int max_nodes, int64_t *shapes,
+                        int *n_nodes, int *out_node, int max_weights, int64_t *wshapes, int *n_weights, char *err,
+                        size_t errlen) {
+    Dag d;
+    int k;
+    if (parse_dag(blob, len, (int)in_shape[1], (int)in_shape[2], (int)in_shape[3], &d, err, errlen)) return -1;
+    if (d.n_nodes > max_nodes || d.n_weights > max_weights) { set_err(err, errlen, "too many nodes for caller", 0); return -1; }
+    for (k = 0; k < d.n_nodes; k++) {
+        shapes[4 * k + 0] = d.node[k].C;
+        shapes[4 * k + 1] = d.node[k].T;
+        shapes[4 * k + 2] = d.H;
+        shapes[4 * k + 3] = d.W;
+        if (d.node[k].op == OP_FC) {
+            const Node *A = &d.node[d.node[k].a];
+            int wi = d.node[k].widx;
+            wshapes[3 * wi + 0] = d.node[k].groups;
+            wshapes[3 * wi + 1] = d.node[k].out / d.node[k].groups;
+            wshapes[3 * wi + 2] = (int64_t)(A->C / d.node[k].groups) * A->T;
+        }
+    }
+    *n_nodes = d.n_nodes;
+    *out_node = d.out;
+    *n_weights = d.n_weights;
+    return 0;
+}
+
+/* Forward (and, when dy != NULL, backward) of the whole batch.
+ *   x        [N, C, H, W] fp64, weights[k] [G, Og, K] fp64 in FC-node order
+ *   y        [N, C_out, T_out, H, W]; dy same shape; dx like x; dw[k] like weights[k]
+ * Returns the number of OpenMP threads used (>= 1), or -1 with err set. */
+int canvas_oracle_run(const char *blob, size_t len, const int64_t in_shape[4], const double *x,
+                      const double *const *weights, int n_weights, const double *dy, double *y, double *dx,
+                      double *const *dw, int n_threads, char *err, size_t errlen) {
+    Dag d;
+    int N = (int)in_shape[0], k, nthr = 1, n, failed = 0;
+    size_t wn[MAX_NODES], xn, yn;
+    double **dwacc = NULL;
+    if (parse_dag(blob, len, (int)in_shape[1], (int)in_shape[2], (int)in_shape[3], &d, err, errlen)) return -1;
+    if (n_weights != d.n_weights) { set_err(err, errlen, "wrong number of weight tensors", 0); return -1; }
+    for (k = 0; k < d.n_nodes; k++)
+        if (d.node[k].op == OP_FC) {
+            const Node *A = &d.node[d.node[k].a];
+            wn[d.node[k].widx] = (size_t)d.node[k].out * (A->C / d.node[k].groups) * A->T;
+        }
+    xn = node_numel(&d, 0);
+    yn = node_numel(&d, d.out);
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+    nthr = omp_get_max_threads();
+    if (nthr > N && N > 0) nthr = N;
+    if (nthr < 1) nthr = 1;
+#endif
+    if (dy) {
+        int t;
+        dwacc = (double **)calloc((size_t)nthr * (d.n_weights + 1), sizeof(double *));
+        for (t = 0; t < nthr; t++)
+            for (k = 0; k < d.n_weights; k++) dwacc[(size_t)t * d.n_weights + k] = (double *)calloc(wn[k], sizeof(double));
+    }
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(nthr)
+#endif
+    for (n = 0; n < N; n++) {
+        double *val[MAX_NODES], *grad[MAX_NODES];
+        int tid = 0, j;
+#ifdef _OPENMP
+        tid = omp_get_thread_num();
+#endif
+        memset(val, 0, sizeof val);
+        memset(grad, 0, sizeof grad);
+        val[0] = (double *)(x + (size_t)n * xn);
+        for (j = 1; j < d.n_nodes; j++) {
+            const Node *nd = &d.node[j];
+            val[j] = (double *)malloc(node_numel(&d, j) * sizeof(double));
+            if (!val[j]) { failed = 1; break; }
+            switch (nd->op) {
+            case OP_UNFOLD: fwd_unfold(&d, nd, val[nd->a], val[j]); break;
+            case OP_SHIFT: fwd_shift(&d, nd, val[nd->a], val[j]); break;
+            case OP_FC: fwd_fc(&d, nd, val[nd->a], weights[nd->widx], val[j]); break;
+            case OP_UNARY: fwd_unary(&d, nd, j, val[nd->a], val[j]); break;
+            case OP_BINARY: fwd_binary(&d, nd, val[nd->a], val[nd->b], val[j]); break;
+            case OP_SOFTMAX: fwd_softmax(&d, nd, val[nd->a], val[j]); break;
+            case OP_FOLD: fwd_fold(&d, nd, val[nd->a], val[j]); break;
+            }
+        }
+        if (!failed) memcpy(y + (size_t)n * yn, val[d.out], yn * sizeof(double));
+        if (dy && !failed) {
+            for (j = 0; j < d.n_nodes; j++) {
+                grad[j] = (double *)calloc(node_numel(&d, j), sizeof(double));
+                if (!grad[j]) failed = 1;
+            }
+            if (!failed) {
+                memcpy(grad[d.out], dy + (size_t)n * yn, yn * sizeof(double));
+                for (j = d.n_nodes - 1; j >= 1; j--) {
+                    const Node *nd = &d.node[j];
+                    switch (nd->op) {
+                    case OP_UNFOLD: bwd_unfold(&d, nd, grad[j], grad[nd->a]); break;
+                    case OP_SHIFT: bwd_shift(&d, nd, grad[j], grad[nd->a]); break;
+                    case OP_FC: bwd_fc(&d, nd, val[nd->a], weights[nd->widx], grad[j], grad[nd->a], dwacc[(size_t)tid * d.n_weights + nd->widx]); break;
+                    case OP_UNARY: bwd_unary(&d, nd, j, val[nd->a], val[j], grad[j], grad[nd->a]); break;
+                    case OP_BINARY: bwd_binary(&d, nd, val[nd->a], val[nd->b], grad[j], grad[nd->a], grad[nd->b]); break;
+                    case OP_SOFTMAX: bwd_softmax(&d, nd, val[j], grad[j], grad[nd->a]); break;
+                    case OP_FOLD: bwd_fold(&d, nd, val[nd->a], grad[j], grad[nd->a]); break;
+                    }
+                }
+                memcpy(dx + (size_t)n * xn, grad[0], xn * sizeof(double));
+            }
+            for (j = 0; j < d.n_nodes; j++) free(grad[j]);
+        }
+        for (j = 1; j < d.n_nodes; j++) free(val[j]);
+    }
+    if (dy) {
+        int t;
+        for (k = 0; k < d.n_weights; k++) {
+            size_t i;
+            for (i = 0; i < wn[k]; i++) dw[k][i] = 0.0;
+            for (t = 0; t < nthr; t++) {
+                const double *src = dwacc[(size_t)t * d.n_weights + k];
+                for (i = 0; i < wn[k]; i++) dw[k][i] += src[i];
+                free(dwacc[(size_t)t * d.n_weights + k]);
+            }
+        }
+        free(dwacc);
+    }
+    if (failed) { set_err(err, errlen, "out of memory", 0); return -1; }
+    return nthr;
+}

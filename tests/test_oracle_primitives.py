@@ -1,0 +1,360 @@
+"""Pins every primitive of the oracle (forward and backward) to identities,
+closed forms, adjoint dot-products and central finite differences.
+
+Primitive definitions: Section 5 of the paper (table of fine-grained primitives).
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2304_07741_amd import workloads as wl
+
+H_ = wl.HEADER
+
+
+def run1(oracle, body, x, weights=(), dy=None):
+    return oracle.run(H_ + body, x, list(weights), dy)
+
+
+# ------------------------------------------------------------------- shift
+
+def test_zero_shift_is_identity(oracle):
+    x = np.random.default_rng(0).standard_normal((2, 4, 5, 6))
+    r = run1(oracle, "%1 = shift %0 dh=0 dw=0\noutput %1\n", x)
+    np.testing.assert_array_equal(r["y"], x)
+
+
+@pytest.mark.parametrize("dh,dw", [(1, 0), (-1, 0), (0, 1), (0, -1), (2, 0), (0, -2)])
+def test_shift_direction_and_zero_fill(oracle, dh, dw):
+    """S(c,h,w) = I(c,h+dh,w+dw): the output at (h,w) reads the input at (h+dh,w+dw)."""
+    x = np.random.default_rng(1).standard_normal((1, 3, 6, 7))
+    r = run1(oracle, f"%1 = shift %0 dh={dh} dw={dw}\noutput %1\n", x)
+    exp = np.zeros_like(x)
+    for h in range(6):
+        for w in range(7):
+            if 0 <= h + dh < 6 and 0 <= w + dw < 7:
+                exp[:, :, h, w] = x[:, :, h + dh, w + dw]
+    np.testing.assert_array_equal(r["y"], exp)
+
+
+def test_shift_then_back_zeroes_a_border_band(oracle):
+    x = np.random.default_rng(2).standard_normal((1, 2, 5, 5))
+    r = run1(oracle, "%1 = shift %0 dh=0 dw=1\n%2 = shift %1 dh=0 dw=-1\noutput %2\n", x)
+    exp = x.copy()
+    exp[:, :, :, 0] = 0.0  # column 0 reads column -1 of the shifted tensor
+    np.testing.assert_array_equal(r["y"], exp)
+
+
+def test_shift_channel_slice(oracle):
+    x = np.random.default_rng(3).standard_normal((1, 6, 4, 4))
+    r = run1(oracle, "%1 = shift %0 dh=1 dw=0 c0=2 c1=4\noutput %1\n", x)
+    np.testing.assert_array_equal(r["y"][:, :2], x[:, :2])
+    np.testing.assert_array_equal(r["y"][:, 4:], x[:, 4:])
+    np.testing.assert_array_equal(r["y"][:, 2:4, :3], x[:, 2:4, 1:])
+    np.testing.assert_array_equal(r["y"][:, 2:4, 3], 0 * x[:, 2:4, 3])
+
+
+@pytest.mark.parametrize("k", [3, 5])
+def test_unfold_tap_equals_shift(oracle, k):
+    """Tap (kh,kw) of Unfold is the tensor shifted by (kh-K/2, kw-K/2)."""
+    x = np.random.default_rng(4).standard_normal((1, 2, 6, 5))
+    u = run1(oracle, f"%1 = unfold %0 kh={k} kw={k}\noutput %1\n", x)["y"]
+    assert u.shape == (1, 2, k * k, 6, 5)
+    for kh in range(k):
+        for kw in range(k):
+            s = run1(oracle, f"%1 = shift %0 dh={kh - k // 2} dw={kw - k // 2}\noutput %1\n", x)["y"]
+            np.testing.assert_array_equal(u[:, :, kh * k + kw], s)
+
+
+# ------------------------------------------- adjoints of the linear primitives
+
+LINEAR_BODIES = [
+    ("%1 = unfold %0 kh=3 kw=3\noutput %1\n", []),
+    ("%1 = unfold %0 kh=5 kw=3\noutput %1\n", []),
+    ("%1 = shift %0 dh=1 dw=-2 c0=1 c1=3\noutput %1\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = shift %1 dh=0 dw=1\n%3 = fold %2 op=sum\noutput %3\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=avg\noutput %2\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = binary %0 %1 op=add\noutput %2\n", []),
+    ("%1 = fc %0 groups=2 out=6\noutput %1\n", [(2, 3, 2)]),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = fc %1 groups=4 out=12\n%3 = binary %2 %1 op=add\noutput %3\n", [(4, 3, 9)]),
+]
+
+
+@pytest.mark.parametrize("body,wshapes", LINEAR_BODIES)
+def test_adjoint_dot_product(oracle, body, wshapes):
+    """<A x, y> == <x, A^T y> for DAGs that are linear in x."""
+    rng = np.random.default_rng(10)
+    x = rng.standard_normal((2, 4, 5, 6))
+    ws = [rng.standard_normal(s) for s in wshapes]
+    y0 = run1(oracle, body, x, ws)["y"]
+    dy = rng.standard_normal(y0.shape)
+    r = run1(oracle, body, x, ws, dy)
+    lhs = float(np.sum(r["y"] * dy))
+    rhs = float(np.sum(x * r["dx"]))
+    assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+    # linear in the weights as well: <dW, W> == <y, dy>
+    for w, dw in zip(ws, r["dw"]):
+        if len(ws) == 1 and "binary" not in body:
+            assert abs(float(np.sum(w * dw)) - lhs) <= 1e-12 * max(1.0, abs(lhs))
+
+
+# ----------------------------------------------------- finite differences
+
+def fd_check(oracle, body, x, ws, h=1e-6, tol=2e-6, n_probe=25, seed=0):
+    rng = np.random.default_rng(seed)
+    y0 = run1(oracle, body, x, ws)["y"]
+    dy = rng.standard_normal(y0.shape)
+    r = run1(oracle, body, x, ws, dy)
+
+    def loss(xx, wws):
+        return float(np.sum(run1(oracle, body, xx, wws)["y"] * dy))
+
+    for _ in range(n_probe):
+        idx = tuple(rng.integers(0, s) for s in x.shape)
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        num = (loss(xp, ws) - loss(xm, ws)) / (2 * h)
+        assert abs(num - r["dx"][idx]) <= tol * max(1.0, abs(num)), (body, idx, num, r["dx"][idx])
+    for k, w in enumerate(ws):
+        for _ in range(min(n_probe, w.size)):
+            idx = tuple(rng.integers(0, s) for s in w.shape)
+            wp = [a.copy() for a in ws]
+            wm = [a.copy() for a in ws]
+            wp[k][idx] += h
+            wm[k][idx] -= h
+            num = (loss(x, wp) - loss(x, wm)) / (2 * h)
+            assert abs(num - r["dw"][k][idx]) <= tol * max(1.0, abs(num)), (body, k, idx)
+
+
+def away_from_kinks(x, margin=1e-2):
+    return np.where(np.abs(x) < margin, margin * np.where(x < 0, -1.0, 1.0), x)
+
+
+FD_BODIES = [
+    ("%1 = unary %0 op=relu\noutput %1\n", []),
+    ("%1 = unary %0 op=abs\noutput %1\n", []),
+    ("%1 = unary %0 op=gelu\noutput %1\n", []),
+    ("%1 = unary %0 op=expclip lo=-1.5 hi=0.75\noutput %1\n", []),
+    ("%1 = softmax %0 axis=C\noutput %1\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = softmax %1 axis=T\noutput %2\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = softmax %1 axis=C\n%3 = fold %2 op=max\noutput %3\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = binary %0 %1 op=mul\n%3 = fold %2 op=avg\noutput %3\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=max\noutput %2\n", []),
+    ("%1 = fc %0 groups=2 out=8\n%2 = unary %1 op=gelu\n%3 = binary %0 %2 op=mul\noutput %3\n", [(2, 4, 2)]),
+    ("%1 = fc %0 groups=1 out=9\n%2 = softmax %1 axis=C\n%3 = unfold %0 kh=3 kw=3\n%4 = binary %2 %3 op=mul\n"
+     "%5 = fold %4 op=sum\n%6 = fc %5 groups=1 out=4\noutput %6\n", [(1, 9, 4), (1, 4, 4)]),
+    ("%1 = shift %0 dh=0 dw=1 c0=0 c1=2\n%2 = fc %1 groups=2 out=4\n%3 = unary %2 op=relu\n%4 = binary %0 %3 op=add\n"
+     "output %4\n", [(2, 2, 2)]),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = fc %1 groups=2 out=4\n%3 = unary %2 op=gelu\n%4 = shift %3 dh=0 dw=1 c0=2 c1=4\n"
+     "%5 = binary %0 %4 op=mul\n%6 = fold %5 op=avg\n%7 = fc %6 groups=1 out=4\noutput %7\n", [(2, 2, 18), (1, 4, 4)]),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=abs\n%3 = binary %0 %2 op=mul\n%4 = softmax %3 axis=T\noutput %4\n", []),
+]
+
+
+@pytest.mark.parametrize("body,wshapes", FD_BODIES)
+def test_finite_differences(oracle, body, wshapes):
+    rng = np.random.default_rng(20)
+    x = away_from_kinks(rng.standard_normal((2, 4, 4, 5)))
+    ws = [rng.standard_normal(s) * 0.5 for s in wshapes]
+    fd_check(oracle, body, x, ws)
+
+
+# ------------------------------------------------------------------ unary
+
+def test_unary_closed_forms(oracle):
+    x = np.array([-3.0, -1.0, -0.25, 0.0, 0.5, 1.0, 2.5, 7.0]).reshape(1, 8, 1, 1)
+    dy = np.ones_like(x)
+    v = x.ravel()
+    r = run1(oracle, "%1 = unary %0 op=relu\noutput %1\n", x, (), dy)
+    np.testing.assert_array_equal(r["y"].ravel(), np.maximum(v, 0))
+    np.testing.assert_array_equal(r["dx"].ravel(), (v > 0).astype(float))  # derivative 0 at 0
+    r = run1(oracle, "%1 = unary %0 op=abs\noutput %1\n", x, (), dy)
+    np.testing.assert_array_equal(r["y"].ravel(), np.abs(v))
+    np.testing.assert_array_equal(r["dx"].ravel(), np.sign(v))  # sign(0) = 0
+    r = run1(oracle, "%1 = unary %0 op=gelu\noutput %1\n", x, (), dy)
+    exp = np.array([t * 0.5 * (1 + math.erf(t / math.sqrt(2))) for t in v])
+    np.testing.assert_allclose(r["y"].ravel(), exp, atol=1e-15)
+    assert r["y"].ravel()[3] == 0.0 and r["dx"].ravel()[3] == 0.5  # gelu(0) = 0, gelu'(0) = 1/2
+    r = run1(oracle, "%1 = unary %0 op=expclip lo=-1 hi=2\noutput %1\n", x, (), dy)
+    np.testing.assert_allclose(r["y"].ravel(), np.exp(np.clip(v, -1, 2)), atol=1e-15)
+    inside = (v > -1) & (v < 2)
+    np.testing.assert_allclose(r["dx"].ravel(), np.where(inside, np.exp(v), 0.0), atol=1e-15)
+    # the boundary itself has zero gradient (open interval)
+    assert r["dx"].ravel()[1] == 0.0
+
+
+# ---------------------------------------------------------------- softmax
+
+@pytest.mark.parametrize("axis", ["C", "T"])
+def test_softmax_invariants(oracle, axis):
+    rng = np.random.default_rng(30)
+    x = rng.standard_normal((2, 5, 4, 3))
+    body = f"%1 = unfold %0 kh=3 kw=3\n%2 = softmax %1 axis={axis}\noutput %2\n"
+    y = run1(oracle, body, x)["y"]  # [N, C, T, H, W]
+    ax = 1 if axis == "C" else 2
+    np.testing.assert_allclose(y.sum(axis=ax), 1.0, atol=1e-14)
+    assert (y > 0).all()
+    dy = rng.standard_normal(y.shape)
+    # gradient w.r.t. the softmax input sums to zero along the axis: check on a DAG without unfold
+    if axis == "C":
+        r = run1(oracle, "%1 = softmax %0 axis=C\noutput %1\n", x, (), dy[:, :, 0])
+        np.testing.assert_allclose(r["dx"].sum(axis=1), 0.0, atol=1e-14)
+        y1 = run1(oracle, "%1 = softmax %0 axis=C\noutput %1\n", x + 3.25)["y"]
+        np.testing.assert_allclose(y1, r["y"], atol=1e-14)  # shift invariance
+        e = np.exp(x)
+        np.testing.assert_allclose(r["y"], e / e.sum(axis=1, keepdims=True), atol=1e-14)
+
+
+def test_softmax_over_single_tap_is_all_ones_with_zero_gradient(oracle):
+    x = np.random.default_rng(31).standard_normal((1, 3, 2, 2))
+    r = run1(oracle, "%1 = softmax %0 axis=T\noutput %1\n", x, (), np.ones((1, 3, 2, 2)))
+    np.testing.assert_array_equal(r["y"], np.ones_like(x))
+    np.testing.assert_array_equal(r["dx"], np.zeros_like(x))
+
+
+def test_softmax_large_inputs_do_not_overflow(oracle):
+    x = np.array([1000.0, 1001.0, 999.0, -1000.0]).reshape(1, 4, 1, 1)
+    y = run1(oracle, "%1 = softmax %0 axis=C\noutput %1\n", x)["y"].ravel()
+    e = np.exp(np.array([0.0, 1.0, -1.0]))
+    np.testing.assert_allclose(y[:3], e / e.sum(), atol=1e-15)
+    assert y[3] == 0.0
+
+
+# ------------------------------------------------------------------- fold
+
+def test_fold_relations(oracle):
+    rng = np.random.default_rng(40)
+    x = rng.standard_normal((2, 3, 5, 4))
+    pre = "%1 = unfold %0 kh=3 kw=3\n"
+    s = run1(oracle, pre + "%2 = fold %1 op=sum\noutput %2\n", x)["y"]
+    a = run1(oracle, pre + "%2 = fold %1 op=avg\noutput %2\n", x)["y"]
+    m = run1(oracle, pre + "%2 = fold %1 op=max\noutput %2\n", x)["y"]
+    u = run1(oracle, pre + "output %1\n", x)["y"]
+    np.testing.assert_allclose(s, u.sum(axis=2), atol=1e-14)
+    np.testing.assert_allclose(a, s / 9.0, atol=1e-15)
+    np.testing.assert_array_equal(m, u.max(axis=2))
+    assert (m >= a - 1e-15).all()
+    # sum-pool of a 3x3 unfold is a box filter; check against scipy's zero-padded correlate
+    from scipy.ndimage import correlate
+
+    box = np.stack([[correlate(x[n, c], np.ones((3, 3)), mode="constant") for c in range(3)] for n in range(2)])
+    np.testing.assert_allclose(s, box, atol=1e-13)
+
+
+def test_fold_over_one_tap_is_identity(oracle):
+    x = np.random.default_rng(41).standard_normal((1, 3, 2, 2))
+    dy = np.random.default_rng(42).standard_normal((1, 3, 2, 2))
+    for op in ("sum", "avg", "max"):
+        r = run1(oracle, f"%1 = fold %0 op={op}\noutput %1\n", x, (), dy)
+        np.testing.assert_array_equal(r["y"], x)
+        np.testing.assert_array_equal(r["dx"], dy)
+
+
+def test_fold_max_ties_take_first_tap(oracle):
+    """Constant input: every interior pixel has 9 equal taps; the gradient goes to tap 0 only."""
+    x = np.ones((1, 1, 4, 4))
+    dy = np.arange(16, dtype=float).reshape(1, 1, 4, 4) + 1
+    # dU via a DAG whose dx is unfold^T of the routed gradient; inspect through a per-tap mul by one-hot weights
+    r = run1(oracle, "%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=max\noutput %2\n", x, (), dy)
+    # pixel (h,w) routes dy to its first maximal tap.  Interior pixels: tap 0 = neighbour (h-1,w-1).
+    exp = np.zeros((4, 4))
+    for h in range(4):
+        for w in range(4):
+            taps = [(kh, kw) for kh in range(3) for kw in range(3)]
+            vals = [1.0 if (0 <= h + kh - 1 < 4 and 0 <= w + kw - 1 < 4) else 0.0 for kh, kw in taps]
+            t = int(np.argmax(vals))  # numpy argmax returns the first maximum
+            kh, kw = taps[t]
+            exp[h + kh - 1, w + kw - 1] += dy[0, 0, h, w]
+    np.testing.assert_array_equal(r["dx"][0, 0], exp)
+
+
+# -------------------------------------------------------------- broadcast
+
+def test_broadcast_equal_shapes_is_elementwise(oracle):
+    rng = np.random.default_rng(50)
+    x = rng.standard_normal((2, 3, 4, 4))
+    r = run1(oracle, "%1 = unary %0 op=abs\n%2 = binary %1 %0 op=mul\noutput %2\n", x)
+    np.testing.assert_allclose(r["y"], np.abs(x) * x, atol=1e-15)
+
+
+def test_broadcast_common_channel_prefix_is_per_channel(oracle):
+    """[C,H,W] onto [C,T,H,W]: the channel dim is a common prefix, so each channel meets its own taps."""
+    rng = np.random.default_rng(51)
+    x = rng.standard_normal((1, 4, 3, 3))
+    r = run1(oracle, "%1 = unfold %0 kh=3 kw=3\n%2 = binary %0 %1 op=mul\noutput %2\n", x)
+    u = run1(oracle, "%1 = unfold %0 kh=3 kw=3\noutput %1\n", x)["y"]
+    np.testing.assert_allclose(r["y"], x[:, :, None] * u, atol=1e-15)
+
+
+def test_broadcast_channel_tiling(oracle):
+    """[C/2,H,W] onto [C,H,W]: the LHS is replicated, lhs channel = c mod (C/2)."""
+    rng = np.random.default_rng(52)
+    x = rng.standard_normal((2, 4, 3, 3))
+    w = rng.standard_normal((1, 2, 4))
+    dy = rng.standard_normal((2, 4, 3, 3))
+    r = run1(oracle, "%1 = fc %0 groups=1 out=2\n%2 = binary %1 %0 op=add\noutput %2\n", x, [w], dy)
+    f = np.einsum("oc,nchw->nohw", w[0], x)
+    np.testing.assert_allclose(r["y"], np.concatenate([f, f], axis=1) + x, atol=1e-14)
+    # gradient to the LHS sums over its replicas
+    gf = dy[:, :2] + dy[:, 2:]
+    np.testing.assert_allclose(r["dw"][0][0], np.einsum("nohw,nchw->oc", gf, x), atol=1e-13)
+
+
+def test_involution_core_against_explicit_dynamic_kernel(oracle):
+    """Section 5: [K*K,H,W] broadcast-multiplied onto [C,K,K,H,W], then summed over taps, is a
+    per-pixel dynamic KxK filter: out(c,h,w) = sum_t k(t,h,w) * x(c,h+dh_t,w+dw_t)."""
+    rng = np.random.default_rng(53)
+    C, H, W = 5, 4, 6
+    x = rng.standard_normal((1, C, H, W))
+    w1 = rng.standard_normal((1, 9, C))
+    body = ("%1 = fc %0 groups=1 out=9\n%2 = unfold %0 kh=3 kw=3\n%3 = binary %1 %2 op=mul\n%4 = fold %3 op=sum\n"
+            "output %4\n")
+    r = run1(oracle, body, x, [w1])
+    ker = np.einsum("tc,nchw->nthw", w1[0], x)
+    exp = np.zeros((1, C, H, W))
+    for c in range(C):
+        for h in range(H):
+            for w in range(W):
+                for t in range(9):
+                    hs, ws = h + t // 3 - 1, w + t % 3 - 1
+                    if 0 <= hs < H and 0 <= ws < W:
+                        exp[0, c, h, w] += ker[0, t, h, w] * x[0, c, hs, ws]
+    np.testing.assert_allclose(r["y"], exp, atol=1e-13)
+
+
+def test_fan_out_gradients_add(oracle):
+    rng = np.random.default_rng(54)
+    x = rng.standard_normal((1, 3, 3, 3))
+    dy = rng.standard_normal((1, 3, 3, 3))
+    r = run1(oracle, "%1 = binary %0 %0 op=add\n%2 = binary %1 %0 op=add\noutput %2\n", x, (), dy)
+    np.testing.assert_allclose(r["y"], 3 * x, atol=1e-15)
+    np.testing.assert_allclose(r["dx"], 3 * dy, atol=1e-15)
+    r = run1(oracle, "%1 = binary %0 %0 op=mul\noutput %1\n", x, (), dy)
+    np.testing.assert_allclose(r["dx"], 2 * x * dy, atol=1e-15)
+
+
+def test_output_can_be_the_input(oracle):
+    x = np.random.default_rng(55).standard_normal((1, 2, 2, 2))
+    r = run1(oracle, "output %0\n", x, (), 2 * x)
+    np.testing.assert_array_equal(r["y"], x)
+    np.testing.assert_array_equal(r["dx"], 2 * x)
+
+
+def test_batch_images_are_independent_and_dw_sums_over_batch(oracle):
+    rng = np.random.default_rng(56)
+    case_body = "%1 = unfold %0 kh=3 kw=3\n%2 = fc %1 groups=1 out=3\n%3 = unary %2 op=gelu\noutput %3\n"
+    x = rng.standard_normal((5, 2, 4, 4))
+    w = rng.standard_normal((1, 3, 18))
+    dy = rng.standard_normal((5, 3, 4, 4))
+    full = run1(oracle, case_body, x, [w], dy)
+    acc = np.zeros_like(w)
+    for n in range(5):
+        one = run1(oracle, case_body, x[n:n + 1], [w], dy[n:n + 1])
+        np.testing.assert_array_equal(one["y"][0], full["y"][n])
+        np.testing.assert_array_equal(one["dx"][0], full["dx"][n])
+        acc += one["dw"][0]
+    np.testing.assert_allclose(full["dw"][0], acc, atol=1e-13)
+    one_thread = oracle.run(H_ + case_body, x, [w], dy, n_threads=1)
+    np.testing.assert_allclose(one_thread["dw"][0], full["dw"][0], atol=1e-13)
