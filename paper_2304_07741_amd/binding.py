@@ -1,0 +1,127 @@
+"""Thin ctypes binding of the C-ABI library (argument marshalling only).
+
+Function names mirror include/canvas_dag.h.  Tensors are torch tensors used
+purely as device memory; the stream is torch's current HIP stream.  Nothing
+here computes: every step of forward and backward runs in the library's kernels.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcanvas_dag.so")
+
+CANVAS_F32, CANVAS_BF16 = 0, 1
+CANVAS_OPT_NO_FUSION = 1
+CANVAS_MAX_NODES = 64
+STATUS = {0: "OK", -1: "INVALID_BLOB", -2: "UNKNOWN_OP", -3: "SHAPE_MISMATCH", -4: "BAD_ARG",
+          -5: "WORKSPACE_TOO_SMALL", -6: "UNSUPPORTED", -7: "HIP_ERROR"}
+EXPORTS = ["canvas_dag_compile", "canvas_dag_query", "canvas_dag_launch_desc", "canvas_dag_forward",
+           "canvas_dag_backward", "canvas_dag_destroy", "canvas_last_error"]
+
+
+class CanvasOptions(ctypes.Structure):
+    _fields_ = [("flags", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 7)]
+
+
+class CanvasDagInfo(ctypes.Structure):
+    _fields_ = [
+        ("n_nodes", ctypes.c_int32), ("out_node", ctypes.c_int32), ("n_weights", ctypes.c_int32),
+        ("n_launches_fwd", ctypes.c_int32), ("n_launches_bwd", ctypes.c_int32), ("fused", ctypes.c_int32),
+        ("reserved0", ctypes.c_int32 * 2),
+        ("out_shape", ctypes.c_int64 * 5),
+        ("node_shape", (ctypes.c_int64 * 5) * CANVAS_MAX_NODES),
+        ("weight_shape", (ctypes.c_int64 * 3) * CANVAS_MAX_NODES),
+        ("weight_node", ctypes.c_int32 * CANVAS_MAX_NODES),
+        ("workspace_bytes", ctypes.c_uint64),
+        ("fc_flops_fwd", ctypes.c_double), ("min_bytes_fwd", ctypes.c_double), ("min_bytes_bwd", ctypes.c_double),
+    ]
+
+
+class CanvasLaunchDesc(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 64), ("bytes", ctypes.c_double), ("flops", ctypes.c_double)]
+
+
+class CanvasError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Load the HIP library; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        lib.canvas_dag_compile.argtypes = [ctypes.c_char_p, sz, ctypes.POINTER(ctypes.c_int64), ctypes.c_int,
+                                           ctypes.POINTER(CanvasOptions), ctypes.POINTER(vp)]
+        lib.canvas_dag_query.argtypes = [vp, ctypes.POINTER(CanvasDagInfo)]
+        lib.canvas_dag_launch_desc.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(CanvasLaunchDesc)]
+        lib.canvas_dag_forward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, sz, vp]
+        lib.canvas_dag_backward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, ctypes.POINTER(vp), vp, sz, vp]
+        lib.canvas_dag_destroy.argtypes = [vp]
+        lib.canvas_dag_destroy.restype = None
+        lib.canvas_last_error.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise CanvasError(rc, load().canvas_last_error().decode())
+
+
+def canvas_dag_compile(blob, in_shape, dtype, flags=0):
+    """Returns an opaque handle (int).  dtype: CANVAS_F32 or CANVAS_BF16."""
+    lib = load()
+    b = blob.encode() if isinstance(blob, str) else bytes(blob)
+    shp = (ctypes.c_int64 * 4)(*[int(v) for v in in_shape])
+    opt = CanvasOptions(flags=flags)
+    h = ctypes.c_void_p()
+    _check(lib.canvas_dag_compile(b, len(b), shp, int(dtype), ctypes.byref(opt), ctypes.byref(h)))
+    return h
+
+
+def canvas_dag_query(handle):
+    info = CanvasDagInfo()
+    _check(load().canvas_dag_query(handle, ctypes.byref(info)))
+    return info
+
+
+def canvas_dag_launch_desc(handle, backward, idx):
+    d = CanvasLaunchDesc()
+    _check(load().canvas_dag_launch_desc(handle, int(backward), int(idx), ctypes.byref(d)))
+    return {"name": d.name.decode(), "bytes": d.bytes, "flops": d.flops}
+
+
+def _ptrs(tensors):
+    arr = (ctypes.c_void_p * max(1, len(tensors)))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def _stream():
+    import torch
+
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def canvas_dag_forward(handle, x, weights, y, workspace):
+    _check(load().canvas_dag_forward(handle, x.data_ptr(), _ptrs(weights), y.data_ptr(), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+def canvas_dag_backward(handle, x, weights, dy, dx, dweights, workspace):
+    _check(load().canvas_dag_backward(handle, x.data_ptr(), _ptrs(weights), dy.data_ptr(), dx.data_ptr(),
+                                      _ptrs(dweights), workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), _stream()))
+
+
+def canvas_dag_destroy(handle):
+    load().canvas_dag_destroy(handle)

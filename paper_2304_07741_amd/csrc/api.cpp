@@ -1,0 +1,171 @@
+// C ABI: compile / query / forward / backward / destroy.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <memory>
+#include <string>
+
+#include "../../include/canvas_dag.h"
+#include "dag.hpp"
+#include "lowering.hpp"
+
+struct canvas_dag {
+    canvas::Dag dag;
+    bool bf16 = false;
+    std::unique_ptr<canvas::Lowering> low;
+    canvas_dag_info info;
+};
+
+namespace {
+
+thread_local std::string g_err;
+
+int set_err(int code, const std::string& msg) {
+    g_err = msg;
+    return code;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_common(const canvas_dag* d, const void* x, const void* const* weights, const void* ws, size_t ws_bytes) {
+    if (!d) return set_err(CANVAS_BAD_ARG, "null dag handle");
+    if (!x || !aligned16(x)) return set_err(CANVAS_BAD_ARG, "x must be a non-null, 16-byte aligned device pointer");
+    if (d->dag.n_weights > 0) {
+        if (!weights) return set_err(CANVAS_BAD_ARG, "weights array is null");
+        for (int i = 0; i < d->dag.n_weights; i++)
+            if (!weights[i] || !aligned16(weights[i])) return set_err(CANVAS_BAD_ARG, "a weight pointer is null or misaligned");
+    }
+    if (ws_bytes < d->low->ws_bytes) return set_err(CANVAS_WORKSPACE_TOO_SMALL, "workspace smaller than workspace_bytes");
+    if (d->low->ws_bytes > 0 && (!ws || !aligned16(ws))) return set_err(CANVAS_BAD_ARG, "workspace must be non-null and 16-byte aligned");
+    return CANVAS_OK;
+}
+
+int finish_launches() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return set_err(CANVAS_HIP_ERROR, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return CANVAS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int canvas_dag_compile(const void* blob, size_t blob_len, const int64_t in_shape[4], canvas_dtype dt,
+                       const canvas_options* opt, canvas_dag** out) {
+    try {
+        if (!out) return set_err(CANVAS_BAD_ARG, "null output handle");
+        *out = nullptr;
+        if (dt != CANVAS_F32 && dt != CANVAS_BF16) return set_err(CANVAS_BAD_ARG, "unknown dtype");
+        uint32_t flags = 0;
+        if (opt) {
+            flags = opt->flags;
+            for (uint32_t r : opt->reserved)
+                if (r) return set_err(CANVAS_BAD_ARG, "reserved option fields must be zero");
+            if (flags & ~CANVAS_OPT_NO_FUSION) return set_err(CANVAS_BAD_ARG, "unknown option flag");
+        }
+        auto d = std::make_unique<canvas_dag>();
+        std::string err;
+        int rc = canvas::parse_dag((const char*)blob, blob_len, in_shape, d->dag, err);
+        if (rc != 0) return set_err(rc, err);
+        d->bf16 = dt == CANVAS_BF16;
+        d->low = canvas::lower(d->dag, d->bf16, (flags & CANVAS_OPT_NO_FUSION) != 0);
+
+        canvas_dag_info& I = d->info;
+        std::memset(&I, 0, sizeof I);
+        const canvas::Dag& g = d->dag;
+        I.n_nodes = (int32_t)g.nodes.size();
+        I.out_node = g.out;
+        I.n_weights = g.n_weights;
+        I.n_launches_fwd = (int32_t)d->low->fwd.size();
+        I.n_launches_bwd = (int32_t)d->low->bwd.size();
+        I.fused = d->low->fused ? 1 : 0;
+        const double esz = d->bf16 ? 2.0 : 4.0;
+        double wbytes = 0, wcount = 0;
+        for (int k = 0; k < I.n_nodes; k++) {
+            const canvas::Node& nd = g.nodes[k];
+            int64_t s[5] = {g.N, nd.C, nd.T, g.H, g.W};
+            std::memcpy(I.node_shape[k], s, sizeof s);
+            if (nd.op == canvas::Op::Fc) {
+                const canvas::Node& A = g.nodes[nd.a];
+                int64_t K = (int64_t)(A.C / nd.groups) * A.T;
+                I.weight_shape[nd.widx][0] = nd.groups;
+                I.weight_shape[nd.widx][1] = nd.out / nd.groups;
+                I.weight_shape[nd.widx][2] = K;
+                I.weight_node[nd.widx] = k;
+                if (nd.live) I.fc_flops_fwd += 2.0 * g.N * g.H * g.W * nd.out * K;
+                wbytes += esz * nd.out * K;
+                wcount += (double)nd.out * K;
+            }
+        }
+        std::memcpy(I.out_shape, I.node_shape[g.out], sizeof I.out_shape);
+        I.workspace_bytes = d->low->ws_bytes;
+        I.min_bytes_fwd = esz * (g.numel(0) + g.numel(g.out)) + wbytes;
+        I.min_bytes_bwd = esz * (2.0 * g.numel(0) + g.numel(g.out)) + wbytes + 4.0 * wcount;
+        *out = d.release();
+        return CANVAS_OK;
+    } catch (const std::exception& e) {
+        return set_err(CANVAS_UNSUPPORTED, std::string("compile failed: ") + e.what());
+    }
+}
+
+int canvas_dag_query(const canvas_dag* dag, canvas_dag_info* info) {
+    if (!dag || !info) return set_err(CANVAS_BAD_ARG, "null argument");
+    *info = dag->info;
+    return CANVAS_OK;
+}
+
+int canvas_dag_launch_desc(const canvas_dag* dag, int backward, int idx, canvas_launch_desc* out) {
+    if (!dag || !out) return set_err(CANVAS_BAD_ARG, "null argument");
+    const auto& v = backward ? dag->low->bwd : dag->low->fwd;
+    if (idx < 0 || idx >= (int)v.size()) return set_err(CANVAS_BAD_ARG, "launch index out of range");
+    std::memset(out, 0, sizeof *out);
+    std::strncpy(out->name, v[idx].name.c_str(), sizeof(out->name) - 1);
+    out->bytes = v[idx].bytes;
+    out->flops = v[idx].flops;
+    return CANVAS_OK;
+}
+
+int canvas_dag_forward(canvas_dag* dag, const void* x, const void* const* weights, void* y, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+    int rc = check_common(dag, x, weights, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (!y || !aligned16(y)) return set_err(CANVAS_BAD_ARG, "y must be a non-null, 16-byte aligned device pointer");
+    canvas::RunArgs a;
+    a.x = x;
+    a.w = weights;
+    a.y = y;
+    a.ws = (char*)workspace;
+    a.stream = (hipStream_t)stream;
+    (void)hipGetLastError();
+    for (const auto& l : dag->low->fwd) l.run(a);
+    return finish_launches();
+}
+
+int canvas_dag_backward(canvas_dag* dag, const void* x, const void* const* weights, const void* dy, void* dx,
+                        void* const* dweights, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_common(dag, x, weights, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (!dy || !aligned16(dy) || !dx || !aligned16(dx)) return set_err(CANVAS_BAD_ARG, "dy and dx must be non-null, 16-byte aligned device pointers");
+    if (dag->dag.n_weights > 0) {
+        if (!dweights) return set_err(CANVAS_BAD_ARG, "dweights array is null");
+        for (int i = 0; i < dag->dag.n_weights; i++)
+            if (!dweights[i] || !aligned16(dweights[i])) return set_err(CANVAS_BAD_ARG, "a dweights pointer is null or misaligned");
+    }
+    canvas::RunArgs a;
+    a.x = x;
+    a.w = weights;
+    a.dy = dy;
+    a.dx = dx;
+    a.dw = dweights;
+    a.ws = (char*)workspace;
+    a.stream = (hipStream_t)stream;
+    (void)hipGetLastError();
+    for (const auto& l : dag->low->bwd) l.run(a);
+    return finish_launches();
+}
+
+void canvas_dag_destroy(canvas_dag* dag) { delete dag; }
+
+const char* canvas_last_error(void) { return g_err.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,39 @@
+// Small device helpers shared by the kernels: bf16 conversion and the element-wise primitives.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace canvas {
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// Round to nearest even; NaN stays NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Element-wise primitives (Section 5): relu, abs, gelu (erf form), exp of the clamped input.
+__device__ __forceinline__ float unary_apply(int kind, float x, float lo, float hi) {
+    switch (kind) {
+    case 0: return x > 0.f ? x : 0.f;
+    case 1: return fabsf(x);
+    case 2: return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
+    default: return expf(fminf(fmaxf(x, lo), hi));
+    }
+}
+
+// Derivatives: relu'(0) = 0, sign(0) = 0, clamped exp has zero slope outside the open interval (lo, hi).
+__device__ __forceinline__ float unary_grad(int kind, float x, float lo, float hi) {
+    switch (kind) {
+    case 0: return x > 0.f ? 1.f : 0.f;
+    case 1: return x > 0.f ? 1.f : (x < 0.f ? -1.f : 0.f);
+    case 2: return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.39894228040143268f * expf(-0.5f * x * x);
+    default: return (x > lo && x < hi) ? expf(x) : 0.f;
+    }
+}
+
+}  // namespace canvas

@@ -1,0 +1,229 @@
+// Unfused lowering: every live node becomes one forward launch and one or two backward launches.
+// Values and gradients of all nodes live in the workspace as fp32 [N, C, T, H, W]; bf16 inputs are
+// widened once on entry and results narrowed once on exit.
+#include "lowering.hpp"
+#include "ref_kernels.hpp"
+
+namespace canvas {
+
+namespace {
+
+struct Layout {
+    std::vector<int64_t> val, grad, wf;  // byte offsets into the workspace; -1 = not in the workspace
+    uint64_t total = 0;
+};
+
+const char* op_name(Op op) {
+    switch (op) {
+    case Op::Unfold: return "unfold";
+    case Op::Shift: return "shift";
+    case Op::Fc: return "fc";
+    case Op::Unary: return "unary";
+    case Op::Binary: return "binary";
+    case Op::Softmax: return "softmax";
+    case Op::Fold: return "fold";
+    default: return "input";
+    }
+}
+
+}  // namespace
+
+std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
+    auto low = std::make_unique<Lowering>();
+    const int n = (int)dag.nodes.size();
+    const int P = dag.P();
+    const int64_t N = dag.N;
+    Layout lay;
+    lay.val.assign(n, -1);
+    lay.grad.assign(n, -1);
+    lay.wf.assign(dag.n_weights, -1);
+    uint64_t off = 0;
+    auto take = [&](int64_t numel) {
+        uint64_t o = off;
+        off += align_up((uint64_t)numel * 4);
+        return (int64_t)o;
+    };
+    for (int k = 0; k < n; k++) {
+        if (!dag.nodes[k].live) continue;
+        if (k > 0 || bf16) lay.val[k] = take(dag.numel(k));
+        lay.grad[k] = take(dag.numel(k));
+    }
+    std::vector<int64_t> wnumel(dag.n_weights);
+    for (int i = 0; i < dag.n_weights; i++) {
+        const Node& f = dag.nodes[dag.weight_node[i]];
+        const Node& A = dag.nodes[f.a];
+        wnumel[i] = (int64_t)f.out * (A.C / f.groups) * A.T;
+        if (bf16 && f.live) lay.wf[i] = take(wnumel[i]);
+    }
+    low->ws_bytes = off;
+    const double esz = bf16 ? 2.0 : 4.0;
+
+    // pointer resolvers
+    auto val = [lay](const RunArgs& a, int k) -> const float* {
+        return lay.val[k] >= 0 ? (const float*)(a.ws + lay.val[k]) : (const float*)a.x;
+    };
+    auto valw = [lay](const RunArgs& a, int k) -> float* { return (float*)(a.ws + lay.val[k]); };
+    auto grad = [lay](const RunArgs& a, int k) -> float* { return (float*)(a.ws + lay.grad[k]); };
+    auto wptr = [lay, bf16](const RunArgs& a, int i) -> const float* {
+        return bf16 ? (const float*)(a.ws + lay.wf[i]) : (const float*)a.w[i];
+    };
+
+    // ---------------------------------------------------------------- forward
+    if (bf16) {
+        int64_t ne = dag.numel(0);
+        low->fwd.push_back({"widen_x", ne * 6.0, 0, [=](const RunArgs& a) { ref::widen_bf16(a.x, valw(a, 0), ne, a.stream); }});
+        for (int i = 0; i < dag.n_weights; i++) {
+            if (lay.wf[i] < 0) continue;
+            int64_t nw = wnumel[i];
+            int64_t o = lay.wf[i];
+            low->fwd.push_back({"widen_w", nw * 6.0, 0, [=](const RunArgs& a) { ref::widen_bf16(a.w[i], (float*)(a.ws + o), nw, a.stream); }});
+        }
+    }
+    for (int k = 1; k < n; k++) {
+        const Node nd = dag.nodes[k];
+        if (!nd.live) continue;
+        const Node A = dag.nodes[nd.a];
+        Launch L;
+        L.name = std::string("node_") + op_name(nd.op) + "_fwd";
+        L.bytes = 4.0 * (dag.numel(nd.a) + dag.numel(k));
+        switch (nd.op) {
+        case Op::Unfold:
+            L.run = [=](const RunArgs& a) { ref::unfold_fwd(val(a, nd.a), valw(a, k), N * A.C, A.T, nd.kh, nd.kw, dag.H, dag.W, a.stream); };
+            break;
+        case Op::Shift:
+            L.run = [=](const RunArgs& a) {
+                ref::shift(val(a, nd.a), valw(a, k), N, nd.C, nd.T, dag.H, dag.W, nd.dh, nd.dw, nd.c0, nd.c1, 0, a.stream);
+            };
+            break;
+        case Op::Fc: {
+            int G = nd.groups, Og = nd.out / G, K = (A.C / G) * A.T;
+            L.flops = 2.0 * N * P * nd.out * K;
+            L.bytes += 4.0 * wnumel[nd.widx];
+            L.run = [=](const RunArgs& a) { ref::fc_fwd(val(a, nd.a), wptr(a, nd.widx), valw(a, k), N, G, Og, K, P, a.stream); };
+            break;
+        }
+        case Op::Unary: {
+            int64_t ne = dag.numel(k);
+            L.run = [=](const RunArgs& a) { ref::unary_fwd(val(a, nd.a), valw(a, k), ne, nd.kind, nd.lo, nd.hi, a.stream); };
+            break;
+        }
+        case Op::Binary: {
+            const Node B = dag.nodes[nd.b];
+            L.bytes = 4.0 * (dag.numel(nd.a) + dag.numel(nd.b) + dag.numel(k));
+            L.run = [=](const RunArgs& a) {
+                ref::binary_fwd(val(a, nd.a), val(a, nd.b), valw(a, k), N, A.C, A.T, B.C, B.T, P, nd.kind, a.stream);
+            };
+            break;
+        }
+        case Op::Softmax:
+            L.run = [=](const RunArgs& a) { ref::softmax_fwd(val(a, nd.a), valw(a, k), N, nd.C, nd.T, P, nd.kind == kAxisC, a.stream); };
+            break;
+        case Op::Fold:
+            L.run = [=](const RunArgs& a) { ref::fold_fwd(val(a, nd.a), valw(a, k), N * A.C, A.T, P, nd.kind, a.stream); };
+            break;
+        default: break;
+        }
+        low->fwd.push_back(std::move(L));
+    }
+    {
+        int64_t ne = dag.numel(dag.out);
+        int o = dag.out;
+        if (bf16) low->fwd.push_back({"narrow_y", ne * 6.0, 0, [=](const RunArgs& a) { ref::narrow_bf16(val(a, o), a.y, ne, a.stream); }});
+        else low->fwd.push_back({"copy_y", ne * 8.0, 0, [=](const RunArgs& a) { ref::copy_f32(val(a, o), (float*)a.y, ne, a.stream); }});
+    }
+
+    // --------------------------------------------------------------- backward
+    std::vector<bool> written(n, false);
+    {
+        int64_t ne = dag.numel(dag.out);
+        int o = dag.out;
+        if (bf16) low->bwd.push_back({"widen_dy", ne * 6.0, 0, [=](const RunArgs& a) { ref::widen_bf16(a.dy, grad(a, o), ne, a.stream); }});
+        else low->bwd.push_back({"copy_dy", ne * 8.0, 0, [=](const RunArgs& a) { ref::copy_f32((const float*)a.dy, grad(a, o), ne, a.stream); }});
+        written[o] = true;
+    }
+    for (int k = n - 1; k >= 1; k--) {
+        const Node nd = dag.nodes[k];
+        if (!nd.live) continue;
+        const Node A = dag.nodes[nd.a];
+        const int acc = written[nd.a] ? 1 : 0;
+        Launch L;
+        L.name = std::string("node_") + op_name(nd.op) + "_bwd";
+        L.bytes = 4.0 * (dag.numel(nd.a) * (1 + acc) + dag.numel(k));
+        switch (nd.op) {
+        case Op::Unfold:
+            L.run = [=](const RunArgs& a) { ref::unfold_bwd(grad(a, k), grad(a, nd.a), N * A.C, A.T, nd.kh, nd.kw, dag.H, dag.W, acc, a.stream); };
+            break;
+        case Op::Shift:
+            L.run = [=](const RunArgs& a) {
+                ref::shift(grad(a, k), grad(a, nd.a), N, nd.C, nd.T, dag.H, dag.W, -nd.dh, -nd.dw, nd.c0, nd.c1, acc, a.stream);
+            };
+            break;
+        case Op::Fc: {
+            int G = nd.groups, Og = nd.out / G, K = (A.C / G) * A.T;
+            Launch D;
+            D.name = "node_fc_dw";
+            D.flops = 2.0 * N * P * nd.out * K;
+            D.bytes = 4.0 * (dag.numel(nd.a) + dag.numel(k) + wnumel[nd.widx]);
+            D.run = [=](const RunArgs& a) { ref::fc_dw(grad(a, k), val(a, nd.a), (float*)a.dw[nd.widx], N, G, Og, K, P, a.stream); };
+            low->bwd.push_back(std::move(D));
+            L.name = "node_fc_dx";
+            L.flops = 2.0 * N * P * nd.out * K;
+            L.bytes += 4.0 * wnumel[nd.widx];
+            L.run = [=](const RunArgs& a) { ref::fc_dx(grad(a, k), wptr(a, nd.widx), grad(a, nd.a), N, G, Og, K, P, acc, a.stream); };
+            break;
+        }
+        case Op::Unary: {
+            int64_t ne = dag.numel(k);
+            L.bytes += 4.0 * ne;
+            L.run = [=](const RunArgs& a) { ref::unary_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), ne, nd.kind, nd.lo, nd.hi, acc, a.stream); };
+            break;
+        }
+        case Op::Binary: {
+            const Node B = dag.nodes[nd.b];
+            // LHS first, then RHS (which may be the same tensor and then accumulates)
+            L.name = "node_binary_bwd_lhs";
+            L.bytes = 4.0 * (dag.numel(nd.a) * (1 + acc) + dag.numel(k) * (nd.kind == kMul ? 2 : 1));
+            L.run = [=](const RunArgs& a) {
+                ref::binary_bwd_lhs(val(a, nd.b), grad(a, k), grad(a, nd.a), N, A.C, A.T, B.C, B.T, P, nd.kind, acc, a.stream);
+            };
+            low->bwd.push_back(std::move(L));
+            written[nd.a] = true;
+            const int acc_r = written[nd.b] ? 1 : 0;
+            Launch R;
+            R.name = "node_binary_bwd_rhs";
+            R.bytes = 4.0 * (dag.numel(nd.b) * (1 + acc_r) + dag.numel(k) + (nd.kind == kMul ? dag.numel(nd.a) : 0));
+            R.run = [=](const RunArgs& a) {
+                ref::binary_bwd_rhs(val(a, nd.a), grad(a, k), grad(a, nd.b), N, A.C, A.T, B.C, B.T, P, nd.kind, acc_r, a.stream);
+            };
+            low->bwd.push_back(std::move(R));
+            written[nd.b] = true;
+            continue;
+        }
+        case Op::Softmax:
+            L.bytes += 4.0 * dag.numel(k);
+            L.run = [=](const RunArgs& a) { ref::softmax_bwd(val(a, k), grad(a, k), grad(a, nd.a), N, nd.C, nd.T, P, nd.kind == kAxisC, acc, a.stream); };
+            break;
+        case Op::Fold:
+            L.bytes += 4.0 * dag.numel(nd.a);
+            L.run = [=](const RunArgs& a) { ref::fold_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * A.C, A.T, P, nd.kind, acc, a.stream); };
+            break;
+        default: break;
+        }
+        low->bwd.push_back(std::move(L));
+        written[nd.a] = true;
+    }
+    for (int i = 0; i < dag.n_weights; i++) {
+        if (dag.nodes[dag.weight_node[i]].live) continue;
+        int64_t nw = wnumel[i];  // an fc the output does not depend on has a zero weight gradient
+        low->bwd.push_back({"zero_dw", nw * 4.0, 0, [=](const RunArgs& a) { ref::fill_f32((float*)a.dw[i], 0.f, nw, a.stream); }});
+    }
+    {
+        int64_t ne = dag.numel(0);
+        if (bf16) low->bwd.push_back({"narrow_dx", ne * 6.0, 0, [=](const RunArgs& a) { ref::narrow_bf16(grad(a, 0), a.dx, ne, a.stream); }});
+        else low->bwd.push_back({"copy_dx", ne * 8.0, 0, [=](const RunArgs& a) { ref::copy_f32(grad(a, 0), (float*)a.dx, ne, a.stream); }});
+    }
+    (void)esz;
+    return low;
+}
+
+}  // namespace canvas

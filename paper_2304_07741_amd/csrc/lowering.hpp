@@ -1,0 +1,47 @@
+// A lowering turns a parsed micro-DAG into a fixed list of kernel launches for forward and backward.
+// It is built once by canvas_dag_compile (host only) and replayed by canvas_dag_forward/backward.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <functional>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "dag.hpp"
+
+namespace canvas {
+
+struct RunArgs {
+    const void* x = nullptr;
+    const void* const* w = nullptr;
+    void* y = nullptr;
+    const void* dy = nullptr;
+    void* dx = nullptr;
+    void* const* dw = nullptr;
+    char* ws = nullptr;
+    hipStream_t stream = nullptr;
+};
+
+struct Launch {
+    std::string name;
+    double bytes = 0;  // algorithmic bytes: every operand of the launch once
+    double flops = 0;  // algorithmic flops of FC contractions
+    std::function<void(const RunArgs&)> run;
+};
+
+struct Lowering {
+    bool fused = false;
+    uint64_t ws_bytes = 0;
+    std::vector<Launch> fwd, bwd;
+};
+
+inline uint64_t align_up(uint64_t v, uint64_t a = 256) { return (v + a - 1) / a * a; }
+
+// One kernel per node, fp32 intermediates.  Handles every legal DAG.
+std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16);
+
+// Picks the lowering: fused kernel families where a pattern applies, else per node.
+std::unique_ptr<Lowering> lower(const Dag& dag, bool bf16, bool no_fusion);
+
+}  // namespace canvas

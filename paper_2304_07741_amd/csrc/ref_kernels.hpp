@@ -1,0 +1,37 @@
+// Launchers of the per-node fp32 kernels (unfused lowering).  All pointers are device pointers;
+// `acc` != 0 adds to the destination instead of overwriting it.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace canvas {
+namespace ref {
+
+void widen_bf16(const void* in, float* out, int64_t n, hipStream_t s);
+void narrow_bf16(const float* in, void* out, int64_t n, hipStream_t s);
+void fill_f32(float* out, float v, int64_t n, hipStream_t s);
+void copy_f32(const float* in, float* out, int64_t n, hipStream_t s);
+void unfold_fwd(const float* in, float* out, int64_t NC, int Tin, int KH, int KW, int H, int W, hipStream_t s);
+void unfold_bwd(const float* gout, float* gin, int64_t NC, int Tin, int KH, int KW, int H, int W, int acc, hipStream_t s);
+void shift(const float* src, float* dst, int64_t N, int C, int T, int H, int W, int dh, int dw, int c0, int c1, int acc,
+           hipStream_t s);
+void fc_fwd(const float* x, const float* wt, float* y, int64_t N, int G, int Og, int K, int P, hipStream_t s);
+void fc_dx(const float* gy, const float* wt, float* gx, int64_t N, int G, int Og, int K, int P, int acc, hipStream_t s);
+void fc_dw(const float* gy, const float* x, float* dw, int64_t N, int G, int Og, int K, int P, hipStream_t s);
+void unary_fwd(const float* in, float* out, int64_t n, int kind, float lo, float hi, hipStream_t s);
+void unary_bwd(const float* in, const float* gout, float* gin, int64_t n, int kind, float lo, float hi, int acc, hipStream_t s);
+void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int kind,
+                hipStream_t s);
+void binary_bwd_rhs(const float* lhs, const float* gout, float* grhs, int64_t N, int CL, int TL, int CR, int TR, int P,
+                    int kind, int acc, hipStream_t s);
+void binary_bwd_lhs(const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
+                    int kind, int acc, hipStream_t s);
+void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s);
+void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C, int T, int P, int axis_c, int acc,
+                 hipStream_t s);
+void fold_fwd(const float* in, float* out, int64_t NC, int T, int P, int kind, hipStream_t s);
+void fold_bwd(const float* in, const float* gout, float* gin, int64_t NC, int T, int P, int kind, int acc, hipStream_t s);
+
+}  // namespace ref
+}  // namespace canvas

@@ -1,0 +1,116 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every declared symbol,
+infers the same shapes as the oracle and rejects illegal blobs with the documented status codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2304_07741_amd import binding as B
+from paper_2304_07741_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__ as g
+
+        g.build()
+    return B.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "canvas_dag.h")).read()
+    declared = set(re.findall(r"\b(canvas_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_info_struct_matches_header(lib):
+    h = B.canvas_dag_compile(wl.blob_conv(3, 1, 16), (1, 16, 8, 8), B.CANVAS_F32)
+    info = B.canvas_dag_query(h)
+    assert info.n_nodes == 3 and info.out_node == 2 and info.n_weights == 1
+    assert list(info.out_shape) == [1, 16, 1, 8, 8]
+    assert list(info.weight_shape[0]) == [1, 16, 144] and info.weight_node[0] == 2
+    assert info.fc_flops_fwd == 2.0 * 64 * 16 * 144
+    assert info.min_bytes_fwd == 4.0 * (1024 + 1024 + 2304)
+    assert info.n_launches_fwd >= 1 and info.n_launches_bwd >= 1
+    d = B.canvas_dag_launch_desc(h, 0, 0)
+    assert d["name"] and d["bytes"] > 0
+    with pytest.raises(B.CanvasError):
+        B.canvas_dag_launch_desc(h, 0, 10000)
+    B.canvas_dag_destroy(h)
+
+
+def test_shapes_agree_with_the_oracle_bit_exactly(lib, oracle):
+    blobs = [wl.blob_conv(5, 2, 8), wl.blob_shift_residual(64), wl.blob_involution(128), wl.blob_sampled(64)]
+    blobs += [wl.fuzz_dag(s)[0] for s in range(100, 300)]
+    for blob in blobs:
+        C = 96 if "fuzz" in blob or blob in blobs[4:] else (128 if blob == blobs[2] else 64)
+        shape = (2, C, 6, 5)
+        ns, out, ws = oracle.infer(blob, shape)
+        for flags in (0, B.CANVAS_OPT_NO_FUSION):
+            h = B.canvas_dag_compile(blob, shape, B.CANVAS_BF16, flags)
+            info = B.canvas_dag_query(h)
+            assert info.n_nodes == len(ns) and info.out_node == out and info.n_weights == len(ws)
+            for k, s in enumerate(ns):
+                assert list(info.node_shape[k]) == [2] + s
+            for k, s in enumerate(ws):
+                assert list(info.weight_shape[k]) == s
+            B.canvas_dag_destroy(h)
+
+
+BAD = [
+    ("%1 = fc %0 groups=3 out=6\noutput %1\n", -3),
+    ("%1 = fc %0 groups=2 out=5\noutput %1\n", -3),
+    ("%1 = unfold %0 kh=2 kw=3\noutput %1\n", -3),
+    ("%1 = shift %0 dh=0 dw=1 c0=3 c1=9\noutput %1\n", -3),
+    ("%1 = fc %0 groups=1 out=5\n%2 = unfold %0 kh=3 kw=1\n%3 = binary %1 %2 op=add\noutput %3\n", -3),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = binary %1 %0 op=add\noutput %2\n", -3),
+    ("%2 = unary %0 op=relu\noutput %2\n", -1),
+    ("%1 = unary %1 op=relu\noutput %1\n", -1),
+    ("%1 = unary %0 op=relu\n", -1),
+    ("%1 = unary %0\noutput %1\n", -1),
+    ("%1 = unary %0 op=tanh\noutput %1\n", -2),
+    ("%1 = softmax %0 axis=H\noutput %1\n", -2),
+    ("%1 = conv %0 k=3\noutput %1\n", -2),
+    ("%1 = unary %0 op=expclip lo=1 hi=1\noutput %1\n", -3),
+]
+
+
+@pytest.mark.parametrize("body,status", BAD)
+def test_illegal_blobs_give_status_codes(lib, body, status):
+    with pytest.raises(B.CanvasError) as e:
+        B.canvas_dag_compile(wl.HEADER + body, (1, 4, 4, 4), B.CANVAS_F32)
+    assert e.value.status == status
+    assert str(e.value)
+
+
+def test_bad_arguments(lib):
+    with pytest.raises(B.CanvasError) as e:
+        B.canvas_dag_compile("garbage", (1, 4, 4, 4), B.CANVAS_F32)
+    assert e.value.status == -1
+    with pytest.raises(B.CanvasError) as e:
+        B.canvas_dag_compile(wl.blob_conv(), (1, 0, 4, 4), B.CANVAS_F32)
+    assert e.value.status == -4
+    with pytest.raises(B.CanvasError) as e:
+        B.canvas_dag_compile(wl.blob_conv(), (1, 4, 4, 4), 7)
+    assert e.value.status == -4
+    with pytest.raises(B.CanvasError) as e:
+        B.canvas_dag_compile(wl.blob_conv(), (1, 4, 4, 4), B.CANVAS_F32, flags=1 << 9)
+    assert e.value.status == -4
+    # forward with null pointers must be refused before any launch (no GPU is touched)
+    h = B.canvas_dag_compile(wl.blob_conv(3, 1, 4), (1, 4, 4, 4), B.CANVAS_F32)
+    rc = lib.canvas_dag_forward(h, None, None, None, None, 0, None)
+    assert rc == -4
+    arr = (ctypes.c_void_p * 1)(0x1000)
+    rc = lib.canvas_dag_forward(h, 0x1000, arr, 0x2000, 0x3000, 0, None)
+    assert rc == -5  # workspace too small
+    rc = lib.canvas_dag_forward(h, 0x1001, arr, 0x2000, 0x3000, 1 << 30, None)
+    assert rc == -4  # misaligned x
+    rc = lib.canvas_dag_backward(h, 0x1000, arr, 0x2000, None, arr, 0x3000, 1 << 30, None)
+    assert rc == -4
+    B.canvas_dag_destroy(h)
