@@ -1,0 +1,166 @@
+"""Benchmark: forward+backward images/s of a micro-DAG kernel on one MI355X, with the roofline fraction
+of its dominant kernel and the CPU oracle timed beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload shift_residual|involution|sampled_cC_hH]
+
+One step = one forward + one backward of the whole micro-DAG over one batch resident in HBM.  Buffer
+sets are rotated so that consecutive steps do not find their operands in the 256 MB last-level cache.
+Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def make_case(name):
+    from paper_2304_07741_amd import workloads as wl
+
+    if name == "shift_residual":
+        return wl.config2()
+    if name == "involution":
+        return wl.config3()
+    if name.startswith("sampled_c"):
+        c, h = name[len("sampled_c"):].split("_h")
+        return wl.config4(int(c), int(h))
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(case, budget_s=12.0):
+    """The oracle as it stands, timed on the host cores on the same workload (whole batch, repeated)."""
+    import numpy as np
+
+    from oracle import canvas_oracle
+    from paper_2304_07741_amd import workloads as wl
+
+    x = case["x"].astype(np.float64)
+    ws = [w.astype(np.float64) for w in case["weights"]]
+    ref = canvas_oracle.run(case["blob"], x, ws)
+    dy = wl.make_dy(case, ref["y"].shape).astype(np.float64)
+    times, threads = [], 1
+    t_end = time.time() + budget_s
+    while len(times) < 3 or (time.time() < t_end and len(times) < 15):
+        t0 = time.perf_counter()
+        r = canvas_oracle.run(case["blob"], x, ws, dy)
+        times.append(time.perf_counter() - t0)
+        threads = r["threads"]
+    N = case["shape"][0]
+    return {"value": N / statistics.median(times), "unit": "images/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"whole batch of {N} images, forward+backward, median of {len(times)} runs, "
+                      f"gcc {' '.join(canvas_oracle.CFLAGS[:2])}, OpenMP over the batch index"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="shift_residual")
+    ap.add_argument("--no-fusion", action="store_true", help="per-node lowering (for comparison)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+
+    from paper_2304_07741_amd import binding as B
+    from paper_2304_07741_amd import harness
+    from paper_2304_07741_amd import workloads as wl
+
+    case = make_case(args.workload)
+    N = case["shape"][0]
+    flags = B.CANVAS_OPT_NO_FUSION if args.no_fusion else 0
+    first = harness.DagRunner(case["blob"], case["shape"], case["dtype"], flags)
+    oshape = first.out_shape if first.out_shape[2] != 1 else (first.out_shape[0], first.out_shape[1], *first.out_shape[3:])
+    dy = wl.make_dy(case, oshape)
+    # rotate buffer sets: > 2x the last-level cache in total, at most 8 sets
+    per_set = sum(t.numel() * t.element_size() for t in (first.x, first.y, first.dy, first.dx)) + int(first.info.workspace_bytes)
+    n_sets = max(2, min(8, -(-600_000_000 // per_set)))
+    runners = [first] + [harness.DagRunner(case["blob"], case["shape"], case["dtype"], flags) for _ in range(n_sets - 1)]
+    for r in runners:
+        r.load(case["x"], case["weights"], dy)
+    torch.cuda.synchronize()
+
+    def step(i):
+        r = runners[i % n_sets]
+        r.forward()
+        r.backward()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    # per-kernel durations: the same steps again with HIP events around every launch
+    nf, nb = first.info.n_launches_fwd, first.info.n_launches_bwd
+    for r in runners:
+        B.canvas_dag_set_timing(r.handle, 1)
+    acc = [[0.0] * nf, [0.0] * nb]
+    psteps = min(args.steps, 50)
+    for i in range(psteps):
+        r = runners[i % n_sets]
+        r.forward()
+        r.backward()
+        for b, n in ((0, nf), (1, nb)):
+            for k, ms in enumerate(B.canvas_dag_get_timing(r.handle, b, n)):
+                acc[b][k] += ms / psteps
+    for r in runners:
+        B.canvas_dag_set_timing(r.handle, 0)
+    launches = []
+    for b in (0, 1):
+        for k, d in enumerate(first.launches(b)):
+            launches.append({"phase": "bwd" if b else "fwd", "name": d["name"], "ms": acc[b][k], "bytes": d["bytes"],
+                             "flops": d["flops"]})
+    dom = max(launches, key=lambda l: l["ms"])
+    hbm_t = dom["bytes"] / (HBM_PEAK_GBS * 1e9)
+    mfma_t = dom["flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if mfma_t > hbm_t:
+        ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    else:
+        ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                "traffic": None}
+    roof["kernel"] = f"{dom['name']} ({dom['phase']})"
+    roof["kernel_ms"] = dom["ms"]
+    roof["algorithmic_bytes"] = dom["bytes"]
+
+    out = {
+        "metric": "micro-DAG fwd+bwd images/sec at ResNet layer shapes; % HBM / MFMA roofline",
+        "value": N / (ms_per_step * 1e-3), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": case["dtype"], "data": "synthetic",
+        "config": {"workload": f"{case['name']} N={case['shape'][0]} C={case['shape'][1]} H=W={case['shape'][2]} "
+                               f"{case['dtype']} (seed {case['seed']})",
+                   "fused": bool(first.info.fused), "buffer_sets": n_sets,
+                   "launches_fwd": nf, "launches_bwd": nb, "workspace_bytes": int(first.info.workspace_bytes)},
+        "roofline": roof,
+        "kernels": [{"phase": l["phase"], "name": l["name"], "ms": round(l["ms"], 5),
+                     "GBps": round(l["bytes"] / max(l["ms"], 1e-9) / 1e6, 1),
+                     "TFLOPps": round(l["flops"] / max(l["ms"], 1e-9) / 1e9, 2)} for l in launches],
+        "min_bytes_fwd_bwd": first.info.min_bytes_fwd + first.info.min_bytes_bwd,
+        "whole_dag_hbm_frac": (first.info.min_bytes_fwd + first.info.min_bytes_bwd) / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(case)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

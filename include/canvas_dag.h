@@ -142,6 +142,16 @@ int canvas_dag_forward(canvas_dag* dag, const void* x, const void* const* weight
 int canvas_dag_backward(canvas_dag* dag, const void* x, const void* const* weights, const void* dy, void* dx,
                         void* const* dweights, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Benchmark aid.  enable != 0: every kernel launch of later forward/backward calls is bracketed by
+ * HIP events on the caller's stream (events are created here, not in the hot path).  enable == 0:
+ * events are destroyed.  Needs a GPU.  Errors: BAD_ARG, HIP_ERROR. */
+int canvas_dag_set_timing(canvas_dag* dag, int enable);
+
+/* Waits for the last timed forward (backward = 0) or backward (= 1) call and writes the duration of
+ * each of its n launches, in milliseconds, to ms (host pointer, n = n_launches_fwd or _bwd).
+ * Errors: BAD_ARG (timing not enabled, no call yet, wrong n), HIP_ERROR. */
+int canvas_dag_get_timing(canvas_dag* dag, int backward, float* ms, int n);
+
 void canvas_dag_destroy(canvas_dag* dag);
 
 /* Message of the last error on this thread ("" when none).  Host pointer owned by the library. */

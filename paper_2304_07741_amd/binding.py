@@ -16,7 +16,8 @@ CANVAS_MAX_NODES = 64
 STATUS = {0: "OK", -1: "INVALID_BLOB", -2: "UNKNOWN_OP", -3: "SHAPE_MISMATCH", -4: "BAD_ARG",
           -5: "WORKSPACE_TOO_SMALL", -6: "UNSUPPORTED", -7: "HIP_ERROR"}
 EXPORTS = ["canvas_dag_compile", "canvas_dag_query", "canvas_dag_launch_desc", "canvas_dag_forward",
-           "canvas_dag_backward", "canvas_dag_destroy", "canvas_last_error"]
+           "canvas_dag_backward", "canvas_dag_set_timing", "canvas_dag_get_timing", "canvas_dag_destroy",
+           "canvas_last_error"]
 
 
 class CanvasOptions(ctypes.Structure):
@@ -64,6 +65,8 @@ def load():
         lib.canvas_dag_launch_desc.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(CanvasLaunchDesc)]
         lib.canvas_dag_forward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, sz, vp]
         lib.canvas_dag_backward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, ctypes.POINTER(vp), vp, sz, vp]
+        lib.canvas_dag_set_timing.argtypes = [vp, ctypes.c_int]
+        lib.canvas_dag_get_timing.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.c_int]
         lib.canvas_dag_destroy.argtypes = [vp]
         lib.canvas_dag_destroy.restype = None
         lib.canvas_last_error.restype = ctypes.c_char_p
@@ -121,6 +124,17 @@ def canvas_dag_backward(handle, x, weights, dy, dx, dweights, workspace):
     _check(load().canvas_dag_backward(handle, x.data_ptr(), _ptrs(weights), dy.data_ptr(), dx.data_ptr(),
                                       _ptrs(dweights), workspace.data_ptr(),
                                       workspace.numel() * workspace.element_size(), _stream()))
+
+
+def canvas_dag_set_timing(handle, enable):
+    _check(load().canvas_dag_set_timing(handle, int(enable)))
+
+
+def canvas_dag_get_timing(handle, backward, n):
+    """Per-launch durations (ms) of the last timed forward or backward call."""
+    ms = (ctypes.c_float * max(1, n))()
+    _check(load().canvas_dag_get_timing(handle, int(backward), ms, int(n)))
+    return [float(ms[i]) for i in range(n)]
 
 
 def canvas_dag_destroy(handle):

@@ -4,6 +4,7 @@
 #include <cstring>
 #include <memory>
 #include <string>
+#include <vector>
 
 #include "../../include/canvas_dag.h"
 #include "dag.hpp"
@@ -14,6 +15,9 @@ struct canvas_dag {
     bool bf16 = false;
     std::unique_ptr<canvas::Lowering> low;
     canvas_dag_info info;
+    bool timing = false;
+    std::vector<hipEvent_t> ev[2];  // n_launches + 1 events per direction
+    bool timed_once[2] = {false, false};
 };
 
 namespace {
@@ -44,6 +48,30 @@ int finish_launches() {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return set_err(CANVAS_HIP_ERROR, std::string("kernel launch failed: ") + hipGetErrorString(e));
     return CANVAS_OK;
+}
+
+void run_launches(canvas_dag* d, int backward, const canvas::RunArgs& a) {
+    const auto& v = backward ? d->low->bwd : d->low->fwd;
+    if (!d->timing) {
+        for (const auto& l : v) l.run(a);
+        return;
+    }
+    auto& ev = d->ev[backward];
+    for (size_t i = 0; i < v.size(); i++) {
+        (void)hipEventRecord(ev[i], a.stream);
+        v[i].run(a);
+    }
+    (void)hipEventRecord(ev[v.size()], a.stream);
+    d->timed_once[backward] = true;
+}
+
+void drop_events(canvas_dag* d) {
+    for (auto& v : d->ev) {
+        for (hipEvent_t e : v) (void)hipEventDestroy(e);
+        v.clear();
+    }
+    d->timing = false;
+    d->timed_once[0] = d->timed_once[1] = false;
 }
 
 }  // namespace
@@ -137,7 +165,7 @@ int canvas_dag_forward(canvas_dag* dag, const void* x, const void* const* weight
     a.ws = (char*)workspace;
     a.stream = (hipStream_t)stream;
     (void)hipGetLastError();
-    for (const auto& l : dag->low->fwd) l.run(a);
+    run_launches(dag, 0, a);
     return finish_launches();
 }
 
@@ -160,11 +188,46 @@ int canvas_dag_backward(canvas_dag* dag, const void* x, const void* const* weigh
     a.ws = (char*)workspace;
     a.stream = (hipStream_t)stream;
     (void)hipGetLastError();
-    for (const auto& l : dag->low->bwd) l.run(a);
+    run_launches(dag, 1, a);
     return finish_launches();
 }
 
-void canvas_dag_destroy(canvas_dag* dag) { delete dag; }
+int canvas_dag_set_timing(canvas_dag* dag, int enable) {
+    if (!dag) return set_err(CANVAS_BAD_ARG, "null dag handle");
+    drop_events(dag);
+    if (!enable) return CANVAS_OK;
+    for (int b = 0; b < 2; b++) {
+        size_t n = (b ? dag->low->bwd.size() : dag->low->fwd.size()) + 1;
+        for (size_t i = 0; i < n; i++) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) {
+                drop_events(dag);
+                return set_err(CANVAS_HIP_ERROR, "hipEventCreate failed");
+            }
+            dag->ev[b].push_back(e);
+        }
+    }
+    dag->timing = true;
+    return CANVAS_OK;
+}
+
+int canvas_dag_get_timing(canvas_dag* dag, int backward, float* ms, int n) {
+    if (!dag || !ms) return set_err(CANVAS_BAD_ARG, "null argument");
+    backward = backward ? 1 : 0;
+    const size_t nl = backward ? dag->low->bwd.size() : dag->low->fwd.size();
+    if (!dag->timing || !dag->timed_once[backward]) return set_err(CANVAS_BAD_ARG, "no timed call to read");
+    if (n != (int)nl) return set_err(CANVAS_BAD_ARG, "n must equal the number of launches");
+    auto& ev = dag->ev[backward];
+    if (hipEventSynchronize(ev[nl]) != hipSuccess) return set_err(CANVAS_HIP_ERROR, "hipEventSynchronize failed");
+    for (size_t i = 0; i < nl; i++)
+        if (hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]) != hipSuccess) return set_err(CANVAS_HIP_ERROR, "hipEventElapsedTime failed");
+    return CANVAS_OK;
+}
+
+void canvas_dag_destroy(canvas_dag* dag) {
+    if (dag) drop_events(dag);
+    delete dag;
+}
 
 const char* canvas_last_error(void) { return g_err.c_str(); }
 
