@@ -142,8 +142,9 @@ int canvas_dag_forward(canvas_dag* dag, const void* x, const void* const* weight
 int canvas_dag_backward(canvas_dag* dag, const void* x, const void* const* weights, const void* dy, void* dx,
                         void* const* dweights, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Benchmark aid.  enable != 0: every kernel launch of later forward/backward calls is bracketed by
- * HIP events on the caller's stream (events are created here, not in the hot path).  enable == 0:
+/* Benchmark aid.  enable != 0: every kernel launch of later forward/backward calls carries a start and
+ * a stop HIP event on the caller's stream (events are created here, not in the hot path), so that
+ * canvas_dag_get_timing reports each kernel's own execution time.  enable == 0:
  * events are destroyed.  Needs a GPU.  Errors: BAD_ARG, HIP_ERROR. */
 int canvas_dag_set_timing(canvas_dag* dag, int enable);
 

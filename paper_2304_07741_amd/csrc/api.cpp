@@ -8,6 +8,7 @@
 
 #include "../../include/canvas_dag.h"
 #include "dag.hpp"
+#include "launch.hpp"
 #include "lowering.hpp"
 
 struct canvas_dag {
@@ -16,9 +17,13 @@ struct canvas_dag {
     std::unique_ptr<canvas::Lowering> low;
     canvas_dag_info info;
     bool timing = false;
-    std::vector<hipEvent_t> ev[2];  // n_launches + 1 events per direction
+    std::vector<hipEvent_t> ev[2];  // a (start, stop) pair per launch and direction
     bool timed_once[2] = {false, false};
 };
+
+namespace canvas {
+thread_local TimingEvents g_timing;
+}
 
 namespace {
 
@@ -58,10 +63,11 @@ void run_launches(canvas_dag* d, int backward, const canvas::RunArgs& a) {
     }
     auto& ev = d->ev[backward];
     for (size_t i = 0; i < v.size(); i++) {
-        (void)hipEventRecord(ev[i], a.stream);
+        canvas::g_timing.start = ev[2 * i];
+        canvas::g_timing.stop = ev[2 * i + 1];
         v[i].run(a);
     }
-    (void)hipEventRecord(ev[v.size()], a.stream);
+    canvas::g_timing = canvas::TimingEvents();
     d->timed_once[backward] = true;
 }
 
@@ -197,7 +203,7 @@ int canvas_dag_set_timing(canvas_dag* dag, int enable) {
     drop_events(dag);
     if (!enable) return CANVAS_OK;
     for (int b = 0; b < 2; b++) {
-        size_t n = (b ? dag->low->bwd.size() : dag->low->fwd.size()) + 1;
+        size_t n = (b ? dag->low->bwd.size() : dag->low->fwd.size()) * 2;
         for (size_t i = 0; i < n; i++) {
             hipEvent_t e;
             if (hipEventCreate(&e) != hipSuccess) {
@@ -218,9 +224,10 @@ int canvas_dag_get_timing(canvas_dag* dag, int backward, float* ms, int n) {
     if (!dag->timing || !dag->timed_once[backward]) return set_err(CANVAS_BAD_ARG, "no timed call to read");
     if (n != (int)nl) return set_err(CANVAS_BAD_ARG, "n must equal the number of launches");
     auto& ev = dag->ev[backward];
-    if (hipEventSynchronize(ev[nl]) != hipSuccess) return set_err(CANVAS_HIP_ERROR, "hipEventSynchronize failed");
-    for (size_t i = 0; i < nl; i++)
-        if (hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]) != hipSuccess) return set_err(CANVAS_HIP_ERROR, "hipEventElapsedTime failed");
+    for (size_t i = 0; i < nl; i++) {
+        if (hipEventSynchronize(ev[2 * i + 1]) != hipSuccess) return set_err(CANVAS_HIP_ERROR, "hipEventSynchronize failed");
+        if (hipEventElapsedTime(&ms[i], ev[2 * i], ev[2 * i + 1]) != hipSuccess) return set_err(CANVAS_HIP_ERROR, "hipEventElapsedTime failed");
+    }
     return CANVAS_OK;
 }
 

@@ -19,7 +19,7 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 // Element-wise primitives (Section 5): relu, abs, gelu (erf form), exp of the clamped input.
 __device__ __forceinline__ float unary_apply(int kind, float x, float lo, float hi) {
     switch (kind) {
-    case 0: return x > 0.f ? x : 0.f;
+    case 0: return __builtin_fmaxf(x, 0.f);
     case 1: return fabsf(x);
     case 2: return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
     default: return expf(fminf(fmaxf(x, lo), hi));

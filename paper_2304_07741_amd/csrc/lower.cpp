@@ -4,7 +4,9 @@
 namespace canvas {
 
 std::unique_ptr<Lowering> lower(const Dag& dag, bool bf16, bool no_fusion) {
-    (void)no_fusion;
+    if (!no_fusion) {
+        if (auto l = lower_sgfc(dag, bf16)) return l;
+    }
     return lower_per_node(dag, bf16);
 }
 

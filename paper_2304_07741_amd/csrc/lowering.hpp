@@ -41,6 +41,9 @@ inline uint64_t align_up(uint64_t v, uint64_t a = 256) { return (v + a - 1) / a 
 // One kernel per node, fp32 intermediates.  Handles every legal DAG.
 std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16);
 
+// Fused shift -> grouped FC -> unary chain -> (+ input); nullptr when the DAG is not of that form.
+std::unique_ptr<Lowering> lower_sgfc(const Dag& dag, bool bf16);
+
 // Picks the lowering: fused kernel families where a pattern applies, else per node.
 std::unique_ptr<Lowering> lower(const Dag& dag, bool bf16, bool no_fusion);
 

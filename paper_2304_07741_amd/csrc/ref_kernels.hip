@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include "device_util.hpp"
+#include "launch.hpp"
 
 namespace canvas {
 namespace ref {
@@ -351,7 +352,7 @@ __global__ void k_fold_bwd(const float* __restrict__ in, const float* __restrict
 
 #define LAUNCH(kern, total, ...)                                                                  \
     do {                                                                                          \
-        if ((total) > 0) hipLaunchKernelGGL(kern, grid_for(total), dim3(kBlock), 0, s, __VA_ARGS__); \
+        if ((total) > 0) CANVAS_LAUNCH(kern, grid_for(total), dim3(kBlock), 0, s, __VA_ARGS__); \
     } while (0)
 
 void widen_bf16(const void* in, float* out, int64_t n, hipStream_t s) { LAUNCH(k_bf16_to_f32, n, (const uint16_t*)in, out, n); }
@@ -382,7 +383,7 @@ void fc_dx(const float* gy, const float* wt, float* gx, int64_t N, int G, int Og
 }
 void fc_dw(const float* gy, const float* x, float* dw, int64_t N, int G, int Og, int K, int P, hipStream_t s) {
     int64_t nw = (int64_t)G * Og * K;
-    if (nw > 0) hipLaunchKernelGGL(k_fc_dw, dim3((unsigned)nw), dim3(kBlock), 0, s, gy, x, dw, (int)N, G, Og, K, P);
+    if (nw > 0) CANVAS_LAUNCH(k_fc_dw, dim3((unsigned)nw), dim3(kBlock), 0, s, gy, x, dw, (int)N, G, Og, K, P);
 }
 void unary_fwd(const float* in, float* out, int64_t n, int kind, float lo, float hi, hipStream_t s) {
     LAUNCH(k_unary_fwd, n, in, out, n, kind, lo, hi);
