@@ -90,7 +90,44 @@ def test_config1_conv_fp32(harness, oracle):
 def test_config2_shift_residual(harness, oracle, N, H, flags):
     case = wl.config2(N=N, H=H)
     res, r, dy = harness.run_case(case, flags)
+    assert r.info.fused == (1 if flags == 0 and H in (56, 8) else 0)
     check_against_oracle(oracle, case, res, dy)
+    r.close()
+
+
+SGFC_VARIANTS = [
+    # (offsets per 16-channel group, unary, residual, N, H, W)
+    ([(0, 1), (0, -1), (1, 0), (-1, 0)], "relu", True, 2, 28, 28),     # 8-pixel units straddle rows
+    ([(0, 2), (-2, 0), (1, 0), (0, 0)], "gelu", True, 2, 16, 24),      # larger shifts, H != W
+    ([(0, 1), (0, -1), (1, 0), (-1, 0)], None, False, 1, 8, 8),         # plain shift convolution
+    ([(0, 0), (0, 0), (0, 0), (0, 0)], "abs", True, 3, 12, 10),         # no shift at all
+    ([(1, 1), (-1, -1), (1, -1), (-1, 1)], "expclip lo=-1 hi=1", False, 2, 8, 16),
+    ([(0, 1), (0, -1), (1, 0), (-1, 0)], "relu", True, 1, 4, 8),        # one half-empty tile
+    ([(0, 9), (0, -9), (5, 0), (-5, 0)], "relu", True, 1, 4, 8),        # shifts larger than the image
+]
+
+
+@pytest.mark.parametrize("idx", range(len(SGFC_VARIANTS)))
+def test_fused_shift_fc_variants(harness, oracle, idx):
+    """The fused shift -> grouped FC -> unary -> (+x) kernels over their parameter space."""
+    offs, unary, res, N, H, W = SGFC_VARIANTS[idx]
+    lines, k = [], 0
+    for g, (dh, dw) in enumerate(offs):
+        lines.append(f"%{k + 1} = shift %{k} dh={dh} dw={dw} c0={16 * g} c1={16 * g + 16}\n")
+        k += 1
+    lines.append(f"%{k + 1} = fc %{k} groups=4 out=64\n")
+    k += 1
+    if unary:
+        lines.append(f"%{k + 1} = unary %{k} op={unary}\n")
+        k += 1
+    if res:
+        lines.append(f"%{k + 1} = binary %{k} %0 op=add\n")
+        k += 1
+    lines.append(f"output %{k}\n")
+    case = _mk("".join(lines), (N, 64, H, W), "bf16", 70 + idx, [(4, 16, 16)], f"sgfc{idx}")
+    res_, r, dy = harness.run_case(case)
+    assert r.info.fused == 1, "the fused lowering was not selected"
+    check_against_oracle(oracle, case, res_, dy)
     r.close()
 
 
