@@ -438,7 +438,7 @@ __device__ __forceinline__ void bwd_body(const Params& P) {
     for (int it = 0; it < P.tiles_per_wave; it++) {
         const int t = (wg * kWaves + wave) * P.tiles_per_wave + it;
         if (t >= tiles_per_group) break;
-        const int n = (int)__umulhi((uint32_t)t, P.magicChunks), chunk = t - n * P.chunks;
+        const int n = P.chunks == 1 ? t : (int)__umulhi((uint32_t)t, P.magicChunks), chunk = t - n * P.chunks;  // magic overflows for 1
         bwd_tile<KC, MO, ACT, RES>(P, rx, rdy, rdx, lds_x, lds_dz, n, g, chunk * kTilePx, lane, wa, wt, dwacc);
     }
     // the workgroup's four wavefronts are summed in a fixed order through LDS: one partial per workgroup;
