@@ -1,0 +1,450 @@
+// Grouped FC on bf16 MFMA with an implicit (never materialised) Unfold of the operand.
+//
+//   forward / data gradient:  y[n, g*Og+o, p] (+)= sum_k w[g][o][k] * row(n, g, k)[p + off(k)]
+//   weight gradient:          dw[g][o][k] = sum_{n,p} dy[n, g*Og+o, p] * row(n, g, k)[p + off(k)]
+//
+// Canvas paper, Section 5: Fully-connected remaps all channel dims (channels of a group and taps) to a
+// new channel dim, groups stay apart; Unfold is an index rearrangement U(c,kh,kw,h,w) = I(c,h+kh,w+kw),
+// so the contraction reads the un-unfolded tensor at shifted addresses with zeros outside the image.
+// The data gradient of an FC that consumed an Unfold is the same contraction applied to dy with
+// transposed, tap-flipped weights (transpose_weights), which also folds the Unfold adjoint in.
+//
+// NCHW keeps pixels contiguous and the contraction index strided, while an MFMA operand wants the
+// contraction index in the lane.  As in the fused shift/FC kernels, a lane loads 8 consecutive pixels of
+// 4 rows and assembles the operand of pixel offset q from the q-th halves (two byte-permutes), so the
+// forward tile needs no LDS.  In the weight gradient the contraction runs over pixels, which is the
+// memory order of both operands: 16-byte loads are MFMA operands as they are.
+#include "gfc_kernels.hpp"
+
+#include <hip/hip_runtime.h>
+
+#include "launch.hpp"
+#include "tile_util.hpp"
+
+namespace canvas {
+namespace gfc {
+
+namespace {
+
+using namespace canvas::tile;
+
+constexpr int kWaves = 4;
+
+__device__ __forceinline__ uint32_t div_magic(uint32_t x, uint32_t magic) { return magic ? __umulhi(x, magic) : x; }
+
+// Validity bits of a lane's 8 consecutive pixels starting at flat pixel p (all of one image):
+// rowpack byte i / colpack byte i hold, for window row i / column i, which of the 8 pixels have their
+// source row / column inside the image.  Needs W >= 4 (a run of 8 pixels wraps at most twice).
+struct PixGeom {
+    uint64_t rowpack, colpack;
+};
+__device__ __forceinline__ PixGeom pix_geom(const Params& P, int p) {
+    PixGeom gm;
+    gm.rowpack = 0;
+    gm.colpack = 0;
+    const int h0 = (int)div_magic((uint32_t)p, P.magicW), w0 = p - h0 * P.W;
+#pragma unroll
+    for (int q = 0; q < 8; q++) {
+        int c = w0 + q, h = h0;
+        if (c >= P.W) { c -= P.W; h++; }
+        if (c >= P.W) { c -= P.W; h++; }
+        const bool inside = p + q < P.P;
+        for (int i = 0; i < P.KH; i++)
+            if (inside && (unsigned)(h + i - P.KH / 2) < (unsigned)P.H) gm.rowpack |= (uint64_t)1 << (8 * i + q);
+        for (int i = 0; i < P.KW; i++)
+            if ((unsigned)(c + i - P.KW / 2) < (unsigned)P.W) gm.colpack |= (uint64_t)1 << (8 * i + q);
+    }
+    return gm;
+}
+__device__ __forceinline__ uint32_t tap_bits(const PixGeom& gm, int khi, int kwi) {
+    return (uint32_t)(gm.rowpack >> (8 * khi)) & (uint32_t)(gm.colpack >> (8 * kwi)) & 0xffu;
+}
+
+// Validity bits of the 8 pixels p..p+7 under the window offset (dh, dw), computed directly.
+__device__ __forceinline__ uint32_t tap_bits_direct(const Params& P, int p, int dh, int dw) {
+    int h = (int)div_magic((uint32_t)p, P.magicW), c = p - h * P.W;
+    uint32_t bits = 0;
+#pragma unroll
+    for (int q = 0; q < 8; q++) {
+        const bool v = p + q < P.P && (unsigned)(h + dh) < (unsigned)P.H && (unsigned)(c + dw) < (unsigned)P.W;
+        bits |= (v ? 1u : 0u) << q;
+        if (++c == P.W) { c = 0; h++; }
+    }
+    return bits;
+}
+
+// 8 consecutive elements at element offset `e` of a bf16 or fp32 buffer as packed bf16.  An fp32 source
+// is split into hi = bf16(x) and lo = bf16(x - hi): feeding both to the MFMA keeps ~16 mantissa bits, so
+// an fp32 intermediate is not degraded to bf16 just because the next node is an FC.
+struct Pair8 {
+    u32x4 hi, lo;
+};
+__device__ __forceinline__ void split2(float a, float b, Pair8& v, int k) {
+    const uint32_t hi = pack_bf16(a, b);
+    v.hi[k] = hi;
+    v.lo[k] = pack_bf16(a - lo_f32(hi), b - hi_f32(hi));
+}
+template <bool F32>
+__device__ __forceinline__ Pair8 load8(rsrc_t r, int e, bool ok) {
+    Pair8 v;
+    if (!F32) {
+        v.hi = bload16(r, ok ? e * 2 : kOob);
+        v.lo = u32x4{0u, 0u, 0u, 0u};
+        return v;
+    }
+    const u32x4 a = bload16(r, ok ? e * 4 : kOob), b = bload16(r, ok ? e * 4 + 16 : kOob);
+    split2(__uint_as_float(a[0]), __uint_as_float(a[1]), v, 0);
+    split2(__uint_as_float(a[2]), __uint_as_float(a[3]), v, 1);
+    split2(__uint_as_float(b[0]), __uint_as_float(b[1]), v, 2);
+    split2(__uint_as_float(b[2]), __uint_as_float(b[3]), v, 3);
+    return v;
+}
+// Same, element by element: used where the 16-byte accesses could be partly outside the buffer (the
+// hardware then drops them as a whole) -- only for tiles at the two ends of a tensor.
+template <bool F32>
+__device__ __forceinline__ Pair8 load8_slow(rsrc_t r, int e, bool ok) {
+    Pair8 v;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        if (F32) {
+            const float a = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, ok ? (e + 2 * k) * 4 : kOob, 0, 0));
+            const float b = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, ok ? (e + 2 * k + 1) * 4 : kOob, 0, 0));
+            split2(a, b, v, k);
+        } else {
+            const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(r, ok ? (e + 2 * k) * 2 : kOob, 0, 0);
+            const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(r, ok ? (e + 2 * k + 1) * 2 : kOob, 0, 0);
+            v.hi[k] = lo | (hi << 16);
+            v.lo[k] = 0u;
+        }
+    }
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------- forward
+// One wavefront: 16*MO output channels x 128 pixels of one image and group; K in steps of 16.
+// Lane (r = lane/16, s = lane%16): B operand rows k = 16*kc + 4r + j at pixels p0+8s..+7; A operand
+// w[o = 16*mo + s][k = 16*kc + 4r ..+3]; accumulator acc[mo][q][j] = y[o = 16*mo + 4r + j][p0 + 8s + q].
+template <int MO, bool SRC_F32, bool DST_F32, bool TAPS>
+__global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int chunk = blockIdx.x * kWaves + wave;
+    if (chunk >= P.chunks) return;
+    const int g = blockIdx.y / P.otiles, ot = blockIdx.y - g * P.otiles, n = blockIdx.z;
+    const int r = lane >> 4, s = lane & 15;
+    const int p0 = chunk * 128, p = p0 + 8 * s;
+    const bool live = p < P.P;
+    const int esz = SRC_F32 ? 4 : 2;
+    const int src_elems = P.N * P.G * P.R * P.P;
+    const rsrc_t rs = make_rsrc(P.src, src_elems * esz);
+    const rsrc_t rw = make_rsrc(P.w, P.G * P.Og * P.K * 2);
+    const int row0 = (n * P.G + g) * P.R;  // first source row of this image and group
+    const int obase = ot * 16 * MO;
+
+    PixGeom gm = {0, 0};
+    if (TAPS) gm = pix_geom(P, live ? p : 0);
+    const int maxoff = (P.KH / 2) * P.W + P.KW / 2;
+    // wave-uniform: could a 16/32-byte access of this tile straddle an end of the source tensor?
+    const bool near_ends = row0 * P.P + p0 - maxoff < 0 || (row0 + P.R - 1) * P.P + p0 + 128 + 8 + maxoff > src_elems;
+
+    float4_t acc[MO][8];
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+        for (int q = 0; q < 8; q++) acc[mo][q] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int k0 = 0; k0 < P.K; k0 += 16) {
+        short4_t wa[MO];
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++) {
+            const int o = obase + mo * 16 + s;
+            const int widx = ((g * P.Og + o) * P.K + k0 + 4 * r) * 2;
+            uint32_t w2[2];
+            if (o < P.Og && k0 + 4 * r + 3 < P.K) {
+                // (the 8-byte access stays inside the weight tensor: it ends at or before the row's end)
+                const auto t = __builtin_amdgcn_raw_buffer_load_b64(rw, widx, 0, 0);
+                w2[0] = t[0];
+                w2[1] = t[1];
+            } else {
+                uint32_t h[4];
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    h[i] = (o < P.Og && k0 + 4 * r + i < P.K) ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rw, widx + 2 * i, 0, 0) : 0u;
+                w2[0] = h[0] | (h[1] << 16);
+                w2[1] = h[2] | (h[3] << 16);
+            }
+            wa[mo] = as_short4(w2[0], w2[1]);
+        }
+        u32x4 xs[4], xl[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int k = k0 + 4 * r + j;
+            int row = k, off = 0;
+            uint32_t bits = 0xffu;
+            if (TAPS) {
+                row = (int)div_magic((uint32_t)k, P.magicTV);
+                const int tv = k - row * P.TV;
+                const int khi = (int)div_magic((uint32_t)tv, P.magicKW), kwi = tv - khi * P.KW;
+                off = (khi - P.KH / 2) * P.W + (kwi - P.KW / 2);
+                bits = tap_bits(gm, khi, kwi);
+            }
+            const bool ok = live && k < P.K;
+            const int e = (row0 + row) * P.P + p + off;
+            const Pair8 v = near_ends ? load8_slow<SRC_F32>(rs, e, ok) : load8<SRC_F32>(rs, e, ok);
+            xs[j] = v.hi;
+            xl[j] = v.lo;
+            if (TAPS) {
+                const u32x4 m = mask_of(bits);
+                xs[j] = xs[j] & m;
+                xl[j] = xl[j] & m;
+            }
+        }
+        short4_t b[8];
+        gather_all(xs, b);
+#pragma unroll
+        for (int q = 0; q < 8; q++)
+#pragma unroll
+            for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[mo], b[q], acc[mo][q]);
+        if (SRC_F32) {
+            gather_all(xl, b);
+#pragma unroll
+            for (int q = 0; q < 8; q++)
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[mo], b[q], acc[mo][q]);
+        }
+    }
+
+    if (!live) return;
+    const int nvalid = min(8, P.P - p);
+    const int dsz = DST_F32 ? 4 : 2;
+    const rsrc_t rd = make_rsrc(P.dst, P.N * P.G * P.Og * P.P * dsz);
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int o = obase + mo * 16 + 4 * r + j;
+            if (o >= P.Og) continue;
+            const int e = ((n * P.G + g) * P.Og + o) * P.P + p;
+            float v[8];
+#pragma unroll
+            for (int q = 0; q < 8; q++) v[q] = acc[mo][q][j];
+            if (nvalid == 8) {
+                if (DST_F32) {
+                    u32x4 lo, hi;
+                    if (P.acc) {
+                        lo = bload16(rd, e * 4);
+                        hi = bload16(rd, e * 4 + 16);
+#pragma unroll
+                        for (int k = 0; k < 4; k++) {
+                            v[k] += __uint_as_float(lo[k]);
+                            v[4 + k] += __uint_as_float(hi[k]);
+                        }
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        lo[k] = __float_as_uint(v[k]);
+                        hi[k] = __float_as_uint(v[4 + k]);
+                    }
+                    bstore16(rd, e * 4, lo);
+                    bstore16(rd, e * 4 + 16, hi);
+                } else {
+                    u32x4 out;
+#pragma unroll
+                    for (int k = 0; k < 4; k++) out[k] = pack_bf16(v[2 * k], v[2 * k + 1]);
+                    bstore16(rd, e * 2, out);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 8; q++) {
+                    if (q >= nvalid) break;
+                    if (DST_F32) {
+                        float* d = reinterpret_cast<float*>(P.dst) + e + q;
+                        *d = P.acc ? *d + v[q] : v[q];
+                    } else {
+                        reinterpret_cast<uint16_t*>(P.dst)[e + q] = (uint16_t)(pack_bf16(v[q], 0.f) & 0xffffu);
+                    }
+                }
+            }
+        }
+}
+
+// ----------------------------------------------------------------------------------- weight gradient
+// One wavefront: a 16*MO x 16*NK tile of dw[g] over a slice of the (image, pixel) range, 32 pixels per
+// step.  Lane (r, s) loads pixels 8r..8r+7 of the step from dy row o = 16*mo + s and from operand row
+// k = 16*nk + s: the two halves of each 16-byte load are the A / B operands of two MFMAs whose
+// contraction slot 4r+jj is pixel 8r + 4*half + jj.  Result: lane holds dw[o = 16*mo + 4r + jj][k = 16*nk + s].
+template <int MO, int NK, bool SRC_F32, bool TAPS>
+__global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int slice = blockIdx.x * kWaves + wave;
+    if (slice >= P.slices) return;
+    const int g = blockIdx.z;
+    const int ot = blockIdx.y / P.ktiles, kt = blockIdx.y - ot * P.ktiles;
+    const int r = lane >> 4, s = lane & 15;
+    const int esz = SRC_F32 ? 4 : 2;
+    const int src_elems = P.N * P.G * P.R * P.P;
+    const rsrc_t rs = make_rsrc(P.src, src_elems * esz);
+    const rsrc_t rdy = make_rsrc(P.dy, P.N * P.G * P.Og * P.P * 4);
+    const int obase = ot * 16 * MO, kbase = kt * 16 * NK;
+
+    // this lane's operand rows: fixed source row, tap offset and window position per nk
+    int krow[NK], koff[NK], khi[NK], kwi[NK];
+    bool kok[NK];
+#pragma unroll
+    for (int nk = 0; nk < NK; nk++) {
+        const int k = kbase + nk * 16 + s;
+        kok[nk] = k < P.K;
+        krow[nk] = k;
+        koff[nk] = 0;
+        khi[nk] = kwi[nk] = 0;
+        if (TAPS) {
+            krow[nk] = (int)div_magic((uint32_t)k, P.magicTV);
+            const int tv = k - krow[nk] * P.TV;
+            khi[nk] = (int)div_magic((uint32_t)tv, P.magicKW);
+            kwi[nk] = tv - khi[nk] * P.KW;
+            koff[nk] = (khi[nk] - P.KH / 2) * P.W + (kwi[nk] - P.KW / 2);
+        }
+    }
+    float4_t acc[MO][NK];
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+        for (int nk = 0; nk < NK; nk++) acc[mo][nk] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    const int c_begin = slice * P.per_slice, c_end = min(P.N * P.chunks32, c_begin + P.per_slice);
+    int n = (int)div_magic((uint32_t)c_begin, P.magicC32);
+    int pc = c_begin - n * P.chunks32;
+    const int maxoff = (P.KH / 2) * P.W + P.KW / 2;
+    for (int c = c_begin; c < c_end; c++) {
+        const int p = pc * 32 + 8 * r;
+        const bool live = p < P.P;
+        const int nvalid = live ? min(8, P.P - p) : 0;
+        const int row0 = (n * P.G + g) * P.R;
+        const bool near_ends = row0 * P.P + pc * 32 - maxoff < 0 || (row0 + P.R - 1) * P.P + pc * 32 + 40 + maxoff > src_elems ||
+                               ((n * P.G + g) * P.Og + P.Og - 1) * P.P + pc * 32 + 40 > P.N * P.G * P.Og * P.P;
+        const u32x4 mvalid = mask_of(nvalid >= 8 ? 0xffu : ((1u << nvalid) - 1u));
+        Pair8 a[MO], b[NK];  // dy is fp32: hi + lo; the operand rows too when they are fp32
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++) {
+            const int o = obase + mo * 16 + s;
+            const bool ok = live && o < P.Og;
+            const int e = ((n * P.G + g) * P.Og + o) * P.P + p;
+            a[mo] = near_ends ? load8_slow<true>(rdy, e, ok) : load8<true>(rdy, e, ok);
+            a[mo].hi = a[mo].hi & mvalid;
+            a[mo].lo = a[mo].lo & mvalid;
+        }
+#pragma unroll
+        for (int nk = 0; nk < NK; nk++) {
+            const bool ok = live && kok[nk];
+            const int e = (row0 + krow[nk]) * P.P + p + koff[nk];
+            b[nk] = near_ends ? load8_slow<SRC_F32>(rs, e, ok) : load8<SRC_F32>(rs, e, ok);
+            if (TAPS) {
+                const u32x4 m = mask_of(live ? tap_bits_direct(P, p, khi[nk] - P.KH / 2, kwi[nk] - P.KW / 2) : 0u);
+                b[nk].hi = b[nk].hi & m;
+                b[nk].lo = b[nk].lo & m;
+            }
+        }
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int nk = 0; nk < NK; nk++) {
+                float4_t c = acc[mo][nk];
+                c = mfma16(as_short4(a[mo].hi[0], a[mo].hi[1]), as_short4(b[nk].hi[0], b[nk].hi[1]), c);
+                c = mfma16(as_short4(a[mo].hi[2], a[mo].hi[3]), as_short4(b[nk].hi[2], b[nk].hi[3]), c);
+                c = mfma16(as_short4(a[mo].lo[0], a[mo].lo[1]), as_short4(b[nk].hi[0], b[nk].hi[1]), c);
+                c = mfma16(as_short4(a[mo].lo[2], a[mo].lo[3]), as_short4(b[nk].hi[2], b[nk].hi[3]), c);
+                if (SRC_F32) {
+                    c = mfma16(as_short4(a[mo].hi[0], a[mo].hi[1]), as_short4(b[nk].lo[0], b[nk].lo[1]), c);
+                    c = mfma16(as_short4(a[mo].hi[2], a[mo].hi[3]), as_short4(b[nk].lo[2], b[nk].lo[3]), c);
+                }
+                acc[mo][nk] = c;
+            }
+        if (++pc == P.chunks32) { pc = 0; n++; }
+    }
+    float* part = P.partial + (long long)slice * P.G * P.Og * P.K;
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+        for (int nk = 0; nk < NK; nk++)
+#pragma unroll
+            for (int jj = 0; jj < 4; jj++) {
+                const int o = obase + mo * 16 + 4 * r + jj, k = kbase + nk * 16 + s;
+                if (o < P.Og && k < P.K) part[((long long)g * P.Og + o) * P.K + k] = acc[mo][nk][jj];
+            }
+}
+
+__global__ void k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ dw, int slices, long long elems) {
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= elems) return;
+    float s = 0.f;
+    for (int k = 0; k < slices; k++) s += partial[(long long)k * elems + e];
+    dw[e] = s;
+}
+
+__global__ void k_transpose_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt, int G, int Og, int R, int TV) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long total = (long long)G * R * Og * TV;
+    if (i >= total) return;
+    const int tv = (int)(i % TV);
+    long long q = i / TV;
+    const int o = (int)(q % Og);
+    q /= Og;
+    const int row = (int)(q % R), g = (int)(q / R);
+    wt[i] = w[((long long)(g * Og + o) * R + row) * TV + (TV - 1 - tv)];
+}
+
+template <int MO>
+void launch_fwd(const Params& P, hipStream_t s) {
+    const dim3 grid((unsigned)((P.chunks + kWaves - 1) / kWaves), (unsigned)(P.G * P.otiles), (unsigned)P.N);
+    const dim3 block(64 * kWaves);
+    const bool taps = P.TV > 1;
+#define GFC_FWD(SF, DF, TP) CANVAS_LAUNCH((k_fwd<MO, SF, DF, TP>), grid, block, 0, s, P)
+    if (P.src_f32) {
+        if (P.dst_f32) { if (taps) GFC_FWD(true, true, true); else GFC_FWD(true, true, false); }
+        else { if (taps) GFC_FWD(true, false, true); else GFC_FWD(true, false, false); }
+    } else {
+        if (P.dst_f32) { if (taps) GFC_FWD(false, true, true); else GFC_FWD(false, true, false); }
+        else { if (taps) GFC_FWD(false, false, true); else GFC_FWD(false, false, false); }
+    }
+#undef GFC_FWD
+}
+
+}  // namespace
+
+int choose_mo(int Og) { return Og <= 16 ? 1 : (Og <= 32 ? 2 : 4); }
+
+void forward(const Params& P, hipStream_t s) {
+    if (P.N * P.G * P.Og * P.P == 0 || P.K == 0) return;
+    switch (choose_mo(P.Og)) {
+    case 1: launch_fwd<1>(P, s); break;
+    case 2: launch_fwd<2>(P, s); break;
+    default: launch_fwd<4>(P, s); break;
+    }
+}
+
+void wgrad_partial(const Params& P, hipStream_t s) {
+    if (P.slices == 0) return;
+    const dim3 grid((unsigned)((P.slices + kWaves - 1) / kWaves), (unsigned)(P.otiles * P.ktiles), (unsigned)P.G);
+    const dim3 block(64 * kWaves);
+    const bool taps = P.TV > 1;
+    if (P.src_f32) {
+        if (taps) CANVAS_LAUNCH((k_wgrad<2, 2, true, true>), grid, block, 0, s, P);
+        else CANVAS_LAUNCH((k_wgrad<2, 2, true, false>), grid, block, 0, s, P);
+    } else {
+        if (taps) CANVAS_LAUNCH((k_wgrad<2, 2, false, true>), grid, block, 0, s, P);
+        else CANVAS_LAUNCH((k_wgrad<2, 2, false, false>), grid, block, 0, s, P);
+    }
+}
+
+void wgrad_reduce(const float* partial, float* dw, int slices, int64_t elems, hipStream_t s) {
+    if (elems > 0) CANVAS_LAUNCH(k_wgrad_reduce, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, s, partial, dw, slices, (long long)elems);
+}
+
+void transpose_weights(const uint16_t* w, uint16_t* wt, int G, int Og, int R, int TV, hipStream_t s) {
+    const long long total = (long long)G * R * Og * TV;
+    if (total > 0) CANVAS_LAUNCH(k_transpose_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, w, wt, G, Og, R, TV);
+}
+
+}  // namespace gfc
+}  // namespace canvas

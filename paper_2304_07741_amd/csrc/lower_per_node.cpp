@@ -2,7 +2,10 @@
 // Values and gradients of all nodes live in the workspace as fp32 [N, C, T, H, W]; bf16 inputs are
 // widened once on entry and results narrowed once on exit.
 #include "lowering.hpp"
+#include "gfc_kernels.hpp"
 #include "ref_kernels.hpp"
+
+#include <algorithm>
 
 namespace canvas {
 
@@ -10,6 +13,7 @@ namespace {
 
 struct Layout {
     std::vector<int64_t> val, grad, wf;  // byte offsets into the workspace; -1 = not in the workspace
+    std::vector<int64_t> wt, part;       // per fc (bf16 path): transposed weights, weight-gradient partials
     uint64_t total = 0;
 };
 
@@ -43,8 +47,34 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         off += align_up((uint64_t)numel * 4);
         return (int64_t)o;
     };
+    // bf16 path: FC nodes run on MFMA and read an Unfold operand implicitly.  An Unfold whose every
+    // consumer is such an FC is never materialised (no value, no gradient, no launch).
+    auto bytes_ok = [&](int64_t numel) { return numel * 4 < ((int64_t)1 << 31); };
+    bool mfma = bf16 && dag.W >= 4 && (int64_t)dag.N * dag.P() < ((int64_t)1 << 28);
+    for (int k = 1; k < n && mfma; k++) {
+        const Node& f = dag.nodes[k];
+        if (!f.live || f.op != Op::Fc) continue;
+        const Node& A = dag.nodes[f.a];
+        const int srcn = A.op == Op::Unfold ? A.a : f.a;  // the larger of the two possible operands is f.a
+        mfma = bytes_ok(dag.numel(f.a)) && bytes_ok(dag.numel(srcn)) && bytes_ok(dag.numel(k)) &&
+               bytes_ok((int64_t)f.out * (A.C / f.groups) * A.T);
+    }
+    std::vector<bool> virt(n, false);
+    if (mfma) {
+        for (int k = 1; k < n; k++) {
+            const Node& u = dag.nodes[k];
+            if (!u.live || u.op != Op::Unfold || u.kh > 7 || u.kw > 7) continue;
+            bool only_fc = true;
+            for (int j = k + 1; j < n; j++) {
+                const Node& c = dag.nodes[j];
+                if (!c.live) continue;
+                if ((c.a == k || c.b == k) && c.op != Op::Fc) only_fc = false;
+            }
+            virt[k] = only_fc && dag.out != k;
+        }
+    }
     for (int k = 0; k < n; k++) {
-        if (!dag.nodes[k].live) continue;
+        if (!dag.nodes[k].live || virt[k]) continue;
         if (k > 0 || bf16) lay.val[k] = take(dag.numel(k));
         lay.grad[k] = take(dag.numel(k));
     }
@@ -53,7 +83,35 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         const Node& f = dag.nodes[dag.weight_node[i]];
         const Node& A = dag.nodes[f.a];
         wnumel[i] = (int64_t)f.out * (A.C / f.groups) * A.T;
-        if (bf16 && f.live) lay.wf[i] = take(wnumel[i]);
+    }
+    // which fc nodes use the MFMA kernels (32-bit buffer offsets must cover their tensors)
+    std::vector<bool> fc_mfma(n, false);
+    lay.wt.assign(dag.n_weights, -1);
+    lay.part.assign(dag.n_weights, -1);
+    std::vector<int> fc_slices(dag.n_weights, 0), fc_per_slice(dag.n_weights, 0);
+    for (int i = 0; i < dag.n_weights; i++) {
+        const int k = dag.weight_node[i];
+        const Node& f = dag.nodes[k];
+        if (!f.live) continue;
+        fc_mfma[k] = mfma;
+        if (!fc_mfma[k]) {
+            if (bf16) lay.wf[i] = take(wnumel[i]);
+            continue;
+        }
+        lay.wt[i] = (int64_t)off;
+        off += align_up((uint64_t)wnumel[i] * 2);
+        const int G = f.groups, Og = f.out / G;
+        const int64_t K = wnumel[i] / f.out;
+        const int64_t tiles = (int64_t)G * ((Og + 31) / 32) * ((K + 31) / 32);
+        const int64_t steps = (int64_t)dag.N * ((P + 31) / 32);
+        int64_t slices = std::max<int64_t>(1, std::min<int64_t>(steps, (4096 + tiles - 1) / tiles));
+        slices = std::max<int64_t>(1, std::min<int64_t>(slices, ((int64_t)256 << 20) / std::max<int64_t>(1, wnumel[i] * 4)));
+        const int64_t per = (steps + slices - 1) / slices;
+        slices = (steps + per - 1) / per;
+        fc_slices[i] = (int)slices;
+        fc_per_slice[i] = (int)per;
+        lay.part[i] = (int64_t)off;
+        off += align_up((uint64_t)slices * wnumel[i] * 4);
     }
     low->ws_bytes = off;
     const double esz = bf16 ? 2.0 : 4.0;
@@ -68,12 +126,39 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         return bf16 ? (const float*)(a.ws + lay.wf[i]) : (const float*)a.w[i];
     };
 
+    // MFMA contraction parameters of fc node k (forward orientation); src pointer filled at run time
+    auto fc_params = [&](int k) {
+        const Node& f = dag.nodes[k];
+        const bool v = virt[f.a];
+        const Node& U = dag.nodes[f.a];
+        const int srcn = v ? U.a : f.a;
+        const Node& S = dag.nodes[srcn];
+        gfc::Params Q;
+        Q.N = dag.N;
+        Q.G = f.groups;
+        Q.R = (S.C / f.groups) * S.T;
+        Q.KH = v ? U.kh : 1;
+        Q.KW = v ? U.kw : 1;
+        Q.TV = Q.KH * Q.KW;
+        Q.K = Q.R * Q.TV;
+        Q.Og = f.out / f.groups;
+        Q.H = dag.H;
+        Q.W = dag.W;
+        Q.P = P;
+        Q.chunks = (P + 127) / 128;
+        Q.magicW = gfc::magic_u32(dag.W);
+        Q.magicTV = gfc::magic_u32(Q.TV);
+        Q.magicKW = gfc::magic_u32(Q.KW);
+        return Q;
+    };
+    auto fc_src = [&](int k) { return virt[dag.nodes[k].a] ? dag.nodes[dag.nodes[k].a].a : dag.nodes[k].a; };
+
     // ---------------------------------------------------------------- forward
     if (bf16) {
         int64_t ne = dag.numel(0);
         low->fwd.push_back({"widen_x", ne * 6.0, 0, [=](const RunArgs& a) { ref::widen_bf16(a.x, valw(a, 0), ne, a.stream); }});
         for (int i = 0; i < dag.n_weights; i++) {
-            if (lay.wf[i] < 0) continue;
+            if (lay.wf[i] < 0) continue;  // MFMA fc nodes read the bf16 weights as they are
             int64_t nw = wnumel[i];
             int64_t o = lay.wf[i];
             low->fwd.push_back({"widen_w", nw * 6.0, 0, [=](const RunArgs& a) { ref::widen_bf16(a.w[i], (float*)(a.ws + o), nw, a.stream); }});
@@ -81,7 +166,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
     }
     for (int k = 1; k < n; k++) {
         const Node nd = dag.nodes[k];
-        if (!nd.live) continue;
+        if (!nd.live || virt[k]) continue;
         const Node A = dag.nodes[nd.a];
         Launch L;
         L.name = std::string("node_") + op_name(nd.op) + "_fwd";
@@ -98,6 +183,25 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         case Op::Fc: {
             int G = nd.groups, Og = nd.out / G, K = (A.C / G) * A.T;
             L.flops = 2.0 * N * P * nd.out * K;
+            if (fc_mfma[k]) {
+                gfc::Params Q = fc_params(k);
+                const int srcn = fc_src(k);
+                const bool src_x = srcn == 0;  // the caller's bf16 input is read directly
+                Q.src_f32 = src_x ? 0 : 1;
+                Q.dst_f32 = 1;
+                Q.otiles = (Q.Og + 16 * gfc::choose_mo(Q.Og) - 1) / (16 * gfc::choose_mo(Q.Og));
+                L.name = Q.TV > 1 ? "gfc_fwd_unfold" : "gfc_fwd";
+                L.bytes = (src_x ? 2.0 : 4.0) * dag.numel(srcn) + 4.0 * dag.numel(k) + 2.0 * wnumel[nd.widx];
+                const int widx = nd.widx;
+                L.run = [=](const RunArgs& a) {
+                    gfc::Params R = Q;
+                    R.src = src_x ? a.x : (const void*)val(a, srcn);
+                    R.w = (const uint16_t*)a.w[widx];
+                    R.dst = valw(a, k);
+                    gfc::forward(R, a.stream);
+                };
+                break;
+            }
             L.bytes += 4.0 * wnumel[nd.widx];
             L.run = [=](const RunArgs& a) { ref::fc_fwd(val(a, nd.a), wptr(a, nd.widx), valw(a, k), N, G, Og, K, P, a.stream); };
             break;
@@ -143,8 +247,62 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
     }
     for (int k = n - 1; k >= 1; k--) {
         const Node nd = dag.nodes[k];
-        if (!nd.live) continue;
+        if (!nd.live || virt[k]) continue;
         const Node A = dag.nodes[nd.a];
+        if (nd.op == Op::Fc && fc_mfma[k]) {
+            const int srcn = fc_src(k), widx = nd.widx;
+            const bool src_x = srcn == 0;
+            const int acc_s = written[srcn] ? 1 : 0;
+            const double flops = 2.0 * N * P * nd.out * (double)(wnumel[widx] / nd.out);
+            // weight gradient: partial sums over slices of the (image, pixel) range, then a fixed-order sum
+            gfc::Params Q = fc_params(k);
+            Q.src_f32 = src_x ? 0 : 1;
+            Q.otiles = (Q.Og + 31) / 32;
+            Q.ktiles = (Q.K + 31) / 32;
+            Q.chunks32 = (P + 31) / 32;
+            Q.magicC32 = gfc::magic_u32(Q.chunks32);
+            Q.slices = fc_slices[widx];
+            Q.per_slice = fc_per_slice[widx];
+            const int64_t poff = lay.part[widx], toff = lay.wt[widx];
+            const int64_t nw = wnumel[widx];
+            const int slices = Q.slices;
+            low->bwd.push_back({Q.TV > 1 ? "gfc_wgrad_unfold" : "gfc_wgrad", (src_x ? 2.0 : 4.0) * dag.numel(srcn) + 4.0 * dag.numel(k) + 4.0 * slices * nw, flops,
+                                [=](const RunArgs& a) {
+                                    gfc::Params R = Q;
+                                    R.src = src_x ? a.x : (const void*)val(a, srcn);
+                                    R.dy = grad(a, k);
+                                    R.partial = (float*)(a.ws + poff);
+                                    gfc::wgrad_partial(R, a.stream);
+                                }});
+            low->bwd.push_back({"gfc_wgrad_reduce", 4.0 * (slices + 1) * nw, 0, [=](const RunArgs& a) {
+                                    gfc::wgrad_reduce((const float*)(a.ws + poff), (float*)a.dw[widx], slices, nw, a.stream);
+                                }});
+            // data gradient: the same contraction on dy with transposed, tap-flipped weights; it writes the
+            // gradient of the FC's source tensor directly (the Unfold adjoint is part of it)
+            gfc::Params D = fc_params(k);
+            const int Rrows = D.R, Og = D.Og;
+            D.R = Og;
+            D.Og = Rrows;
+            D.K = Og * D.TV;
+            D.src_f32 = 1;
+            D.dst_f32 = 1;
+            D.acc = acc_s;
+            D.otiles = (D.Og + 16 * gfc::choose_mo(D.Og) - 1) / (16 * gfc::choose_mo(D.Og));
+            const int G = nd.groups, TV = D.TV;
+            low->bwd.push_back({"gfc_transpose_w", 4.0 * nw, 0, [=](const RunArgs& a) {
+                                    gfc::transpose_weights((const uint16_t*)a.w[widx], (uint16_t*)(a.ws + toff), G, Og, Rrows, TV, a.stream);
+                                }});
+            low->bwd.push_back({TV > 1 ? "gfc_dgrad_unfold" : "gfc_dgrad", 4.0 * dag.numel(k) + 4.0 * dag.numel(srcn) * (1 + acc_s) + 2.0 * nw, flops,
+                                [=](const RunArgs& a) {
+                                    gfc::Params R = D;
+                                    R.src = grad(a, k);
+                                    R.w = (const uint16_t*)(a.ws + toff);
+                                    R.dst = grad(a, srcn);
+                                    gfc::forward(R, a.stream);
+                                }});
+            written[srcn] = true;
+            continue;
+        }
         const int acc = written[nd.a] ? 1 : 0;
         Launch L;
         L.name = std::string("node_") + op_name(nd.op) + "_bwd";

@@ -31,110 +31,23 @@
 
 #include "device_util.hpp"
 #include "launch.hpp"
+#include "tile_util.hpp"
 
 namespace canvas {
 namespace sgfc {
 
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef short short4_t __attribute__((ext_vector_type(4)));
-typedef float float4_t __attribute__((ext_vector_type(4)));
-typedef float float2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
+using namespace canvas::tile;
 
 constexpr int kTilePx = 128;  // pixels per wavefront tile
 constexpr int kWaves = 4;     // wavefronts per workgroup
 constexpr int kActNone = -1;  // ACT template value: no unary node; otherwise a UnaryKind
-constexpr int kOob = -16;     // byte offset outside every buffer: loads give 0, stores are dropped
 
-// Raw buffer over `bytes` bytes at p (bytes < 2^31): accesses at offsets outside [0, bytes) are discarded by hardware.
-__device__ __forceinline__ rsrc_t make_rsrc(const void* p, int bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ u32x4 bload16(rsrc_t r, int byte_off) { return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0); }
-__device__ __forceinline__ void bstore16(rsrc_t r, int byte_off, u32x4 v) { __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, 0); }
-
-// The hardware drops a 16-byte access as a whole when any part of it is out of range.  Only a shifted
-// access at the very start or end of a tensor can be partly out of range while holding valid pixels;
-// such a register is re-read element by element (2-byte accesses are either inside or outside).
-__device__ __forceinline__ void reload_if_partial(u32x4& v, rsrc_t r, int byte_off, int bytes) {
-    const bool partial = (byte_off < 0 && byte_off > -16) || (byte_off < bytes && byte_off + 16 > bytes);
-    if (partial) {
-#pragma unroll
-        for (int k = 0; k < 4; k++) {
-            const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(r, byte_off + 4 * k, 0, 0);
-            const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(r, byte_off + 4 * k + 2, 0, 0);
-            v[k] = lo | (hi << 16);
-        }
-    }
-}
 // True (wave-uniform) when a tile's shifted accesses [first plane, last plane] x [p0+off, p0+off+136) leave the tensor.
 __device__ __forceinline__ bool tile_near_ends(int first_plane, int last_plane, int Pn, int p0, int off, int total_elems) {
     return first_plane * Pn + p0 + off < 0 || last_plane * Pn + p0 + off + kTilePx + 8 > total_elems;
 }
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-    float2_t f = {a, b};
-    bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
-    uint32_t u;
-    __builtin_memcpy(&u, &h, 4);
-    return u;
-}
-__device__ __forceinline__ float lo_f32(uint32_t d) { return __uint_as_float(d << 16); }
-__device__ __forceinline__ float hi_f32(uint32_t d) { return __uint_as_float(d & 0xffff0000u); }
-template <int Q>
-__device__ __forceinline__ float elem_f32(const u32x4& v) {
-    return (Q & 1) ? hi_f32(v[Q >> 1]) : lo_f32(v[Q >> 1]);
-}
-
-__device__ __forceinline__ short4_t as_short4(uint32_t lo, uint32_t hi) {
-    uint32_t t[2] = {lo, hi};
-    short4_t r;
-    __builtin_memcpy(&r, t, 8);
-    return r;
-}
-
-// Element Q (0..7) of each of four 16-byte registers -> one MFMA operand (4 bf16).
-template <int Q>
-__device__ __forceinline__ short4_t gather4(const u32x4& a, const u32x4& b, const u32x4& c, const u32x4& d) {
-    constexpr uint32_t sel = (Q & 1) ? 0x07060302u : 0x05040100u;
-    return as_short4(__builtin_amdgcn_perm(b[Q >> 1], a[Q >> 1], sel), __builtin_amdgcn_perm(d[Q >> 1], c[Q >> 1], sel));
-}
-__device__ __forceinline__ void gather_all(const u32x4 (&x)[4], short4_t (&out)[8]) {
-    out[0] = gather4<0>(x[0], x[1], x[2], x[3]);
-    out[1] = gather4<1>(x[0], x[1], x[2], x[3]);
-    out[2] = gather4<2>(x[0], x[1], x[2], x[3]);
-    out[3] = gather4<3>(x[0], x[1], x[2], x[3]);
-    out[4] = gather4<4>(x[0], x[1], x[2], x[3]);
-    out[5] = gather4<5>(x[0], x[1], x[2], x[3]);
-    out[6] = gather4<6>(x[0], x[1], x[2], x[3]);
-    out[7] = gather4<7>(x[0], x[1], x[2], x[3]);
-}
-
-__device__ __forceinline__ short4_t pack4(float a, float b, float c, float d) { return as_short4(pack_bf16(a, b), pack_bf16(c, d)); }
-
-__device__ __forceinline__ float4_t mfma16(short4_t a, short4_t b, float4_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
-}
-
-// kMaskLut.m[b] = the four dword masks that keep the bf16 elements whose bit is set in the 8-bit pattern b.
-struct alignas(16) MaskLut {
-    uint32_t m[256][4];
-};
-constexpr MaskLut make_mask_lut() {
-    MaskLut t{};
-    for (int b = 0; b < 256; b++)
-        for (int k = 0; k < 4; k++)
-            t.m[b][k] = (((b >> (2 * k)) & 1) ? 0x0000ffffu : 0u) | (((b >> (2 * k + 1)) & 1) ? 0xffff0000u : 0u);
-    return t;
-}
-__device__ const MaskLut kMaskLut = make_mask_lut();
-
-// Keeps a loaded value live at this point, so that the compiler issues its load before, not after, the
-// work that follows (it would otherwise sink loads into the block that first uses them).
-__device__ __forceinline__ void pin(u32x4& v) { asm volatile("" : "+v"(v)); }
 
 // Validity of the 128 pixels of a tile under a shift: bit i is 1 when tile pixel i exists (p < P) and
 // its source pixel (h+dh, w+dw) lies inside the image.  magic = ceil(2^32 / W) gives h = p / W exactly.
@@ -161,7 +74,6 @@ __device__ __forceinline__ uint32_t unit_bits(const TileMask& m, int u) {
     return (u & 8) ? b : a;
 }
 
-__device__ __forceinline__ u32x4 mask_of(uint32_t bits) { return reinterpret_cast<const u32x4*>(kMaskLut.m)[bits]; }
 
 template <int ACT>
 __device__ __forceinline__ float act_apply(const Params& P, float z) {
