@@ -22,6 +22,30 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
+# HBM bytes per launch from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then WRITE_SIZE, KiB per
+# dispatch; a plain 25 088 KiB copy reads FETCH_SIZE 12 554 -> factor 1.998, WRITE_SIZE 25 088 -> factor 1.0).
+# Valid only for the kernel sources they were taken on (hash below), otherwise `traffic` is null.
+TRAFFIC_SOURCES = ["paper_2304_07741_amd/csrc/sgfc_kernels.hip", "paper_2304_07741_amd/csrc/tile_util.hpp",
+                   "paper_2304_07741_amd/csrc/lower_sgfc.cpp"]
+TRAFFIC_SHA256 = "0dc688250342f70e0c12875c0ee507b55764e9367a0f78bd1ffabc1142bb663a"
+TRAFFIC_KIB = {("shift_residual", "sgfc_bwd"): (26388.6 * 1.998, 25907.6), ("shift_residual", "sgfc_fwd"): (14404.2 * 1.998, 25088.3)}
+
+
+def measured_traffic(workload, kernel):
+    import hashlib
+
+    h = hashlib.sha256()
+    try:
+        for f in TRAFFIC_SOURCES:
+            h.update(open(os.path.join(ROOT, f), "rb").read())
+    except OSError:
+        return None
+    if h.hexdigest() != TRAFFIC_SHA256 or (workload, kernel) not in TRAFFIC_KIB:
+        return None
+    fetch, write = TRAFFIC_KIB[(workload, kernel)]
+    return (fetch + write) * 1024.0
+
+
 def make_case(name):
     from paper_2304_07741_amd import workloads as wl
 
@@ -137,6 +161,8 @@ def main():
         ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                 "traffic": None}
+    if roof["bound"] == "hbm" and not args.no_fusion:
+        roof["traffic"] = measured_traffic(args.workload, dom["name"])
     roof["kernel"] = f"{dom['name']} ({dom['phase']})"
     roof["kernel_ms"] = dom["ms"]
     roof["algorithmic_bytes"] = dom["bytes"]

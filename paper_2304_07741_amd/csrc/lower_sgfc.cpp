@@ -80,7 +80,7 @@ std::unique_ptr<Lowering> lower_sgfc(const Dag& dag, bool bf16) {
     P.chunks = (Pn + 127) / 128;
     P.magicChunks = (uint32_t)((((uint64_t)1 << 32) + P.chunks - 1) / P.chunks);
     P.total_tiles = (long long)dag.N * G * P.chunks;
-    int tpw = 1;
+    int tpw = 2;  // two tiles per wavefront measured best at the ResNet-18 stage-1 shape
     if (const char* e = std::getenv("CANVAS_SGFC_TPW")) tpw = std::max(1, std::atoi(e));
     P.tiles_per_wave = tpw;
     const int tiles_per_group = dag.N * P.chunks;

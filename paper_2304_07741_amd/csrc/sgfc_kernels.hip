@@ -135,7 +135,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         for (int mo = 0; mo < MO; mo++)
 #pragma unroll
             for (int j = 0; j < 4; j++) {
-                xr[mo][j] = bload16(rx, live ? xo + ((mo * 16 + 4 * r + j) * P.P + p) * 2 : kOob);
+                xr[mo][j] = bload16_nt(rx, live ? xo + ((mo * 16 + 4 * r + j) * P.P + p) * 2 : kOob);
                 pin(xr[mo][j]);
             }
     }
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
             u32x4 out;
 #pragma unroll
             for (int k = 0; k < 4; k++) out[k] = pack_bf16(v[2 * k], v[2 * k + 1]);
-            bstore16(ry, live ? yo + ((mo * 16 + 4 * r + j) * P.P + p) * 2 : kOob, out);
+            bstore16_nt(ry, live ? yo + ((mo * 16 + 4 * r + j) * P.P + p) * 2 : kOob, out);
         }
 }
 
@@ -208,7 +208,7 @@ __device__ __forceinline__ void bwd_tile(const Params& P, rsrc_t rx, rsrc_t rdy,
 #pragma unroll
     for (int kc = 0; kc < KC; kc++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) xa[kc][j] = bload16(rx, liveA ? xg + ((kc * 16 + 4 * r + j) * P.P + pA) * 2 : kOob);
+        for (int j = 0; j < 4; j++) xa[kc][j] = bload16_nt(rx, liveA ? xg + ((kc * 16 + 4 * r + j) * P.P + pA) * 2 : kOob);
 #pragma unroll
     for (int mo = 0; mo < MO; mo++)
 #pragma unroll
@@ -225,7 +225,7 @@ __device__ __forceinline__ void bwd_tile(const Params& P, rsrc_t rx, rsrc_t rdy,
         for (int kc = 0; kc < KC; kc++)
 #pragma unroll
             for (int j = 0; j < 4; j++) {
-                dyu[kc][j] = bload16(rdy, liveA ? dyg + ((kc * 16 + 4 * r + j) * P.P + pA) * 2 : kOob);
+                dyu[kc][j] = bload16_nt(rdy, liveA ? dyg + ((kc * 16 + 4 * r + j) * P.P + pA) * 2 : kOob);
                 pin(dyu[kc][j]);
             }
     }
@@ -295,7 +295,7 @@ __device__ __forceinline__ void bwd_tile(const Params& P, rsrc_t rx, rsrc_t rdy,
             u32x4 out;
 #pragma unroll
             for (int k = 0; k < 4; k++) out[k] = pack_bf16(v[2 * k], v[2 * k + 1]);
-            bstore16(rdx, liveA ? xg + ((kc * 16 + 4 * r + j) * P.P + pA) * 2 : kOob, out);
+            bstore16_nt(rdx, liveA ? xg + ((kc * 16 + 4 * r + j) * P.P + pA) * 2 : kOob, out);
         }
     }
     // dW += dz x^T over the tile's pixels: lane reads channel s, unit 4m+r (8 consecutive pixels) of both tiles;

@@ -23,6 +23,9 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* p, int bytes) {
 }
 __device__ __forceinline__ u32x4 bload16(rsrc_t r, int byte_off) { return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0); }
 __device__ __forceinline__ void bstore16(rsrc_t r, int byte_off, u32x4 v) { __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, 0); }
+// Streaming variants (non-temporal hint) for data that is touched once.
+__device__ __forceinline__ u32x4 bload16_nt(rsrc_t r, int byte_off) { return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 2); }
+__device__ __forceinline__ void bstore16_nt(rsrc_t r, int byte_off, u32x4 v) { __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, 2); }
 
 // The hardware drops a 16-byte access as a whole when any part of it is out of range.  Only a shifted
 // access at the very start or end of a tensor can be partly out of range while holding valid pixels;
