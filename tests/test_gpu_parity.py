@@ -131,6 +131,32 @@ def test_fused_shift_fc_variants(harness, oracle, idx):
     r.close()
 
 
+GFC_CASES = [
+    # (body, weight shapes, input shape): the MFMA grouped-FC kernels on awkward sizes
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = fc %1 groups=1 out=40\noutput %2\n", [(1, 40, 180)], (5, 20, 7, 7)),      # 7x7 planes, odd K
+    ("%1 = unfold %0 kh=5 kw=5\n%2 = fc %1 groups=2 out=6\noutput %2\n", [(2, 3, 250)], (2, 20, 9, 5)),        # W=5, 5x5 window
+    ("%1 = unfold %0 kh=7 kw=3\n%2 = fc %1 groups=4 out=36\noutput %2\n", [(4, 9, 105)], (3, 20, 6, 13)),      # 7x3 window
+    ("%1 = unfold %0 kh=3 kw=1\n%2 = unfold %1 kh=1 kw=3\n%3 = fc %2 groups=5 out=10\noutput %3\n", [(5, 2, 36)], (2, 20, 5, 9)),  # taps on taps
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=gelu\n%3 = fc %2 groups=1 out=17\noutput %3\n", [(1, 17, 180)], (2, 20, 4, 11)),  # materialised taps
+    ("%1 = fc %0 groups=1 out=130\n%2 = fc %1 groups=13 out=26\n%3 = fc %2 groups=2 out=20\noutput %3\n",
+     [(1, 130, 20), (13, 2, 10), (2, 10, 13)], (3, 20, 3, 4)),                                                      # chained, tiny planes (W=4)
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = fc %1 groups=1 out=10\n%3 = fc %1 groups=20 out=20\n%4 = binary %2 %3 op=add\noutput %4\n",
+     [(1, 10, 180), (20, 1, 9)], (2, 20, 6, 6)),                                                                     # one unfold, two FCs
+    ("%1 = fc %0 groups=1 out=70\noutput %1\n", [(1, 70, 20)], (1, 20, 1, 130)),                                  # single row image
+]
+
+
+@pytest.mark.parametrize("idx", range(len(GFC_CASES)))
+def test_mfma_grouped_fc_shapes(harness, oracle, idx):
+    body, wshapes, shape = GFC_CASES[idx]
+    case = _mk(body, shape, "bf16", 90 + idx, wshapes, f"gfc{idx}")
+    res, r, dy = harness.run_case(case)
+    names = [d["name"] for d in r.launches(0)] + [d["name"] for d in r.launches(1)]
+    assert any(n.startswith("gfc_") for n in names), names
+    check_against_oracle(oracle, case, res, dy)
+    r.close()
+
+
 @pytest.mark.parametrize("flags", [0, B.CANVAS_OPT_NO_FUSION])
 @pytest.mark.parametrize("N,H", [(2, 28), (3, 9), (32, 28)])
 def test_config3_involution(harness, oracle, N, H, flags):
