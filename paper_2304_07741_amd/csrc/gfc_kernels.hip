@@ -121,31 +121,43 @@ __device__ __forceinline__ Pair8 load8_slow(rsrc_t r, int e, bool ok) {
 }
 
 // ------------------------------------------------------------------------------------------- forward
-// One wavefront: 16*MO output channels x 128 pixels of one image and group; K in steps of 16.
-// Lane (r = lane/16, s = lane%16): B operand rows k = 16*kc + 4r + j at pixels p0+8s..+7; A operand
-// w[o = 16*mo + s][k = 16*kc + 4r ..+3]; accumulator acc[mo][q][j] = y[o = 16*mo + 4r + j][p0 + 8s + q].
+// One wavefront: 16*MO output channels of one group x 16 units of 8 pixels; K in steps of 16.  Units are
+// numbered across the whole batch (unit U -> image U / units_per_image), so small images (7x7, 14x14)
+// still fill the tile.  Lane (r = lane/16, s = lane%16): B operand rows k = k0 + 4r + j of unit s; A
+// operand w[o = 16*mo + s][k = k0 + 4r ..+3]; accumulator acc[mo][q][j] = y[o = 16*mo + 4r + j][pixel q of unit s].
+template <bool F32>
+struct RawChunk {
+    u32x4 a[4], b[F32 ? 4 : 1];  // rows j = 0..3: 8 elements each (fp32: a = first four, b = last four)
+};
+
 template <int MO, bool SRC_F32, bool DST_F32, bool TAPS>
 __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int chunk = blockIdx.x * kWaves + wave;
-    if (chunk >= P.chunks) return;
-    const int g = blockIdx.y / P.otiles, ot = blockIdx.y - g * P.otiles, n = blockIdx.z;
+    const int tile = blockIdx.x * kWaves + wave;
+    const int total_units = P.N * P.upi;
+    if (tile * 16 >= total_units) return;
+    const int g = blockIdx.y / P.otiles, ot = blockIdx.y - g * P.otiles;
     const int r = lane >> 4, s = lane & 15;
-    const int p0 = chunk * 128, p = p0 + 8 * s;
-    const bool live = p < P.P;
+    const int U = tile * 16 + s;
+    const bool live = U < total_units;
+    const int n = live ? (int)div_magic((uint32_t)U, P.magicUpi) : 0;
+    const int p = live ? (U - n * P.upi) * 8 : 0;
     const int esz = SRC_F32 ? 4 : 2;
     const int src_elems = P.N * P.G * P.R * P.P;
     const rsrc_t rs = make_rsrc(P.src, src_elems * esz);
     const rsrc_t rw = make_rsrc(P.w, P.G * P.Og * P.K * 2);
-    const int row0 = (n * P.G + g) * P.R;  // first source row of this image and group
+    const int row0 = (n * P.G + g) * P.R;  // first source row of this lane's image and group
     const int obase = ot * 16 * MO;
 
     PixGeom gm = {0, 0};
-    if (TAPS) gm = pix_geom(P, live ? p : 0);
+    if (TAPS) gm = pix_geom(P, p);
     const int maxoff = (P.KH / 2) * P.W + P.KW / 2;
     // wave-uniform: could a 16/32-byte access of this tile straddle an end of the source tensor?
-    const bool near_ends = row0 * P.P + p0 - maxoff < 0 || (row0 + P.R - 1) * P.P + p0 + 128 + 8 + maxoff > src_elems;
+    const int n_first = (int)div_magic((uint32_t)(tile * 16), P.magicUpi);
+    const int n_last = (int)div_magic((uint32_t)min(tile * 16 + 15, total_units - 1), P.magicUpi);
+    const bool near_ends = (n_first * P.G + g) * P.R * P.P - maxoff < 0 ||
+                           ((n_last * P.G + g) * P.R + P.R) * P.P + 8 + maxoff > src_elems;
 
     float4_t acc[MO][8];
 #pragma unroll
@@ -153,8 +165,20 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
 #pragma unroll
         for (int q = 0; q < 8; q++) acc[mo][q] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    for (int k0 = 0; k0 < P.K; k0 += 16) {
-        short4_t wa[MO];
+    // element offset and validity bits of row k = k0 + 4r + j for this lane's unit
+    auto row_elem = [&](int k, uint32_t& bits) {
+        int row = k, off = 0;
+        bits = 0xffu;
+        if (TAPS) {
+            row = (int)div_magic((uint32_t)k, P.magicTV);
+            const int tv = k - row * P.TV;
+            const int khi = (int)div_magic((uint32_t)tv, P.magicKW), kwi = tv - khi * P.KW;
+            off = (khi - P.KH / 2) * P.W + (kwi - P.KW / 2);
+            bits = tap_bits(gm, khi, kwi);
+        }
+        return (row0 + row) * P.P + p + off;
+    };
+    auto load_raw = [&](int k0, RawChunk<SRC_F32>& c, short4_t (&wa)[MO]) {
 #pragma unroll
         for (int mo = 0; mo < MO; mo++) {
             const int o = obase + mo * 16 + s;
@@ -175,28 +199,62 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
             }
             wa[mo] = as_short4(w2[0], w2[1]);
         }
-        u32x4 xs[4], xl[4];
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             const int k = k0 + 4 * r + j;
-            int row = k, off = 0;
-            uint32_t bits = 0xffu;
-            if (TAPS) {
-                row = (int)div_magic((uint32_t)k, P.magicTV);
-                const int tv = k - row * P.TV;
-                const int khi = (int)div_magic((uint32_t)tv, P.magicKW), kwi = tv - khi * P.KW;
-                off = (khi - P.KH / 2) * P.W + (kwi - P.KW / 2);
-                bits = tap_bits(gm, khi, kwi);
-            }
+            uint32_t bits;
+            const int e = row_elem(k, bits);
             const bool ok = live && k < P.K;
-            const int e = (row0 + row) * P.P + p + off;
-            const Pair8 v = near_ends ? load8_slow<SRC_F32>(rs, e, ok) : load8<SRC_F32>(rs, e, ok);
-            xs[j] = v.hi;
-            xl[j] = v.lo;
-            if (TAPS) {
+            if (SRC_F32) {
+                c.a[j] = bload16(rs, ok ? e * 4 : kOob);
+                c.b[j & (SRC_F32 ? 3 : 0)] = bload16(rs, ok ? e * 4 + 16 : kOob);
+            } else {
+                c.a[j] = bload16(rs, ok ? e * 2 : kOob);
+            }
+        }
+    };
+
+    for (int k0 = 0; k0 < P.K; k0 += 16) {
+        RawChunk<SRC_F32> cur;
+        short4_t wa[MO];
+        load_raw(k0, cur, wa);
+        u32x4 xs[4], xl[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            if (SRC_F32) {
+                Pair8 v;
+                const u32x4 a = cur.a[j], b = cur.b[j & (SRC_F32 ? 3 : 0)];
+                split2(__uint_as_float(a[0]), __uint_as_float(a[1]), v, 0);
+                split2(__uint_as_float(a[2]), __uint_as_float(a[3]), v, 1);
+                split2(__uint_as_float(b[0]), __uint_as_float(b[1]), v, 2);
+                split2(__uint_as_float(b[2]), __uint_as_float(b[3]), v, 3);
+                xs[j] = v.hi;
+                xl[j] = v.lo;
+            } else {
+                xs[j] = cur.a[j];
+            }
+        }
+        if (near_ends) {
+            // tiles at the two ends of the tensor: a 16-byte access that is partly outside was dropped
+            // as a whole by the hardware, so re-read element by element
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int k = k0 + 4 * r + j;
+                uint32_t bits;
+                const int e = row_elem(k, bits);
+                const Pair8 v = load8_slow<SRC_F32>(rs, e, live && k < P.K);
+                xs[j] = v.hi;
+                xl[j] = v.lo;
+            }
+        }
+        if (TAPS) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                uint32_t bits;
+                (void)row_elem(k0 + 4 * r + j, bits);
                 const u32x4 m = mask_of(bits);
                 xs[j] = xs[j] & m;
-                xl[j] = xl[j] & m;
+                if (SRC_F32) xl[j] = xl[j] & m;
             }
         }
         short4_t b[8];
@@ -374,12 +432,33 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
             }
 }
 
-__global__ void k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ dw, int slices, long long elems) {
-    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (e >= elems) return;
+// dw[e] = sum over slices, in a fixed order: 8 segments of slices per element, combined through LDS.
+__global__ __launch_bounds__(256) void k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ dw, int slices, long long elems) {
+    __shared__ float red[8][32];
+    const int el = threadIdx.x & 31, seg = threadIdx.x >> 5;
+    const long long e = (long long)blockIdx.x * 32 + el;
+    const int per = (slices + 7) / 8;
     float s = 0.f;
-    for (int k = 0; k < slices; k++) s += partial[(long long)k * elems + e];
-    dw[e] = s;
+    if (e < elems) {
+        const int end = min(slices, (seg + 1) * per);
+        int k = seg * per;
+        for (; k + 4 <= end; k += 4) {  // four independent loads in flight, summed in slice order
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) v[i] = partial[(long long)(k + i) * elems + e];
+#pragma unroll
+            for (int i = 0; i < 4; i++) s += v[i];
+        }
+        for (; k < end; k++) s += partial[(long long)k * elems + e];
+    }
+    red[seg][el] = s;
+    __syncthreads();
+    if (seg == 0 && e < elems) {
+        float t = red[0][el];
+#pragma unroll
+        for (int i = 1; i < 8; i++) t += red[i][el];
+        dw[e] = t;
+    }
 }
 
 __global__ void k_transpose_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt, int G, int Og, int R, int TV) {
@@ -396,7 +475,8 @@ __global__ void k_transpose_weights(const uint16_t* __restrict__ w, uint16_t* __
 
 template <int MO>
 void launch_fwd(const Params& P, hipStream_t s) {
-    const dim3 grid((unsigned)((P.chunks + kWaves - 1) / kWaves), (unsigned)(P.G * P.otiles), (unsigned)P.N);
+    const int tiles = (P.N * P.upi + 15) / 16;
+    const dim3 grid((unsigned)((tiles + kWaves - 1) / kWaves), (unsigned)(P.G * P.otiles));
     const dim3 block(64 * kWaves);
     const bool taps = P.TV > 1;
 #define GFC_FWD(SF, DF, TP) CANVAS_LAUNCH((k_fwd<MO, SF, DF, TP>), grid, block, 0, s, P)
@@ -438,7 +518,7 @@ void wgrad_partial(const Params& P, hipStream_t s) {
 }
 
 void wgrad_reduce(const float* partial, float* dw, int slices, int64_t elems, hipStream_t s) {
-    if (elems > 0) CANVAS_LAUNCH(k_wgrad_reduce, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, s, partial, dw, slices, (long long)elems);
+    if (elems > 0) CANVAS_LAUNCH(k_wgrad_reduce, dim3((unsigned)((elems + 31) / 32)), dim3(256), 0, s, partial, dw, slices, (long long)elems);
 }
 
 void transpose_weights(const uint16_t* w, uint16_t* wt, int G, int Og, int R, int TV, hipStream_t s) {

@@ -20,10 +20,10 @@ struct Params {
     float* partial = nullptr;     // weight gradient: [slices, G*Og*K] fp32
     int N = 0, G = 0, R = 0, KH = 1, KW = 1, TV = 1, K = 0, Og = 0, H = 0, W = 0, P = 0;
     int src_f32 = 0, dst_f32 = 1, acc = 0;  // acc: dst += result
-    int chunks = 0;               // forward: ceil(P / 128)
+    int upi = 0;                  // forward: 8-pixel units per image, ceil(P / 8)
     int otiles = 0, ktiles = 0;   // tiles of 16*MO output channels / 16*NK contraction rows
     int slices = 0, chunks32 = 0, per_slice = 0;  // weight gradient: pixel chunks of 32 split over slices
-    uint32_t magicW = 0, magicTV = 0, magicKW = 0, magicC32 = 0;
+    uint32_t magicW = 0, magicTV = 0, magicKW = 0, magicC32 = 0, magicUpi = 0;
 };
 
 inline uint32_t magic_u32(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }

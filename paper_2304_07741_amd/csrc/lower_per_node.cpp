@@ -104,8 +104,8 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         const int64_t K = wnumel[i] / f.out;
         const int64_t tiles = (int64_t)G * ((Og + 31) / 32) * ((K + 31) / 32);
         const int64_t steps = (int64_t)dag.N * ((P + 31) / 32);
-        int64_t slices = std::max<int64_t>(1, std::min<int64_t>(steps, (4096 + tiles - 1) / tiles));
-        slices = std::max<int64_t>(1, std::min<int64_t>(slices, ((int64_t)256 << 20) / std::max<int64_t>(1, wnumel[i] * 4)));
+        int64_t slices = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(steps, 1024), (4096 + tiles - 1) / tiles));
+        slices = std::max<int64_t>(1, std::min<int64_t>(slices, ((int64_t)32 << 20) / std::max<int64_t>(1, wnumel[i] * 4)));
         const int64_t per = (steps + slices - 1) / slices;
         slices = (steps + per - 1) / per;
         fc_slices[i] = (int)slices;
@@ -145,7 +145,8 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         Q.H = dag.H;
         Q.W = dag.W;
         Q.P = P;
-        Q.chunks = (P + 127) / 128;
+        Q.upi = (P + 7) / 8;
+        Q.magicUpi = gfc::magic_u32(Q.upi);
         Q.magicW = gfc::magic_u32(dag.W);
         Q.magicTV = gfc::magic_u32(Q.TV);
         Q.magicKW = gfc::magic_u32(Q.KW);
