@@ -16,6 +16,8 @@
 // memory order of both operands: 16-byte loads are MFMA operands as they are.
 #include "gfc_kernels.hpp"
 
+#include <algorithm>
+
 #include <hip/hip_runtime.h>
 
 #include "launch.hpp"
@@ -306,6 +308,14 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                     bstore16(rd, e * 4, lo);
                     bstore16(rd, e * 4 + 16, hi);
                 } else {
+                    if (P.addend) {  // bf16 tensor of the output's shape added before rounding
+                        const u32x4 ad = bload16(make_rsrc(P.addend, P.N * P.G * P.Og * P.P * 2), e * 2);
+#pragma unroll
+                        for (int k = 0; k < 4; k++) {
+                            v[2 * k] += lo_f32(ad[k]);
+                            v[2 * k + 1] += hi_f32(ad[k]);
+                        }
+                    }
                     u32x4 out;
 #pragma unroll
                     for (int k = 0; k < 4; k++) out[k] = pack_bf16(v[2 * k], v[2 * k + 1]);
@@ -319,7 +329,9 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                         float* d = reinterpret_cast<float*>(P.dst) + e + q;
                         *d = P.acc ? *d + v[q] : v[q];
                     } else {
-                        reinterpret_cast<uint16_t*>(P.dst)[e + q] = (uint16_t)(pack_bf16(v[q], 0.f) & 0xffffu);
+                        float t = v[q];
+                        if (P.addend) t += __uint_as_float((uint32_t)P.addend[e + q] << 16);
+                        reinterpret_cast<uint16_t*>(P.dst)[e + q] = (uint16_t)(pack_bf16(t, 0.f) & 0xffffu);
                     }
                 }
             }
@@ -331,7 +343,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
 // step.  Lane (r, s) loads pixels 8r..8r+7 of the step from dy row o = 16*mo + s and from operand row
 // k = 16*nk + s: the two halves of each 16-byte load are the A / B operands of two MFMAs whose
 // contraction slot 4r+jj is pixel 8r + 4*half + jj.  Result: lane holds dw[o = 16*mo + 4r + jj][k = 16*nk + s].
-template <int MO, int NK, bool SRC_F32, bool TAPS>
+template <int MO, int NK, bool SRC_F32, bool DY_F32, bool TAPS>
 __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -343,7 +355,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
     const int esz = SRC_F32 ? 4 : 2;
     const int src_elems = P.N * P.G * P.R * P.P;
     const rsrc_t rs = make_rsrc(P.src, src_elems * esz);
-    const rsrc_t rdy = make_rsrc(P.dy, P.N * P.G * P.Og * P.P * 4);
+    const rsrc_t rdy = make_rsrc(P.dy, P.N * P.G * P.Og * P.P * (DY_F32 ? 4 : 2));
     const int obase = ot * 16 * MO, kbase = kt * 16 * NK;
 
     // this lane's operand rows: fixed source row, tap offset and window position per nk
@@ -388,7 +400,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
             const int o = obase + mo * 16 + s;
             const bool ok = live && o < P.Og;
             const int e = ((n * P.G + g) * P.Og + o) * P.P + p;
-            a[mo] = near_ends ? load8_slow<true>(rdy, e, ok) : load8<true>(rdy, e, ok);
+            a[mo] = near_ends ? load8_slow<DY_F32>(rdy, e, ok) : load8<DY_F32>(rdy, e, ok);
             a[mo].hi = a[mo].hi & mvalid;
             a[mo].lo = a[mo].lo & mvalid;
         }
@@ -410,8 +422,10 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
                 float4_t c = acc[mo][nk];
                 c = mfma16(as_short4(a[mo].hi[0], a[mo].hi[1]), as_short4(b[nk].hi[0], b[nk].hi[1]), c);
                 c = mfma16(as_short4(a[mo].hi[2], a[mo].hi[3]), as_short4(b[nk].hi[2], b[nk].hi[3]), c);
-                c = mfma16(as_short4(a[mo].lo[0], a[mo].lo[1]), as_short4(b[nk].hi[0], b[nk].hi[1]), c);
-                c = mfma16(as_short4(a[mo].lo[2], a[mo].lo[3]), as_short4(b[nk].hi[2], b[nk].hi[3]), c);
+                if (DY_F32) {
+                    c = mfma16(as_short4(a[mo].lo[0], a[mo].lo[1]), as_short4(b[nk].hi[0], b[nk].hi[1]), c);
+                    c = mfma16(as_short4(a[mo].lo[2], a[mo].lo[3]), as_short4(b[nk].hi[2], b[nk].hi[3]), c);
+                }
                 if (SRC_F32) {
                     c = mfma16(as_short4(a[mo].hi[0], a[mo].hi[1]), as_short4(b[nk].lo[0], b[nk].lo[1]), c);
                     c = mfma16(as_short4(a[mo].hi[2], a[mo].hi[3]), as_short4(b[nk].lo[2], b[nk].lo[3]), c);
@@ -494,6 +508,56 @@ void launch_fwd(const Params& P, hipStream_t s) {
 
 int choose_mo(int Og) { return Og <= 16 ? 1 : (Og <= 32 ? 2 : 4); }
 
+Params shape(int N, int G, int rows, int KH, int KW, int Og, int H, int W) {
+    Params Q;
+    Q.N = N;
+    Q.G = G;
+    Q.R = rows;
+    Q.KH = KH;
+    Q.KW = KW;
+    Q.TV = KH * KW;
+    Q.K = rows * Q.TV;
+    Q.Og = Og;
+    Q.H = H;
+    Q.W = W;
+    Q.P = H * W;
+    Q.upi = (Q.P + 7) / 8;
+    Q.magicUpi = magic_u32(Q.upi);
+    Q.magicW = magic_u32(W);
+    Q.magicTV = magic_u32(Q.TV);
+    Q.magicKW = magic_u32(Q.KW);
+    return Q;
+}
+
+void prepare_forward(Params& P) {
+    const int mo = 16 * choose_mo(P.Og);
+    P.otiles = (P.Og + mo - 1) / mo;
+}
+
+void prepare_wgrad(Params& P) {
+    P.otiles = (P.Og + 31) / 32;
+    P.ktiles = (P.K + 31) / 32;
+    P.chunks32 = (P.P + 31) / 32;
+    P.magicC32 = magic_u32(P.chunks32);
+    const int64_t wnumel = (int64_t)P.G * P.Og * P.K;
+    const int64_t tiles = (int64_t)P.G * P.otiles * P.ktiles;
+    const int64_t steps = (int64_t)P.N * P.chunks32;
+    int64_t slices = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(steps, 1024), (4096 + tiles - 1) / std::max<int64_t>(1, tiles)));
+    slices = std::max<int64_t>(1, std::min<int64_t>(slices, ((int64_t)32 << 20) / std::max<int64_t>(1, wnumel * 4)));
+    const int64_t per = std::max<int64_t>(1, (steps + slices - 1) / slices);
+    P.per_slice = (int)per;
+    P.slices = (int)((steps + per - 1) / per);
+}
+
+Params data_gradient_of(const Params& fwd) {
+    Params D = fwd;
+    D.R = fwd.Og;
+    D.Og = fwd.R;
+    D.K = fwd.Og * fwd.TV;
+    prepare_forward(D);
+    return D;
+}
+
 void forward(const Params& P, hipStream_t s) {
     if (P.N * P.G * P.Og * P.P == 0 || P.K == 0) return;
     switch (choose_mo(P.Og)) {
@@ -508,13 +572,11 @@ void wgrad_partial(const Params& P, hipStream_t s) {
     const dim3 grid((unsigned)((P.slices + kWaves - 1) / kWaves), (unsigned)(P.otiles * P.ktiles), (unsigned)P.G);
     const dim3 block(64 * kWaves);
     const bool taps = P.TV > 1;
-    if (P.src_f32) {
-        if (taps) CANVAS_LAUNCH((k_wgrad<2, 2, true, true>), grid, block, 0, s, P);
-        else CANVAS_LAUNCH((k_wgrad<2, 2, true, false>), grid, block, 0, s, P);
-    } else {
-        if (taps) CANVAS_LAUNCH((k_wgrad<2, 2, false, true>), grid, block, 0, s, P);
-        else CANVAS_LAUNCH((k_wgrad<2, 2, false, false>), grid, block, 0, s, P);
-    }
+#define GFC_WG(SF, DF) \
+    do { if (taps) CANVAS_LAUNCH((k_wgrad<2, 2, SF, DF, true>), grid, block, 0, s, P); else CANVAS_LAUNCH((k_wgrad<2, 2, SF, DF, false>), grid, block, 0, s, P); } while (0)
+    if (P.src_f32) { if (P.dy_f32) GFC_WG(true, true); else GFC_WG(true, false); }
+    else { if (P.dy_f32) GFC_WG(false, true); else GFC_WG(false, false); }
+#undef GFC_WG
 }
 
 void wgrad_reduce(const float* partial, float* dw, int slices, int64_t elems, hipStream_t s) {

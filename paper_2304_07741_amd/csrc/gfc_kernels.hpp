@@ -16,10 +16,11 @@ struct Params {
     const void* src = nullptr;    // row tensor, fp32 or bf16
     const uint16_t* w = nullptr;  // [G, Og, K] bf16
     void* dst = nullptr;          // forward: [N, G*Og, P] fp32 or bf16
-    const float* dy = nullptr;    // weight gradient: [N, G*Og, P] fp32
+    const void* dy = nullptr;     // weight gradient: [N, G*Og, P] fp32 or bf16 (dy_f32)
+    const uint16_t* addend = nullptr;  // forward with bf16 dst: optional bf16 tensor added to the result
     float* partial = nullptr;     // weight gradient: [slices, G*Og*K] fp32
     int N = 0, G = 0, R = 0, KH = 1, KW = 1, TV = 1, K = 0, Og = 0, H = 0, W = 0, P = 0;
-    int src_f32 = 0, dst_f32 = 1, acc = 0;  // acc: dst += result
+    int src_f32 = 0, dst_f32 = 1, dy_f32 = 1, acc = 0;  // acc: dst += result (fp32 dst only)
     int upi = 0;                  // forward: 8-pixel units per image, ceil(P / 8)
     int otiles = 0, ktiles = 0;   // tiles of 16*MO output channels / 16*NK contraction rows
     int slices = 0, chunks32 = 0, per_slice = 0;  // weight gradient: pixel chunks of 32 split over slices
@@ -37,6 +38,15 @@ void wgrad_reduce(const float* partial, float* dw, int slices, int64_t elems, hi
 // wt[g][row][o*TV + tv] = w[g][o][row*TV + (TV-1-tv)]: the weights of the data-gradient contraction
 void transpose_weights(const uint16_t* w, uint16_t* wt, int G, int Og, int R, int TV, hipStream_t s);
 int choose_mo(int Og);
+
+// Host-side set-up shared by the lowerings.  `shape` fills the geometry of a contraction whose operand has
+// `rows` rows per group seen through a KH x KW window; the three `prepare_*` calls complete it for one launch kind.
+Params shape(int N, int G, int rows, int KH, int KW, int Og, int H, int W);
+void prepare_forward(Params& P);
+// Splits the N * ceil(P/32) pixel chunks over at most 1024 slices (partials of at most 32 MB).
+void prepare_wgrad(Params& P);
+// Forward geometry -> geometry of the data gradient (rows and outputs swapped); use with transposed weights.
+Params data_gradient_of(const Params& fwd);
 
 }  // namespace gfc
 }  // namespace canvas

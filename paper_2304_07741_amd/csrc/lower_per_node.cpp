@@ -84,11 +84,22 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         const Node& A = dag.nodes[f.a];
         wnumel[i] = (int64_t)f.out * (A.C / f.groups) * A.T;
     }
+    // MFMA contraction parameters of fc node k (forward orientation); src pointer filled at run time
+    auto fc_params = [&](int k) {
+        const Node& f = dag.nodes[k];
+        const bool v = virt[f.a];
+        const Node& U = dag.nodes[f.a];
+        const int srcn = v ? U.a : f.a;
+        const Node& S = dag.nodes[srcn];
+        gfc::Params Q = gfc::shape(dag.N, f.groups, (S.C / f.groups) * S.T, v ? U.kh : 1, v ? U.kw : 1, f.out / f.groups, dag.H, dag.W);
+        return Q;
+    };
+    auto fc_src = [&](int k) { return virt[dag.nodes[k].a] ? dag.nodes[dag.nodes[k].a].a : dag.nodes[k].a; };
+
     // which fc nodes use the MFMA kernels (32-bit buffer offsets must cover their tensors)
     std::vector<bool> fc_mfma(n, false);
     lay.wt.assign(dag.n_weights, -1);
     lay.part.assign(dag.n_weights, -1);
-    std::vector<int> fc_slices(dag.n_weights, 0), fc_per_slice(dag.n_weights, 0);
     for (int i = 0; i < dag.n_weights; i++) {
         const int k = dag.weight_node[i];
         const Node& f = dag.nodes[k];
@@ -100,16 +111,9 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         }
         lay.wt[i] = (int64_t)off;
         off += align_up((uint64_t)wnumel[i] * 2);
-        const int G = f.groups, Og = f.out / G;
-        const int64_t K = wnumel[i] / f.out;
-        const int64_t tiles = (int64_t)G * ((Og + 31) / 32) * ((K + 31) / 32);
-        const int64_t steps = (int64_t)dag.N * ((P + 31) / 32);
-        int64_t slices = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(steps, 1024), (4096 + tiles - 1) / tiles));
-        slices = std::max<int64_t>(1, std::min<int64_t>(slices, ((int64_t)32 << 20) / std::max<int64_t>(1, wnumel[i] * 4)));
-        const int64_t per = (steps + slices - 1) / slices;
-        slices = (steps + per - 1) / per;
-        fc_slices[i] = (int)slices;
-        fc_per_slice[i] = (int)per;
+        gfc::Params Q = fc_params(k);
+        gfc::prepare_wgrad(Q);
+        const int64_t slices = Q.slices;
         lay.part[i] = (int64_t)off;
         off += align_up((uint64_t)slices * wnumel[i] * 4);
     }
@@ -125,34 +129,6 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
     auto wptr = [lay, bf16](const RunArgs& a, int i) -> const float* {
         return bf16 ? (const float*)(a.ws + lay.wf[i]) : (const float*)a.w[i];
     };
-
-    // MFMA contraction parameters of fc node k (forward orientation); src pointer filled at run time
-    auto fc_params = [&](int k) {
-        const Node& f = dag.nodes[k];
-        const bool v = virt[f.a];
-        const Node& U = dag.nodes[f.a];
-        const int srcn = v ? U.a : f.a;
-        const Node& S = dag.nodes[srcn];
-        gfc::Params Q;
-        Q.N = dag.N;
-        Q.G = f.groups;
-        Q.R = (S.C / f.groups) * S.T;
-        Q.KH = v ? U.kh : 1;
-        Q.KW = v ? U.kw : 1;
-        Q.TV = Q.KH * Q.KW;
-        Q.K = Q.R * Q.TV;
-        Q.Og = f.out / f.groups;
-        Q.H = dag.H;
-        Q.W = dag.W;
-        Q.P = P;
-        Q.upi = (P + 7) / 8;
-        Q.magicUpi = gfc::magic_u32(Q.upi);
-        Q.magicW = gfc::magic_u32(dag.W);
-        Q.magicTV = gfc::magic_u32(Q.TV);
-        Q.magicKW = gfc::magic_u32(Q.KW);
-        return Q;
-    };
-    auto fc_src = [&](int k) { return virt[dag.nodes[k].a] ? dag.nodes[dag.nodes[k].a].a : dag.nodes[k].a; };
 
     // ---------------------------------------------------------------- forward
     if (bf16) {
@@ -190,7 +166,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
                 const bool src_x = srcn == 0;  // the caller's bf16 input is read directly
                 Q.src_f32 = src_x ? 0 : 1;
                 Q.dst_f32 = 1;
-                Q.otiles = (Q.Og + 16 * gfc::choose_mo(Q.Og) - 1) / (16 * gfc::choose_mo(Q.Og));
+                gfc::prepare_forward(Q);
                 L.name = Q.TV > 1 ? "gfc_fwd_unfold" : "gfc_fwd";
                 L.bytes = (src_x ? 2.0 : 4.0) * dag.numel(srcn) + 4.0 * dag.numel(k) + 2.0 * wnumel[nd.widx];
                 const int widx = nd.widx;
@@ -258,12 +234,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             // weight gradient: partial sums over slices of the (image, pixel) range, then a fixed-order sum
             gfc::Params Q = fc_params(k);
             Q.src_f32 = src_x ? 0 : 1;
-            Q.otiles = (Q.Og + 31) / 32;
-            Q.ktiles = (Q.K + 31) / 32;
-            Q.chunks32 = (P + 31) / 32;
-            Q.magicC32 = gfc::magic_u32(Q.chunks32);
-            Q.slices = fc_slices[widx];
-            Q.per_slice = fc_per_slice[widx];
+            gfc::prepare_wgrad(Q);
             const int64_t poff = lay.part[widx], toff = lay.wt[widx];
             const int64_t nw = wnumel[widx];
             const int slices = Q.slices;
@@ -280,15 +251,11 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
                                 }});
             // data gradient: the same contraction on dy with transposed, tap-flipped weights; it writes the
             // gradient of the FC's source tensor directly (the Unfold adjoint is part of it)
-            gfc::Params D = fc_params(k);
-            const int Rrows = D.R, Og = D.Og;
-            D.R = Og;
-            D.Og = Rrows;
-            D.K = Og * D.TV;
+            gfc::Params D = gfc::data_gradient_of(Q);
+            const int Rrows = Q.R, Og = Q.Og;
             D.src_f32 = 1;
             D.dst_f32 = 1;
             D.acc = acc_s;
-            D.otiles = (D.Og + 16 * gfc::choose_mo(D.Og) - 1) / (16 * gfc::choose_mo(D.Og));
             const int G = nd.groups, TV = D.TV;
             low->bwd.push_back({"gfc_transpose_w", 4.0 * nw, 0, [=](const RunArgs& a) {
                                     gfc::transpose_weights((const uint16_t*)a.w[widx], (uint16_t*)(a.ws + toff), G, Og, Rrows, TV, a.stream);

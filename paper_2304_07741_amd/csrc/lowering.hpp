@@ -44,6 +44,10 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16);
 // Fused shift -> grouped FC -> unary chain -> (+ input); nullptr when the DAG is not of that form.
 std::unique_ptr<Lowering> lower_sgfc(const Dag& dag, bool bf16);
 
+// [Unfold] -> grouped FC -> [unary] -> Shift* -> add|mul with the input -> grouped FC, bf16 intermediates;
+// nullptr when the DAG is not of that form.
+std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16);
+
 // Picks the lowering: fused kernel families where a pattern applies, else per node.
 std::unique_ptr<Lowering> lower(const Dag& dag, bool bf16, bool no_fusion);
 

@@ -171,6 +171,7 @@ def test_config3_involution(harness, oracle, N, H, flags):
 def test_config4_sampled_small_batch(harness, oracle, C, H, N, flags):
     case = wl.config4(C, H, N=N)
     res, r, dy = harness.run_case(case, flags)
+    assert r.info.fused == (1 if flags == 0 else 0)
     check_against_oracle(oracle, case, res, dy)
     r.close()
 
@@ -179,6 +180,52 @@ def test_config4_sampled_small_batch(harness, oracle, C, H, N, flags):
 def test_config4_sampled_full_batch(harness, oracle, C, H):
     case = wl.config4(C, H, N=128)
     res, r, dy = harness.run_case(case)
+    assert r.info.fused == 1
+    check_against_oracle(oracle, case, res, dy)
+    r.close()
+
+
+UFC_VARIANTS = [
+    # (window, groups of FC1, unary, shifts [(dh, dw, c0, c1)], binary, identity fold, groups of FC2, out of FC2, N, C, H, W)
+    (3, 8, "gelu", [(0, 1, 24, 48)], "mul", True, 1, 48, 2, 48, 9, 11),          # ragged 8-pixel tail, odd width
+    (3, 4, "relu", [(1, 0, 0, 16), (-1, 0, 16, 32)], "add", False, 2, 64, 3, 32, 8, 8),
+    (5, 2, None, [], "mul", False, 1, 16, 2, 16, 7, 7),                            # no unary, no shift, 5x5 window
+    (1, 1, "abs", [(0, -1, 0, 8), (2, 0, 8, 12), (0, 3, 20, 24)], "mul", True, 4, 24, 1, 24, 6, 10),  # no unfold
+    (3, 8, "gelu", [(5, 0, 0, 32)], "add", False, 1, 96, 2, 64, 4, 12),           # shift beyond the image
+    (3, 1, "gelu", [(0, 1, 4, 8)], "mul", False, 1, 8, 5, 8, 5, 4),                # tiny channel counts
+    (3, 8, "expclip lo=-1 hi=1", [(0, 1, 0, 32)], "add", False, 1, 96, 2, 64, 4, 12),  # clip bounds: not fused
+]
+
+
+@pytest.mark.parametrize("idx", range(len(UFC_VARIANTS)))
+def test_fused_unfold_fc_gate_fc_variants(harness, oracle, idx):
+    """The lowering of [Unfold] -> FC -> [unary] -> Shift* -> add|mul with x -> FC over its parameter space."""
+    k, g1, act, shifts, bop, fold, g2, o2, N, C, H, W = UFC_VARIANTS[idx]
+    lines, cur = [], 0
+
+    def emit(text):
+        nonlocal cur
+        cur += 1
+        lines.append(f"%{cur} = {text}")
+        return cur
+
+    if k > 1:
+        emit(f"unfold %0 kh={k} kw={k}")
+    emit(f"fc %{cur} groups={g1} out={C}")
+    if act:
+        emit(f"unary %{cur} op={act}")
+    for dh, dw, c0, c1 in shifts:
+        emit(f"shift %{cur} dh={dh} dw={dw} c0={c0} c1={c1}")
+    emit(f"binary %0 %{cur} op={bop}" if idx % 2 == 0 else f"binary %{cur} %0 op={bop}")
+    if fold:
+        emit(f"fold %{cur} op=avg")
+    emit(f"fc %{cur} groups={g2} out={o2}")
+    body = "\n".join(lines) + f"\noutput %{cur}\n"
+    wshapes = [(g1, C // g1, (C // g1) * k * k), (g2, o2 // g2, C // g2)]
+    case = _mk(body, (N, C, H, W), "bf16", 300 + idx, wshapes, f"ufc{idx}")
+    res, r, dy = harness.run_case(case)
+    # bf16 intermediates would move values across the clip bounds of expclip: that unary keeps the per-node lowering
+    assert r.info.fused == (0 if act and act.startswith("expclip") else 1), "unexpected choice of lowering"
     check_against_oracle(oracle, case, res, dy)
     r.close()
 
