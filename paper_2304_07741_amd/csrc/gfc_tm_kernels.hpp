@@ -1,0 +1,47 @@
+// Tap-major grouped FC on bf16 MFMA for bf16 operands and the common windows (1x1, 3x3, 5x5): the fast
+// path of the contraction in gfc_kernels.hpp (same mathematics: Canvas paper, Section 5, Fully-connected,
+// Group, Unfold).  The weights are first repacked so that
+//   * the contraction index runs tap-major: k' = tap * Rp + row, hence one MFMA step of 16 rows has ONE
+//     window tap, and the three (five) horizontal taps of a window row are served from one set of loaded
+//     registers (the horizontal shift is a different static selector of the operand gather);
+//   * groups with fewer than 16 rows are merged, gm = 16 / R groups per tile, into a block-diagonal weight
+//     (zeros between groups), rows and outputs padded with zeros to multiples of 16.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace canvas {
+namespace gfctm {
+
+struct Params {
+    const uint16_t* src = nullptr;     // row tensor [N, G, R, P] bf16
+    const uint16_t* wp = nullptr;      // packed weights [Gm][Omp][TV][Rp] bf16
+    void* dst = nullptr;               // forward: [N, G*Og, P] bf16 or fp32
+    const uint16_t* addend = nullptr;  // forward, bf16 dst: optional tensor added before rounding
+    const uint16_t* dy = nullptr;      // weight gradient: [N, G*Og, P] bf16
+    float* partial = nullptr;          // weight gradient: [slices][Gm][Omp][TV][Rp] fp32
+    int N = 0, H = 0, W = 0, P = 0, upi = 0;
+    int G = 0, R = 0, Og = 0;          // the FC's own grouping: R rows and Og outputs per group
+    int gm = 1, Gm = 0;                // groups merged per tile, merged group count ceil(G / gm)
+    int Rp = 0, Omp = 0;               // rows / outputs per merged group, padded
+    int KH = 1, KW = 1, TV = 1;
+    int mo = 1, otiles = 1;            // 16*mo outputs per wavefront, Omp = 16*mo*otiles
+    int dst_f32 = 0, acc = 0;
+    int nsplit = 1, chunks = 0, imgs_per_split = 0;  // weight gradient: slices = chunks (64-pixel positions) x nsplit (image ranges)
+    uint32_t magicW = 0, magicUpi = 0;
+};
+
+// Whether the fast path covers a contraction of this geometry (bf16 operands are the caller's business).
+bool supported(int N, int G, int R, int KH, int KW, int Og, int H, int W);
+Params shape(int N, int G, int R, int KH, int KW, int Og, int H, int W);
+// Geometry of the data gradient: rows and outputs swapped (pack the weights with transposed = true).
+Params data_gradient_of(const Params& fwd);
+inline int64_t packed_elems(const Params& P) { return (int64_t)P.Gm * P.Omp * P.TV * P.Rp; }
+
+// wp <- w [G][Og][R][TV] (transposed: the FC's own weights [G][R][Og][TV], read with rows/outputs swapped and taps flipped)
+void pack_weights(const uint16_t* w, uint16_t* wp, const Params& P, bool transposed, hipStream_t s);
+void forward(const Params& P, hipStream_t s);
+
+}  // namespace gfctm
+}  // namespace canvas
