@@ -263,6 +263,273 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         }
 }
 
+// ----------------------------------------------------------------------------------- weight gradient
+// dwp[gmi][o'][tap][row'] = sum over (image, pixel) of dy[o'](p) * x[row'](p + off(tap)), zero outside the image.
+// The contraction runs over pixels, the memory order of both operands, so 16-byte loads are MFMA operands
+// as they are: lane (r, s) holds pixels 8r..8r+7 of a 32-pixel chunk, of dy row 16*mo + s (A) and of x row
+// 16*rc + s (B); result lane holds dw[o' = 16*mo + 4r + jj][row' = 16*rc + s].
+// A wavefront owns one chunk POSITION inside the image and walks over a range of images, so everything
+// that depends on the position -- the zero-padding masks -- is computed once.  Per image and window row it
+// loads the x pixels of its unit plus two on either side; the horizontal taps are funnel shifts of those
+// registers.  Horizontal validity (a property of the output pixel) masks dy, once per window column;
+// vertical validity masks x, only in chunks that touch the first / last image rows.
+// The four wavefronts of a workgroup take four consecutive (image range, position) items of the same
+// (group, output tile, row chunk); their sums are added through LDS in a fixed order: one partial per workgroup.
+template <int MO, int KH, int KW>
+struct Step {
+    u32x4 dy[MO];
+    uint32_t x[KH][6];  // per window row: [pixels -2,-1] pixels 0..7 [pixels 8,9]
+};
+
+template <int MO, int KH, int KW>
+__global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
+    constexpr int TV = KH * KW, HW = KW / 2, HH = KH / 2;
+    constexpr int NE = MO * TV * 4;  // accumulator floats per lane
+    static_assert(HW >= 1 && HW <= 2, "windows with a halo of one or two pixels");
+    __shared__ float red[2][NE][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane >> 4, s = lane & 15;
+    const int nrc = P.Rp >> 4;
+    const int rc = blockIdx.y % nrc;
+    const int got = blockIdx.y / nrc;
+    const int otiles = P.Omp / (16 * MO);
+    const int gmi = got / otiles, ot = got - gmi * otiles;
+    const int gcount = min(P.gm, P.G - gmi * P.gm);
+    const int Rm = gcount * P.R, Om = gcount * P.Og;
+    const int items = P.chunks * P.nsplit;
+    const int item = blockIdx.x * kWaves + wave;
+    const bool active = item < items;
+    const int isplit = active ? item / P.chunks : 0;
+    const int pc = active ? item - isplit * P.chunks : 0;
+    const int i0 = isplit * P.imgs_per_split;
+    const int i1 = active ? min(P.N, i0 + P.imgs_per_split) : i0;
+
+    const int rows_img = P.G * P.R, outs_img = P.G * P.Og;
+    const int src_elems = P.N * rows_img * P.P, dy_elems = P.N * outs_img * P.P;
+    const rsrc_t rs = make_rsrc(P.src, src_elems * 2);
+    const rsrc_t rdy = make_rsrc(P.dy, dy_elems * 2);
+    const int grow0 = gmi * P.gm * P.R, gout0 = gmi * P.gm * P.Og;
+    const int p = pc * 32 + 8 * r;
+    const bool livepx = p < P.P;
+    const int nvalid = livepx ? min(8, P.P - p) : 0;
+    const int maxoff = HH * P.W + 2;
+
+    // per-lane constants: element offsets inside an image, load enables, masks
+    int edy[MO];
+    bool dyok[MO];
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++) {
+        const int o = ot * 16 * MO + mo * 16 + s;
+        dyok[mo] = livepx && o < Om;
+        edy[mo] = (gout0 + o) * P.P + p;
+    }
+    const int row = rc * 16 + s;
+    const bool xok = livepx && row < Rm;
+    const int ex = (grow0 + row) * P.P + p;
+
+    u32x4 dymask[KW];  // pixel exists and its source column under window column kw is inside the image
+    {
+        const int h0 = (int)div_magic((uint32_t)min(p, P.P - 1), P.magicW);
+        int c = min(p, P.P - 1) - h0 * P.W;
+        uint32_t bits[KW];
+#pragma unroll
+        for (int kw = 0; kw < KW; kw++) bits[kw] = 0;
+#pragma unroll
+        for (int q = 0; q < 8; q++) {
+#pragma unroll
+            for (int kw = 0; kw < KW; kw++)
+                if (q < nvalid && (unsigned)(c + kw - HW) < (unsigned)P.W) bits[kw] |= 1u << q;
+            if (++c == P.W) c = 0;
+        }
+#pragma unroll
+        for (int kw = 0; kw < KW; kw++) dymask[kw] = mask_of(bits[kw]);
+    }
+    bool needrow[KH];
+#pragma unroll
+    for (int kh = 0; kh < KH; kh++) {
+        const int first = p - 2 + (kh - HH) * P.W, last = p + 9 + (kh - HH) * P.W;
+        needrow[kh] = kh != HH && __builtin_amdgcn_ballot_w64(livepx && (first < 0 || last >= P.P)) != 0;
+    }
+
+    float4_t acc[MO][TV];
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+        for (int t = 0; t < TV; t++) acc[mo][t] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    auto issue = [&](int n, bool valid, Step<MO, KH, KW>& st) {
+        // wave-uniform: could a multi-byte access of this step straddle an end of a tensor?  (the hardware
+        // drops such an access as a whole; those steps read element by element)
+        const int xrow0 = n * rows_img + grow0 + rc * 16, yrow0 = n * outs_img + gout0 + ot * 16 * MO;
+        const bool near_ends = xrow0 * P.P + pc * 32 - maxoff < 0 || (xrow0 + 16) * P.P + pc * 32 + 48 + maxoff > src_elems ||
+                               (yrow0 + 16 * MO) * P.P + pc * 32 + 40 > dy_elems;
+        const int nx = n * rows_img * P.P, ny = n * outs_img * P.P;
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++) {
+            const bool ok = valid && dyok[mo];
+            const int e = ny + edy[mo];
+            if (!near_ends) {
+                st.dy[mo] = bload16(rdy, ok ? e * 2 : kOob);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(rdy, ok ? (e + 2 * k) * 2 : kOob, 0, 0);
+                    const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(rdy, ok ? (e + 2 * k + 1) * 2 : kOob, 0, 0);
+                    st.dy[mo][k] = (lo & 0xffffu) | (hi << 16);
+                }
+            }
+        }
+#pragma unroll
+        for (int kh = 0; kh < KH; kh++) {
+            const bool ok = valid && xok;
+            const int e = nx + ex + (kh - HH) * P.W;
+            if (!near_ends) {
+                const u32x4 m = bload16(rs, ok ? e * 2 : kOob);
+#pragma unroll
+                for (int k = 0; k < 4; k++) st.x[kh][k + 1] = m[k];
+                st.x[kh][0] = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? (e - 2) * 2 : kOob, 0, 0);
+                st.x[kh][5] = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? (e + 8) * 2 : kOob, 0, 0);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 6; k++) {
+                    const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? (e + 2 * k - 2) * 2 : kOob, 0, 0);
+                    const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? (e + 2 * k - 1) * 2 : kOob, 0, 0);
+                    st.x[kh][k] = (lo & 0xffffu) | (hi << 16);
+                }
+            }
+        }
+    };
+
+    auto consume = [&](Step<MO, KH, KW>& st) {
+#pragma unroll
+        for (int kh = 0; kh < KH; kh++)
+            if (needrow[kh]) {
+#pragma unroll
+                for (int k = 0; k < 6; k++) {
+                    const int i = 2 * k - 2;
+                    const bool lo = (unsigned)(p + i + (kh - HH) * P.W) < (unsigned)P.P;
+                    const bool hi = (unsigned)(p + i + 1 + (kh - HH) * P.W) < (unsigned)P.P;
+                    st.x[kh][k] &= (lo ? 0x0000ffffu : 0u) | (hi ? 0xffff0000u : 0u);
+                }
+            }
+#pragma unroll
+        for (int kw = 0; kw < KW; kw++) {
+            u32x4 a[MO];
+#pragma unroll
+            for (int mo = 0; mo < MO; mo++) a[mo] = st.dy[mo] & dymask[kw];
+#pragma unroll
+            for (int kh = 0; kh < KH; kh++) {
+                // pixels dw .. dw + 7 of the row registers (element index of pixel 0 is 2)
+                const int dw = kw - HW;
+                uint32_t xs[4];
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const int e0 = 2 * k + 2 + dw;  // first element of output dword k
+                    xs[k] = (e0 & 1) ? __builtin_amdgcn_alignbit(st.x[kh][(e0 >> 1) + 1], st.x[kh][e0 >> 1], 16) : st.x[kh][e0 >> 1];
+                }
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++) {
+                    float4_t c = acc[mo][kh * KW + kw];
+                    c = mfma16(as_short4(a[mo][0], a[mo][1]), as_short4(xs[0], xs[1]), c);
+                    c = mfma16(as_short4(a[mo][2], a[mo][3]), as_short4(xs[2], xs[3]), c);
+                    acc[mo][kh * KW + kw] = c;
+                }
+            }
+        }
+    };
+
+    // two images per trip: the loads of the next image are in flight while this one is multiplied
+    Step<MO, KH, KW> st[2];
+    issue(i0, i0 < i1, st[0]);
+    for (int n = i0; n < i1; n += 2) {
+        issue(n + 1, n + 1 < i1, st[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(st[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(n + 2, n + 2 < i1, st[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (n + 1 < i1) consume(st[1]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // sum of the workgroup's four wavefronts in a fixed order: (w0 + w2) + (w1 + w3), through LDS
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int t = 0; t < TV; t++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) red[slot][(mo * TV + t) * 4 + jj][lane] = acc[mo][t][jj];
+    };
+    auto add = [&](int slot) {
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int t = 0; t < TV; t++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) acc[mo][t][jj] += red[slot][(mo * TV + t) * 4 + jj][lane];
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) add(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave == 0) {
+        add(0);
+        float* part = P.partial + (long long)blockIdx.x * P.Gm * P.Omp * TV * P.Rp;
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int t = 0; t < TV; t++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) {
+                    const int o = ot * 16 * MO + mo * 16 + 4 * r + jj;
+                    part[((long long)(gmi * P.Omp + o) * TV + t) * P.Rp + rc * 16 + s] = acc[mo][t][jj];
+                }
+    }
+}
+
+// dw[g][o][row][tap] = sum over the workgroup partials of dwp[g / gm][(g % gm) * Og + o][tap][(g % gm) * R + row],
+// in a fixed order: 8 segments of partials per element, combined through LDS.
+__global__ __launch_bounds__(256) void k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ dw, int slices, int G, int R, int Og,
+                                                      int TV, int gm, int Omp, int Rp, long long packed) {
+    __shared__ float red[8][32];
+    const int el = threadIdx.x & 31, seg = threadIdx.x >> 5;
+    const long long e = (long long)blockIdx.x * 32 + el;
+    const long long elems = (long long)G * Og * R * TV;
+    float sum = 0.f;
+    if (e < elems) {
+        const int tap = (int)(e % TV);
+        long long t = e / TV;
+        const int row = (int)(t % R);
+        t /= R;
+        const int o = (int)(t % Og), g = (int)(t / Og);
+        const int gmi = g / gm, sub = g - gmi * gm;
+        const long long idx = ((long long)(gmi * Omp + sub * Og + o) * TV + tap) * Rp + sub * R + row;
+        const int per = (slices + 7) / 8;
+        const int end = min(slices, (seg + 1) * per);
+        int k = seg * per;
+        for (; k + 4 <= end; k += 4) {  // four independent loads in flight, summed in slice order
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) v[i] = partial[(long long)(k + i) * packed + idx];
+#pragma unroll
+            for (int i = 0; i < 4; i++) sum += v[i];
+        }
+        for (; k < end; k++) sum += partial[(long long)k * packed + idx];
+    }
+    red[seg][el] = sum;
+    __syncthreads();
+    if (seg == 0 && e < elems) {
+        float t = red[0][el];
+#pragma unroll
+        for (int i = 1; i < 8; i++) t += red[i][el];
+        dw[e] = t;
+    }
+}
+
 // wp[gmi][op][tap][rp]: block-diagonal over the gm merged groups, zero in the padding
 __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int G, int R, int Og, int TV, int gm, int Gm,
                                int Rp, int Omp, int transposed) {
@@ -350,6 +617,43 @@ void pack_weights(const uint16_t* w, uint16_t* wp, const Params& P, bool transpo
     if (total > 0)
         CANVAS_LAUNCH(k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, w, wp, P.G, P.R, P.Og, P.TV, P.gm, P.Gm, P.Rp,
                       P.Omp, transposed ? 1 : 0);
+}
+
+// outputs per wavefront tile of the weight gradient, in units of 16 (its accumulators are MO x taps)
+static int wgrad_mo(const Params& P) { return P.KH == 3 && P.Omp % 32 == 0 ? 2 : 1; }
+
+void prepare_wgrad(Params& P) {
+    P.chunks = (P.P + 31) / 32;
+    const int64_t tiles = (int64_t)P.Gm * (P.Omp / (16 * wgrad_mo(P))) * (P.Rp / 16);
+    const int64_t packed = packed_elems(P);
+    // about 3.5 k wavefronts; partials at most max(8 MB, 30 % of the operand bytes)
+    int64_t nsplit = std::max<int64_t>(1, std::min<int64_t>(P.N, (3584 + P.chunks * tiles - 1) / (P.chunks * tiles)));
+    const int64_t operand_bytes = (int64_t)P.N * P.G * (P.R + P.Og) * P.P * 2;
+    const int64_t cap = std::max<int64_t>((int64_t)8 << 20, operand_bytes * 3 / 10);
+    nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, kWaves * cap / (packed * 4 * P.chunks)));
+    P.imgs_per_split = (int)((P.N + nsplit - 1) / nsplit);
+    P.nsplit = (P.N + P.imgs_per_split - 1) / P.imgs_per_split;
+}
+
+int wgrad_slices(const Params& P) { return (P.chunks * P.nsplit + kWaves - 1) / kWaves; }
+
+void wgrad_partial(const Params& P, hipStream_t s) {
+    const int mo = wgrad_mo(P);
+    const dim3 grid((unsigned)wgrad_slices(P), (unsigned)(P.Gm * (P.Omp / (16 * mo)) * (P.Rp / 16)));
+    const dim3 block(64 * kWaves);
+    if (P.KH == 3) {
+        if (mo == 1) CANVAS_LAUNCH((k_wgrad<1, 3, 3>), grid, block, 0, s, P);
+        else CANVAS_LAUNCH((k_wgrad<2, 3, 3>), grid, block, 0, s, P);
+    } else {
+        CANVAS_LAUNCH((k_wgrad<1, 5, 5>), grid, block, 0, s, P);
+    }
+}
+
+void wgrad_reduce(const Params& P, float* dw, hipStream_t s) {
+    const long long elems = (long long)P.G * P.Og * P.R * P.TV;
+    if (elems > 0)
+        CANVAS_LAUNCH(k_wgrad_reduce, dim3((unsigned)((elems + 31) / 32)), dim3(256), 0, s, (const float*)P.partial, dw, wgrad_slices(P), P.G, P.R,
+                      P.Og, P.TV, P.gm, P.Omp, P.Rp, (long long)packed_elems(P));
 }
 
 void forward(const Params& P, hipStream_t s) {

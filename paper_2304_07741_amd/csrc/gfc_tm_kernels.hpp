@@ -28,7 +28,7 @@ struct Params {
     int KH = 1, KW = 1, TV = 1;
     int mo = 1, otiles = 1;            // 16*mo outputs per wavefront, Omp = 16*mo*otiles
     int dst_f32 = 0, acc = 0;
-    int nsplit = 1, chunks = 0, imgs_per_split = 0;  // weight gradient: slices = chunks (64-pixel positions) x nsplit (image ranges)
+    int nsplit = 1, chunks = 0, imgs_per_split = 0;  // weight gradient: work items = chunks (32-pixel positions) x nsplit (image ranges)
     uint32_t magicW = 0, magicUpi = 0;
 };
 
@@ -42,6 +42,13 @@ inline int64_t packed_elems(const Params& P) { return (int64_t)P.Gm * P.Omp * P.
 // wp <- w [G][Og][R][TV] (transposed: the FC's own weights [G][R][Og][TV], read with rows/outputs swapped and taps flipped)
 void pack_weights(const uint16_t* w, uint16_t* wp, const Params& P, bool transposed, hipStream_t s);
 void forward(const Params& P, hipStream_t s);
+
+// Weight gradient of a windowed contraction (KH = KW = 3 or 5).  prepare_wgrad splits the work; the partials
+// buffer holds wgrad_slices(P) * packed_elems(P) floats; wgrad_reduce sums them into dw [G][Og][R][TV] (fp32).
+void prepare_wgrad(Params& P);
+int wgrad_slices(const Params& P);
+void wgrad_partial(const Params& P, hipStream_t s);
+void wgrad_reduce(const Params& P, float* dw, hipStream_t s);
 
 }  // namespace gfctm
 }  // namespace canvas

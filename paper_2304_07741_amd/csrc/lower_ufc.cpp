@@ -206,16 +206,36 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
                             R.dx1 = (uint16_t*)a.dx;  // completed by the data gradient of FC1 below
                             ufc::mid_backward(R, a.stream);
                         }});
-    low->bwd.push_back({KH * KW > 1 ? "ufc_fc1_wgrad_unfold" : "ufc_fc1_wgrad", 2.0 * act + 4.0 * s1 * nw1, fl1, [=](const RunArgs& a) {
-                            gfc::Params R = W1;
-                            R.src = a.x;
-                            R.dy = a.ws + odz;
-                            R.partial = (float*)(a.ws + op1);
-                            gfc::wgrad_partial(R, a.stream);
-                        }});
-    low->bwd.push_back({"ufc_fc1_wgrad_reduce", 4.0 * (s1 + 1) * nw1, 0, [=](const RunArgs& a) {
-                            gfc::wgrad_reduce((const float*)(a.ws + op1), (float*)a.dw[w1], s1, nw1, a.stream);
-                        }});
+    if (TV > 1 && gfctm::supported(dag.N, G1, C / G1, KH, KW, C / G1, dag.H, dag.W)) {
+        gfctm::Params T = gfctm::shape(dag.N, G1, C / G1, KH, KW, C / G1, dag.H, dag.W);
+        gfctm::prepare_wgrad(T);
+        const int ts = gfctm::wgrad_slices(T);
+        const int64_t pk = gfctm::packed_elems(T);
+        const int64_t opt = take((uint64_t)ts * pk * 4);
+        low->bwd.push_back({"ufc_fc1_wgrad_unfold", 2.0 * act + 4.0 * ts * pk, fl1, [=](const RunArgs& a) {
+                                gfctm::Params R = T;
+                                R.src = (const uint16_t*)a.x;
+                                R.dy = (const uint16_t*)(a.ws + odz);
+                                R.partial = (float*)(a.ws + opt);
+                                gfctm::wgrad_partial(R, a.stream);
+                            }});
+        low->bwd.push_back({"ufc_fc1_wgrad_reduce", 4.0 * ts * pk + 4.0 * nw1, 0, [=](const RunArgs& a) {
+                                gfctm::Params R = T;
+                                R.partial = (float*)(a.ws + opt);
+                                gfctm::wgrad_reduce(R, (float*)a.dw[w1], a.stream);
+                            }});
+    } else {
+        low->bwd.push_back({KH * KW > 1 ? "ufc_fc1_wgrad_unfold" : "ufc_fc1_wgrad", 2.0 * act + 4.0 * s1 * nw1, fl1, [=](const RunArgs& a) {
+                                gfc::Params R = W1;
+                                R.src = a.x;
+                                R.dy = a.ws + odz;
+                                R.partial = (float*)(a.ws + op1);
+                                gfc::wgrad_partial(R, a.stream);
+                            }});
+        low->bwd.push_back({"ufc_fc1_wgrad_reduce", 4.0 * (s1 + 1) * nw1, 0, [=](const RunArgs& a) {
+                                gfc::wgrad_reduce((const float*)(a.ws + op1), (float*)a.dw[w1], s1, nw1, a.stream);
+                            }});
+    }
     // mid_backward left dx_direct in dx; the data gradient of FC1 (through the Unfold adjoint) adds to it
     emit_fc(low->bwd, TV > 1 ? "ufc_fc1_dgrad_unfold" : "ufc_fc1_dgrad", G1, C / G1, KH, KW, C / G1, true, w1,
             [=](const RunArgs& a) { return (const void*)(a.ws + odz); }, [](const RunArgs& a) { return (const void*)a.dx; }, true,
