@@ -38,7 +38,10 @@ struct Group {
     short4_t a[KW][MO];             // weights of the KW taps of this window row
 };
 
-template <int MO, int KH, int KW, bool DST_F32>
+// KS > 1: the KS wavefronts that share a tile split its row chunks (chunk c goes to wavefront c % KS) and
+// their accumulators are added through LDS in wavefront order; for contractions with many channels on
+// few pixels, where one wavefront per tile would leave most SIMDs idle on a long serial K loop.
+template <int MO, int KH, int KW, bool DST_F32, int KS>
 __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     constexpr int TV = KH * KW, HW = KW / 2, HH = KH / 2;
     constexpr bool HALO = KW > 1;
@@ -47,15 +50,18 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     static_assert(HW <= 2, "halo of two pixels");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x * kWaves + wave;
+    const int tile = blockIdx.x * (kWaves / KS) + wave / KS, ks = wave % KS;
     const int total_units = P.N * P.upi;
-    if (tile * 16 >= total_units) return;
+    const bool active = tile * 16 < total_units;
+    if constexpr (KS == 1) {
+        if (!active) return;
+    }
     const int gmi = blockIdx.y / P.otiles, ot = blockIdx.y - gmi * P.otiles;
     const int gcount = min(P.gm, P.G - gmi * P.gm);
     const int Rm = gcount * P.R, Om = gcount * P.Og;
     const int r = lane >> 4, s = lane & 15;
     const int U = tile * 16 + s;
-    const bool live = U < total_units;
+    const bool live = active && U < total_units;
     const int n = live ? (int)div_magic((uint32_t)U, P.magicUpi) : 0;
     const int p = live ? (U - n * P.upi) * 8 : 0;
     const int rows_img = P.G * P.R;
@@ -70,7 +76,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
 
     // wave-uniform: could a multi-byte access of this tile straddle an end of the source tensor?  (the
     // hardware drops such an access as a whole, so those tiles read element by element)
-    const int n_first = (int)div_magic((uint32_t)(tile * 16), P.magicUpi);
+    const int n_first = (int)div_magic((uint32_t)min(tile * 16, total_units - 1), P.magicUpi);
     const int n_last = (int)div_magic((uint32_t)min(tile * 16 + 15, total_units - 1), P.magicUpi);
     const int maxoff = HH * P.W + 2;
     const bool near_ends = (n_first * rows_img + grow0) * P.P - maxoff < 0 ||
@@ -181,16 +187,17 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     // are issued before the current group is multiplied
     constexpr int UNR = KH > 1 ? KH : 2;
     Group<MO, KW> buf[UNR];
-    const int NG = nrc * KH;
-    issue(0, 0, true, buf[0]);
+    const int nrc_mine = active && ks < nrc ? (nrc - ks + KS - 1) / KS : 0;  // this wavefront's chunks: ks, ks + KS, ...
+    const int NG = nrc_mine * KH;
+    issue(ks, 0, NG > 0, buf[0]);
     for (int it = 0; it * UNR < NG; it++) {
 #pragma unroll
         for (int u = 0; u < UNR; u++) {
             const int g = it * UNR + u;
             if (KH > 1 || g < NG) {
                 const int khn = KH > 1 ? (u + 1) % KH : 0;
-                const int rcn = KH > 1 ? (u + 1 == KH ? it + 1 : it) : g + 1;
-                issue(rcn, khn, g + 1 < NG, buf[(u + 1) % UNR]);
+                const int rcn = KH > 1 ? (u + 1 == KH ? it + 1 : it) : g + 1;  // index among this wavefront's chunks
+                issue(ks + rcn * KS, khn, g + 1 < NG, buf[(u + 1) % UNR]);
                 __builtin_amdgcn_sched_barrier(0);
                 consume(KH > 1 ? u : 0, buf[u]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -198,6 +205,32 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         }
     }
 
+    if constexpr (KS > 1) {
+        // wavefronts ks = 1 .. KS-1 hand their sums to wavefront 0 of the tile, one after the other
+        __shared__ float red[kWaves / KS][MO * 32][64];
+        const int sub = wave / KS;
+        for (int v = 1; v < KS; v++) {
+            if (ks == v) {
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+                    for (int q = 0; q < 8; q++)
+#pragma unroll
+                        for (int j = 0; j < 4; j++) red[sub][(mo * 8 + q) * 4 + j][lane] = acc[mo][q][j];
+            }
+            __syncthreads();
+            if (ks == 0) {
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+                    for (int q = 0; q < 8; q++)
+#pragma unroll
+                        for (int j = 0; j < 4; j++) acc[mo][q][j] += red[sub][(mo * 8 + q) * 4 + j][lane];
+            }
+            __syncthreads();
+        }
+        if (ks != 0) return;
+    }
     if (!live) return;
     const int nvalid = min(8, P.P - p);
     const int outs_img = P.G * P.Og;
@@ -550,13 +583,17 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
     wp[i] = v;
 }
 
-// One tile per wavefront.  (Measured on MI355X: persistent wavefronts that walk over several tiles and
-// issue the next tile's first loads early, with or without cache-line touches ahead, were not faster.)
+// One tile per wavefront (KS = 1) or per KS wavefronts.  (Measured on MI355X: persistent wavefronts that
+// walk over several tiles and issue the next tile's first loads early, with or without cache-line
+// touches ahead, were not faster than letting the hardware scheduler balance one-tile workgroups.)
 template <int MO, int KH, int KW, bool DST_F32>
 void launch_fwd_k(const Params& P, hipStream_t s) {
     const int tiles = (P.N * P.upi + 15) / 16;
-    const int gx = (tiles + kWaves - 1) / kWaves;
-    CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32>), dim3((unsigned)gx, (unsigned)(P.Gm * P.otiles)), dim3(64 * kWaves), 0, s, P);
+    const dim3 block(64 * kWaves);
+    const unsigned gy = (unsigned)(P.Gm * P.otiles);
+    if (P.ksplit == 4) CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 4>), dim3((unsigned)tiles, gy), block, 0, s, P);
+    else if (P.ksplit == 2) CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 2>), dim3((unsigned)((tiles + 1) / 2), gy), block, 0, s, P);
+    else CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 1>), dim3((unsigned)((tiles + kWaves - 1) / kWaves), gy), block, 0, s, P);
 }
 
 template <int MO, bool DST_F32>
@@ -599,10 +636,13 @@ Params shape(int N, int G, int R, int KH, int KW, int Og, int H, int W) {
     Q.Rp = (Q.gm * R + 15) / 16 * 16;
     const int Om = Q.gm * Og;
     Q.mo = Om <= 16 ? 1 : (Om <= 32 || KW > 1 ? 2 : 4);  // windows: the buffers of two groups leave room for 32 outputs
-    // small problems: more, narrower wavefront tiles rather than idle SIMDs
-    const int64_t tiles = ((int64_t)N * Q.upi + 15) / 16;
-    while (Q.mo > 1 && tiles * Q.Gm * ((Om + 16 * Q.mo - 1) / (16 * Q.mo)) < 2048) Q.mo /= 2;
     Q.otiles = (Om + 16 * Q.mo - 1) / (16 * Q.mo);
+    // few tiles with a long K loop: split the row chunks of a tile over 2 or 4 wavefronts
+    const int64_t waves = (((int64_t)N * Q.upi + 15) / 16) * Q.Gm * Q.otiles;
+    const int nrc = Q.Rp / 16;
+    Q.ksplit = 1;
+    if (waves < 2048 && nrc >= 2) Q.ksplit = 2;
+    if (waves < 1024 && nrc >= 4) Q.ksplit = 4;
     Q.Omp = Q.otiles * 16 * Q.mo;
     auto magic = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); };
     Q.magicW = magic((uint32_t)W);

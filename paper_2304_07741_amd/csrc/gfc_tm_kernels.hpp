@@ -27,6 +27,7 @@ struct Params {
     int Rp = 0, Omp = 0;               // rows / outputs per merged group, padded
     int KH = 1, KW = 1, TV = 1;
     int mo = 1, otiles = 1;            // 16*mo outputs per wavefront, Omp = 16*mo*otiles
+    int ksplit = 1;                    // forward: wavefronts that share one tile and split its row chunks (1, 2, 4)
     int dst_f32 = 0, acc = 0;
     int nsplit = 1, chunks = 0, imgs_per_split = 0;  // weight gradient: work items = chunks (32-pixel positions) x nsplit (image ranges)
     uint32_t magicW = 0, magicUpi = 0;

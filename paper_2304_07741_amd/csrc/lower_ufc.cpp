@@ -133,8 +133,9 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
     auto emit_fc = [&](std::vector<Launch>& list, const std::string& name, int G, int R, int kh, int kw, int Og, bool transposed, int widx,
                        Ptr src, Ptr dst, bool addend_is_dst, double bytes, double flops) {
         const int64_t nw = (int64_t)G * Og * R * kh * kw;
-        // (1x1 contractions stay on the generic kernel: measured faster there)
-        if (kh * kw > 1 && gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W)) {
+        // (1x1 contractions with enough tiles to fill the chip stay on the generic kernel: measured faster there)
+        if (gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W) &&
+            (kh * kw > 1 || gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W).ksplit > 1)) {
             const gfctm::Params T = gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
             const bool identity = !transposed && T.TV == 1 && T.gm == 1 && T.Rp == R && T.Omp == Og;
             const int64_t opk = identity ? -1 : take((uint64_t)gfctm::packed_elems(T) * 2);
