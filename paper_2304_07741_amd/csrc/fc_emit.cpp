@@ -1,0 +1,92 @@
+#include "fc_emit.hpp"
+
+#include "gfc_kernels.hpp"
+#include "gfc_tm_kernels.hpp"
+
+namespace canvas {
+
+void emit_fc(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
+             bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32) {
+    const int64_t nw = (int64_t)G * Og * R * kh * kw;
+    // (1x1 contractions with enough tiles to fill the chip stay on the generic kernel: measured faster there)
+    if (!src.f32 && gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W) &&
+        (kh * kw > 1 || gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W).ksplit > 1)) {
+        const gfctm::Params T = gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
+        const bool identity = !transposed && T.TV == 1 && T.gm == 1 && T.Rp == R && T.Omp == Og;
+        const int64_t opk = identity ? -1 : take((uint64_t)gfctm::packed_elems(T) * 2);
+        if (!identity)
+            list.push_back({name + "_pack_w", 2.0 * nw + 2.0 * gfctm::packed_elems(T), 0, [=](const RunArgs& a) {
+                                gfctm::pack_weights((const uint16_t*)a.w[widx], (uint16_t*)(a.ws + opk), T, transposed, a.stream);
+                            }});
+        list.push_back({name, bytes, flops, [=](const RunArgs& a) {
+                            gfctm::Params Q = T;
+                            Q.src = (const uint16_t*)src.ptr(a);
+                            Q.wp = identity ? (const uint16_t*)a.w[widx] : (const uint16_t*)(a.ws + opk);
+                            Q.dst = const_cast<void*>(dst(a));
+                            Q.dst_f32 = dst_f32 ? 1 : 0;
+                            Q.addend = addend_is_dst ? (const uint16_t*)dst(a) : nullptr;  // each lane reads the elements it then overwrites
+                            gfctm::forward(Q, a.stream);
+                        }});
+        return;
+    }
+    gfc::Params F = gfc::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
+    F.src_f32 = src.f32 ? 1 : 0;
+    F.dst_f32 = dst_f32 ? 1 : 0;
+    gfc::prepare_forward(F);
+    const int64_t owt = transposed ? take((uint64_t)nw * 2) : -1;
+    if (transposed)  // (R, Og) are the swapped dims: the FC's own weights are [G][R][Og][taps]
+        list.push_back({name + "_transpose_w", 4.0 * nw, 0, [=](const RunArgs& a) {
+                            gfc::transpose_weights((const uint16_t*)a.w[widx], (uint16_t*)(a.ws + owt), G, R, Og, kh * kw, a.stream);
+                        }});
+    list.push_back({name, bytes, flops, [=](const RunArgs& a) {
+                        gfc::Params Q = F;
+                        Q.src = src.ptr(a);
+                        Q.w = transposed ? (const uint16_t*)(a.ws + owt) : (const uint16_t*)a.w[widx];
+                        Q.dst = const_cast<void*>(dst(a));
+                        Q.addend = addend_is_dst ? (const uint16_t*)dst(a) : nullptr;
+                        gfc::forward(Q, a.stream);
+                    }});
+}
+
+void emit_wgrad(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
+                int widx, FcOperand src, FcOperand dy, double operand_bytes, double flops) {
+    const int64_t nw = (int64_t)G * Og * R * kh * kw;
+    if (kh * kw > 1 && !src.f32 && !dy.f32 && gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W)) {
+        gfctm::Params T = gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
+        gfctm::prepare_wgrad(T);
+        const int ts = gfctm::wgrad_slices(T);
+        const int64_t pk = gfctm::packed_elems(T);
+        const int64_t opt = take((uint64_t)ts * pk * 4);
+        list.push_back({name, operand_bytes + 4.0 * ts * pk, flops, [=](const RunArgs& a) {
+                            gfctm::Params Q = T;
+                            Q.src = (const uint16_t*)src.ptr(a);
+                            Q.dy = (const uint16_t*)dy.ptr(a);
+                            Q.partial = (float*)(a.ws + opt);
+                            gfctm::wgrad_partial(Q, a.stream);
+                        }});
+        list.push_back({name + "_reduce", 4.0 * ts * pk + 4.0 * nw, 0, [=](const RunArgs& a) {
+                            gfctm::Params Q = T;
+                            Q.partial = (float*)(a.ws + opt);
+                            gfctm::wgrad_reduce(Q, (float*)a.dw[widx], a.stream);
+                        }});
+        return;
+    }
+    gfc::Params W = gfc::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
+    W.src_f32 = src.f32 ? 1 : 0;
+    W.dy_f32 = dy.f32 ? 1 : 0;
+    gfc::prepare_wgrad(W);
+    const int slices = W.slices;
+    const int64_t op = take((uint64_t)slices * nw * 4);
+    list.push_back({name, operand_bytes + 4.0 * slices * nw, flops, [=](const RunArgs& a) {
+                        gfc::Params Q = W;
+                        Q.src = src.ptr(a);
+                        Q.dy = dy.ptr(a);
+                        Q.partial = (float*)(a.ws + op);
+                        gfc::wgrad_partial(Q, a.stream);
+                    }});
+    list.push_back({name + "_reduce", 4.0 * (slices + 1) * nw, 0, [=](const RunArgs& a) {
+                        gfc::wgrad_reduce((const float*)(a.ws + op), (float*)a.dw[widx], slices, nw, a.stream);
+                    }});
+}
+
+}  // namespace canvas

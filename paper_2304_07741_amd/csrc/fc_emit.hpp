@@ -1,0 +1,32 @@
+// Launch lists of one FC-shaped contraction on the MFMA kernels, shared by the fused lowerings: picks the
+// tap-major kernels (with their weight-packing launch) where they apply, else the generic kernels.
+#pragma once
+#include <functional>
+#include <string>
+#include <vector>
+
+#include "lowering.hpp"
+
+namespace canvas {
+
+// Workspace carving: returns the byte offset of a new 256-byte aligned block.
+using TakeFn = std::function<int64_t(uint64_t)>;
+using PtrFn = std::function<const void*(const RunArgs&)>;
+
+struct FcOperand {
+    PtrFn ptr;
+    bool f32 = false;  // fp32 tensor (else bf16)
+};
+
+// y = FC(src) (forward), or, with `transposed`, the data gradient src = dy -> dst = d(source of the FC):
+// then (R, Og) are the swapped dims and the FC's own weights [G][R][Og][taps] are read transposed with the
+// taps flipped.  `addend_is_dst`: dst (bf16) already holds a tensor that the result is added to.
+// dst is bf16 unless dst_f32.
+void emit_fc(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
+             bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32 = false);
+
+// dw[widx] = sum over (image, pixel) of dy (x) rows of src (through the window kh x kw); partials + fixed-order reduce.
+void emit_wgrad(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
+                int widx, FcOperand src, FcOperand dy, double operand_bytes, double flops);
+
+}  // namespace canvas

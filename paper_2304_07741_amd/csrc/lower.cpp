@@ -7,6 +7,7 @@ std::unique_ptr<Lowering> lower(const Dag& dag, bool bf16, bool no_fusion) {
     if (!no_fusion) {
         if (auto l = lower_sgfc(dag, bf16)) return l;
         if (auto l = lower_ufc(dag, bf16)) return l;
+        if (auto l = lower_dyn(dag, bf16)) return l;
     }
     return lower_per_node(dag, bf16);
 }

@@ -10,8 +10,8 @@
 #include <functional>
 #include <vector>
 
+#include "fc_emit.hpp"
 #include "gfc_kernels.hpp"
-#include "gfc_tm_kernels.hpp"
 #include "lowering.hpp"
 #include "ufc_kernels.hpp"
 
@@ -92,14 +92,7 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
     if ((int64_t)dag.N * std::max(C, O2) * Pn * 2 >= ((int64_t)1 << 31) || dag.W < 4 || (int64_t)dag.N * Pn >= ((int64_t)1 << 28)) return nullptr;
 
     const int G1 = fc1.groups, G2 = fc2.groups;
-    gfc::Params F1 = gfc::shape(dag.N, G1, C / G1, KH, KW, C / G1, dag.H, dag.W);
-    gfc::Params F2 = gfc::shape(dag.N, G2, C / G2, 1, 1, O2 / G2, dag.H, dag.W);
-    F1.src_f32 = F2.src_f32 = 0;
-    F1.dst_f32 = F2.dst_f32 = 0;
-    F1.dy_f32 = F2.dy_f32 = 0;
-    gfc::Params W1 = F1, W2 = F2;
-    gfc::prepare_wgrad(W1);
-    gfc::prepare_wgrad(W2);
+    const int K1 = (C / G1) * KH * KW, K2 = C / G2;
     M.N = dag.N;
     M.C = C;
     M.H = dag.H;
@@ -112,7 +105,7 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
 
     auto low = std::make_unique<Lowering>();
     low->fused = true;
-    const int64_t nw1 = (int64_t)C * F1.K, nw2 = (int64_t)O2 * F2.K;
+    const int64_t nw1 = (int64_t)C * K1, nw2 = (int64_t)O2 * K2;
     const double act = 2.0 * dag.numel(0), outb = 2.0 * dag.numel(dag.out);
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) {
@@ -121,59 +114,16 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
         return (int64_t)o;
     };
     const int64_t oz = take((uint64_t)act), ov = take((uint64_t)act), odv = take((uint64_t)act), odz = take((uint64_t)act);
-    const int64_t op1 = take((uint64_t)W1.slices * nw1 * 4), op2 = take((uint64_t)W2.slices * nw2 * 4);
-    low->ws_bytes = off;
     const int w1 = fc1.widx, w2 = fc2.widx;
-    const double fl1 = 2.0 * dag.N * Pn * (double)C * F1.K, fl2 = 2.0 * dag.N * Pn * (double)O2 * F2.K;
+    const double fl1 = 2.0 * dag.N * Pn * (double)C * K1, fl2 = 2.0 * dag.N * Pn * (double)O2 * K2;
 
-    // One FC-shaped contraction (forward, or a data gradient when `transposed`): the tap-major kernels
-    // with a weight-packing launch in front where they apply, else the generic kernel (whose data
-    // gradient wants the weights transposed first).
-    using Ptr = std::function<const void*(const RunArgs&)>;
-    auto emit_fc = [&](std::vector<Launch>& list, const std::string& name, int G, int R, int kh, int kw, int Og, bool transposed, int widx,
-                       Ptr src, Ptr dst, bool addend_is_dst, double bytes, double flops) {
-        const int64_t nw = (int64_t)G * Og * R * kh * kw;
-        // (1x1 contractions with enough tiles to fill the chip stay on the generic kernel: measured faster there)
-        if (gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W) &&
-            (kh * kw > 1 || gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W).ksplit > 1)) {
-            const gfctm::Params T = gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
-            const bool identity = !transposed && T.TV == 1 && T.gm == 1 && T.Rp == R && T.Omp == Og;
-            const int64_t opk = identity ? -1 : take((uint64_t)gfctm::packed_elems(T) * 2);
-            if (!identity)
-                list.push_back({name + "_pack_w", 2.0 * nw + 2.0 * gfctm::packed_elems(T), 0, [=](const RunArgs& a) {
-                                    gfctm::pack_weights((const uint16_t*)a.w[widx], (uint16_t*)(a.ws + opk), T, transposed, a.stream);
-                                }});
-            list.push_back({name, bytes, flops, [=](const RunArgs& a) {
-                                gfctm::Params Q = T;
-                                Q.src = (const uint16_t*)src(a);
-                                Q.wp = identity ? (const uint16_t*)a.w[widx] : (const uint16_t*)(a.ws + opk);
-                                Q.dst = const_cast<void*>(dst(a));
-                                Q.addend = addend_is_dst ? (const uint16_t*)dst(a) : nullptr;  // each lane reads the elements it then overwrites
-                                gfctm::forward(Q, a.stream);
-                            }});
-            return;
-        }
-        gfc::Params F = gfc::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
-        F.src_f32 = 0;
-        F.dst_f32 = 0;
-        gfc::prepare_forward(F);
-        const int64_t owt = transposed ? take((uint64_t)nw * 2) : -1;
-        if (transposed)  // here (R, Og) are already the swapped dims: the FC's own weights are [G][R][Og][taps]
-            list.push_back({name + "_transpose_w", 4.0 * nw, 0, [=](const RunArgs& a) {
-                                gfc::transpose_weights((const uint16_t*)a.w[widx], (uint16_t*)(a.ws + owt), G, R, Og, kh * kw, a.stream);
-                            }});
-        list.push_back({name, bytes, flops, [=](const RunArgs& a) {
-                            gfc::Params Q = F;
-                            Q.src = src(a);
-                            Q.w = transposed ? (const uint16_t*)(a.ws + owt) : (const uint16_t*)a.w[widx];
-                            Q.dst = const_cast<void*>(dst(a));
-                            Q.addend = addend_is_dst ? (const uint16_t*)dst(a) : nullptr;
-                            gfc::forward(Q, a.stream);
-                        }});
-    };
     const int TV = KH * KW;
-    emit_fc(low->fwd, TV > 1 ? "ufc_fc1_unfold" : "ufc_fc1", G1, C / G1, KH, KW, C / G1, false, w1,
-            [](const RunArgs& a) { return a.x; }, [=](const RunArgs& a) { return (const void*)(a.ws + oz); }, false, 2.0 * act + 2.0 * nw1, fl1);
+    const TakeFn takef = take;
+    const FcOperand in_x{[](const RunArgs& a) { return a.x; }, false};
+    const FcOperand in_dy{[](const RunArgs& a) { return a.dy; }, false};
+    auto ws_at = [](int64_t o) { return [=](const RunArgs& a) { return (const void*)(a.ws + o); }; };
+    emit_fc(low->fwd, dag, takef, TV > 1 ? "ufc_fc1_unfold" : "ufc_fc1", G1, C / G1, KH, KW, C / G1, false, w1, in_x, ws_at(oz), false,
+            2.0 * act + 2.0 * nw1, fl1);
     low->fwd.push_back({"ufc_mid_fwd", 3.0 * act, 0, [=](const RunArgs& a) {
                             ufc::MidParams R = M;
                             R.x = (const uint16_t*)a.x;
@@ -181,23 +131,12 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
                             R.v = (uint16_t*)(a.ws + ov);
                             ufc::mid_forward(R, a.stream);
                         }});
-    emit_fc(low->fwd, "ufc_fc2", G2, C / G2, 1, 1, O2 / G2, false, w2, [=](const RunArgs& a) { return (const void*)(a.ws + ov); },
+    emit_fc(low->fwd, dag, takef, "ufc_fc2", G2, C / G2, 1, 1, O2 / G2, false, w2, FcOperand{ws_at(ov), false},
             [](const RunArgs& a) { return (const void*)a.y; }, false, act + outb + 2.0 * nw2, fl2);
 
     // backward (forward must have run with the same workspace: z and v are read back, and left intact)
-    const int s1 = W1.slices, s2 = W2.slices;
-    low->bwd.push_back({"ufc_fc2_wgrad", act + outb + 4.0 * s2 * nw2, fl2, [=](const RunArgs& a) {
-                            gfc::Params R = W2;
-                            R.src = a.ws + ov;
-                            R.dy = a.dy;
-                            R.partial = (float*)(a.ws + op2);
-                            gfc::wgrad_partial(R, a.stream);
-                        }});
-    low->bwd.push_back({"ufc_fc2_wgrad_reduce", 4.0 * (s2 + 1) * nw2, 0, [=](const RunArgs& a) {
-                            gfc::wgrad_reduce((const float*)(a.ws + op2), (float*)a.dw[w2], s2, nw2, a.stream);
-                        }});
-    emit_fc(low->bwd, "ufc_fc2_dgrad", G2, O2 / G2, 1, 1, C / G2, true, w2, [](const RunArgs& a) { return a.dy; },
-            [=](const RunArgs& a) { return (const void*)(a.ws + odv); }, false, act + outb + 2.0 * nw2, fl2);
+    emit_wgrad(low->bwd, dag, takef, "ufc_fc2_wgrad", G2, C / G2, 1, 1, O2 / G2, w2, FcOperand{ws_at(ov), false}, in_dy, act + outb, fl2);
+    emit_fc(low->bwd, dag, takef, "ufc_fc2_dgrad", G2, O2 / G2, 1, 1, C / G2, true, w2, in_dy, ws_at(odv), false, act + outb + 2.0 * nw2, fl2);
     low->bwd.push_back({"ufc_mid_bwd", (M.bin ? 5.0 : 4.0) * act, 0, [=](const RunArgs& a) {
                             ufc::MidParams R = M;
                             R.x = (const uint16_t*)a.x;
@@ -207,40 +146,11 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
                             R.dx1 = (uint16_t*)a.dx;  // completed by the data gradient of FC1 below
                             ufc::mid_backward(R, a.stream);
                         }});
-    if (TV > 1 && gfctm::supported(dag.N, G1, C / G1, KH, KW, C / G1, dag.H, dag.W)) {
-        gfctm::Params T = gfctm::shape(dag.N, G1, C / G1, KH, KW, C / G1, dag.H, dag.W);
-        gfctm::prepare_wgrad(T);
-        const int ts = gfctm::wgrad_slices(T);
-        const int64_t pk = gfctm::packed_elems(T);
-        const int64_t opt = take((uint64_t)ts * pk * 4);
-        low->bwd.push_back({"ufc_fc1_wgrad_unfold", 2.0 * act + 4.0 * ts * pk, fl1, [=](const RunArgs& a) {
-                                gfctm::Params R = T;
-                                R.src = (const uint16_t*)a.x;
-                                R.dy = (const uint16_t*)(a.ws + odz);
-                                R.partial = (float*)(a.ws + opt);
-                                gfctm::wgrad_partial(R, a.stream);
-                            }});
-        low->bwd.push_back({"ufc_fc1_wgrad_reduce", 4.0 * ts * pk + 4.0 * nw1, 0, [=](const RunArgs& a) {
-                                gfctm::Params R = T;
-                                R.partial = (float*)(a.ws + opt);
-                                gfctm::wgrad_reduce(R, (float*)a.dw[w1], a.stream);
-                            }});
-    } else {
-        low->bwd.push_back({KH * KW > 1 ? "ufc_fc1_wgrad_unfold" : "ufc_fc1_wgrad", 2.0 * act + 4.0 * s1 * nw1, fl1, [=](const RunArgs& a) {
-                                gfc::Params R = W1;
-                                R.src = a.x;
-                                R.dy = a.ws + odz;
-                                R.partial = (float*)(a.ws + op1);
-                                gfc::wgrad_partial(R, a.stream);
-                            }});
-        low->bwd.push_back({"ufc_fc1_wgrad_reduce", 4.0 * (s1 + 1) * nw1, 0, [=](const RunArgs& a) {
-                                gfc::wgrad_reduce((const float*)(a.ws + op1), (float*)a.dw[w1], s1, nw1, a.stream);
-                            }});
-    }
+    emit_wgrad(low->bwd, dag, takef, TV > 1 ? "ufc_fc1_wgrad_unfold" : "ufc_fc1_wgrad", G1, C / G1, KH, KW, C / G1, w1, in_x,
+               FcOperand{ws_at(odz), false}, 2.0 * act, fl1);
     // mid_backward left dx_direct in dx; the data gradient of FC1 (through the Unfold adjoint) adds to it
-    emit_fc(low->bwd, TV > 1 ? "ufc_fc1_dgrad_unfold" : "ufc_fc1_dgrad", G1, C / G1, KH, KW, C / G1, true, w1,
-            [=](const RunArgs& a) { return (const void*)(a.ws + odz); }, [](const RunArgs& a) { return (const void*)a.dx; }, true,
-            3.0 * act + 2.0 * nw1, fl1);
+    emit_fc(low->bwd, dag, takef, TV > 1 ? "ufc_fc1_dgrad_unfold" : "ufc_fc1_dgrad", G1, C / G1, KH, KW, C / G1, true, w1,
+            FcOperand{ws_at(odz), false}, [](const RunArgs& a) { return (const void*)a.dx; }, true, 3.0 * act + 2.0 * nw1, fl1);
     low->ws_bytes = off;
     return low;
 }

@@ -48,6 +48,10 @@ std::unique_ptr<Lowering> lower_sgfc(const Dag& dag, bool bf16);
 // nullptr when the DAG is not of that form.
 std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16);
 
+// FC -> [softmax] -> broadcast-mul onto Unfold(x) -> Fold(sum|avg over taps) -> FC (per-pixel window weights);
+// nullptr when the DAG is not of that form.
+std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16);
+
 // Picks the lowering: fused kernel families where a pattern applies, else per node.
 std::unique_ptr<Lowering> lower(const Dag& dag, bool bf16, bool no_fusion);
 

@@ -162,6 +162,48 @@ def test_mfma_grouped_fc_shapes(harness, oracle, idx):
 def test_config3_involution(harness, oracle, N, H, flags):
     case = wl.config3(N=N, H=H)
     res, r, dy = harness.run_case(case, flags)
+    assert r.info.fused == (1 if flags == 0 else 0)
+    check_against_oracle(oracle, case, res, dy)
+    r.close()
+
+
+DYN_VARIANTS = [
+    # (window, groups of FC1, softmax, fold, groups of FC2, out of FC2, N, C, H, W, unfold first)
+    (3, 1, True, "sum", 1, 24, 2, 24, 9, 11, False),     # ragged 8-pixel tail, odd width
+    (5, 1, True, "avg", 2, 32, 2, 16, 7, 7, True),       # 5x5 window, average over the taps, unfold listed first
+    (3, 3, False, "sum", 1, 12, 3, 12, 6, 10, False),    # no softmax, grouped FC1 (3 groups of 3 taps)
+    (3, 1, True, "avg", 4, 64, 1, 32, 4, 12, False),     # image of four rows
+    (5, 5, False, "sum", 1, 40, 2, 40, 5, 4, True),      # window larger than the image width
+]
+
+
+@pytest.mark.parametrize("idx", range(len(DYN_VARIANTS)))
+def test_fused_dynamic_window_weights_variants(harness, oracle, idx):
+    """The lowering of FC -> [softmax] -> broadcast-mul onto Unfold(x) -> Fold over taps -> FC over its parameter space."""
+    k, g1, soft, fold, g2, o2, N, C, H, W, unfold_first = DYN_VARIANTS[idx]
+    lines, cur = [], 0
+
+    def emit(text):
+        nonlocal cur
+        cur += 1
+        lines.append(f"%{cur} = {text}")
+        return cur
+
+    if unfold_first:
+        u = emit(f"unfold %0 kh={k} kw={k}")
+    a = emit(f"fc %0 groups={g1} out={k * k}")
+    if soft:
+        a = emit(f"softmax %{a} axis=C")
+    if not unfold_first:
+        u = emit(f"unfold %0 kh={k} kw={k}")
+    emit(f"binary %{a} %{u} op=mul")
+    emit(f"fold %{cur} op={fold}")
+    emit(f"fc %{cur} groups={g2} out={o2}")
+    body = "\n".join(lines) + f"\noutput %{cur}\n"
+    wshapes = [(g1, k * k // g1, C // g1), (g2, o2 // g2, C // g2)]
+    case = _mk(body, (N, C, H, W), "bf16", 400 + idx, wshapes, f"dyn{idx}")
+    res, r, dy = harness.run_case(case)
+    assert r.info.fused == 1, "the fused lowering was not selected"
     check_against_oracle(oracle, case, res, dy)
     r.close()
 
@@ -194,6 +236,8 @@ UFC_VARIANTS = [
     (3, 8, "gelu", [(5, 0, 0, 32)], "add", False, 1, 96, 2, 64, 4, 12),           # shift beyond the image
     (3, 1, "gelu", [(0, 1, 4, 8)], "mul", False, 1, 8, 5, 8, 5, 4),                # tiny channel counts
     (3, 8, "expclip lo=-1 hi=1", [(0, 1, 0, 32)], "add", False, 1, 96, 2, 64, 4, 12),  # clip bounds: not fused
+    (3, 3, "relu", [(0, -1, 0, 12)], "mul", False, 3, 48, 2, 24, 8, 16),           # 3 groups of 8 rows: the last merged pair is half empty
+    (5, 5, "abs", [], "add", True, 1, 20, 1, 20, 9, 9),                             # groups of 4 rows: four merged, one left over
 ]
 
 
