@@ -114,3 +114,52 @@ def test_bad_arguments(lib):
     rc = lib.canvas_dag_backward(h, 0x1000, arr, 0x2000, None, arr, 0x3000, 1 << 30, None)
     assert rc == -4
     B.canvas_dag_destroy(h)
+
+
+def _compile_info(blob, shape, dtype=B.CANVAS_BF16, flags=0):
+    h = B.canvas_dag_compile(blob, shape, dtype, flags)
+    info = B.canvas_dag_query(h)
+    names = ([B.canvas_dag_launch_desc(h, 0, i)["name"] for i in range(info.n_launches_fwd)],
+             [B.canvas_dag_launch_desc(h, 1, i)["name"] for i in range(info.n_launches_bwd)])
+    out = (info.fused, int(info.workspace_bytes), names)
+    B.canvas_dag_destroy(h)
+    return out
+
+
+def test_lowering_selection(lib):
+    """Which lowering compile picks (host logic only): the three fused families on their patterns, per node elsewhere."""
+    H = wl.HEADER
+    # config 2: shift -> grouped FC -> relu -> + x
+    fused, ws, (fwd, bwd) = _compile_info(wl.blob_shift_residual(64), (64, 64, 56, 56))
+    assert fused == 1 and fwd == ["sgfc_fwd"] and bwd == ["sgfc_bwd", "sgfc_dw_reduce"] and ws < (1 << 20)
+    # ... but not in fp32, not with fusion off, not when H*W is no multiple of 8
+    assert _compile_info(wl.blob_shift_residual(64), (2, 64, 56, 56), B.CANVAS_F32)[0] == 0
+    assert _compile_info(wl.blob_shift_residual(64), (2, 64, 56, 56), B.CANVAS_BF16, B.CANVAS_OPT_NO_FUSION)[0] == 0
+    assert _compile_info(wl.blob_shift_residual(64), (2, 64, 13, 13))[0] == 0
+    # config 4: unfold -> FC -> gelu -> shift -> * x -> fold(1 tap) -> FC; windowed contractions on the tap-major kernels
+    fused, ws, (fwd, bwd) = _compile_info(wl.blob_sampled(64), (128, 64, 56, 56))
+    assert fused == 1 and "ufc_fc1_unfold_pack_w" in fwd and "ufc_mid_fwd" in fwd and fwd[-1] == "ufc_fc2"
+    assert bwd[-1] == "ufc_fc1_dgrad_unfold" and "ufc_mid_bwd" in bwd and "ufc_fc1_wgrad_unfold_reduce" in bwd
+    assert 4 * 128 * 64 * 56 * 56 * 2 <= ws < 5 * 128 * 64 * 56 * 56 * 2   # z, v, dv, dz + partials and packed weights
+    # a unary whose decisions bf16 rounding could change keeps fp32 intermediates
+    clip = H + ("%1 = unfold %0 kh=3 kw=3\n%2 = fc %1 groups=8 out=64\n%3 = unary %2 op=expclip lo=-1 hi=1\n"
+                "%4 = binary %0 %3 op=mul\n%5 = fc %4 groups=1 out=64\noutput %5\n")
+    assert _compile_info(clip, (2, 64, 8, 8))[0] == 0
+    assert _compile_info(clip.replace("expclip lo=-1 hi=1", "relu"), (2, 64, 8, 8))[0] == 1
+    # config 3: per-pixel window weights
+    fused, ws, (fwd, bwd) = _compile_info(wl.blob_involution(128, 3), (32, 128, 28, 28))
+    assert fused == 1 and "dyn_apply" in fwd and "dyn_softmax" in fwd and "dyn_apply_da" in bwd and "dyn_apply_dx" in bwd
+    # 9 softmax channels onto 9 unfolded channels would be the per-channel broadcast, not the tap pairing
+    assert _compile_info(wl.blob_involution(9, 3).replace("out=9\noutput", "out=9\noutput"), (2, 9, 8, 8))[0] == 0
+    # a 7x7 window is outside the fused kernels
+    assert _compile_info(wl.blob_involution(128, 7), (2, 128, 8, 8))[0] == 0
+
+
+def test_workspace_grows_with_batch_only_where_it_should(lib):
+    """The config-2 lowering keeps only weight-gradient partials; the others keep activations."""
+    small = _compile_info(wl.blob_shift_residual(64), (8, 64, 56, 56))[1]
+    big = _compile_info(wl.blob_shift_residual(64), (64, 64, 56, 56))[1]
+    assert big <= 8 * small and big < (1 << 20)
+    a = _compile_info(wl.blob_sampled(64), (2, 64, 16, 16))[1]
+    b = _compile_info(wl.blob_sampled(64), (4, 64, 16, 16))[1]
+    assert 1.5 * a < b < 2.5 * a
