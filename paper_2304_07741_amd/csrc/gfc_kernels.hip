@@ -535,8 +535,11 @@ void prepare_forward(Params& P) {
 }
 
 void prepare_wgrad(Params& P) {
-    P.otiles = (P.Og + 31) / 32;
-    P.ktiles = (P.K + 31) / 32;
+    // bf16 operands without a window and at least 64 x 64 weights per group: 64 x 64 tiles (each loaded
+    // register feeds four MFMAs instead of two); set src_f32 / dy_f32 before this call
+    P.wtile = (!P.src_f32 && !P.dy_f32 && P.TV == 1 && P.Og >= 64 && P.K >= 64) ? 4 : 2;
+    P.otiles = (P.Og + 16 * P.wtile - 1) / (16 * P.wtile);
+    P.ktiles = (P.K + 16 * P.wtile - 1) / (16 * P.wtile);
     P.chunks32 = (P.P + 31) / 32;
     P.magicC32 = magic_u32(P.chunks32);
     const int64_t wnumel = (int64_t)P.G * P.Og * P.K;
@@ -574,6 +577,10 @@ void wgrad_partial(const Params& P, hipStream_t s) {
     const bool taps = P.TV > 1;
 #define GFC_WG(SF, DF) \
     do { if (taps) CANVAS_LAUNCH((k_wgrad<2, 2, SF, DF, true>), grid, block, 0, s, P); else CANVAS_LAUNCH((k_wgrad<2, 2, SF, DF, false>), grid, block, 0, s, P); } while (0)
+    if (P.wtile == 4) {
+        CANVAS_LAUNCH((k_wgrad<4, 4, false, false, false>), grid, block, 0, s, P);
+        return;
+    }
     if (P.src_f32) { if (P.dy_f32) GFC_WG(true, true); else GFC_WG(true, false); }
     else { if (P.dy_f32) GFC_WG(false, true); else GFC_WG(false, false); }
 #undef GFC_WG

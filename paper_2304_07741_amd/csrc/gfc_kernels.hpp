@@ -24,6 +24,7 @@ struct Params {
     int upi = 0;                  // forward: 8-pixel units per image, ceil(P / 8)
     int otiles = 0, ktiles = 0;   // tiles of 16*MO output channels / 16*NK contraction rows
     int slices = 0, chunks32 = 0, per_slice = 0;  // weight gradient: pixel chunks of 32 split over slices
+    int wtile = 2;                // weight gradient: the wavefront's dW tile is (16*wtile) x (16*wtile)
     uint32_t magicW = 0, magicTV = 0, magicKW = 0, magicC32 = 0, magicUpi = 0;
 };
 

@@ -472,18 +472,27 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
         }
     };
 
-    // two images per trip: the loads of the next image are in flight while this one is multiplied
-    Step<MO, KH, KW> st[2];
-    issue(i0, i0 < i1, st[0]);
-    for (int n = i0; n < i1; n += 2) {
-        issue(n + 1, n + 1 < i1, st[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(st[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        issue(n + 2, n + 2 < i1, st[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        if (n + 1 < i1) consume(st[1]);
-        __builtin_amdgcn_sched_barrier(0);
+    if constexpr (KH <= 3) {
+        // two images per trip: the loads of the next image are in flight while this one is multiplied
+        Step<MO, KH, KW> st[2];
+        issue(i0, i0 < i1, st[0]);
+        for (int n = i0; n < i1; n += 2) {
+            issue(n + 1, n + 1 < i1, st[1]);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(st[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            issue(n + 2, n + 2 < i1, st[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (n + 1 < i1) consume(st[1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+        // 5x5: 100 accumulator registers; one image in flight keeps the kernel under 256 registers
+        Step<MO, KH, KW> st;
+        for (int n = i0; n < i1; n++) {
+            issue(n, true, st);
+            consume(st);
+        }
     }
 
     // sum of the workgroup's four wavefronts in a fixed order: (w0 + w2) + (w1 + w3), through LDS
