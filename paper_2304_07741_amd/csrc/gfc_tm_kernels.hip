@@ -594,7 +594,8 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
 
 // One tile per wavefront (KS = 1) or per KS wavefronts.  (Measured on MI355X: persistent wavefronts that
 // walk over several tiles and issue the next tile's first loads early, with or without cache-line
-// touches ahead, were not faster than letting the hardware scheduler balance one-tile workgroups.)
+// touches ahead, were not faster than letting the hardware scheduler balance one-tile workgroups; nor was
+// a 1x1 variant that keeps three groups of loads in flight instead of one.)
 template <int MO, int KH, int KW, bool DST_F32>
 void launch_fwd_k(const Params& P, hipStream_t s) {
     const int tiles = (P.N * P.upi + 15) / 16;
