@@ -25,9 +25,10 @@
  *     canvas-dag 1
  *     %1 = unfold %0 kh=3 kw=3
  *     %2 = fc %1 groups=8 out=64
- *     %3 = unary %2 op=gelu            (relu | abs | gelu | expclip lo=.. hi=..)
+ *     %3 = unary %2 op=gelu            (relu | abs | gelu | sin | expclip lo=.. hi=..)
  *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
- *     %5 = binary %0 %4 op=mul         (first operand LHS, second RHS; add | mul)
+ *     %5 = binary %0 %4 op=mul         (first operand LHS, second RHS; add | sub | mul | min | max;
+ *                                       sub is tile(LHS) - RHS; a tie of min / max sends the gradient to the LHS)
  *     %6 = fold %5 op=avg              (sum | avg | max)
  *     %7 = softmax %6 axis=C           (C | T)
  *     output %7
@@ -45,8 +46,8 @@
 #define MAX_NODES 64
 
 enum { OP_INPUT = 0, OP_UNFOLD, OP_SHIFT, OP_FC, OP_UNARY, OP_BINARY, OP_SOFTMAX, OP_FOLD };
-enum { UN_RELU = 0, UN_ABS, UN_GELU, UN_EXPCLIP };
-enum { BIN_ADD = 0, BIN_MUL };
+enum { UN_RELU = 0, UN_ABS, UN_GELU, UN_EXPCLIP, UN_SIN };
+enum { BIN_ADD = 0, BIN_MUL, BIN_SUB, BIN_MIN, BIN_MAX };
 enum { AXIS_C = 0, AXIS_T };
 enum { FOLD_SUM = 0, FOLD_AVG, FOLD_MAX };
 
@@ -231,6 +232,7 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 if (!strcmp(k2, "relu")) nd->kind = UN_RELU;
                 else if (!strcmp(k2, "abs")) nd->kind = UN_ABS;
                 else if (!strcmp(k2, "gelu")) nd->kind = UN_GELU;
+                else if (!strcmp(k2, "sin")) nd->kind = UN_SIN;
                 else if (!strcmp(k2, "expclip")) {
                     nd->kind = UN_EXPCLIP;
                     if (attr_dbl(tok, ntok, "lo", &nd->lo) != 1 || attr_dbl(tok, ntok, "hi", &nd->hi) != 1 || !(nd->lo < nd->hi)) {
@@ -250,6 +252,9 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 }
                 if (!strcmp(k2, "add")) nd->kind = BIN_ADD;
                 else if (!strcmp(k2, "mul")) nd->kind = BIN_MUL;
+                else if (!strcmp(k2, "sub")) nd->kind = BIN_SUB;
+                else if (!strcmp(k2, "min")) nd->kind = BIN_MIN;
+                else if (!strcmp(k2, "max")) nd->kind = BIN_MAX;
                 else { set_err(err, errlen, "unknown binary op", lineno); goto done; }
                 B = &d->node[nd->b];
                 if (!broadcast_legal(A->C, A->T, B->C, B->T)) {
@@ -368,6 +373,7 @@ static void fwd_unary(const Dag *d, const Node *nd, int k, const double *in, dou
         case UN_ABS: y = fabs(x); break;
         case UN_GELU: y = x * gelu_cdf(x); break;
         case UN_EXPCLIP: y = exp(x < nd->lo ? nd->lo : (x > nd->hi ? nd->hi : x)); break;
+        case UN_SIN: y = sin(x); break;
         }
         out[j] = y;
     }
@@ -382,7 +388,17 @@ static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
             double *orow = out + ((size_t)c * nd->T + t) * P;
             broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             lrow = lhs + ((size_t)cl * L->T + tl) * P;
-            for (p = 0; p < P; p++) orow[p] = nd->kind == BIN_ADD ? lrow[p] + rrow[p] : lrow[p] * rrow[p];
+            for (p = 0; p < P; p++) {
+                double a = lrow[p], b = rrow[p], y = 0.0;
+                switch (nd->kind) {
+                case BIN_ADD: y = a + b; break;
+                case BIN_MUL: y = a * b; break;
+                case BIN_SUB: y = a - b; break;
+                case BIN_MIN: y = a <= b ? a : b; break;
+                case BIN_MAX: y = a >= b ? a : b; break;
+                }
+                orow[p] = y;
+            }
         }
 }
 
@@ -495,6 +511,7 @@ static void bwd_unary(const Dag *d, const Node *nd, int k, const double *in, con
         case UN_ABS: dv = x > 0.0 ? 1.0 : (x < 0.0 ? -1.0 : 0.0); break;
         case UN_GELU: dv = gelu_cdf(x) + x * gelu_pdf(x); break;
         case UN_EXPCLIP: dv = (x > nd->lo && x < nd->hi) ? out[j] : 0.0; break;
+        case UN_SIN: dv = cos(x); break;
         }
         gin[j] += gout[j] * dv;
     }
@@ -509,12 +526,13 @@ static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
             broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             lo = ((size_t)cl * L->T + tl) * P;
             for (p = 0; p < P; p++) {
-                if (nd->kind == BIN_ADD) {
-                    glhs[lo + p] += gout[ro + p];
-                    grhs[ro + p] += gout[ro + p];
-                } else {
-                    glhs[lo + p] += gout[ro + p] * rhs[ro + p];
-                    grhs[ro + p] += gout[ro + p] * lhs[lo + p];
+                double g = gout[ro + p], a = lhs[lo + p], b = rhs[ro + p];
+                switch (nd->kind) {
+                case BIN_ADD: glhs[lo + p] += g; grhs[ro + p] += g; break;
+                case BIN_MUL: glhs[lo + p] += g * b; grhs[ro + p] += g * a; break;
+                case BIN_SUB: glhs[lo + p] += g; grhs[ro + p] -= g; break;
+                case BIN_MIN: if (a <= b) glhs[lo + p] += g; else grhs[ro + p] += g; break;
+                case BIN_MAX: if (a >= b) glhs[lo + p] += g; else grhs[ro + p] += g; break;
                 }
             }
         }

@@ -150,6 +150,10 @@ FD_BODIES = [
     ("%1 = unfold %0 kh=3 kw=3\n%2 = fc %1 groups=2 out=4\n%3 = unary %2 op=gelu\n%4 = shift %3 dh=0 dw=1 c0=2 c1=4\n"
      "%5 = binary %0 %4 op=mul\n%6 = fold %5 op=avg\n%7 = fc %6 groups=1 out=4\noutput %7\n", [(2, 2, 18), (1, 4, 4)]),
     ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=abs\n%3 = binary %0 %2 op=mul\n%4 = softmax %3 axis=T\noutput %4\n", []),
+    ("%1 = unary %0 op=sin\noutput %1\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=sin\n%3 = binary %0 %2 op=sub\n%4 = fold %3 op=sum\noutput %4\n", []),
+    ("%1 = shift %0 dh=1 dw=0\n%2 = unary %1 op=gelu\n%3 = binary %2 %0 op=max\noutput %3\n", []),
+    ("%1 = unfold %0 kh=3 kw=1\n%2 = fc %0 groups=1 out=2\n%3 = binary %2 %1 op=min\n%4 = fold %3 op=avg\noutput %4\n", [(1, 2, 4)]),
 ]
 
 
@@ -183,6 +187,73 @@ def test_unary_closed_forms(oracle):
     np.testing.assert_allclose(r["dx"].ravel(), np.where(inside, np.exp(v), 0.0), atol=1e-15)
     # the boundary itself has zero gradient (open interval)
     assert r["dx"].ravel()[1] == 0.0
+
+
+def test_sin_closed_form(oracle):
+    x = np.array([-math.pi, -0.5 * math.pi, -0.3, 0.0, 0.3, 0.5 * math.pi, 2.0, 9.0]).reshape(1, 8, 1, 1)
+    r = run1(oracle, "%1 = unary %0 op=sin\noutput %1\n", x, (), np.ones_like(x))
+    np.testing.assert_allclose(r["y"].ravel(), np.sin(x.ravel()), atol=1e-15)
+    np.testing.assert_allclose(r["dx"].ravel(), np.cos(x.ravel()), atol=1e-15)
+    assert r["y"].ravel()[3] == 0.0 and r["dx"].ravel()[3] == 1.0
+    # sin(x)^2 + (d/dx sin x)^2 = 1
+    np.testing.assert_allclose(r["y"] ** 2 + r["dx"] ** 2, 1.0, atol=1e-15)
+
+
+# ------------------------------------------------- blends other than add/mul
+
+def test_sub_min_max_definitions_and_operand_order(oracle):
+    """out = op(tile(LHS), RHS): sub is LHS - RHS; min + max = LHS + RHS; max - min = |LHS - RHS|."""
+    rng = np.random.default_rng(30)
+    x = rng.standard_normal((2, 3, 4, 5))
+    body = "%1 = shift %0 dh=0 dw=1\n%2 = binary %0 %1 op={op}\noutput %2\n"
+    a = x
+    b = np.zeros_like(x)
+    b[..., :-1] = x[..., 1:]
+    got = {op: run1(oracle, body.format(op=op), x)["y"] for op in ("sub", "min", "max", "add")}
+    np.testing.assert_array_equal(got["sub"], a - b)
+    np.testing.assert_array_equal(got["min"], np.minimum(a, b))
+    np.testing.assert_array_equal(got["max"], np.maximum(a, b))
+    np.testing.assert_array_equal(got["min"] + got["max"], got["add"])
+    np.testing.assert_array_equal(got["max"] - got["min"], np.abs(got["sub"]))
+    # swapping the operands negates sub and leaves min / max alone
+    swapped = "%1 = shift %0 dh=0 dw=1\n%2 = binary %1 %0 op={op}\noutput %2\n"
+    np.testing.assert_array_equal(run1(oracle, swapped.format(op="sub"), x)["y"], b - a)
+    np.testing.assert_array_equal(run1(oracle, swapped.format(op="max"), x)["y"], got["max"])
+
+
+def test_sub_min_max_gradients(oracle):
+    """sub: +g to the LHS, -g to the RHS.  min / max: all of g to the selected side; a tie goes to the LHS."""
+    # two weight-free routes from x: LHS = relu(x) (gradient 1 where x > 0), RHS = |x| (gradient sign x)
+    x = np.array([-2.0, -0.5, 0.0, 0.5, 3.0]).reshape(1, 5, 1, 1)
+    g = np.array([1.0, 2.0, 3.0, 4.0, 5.0]).reshape(1, 5, 1, 1)
+    body = "%1 = unary %0 op=relu\n%2 = unary %0 op=abs\n%3 = binary %1 %2 op={op}\noutput %3\n"
+    v = x.ravel()
+    relu_g, abs_g = (v > 0).astype(float), np.sign(v)
+    r = run1(oracle, body.format(op="sub"), x, (), g)
+    np.testing.assert_array_equal(r["y"].ravel(), np.maximum(v, 0) - np.abs(v))
+    np.testing.assert_array_equal(r["dx"].ravel(), g.ravel() * (relu_g - abs_g))
+    # relu(x) <= |x| everywhere, equal for x >= 0: min picks the LHS on ties, max picks the LHS only on ties
+    r = run1(oracle, body.format(op="min"), x, (), g)
+    np.testing.assert_array_equal(r["y"].ravel(), np.maximum(v, 0))
+    np.testing.assert_array_equal(r["dx"].ravel(), g.ravel() * relu_g)
+    r = run1(oracle, body.format(op="max"), x, (), g)
+    np.testing.assert_array_equal(r["y"].ravel(), np.abs(v))
+    np.testing.assert_array_equal(r["dx"].ravel(), g.ravel() * np.where(v >= 0, relu_g, abs_g))
+
+
+def test_min_max_broadcast_sums_over_replicas(oracle):
+    """LHS [C,1] against RHS [C,9]: the LHS gradient is the sum over the taps that selected it."""
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal((1, 2, 4, 4))
+    g = rng.standard_normal((1, 2, 9, 4, 4))
+    r = run1(oracle, "%1 = unfold %0 kh=3 kw=3\n%2 = binary %0 %1 op=max\noutput %2\n", x, (), g)
+    u = run1(oracle, "%1 = unfold %0 kh=3 kw=3\noutput %1\n", x)["y"]
+    a = np.broadcast_to(x[:, :, None], u.shape)
+    np.testing.assert_array_equal(r["y"], np.maximum(a, u))
+    lhs_wins = a >= u
+    # route through the unfold adjoint for the RHS part: reuse the oracle's own (separately pinned) unfold backward
+    rhs_part = run1(oracle, "%1 = unfold %0 kh=3 kw=3\noutput %1\n", x, (), np.where(lhs_wins, 0.0, g))["dx"]
+    np.testing.assert_allclose(r["dx"], np.where(lhs_wins, g, 0.0).sum(axis=2) + rhs_part, atol=1e-14)
 
 
 # ---------------------------------------------------------------- softmax
