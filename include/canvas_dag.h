@@ -14,9 +14,9 @@
  *     canvas-dag 1
  *     %1 = unfold %0 kh=3 kw=3
  *     %2 = fc %1 groups=8 out=64
- *     %3 = unary %2 op=gelu            relu | abs | gelu | expclip lo=<f> hi=<f>
+ *     %3 = unary %2 op=gelu            relu | abs | gelu | sin | expclip lo=<f> hi=<f>
  *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
- *     %5 = binary %0 %4 op=mul         first operand LHS, second RHS; add | mul
+ *     %5 = binary %0 %4 op=mul         first operand LHS, second RHS; add | sub | mul | min | max
  *     %6 = fold %5 op=avg              sum | avg | max
  *     %7 = softmax %6 axis=C           C | T
  *     output %7
@@ -31,17 +31,18 @@
  *   fc       y(n,g*Og+o,h,w) = sum_{c'<C/G, t<T} W[g][o][c'*T+t] * x(n,g*(C/G)+c',t,h,w);
  *            contracts channels of a group and all taps, keeps groups apart, no
  *            bias (Section 5, Fully-connected; group rearrangement g*GROUP_SIZE+c).
- *   unary    relu, abs, gelu (erf form), exp(clamp(x,lo,hi)) (Section 5, element-wise).
+ *   unary    relu, abs, gelu (erf form), sin, exp(clamp(x,lo,hi)) (Section 5, element-wise).
  *   binary   out = op(tile(LHS), RHS), shape of RHS (Section 5, Broadcast): with
  *            dims [C,T] of both sides, equal C is a common prefix (lhs c = c,
  *            lhs t = t mod T_L); otherwise the LHS is replicated along the
  *            flattened (c*T_R + t) index modulo C_L*T_L.  The LHS size must
- *            divide the RHS size.
+ *            divide the RHS size.  op: add, sub (tile(LHS) - RHS), mul, min, max.
  *   softmax  along C (per n,t,h,w) or along T (per n,c,h,w) (Section 5, Softmax).
  *   fold     sum, avg or max over T; T disappears (Section 5, Folding).  Max
  *            sends its gradient to the first maximal tap.
  *   backward exact vector-Jacobian products of the above; relu'(0) = 0,
- *            sign(0) = 0, expclip has zero gradient outside the open interval.
+ *            sign(0) = 0, expclip has zero gradient outside the open interval; a
+ *            tie of binary min / max sends the gradient to the LHS.
  *
  * Threading: a canvas_dag handle may be used by one thread at a time.  All
  * functions return CANVAS_OK (0) or a negative canvas_status; they never throw

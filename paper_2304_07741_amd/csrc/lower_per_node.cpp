@@ -308,18 +308,18 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             const Node B = dag.nodes[nd.b];
             // LHS first, then RHS (which may be the same tensor and then accumulates)
             L.name = "node_binary_bwd_lhs";
-            L.bytes = 4.0 * (dag.numel(nd.a) * (1 + acc) + dag.numel(k) * (nd.kind == kMul ? 2 : 1));
+            L.bytes = 4.0 * (dag.numel(nd.a) * (1 + acc) + dag.numel(k) * (nd.kind == kAdd || nd.kind == kSub ? 1 : 2));
             L.run = [=](const RunArgs& a) {
-                ref::binary_bwd_lhs(val(a, nd.b), grad(a, k), grad(a, nd.a), N, A.C, A.T, B.C, B.T, P, nd.kind, acc, a.stream);
+                ref::binary_bwd_lhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.a), N, A.C, A.T, B.C, B.T, P, nd.kind, acc, a.stream);
             };
             low->bwd.push_back(std::move(L));
             written[nd.a] = true;
             const int acc_r = written[nd.b] ? 1 : 0;
             Launch R;
             R.name = "node_binary_bwd_rhs";
-            R.bytes = 4.0 * (dag.numel(nd.b) * (1 + acc_r) + dag.numel(k) + (nd.kind == kMul ? dag.numel(nd.a) : 0));
+            R.bytes = 4.0 * (dag.numel(nd.b) * (1 + acc_r) + dag.numel(k) + (nd.kind == kAdd || nd.kind == kSub ? 0 : dag.numel(nd.a)));
             R.run = [=](const RunArgs& a) {
-                ref::binary_bwd_rhs(val(a, nd.a), grad(a, k), grad(a, nd.b), N, A.C, A.T, B.C, B.T, P, nd.kind, acc_r, a.stream);
+                ref::binary_bwd_rhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.b), N, A.C, A.T, B.C, B.T, P, nd.kind, acc_r, a.stream);
             };
             low->bwd.push_back(std::move(R));
             written[nd.b] = true;

@@ -37,7 +37,7 @@ std::unique_ptr<Lowering> lower_sgfc(const Dag& dag, bool bf16) {
     sgfc::Params P;
     if (k < n && dag.nodes[k].op == Op::Unary) {
         const Node& u = dag.nodes[k];
-        if (u.a != prev) return nullptr;
+        if (u.a != prev || u.kind > kExpClip) return nullptr;  // the kernels are instantiated for relu, abs, gelu, expclip
         P.act = u.kind;
         P.ulo = u.lo;
         P.uhi = u.hi;

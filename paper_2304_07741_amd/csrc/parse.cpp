@@ -149,6 +149,7 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             if (it->second == "relu") nd.kind = kRelu;
             else if (it->second == "abs") nd.kind = kAbs;
             else if (it->second == "gelu") nd.kind = kGelu;
+            else if (it->second == "sin") nd.kind = kSin;
             else if (it->second == "expclip") {
                 nd.kind = kExpClip;
                 if (!get_float(l, "lo", nd.lo) || !get_float(l, "hi", nd.hi)) return fail(err, lineno, "expclip needs lo= hi=", kInvalidBlob);
@@ -164,6 +165,9 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             if (it == l.attr.end()) return fail(err, lineno, "binary needs op=", kInvalidBlob);
             if (it->second == "add") nd.kind = kAdd;
             else if (it->second == "mul") nd.kind = kMul;
+            else if (it->second == "sub") nd.kind = kSub;
+            else if (it->second == "min") nd.kind = kBinMin;
+            else if (it->second == "max") nd.kind = kBinMax;
             else return fail(err, lineno, "unknown binary op '" + it->second + "'", kUnknownOp);
             const Node& B = dag.nodes[nd.b];
             bool legal = (A.C == B.C) ? (B.T % A.T == 0) : (((int64_t)B.C * B.T) % ((int64_t)A.C * A.T) == 0);

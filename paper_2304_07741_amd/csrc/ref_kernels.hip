@@ -199,11 +199,11 @@ __global__ void k_binary_fwd(const float* __restrict__ lhs, const float* __restr
     int cl, tl;
     bsrc(CL, TL, TR, c, t, CL == CR, cl, tl);
     float a = lhs[((n * CL + cl) * TL + tl) * P + p], b = rhs[i];
-    out[i] = kind == 0 ? a + b : a * b;
+    out[i] = binary_apply(kind, a, b);
 }
 
-__global__ void k_binary_bwd_rhs(const float* __restrict__ lhs, const float* __restrict__ gout, float* __restrict__ grhs,
-                                 int64_t total, int CL, int TL, int CR, int TR, int P, int kind, int acc) {
+__global__ void k_binary_bwd_rhs(const float* __restrict__ lhs, const float* __restrict__ rhs, const float* __restrict__ gout,
+                                 float* __restrict__ grhs, int64_t total, int CL, int TL, int CR, int TR, int P, int kind, int acc) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
     float g = gout[i];
@@ -216,14 +216,14 @@ __global__ void k_binary_bwd_rhs(const float* __restrict__ lhs, const float* __r
         int64_t n = r / CR;
         int cl, tl;
         bsrc(CL, TL, TR, c, t, CL == CR, cl, tl);
-        g *= lhs[((n * CL + cl) * TL + tl) * P + p];
+        g *= binary_grad_rhs(kind, lhs[((n * CL + cl) * TL + tl) * P + p], rhs[i]);
     }
     grhs[i] = acc ? grhs[i] + g : g;
 }
 
 // One thread per LHS element sums over the RHS elements it was replicated onto.
-__global__ void k_binary_bwd_lhs(const float* __restrict__ rhs, const float* __restrict__ gout, float* __restrict__ glhs,
-                                 int64_t total, int CL, int TL, int CR, int TR, int P, int kind, int acc) {
+__global__ void k_binary_bwd_lhs(const float* __restrict__ lhs, const float* __restrict__ rhs, const float* __restrict__ gout,
+                                 float* __restrict__ glhs, int64_t total, int CL, int TL, int CR, int TR, int P, int kind, int acc) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
     int p = (int)(i % P);
@@ -232,17 +232,18 @@ __global__ void k_binary_bwd_lhs(const float* __restrict__ rhs, const float* __r
     r /= TL;
     int cl = (int)(r % CL);
     int64_t n = r / CL;
+    const float a = lhs[i];
     float s = 0.f;
     if (CL == CR) {
         for (int t = tl; t < TR; t += TL) {
             int64_t j = ((n * CR + cl) * TR + t) * P + p;
-            s += kind == 0 ? gout[j] : gout[j] * rhs[j];
+            s += kind == 0 ? gout[j] : gout[j] * binary_grad_lhs(kind, a, rhs[j]);
         }
     } else {
         long long L = (long long)CL * TL, R = (long long)CR * TR;
         for (long long f = (long long)cl * TL + tl; f < R; f += L) {
             int64_t j = (n * R + f) * P + p;
-            s += kind == 0 ? gout[j] : gout[j] * rhs[j];
+            s += kind == 0 ? gout[j] : gout[j] * binary_grad_lhs(kind, a, rhs[j]);
         }
     }
     glhs[i] = acc ? glhs[i] + s : s;
@@ -396,15 +397,15 @@ void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int C
     int64_t total = N * CR * TR * P;
     LAUNCH(k_binary_fwd, total, lhs, rhs, out, total, CL, TL, CR, TR, P, kind);
 }
-void binary_bwd_rhs(const float* lhs, const float* gout, float* grhs, int64_t N, int CL, int TL, int CR, int TR, int P,
+void binary_bwd_rhs(const float* lhs, const float* rhs, const float* gout, float* grhs, int64_t N, int CL, int TL, int CR, int TR, int P,
                     int kind, int acc, hipStream_t s) {
     int64_t total = N * CR * TR * P;
-    LAUNCH(k_binary_bwd_rhs, total, lhs, gout, grhs, total, CL, TL, CR, TR, P, kind, acc);
+    LAUNCH(k_binary_bwd_rhs, total, lhs, rhs, gout, grhs, total, CL, TL, CR, TR, P, kind, acc);
 }
-void binary_bwd_lhs(const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
+void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
                     int kind, int acc, hipStream_t s) {
     int64_t total = N * CL * TL * P;
-    LAUNCH(k_binary_bwd_lhs, total, rhs, gout, glhs, total, CL, TL, CR, TR, P, kind, acc);
+    LAUNCH(k_binary_bwd_lhs, total, lhs, rhs, gout, glhs, total, CL, TL, CR, TR, P, kind, acc);
 }
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s) {
     int64_t total = N * (axis_c ? T : C) * P;

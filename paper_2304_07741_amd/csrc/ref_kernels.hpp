@@ -23,9 +23,9 @@ void unary_fwd(const float* in, float* out, int64_t n, int kind, float lo, float
 void unary_bwd(const float* in, const float* gout, float* gin, int64_t n, int kind, float lo, float hi, int acc, hipStream_t s);
 void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int kind,
                 hipStream_t s);
-void binary_bwd_rhs(const float* lhs, const float* gout, float* grhs, int64_t N, int CL, int TL, int CR, int TR, int P,
+void binary_bwd_rhs(const float* lhs, const float* rhs, const float* gout, float* grhs, int64_t N, int CL, int TL, int CR, int TR, int P,
                     int kind, int acc, hipStream_t s);
-void binary_bwd_lhs(const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
+void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
                     int kind, int acc, hipStream_t s);
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s);
 void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C, int T, int P, int axis_c, int acc,

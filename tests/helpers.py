@@ -53,7 +53,7 @@ def assert_close(got, ref, tol, what, kinks=False, floor=1e-30):
 
 
 def has_kinks(blob):
-    return any(k in blob for k in ("relu", "abs", "op=max", "expclip"))
+    return any(k in blob for k in ("relu", "abs", "op=max", "op=min", "expclip"))
 
 
 def check_against_oracle(oracle, case, res, dy, what=None):

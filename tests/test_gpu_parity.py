@@ -55,6 +55,11 @@ PRIMS = [
     ("%1 = binary %0 %0 op=mul\n%2 = binary %1 %0 op=add\noutput %2\n", []),
     ("output %0\n", []),
     ("%1 = unary %0 op=relu\n%2 = fc %0 groups=1 out=12\noutput %1\n", [(1, 12, 12)]),  # dead fc: zero dW
+    ("%1 = unary %0 op=sin\noutput %1\n", []),
+    ("%1 = shift %0 dh=1 dw=0\n%2 = binary %0 %1 op=sub\noutput %2\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = binary %0 %1 op=max\noutput %2\n", []),
+    ("%1 = unfold %0 kh=3 kw=1\n%2 = fc %0 groups=3 out=6\n%3 = binary %2 %1 op=min\n%4 = fold %3 op=avg\noutput %4\n", [(3, 2, 4)]),
+    ("%1 = unary %0 op=gelu\n%2 = binary %1 %0 op=min\n%3 = binary %0 %2 op=sub\noutput %3\n", []),
 ]
 
 
@@ -238,6 +243,7 @@ UFC_VARIANTS = [
     (3, 8, "expclip lo=-1 hi=1", [(0, 1, 0, 32)], "add", False, 1, 96, 2, 64, 4, 12),  # clip bounds: not fused
     (3, 3, "relu", [(0, -1, 0, 12)], "mul", False, 3, 48, 2, 24, 8, 16),           # 3 groups of 8 rows: the last merged pair is half empty
     (5, 5, "abs", [], "add", True, 1, 20, 1, 20, 9, 9),                             # groups of 4 rows: four merged, one left over
+    (3, 2, "sin", [(0, 1, 0, 8)], "mul", False, 2, 16, 2, 16, 8, 8),                # a smooth unary outside the first four
 ]
 
 

@@ -151,6 +151,10 @@ def test_lowering_selection(lib):
     assert fused == 1 and "dyn_apply" in fwd and "dyn_softmax" in fwd and "dyn_apply_da" in bwd and "dyn_apply_dx" in bwd
     # 9 softmax channels onto 9 unfolded channels would be the per-channel broadcast, not the tap pairing
     assert _compile_info(wl.blob_involution(9, 3).replace("out=9\noutput", "out=9\noutput"), (2, 9, 8, 8))[0] == 0
+    # the config-2 kernels are instantiated for relu / abs / gelu / expclip only
+    assert _compile_info(wl.blob_shift_residual(64).replace("relu", "sin"), (2, 64, 8, 8))[0] == 0
+    # blends other than add / mul with the input keep the per-node lowering
+    assert _compile_info(clip.replace("expclip lo=-1 hi=1", "relu").replace("op=mul", "op=max"), (2, 64, 8, 8))[0] == 0
     # a 7x7 window is outside the fused kernels
     assert _compile_info(wl.blob_involution(128, 7), (2, 128, 8, 8))[0] == 0
 
