@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void k_bwd_dx(Params P) {
     store8_bf16(rdx, P.dx, nc * P.P + p, acc, min(8, P.P - p));
 }
 
-// block = 16 units x 16 channel slices (lane % 16 = slice: channels slice, slice + 16, ...)
+// block = 16 units x 16 channel slices (lane % 16 = slice: channels slice, slice + 16, ...) of one window row
 template <int KH, int KW>
 __global__ __launch_bounds__(256) void k_bwd_da(Params P) {
     constexpr int HH = KH / 2, HW = KW / 2, TV = KH * KW;
@@ -165,8 +165,8 @@ __global__ __launch_bounds__(256) void k_bwd_da(Params P) {
     const rsrc_t rdu = make_rsrc(P.du, xtotal * 2), rx = make_rsrc(P.x, xtotal * 2);
     const Pix g = pixels(P, p);
     const int nvalid = min(8, P.P - p);
-#pragma unroll 1
-    for (int kh = 0; kh < KH; kh++) {
+    {
+        const int kh = blockIdx.y;  // one window row per block: KH times the parallelism, the rows are independent
         float acc[KW][8];
 #pragma unroll
         for (int kw = 0; kw < KW; kw++)
@@ -246,7 +246,7 @@ void backward_dx(const Params& P, hipStream_t s) {
 void backward_da(const Params& P, hipStream_t s) {
     const long long units = (long long)P.N * P.upi;
     if (units == 0) return;
-    const dim3 grid((unsigned)((units + 15) / 16)), block(256);
+    const dim3 grid((unsigned)((units + 15) / 16), (unsigned)P.KH), block(256);
     dispatch(P, [&] { CANVAS_LAUNCH((k_bwd_da<3, 3>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_bwd_da<5, 5>), grid, block, 0, s, P); });
 }
 

@@ -75,7 +75,7 @@ void emit_wgrad(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, c
     W.src_f32 = src.f32 ? 1 : 0;
     W.dy_f32 = dy.f32 ? 1 : 0;
     gfc::prepare_wgrad(W);
-    const int slices = W.slices;
+    const int slices = gfc::wgrad_partials(W);
     const int64_t op = take((uint64_t)slices * nw * 4);
     list.push_back({name, operand_bytes + 4.0 * slices * nw, flops, [=](const RunArgs& a) {
                         gfc::Params Q = W;

@@ -348,7 +348,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int slice = blockIdx.x * kWaves + wave;
-    if (slice >= P.slices) return;
+    const bool active = slice < P.slices;  // (no early exit: every wavefront takes part in the workgroup sum below)
     const int g = blockIdx.z;
     const int ot = blockIdx.y / P.ktiles, kt = blockIdx.y - ot * P.ktiles;
     const int r = lane >> 4, s = lane & 15;
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
 #pragma unroll
         for (int nk = 0; nk < NK; nk++) acc[mo][nk] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    const int c_begin = slice * P.per_slice, c_end = min(P.N * P.chunks32, c_begin + P.per_slice);
+    const int c_begin = active ? slice * P.per_slice : 0, c_end = active ? min(P.N * P.chunks32, c_begin + P.per_slice) : 0;
     int n = (int)div_magic((uint32_t)c_begin, P.magicC32);
     int pc = c_begin - n * P.chunks32;
     const int maxoff = (P.KH / 2) * P.W + P.KW / 2;
@@ -434,7 +434,34 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
             }
         if (++pc == P.chunks32) { pc = 0; n++; }
     }
-    float* part = P.partial + (long long)slice * P.G * P.Og * P.K;
+    // sum of the workgroup's four wavefronts (consecutive slices of the same tile) in a fixed order,
+    // (w0 + w2) + (w1 + w3), through LDS: one partial per workgroup
+    __shared__ float red[2][MO * NK * 4][64];
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int nk = 0; nk < NK; nk++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) red[slot][(mo * NK + nk) * 4 + jj][lane] = acc[mo][nk][jj];
+    };
+    auto add = [&](int slot) {
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int nk = 0; nk < NK; nk++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) acc[mo][nk][jj] += red[slot][(mo * NK + nk) * 4 + jj][lane];
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) add(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave != 0) return;
+    add(0);
+    float* part = P.partial + (long long)blockIdx.x * P.G * P.Og * P.K;
 #pragma unroll
     for (int mo = 0; mo < MO; mo++)
 #pragma unroll
@@ -545,8 +572,10 @@ void prepare_wgrad(Params& P) {
     const int64_t wnumel = (int64_t)P.G * P.Og * P.K;
     const int64_t tiles = (int64_t)P.G * P.otiles * P.ktiles;
     const int64_t steps = (int64_t)P.N * P.chunks32;
+    // at most 1024 slices per tile and about 4 k wavefronts in all (more, shorter slices measured slower);
+    // one partial per workgroup of kWaves slices, at most 16 MB of partials
     int64_t slices = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(steps, 1024), (4096 + tiles - 1) / std::max<int64_t>(1, tiles)));
-    slices = std::max<int64_t>(1, std::min<int64_t>(slices, ((int64_t)32 << 20) / std::max<int64_t>(1, wnumel * 4)));
+    slices = std::max<int64_t>(1, std::min<int64_t>(slices, kWaves * (((int64_t)16 << 20) / std::max<int64_t>(1, wnumel * 4))));
     const int64_t per = std::max<int64_t>(1, (steps + slices - 1) / slices);
     P.per_slice = (int)per;
     P.slices = (int)((steps + per - 1) / per);
@@ -585,6 +614,8 @@ void wgrad_partial(const Params& P, hipStream_t s) {
     else { if (P.dy_f32) GFC_WG(false, true); else GFC_WG(false, false); }
 #undef GFC_WG
 }
+
+int wgrad_partials(const Params& P) { return (P.slices + kWaves - 1) / kWaves; }
 
 void wgrad_reduce(const float* partial, float* dw, int slices, int64_t elems, hipStream_t s) {
     if (elems > 0) CANVAS_LAUNCH(k_wgrad_reduce, dim3((unsigned)((elems + 31) / 32)), dim3(256), 0, s, partial, dw, slices, (long long)elems);

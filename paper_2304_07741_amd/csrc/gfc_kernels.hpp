@@ -18,7 +18,7 @@ struct Params {
     void* dst = nullptr;          // forward: [N, G*Og, P] fp32 or bf16
     const void* dy = nullptr;     // weight gradient: [N, G*Og, P] fp32 or bf16 (dy_f32)
     const uint16_t* addend = nullptr;  // forward with bf16 dst: optional bf16 tensor added to the result
-    float* partial = nullptr;     // weight gradient: [slices, G*Og*K] fp32
+    float* partial = nullptr;     // weight gradient: [wgrad_partials(P), G*Og*K] fp32
     int N = 0, G = 0, R = 0, KH = 1, KW = 1, TV = 1, K = 0, Og = 0, H = 0, W = 0, P = 0;
     int src_f32 = 0, dst_f32 = 1, dy_f32 = 1, acc = 0;  // acc: dst += result (fp32 dst only)
     int upi = 0;                  // forward: 8-pixel units per image, ceil(P / 8)
@@ -32,10 +32,12 @@ inline uint32_t magic_u32(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint6
 
 // y[n, g*Og+o, p] (+)= sum_k w[g][o][k] * src_row(n, g, k)[p + off(k)]
 void forward(const Params& P, hipStream_t s);
-// partial[slice][g][o][k] = sum over the slice's (n, p) of dy[n, g*Og+o, p] * src_row(n, g, k)[p + off(k)]
+// partial[wg][g][o][k] = sum over the (n, p) of the workgroup's four slices of dy[n, g*Og+o, p] * src_row(n, g, k)[p + off(k)]
 void wgrad_partial(const Params& P, hipStream_t s);
-// dw[e] = sum_slice partial[slice][e]
-void wgrad_reduce(const float* partial, float* dw, int slices, int64_t elems, hipStream_t s);
+// number of partials wgrad_partial writes (one per workgroup of four slices)
+int wgrad_partials(const Params& P);
+// dw[e] = sum_i partial[i][e], i < count
+void wgrad_reduce(const float* partial, float* dw, int count, int64_t elems, hipStream_t s);
 // wt[g][row][o*TV + tv] = w[g][o][row*TV + (TV-1-tv)]: the weights of the data-gradient contraction
 void transpose_weights(const uint16_t* w, uint16_t* wt, int G, int Og, int R, int TV, hipStream_t s);
 int choose_mo(int Og);
@@ -44,7 +46,7 @@ int choose_mo(int Og);
 // `rows` rows per group seen through a KH x KW window; the three `prepare_*` calls complete it for one launch kind.
 Params shape(int N, int G, int rows, int KH, int KW, int Og, int H, int W);
 void prepare_forward(Params& P);
-// Splits the N * ceil(P/32) pixel chunks over at most 1024 slices (partials of at most 32 MB).
+// Splits the N * ceil(P/32) pixel chunks over at most 1024 slices (one partial per four slices, at most 16 MB).
 void prepare_wgrad(Params& P);
 // Forward geometry -> geometry of the data gradient (rows and outputs swapped); use with transposed weights.
 Params data_gradient_of(const Params& fwd);

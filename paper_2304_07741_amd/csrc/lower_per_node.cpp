@@ -113,7 +113,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         off += align_up((uint64_t)wnumel[i] * 2);
         gfc::Params Q = fc_params(k);
         gfc::prepare_wgrad(Q);
-        const int64_t slices = Q.slices;
+        const int64_t slices = gfc::wgrad_partials(Q);
         lay.part[i] = (int64_t)off;
         off += align_up((uint64_t)slices * wnumel[i] * 4);
     }
@@ -237,7 +237,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             gfc::prepare_wgrad(Q);
             const int64_t poff = lay.part[widx], toff = lay.wt[widx];
             const int64_t nw = wnumel[widx];
-            const int slices = Q.slices;
+            const int slices = gfc::wgrad_partials(Q);
             low->bwd.push_back({Q.TV > 1 ? "gfc_wgrad_unfold" : "gfc_wgrad", (src_x ? 2.0 : 4.0) * dag.numel(srcn) + 4.0 * dag.numel(k) + 4.0 * slices * nw, flops,
                                 [=](const RunArgs& a) {
                                     gfc::Params R = Q;
