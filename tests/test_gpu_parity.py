@@ -163,7 +163,7 @@ def test_mfma_grouped_fc_shapes(harness, oracle, idx):
 
 
 @pytest.mark.parametrize("flags", [0, B.CANVAS_OPT_NO_FUSION])
-@pytest.mark.parametrize("N,H", [(2, 28), (3, 9), (32, 28)])
+@pytest.mark.parametrize("N,H", [(2, 28), (3, 9), (32, 28), (1, 4)])
 def test_config3_involution(harness, oracle, N, H, flags):
     case = wl.config3(N=N, H=H)
     res, r, dy = harness.run_case(case, flags)
@@ -214,7 +214,7 @@ def test_fused_dynamic_window_weights_variants(harness, oracle, idx):
 
 
 @pytest.mark.parametrize("flags", [0, B.CANVAS_OPT_NO_FUSION])
-@pytest.mark.parametrize("C,H,N", [(64, 56, 2), (128, 28, 2), (256, 14, 3), (512, 7, 5), (64, 11, 2)])
+@pytest.mark.parametrize("C,H,N", [(64, 56, 2), (128, 28, 2), (256, 14, 3), (512, 7, 5), (64, 11, 2), (64, 4, 1), (1024, 7, 2), (8, 5, 3)])
 def test_config4_sampled_small_batch(harness, oracle, C, H, N, flags):
     case = wl.config4(C, H, N=N)
     res, r, dy = harness.run_case(case, flags)
