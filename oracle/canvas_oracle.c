@@ -30,7 +30,7 @@
  *     %5 = binary %0 %4 op=mul         (first operand LHS, second RHS; add | sub | mul | min | max;
  *                                       sub is tile(LHS) - RHS; a tie of min / max sends the gradient to the LHS)
  *     %6 = fold %5 op=avg              (sum | avg | max)
- *     %7 = softmax %6 axis=C           (C | T)
+ *     %7 = softmax %6 axis=C           (C | T | CT: over channels, over taps, or over both jointly)
  *     output %7
  * %0 is the input [N, C, H, W].
  */
@@ -48,7 +48,7 @@
 enum { OP_INPUT = 0, OP_UNFOLD, OP_SHIFT, OP_FC, OP_UNARY, OP_BINARY, OP_SOFTMAX, OP_FOLD };
 enum { UN_RELU = 0, UN_ABS, UN_GELU, UN_EXPCLIP, UN_SIN };
 enum { BIN_ADD = 0, BIN_MUL, BIN_SUB, BIN_MIN, BIN_MAX };
-enum { AXIS_C = 0, AXIS_T };
+enum { AXIS_C = 0, AXIS_T, AXIS_CT };
 enum { FOLD_SUM = 0, FOLD_AVG, FOLD_MAX };
 
 typedef struct {
@@ -268,6 +268,7 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 nd->op = OP_SOFTMAX;
                 if (k2 && !strcmp(k2, "C")) nd->kind = AXIS_C;
                 else if (k2 && !strcmp(k2, "T")) nd->kind = AXIS_T;
+                else if (k2 && !strcmp(k2, "CT")) nd->kind = AXIS_CT;
                 else { set_err(err, errlen, "softmax needs axis=C|T", lineno); goto done; }
                 nd->C = A->C;
                 nd->T = A->T;
@@ -402,25 +403,25 @@ static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
         }
 }
 
-/* Softmax along one axis (channels or taps), every other index fixed. */
+/* Softmax along channels, along taps, or along both jointly (the [C, T] block is contiguous), every other index fixed. */
 static void fwd_softmax(const Dag *d, const Node *nd, const double *in, double *out) {
     int P = d->H * d->W, C = nd->C, T = nd->T;
-    int len = nd->kind == AXIS_C ? C : T, outer = nd->kind == AXIS_C ? T : C;
+    int len = nd->kind == AXIS_C ? C : (nd->kind == AXIS_T ? T : C * T), outer = nd->kind == AXIS_C ? T : (nd->kind == AXIS_T ? C : 1);
     int o, p, k;
     for (o = 0; o < outer; o++)
         for (p = 0; p < P; p++) {
             double m = -INFINITY, s = 0.0;
             for (k = 0; k < len; k++) {
-                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : (nd->kind == AXIS_T ? ((size_t)o * T + k) * P + p : (size_t)k * P + p);
                 if (in[idx] > m) m = in[idx];
             }
             for (k = 0; k < len; k++) {
-                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : (nd->kind == AXIS_T ? ((size_t)o * T + k) * P + p : (size_t)k * P + p);
                 out[idx] = exp(in[idx] - m);
                 s += out[idx];
             }
             for (k = 0; k < len; k++) {
-                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : (nd->kind == AXIS_T ? ((size_t)o * T + k) * P + p : (size_t)k * P + p);
                 out[idx] /= s;
             }
         }
@@ -540,17 +541,17 @@ static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
 
 static void bwd_softmax(const Dag *d, const Node *nd, const double *out, const double *gout, double *gin) {
     int P = d->H * d->W, C = nd->C, T = nd->T;
-    int len = nd->kind == AXIS_C ? C : T, outer = nd->kind == AXIS_C ? T : C;
+    int len = nd->kind == AXIS_C ? C : (nd->kind == AXIS_T ? T : C * T), outer = nd->kind == AXIS_C ? T : (nd->kind == AXIS_T ? C : 1);
     int o, p, k;
     for (o = 0; o < outer; o++)
         for (p = 0; p < P; p++) {
             double dot = 0.0;
             for (k = 0; k < len; k++) {
-                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : (nd->kind == AXIS_T ? ((size_t)o * T + k) * P + p : (size_t)k * P + p);
                 dot += gout[idx] * out[idx];
             }
             for (k = 0; k < len; k++) {
-                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : ((size_t)o * T + k) * P + p;
+                size_t idx = nd->kind == AXIS_C ? ((size_t)k * T + o) * P + p : (nd->kind == AXIS_T ? ((size_t)o * T + k) * P + p : (size_t)k * P + p);
                 gin[idx] += out[idx] * (gout[idx] - dot);
             }
         }

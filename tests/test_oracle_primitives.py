@@ -150,6 +150,7 @@ FD_BODIES = [
     ("%1 = unfold %0 kh=3 kw=3\n%2 = fc %1 groups=2 out=4\n%3 = unary %2 op=gelu\n%4 = shift %3 dh=0 dw=1 c0=2 c1=4\n"
      "%5 = binary %0 %4 op=mul\n%6 = fold %5 op=avg\n%7 = fc %6 groups=1 out=4\noutput %7\n", [(2, 2, 18), (1, 4, 4)]),
     ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=abs\n%3 = binary %0 %2 op=mul\n%4 = softmax %3 axis=T\noutput %4\n", []),
+    ("%1 = unfold %0 kh=1 kw=3\n%2 = softmax %1 axis=CT\n%3 = fold %2 op=max\noutput %3\n", []),
     ("%1 = unary %0 op=sin\noutput %1\n", []),
     ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=sin\n%3 = binary %0 %2 op=sub\n%4 = fold %3 op=sum\noutput %4\n", []),
     ("%1 = shift %0 dh=1 dw=0\n%2 = unary %1 op=gelu\n%3 = binary %2 %0 op=max\noutput %3\n", []),
@@ -276,6 +277,29 @@ def test_softmax_invariants(oracle, axis):
         np.testing.assert_allclose(y1, r["y"], atol=1e-14)  # shift invariance
         e = np.exp(x)
         np.testing.assert_allclose(r["y"], e / e.sum(axis=1, keepdims=True), atol=1e-14)
+
+
+def test_joint_softmax_over_channels_and_taps(oracle):
+    """axis=CT: one distribution over all (channel, tap) pairs of a pixel."""
+    rng = np.random.default_rng(33)
+    x = rng.standard_normal((2, 3, 4, 5))
+    body = "%1 = unfold %0 kh=3 kw=1\n%2 = softmax %1 axis=CT\noutput %2\n"
+    u = run1(oracle, "%1 = unfold %0 kh=3 kw=1\noutput %1\n", x)["y"]  # [N, C, T, H, W]
+    y = run1(oracle, body, x)["y"]
+    e = np.exp(u - u.max(axis=(1, 2), keepdims=True))
+    np.testing.assert_allclose(y, e / e.sum(axis=(1, 2), keepdims=True), atol=1e-15)
+    np.testing.assert_allclose(y.sum(axis=(1, 2)), 1.0, atol=1e-14)
+    # with one tap it is the channel softmax, with one channel the tap softmax
+    np.testing.assert_array_equal(run1(oracle, "%1 = softmax %0 axis=CT\noutput %1\n", x)["y"],
+                                  run1(oracle, "%1 = softmax %0 axis=C\noutput %1\n", x)["y"])
+    x1 = x[:, :1]
+    np.testing.assert_array_equal(run1(oracle, "%1 = unfold %0 kh=3 kw=3\n%2 = softmax %1 axis=CT\noutput %2\n", x1)["y"],
+                                  run1(oracle, "%1 = unfold %0 kh=3 kw=3\n%2 = softmax %1 axis=T\noutput %2\n", x1)["y"])
+    # Jacobian-vector product: dx_j = y_j (g_j - sum_k g_k y_k) over the joint index, through the unfold adjoint
+    g = rng.standard_normal(y.shape)
+    r = run1(oracle, body, x, (), g)
+    gu = y * (g - (g * y).sum(axis=(1, 2), keepdims=True))
+    np.testing.assert_allclose(r["dx"], run1(oracle, "%1 = unfold %0 kh=3 kw=1\noutput %1\n", x, (), gu)["dx"], atol=1e-14)
 
 
 def test_softmax_over_single_tap_is_all_ones_with_zero_gradient(oracle):
