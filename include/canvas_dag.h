@@ -18,7 +18,7 @@
  *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
  *     %5 = binary %0 %4 op=mul         first operand LHS, second RHS; add | sub | mul | min | max
  *     %6 = fold %5 op=avg              sum | avg | max
- *     %7 = softmax %6 axis=C           C | T
+ *     %7 = softmax %6 axis=C           C | T | CT
  *     output %7
  *
  * Tensors are [N, C, T, H, W], contiguous, T = number of unfolded taps (1 when
@@ -37,7 +37,8 @@
  *            lhs t = t mod T_L); otherwise the LHS is replicated along the
  *            flattened (c*T_R + t) index modulo C_L*T_L.  The LHS size must
  *            divide the RHS size.  op: add, sub (tile(LHS) - RHS), mul, min, max.
- *   softmax  along C (per n,t,h,w) or along T (per n,c,h,w) (Section 5, Softmax).
+ *   softmax  along C (per n,t,h,w), along T (per n,c,h,w) or along both jointly
+ *            (axis=CT, per n,h,w) (Section 5, Softmax over contiguous dims).
  *   fold     sum, avg or max over T; T disappears (Section 5, Folding).  Max
  *            sends its gradient to the first maximal tap.
  *   backward exact vector-Jacobian products of the above; relu'(0) = 0,

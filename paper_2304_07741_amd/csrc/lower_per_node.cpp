@@ -197,7 +197,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             break;
         }
         case Op::Softmax:
-            L.run = [=](const RunArgs& a) { ref::softmax_fwd(val(a, nd.a), valw(a, k), N, nd.C, nd.T, P, nd.kind == kAxisC, a.stream); };
+            L.run = [=](const RunArgs& a) { ref::softmax_fwd(val(a, nd.a), valw(a, k), N, nd.C, nd.T, P, nd.kind == kAxisCT ? 2 : (nd.kind == kAxisC ? 1 : 0), a.stream); };
             break;
         case Op::Fold:
             L.run = [=](const RunArgs& a) { ref::fold_fwd(val(a, nd.a), valw(a, k), N * A.C, A.T, P, nd.kind, a.stream); };
@@ -327,7 +327,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         }
         case Op::Softmax:
             L.bytes += 4.0 * dag.numel(k);
-            L.run = [=](const RunArgs& a) { ref::softmax_bwd(val(a, k), grad(a, k), grad(a, nd.a), N, nd.C, nd.T, P, nd.kind == kAxisC, acc, a.stream); };
+            L.run = [=](const RunArgs& a) { ref::softmax_bwd(val(a, k), grad(a, k), grad(a, nd.a), N, nd.C, nd.T, P, nd.kind == kAxisCT ? 2 : (nd.kind == kAxisC ? 1 : 0), acc, a.stream); };
             break;
         case Op::Fold:
             L.bytes += 4.0 * dag.numel(nd.a);

@@ -180,6 +180,7 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             if (it == l.attr.end()) return fail(err, lineno, "softmax needs axis=", kInvalidBlob);
             if (it->second == "C") nd.kind = kAxisC;
             else if (it->second == "T") nd.kind = kAxisT;
+            else if (it->second == "CT") nd.kind = kAxisCT;
             else return fail(err, lineno, "softmax axis must be C or T", kUnknownOp);
             nd.C = A.C;
             nd.T = A.T;

@@ -258,7 +258,11 @@ __global__ void k_softmax_fwd(const float* __restrict__ in, float* __restrict__ 
     int64_t r = i / P;
     int len, outer;
     int64_t stride, base;
-    if (axis_c) {
+    if (axis_c == 2) {  // channels and taps jointly: the [C, T] block of a pixel, stride P
+        len = C * T; outer = 1;
+        base = r * len * P + p;
+        stride = P;
+    } else if (axis_c) {
         len = C; outer = T;
         int t = (int)(r % outer);
         int64_t n = r / outer;
@@ -287,7 +291,11 @@ __global__ void k_softmax_bwd(const float* __restrict__ y, const float* __restri
     int64_t r = i / P;
     int len;
     int64_t stride, base;
-    if (axis_c) {
+    if (axis_c == 2) {
+        len = C * T;
+        base = r * len * P + p;
+        stride = P;
+    } else if (axis_c) {
         len = C;
         int t = (int)(r % T);
         int64_t n = r / T;
@@ -408,12 +416,12 @@ void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float
     LAUNCH(k_binary_bwd_lhs, total, lhs, rhs, gout, glhs, total, CL, TL, CR, TR, P, kind, acc);
 }
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s) {
-    int64_t total = N * (axis_c ? T : C) * P;
+    int64_t total = N * (axis_c == 2 ? 1 : (axis_c ? T : C)) * P;
     LAUNCH(k_softmax_fwd, total, in, out, total, C, T, P, axis_c);
 }
 void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C, int T, int P, int axis_c, int acc,
                  hipStream_t s) {
-    int64_t total = N * (axis_c ? T : C) * P;
+    int64_t total = N * (axis_c == 2 ? 1 : (axis_c ? T : C)) * P;
     LAUNCH(k_softmax_bwd, total, y, gout, gin, total, C, T, P, axis_c, acc);
 }
 void fold_fwd(const float* in, float* out, int64_t NC, int T, int P, int kind, hipStream_t s) {

@@ -27,6 +27,7 @@ void binary_bwd_rhs(const float* lhs, const float* rhs, const float* gout, float
                     int kind, int acc, hipStream_t s);
 void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
                     int kind, int acc, hipStream_t s);
+// axis_c: 1 = over channels, 0 = over taps, 2 = over both jointly
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s);
 void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C, int T, int P, int axis_c, int acc,
                  hipStream_t s);

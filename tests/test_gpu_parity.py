@@ -56,6 +56,8 @@ PRIMS = [
     ("output %0\n", []),
     ("%1 = unary %0 op=relu\n%2 = fc %0 groups=1 out=12\noutput %1\n", [(1, 12, 12)]),  # dead fc: zero dW
     ("%1 = unary %0 op=sin\noutput %1\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = softmax %1 axis=CT\noutput %2\n", []),
+    ("%1 = softmax %0 axis=CT\n%2 = binary %1 %0 op=mul\noutput %2\n", []),
     ("%1 = shift %0 dh=1 dw=0\n%2 = binary %0 %1 op=sub\noutput %2\n", []),
     ("%1 = unfold %0 kh=3 kw=3\n%2 = binary %0 %1 op=max\noutput %2\n", []),
     ("%1 = unfold %0 kh=3 kw=1\n%2 = fc %0 groups=3 out=6\n%3 = binary %2 %1 op=min\n%4 = fold %3 op=avg\noutput %4\n", [(3, 2, 4)]),
