@@ -29,7 +29,10 @@
  *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
  *     %5 = binary %0 %4 op=mul         (first operand LHS, second RHS; add | sub | mul | min | max;
  *                                       sub is tile(LHS) - RHS; a tie of min / max sends the gradient to the LHS)
- *     %6 = fold %5 op=avg              (sum | avg | max)
+ *     %6 = fold %5 op=avg              (sum | avg | max; axis=T (default) folds the taps, axis=HW folds the
+ *                                       pixels: the result is a [C, T, 1, 1] tensor, which FC, unary, softmax,
+ *                                       fold over T and binary accept; as the LHS of a binary it is
+ *                                       replicated over the pixels of a full-size RHS)
  *     %7 = softmax %6 axis=C           (C | T | CT: over channels, over taps, or over both jointly)
  *     output %7
  * %0 is the input [N, C, H, W].
@@ -60,6 +63,8 @@ typedef struct {
     int kind;           /* unary / binary / fold kind, softmax axis */
     double lo, hi;      /* expclip */
     int C, T;           /* inferred shape [C, T, H, W] */
+    int pooled;         /* 1: the spatial dims have been folded away, shape [C, T, 1, 1] */
+    int axis_hw;        /* fold: 1 = over the pixels, 0 = over the taps */
     int widx;           /* fc: index into the weight list */
 } Node;
 
@@ -194,6 +199,11 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
         {
             const Node *A = &d->node[nd->a];
             const char *opn = tok[2];
+            nd->pooled = A->pooled;  /* (binary takes the RHS's below) */
+            if ((!strcmp(opn, "unfold") || !strcmp(opn, "shift")) && A->pooled) {
+                set_err(err, errlen, "unfold / shift need the spatial dims", lineno);
+                goto done;
+            }
             if (!strcmp(opn, "unfold")) {
                 nd->op = OP_UNFOLD;
                 if (attr_int(tok, ntok, "kh", &nd->kh) != 1 || attr_int(tok, ntok, "kw", &nd->kw) != 1 ||
@@ -257,10 +267,11 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 else if (!strcmp(k2, "max")) nd->kind = BIN_MAX;
                 else { set_err(err, errlen, "unknown binary op", lineno); goto done; }
                 B = &d->node[nd->b];
-                if (!broadcast_legal(A->C, A->T, B->C, B->T)) {
+                if (!broadcast_legal(A->C, A->T, B->C, B->T) || (!A->pooled && B->pooled)) {
                     set_err(err, errlen, "broadcast: LHS size does not divide RHS size", lineno);
                     goto done;
                 }
+                nd->pooled = B->pooled;
                 nd->C = B->C;
                 nd->T = B->T;
             } else if (!strcmp(opn, "softmax")) {
@@ -279,8 +290,19 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 else if (k2 && !strcmp(k2, "avg")) nd->kind = FOLD_AVG;
                 else if (k2 && !strcmp(k2, "max")) nd->kind = FOLD_MAX;
                 else { set_err(err, errlen, "fold needs op=sum|avg|max", lineno); goto done; }
+                {
+                    const char *ax = find_attr(tok, ntok, "axis");
+                    if (ax && !strcmp(ax, "HW")) nd->axis_hw = 1;
+                    else if (ax && strcmp(ax, "T")) { set_err(err, errlen, "fold axis must be T or HW", lineno); goto done; }
+                }
                 nd->C = A->C;
-                nd->T = 1;
+                if (nd->axis_hw) {
+                    if (A->pooled) { set_err(err, errlen, "fold axis=HW: the spatial dims are already folded", lineno); goto done; }
+                    nd->T = A->T;
+                    nd->pooled = 1;
+                } else {
+                    nd->T = 1;
+                }
             } else {
                 set_err(err, errlen, "unknown op", lineno);
                 goto done;
@@ -298,7 +320,8 @@ done:
 
 /* ------------------------------------------------------- forward, one image */
 
-static size_t node_numel(const Dag *d, int k) { return (size_t)d->node[k].C * d->node[k].T * d->H * d->W; }
+static int node_P(const Dag *d, const Node *nd) { return nd->pooled ? 1 : d->H * d->W; }
+static size_t node_numel(const Dag *d, int k) { return (size_t)d->node[k].C * d->node[k].T * node_P(d, &d->node[k]); }
 
 /* Unfold (Section 5): U(c, kh, kw, h, w) = I(c, h + kh, w + kw) with the window
  * centred on the pixel (kh, kw run over [-K/2, K/2]) and zeros outside the
@@ -348,7 +371,7 @@ static void fwd_shift(const Dag *d, const Node *nd, const double *in, double *ou
  * y[g*Og + o, p] = sum_{c', t} Wt[g, o, c'*T + t] * x[g*Cg + c', t, p]. */
 static void fwd_fc(const Dag *d, const Node *nd, const double *in, const double *wt, double *out) {
     const Node *A = &d->node[nd->a];
-    int P = d->H * d->W, G = nd->groups, Cg = A->C / G, Og = nd->out / G, K = Cg * A->T;
+    int P = node_P(d, nd), G = nd->groups, Cg = A->C / G, Og = nd->out / G, K = Cg * A->T;
     int g, o, i, p;
     for (g = 0; g < G; g++)
         for (o = 0; o < Og; o++) {
@@ -382,15 +405,15 @@ static void fwd_unary(const Dag *d, const Node *nd, int k, const double *in, dou
 
 static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const double *rhs, double *out) {
     const Node *L = &d->node[nd->a];
-    int P = d->H * d->W, c, t, p, cl, tl;
+    int P = node_P(d, nd), PL = node_P(d, L), c, t, p, cl, tl;  /* PL == 1 < P: the LHS is replicated over the pixels */
     for (c = 0; c < nd->C; c++)
         for (t = 0; t < nd->T; t++) {
             const double *lrow, *rrow = rhs + ((size_t)c * nd->T + t) * P;
             double *orow = out + ((size_t)c * nd->T + t) * P;
             broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
-            lrow = lhs + ((size_t)cl * L->T + tl) * P;
+            lrow = lhs + ((size_t)cl * L->T + tl) * PL;
             for (p = 0; p < P; p++) {
-                double a = lrow[p], b = rrow[p], y = 0.0;
+                double a = lrow[PL == 1 ? 0 : p], b = rrow[p], y = 0.0;
                 switch (nd->kind) {
                 case BIN_ADD: y = a + b; break;
                 case BIN_MUL: y = a * b; break;
@@ -405,7 +428,7 @@ static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
 
 /* Softmax along channels, along taps, or along both jointly (the [C, T] block is contiguous), every other index fixed. */
 static void fwd_softmax(const Dag *d, const Node *nd, const double *in, double *out) {
-    int P = d->H * d->W, C = nd->C, T = nd->T;
+    int P = node_P(d, nd), C = nd->C, T = nd->T;
     int len = nd->kind == AXIS_C ? C : (nd->kind == AXIS_T ? T : C * T), outer = nd->kind == AXIS_C ? T : (nd->kind == AXIS_T ? C : 1);
     int o, p, k;
     for (o = 0; o < outer; o++)
@@ -427,10 +450,23 @@ static void fwd_softmax(const Dag *d, const Node *nd, const double *in, double *
         }
 }
 
-/* Folding over the tap dim: sum, average or max; the tap dim disappears. */
+/* Folding: sum, average or max over the tap dim (it disappears) or over the spatial dims (they become 1 x 1). */
 static void fwd_fold(const Dag *d, const Node *nd, const double *in, double *out) {
     const Node *A = &d->node[nd->a];
-    int P = d->H * d->W, T = A->T, c, t, p;
+    int P = node_P(d, A), T = A->T, c, t, p;
+    if (nd->axis_hw) {  /* over the pixels of every (channel, tap) plane */
+        for (c = 0; c < nd->C * T; c++) {
+            double acc = in[(size_t)c * P];
+            for (p = 1; p < P; p++) {
+                double v = in[(size_t)c * P + p];
+                if (nd->kind == FOLD_MAX) { if (v > acc) acc = v; }
+                else acc += v;
+            }
+            if (nd->kind == FOLD_AVG) acc /= P;
+            out[c] = acc;
+        }
+        return;
+    }
     for (c = 0; c < nd->C; c++)
         for (p = 0; p < P; p++) {
             double acc = in[((size_t)c * T) * P + p];
@@ -484,7 +520,7 @@ static void bwd_shift(const Dag *d, const Node *nd, const double *gout, double *
 
 static void bwd_fc(const Dag *d, const Node *nd, const double *in, const double *wt, const double *gout, double *gin, double *gw) {
     const Node *A = &d->node[nd->a];
-    int P = d->H * d->W, G = nd->groups, Cg = A->C / G, Og = nd->out / G, K = Cg * A->T;
+    int P = node_P(d, nd), G = nd->groups, Cg = A->C / G, Og = nd->out / G, K = Cg * A->T;
     int g, o, i, p;
     for (g = 0; g < G; g++)
         for (o = 0; o < Og; o++) {
@@ -520,27 +556,28 @@ static void bwd_unary(const Dag *d, const Node *nd, int k, const double *in, con
 
 static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const double *rhs, const double *gout, double *glhs, double *grhs) {
     const Node *L = &d->node[nd->a];
-    int P = d->H * d->W, c, t, p, cl, tl;
+    int P = node_P(d, nd), PL = node_P(d, L), c, t, p, cl, tl;
     for (c = 0; c < nd->C; c++)
         for (t = 0; t < nd->T; t++) {
             size_t ro = ((size_t)c * nd->T + t) * P, lo;
             broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
-            lo = ((size_t)cl * L->T + tl) * P;
+            lo = ((size_t)cl * L->T + tl) * PL;
             for (p = 0; p < P; p++) {
-                double g = gout[ro + p], a = lhs[lo + p], b = rhs[ro + p];
+                size_t lp = lo + (PL == 1 ? 0 : p);
+                double g = gout[ro + p], a = lhs[lp], b = rhs[ro + p];
                 switch (nd->kind) {
-                case BIN_ADD: glhs[lo + p] += g; grhs[ro + p] += g; break;
-                case BIN_MUL: glhs[lo + p] += g * b; grhs[ro + p] += g * a; break;
-                case BIN_SUB: glhs[lo + p] += g; grhs[ro + p] -= g; break;
-                case BIN_MIN: if (a <= b) glhs[lo + p] += g; else grhs[ro + p] += g; break;
-                case BIN_MAX: if (a >= b) glhs[lo + p] += g; else grhs[ro + p] += g; break;
+                case BIN_ADD: glhs[lp] += g; grhs[ro + p] += g; break;
+                case BIN_MUL: glhs[lp] += g * b; grhs[ro + p] += g * a; break;
+                case BIN_SUB: glhs[lp] += g; grhs[ro + p] -= g; break;
+                case BIN_MIN: if (a <= b) glhs[lp] += g; else grhs[ro + p] += g; break;
+                case BIN_MAX: if (a >= b) glhs[lp] += g; else grhs[ro + p] += g; break;
                 }
             }
         }
 }
 
 static void bwd_softmax(const Dag *d, const Node *nd, const double *out, const double *gout, double *gin) {
-    int P = d->H * d->W, C = nd->C, T = nd->T;
+    int P = node_P(d, nd), C = nd->C, T = nd->T;
     int len = nd->kind == AXIS_C ? C : (nd->kind == AXIS_T ? T : C * T), outer = nd->kind == AXIS_C ? T : (nd->kind == AXIS_T ? C : 1);
     int o, p, k;
     for (o = 0; o < outer; o++)
@@ -560,7 +597,22 @@ static void bwd_softmax(const Dag *d, const Node *nd, const double *out, const d
 /* Max takes the gradient to the first maximal tap (lowest t) only. */
 static void bwd_fold(const Dag *d, const Node *nd, const double *in, const double *gout, double *gin) {
     const Node *A = &d->node[nd->a];
-    int P = d->H * d->W, T = A->T, c, t, p;
+    int P = node_P(d, A), T = A->T, c, t, p;
+    if (nd->axis_hw) {  /* max: to the first maximal pixel (lowest flat index) only */
+        for (c = 0; c < nd->C * T; c++) {
+            double g = gout[c];
+            if (nd->kind == FOLD_MAX) {
+                int best = 0;
+                for (p = 1; p < P; p++)
+                    if (in[(size_t)c * P + p] > in[(size_t)c * P + best]) best = p;
+                gin[(size_t)c * P + best] += g;
+            } else {
+                if (nd->kind == FOLD_AVG) g /= P;
+                for (p = 0; p < P; p++) gin[(size_t)c * P + p] += g;
+            }
+        }
+        return;
+    }
     for (c = 0; c < nd->C; c++)
         for (p = 0; p < P; p++) {
             double g = gout[(size_t)c * P + p];
@@ -590,8 +642,8 @@ int canvas_oracle_infer(const char *blob, size_t len, const int64_t in_shape[4],
     for (k = 0; k < d.n_nodes; k++) {
         shapes[4 * k + 0] = d.node[k].C;
         shapes[4 * k + 1] = d.node[k].T;
-        shapes[4 * k + 2] = d.H;
-        shapes[4 * k + 3] = d.W;
+        shapes[4 * k + 2] = d.node[k].pooled ? 1 : d.H;
+        shapes[4 * k + 3] = d.node[k].pooled ? 1 : d.W;
         if (d.node[k].op == OP_FC) {
             const Node *A = &d.node[d.node[k].a];
             int wi = d.node[k].widx;

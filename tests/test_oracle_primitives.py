@@ -151,6 +151,10 @@ FD_BODIES = [
      "%5 = binary %0 %4 op=mul\n%6 = fold %5 op=avg\n%7 = fc %6 groups=1 out=4\noutput %7\n", [(2, 2, 18), (1, 4, 4)]),
     ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=abs\n%3 = binary %0 %2 op=mul\n%4 = softmax %3 axis=T\noutput %4\n", []),
     ("%1 = unfold %0 kh=1 kw=3\n%2 = softmax %1 axis=CT\n%3 = fold %2 op=max\noutput %3\n", []),
+    # squeeze-and-excite: pooled descriptor -> FC -> gelu -> FC -> softmax -> gate on x
+    ("%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=2\n%3 = unary %2 op=gelu\n%4 = fc %3 groups=1 out=4\n"
+     "%5 = softmax %4 axis=C\n%6 = binary %5 %0 op=mul\noutput %6\n", [(1, 2, 4), (1, 4, 2)]),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=max axis=HW\n%3 = binary %2 %1 op=sub\n%4 = fold %3 op=avg\noutput %4\n", []),
     ("%1 = unary %0 op=sin\noutput %1\n", []),
     ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=sin\n%3 = binary %0 %2 op=sub\n%4 = fold %3 op=sum\noutput %4\n", []),
     ("%1 = shift %0 dh=1 dw=0\n%2 = unary %1 op=gelu\n%3 = binary %2 %0 op=max\noutput %3\n", []),
@@ -255,6 +259,70 @@ def test_min_max_broadcast_sums_over_replicas(oracle):
     # route through the unfold adjoint for the RHS part: reuse the oracle's own (separately pinned) unfold backward
     rhs_part = run1(oracle, "%1 = unfold %0 kh=3 kw=3\noutput %1\n", x, (), np.where(lhs_wins, 0.0, g))["dx"]
     np.testing.assert_allclose(r["dx"], np.where(lhs_wins, g, 0.0).sum(axis=2) + rhs_part, atol=1e-14)
+
+
+# ------------------------------------------- fold over the spatial dims
+
+def test_spatial_fold_definitions(oracle):
+    """fold axis=HW: sum / mean / max over the pixels of every (channel, tap) plane; the result is [C, T, 1, 1]."""
+    rng = np.random.default_rng(40)
+    x = rng.standard_normal((2, 3, 4, 5))
+    for op, fn in (("sum", np.sum), ("avg", np.mean), ("max", np.max)):
+        y = run1(oracle, f"%1 = fold %0 op={op} axis=HW\noutput %1\n", x)["y"]
+        assert y.shape == (2, 3, 1, 1)
+        np.testing.assert_allclose(y[:, :, 0, 0], fn(x, axis=(2, 3)), atol=1e-14)
+    u = run1(oracle, "%1 = unfold %0 kh=3 kw=1\noutput %1\n", x)["y"]
+    y = run1(oracle, "%1 = unfold %0 kh=3 kw=1\n%2 = fold %1 op=avg axis=HW\noutput %2\n", x)["y"]
+    assert y.shape == (2, 3, 3, 1, 1)
+    np.testing.assert_allclose(y[..., 0, 0], u.mean(axis=(3, 4)), atol=1e-14)
+    # folding the taps and the pixels commutes for sum / avg
+    a = run1(oracle, "%1 = unfold %0 kh=3 kw=1\n%2 = fold %1 op=avg axis=HW\n%3 = fold %2 op=avg\noutput %3\n", x)["y"]
+    b = run1(oracle, "%1 = unfold %0 kh=3 kw=1\n%2 = fold %1 op=avg\n%3 = fold %2 op=avg axis=HW\noutput %3\n", x)["y"]
+    np.testing.assert_allclose(a, b, atol=1e-14)
+
+
+def test_spatial_fold_gradients(oracle):
+    x = np.arange(24, dtype=float).reshape(1, 2, 3, 4)
+    x[0, 1] = 5.0            # a plane of ties: max takes the first pixel
+    x[0, 0, 1, 2] = 100.0    # a unique maximum
+    g = np.array([2.0, -3.0]).reshape(1, 2, 1, 1)
+    r = run1(oracle, "%1 = fold %0 op=sum axis=HW\noutput %1\n", x, (), g)
+    np.testing.assert_array_equal(r["dx"], np.broadcast_to(g, x.shape))
+    r = run1(oracle, "%1 = fold %0 op=avg axis=HW\noutput %1\n", x, (), g)
+    np.testing.assert_allclose(r["dx"], np.broadcast_to(g / 12.0, x.shape), atol=1e-16)
+    r = run1(oracle, "%1 = fold %0 op=max axis=HW\noutput %1\n", x, (), g)
+    exp = np.zeros_like(x)
+    exp[0, 0, 1, 2] = 2.0
+    exp[0, 1, 0, 0] = -3.0
+    np.testing.assert_array_equal(r["dx"], exp)
+
+
+def test_pooled_tensor_is_replicated_over_pixels(oracle):
+    """y = x * mean_hw(x): closed-form value and gradient; an FC of a pooled tensor is a matrix-vector product."""
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((2, 3, 4, 5))
+    g = rng.standard_normal(x.shape)
+    r = run1(oracle, "%1 = fold %0 op=avg axis=HW\n%2 = binary %1 %0 op=mul\noutput %2\n", x, (), g)
+    m = x.mean(axis=(2, 3), keepdims=True)
+    np.testing.assert_allclose(r["y"], x * m, atol=1e-14)
+    np.testing.assert_allclose(r["dx"], g * m + (g * x).sum(axis=(2, 3), keepdims=True) / 20.0, atol=1e-14)
+    w = rng.standard_normal((1, 4, 3))
+    gy = rng.standard_normal((2, 4, 1, 1))
+    r = run1(oracle, "%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=4\noutput %2\n", x, [w], gy)
+    np.testing.assert_allclose(r["y"][:, :, 0, 0], m[:, :, 0, 0] @ w[0].T, atol=1e-14)
+    np.testing.assert_allclose(r["dw"][0][0], gy[:, :, 0, 0].T @ m[:, :, 0, 0], atol=1e-14)
+    np.testing.assert_allclose(r["dx"], np.broadcast_to(((gy[:, :, 0, 0] @ w[0]) / 20.0)[:, :, None, None], x.shape), atol=1e-14)
+
+
+def test_spatial_fold_legality(oracle):
+    x = np.zeros((1, 4, 3, 3))
+    for body in ("%1 = fold %0 op=avg axis=HW\n%2 = unfold %1 kh=3 kw=3\noutput %2\n",      # no window without pixels
+                 "%1 = fold %0 op=avg axis=HW\n%2 = shift %1 dh=0 dw=1\noutput %2\n",
+                 "%1 = fold %0 op=avg axis=HW\n%2 = fold %1 op=max axis=HW\noutput %2\n",       # already folded
+                 "%1 = fold %0 op=avg axis=HW\n%2 = binary %0 %1 op=add\noutput %2\n",          # LHS larger than RHS
+                 "%1 = fold %0 op=avg axis=C\noutput %1\n"):
+        with pytest.raises(Exception):
+            run1(oracle, body, x)
 
 
 # ---------------------------------------------------------------- softmax
