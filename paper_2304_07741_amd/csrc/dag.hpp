@@ -25,6 +25,8 @@ struct Node {
     int groups = 1, out = 0;     // fc
     int kind = 0;                // UnaryKind / BinaryKind / AxisKind / FoldKind
     float lo = 0.f, hi = 0.f;    // expclip bounds
+    int axis_hw = 0;             // fold: 1 = over the pixels (the result is pooled), 0 = over the taps
+    bool pooled = false;         // the spatial dims have been folded away: shape [N, C, T, 1, 1]
     int C = 0, T = 1;            // inferred shape
     int widx = -1;               // fc: index into the weight list
     bool live = false;           // reaches the output
@@ -37,8 +39,9 @@ struct Dag {
     int n_weights = 0;
     std::vector<int> weight_node;
 
-    int64_t numel(int k) const { return (int64_t)N * nodes[k].C * nodes[k].T * H * W; }
     int P() const { return H * W; }
+    int Pk(int k) const { return nodes[k].pooled ? 1 : H * W; }  // pixels of node k
+    int64_t numel(int k) const { return (int64_t)N * nodes[k].C * nodes[k].T * Pk(k); }
 };
 
 // Status codes mirror canvas_status in the public header.

@@ -19,7 +19,7 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
     if (!bf16) return nullptr;
     const int n = (int)dag.nodes.size();
     for (int k = 0; k < n; k++)
-        if (!dag.nodes[k].live) return nullptr;
+        if (!dag.nodes[k].live || dag.nodes[k].pooled) return nullptr;  // (no tensor with folded spatial dims in this pattern)
     // the nodes in any valid order: exactly one of each kind (softmax optional)
     int ifc1 = -1, isoft = -1, iunf = -1, ibin = -1, ifold = -1, ifc2 = -1;
     for (int k = 1; k < n; k++) {

@@ -104,7 +104,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         const int k = dag.weight_node[i];
         const Node& f = dag.nodes[k];
         if (!f.live) continue;
-        fc_mfma[k] = mfma;
+        fc_mfma[k] = mfma && !f.pooled;  // (a 1 x 1 image has no 8-pixel units: the plain kernels take it)
         if (!fc_mfma[k]) {
             if (bf16) lay.wf[i] = take(wnumel[i]);
             continue;
@@ -159,7 +159,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             break;
         case Op::Fc: {
             int G = nd.groups, Og = nd.out / G, K = (A.C / G) * A.T;
-            L.flops = 2.0 * N * P * nd.out * K;
+            L.flops = 2.0 * N * dag.Pk(k) * nd.out * K;
             if (fc_mfma[k]) {
                 gfc::Params Q = fc_params(k);
                 const int srcn = fc_src(k);
@@ -180,7 +180,8 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
                 break;
             }
             L.bytes += 4.0 * wnumel[nd.widx];
-            L.run = [=](const RunArgs& a) { ref::fc_fwd(val(a, nd.a), wptr(a, nd.widx), valw(a, k), N, G, Og, K, P, a.stream); };
+            const int Pn = dag.Pk(k);
+            L.run = [=](const RunArgs& a) { ref::fc_fwd(val(a, nd.a), wptr(a, nd.widx), valw(a, k), N, G, Og, K, Pn, a.stream); };
             break;
         }
         case Op::Unary: {
@@ -191,16 +192,26 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         case Op::Binary: {
             const Node B = dag.nodes[nd.b];
             L.bytes = 4.0 * (dag.numel(nd.a) + dag.numel(nd.b) + dag.numel(k));
+            const int Pn = dag.Pk(k), PL = dag.Pk(nd.a);
             L.run = [=](const RunArgs& a) {
-                ref::binary_fwd(val(a, nd.a), val(a, nd.b), valw(a, k), N, A.C, A.T, B.C, B.T, P, nd.kind, a.stream);
+                ref::binary_fwd(val(a, nd.a), val(a, nd.b), valw(a, k), N, A.C, A.T, B.C, B.T, Pn, PL, nd.kind, a.stream);
             };
             break;
         }
         case Op::Softmax:
-            L.run = [=](const RunArgs& a) { ref::softmax_fwd(val(a, nd.a), valw(a, k), N, nd.C, nd.T, P, nd.kind == kAxisCT ? 2 : (nd.kind == kAxisC ? 1 : 0), a.stream); };
+            {
+                const int Pn = dag.Pk(k);
+                L.run = [=](const RunArgs& a) { ref::softmax_fwd(val(a, nd.a), valw(a, k), N, nd.C, nd.T, Pn, nd.kind == kAxisCT ? 2 : (nd.kind == kAxisC ? 1 : 0), a.stream); };
+            }
             break;
         case Op::Fold:
-            L.run = [=](const RunArgs& a) { ref::fold_fwd(val(a, nd.a), valw(a, k), N * A.C, A.T, P, nd.kind, a.stream); };
+            if (nd.axis_hw) {
+                L.name = "node_pool_fwd";
+                L.run = [=](const RunArgs& a) { ref::pool_fwd(val(a, nd.a), valw(a, k), N * A.C * A.T, P, nd.kind, a.stream); };
+            } else {
+                const int Pn = dag.Pk(k);
+                L.run = [=](const RunArgs& a) { ref::fold_fwd(val(a, nd.a), valw(a, k), N * A.C, A.T, Pn, nd.kind, a.stream); };
+            }
             break;
         default: break;
         }
@@ -288,14 +299,15 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             int G = nd.groups, Og = nd.out / G, K = (A.C / G) * A.T;
             Launch D;
             D.name = "node_fc_dw";
-            D.flops = 2.0 * N * P * nd.out * K;
+            const int Pn = dag.Pk(k);
+            D.flops = 2.0 * N * Pn * nd.out * K;
             D.bytes = 4.0 * (dag.numel(nd.a) + dag.numel(k) + wnumel[nd.widx]);
-            D.run = [=](const RunArgs& a) { ref::fc_dw(grad(a, k), val(a, nd.a), (float*)a.dw[nd.widx], N, G, Og, K, P, a.stream); };
+            D.run = [=](const RunArgs& a) { ref::fc_dw(grad(a, k), val(a, nd.a), (float*)a.dw[nd.widx], N, G, Og, K, Pn, a.stream); };
             low->bwd.push_back(std::move(D));
             L.name = "node_fc_dx";
-            L.flops = 2.0 * N * P * nd.out * K;
+            L.flops = 2.0 * N * Pn * nd.out * K;
             L.bytes += 4.0 * wnumel[nd.widx];
-            L.run = [=](const RunArgs& a) { ref::fc_dx(grad(a, k), wptr(a, nd.widx), grad(a, nd.a), N, G, Og, K, P, acc, a.stream); };
+            L.run = [=](const RunArgs& a) { ref::fc_dx(grad(a, k), wptr(a, nd.widx), grad(a, nd.a), N, G, Og, K, Pn, acc, a.stream); };
             break;
         }
         case Op::Unary: {
@@ -309,8 +321,9 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             // LHS first, then RHS (which may be the same tensor and then accumulates)
             L.name = "node_binary_bwd_lhs";
             L.bytes = 4.0 * (dag.numel(nd.a) * (1 + acc) + dag.numel(k) * (nd.kind == kAdd || nd.kind == kSub ? 1 : 2));
+            const int Pn = dag.Pk(k), PL = dag.Pk(nd.a);
             L.run = [=](const RunArgs& a) {
-                ref::binary_bwd_lhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.a), N, A.C, A.T, B.C, B.T, P, nd.kind, acc, a.stream);
+                ref::binary_bwd_lhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.a), N, A.C, A.T, B.C, B.T, Pn, PL, nd.kind, acc, a.stream);
             };
             low->bwd.push_back(std::move(L));
             written[nd.a] = true;
@@ -319,7 +332,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             R.name = "node_binary_bwd_rhs";
             R.bytes = 4.0 * (dag.numel(nd.b) * (1 + acc_r) + dag.numel(k) + (nd.kind == kAdd || nd.kind == kSub ? 0 : dag.numel(nd.a)));
             R.run = [=](const RunArgs& a) {
-                ref::binary_bwd_rhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.b), N, A.C, A.T, B.C, B.T, P, nd.kind, acc_r, a.stream);
+                ref::binary_bwd_rhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.b), N, A.C, A.T, B.C, B.T, Pn, PL, nd.kind, acc_r, a.stream);
             };
             low->bwd.push_back(std::move(R));
             written[nd.b] = true;
@@ -327,11 +340,20 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
         }
         case Op::Softmax:
             L.bytes += 4.0 * dag.numel(k);
-            L.run = [=](const RunArgs& a) { ref::softmax_bwd(val(a, k), grad(a, k), grad(a, nd.a), N, nd.C, nd.T, P, nd.kind == kAxisCT ? 2 : (nd.kind == kAxisC ? 1 : 0), acc, a.stream); };
+            {
+                const int Pn = dag.Pk(k);
+                L.run = [=](const RunArgs& a) { ref::softmax_bwd(val(a, k), grad(a, k), grad(a, nd.a), N, nd.C, nd.T, Pn, nd.kind == kAxisCT ? 2 : (nd.kind == kAxisC ? 1 : 0), acc, a.stream); };
+            }
             break;
         case Op::Fold:
             L.bytes += 4.0 * dag.numel(nd.a);
-            L.run = [=](const RunArgs& a) { ref::fold_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * A.C, A.T, P, nd.kind, acc, a.stream); };
+            if (nd.axis_hw) {
+                L.name = "node_pool_bwd";
+                L.run = [=](const RunArgs& a) { ref::pool_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * A.C * A.T, P, nd.kind, acc, a.stream); };
+            } else {
+                const int Pn = dag.Pk(k);
+                L.run = [=](const RunArgs& a) { ref::fold_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * A.C, A.T, Pn, nd.kind, acc, a.stream); };
+            }
             break;
         default: break;
         }

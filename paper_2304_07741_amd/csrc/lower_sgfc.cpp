@@ -12,7 +12,7 @@ std::unique_ptr<Lowering> lower_sgfc(const Dag& dag, bool bf16) {
     if (!bf16) return nullptr;
     const int n = (int)dag.nodes.size();
     for (int k = 0; k < n; k++)
-        if (!dag.nodes[k].live) return nullptr;
+        if (!dag.nodes[k].live || dag.nodes[k].pooled) return nullptr;  // (no tensor with folded spatial dims in this pattern)
     int k = 1, prev = 0;
     // shifts
     std::vector<int> sdh(dag.nodes[0].C, 0), sdw(dag.nodes[0].C, 0);

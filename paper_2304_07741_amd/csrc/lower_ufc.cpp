@@ -21,7 +21,7 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
     if (!bf16) return nullptr;
     const int n = (int)dag.nodes.size();
     for (int k = 0; k < n; k++)
-        if (!dag.nodes[k].live) return nullptr;
+        if (!dag.nodes[k].live || dag.nodes[k].pooled) return nullptr;  // (no tensor with folded spatial dims in this pattern)
     const int C = dag.nodes[0].C, Pn = dag.P();
     int k = 1, prev = 0;
     int KH = 1, KW = 1;

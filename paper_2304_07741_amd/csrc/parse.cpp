@@ -113,6 +113,8 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
         const Node& A = dag.nodes[nd.a];
         const std::string& op = l.pos[2];
         bool present;
+        nd.pooled = A.pooled;  // (binary takes the RHS's below)
+        if ((op == "unfold" || op == "shift") && A.pooled) return fail(err, lineno, op + " needs the spatial dims", kShapeMismatch);
         if (op == "unfold") {
             nd.op = Op::Unfold;
             if (!get_int(l, "kh", nd.kh, true, present) || !get_int(l, "kw", nd.kw, true, present))
@@ -171,6 +173,8 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             else return fail(err, lineno, "unknown binary op '" + it->second + "'", kUnknownOp);
             const Node& B = dag.nodes[nd.b];
             bool legal = (A.C == B.C) ? (B.T % A.T == 0) : (((int64_t)B.C * B.T) % ((int64_t)A.C * A.T) == 0);
+            if (!A.pooled && B.pooled) legal = false;  // a pooled LHS is replicated over the pixels, not the reverse
+            nd.pooled = B.pooled;
             if (!legal) return fail(err, lineno, "broadcast: LHS size does not divide RHS size", kShapeMismatch);
             nd.C = B.C;
             nd.T = B.T;
@@ -192,8 +196,17 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             else if (it->second == "avg") nd.kind = kAvg;
             else if (it->second == "max") nd.kind = kMax;
             else return fail(err, lineno, "unknown fold op '" + it->second + "'", kUnknownOp);
+            auto ax = l.attr.find("axis");
+            if (ax != l.attr.end() && ax->second == "HW") nd.axis_hw = 1;
+            else if (ax != l.attr.end() && ax->second != "T") return fail(err, lineno, "fold axis must be T or HW", kUnknownOp);
             nd.C = A.C;
-            nd.T = 1;
+            if (nd.axis_hw) {
+                if (A.pooled) return fail(err, lineno, "fold axis=HW: the spatial dims are already folded", kShapeMismatch);
+                nd.T = A.T;
+                nd.pooled = true;
+            } else {
+                nd.T = 1;
+            }
         } else {
             return fail(err, lineno, "unknown op '" + op + "'", kUnknownOp);
         }

@@ -186,8 +186,9 @@ __device__ inline void bsrc(int CL, int TL, int TR, int c, int t, int same_c, in
     }
 }
 
+// PL: pixels of the LHS, P or 1 (a pooled LHS is replicated over the pixels)
 __global__ void k_binary_fwd(const float* __restrict__ lhs, const float* __restrict__ rhs, float* __restrict__ out,
-                             int64_t total, int CL, int TL, int CR, int TR, int P, int kind) {
+                             int64_t total, int CL, int TL, int CR, int TR, int P, int PL, int kind) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
     int p = (int)(i % P);
@@ -198,12 +199,12 @@ __global__ void k_binary_fwd(const float* __restrict__ lhs, const float* __restr
     int64_t n = r / CR;
     int cl, tl;
     bsrc(CL, TL, TR, c, t, CL == CR, cl, tl);
-    float a = lhs[((n * CL + cl) * TL + tl) * P + p], b = rhs[i];
+    float a = lhs[((n * CL + cl) * TL + tl) * PL + (PL == 1 ? 0 : p)], b = rhs[i];
     out[i] = binary_apply(kind, a, b);
 }
 
 __global__ void k_binary_bwd_rhs(const float* __restrict__ lhs, const float* __restrict__ rhs, const float* __restrict__ gout,
-                                 float* __restrict__ grhs, int64_t total, int CL, int TL, int CR, int TR, int P, int kind, int acc) {
+                                 float* __restrict__ grhs, int64_t total, int CL, int TL, int CR, int TR, int P, int PL, int kind, int acc) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
     float g = gout[i];
@@ -216,35 +217,39 @@ __global__ void k_binary_bwd_rhs(const float* __restrict__ lhs, const float* __r
         int64_t n = r / CR;
         int cl, tl;
         bsrc(CL, TL, TR, c, t, CL == CR, cl, tl);
-        g *= binary_grad_rhs(kind, lhs[((n * CL + cl) * TL + tl) * P + p], rhs[i]);
+        g *= binary_grad_rhs(kind, lhs[((n * CL + cl) * TL + tl) * PL + (PL == 1 ? 0 : p)], rhs[i]);
     }
     grhs[i] = acc ? grhs[i] + g : g;
 }
 
-// One thread per LHS element sums over the RHS elements it was replicated onto.
+// One thread per LHS element sums over the RHS elements it was replicated onto (channels / taps, and all
+// pixels when the LHS is pooled), in a fixed order.
 __global__ void k_binary_bwd_lhs(const float* __restrict__ lhs, const float* __restrict__ rhs, const float* __restrict__ gout,
-                                 float* __restrict__ glhs, int64_t total, int CL, int TL, int CR, int TR, int P, int kind, int acc) {
+                                 float* __restrict__ glhs, int64_t total, int CL, int TL, int CR, int TR, int P, int PL, int kind, int acc) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
-    int p = (int)(i % P);
-    int64_t r = i / P;
+    int pl = (int)(i % PL);
+    int64_t r = i / PL;
     int tl = (int)(r % TL);
     r /= TL;
     int cl = (int)(r % CL);
     int64_t n = r / CL;
     const float a = lhs[i];
+    const int p0 = PL == 1 ? 0 : pl, p1 = PL == 1 ? P : pl + 1;
     float s = 0.f;
     if (CL == CR) {
-        for (int t = tl; t < TR; t += TL) {
-            int64_t j = ((n * CR + cl) * TR + t) * P + p;
-            s += kind == 0 ? gout[j] : gout[j] * binary_grad_lhs(kind, a, rhs[j]);
-        }
+        for (int t = tl; t < TR; t += TL)
+            for (int p = p0; p < p1; p++) {
+                int64_t j = ((n * CR + cl) * TR + t) * P + p;
+                s += kind == 0 ? gout[j] : gout[j] * binary_grad_lhs(kind, a, rhs[j]);
+            }
     } else {
         long long L = (long long)CL * TL, R = (long long)CR * TR;
-        for (long long f = (long long)cl * TL + tl; f < R; f += L) {
-            int64_t j = (n * R + f) * P + p;
-            s += kind == 0 ? gout[j] : gout[j] * binary_grad_lhs(kind, a, rhs[j]);
-        }
+        for (long long f = (long long)cl * TL + tl; f < R; f += L)
+            for (int p = p0; p < p1; p++) {
+                int64_t j = (n * R + f) * P + p;
+                s += kind == 0 ? gout[j] : gout[j] * binary_grad_lhs(kind, a, rhs[j]);
+            }
     }
     glhs[i] = acc ? glhs[i] + s : s;
 }
@@ -369,6 +374,64 @@ void narrow_bf16(const float* in, void* out, int64_t n, hipStream_t s) { LAUNCH(
 void fill_f32(float* out, float v, int64_t n, hipStream_t s) { LAUNCH(k_fill_f32, n, out, v, n); }
 void copy_f32(const float* in, float* out, int64_t n, hipStream_t s) { LAUNCH(k_copy_f32, n, in, out, n); }
 
+// Fold over the pixels: one workgroup per (n, c, t) plane.  Each thread folds a strided subset in pixel
+// order, then a tree over the 256 threads with a fixed pairing; max keeps the lowest pixel index among equals.
+__global__ __launch_bounds__(256) void k_pool_fwd(const float* __restrict__ in, float* __restrict__ out, int P, int kind) {
+    __shared__ float red[256];
+    const float* src = in + (int64_t)blockIdx.x * P;
+    const int tid = threadIdx.x;
+    float a = kind == 2 ? -INFINITY : 0.f;
+    for (int p = tid; p < P; p += 256) {
+        const float v = src[p];
+        if (kind == 2) a = v > a ? v : a;
+        else a += v;
+    }
+    red[tid] = a;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (tid < w) red[tid] = kind == 2 ? fmaxf(red[tid], red[tid + w]) : red[tid] + red[tid + w];
+        __syncthreads();
+    }
+    if (tid == 0) out[blockIdx.x] = kind == 1 ? red[0] / (float)P : red[0];
+}
+
+__global__ __launch_bounds__(256) void k_pool_bwd(const float* __restrict__ in, const float* __restrict__ gout, float* __restrict__ gin, int P,
+                                                  int kind, int acc) {
+    __shared__ float rv[256];
+    __shared__ int ri[256];
+    const float* src = in + (int64_t)blockIdx.x * P;
+    float* dst = gin + (int64_t)blockIdx.x * P;
+    const int tid = threadIdx.x;
+    float g = gout[blockIdx.x];
+    int best = -1;
+    if (kind == 2) {  // first maximal pixel of the plane
+        float a = -INFINITY;
+        int ai = 0x7fffffff;
+        for (int p = tid; p < P; p += 256) {
+            const float v = src[p];
+            if (v > a) { a = v; ai = p; }
+        }
+        rv[tid] = a;
+        ri[tid] = ai;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if (tid < w) {
+                const float b = rv[tid + w];
+                const int bi = ri[tid + w];
+                if (b > rv[tid] || (b == rv[tid] && bi < ri[tid])) { rv[tid] = b; ri[tid] = bi; }
+            }
+            __syncthreads();
+        }
+        best = ri[0];
+    } else if (kind == 1) {
+        g /= (float)P;
+    }
+    for (int p = tid; p < P; p += 256) {
+        const float v = kind == 2 ? (p == best ? g : 0.f) : g;
+        dst[p] = acc ? dst[p] + v : v;
+    }
+}
+
 void unfold_fwd(const float* in, float* out, int64_t NC, int Tin, int KH, int KW, int H, int W, hipStream_t s) {
     int64_t total = NC * Tin * KH * KW * H * W;
     LAUNCH(k_unfold_fwd, total, in, out, total, Tin, KH, KW, H, W);
@@ -400,20 +463,26 @@ void unary_fwd(const float* in, float* out, int64_t n, int kind, float lo, float
 void unary_bwd(const float* in, const float* gout, float* gin, int64_t n, int kind, float lo, float hi, int acc, hipStream_t s) {
     LAUNCH(k_unary_bwd, n, in, gout, gin, n, kind, lo, hi, acc);
 }
-void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int kind,
+void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int PL, int kind,
                 hipStream_t s) {
     int64_t total = N * CR * TR * P;
-    LAUNCH(k_binary_fwd, total, lhs, rhs, out, total, CL, TL, CR, TR, P, kind);
+    LAUNCH(k_binary_fwd, total, lhs, rhs, out, total, CL, TL, CR, TR, P, PL, kind);
 }
 void binary_bwd_rhs(const float* lhs, const float* rhs, const float* gout, float* grhs, int64_t N, int CL, int TL, int CR, int TR, int P,
-                    int kind, int acc, hipStream_t s) {
+                    int PL, int kind, int acc, hipStream_t s) {
     int64_t total = N * CR * TR * P;
-    LAUNCH(k_binary_bwd_rhs, total, lhs, rhs, gout, grhs, total, CL, TL, CR, TR, P, kind, acc);
+    LAUNCH(k_binary_bwd_rhs, total, lhs, rhs, gout, grhs, total, CL, TL, CR, TR, P, PL, kind, acc);
 }
 void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
-                    int kind, int acc, hipStream_t s) {
-    int64_t total = N * CL * TL * P;
-    LAUNCH(k_binary_bwd_lhs, total, lhs, rhs, gout, glhs, total, CL, TL, CR, TR, P, kind, acc);
+                    int PL, int kind, int acc, hipStream_t s) {
+    int64_t total = N * CL * TL * PL;
+    LAUNCH(k_binary_bwd_lhs, total, lhs, rhs, gout, glhs, total, CL, TL, CR, TR, P, PL, kind, acc);
+}
+void pool_fwd(const float* in, float* out, int64_t rows, int P, int kind, hipStream_t s) {
+    if (rows > 0) CANVAS_LAUNCH(k_pool_fwd, dim3((unsigned)rows), dim3(256), 0, s, in, out, P, kind);
+}
+void pool_bwd(const float* in, const float* gout, float* gin, int64_t rows, int P, int kind, int acc, hipStream_t s) {
+    if (rows > 0) CANVAS_LAUNCH(k_pool_bwd, dim3((unsigned)rows), dim3(256), 0, s, in, gout, gin, P, kind, acc);
 }
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s) {
     int64_t total = N * (axis_c == 2 ? 1 : (axis_c ? T : C)) * P;

@@ -21,18 +21,22 @@ void fc_dx(const float* gy, const float* wt, float* gx, int64_t N, int G, int Og
 void fc_dw(const float* gy, const float* x, float* dw, int64_t N, int G, int Og, int K, int P, hipStream_t s);
 void unary_fwd(const float* in, float* out, int64_t n, int kind, float lo, float hi, hipStream_t s);
 void unary_bwd(const float* in, const float* gout, float* gin, int64_t n, int kind, float lo, float hi, int acc, hipStream_t s);
-void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int kind,
+// P: pixels of the RHS / result; PL: pixels of the LHS (P, or 1 for a pooled LHS replicated over the pixels)
+void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int PL, int kind,
                 hipStream_t s);
 void binary_bwd_rhs(const float* lhs, const float* rhs, const float* gout, float* grhs, int64_t N, int CL, int TL, int CR, int TR, int P,
-                    int kind, int acc, hipStream_t s);
+                    int PL, int kind, int acc, hipStream_t s);
 void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
-                    int kind, int acc, hipStream_t s);
+                    int PL, int kind, int acc, hipStream_t s);
 // axis_c: 1 = over channels, 0 = over taps, 2 = over both jointly
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s);
 void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C, int T, int P, int axis_c, int acc,
                  hipStream_t s);
 void fold_fwd(const float* in, float* out, int64_t NC, int T, int P, int kind, hipStream_t s);
 void fold_bwd(const float* in, const float* gout, float* gin, int64_t NC, int T, int P, int kind, int acc, hipStream_t s);
+// Fold over the P pixels of each of `rows` planes (kind as fold: sum, avg, max with the first maximum taking the gradient)
+void pool_fwd(const float* in, float* out, int64_t rows, int P, int kind, hipStream_t s);
+void pool_bwd(const float* in, const float* gout, float* gin, int64_t rows, int P, int kind, int acc, hipStream_t s);
 
 }  // namespace ref
 }  // namespace canvas

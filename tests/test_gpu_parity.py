@@ -56,6 +56,12 @@ PRIMS = [
     ("output %0\n", []),
     ("%1 = unary %0 op=relu\n%2 = fc %0 groups=1 out=12\noutput %1\n", [(1, 12, 12)]),  # dead fc: zero dW
     ("%1 = unary %0 op=sin\noutput %1\n", []),
+    ("%1 = fold %0 op=avg axis=HW\noutput %1\n", []),
+    ("%1 = fold %0 op=max axis=HW\n%2 = binary %1 %0 op=sub\noutput %2\n", []),
+    ("%1 = unfold %0 kh=3 kw=1\n%2 = fold %1 op=sum axis=HW\n%3 = softmax %2 axis=T\n%4 = binary %3 %1 op=mul\n%5 = fold %4 op=sum\noutput %5\n", []),
+    # squeeze-and-excite: pooled descriptor -> FC -> gelu -> FC -> softmax over channels -> gate on x
+    ("%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=4\n%3 = unary %2 op=gelu\n%4 = fc %3 groups=2 out=12\n"
+     "%5 = softmax %4 axis=C\n%6 = binary %5 %0 op=mul\noutput %6\n", [(1, 4, 12), (2, 6, 2)]),
     ("%1 = unfold %0 kh=3 kw=3\n%2 = softmax %1 axis=CT\noutput %2\n", []),
     ("%1 = softmax %0 axis=CT\n%2 = binary %1 %0 op=mul\noutput %2\n", []),
     ("%1 = shift %0 dh=1 dw=0\n%2 = binary %0 %1 op=sub\noutput %2\n", []),

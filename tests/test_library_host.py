@@ -159,6 +159,29 @@ def test_lowering_selection(lib):
     assert _compile_info(wl.blob_involution(128, 7), (2, 128, 8, 8))[0] == 0
 
 
+def test_spatial_fold_shapes_and_legality(lib, oracle):
+    """fold axis=HW gives [N, C, T, 1, 1]; the shapes agree with the oracle; windows and reversed broadcasts are refused."""
+    H = wl.HEADER
+    se = H + ("%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=4\n%3 = unary %2 op=gelu\n%4 = fc %3 groups=1 out=12\n"
+              "%5 = softmax %4 axis=C\n%6 = binary %5 %0 op=mul\noutput %6\n")
+    ns, out, ws = oracle.infer(se, (2, 12, 6, 5))
+    h = B.canvas_dag_compile(se, (2, 12, 6, 5), B.CANVAS_BF16)
+    info = B.canvas_dag_query(h)
+    for k, s in enumerate(ns):
+        assert list(info.node_shape[k]) == [2] + s
+    assert list(info.node_shape[1]) == [2, 12, 1, 1, 1] and list(info.out_shape) == [2, 12, 1, 6, 5] and info.fused == 0
+    B.canvas_dag_destroy(h)
+    for body in ("%1 = fold %0 op=avg axis=HW\n%2 = unfold %1 kh=3 kw=3\noutput %2\n",
+                 "%1 = fold %0 op=avg axis=HW\n%2 = shift %1 dh=0 dw=1\noutput %2\n",
+                 "%1 = fold %0 op=avg axis=HW\n%2 = fold %1 op=max axis=HW\noutput %2\n",
+                 "%1 = fold %0 op=avg axis=HW\n%2 = binary %0 %1 op=add\noutput %2\n"):
+        with pytest.raises(B.CanvasError) as e:
+            B.canvas_dag_compile(H + body, (2, 12, 6, 5), B.CANVAS_BF16)
+        assert e.value.status == -3
+        with pytest.raises(Exception):
+            oracle.infer(H + body, (2, 12, 6, 5))
+
+
 def test_workspace_grows_with_batch_only_where_it_should(lib):
     """The config-2 lowering keeps only weight-gradient partials; the others keep activations."""
     small = _compile_info(wl.blob_shift_residual(64), (8, 64, 56, 56))[1]
