@@ -32,7 +32,8 @@
  *     %6 = fold %5 op=avg              (sum | avg | max; axis=T (default) folds the taps, axis=HW folds the
  *                                       pixels: the result is a [C, T, 1, 1] tensor, which FC, unary, softmax,
  *                                       fold over T and binary accept; as the LHS of a binary it is
- *                                       replicated over the pixels of a full-size RHS)
+ *                                       replicated over the pixels of a full-size RHS; axis=C groups=G folds the
+ *                                       C/G channels of each of G groups: the result has G channels)
  *     %7 = softmax %6 axis=C           (C | T | CT: over channels, over taps, or over both jointly)
  *     output %7
  * %0 is the input [N, C, H, W].
@@ -65,6 +66,7 @@ typedef struct {
     int C, T;           /* inferred shape [C, T, H, W] */
     int pooled;         /* 1: the spatial dims have been folded away, shape [C, T, 1, 1] */
     int axis_hw;        /* fold: 1 = over the pixels, 0 = over the taps */
+    int axis_c;         /* fold: 1 = over the C / groups channels of each of `groups` channel groups */
     int widx;           /* fc: index into the weight list */
 } Node;
 
@@ -293,10 +295,19 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 {
                     const char *ax = find_attr(tok, ntok, "axis");
                     if (ax && !strcmp(ax, "HW")) nd->axis_hw = 1;
-                    else if (ax && strcmp(ax, "T")) { set_err(err, errlen, "fold axis must be T or HW", lineno); goto done; }
+                    else if (ax && !strcmp(ax, "C")) nd->axis_c = 1;
+                    else if (ax && strcmp(ax, "T")) { set_err(err, errlen, "fold axis must be T, HW or C", lineno); goto done; }
                 }
                 nd->C = A->C;
-                if (nd->axis_hw) {
+                if (nd->axis_c) {
+                    nd->groups = 1;
+                    if (attr_int(tok, ntok, "groups", &nd->groups) < 0 || nd->groups < 1 || A->C % nd->groups) {
+                        set_err(err, errlen, "fold axis=C: groups must divide the channels", lineno);
+                        goto done;
+                    }
+                    nd->C = nd->groups;
+                    nd->T = A->T;
+                } else if (nd->axis_hw) {
                     if (A->pooled) { set_err(err, errlen, "fold axis=HW: the spatial dims are already folded", lineno); goto done; }
                     nd->T = A->T;
                     nd->pooled = 1;
@@ -454,6 +465,22 @@ static void fwd_softmax(const Dag *d, const Node *nd, const double *in, double *
 static void fwd_fold(const Dag *d, const Node *nd, const double *in, double *out) {
     const Node *A = &d->node[nd->a];
     int P = node_P(d, A), T = A->T, c, t, p;
+    if (nd->axis_c) {  /* over the channels of each group: out[g, t, p] from in[g*Cg + c', t, p] */
+        int Cg = A->C / nd->groups, g;
+        for (g = 0; g < nd->groups; g++)
+            for (t = 0; t < T; t++)
+                for (p = 0; p < P; p++) {
+                    double acc = in[(((size_t)g * Cg) * T + t) * P + p];
+                    for (c = 1; c < Cg; c++) {
+                        double v = in[(((size_t)g * Cg + c) * T + t) * P + p];
+                        if (nd->kind == FOLD_MAX) { if (v > acc) acc = v; }
+                        else acc += v;
+                    }
+                    if (nd->kind == FOLD_AVG) acc /= Cg;
+                    out[((size_t)g * T + t) * P + p] = acc;
+                }
+        return;
+    }
     if (nd->axis_hw) {  /* over the pixels of every (channel, tap) plane */
         for (c = 0; c < nd->C * T; c++) {
             double acc = in[(size_t)c * P];
@@ -598,6 +625,24 @@ static void bwd_softmax(const Dag *d, const Node *nd, const double *out, const d
 static void bwd_fold(const Dag *d, const Node *nd, const double *in, const double *gout, double *gin) {
     const Node *A = &d->node[nd->a];
     int P = node_P(d, A), T = A->T, c, t, p;
+    if (nd->axis_c) {  /* max: to the first maximal channel of the group only */
+        int Cg = A->C / nd->groups, g;
+        for (g = 0; g < nd->groups; g++)
+            for (t = 0; t < T; t++)
+                for (p = 0; p < P; p++) {
+                    double gg = gout[((size_t)g * T + t) * P + p];
+                    if (nd->kind == FOLD_MAX) {
+                        int best = 0;
+                        for (c = 1; c < Cg; c++)
+                            if (in[(((size_t)g * Cg + c) * T + t) * P + p] > in[(((size_t)g * Cg + best) * T + t) * P + p]) best = c;
+                        gin[(((size_t)g * Cg + best) * T + t) * P + p] += gg;
+                    } else {
+                        if (nd->kind == FOLD_AVG) gg /= Cg;
+                        for (c = 0; c < Cg; c++) gin[(((size_t)g * Cg + c) * T + t) * P + p] += gg;
+                    }
+                }
+        return;
+    }
     if (nd->axis_hw) {  /* max: to the first maximal pixel (lowest flat index) only */
         for (c = 0; c < nd->C * T; c++) {
             double g = gout[c];

@@ -155,6 +155,7 @@ FD_BODIES = [
     ("%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=2\n%3 = unary %2 op=gelu\n%4 = fc %3 groups=1 out=4\n"
      "%5 = softmax %4 axis=C\n%6 = binary %5 %0 op=mul\noutput %6\n", [(1, 2, 4), (1, 4, 2)]),
     ("%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=max axis=HW\n%3 = binary %2 %1 op=sub\n%4 = fold %3 op=avg\noutput %4\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=max axis=C groups=2\n%3 = fold %2 op=avg\n%4 = binary %3 %0 op=mul\noutput %4\n", []),
     ("%1 = unary %0 op=sin\noutput %1\n", []),
     ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=sin\n%3 = binary %0 %2 op=sub\n%4 = fold %3 op=sum\noutput %4\n", []),
     ("%1 = shift %0 dh=1 dw=0\n%2 = unary %1 op=gelu\n%3 = binary %2 %0 op=max\noutput %3\n", []),
@@ -314,13 +315,49 @@ def test_pooled_tensor_is_replicated_over_pixels(oracle):
     np.testing.assert_allclose(r["dx"], np.broadcast_to(((gy[:, :, 0, 0] @ w[0]) / 20.0)[:, :, None, None], x.shape), atol=1e-14)
 
 
+def test_channel_group_fold(oracle):
+    """fold axis=C groups=G: sum / mean / max over the C/G channels of each group; G channels remain."""
+    rng = np.random.default_rng(42)
+    x = rng.standard_normal((2, 6, 3, 4))
+    xg = x.reshape(2, 3, 2, 3, 4)
+    for op, fn in (("sum", np.sum), ("avg", np.mean), ("max", np.max)):
+        y = run1(oracle, f"%1 = fold %0 op={op} axis=C groups=3\noutput %1\n", x)["y"]
+        assert y.shape == (2, 3, 3, 4)
+        np.testing.assert_allclose(y, fn(xg, axis=2), atol=1e-15)
+        y1 = run1(oracle, f"%1 = fold %0 op={op} axis=C\noutput %1\n", x)["y"]  # one group: all channels
+        np.testing.assert_allclose(y1[:, 0], fn(x, axis=1), atol=1e-15)
+        # as many groups as channels: the identity
+        np.testing.assert_array_equal(run1(oracle, f"%1 = fold %0 op={op} axis=C groups=6\noutput %1\n", x)["y"], x)
+    # with taps: every tap is folded on its own
+    u = run1(oracle, "%1 = unfold %0 kh=1 kw=3\noutput %1\n", x)["y"]
+    y = run1(oracle, "%1 = unfold %0 kh=1 kw=3\n%2 = fold %1 op=avg axis=C groups=2\noutput %2\n", x)["y"]
+    np.testing.assert_allclose(y, u.reshape(2, 2, 3, 3, 3, 4).mean(axis=2), atol=1e-15)
+    # gradients: sum replicates, avg divides by the group size, max goes to the first maximal channel
+    g = rng.standard_normal((2, 3, 3, 4))
+    r = run1(oracle, "%1 = fold %0 op=sum axis=C groups=3\noutput %1\n", x, (), g)
+    np.testing.assert_array_equal(r["dx"], np.repeat(g, 2, axis=1))
+    r = run1(oracle, "%1 = fold %0 op=avg axis=C groups=3\noutput %1\n", x, (), g)
+    np.testing.assert_allclose(r["dx"], np.repeat(g, 2, axis=1) / 2.0, atol=1e-16)
+    xt = x.copy()
+    xt[:, 1] = xt[:, 0]  # a tie inside group 0: the first channel takes it
+    r = run1(oracle, "%1 = fold %0 op=max axis=C groups=3\noutput %1\n", xt, (), g)
+    first = np.argmax(xt.reshape(2, 3, 2, 3, 4), axis=2)
+    exp = np.zeros((2, 3, 2, 3, 4))
+    for c in range(2):
+        exp[:, :, c] = np.where(first == c, g, 0.0)
+    np.testing.assert_array_equal(r["dx"], exp.reshape(2, 6, 3, 4))
+    assert (r["dx"][:, 1] == 0).all()
+    with pytest.raises(Exception):
+        run1(oracle, "%1 = fold %0 op=avg axis=C groups=4\noutput %1\n", x)
+
+
 def test_spatial_fold_legality(oracle):
     x = np.zeros((1, 4, 3, 3))
     for body in ("%1 = fold %0 op=avg axis=HW\n%2 = unfold %1 kh=3 kw=3\noutput %2\n",      # no window without pixels
                  "%1 = fold %0 op=avg axis=HW\n%2 = shift %1 dh=0 dw=1\noutput %2\n",
                  "%1 = fold %0 op=avg axis=HW\n%2 = fold %1 op=max axis=HW\noutput %2\n",       # already folded
                  "%1 = fold %0 op=avg axis=HW\n%2 = binary %0 %1 op=add\noutput %2\n",          # LHS larger than RHS
-                 "%1 = fold %0 op=avg axis=C\noutput %1\n"):
+                 "%1 = fold %0 op=avg axis=X\noutput %1\n"):
         with pytest.raises(Exception):
             run1(oracle, body, x)
 
