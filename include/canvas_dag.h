@@ -17,7 +17,7 @@
  *     %3 = unary %2 op=gelu            relu | abs | gelu | sin | expclip lo=<f> hi=<f>
  *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
  *     %5 = binary %0 %4 op=mul         first operand LHS, second RHS; add | sub | mul | min | max
- *     %6 = fold %5 op=avg              sum | avg | max [axis=T | HW]
+ *     %6 = fold %5 op=avg              sum | avg | max [axis=T | HW | C [groups=<G>]]
  *     %7 = softmax %6 axis=C           C | T | CT
  *     output %7
  *
@@ -44,7 +44,9 @@
  *            pixels are folded instead (global pooling): the result is
  *            [N, C, T, 1, 1]; fc, unary, softmax, fold over T and binary accept
  *            such a tensor (unfold and shift do not), and as the LHS of a
- *            binary it is replicated over the pixels of a full-size RHS.
+ *            binary it is replicated over the pixels of a full-size RHS.  With
+ *            axis=C groups=G (default 1) the C/G channels of each of G channel
+ *            groups are folded: G channels remain.
  *   backward exact vector-Jacobian products of the above; relu'(0) = 0,
  *            sign(0) = 0, expclip has zero gradient outside the open interval; a
  *            tie of binary min / max sends the gradient to the LHS.

@@ -26,6 +26,7 @@ struct Node {
     int kind = 0;                // UnaryKind / BinaryKind / AxisKind / FoldKind
     float lo = 0.f, hi = 0.f;    // expclip bounds
     int axis_hw = 0;             // fold: 1 = over the pixels (the result is pooled), 0 = over the taps
+    int axis_c = 0;              // fold: 1 = over the C / groups channels of each of `groups` channel groups
     bool pooled = false;         // the spatial dims have been folded away: shape [N, C, T, 1, 1]
     int C = 0, T = 1;            // inferred shape
     int widx = -1;               // fc: index into the weight list

@@ -49,7 +49,7 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
     }
     // LHS [TV, 1] onto RHS [C, TV]: with C != TV the broadcast index (c*TV + t) % TV = t pairs channel t with tap t
     if (bin.kind != kMul || bin.a != alast || bin.b != iunf || C == TV) return nullptr;
-    if (fold.a != ibin || (fold.kind != kSum && fold.kind != kAvg)) return nullptr;
+    if (fold.a != ibin || fold.axis_c || fold.axis_hw || (fold.kind != kSum && fold.kind != kAvg)) return nullptr;
     if (fc2.a != ifold || dag.out != ifc2) return nullptr;
     // every intermediate has exactly the one consumer of the pattern
     for (int k = 1; k < n; k++) {

@@ -205,7 +205,12 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             }
             break;
         case Op::Fold:
-            if (nd.axis_hw) {
+            if (nd.axis_c) {
+                const int64_t TP = (int64_t)A.T * dag.Pk(nd.a);
+                const int Cg = A.C / nd.groups;
+                L.name = "node_cfold_fwd";
+                L.run = [=](const RunArgs& a) { ref::cfold_fwd(val(a, nd.a), valw(a, k), N * nd.groups, Cg, TP, nd.kind, a.stream); };
+            } else if (nd.axis_hw) {
                 L.name = "node_pool_fwd";
                 L.run = [=](const RunArgs& a) { ref::pool_fwd(val(a, nd.a), valw(a, k), N * A.C * A.T, P, nd.kind, a.stream); };
             } else {
@@ -347,7 +352,12 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             break;
         case Op::Fold:
             L.bytes += 4.0 * dag.numel(nd.a);
-            if (nd.axis_hw) {
+            if (nd.axis_c) {
+                const int64_t TP = (int64_t)A.T * dag.Pk(nd.a);
+                const int Cg = A.C / nd.groups;
+                L.name = "node_cfold_bwd";
+                L.run = [=](const RunArgs& a) { ref::cfold_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * nd.groups, Cg, TP, nd.kind, acc, a.stream); };
+            } else if (nd.axis_hw) {
                 L.name = "node_pool_bwd";
                 L.run = [=](const RunArgs& a) { ref::pool_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * A.C * A.T, P, nd.kind, acc, a.stream); };
             } else {

@@ -75,7 +75,7 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
         M.bin = b.kind == kMul ? 1 : 0;
         prev = k++;
     }
-    while (k < n && dag.nodes[k].op == Op::Fold && dag.nodes[dag.nodes[k].a].T == 1) {  // a fold over one tap is the identity
+    while (k < n && dag.nodes[k].op == Op::Fold && !dag.nodes[k].axis_c && !dag.nodes[k].axis_hw && dag.nodes[dag.nodes[k].a].T == 1) {  // a fold over one tap is the identity
         if (dag.nodes[k].a != prev) return nullptr;
         prev = k++;
     }

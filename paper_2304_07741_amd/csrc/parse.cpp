@@ -198,9 +198,16 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             else return fail(err, lineno, "unknown fold op '" + it->second + "'", kUnknownOp);
             auto ax = l.attr.find("axis");
             if (ax != l.attr.end() && ax->second == "HW") nd.axis_hw = 1;
-            else if (ax != l.attr.end() && ax->second != "T") return fail(err, lineno, "fold axis must be T or HW", kUnknownOp);
+            else if (ax != l.attr.end() && ax->second == "C") nd.axis_c = 1;
+            else if (ax != l.attr.end() && ax->second != "T") return fail(err, lineno, "fold axis must be T, HW or C", kUnknownOp);
             nd.C = A.C;
-            if (nd.axis_hw) {
+            if (nd.axis_c) {
+                nd.groups = 1;
+                if (!get_int(l, "groups", nd.groups, false, present)) return fail(err, lineno, "fold axis=C: bad groups=", kInvalidBlob);
+                if (nd.groups < 1 || A.C % nd.groups) return fail(err, lineno, "fold axis=C: groups must divide the channels", kShapeMismatch);
+                nd.C = nd.groups;
+                nd.T = A.T;
+            } else if (nd.axis_hw) {
                 if (A.pooled) return fail(err, lineno, "fold axis=HW: the spatial dims are already folded", kShapeMismatch);
                 nd.T = A.T;
                 nd.pooled = true;

@@ -374,6 +374,47 @@ void narrow_bf16(const float* in, void* out, int64_t n, hipStream_t s) { LAUNCH(
 void fill_f32(float* out, float v, int64_t n, hipStream_t s) { LAUNCH(k_fill_f32, n, out, v, n); }
 void copy_f32(const float* in, float* out, int64_t n, hipStream_t s) { LAUNCH(k_copy_f32, n, in, out, n); }
 
+// Fold over the Cg channels of each channel group: one thread per output element (n, g, t, p); the channels
+// of a group are Cg planes `stride` = T*P elements apart.
+__global__ void k_cfold_fwd(const float* __restrict__ in, float* __restrict__ out, int64_t total, int Cg, int64_t stride, int kind) {
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= total) return;
+    const int64_t ng = i / stride, rest = i - ng * stride;  // (n, g) and (t, p)
+    const float* src = in + ng * Cg * stride + rest;
+    float a = src[0];
+    for (int c = 1; c < Cg; c++) {
+        float v = src[(int64_t)c * stride];
+        if (kind == 2) a = v > a ? v : a;
+        else a += v;
+    }
+    if (kind == 1) a /= (float)Cg;
+    out[i] = a;
+}
+
+__global__ void k_cfold_bwd(const float* __restrict__ in, const float* __restrict__ gout, float* __restrict__ gin, int64_t total, int Cg,
+                            int64_t stride, int kind, int acc) {
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= total) return;
+    const int64_t ng = i / stride, rest = i - ng * stride;
+    const float* src = in + ng * Cg * stride + rest;
+    float* dst = gin + ng * Cg * stride + rest;
+    float g = gout[i];
+    int best = 0;
+    if (kind == 2) {
+        float a = src[0];
+        for (int c = 1; c < Cg; c++) {
+            float v = src[(int64_t)c * stride];
+            if (v > a) { a = v; best = c; }
+        }
+    } else if (kind == 1) {
+        g /= (float)Cg;
+    }
+    for (int c = 0; c < Cg; c++) {
+        float v = kind == 2 ? (c == best ? g : 0.f) : g;
+        dst[(int64_t)c * stride] = acc ? dst[(int64_t)c * stride] + v : v;
+    }
+}
+
 // Fold over the pixels: one workgroup per (n, c, t) plane.  Each thread folds a strided subset in pixel
 // order, then a tree over the 256 threads with a fixed pairing; max keeps the lowest pixel index among equals.
 __global__ __launch_bounds__(256) void k_pool_fwd(const float* __restrict__ in, float* __restrict__ out, int P, int kind) {
@@ -477,6 +518,14 @@ void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float
                     int PL, int kind, int acc, hipStream_t s) {
     int64_t total = N * CL * TL * PL;
     LAUNCH(k_binary_bwd_lhs, total, lhs, rhs, gout, glhs, total, CL, TL, CR, TR, P, PL, kind, acc);
+}
+void cfold_fwd(const float* in, float* out, int64_t NG, int Cg, int64_t TP, int kind, hipStream_t s) {
+    int64_t total = NG * TP;
+    LAUNCH(k_cfold_fwd, total, in, out, total, Cg, TP, kind);
+}
+void cfold_bwd(const float* in, const float* gout, float* gin, int64_t NG, int Cg, int64_t TP, int kind, int acc, hipStream_t s) {
+    int64_t total = NG * TP;
+    LAUNCH(k_cfold_bwd, total, in, gout, gin, total, Cg, TP, kind, acc);
 }
 void pool_fwd(const float* in, float* out, int64_t rows, int P, int kind, hipStream_t s) {
     if (rows > 0) CANVAS_LAUNCH(k_pool_fwd, dim3((unsigned)rows), dim3(256), 0, s, in, out, P, kind);

@@ -34,6 +34,9 @@ void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C
                  hipStream_t s);
 void fold_fwd(const float* in, float* out, int64_t NC, int T, int P, int kind, hipStream_t s);
 void fold_bwd(const float* in, const float* gout, float* gin, int64_t NC, int T, int P, int kind, int acc, hipStream_t s);
+// Fold over the Cg channels of each of NG (image, group) pairs; a channel is TP = taps * pixels elements
+void cfold_fwd(const float* in, float* out, int64_t NG, int Cg, int64_t TP, int kind, hipStream_t s);
+void cfold_bwd(const float* in, const float* gout, float* gin, int64_t NG, int Cg, int64_t TP, int kind, int acc, hipStream_t s);
 // Fold over the P pixels of each of `rows` planes (kind as fold: sum, avg, max with the first maximum taking the gradient)
 void pool_fwd(const float* in, float* out, int64_t rows, int P, int kind, hipStream_t s);
 void pool_bwd(const float* in, const float* gout, float* gin, int64_t rows, int P, int kind, int acc, hipStream_t s);

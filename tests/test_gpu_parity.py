@@ -57,6 +57,9 @@ PRIMS = [
     ("%1 = unary %0 op=relu\n%2 = fc %0 groups=1 out=12\noutput %1\n", [(1, 12, 12)]),  # dead fc: zero dW
     ("%1 = unary %0 op=sin\noutput %1\n", []),
     ("%1 = fold %0 op=avg axis=HW\noutput %1\n", []),
+    ("%1 = fold %0 op=max axis=C groups=3\noutput %1\n", []),
+    ("%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=avg axis=C groups=4\n%3 = fold %2 op=sum\n%4 = fc %3 groups=2 out=12\n%5 = binary %4 %0 op=add\noutput %5\n", [(2, 6, 2)]),
+    ("%1 = fold %0 op=sum axis=C\n%2 = unary %1 op=gelu\n%3 = binary %2 %0 op=mul\noutput %3\n", []),
     ("%1 = fold %0 op=max axis=HW\n%2 = binary %1 %0 op=sub\noutput %2\n", []),
     ("%1 = unfold %0 kh=3 kw=1\n%2 = fold %1 op=sum axis=HW\n%3 = softmax %2 axis=T\n%4 = binary %3 %1 op=mul\n%5 = fold %4 op=sum\noutput %5\n", []),
     # squeeze-and-excite: pooled descriptor -> FC -> gelu -> FC -> softmax over channels -> gate on x
