@@ -2,6 +2,7 @@
 of its dominant kernel and the CPU oracle timed beside it.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload shift_residual|involution|sampled_cC_hH]
+    python bench.py --infer BATCH [--workload ...]     (forward-only latency of the inference plan, not the headline)
 
 One step = one forward + one backward of the whole micro-DAG over one batch resident in HBM.  Buffer
 sets are rotated so that consecutive steps do not find their operands in the 256 MB last-level cache.
@@ -46,17 +47,77 @@ def measured_traffic(workload, kernel):
     return (fetch + write) * 1024.0
 
 
-def make_case(name):
+def make_case(name, batch=None):
     from paper_2304_07741_amd import workloads as wl
 
+    kw = {} if batch is None else {"N": int(batch)}
     if name == "shift_residual":
-        return wl.config2()
+        return wl.config2(**kw)
     if name == "involution":
-        return wl.config3()
+        return wl.config3(**kw)
     if name.startswith("sampled_c"):
         c, h = name[len("sampled_c"):].split("_h")
-        return wl.config4(int(c), int(h))
+        return wl.config4(int(c), int(h), **kw)
     raise SystemExit(f"unknown workload {name}")
+
+
+def infer_latency(args):
+    """Forward-only latency of the inference plan at a small batch: eager calls and replays of one HIP graph
+    that holds the forward launches (the library neither allocates nor synchronises, so it can be captured)."""
+    import torch
+
+    from paper_2304_07741_amd import binding as B
+    from paper_2304_07741_amd import harness
+
+    case = make_case(args.workload, args.infer)
+    flags = (B.CANVAS_OPT_NO_FUSION if args.no_fusion else 0) | B.CANVAS_OPT_INFERENCE
+    r = harness.DagRunner(case["blob"], case["shape"], case["dtype"], flags)
+    r.load(case["x"], case["weights"])
+    r.prepare()
+    for _ in range(args.warmup):
+        r.forward()
+    torch.cuda.synchronize()
+
+    def timed(fn):
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t0) / args.steps
+
+    eager_ms = timed(r.forward)
+    y_eager = r.y.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        r.forward()
+        with torch.cuda.graph(g, stream=side):
+            r.forward()
+    torch.cuda.synchronize()
+    r.y.zero_()
+    g.replay()
+    torch.cuda.synchronize()
+    same = bool(torch.equal(r.y, y_eager))
+    graph_ms = timed(g.replay)
+    B.canvas_dag_set_timing(r.handle, 1)
+    nf = r.info.n_launches_fwd
+    acc = [0.0] * nf
+    for _ in range(20):
+        r.forward()
+        for k, ms in enumerate(B.canvas_dag_get_timing(r.handle, 0, nf)):
+            acc[k] += ms / 20
+    B.canvas_dag_set_timing(r.handle, 0)
+    N = case["shape"][0]
+    print(json.dumps({
+        "metric": "micro-DAG forward latency, inference plan", "value": eager_ms, "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": eager_ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": case["dtype"], "data": "synthetic",
+        "config": {"workload": f"{case['name']} N={N} C={case['shape'][1]} H=W={case['shape'][2]} {case['dtype']} (seed {case['seed']})",
+                   "fused": bool(r.info.fused), "launches_fwd": nf, "launches_prepare": r.info.n_launches_prepare},
+        "eager_ms": eager_ms, "graph_ms": graph_ms, "graph_equals_eager": same, "kernel_sum_ms": sum(acc),
+        "images_per_s_graph": N / (graph_ms * 1e-3),
+        "kernels": [{"name": d["name"], "ms": round(acc[k], 5)} for k, d in enumerate(r.launches(0))]}))
 
 
 def cpu_baseline(case, budget_s=12.0):
@@ -91,9 +152,13 @@ def main():
     ap.add_argument("--workload", default="shift_residual")
     ap.add_argument("--no-fusion", action="store_true", help="per-node lowering (for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--infer", type=int, default=0, metavar="BATCH",
+                    help="instead of the training step: forward-only latency of the inference plan at this batch size")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
+    if args.infer:
+        return infer_latency(args)
 
     import torch
 

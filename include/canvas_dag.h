@@ -85,6 +85,8 @@ typedef enum {
 
 /* Option flags for canvas_dag_compile. */
 #define CANVAS_OPT_NO_FUSION 1u /* one kernel per node, fp32 intermediates (reference lowering) */
+#define CANVAS_OPT_INFERENCE 2u /* forward-only plan: no backward, weight repacking / widening taken out of
+                                   canvas_dag_forward into canvas_dag_prepare (run once per set of weights) */
 
 typedef struct canvas_options {
     uint32_t flags;
@@ -97,7 +99,8 @@ typedef struct canvas_dag_info {
     int32_t n_weights;                        /* number of fc nodes */
     int32_t n_launches_fwd, n_launches_bwd;   /* kernels enqueued per call */
     int32_t fused;                            /* 1 when a fused lowering was chosen, 0 for the per-node lowering */
-    int32_t reserved0[2];
+    int32_t n_launches_prepare;               /* inference plans: kernels canvas_dag_prepare enqueues, else 0 */
+    int32_t reserved0[1];
     int64_t out_shape[5];                     /* N, C, T, H, W */
     int64_t node_shape[CANVAS_MAX_NODES][5];  /* N, C, T, H, W per node */
     int64_t weight_shape[CANVAS_MAX_NODES][3];/* G, C_out/G, (C_in/G)*T per fc node, in node order */
@@ -141,12 +144,21 @@ int canvas_dag_launch_desc(const canvas_dag* dag, int backward, int idx, canvas_
 int canvas_dag_forward(canvas_dag* dag, const void* x, const void* const* weights, void* y, void* workspace,
                        size_t workspace_bytes, void* stream);
 
+/* Inference plans (CANVAS_OPT_INFERENCE) only: enqueue the weight-only work of the forward pass
+ * (repacking into MFMA operand order, widening) on `stream`; its results live in the workspace, so
+ * call it once before the first canvas_dag_forward on that workspace and again whenever the weights
+ * change.  A no-op for plans that have no such work.  Errors: BAD_ARG (also: not an inference plan),
+ * WORKSPACE_TOO_SMALL, HIP_ERROR.  Callers: serving loops at batch 1-8 where the per-call repacking
+ * launches would dominate the latency. */
+int canvas_dag_prepare(canvas_dag* dag, const void* const* weights, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Enqueue the backward pass of the preceding canvas_dag_forward on the same
  * x, weights and workspace.
  *   dy       like y, dtype dt, read
  *   dx       like x, dtype dt, written
  *   dweights host array of n_weights device pointers, fp32, shaped like the weights, overwritten
- * Deterministic: no floating-point atomics, two runs give identical bits. */
+ * Deterministic: no floating-point atomics, two runs give identical bits.
+ * Errors as canvas_dag_forward; UNSUPPORTED for an inference plan. */
 int canvas_dag_backward(canvas_dag* dag, const void* x, const void* const* weights, const void* dy, void* dx,
                         void* const* dweights, void* workspace, size_t workspace_bytes, void* stream);
 

@@ -12,11 +12,12 @@ LIB_PATH = os.path.join(_HERE, "libcanvas_dag.so")
 
 CANVAS_F32, CANVAS_BF16 = 0, 1
 CANVAS_OPT_NO_FUSION = 1
+CANVAS_OPT_INFERENCE = 2
 CANVAS_MAX_NODES = 64
 STATUS = {0: "OK", -1: "INVALID_BLOB", -2: "UNKNOWN_OP", -3: "SHAPE_MISMATCH", -4: "BAD_ARG",
           -5: "WORKSPACE_TOO_SMALL", -6: "UNSUPPORTED", -7: "HIP_ERROR"}
 EXPORTS = ["canvas_dag_compile", "canvas_dag_query", "canvas_dag_launch_desc", "canvas_dag_forward",
-           "canvas_dag_backward", "canvas_dag_set_timing", "canvas_dag_get_timing", "canvas_dag_destroy",
+           "canvas_dag_backward", "canvas_dag_prepare", "canvas_dag_set_timing", "canvas_dag_get_timing", "canvas_dag_destroy",
            "canvas_last_error"]
 
 
@@ -28,7 +29,7 @@ class CanvasDagInfo(ctypes.Structure):
     _fields_ = [
         ("n_nodes", ctypes.c_int32), ("out_node", ctypes.c_int32), ("n_weights", ctypes.c_int32),
         ("n_launches_fwd", ctypes.c_int32), ("n_launches_bwd", ctypes.c_int32), ("fused", ctypes.c_int32),
-        ("reserved0", ctypes.c_int32 * 2),
+        ("n_launches_prepare", ctypes.c_int32), ("reserved0", ctypes.c_int32 * 1),
         ("out_shape", ctypes.c_int64 * 5),
         ("node_shape", (ctypes.c_int64 * 5) * CANVAS_MAX_NODES),
         ("weight_shape", (ctypes.c_int64 * 3) * CANVAS_MAX_NODES),
@@ -65,6 +66,7 @@ def load():
         lib.canvas_dag_launch_desc.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(CanvasLaunchDesc)]
         lib.canvas_dag_forward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, sz, vp]
         lib.canvas_dag_backward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, ctypes.POINTER(vp), vp, sz, vp]
+        lib.canvas_dag_prepare.argtypes = [vp, ctypes.POINTER(vp), vp, sz, vp]
         lib.canvas_dag_set_timing.argtypes = [vp, ctypes.c_int]
         lib.canvas_dag_get_timing.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.c_int]
         lib.canvas_dag_destroy.argtypes = [vp]
@@ -124,6 +126,12 @@ def canvas_dag_backward(handle, x, weights, dy, dx, dweights, workspace):
     _check(load().canvas_dag_backward(handle, x.data_ptr(), _ptrs(weights), dy.data_ptr(), dx.data_ptr(),
                                       _ptrs(dweights), workspace.data_ptr(),
                                       workspace.numel() * workspace.element_size(), _stream()))
+
+
+def canvas_dag_prepare(handle, weights, workspace):
+    """Inference plans only: derive what depends on the weights alone (packed / widened copies) into the workspace."""
+    _check(load().canvas_dag_prepare(handle, _ptrs(weights), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream()))
 
 
 def canvas_dag_set_timing(handle, enable):

@@ -14,6 +14,7 @@
 struct canvas_dag {
     canvas::Dag dag;
     bool bf16 = false;
+    bool inference = false;
     std::unique_ptr<canvas::Lowering> low;
     canvas_dag_info info;
     bool timing = false;
@@ -95,7 +96,7 @@ int canvas_dag_compile(const void* blob, size_t blob_len, const int64_t in_shape
             flags = opt->flags;
             for (uint32_t r : opt->reserved)
                 if (r) return set_err(CANVAS_BAD_ARG, "reserved option fields must be zero");
-            if (flags & ~CANVAS_OPT_NO_FUSION) return set_err(CANVAS_BAD_ARG, "unknown option flag");
+            if (flags & ~(CANVAS_OPT_NO_FUSION | CANVAS_OPT_INFERENCE)) return set_err(CANVAS_BAD_ARG, "unknown option flag");
         }
         auto d = std::make_unique<canvas_dag>();
         std::string err;
@@ -103,6 +104,8 @@ int canvas_dag_compile(const void* blob, size_t blob_len, const int64_t in_shape
         if (rc != 0) return set_err(rc, err);
         d->bf16 = dt == CANVAS_BF16;
         d->low = canvas::lower(d->dag, d->bf16, (flags & CANVAS_OPT_NO_FUSION) != 0);
+        d->inference = (flags & CANVAS_OPT_INFERENCE) != 0;
+        if (d->inference) canvas::make_inference_plan(*d->low);
 
         canvas_dag_info& I = d->info;
         std::memset(&I, 0, sizeof I);
@@ -112,6 +115,7 @@ int canvas_dag_compile(const void* blob, size_t blob_len, const int64_t in_shape
         I.n_weights = g.n_weights;
         I.n_launches_fwd = (int32_t)d->low->fwd.size();
         I.n_launches_bwd = (int32_t)d->low->bwd.size();
+        I.n_launches_prepare = (int32_t)d->low->prep.size();
         I.fused = d->low->fused ? 1 : 0;
         const double esz = d->bf16 ? 2.0 : 4.0;
         double wbytes = 0, wcount = 0;
@@ -175,8 +179,24 @@ int canvas_dag_forward(canvas_dag* dag, const void* x, const void* const* weight
     return finish_launches();
 }
 
+int canvas_dag_prepare(canvas_dag* dag, const void* const* weights, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!dag) return set_err(CANVAS_BAD_ARG, "null dag handle");
+    if (!dag->inference) return set_err(CANVAS_BAD_ARG, "canvas_dag_prepare needs a plan compiled with CANVAS_OPT_INFERENCE");
+    if (dag->low->prep.empty()) return CANVAS_OK;
+    int rc = check_common(dag, workspace, weights, workspace, workspace_bytes);  // (no x here: the workspace stands in for the pointer check)
+    if (rc) return rc;
+    canvas::RunArgs a;
+    a.w = weights;
+    a.ws = (char*)workspace;
+    a.stream = (hipStream_t)stream;
+    (void)hipGetLastError();
+    for (const auto& l : dag->low->prep) l.run(a);
+    return finish_launches();
+}
+
 int canvas_dag_backward(canvas_dag* dag, const void* x, const void* const* weights, const void* dy, void* dx,
                         void* const* dweights, void* workspace, size_t workspace_bytes, void* stream) {
+    if (dag && dag->inference) return set_err(CANVAS_UNSUPPORTED, "this plan was compiled for inference: it has no backward pass");
     int rc = check_common(dag, x, weights, workspace, workspace_bytes);
     if (rc) return rc;
     if (!dy || !aligned16(dy) || !dx || !aligned16(dx)) return set_err(CANVAS_BAD_ARG, "dy and dx must be non-null, 16-byte aligned device pointers");

@@ -17,7 +17,7 @@ void emit_fc(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, cons
         if (!identity)
             list.push_back({name + "_pack_w", 2.0 * nw + 2.0 * gfctm::packed_elems(T), 0, [=](const RunArgs& a) {
                                 gfctm::pack_weights((const uint16_t*)a.w[widx], (uint16_t*)(a.ws + opk), T, transposed, a.stream);
-                            }});
+                            }, true});
         list.push_back({name, bytes, flops, [=](const RunArgs& a) {
                             gfctm::Params Q = T;
                             Q.src = (const uint16_t*)src.ptr(a);

@@ -12,4 +12,11 @@ std::unique_ptr<Lowering> lower(const Dag& dag, bool bf16, bool no_fusion) {
     return lower_per_node(dag, bf16);
 }
 
+void make_inference_plan(Lowering& low) {
+    std::vector<Launch> keep;
+    for (auto& l : low.fwd) (l.prep ? low.prep : keep).push_back(std::move(l));
+    low.fwd = std::move(keep);
+    low.bwd.clear();
+}
+
 }  // namespace canvas

@@ -138,7 +138,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             if (lay.wf[i] < 0) continue;  // MFMA fc nodes read the bf16 weights as they are
             int64_t nw = wnumel[i];
             int64_t o = lay.wf[i];
-            low->fwd.push_back({"widen_w", nw * 6.0, 0, [=](const RunArgs& a) { ref::widen_bf16(a.w[i], (float*)(a.ws + o), nw, a.stream); }});
+            low->fwd.push_back({"widen_w", nw * 6.0, 0, [=](const RunArgs& a) { ref::widen_bf16(a.w[i], (float*)(a.ws + o), nw, a.stream); }, true});
         }
     }
     for (int k = 1; k < n; k++) {

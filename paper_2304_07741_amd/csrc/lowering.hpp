@@ -28,13 +28,18 @@ struct Launch {
     double bytes = 0;  // algorithmic bytes: every operand of the launch once
     double flops = 0;  // algorithmic flops of FC contractions
     std::function<void(const RunArgs&)> run;
+    bool prep = false;  // touches only the weights (packing, widening): an inference plan runs it once, ahead of the forward calls
 };
 
 struct Lowering {
     bool fused = false;
     uint64_t ws_bytes = 0;
     std::vector<Launch> fwd, bwd;
+    std::vector<Launch> prep;  // inference plans only: the weight-only launches taken out of fwd
 };
+
+// Turns a lowering into a forward-only plan: weight-only launches move to `prep`, the backward list is dropped.
+void make_inference_plan(Lowering& low);
 
 inline uint64_t align_up(uint64_t v, uint64_t a = 256) { return (v + a - 1) / a * a; }
 

@@ -49,6 +49,9 @@ class DagRunner:
         if dy is not None:
             self._up(self.dy, dy)
 
+    def prepare(self):
+        B.canvas_dag_prepare(self.handle, self.w, self.ws)
+
     def forward(self):
         B.canvas_dag_forward(self.handle, self.x, self.w, self.y, self.ws)
 

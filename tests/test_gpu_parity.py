@@ -324,6 +324,85 @@ def test_backward_is_deterministic(harness):
     r2.close()
 
 
+INFER_CASES = [lambda o: wl.config2(N=2, H=24), lambda o: wl.config2(N=1, H=56), lambda o: wl.config3(N=2, H=14), lambda o: wl.config3(N=8, H=28),
+               lambda o: wl.config4(64, 28, N=1), lambda o: wl.config4(256, 14, N=8), lambda o: wl.config4(512, 7, N=4),
+               lambda o: _fuzz_case(o, 123), lambda o: _fuzz_case(o, 207)]
+
+
+@pytest.mark.parametrize("flags", [0, B.CANVAS_OPT_NO_FUSION])
+@pytest.mark.parametrize("idx", range(len(INFER_CASES)))
+def test_inference_plan_matches_training_forward(harness, oracle, idx, flags):
+    """The inference plan (weight-only work hoisted into canvas_dag_prepare, batch 1-8) runs the same
+    kernels on the same operands, so its forward equals the training plan's bit for bit, also on repeated
+    calls and after the weights change; the training forward itself is checked against the oracle."""
+    import torch
+
+    case = INFER_CASES[idx](oracle)
+    res, rt, dy = harness.run_case(case, flags)
+    check_against_oracle(oracle, case, res, dy, what=f"{case['name']} flags={flags}")
+    ri = harness.DagRunner(case["blob"], case["shape"], case["dtype"], flags | B.CANVAS_OPT_INFERENCE)
+    try:
+        assert ri.info.n_launches_bwd == 0 and ri.info.fused == rt.info.fused
+        ri.load(case["x"], case["weights"])
+        ri.ws.fill_(0xFF)
+        ri.prepare()
+        for _ in range(3):
+            ri.y.fill_(float("nan"))
+            ri.forward()
+            assert np.array_equal(ri.results()["y"], res["y"])
+        with pytest.raises(B.CanvasError) as e:
+            ri.backward()
+        assert e.value.status == -6
+        # new weights: prepare again, compare with the training plan on the same weights
+        w2 = [np.ascontiguousarray(w[..., ::-1]) * 0.5 for w in case["weights"]]
+        rt.load(case["x"], w2)
+        rt.forward()
+        ri.load(case["x"], w2)
+        ri.prepare()
+        ri.forward()
+        assert np.array_equal(ri.results()["y"], rt.results()["y"])
+        assert not np.array_equal(ri.results()["y"], res["y"]) or not case["weights"]
+    finally:
+        ri.close()
+        rt.close()
+
+
+@pytest.mark.parametrize("which", ["config2", "config3", "config4"])
+def test_inference_forward_replays_from_a_hip_graph(harness, which):
+    """The forward of an inference plan is a fixed list of kernel launches (no allocation, no memset, no
+    synchronisation), so a captured HIP graph of it gives the eager result on every replay, with other
+    work and new inputs between the replays."""
+    import torch
+
+    case = {"config2": lambda: wl.config2(N=4, H=28), "config3": lambda: wl.config3(N=2, H=14),
+            "config4": lambda: wl.config4(128, 14, N=4)}[which]()
+    r = harness.DagRunner(case["blob"], case["shape"], case["dtype"], B.CANVAS_OPT_INFERENCE)
+    try:
+        r.load(case["x"], case["weights"])
+        r.prepare()
+        r.forward()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            r.forward()
+            with torch.cuda.graph(g, stream=side):
+                r.forward()
+        torch.cuda.synchronize()
+        for rep in range(4):
+            r.x.copy_(torch.roll(r.x, rep + 1, dims=0) * (1.0 + 0.25 * rep))  # eager work on new inputs
+            r.forward()
+            want = r.y.clone()
+            r.y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(r.y, want), f"replay {rep}"
+    finally:
+        r.close()
+
+
 def test_runtime_argument_checks(harness):
     import torch
 

@@ -190,3 +190,33 @@ def test_workspace_grows_with_batch_only_where_it_should(lib):
     a = _compile_info(wl.blob_sampled(64), (2, 64, 16, 16))[1]
     b = _compile_info(wl.blob_sampled(64), (4, 64, 16, 16))[1]
     assert 1.5 * a < b < 2.5 * a
+
+
+def test_inference_plan_moves_weight_only_launches_out_of_forward(lib):
+    """An inference plan has the training plan's forward launches minus the weight-only ones, no backward,
+    and refuses misuse before any launch (host logic only)."""
+    for blob, shape in [(wl.blob_sampled(64), (2, 64, 14, 14)), (wl.blob_involution(128), (2, 128, 12, 12)),
+                        (wl.blob_shift_residual(64), (2, 64, 16, 16)), (wl.blob_conv(3, 1, 16), (2, 16, 8, 8))]:
+        for flags in (0, B.CANVAS_OPT_NO_FUSION):
+            ht = B.canvas_dag_compile(blob, shape, B.CANVAS_BF16, flags)
+            hi = B.canvas_dag_compile(blob, shape, B.CANVAS_BF16, flags | B.CANVAS_OPT_INFERENCE)
+            it, ii = B.canvas_dag_query(ht), B.canvas_dag_query(hi)
+            assert it.n_launches_prepare == 0 and ii.n_launches_bwd == 0
+            assert ii.n_launches_fwd + ii.n_launches_prepare == it.n_launches_fwd
+            assert ii.fused == it.fused and ii.workspace_bytes == it.workspace_bytes
+            tn = [B.canvas_dag_launch_desc(ht, 0, i)["name"] for i in range(it.n_launches_fwd)]
+            inn = [B.canvas_dag_launch_desc(hi, 0, i)["name"] for i in range(ii.n_launches_fwd)]
+            assert [n for n in tn if n in inn] == inn  # same kernels, same order
+            assert all("pack" in n or "widen" in n for n in tn if n not in inn)
+            arr = (ctypes.c_void_p * 4)(0x1000, 0x1000, 0x1000, 0x1000)
+            assert lib.canvas_dag_backward(hi, 0x1000, arr, 0x2000, 0x4000, arr, 0x3000, 1 << 40, None) == -6
+            assert lib.canvas_dag_prepare(ht, arr, 0x3000, 1 << 40, None) == -4  # not an inference plan
+            if ii.n_launches_prepare:
+                assert lib.canvas_dag_prepare(hi, arr, 0x3000, 0, None) == -5
+                assert lib.canvas_dag_prepare(hi, None, 0x3000, 1 << 40, None) == -4
+            B.canvas_dag_destroy(ht)
+            B.canvas_dag_destroy(hi)
+    # the tap-major windows of the sampled kernel do repack their weights: something must have moved
+    hi = B.canvas_dag_compile(wl.blob_sampled(64), (2, 64, 14, 14), B.CANVAS_BF16, B.CANVAS_OPT_INFERENCE)
+    assert B.canvas_dag_query(hi).n_launches_prepare >= 1
+    B.canvas_dag_destroy(hi)
