@@ -35,7 +35,14 @@
  *                                       replicated over the pixels of a full-size RHS; axis=C groups=G folds the
  *                                       C/G channels of each of G groups: the result has G channels)
  *     %7 = softmax %6 axis=C           (C | T | CT: over channels, over taps, or over both jointly)
- *     output %7
+ *     %8 = group %7 groups=4           (the Group primitive as a node of its own: the same data seen as
+ *                                       [G, C/G, T, H, W]; groups=C makes every channel a group.  The view
+ *                                       travels through unfold, shift, unary, softmax, fold over T / HW and
+ *                                       through an fc, whose `groups=` may then be left out (it contracts per
+ *                                       group and its output is [G, out/G]); a binary result has the view of
+ *                                       its RHS; when both operands of a binary have the same view, G is a
+ *                                       common leading dim and the LHS is replicated inside each group)
+ *     output %8
  * %0 is the input [N, C, H, W].
  */
 #include <math.h>
@@ -49,7 +56,7 @@
 
 #define MAX_NODES 64
 
-enum { OP_INPUT = 0, OP_UNFOLD, OP_SHIFT, OP_FC, OP_UNARY, OP_BINARY, OP_SOFTMAX, OP_FOLD };
+enum { OP_INPUT = 0, OP_UNFOLD, OP_SHIFT, OP_FC, OP_UNARY, OP_BINARY, OP_SOFTMAX, OP_FOLD, OP_GROUP };
 enum { UN_RELU = 0, UN_ABS, UN_GELU, UN_EXPCLIP, UN_SIN };
 enum { BIN_ADD = 0, BIN_MUL, BIN_SUB, BIN_MIN, BIN_MAX };
 enum { AXIS_C = 0, AXIS_T, AXIS_CT };
@@ -68,6 +75,7 @@ typedef struct {
     int axis_hw;        /* fold: 1 = over the pixels, 0 = over the taps */
     int axis_c;         /* fold: 1 = over the C / groups channels of each of `groups` channel groups */
     int widx;           /* fc: index into the weight list */
+    int grp;            /* Group view of the channel dim: [grp, C/grp]; 1 = not grouped */
 } Node;
 
 typedef struct {
@@ -150,6 +158,17 @@ static void broadcast_index(int CL, int TL, int CR, int TR, int c, int t, int *c
     (void)CR;
 }
 
+/* With the same Group view [G, ./G] on both sides, G is a common prefix of the two dim lists: the rule
+ * above applies inside each group, to [CL/G, TL] and [CR/G, TR] (Section 5: [G, x/G, H, W] onto
+ * [G, C/G, K_H, H, W] needs x/G | C/G * K_H). */
+static int broadcast_legal_g(int G, int CL, int TL, int CR, int TR) { return broadcast_legal(CL / G, TL, CR / G, TR); }
+
+static void broadcast_index_g(int G, int CL, int TL, int CR, int TR, int c, int t, int *cl, int *tl) {
+    int g = c / (CR / G);
+    broadcast_index(CL / G, TL, CR / G, TR, c % (CR / G), t, cl, tl);
+    *cl += g * (CL / G);
+}
+
 static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d, char *err, size_t errlen) {
     char *buf = (char *)malloc(len + 1), *save1 = NULL, *line;
     int lineno = 0, seen_header = 0, seen_output = 0, rc = -1;
@@ -163,6 +182,7 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
     d->node[0].op = OP_INPUT;
     d->node[0].C = C0;
     d->node[0].T = 1;
+    d->node[0].grp = 1;
     d->out = -1;
     for (line = strtok_r(buf, "\n", &save1); line; line = strtok_r(NULL, "\n", &save1)) {
         char *tok[32], *save2 = NULL, *t;
@@ -202,6 +222,7 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
             const Node *A = &d->node[nd->a];
             const char *opn = tok[2];
             nd->pooled = A->pooled;  /* (binary takes the RHS's below) */
+            nd->grp = A->grp;        /* (likewise) */
             if ((!strcmp(opn, "unfold") || !strcmp(opn, "shift")) && A->pooled) {
                 set_err(err, errlen, "unfold / shift need the spatial dims", lineno);
                 goto done;
@@ -227,9 +248,24 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 }
                 nd->C = A->C;
                 nd->T = A->T;
+            } else if (!strcmp(opn, "group")) {
+                nd->op = OP_GROUP;
+                if (attr_int(tok, ntok, "groups", &nd->grp) != 1 || nd->grp < 1 || A->C % nd->grp) {
+                    set_err(err, errlen, "group needs groups | C", lineno);
+                    goto done;
+                }
+                nd->C = A->C;
+                nd->T = A->T;
             } else if (!strcmp(opn, "fc")) {
+                int has;
                 nd->op = OP_FC;
-                if (attr_int(tok, ntok, "groups", &nd->groups) != 1 || attr_int(tok, ntok, "out", &nd->out) != 1 ||
+                nd->groups = A->grp;  /* a grouped operand: per-group FC unless stated otherwise ... */
+                has = attr_int(tok, ntok, "groups", &nd->groups);
+                if (has < 0 || (has == 1 && A->grp > 1 && nd->groups != A->grp)) {  /* ... and stating otherwise is an error */
+                    set_err(err, errlen, "fc groups= contradicts the Group view of its operand", lineno);
+                    goto done;
+                }
+                if (attr_int(tok, ntok, "out", &nd->out) != 1 ||
                     nd->groups < 1 || nd->out < 1 || A->C % nd->groups || nd->out % nd->groups) {
                     set_err(err, errlen, "fc needs groups | C and groups | out", lineno);
                     goto done;
@@ -269,11 +305,14 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 else if (!strcmp(k2, "max")) nd->kind = BIN_MAX;
                 else { set_err(err, errlen, "unknown binary op", lineno); goto done; }
                 B = &d->node[nd->b];
-                if (!broadcast_legal(A->C, A->T, B->C, B->T) || (!A->pooled && B->pooled)) {
+                if (!(A->grp == B->grp && A->grp > 1 ? broadcast_legal_g(A->grp, A->C, A->T, B->C, B->T)
+                                                     : broadcast_legal(A->C, A->T, B->C, B->T)) ||
+                    (!A->pooled && B->pooled)) {
                     set_err(err, errlen, "broadcast: LHS size does not divide RHS size", lineno);
                     goto done;
                 }
                 nd->pooled = B->pooled;
+                nd->grp = B->grp;
                 nd->C = B->C;
                 nd->T = B->T;
             } else if (!strcmp(opn, "softmax")) {
@@ -307,6 +346,7 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                     }
                     nd->C = nd->groups;
                     nd->T = A->T;
+                    nd->grp = 1;
                 } else if (nd->axis_hw) {
                     if (A->pooled) { set_err(err, errlen, "fold axis=HW: the spatial dims are already folded", lineno); goto done; }
                     nd->T = A->T;
@@ -421,7 +461,8 @@ static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
         for (t = 0; t < nd->T; t++) {
             const double *lrow, *rrow = rhs + ((size_t)c * nd->T + t) * P;
             double *orow = out + ((size_t)c * nd->T + t) * P;
-            broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
+            if (L->grp == nd->grp && nd->grp > 1) broadcast_index_g(nd->grp, L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
+            else broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             lrow = lhs + ((size_t)cl * L->T + tl) * PL;
             for (p = 0; p < P; p++) {
                 double a = lrow[PL == 1 ? 0 : p], b = rrow[p], y = 0.0;
@@ -587,7 +628,8 @@ static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
     for (c = 0; c < nd->C; c++)
         for (t = 0; t < nd->T; t++) {
             size_t ro = ((size_t)c * nd->T + t) * P, lo;
-            broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
+            if (L->grp == nd->grp && nd->grp > 1) broadcast_index_g(nd->grp, L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
+            else broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             lo = ((size_t)cl * L->T + tl) * PL;
             for (p = 0; p < P; p++) {
                 size_t lp = lo + (PL == 1 ? 0 : p);
@@ -759,6 +801,7 @@ int canvas_oracle_run(const char *blob, size_t len, const int64_t in_shape[4], c
             case OP_BINARY: fwd_binary(&d, nd, val[nd->a], val[nd->b], val[j]); break;
             case OP_SOFTMAX: fwd_softmax(&d, nd, val[nd->a], val[j]); break;
             case OP_FOLD: fwd_fold(&d, nd, val[nd->a], val[j]); break;
+            case OP_GROUP: memcpy(val[j], val[nd->a], node_numel(&d, j) * sizeof(double)); break;  /* a view: same data */
             }
         }
         if (!failed) memcpy(y + (size_t)n * yn, val[d.out], yn * sizeof(double));
@@ -779,6 +822,11 @@ int canvas_oracle_run(const char *blob, size_t len, const int64_t in_shape[4], c
                     case OP_BINARY: bwd_binary(&d, nd, val[nd->a], val[nd->b], grad[j], grad[nd->a], grad[nd->b]); break;
                     case OP_SOFTMAX: bwd_softmax(&d, nd, val[j], grad[j], grad[nd->a]); break;
                     case OP_FOLD: bwd_fold(&d, nd, val[nd->a], grad[j], grad[nd->a]); break;
+                    case OP_GROUP: {
+                        size_t i, cnt = node_numel(&d, j);
+                        for (i = 0; i < cnt; i++) grad[nd->a][i] += grad[j][i];
+                        break;
+                    }
                     }
                 }
                 memcpy(dx + (size_t)n * xn, grad[0], xn * sizeof(double));

@@ -160,6 +160,10 @@ FD_BODIES = [
     ("%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=sin\n%3 = binary %0 %2 op=sub\n%4 = fold %3 op=sum\noutput %4\n", []),
     ("%1 = shift %0 dh=1 dw=0\n%2 = unary %1 op=gelu\n%3 = binary %2 %0 op=max\noutput %3\n", []),
     ("%1 = unfold %0 kh=3 kw=1\n%2 = fc %0 groups=1 out=2\n%3 = binary %2 %1 op=min\n%4 = fold %3 op=avg\noutput %4\n", [(1, 2, 4)]),
+    # grouped Involution: per-group window weights, replicated inside each group
+    ("%1 = group %0 groups=2\n%2 = fc %1 out=6\n%3 = softmax %2 axis=C\n%4 = unfold %1 kh=3 kw=1\n%5 = binary %3 %4 op=mul\n"
+     "%6 = fold %5 op=sum\n%7 = fc %6 out=4\noutput %7\n", [(2, 3, 2), (2, 2, 2)]),
+    ("%1 = group %0 groups=4\n%2 = unfold %1 kh=3 kw=3\n%3 = fc %2 out=8\n%4 = unary %3 op=gelu\n%5 = binary %1 %4 op=mul\noutput %5\n", [(4, 2, 9)]),
 ]
 
 
@@ -522,6 +526,108 @@ def test_involution_core_against_explicit_dynamic_kernel(oracle):
                     if 0 <= hs < H and 0 <= ws < W:
                         exp[0, c, h, w] += ker[0, t, h, w] * x[0, c, hs, ws]
     np.testing.assert_allclose(r["y"], exp, atol=1e-13)
+
+
+# ------------------------------------------------------- Group as a node of its own
+
+def test_group_is_a_view_and_fc_inherits_it(oracle):
+    """Section 5, Group: a rearrangement without copies; a following FC works inside each group, so
+    group + fc equals the fc with the groups written on it, values and gradients alike."""
+    rng = np.random.default_rng(70)
+    x = rng.standard_normal((2, 6, 4, 5))
+    r = run1(oracle, "%1 = group %0 groups=3\noutput %1\n", x, [], x * 2.0)
+    np.testing.assert_array_equal(r["y"], x)
+    np.testing.assert_array_equal(r["dx"], x * 2.0)
+    w = rng.standard_normal((3, 2, 18))
+    a = "%1 = group %0 groups=3\n%2 = unfold %1 kh=3 kw=3\n%3 = unary %2 op=abs\n%4 = fc %3 out=6\noutput %4\n"
+    b = "%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=abs\n%3 = fc %2 groups=3 out=6\noutput %3\n"
+    dy = rng.standard_normal((2, 6, 4, 5))
+    ra, rb = run1(oracle, a, x, [w], dy), run1(oracle, b, x, [w], dy)
+    for k in ("y", "dx"):
+        np.testing.assert_array_equal(ra[k], rb[k])
+    np.testing.assert_array_equal(ra["dw"][0], rb["dw"][0])
+    # stating the same groups again is allowed, contradicting the view is not
+    run1(oracle, "%1 = group %0 groups=3\n%2 = fc %1 groups=3 out=6\noutput %2\n", x, [rng.standard_normal((3, 2, 2))])
+    for bad in ("%1 = group %0 groups=3\n%2 = fc %1 groups=2 out=6\noutput %2\n", "%1 = group %0 groups=4\noutput %1\n",
+                "%1 = group %0\noutput %1\n", "%1 = group %0 groups=0\noutput %1\n"):
+        with pytest.raises(Exception):
+            run1(oracle, bad, x, [rng.standard_normal((2, 3, 3))])
+
+
+def test_depthwise_group_is_a_per_channel_filter(oracle):
+    """[X] => [X, 1]: every channel its own group; Unfold + FC is then a depth-wise convolution."""
+    rng = np.random.default_rng(71)
+    C, H, W = 5, 6, 4
+    x = rng.standard_normal((1, C, H, W))
+    w = rng.standard_normal((C, 1, 9))
+    y = run1(oracle, f"%1 = group %0 groups={C}\n%2 = unfold %1 kh=3 kw=3\n%3 = fc %2 out={C}\noutput %3\n", x, [w])["y"]
+    exp = np.zeros_like(x)
+    xp = np.pad(x, ((0, 0), (0, 0), (1, 1), (1, 1)))
+    for c in range(C):
+        for kh in range(3):
+            for kw in range(3):
+                exp[0, c] += w[c, 0, kh * 3 + kw] * xp[0, c, kh:kh + H, kw:kw + W]
+    np.testing.assert_allclose(y, exp, atol=1e-13)
+
+
+def test_grouped_broadcast_equals_the_groups_run_one_by_one(oracle):
+    """With the same Group view on both sides G is a common leading dim (Section 5: [G, x/G, H, W] onto
+    [G, C/G, K_H, H, W]): the blend of group g involves only the channels of group g, i.e. the result is
+    what the ungrouped DAG gives on each group's channel slice, concatenated."""
+    rng = np.random.default_rng(72)
+    G, C, H, W = 2, 8, 4, 5
+    x = rng.standard_normal((2, C, H, W))
+    w = rng.standard_normal((G, 3, C // G))          # fc to 3 channels per group = one per tap of a 3x1 window
+    dy = rng.standard_normal((2, C, 3, H, W))
+    for op in ("mul", "sub", "max"):
+        body = (f"%1 = group %0 groups={G}\n%2 = fc %1 out={3 * G}\n%3 = unfold %1 kh=3 kw=1\n"
+                f"%4 = binary %2 %3 op={op}\noutput %4\n")
+        r = run1(oracle, body, x, [w], dy)
+        one = f"%1 = fc %0 groups=1 out=3\n%2 = unfold %0 kh=3 kw=1\n%3 = binary %1 %2 op={op}\noutput %3\n"
+        cg = C // G
+        for g in range(G):
+            sl = slice(g * cg, (g + 1) * cg)
+            rg = run1(oracle, one, np.ascontiguousarray(x[:, sl]), [w[g:g + 1]], np.ascontiguousarray(dy[:, sl]))
+            np.testing.assert_array_equal(r["y"][:, sl], rg["y"])
+            np.testing.assert_allclose(r["dx"][:, sl], rg["dx"], atol=1e-13)
+            np.testing.assert_allclose(r["dw"][0][g], rg["dw"][0][0], atol=1e-12)
+        # and it differs from the blend without the common group dim (flat replication pairs other channels)
+        flat = f"%1 = fc %0 groups={G} out={3 * G}\n%2 = unfold %0 kh=3 kw=1\n%3 = binary %1 %2 op={op}\noutput %3\n"
+        assert not np.allclose(run1(oracle, flat, x, [w])["y"], r["y"])
+
+
+def test_grouped_involution_against_explicit_per_group_kernel(oracle):
+    """Section 5's Involution: [G, K, K, H, W] times [G, C/G, K, K, H, W], summed over the window:
+    out(g, c, h, w) = sum_t ker(g, t, h, w) * x(g, c, h + dh_t, w + dw_t)."""
+    rng = np.random.default_rng(73)
+    G, C, H, W = 3, 6, 4, 5
+    cg = C // G
+    x = rng.standard_normal((1, C, H, W))
+    w1 = rng.standard_normal((G, 9, cg))
+    body = (f"%1 = group %0 groups={G}\n%2 = fc %1 out={9 * G}\n%3 = unfold %1 kh=3 kw=3\n%4 = binary %2 %3 op=mul\n"
+            "%5 = fold %4 op=sum\noutput %5\n")
+    y = run1(oracle, body, x, [w1])["y"]
+    xg = x.reshape(1, G, cg, H, W)
+    ker = np.einsum("gtc,ngchw->ngthw", w1, xg)
+    xp = np.pad(xg, ((0, 0), (0, 0), (0, 0), (1, 1), (1, 1)))
+    exp = np.zeros_like(xg)
+    for t in range(9):
+        exp += ker[:, :, t][:, :, None] * xp[:, :, :, t // 3:t // 3 + H, t % 3:t % 3 + W]
+    np.testing.assert_allclose(y, exp.reshape(1, C, H, W), atol=1e-13)
+
+
+def test_group_view_legality_and_propagation(oracle):
+    x = np.zeros((1, 8, 3, 3))
+    # LHS [G=2, 3 per group] onto RHS [G=2, 4 per group]: 3 does not divide 4 (flat 6 | 8 fails as well)
+    with pytest.raises(Exception):
+        run1(oracle, "%1 = group %0 groups=2\n%2 = fc %1 out=6\n%3 = binary %2 %1 op=add\noutput %3\n", x, [np.zeros((2, 3, 4))])
+    # per group 2 | 4 holds, while flat replication of 4 onto 8 would hold too; views differ -> flat rule
+    run1(oracle, "%1 = group %0 groups=2\n%2 = fc %1 out=4\n%3 = binary %2 %0 op=add\noutput %3\n", x, [np.zeros((2, 2, 4))])
+    # a channel fold drops the view: the following fc is an ordinary one
+    _, _, ws = oracle.infer(H_ + "%1 = group %0 groups=2\n%2 = fold %1 op=sum axis=C groups=4\n%3 = fc %2 out=4\noutput %3\n", (1, 8, 3, 3))
+    assert ws == [[1, 4, 4]]
+    ns, _, ws = oracle.infer(H_ + "%1 = group %0 groups=4\n%2 = unfold %1 kh=3 kw=3\n%3 = fold %2 op=max axis=HW\n%4 = fc %3 out=12\noutput %4\n", (1, 8, 3, 3))
+    assert ws == [[4, 3, 18]] and ns[4] == [12, 1, 1, 1]
 
 
 def test_fan_out_gradients_add(oracle):
