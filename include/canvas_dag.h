@@ -19,7 +19,8 @@
  *     %5 = binary %0 %4 op=mul         first operand LHS, second RHS; add | sub | mul | min | max
  *     %6 = fold %5 op=avg              sum | avg | max [axis=T | HW | C [groups=<G>]]
  *     %7 = softmax %6 axis=C           C | T | CT
- *     output %7
+ *     %8 = group %7 groups=4           a view [G, C/G] of the channels; groups=C: every channel a group
+ *     output %8
  *
  * Tensors are [N, C, T, H, W], contiguous, T = number of unfolded taps (1 when
  * the tensor has none; then the layout is plain NCHW).
@@ -47,6 +48,16 @@
  *            binary it is replicated over the pixels of a full-size RHS.  With
  *            axis=C groups=G (default 1) the C/G channels of each of G channel
  *            groups are folded: G channels remain.
+ *   group    the Group primitive as a node (Section 5, Group: [.., X, ..] => [.., G, X/G, ..]
+ *            or [.., X, 1, ..]): the same data, seen as G channel groups.  The view
+ *            travels through unfold, shift, unary, softmax and fold over T / HW; an
+ *            fc of a grouped tensor contracts inside each group (its groups= may be
+ *            left out, and must equal G when given) and its output keeps the view;
+ *            a binary result has the view of its RHS; when both operands of a binary
+ *            carry the same view, G is a common leading dim and the Broadcast rule
+ *            applies inside each group to [C_L/G, T_L] and [C_R/G, T_R] (Section 5:
+ *            [G, x/G, H, W] onto [G, C/G, K_H, H, W]).  fold axis=C drops the view.
+ *            An fc without groups= on a tensor without a view has one group.
  *   backward exact vector-Jacobian products of the above; relu'(0) = 0,
  *            sign(0) = 0, expclip has zero gradient outside the open interval; a
  *            tie of binary min / max sends the gradient to the LHS.

@@ -10,7 +10,7 @@
 
 namespace canvas {
 
-enum class Op : int { Input = 0, Unfold, Shift, Fc, Unary, Binary, Softmax, Fold };
+enum class Op : int { Input = 0, Unfold, Shift, Fc, Unary, Binary, Softmax, Fold, Group };
 enum UnaryKind : int { kRelu = 0, kAbs, kGelu, kExpClip, kSin };
 enum BinaryKind : int { kAdd = 0, kMul, kSub, kBinMin, kBinMax };
 enum AxisKind : int { kAxisC = 0, kAxisT, kAxisCT };
@@ -28,6 +28,8 @@ struct Node {
     int axis_hw = 0;             // fold: 1 = over the pixels (the result is pooled), 0 = over the taps
     int axis_c = 0;              // fold: 1 = over the C / groups channels of each of `groups` channel groups
     bool pooled = false;         // the spatial dims have been folded away: shape [N, C, T, 1, 1]
+    int grp = 1;                 // Group view of the channel dim, [grp, C / grp] (1 = none)
+    int bgroups = 1;             // binary: > 1 when both operands carry this same view, the blend then runs inside each group
     int C = 0, T = 1;            // inferred shape
     int widx = -1;               // fc: index into the weight list
     bool live = false;           // reaches the output
@@ -46,7 +48,12 @@ struct Dag {
 };
 
 // Status codes mirror canvas_status in the public header.
+// A Group node is a view: nodes that name it as an operand are wired to the tensor it views (and take
+// the view from it), so a Group node is live only when it is the output itself.
 int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag, std::string& err);
+
+// The DAG without its dead Group nodes, renumbered: what the lowerings work on.
+Dag without_dead_views(const Dag& dag);
 
 // Broadcast index map (Section 5, Blending primitives): the LHS element that meets RHS element (c, t).
 inline void broadcast_src(int CL, int TL, int CR, int TR, int c, int t, int& cl, int& tl) {

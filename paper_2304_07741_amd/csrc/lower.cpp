@@ -3,7 +3,8 @@
 
 namespace canvas {
 
-std::unique_ptr<Lowering> lower(const Dag& dag, bool bf16, bool no_fusion) {
+std::unique_ptr<Lowering> lower(const Dag& full, bool bf16, bool no_fusion) {
+    const Dag dag = without_dead_views(full);
     if (!no_fusion) {
         if (auto l = lower_sgfc(dag, bf16)) return l;
         if (auto l = lower_ufc(dag, bf16)) return l;

@@ -1,8 +1,10 @@
 // Pattern match and lowering for per-pixel window weights (the Involution form of the Canvas paper, Section 5):
 //     l = FC1(x) [TV channels];  a = softmax_C(l) (optional);  U = Unfold(x) [C, TV];
 //     m = a (broadcast-mul) U;  u = Fold_{sum|avg over taps}(m);  y = FC2(u)
-// with TV = KH*KW, so that the broadcast pairs channel t of a with tap t of U.  The unfolded tensor and the
-// product m are never materialised:
+// with TV = KH*KW, so that the broadcast pairs channel t of a with tap t of U.  With a Group view [G, C/G] on x
+// (and hence on l, a and U) the blend runs inside each group: l has G*TV channels and channel g*TV + t meets
+// tap t of the channels of group g; (image, group) pairs are then independent, and the kernels see N*G
+// "images" of C/G channels.  The unfolded tensor and the product m are never materialised:
 //     forward   l (fp32), a (fp32), u (bf16) -> y
 //     backward  dW2 = dy . u;  du = FC2^T dy;  dx = dyn^T(a, du);  da = sum_c du . U;  dl = softmax'(a, da);
 //               dW1 = dl . x;  dx += FC1^T dl
@@ -40,7 +42,8 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
     const Node &fc1 = dag.nodes[ifc1], &unf = dag.nodes[iunf], &bin = dag.nodes[ibin], &fold = dag.nodes[ifold], &fc2 = dag.nodes[ifc2];
     const int C = dag.nodes[0].C, TV = unf.kh * unf.kw, Pn = dag.P();
     if (dag.nodes[0].T != 1 || unf.a != 0 || !dyn::supported(unf.kh, unf.kw)) return nullptr;
-    if (fc1.a != 0 || fc1.out != TV) return nullptr;
+    const int Gb = bin.bgroups, TVa = Gb * TV;  // groups of the blend, channels of l and a
+    if (fc1.a != 0 || fc1.out != TVa || C % Gb || (Gb > 1 && fc1.groups != Gb)) return nullptr;
     int alast = ifc1;
     if (isoft >= 0) {
         const Node& sm = dag.nodes[isoft];
@@ -48,7 +51,8 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
         alast = isoft;
     }
     // LHS [TV, 1] onto RHS [C, TV]: with C != TV the broadcast index (c*TV + t) % TV = t pairs channel t with tap t
-    if (bin.kind != kMul || bin.a != alast || bin.b != iunf || C == TV) return nullptr;
+    // (inside each group when Gb > 1: C/Gb channels)
+    if (bin.kind != kMul || bin.a != alast || bin.b != iunf || C / Gb == TV) return nullptr;
     if (fold.a != ibin || fold.axis_c || fold.axis_hw || (fold.kind != kSum && fold.kind != kAvg)) return nullptr;
     if (fc2.a != ifold || dag.out != ifc2) return nullptr;
     // every intermediate has exactly the one consumer of the pattern
@@ -63,15 +67,17 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
         if (k != ifc1 && k != iunf && uses(0)) return nullptr;
     }
     const int O2 = fc2.out, G1 = fc1.groups, G2 = fc2.groups;
-    if ((int64_t)dag.N * std::max(C, O2) * Pn * 2 >= ((int64_t)1 << 31) || (int64_t)dag.N * TV * Pn * 4 >= ((int64_t)1 << 31) || dag.W < 4 ||
+    if ((int64_t)dag.N * std::max(C, O2) * Pn * 2 >= ((int64_t)1 << 31) || (int64_t)dag.N * TVa * Pn * 4 >= ((int64_t)1 << 31) || dag.W < 4 ||
         (int64_t)dag.N * Pn >= ((int64_t)1 << 28))
         return nullptr;
     const int upi = (Pn + 7) / 8;
-    if ((int64_t)dag.N * C * upi >= ((int64_t)1 << 31) || (int64_t)dag.N * upi * upi >= ((int64_t)1 << 32)) return nullptr;
+    if ((int64_t)dag.N * C * upi >= ((int64_t)1 << 31) || (int64_t)dag.N * Gb * upi * upi >= ((int64_t)1 << 32) ||
+        (int64_t)dag.N * Gb >= ((int64_t)1 << 24))
+        return nullptr;
 
     dyn::Params D;
-    D.N = dag.N;
-    D.C = C;
+    D.N = dag.N * Gb;
+    D.C = C / Gb;
     D.H = dag.H;
     D.W = dag.W;
     D.P = Pn;
@@ -91,12 +97,12 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
         off += align_up(bytes);
         return (int64_t)o;
     };
-    const double act = 2.0 * dag.numel(0), outb = 2.0 * dag.numel(dag.out), ab = 4.0 * dag.N * TV * Pn;
+    const double act = 2.0 * dag.numel(0), outb = 2.0 * dag.numel(dag.out), ab = 4.0 * dag.N * TVa * Pn;
     const int64_t ol = take((uint64_t)ab), oa = isoft >= 0 ? take((uint64_t)ab) : ol;  // logits, softmax output (fp32)
     const int64_t ou = take((uint64_t)act), odu = take((uint64_t)act);
     const int64_t oda = take((uint64_t)ab), odl = isoft >= 0 ? take((uint64_t)ab) : oda;
     const int w1 = fc1.widx, w2 = fc2.widx;
-    const int64_t nw1 = (int64_t)TV * (C / G1), nw2 = (int64_t)O2 * (C / G2);
+    const int64_t nw1 = (int64_t)TVa * (C / G1), nw2 = (int64_t)O2 * (C / G2);
     const double fl1 = 2.0 * dag.N * Pn * (double)nw1, fl2 = 2.0 * dag.N * Pn * (double)nw2;
     const double fld = 2.0 * dag.N * Pn * (double)C * TV;
     const int64_t N = dag.N;
@@ -105,10 +111,10 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
     const FcOperand in_x{[](const RunArgs& a) { return a.x; }, false};
     const FcOperand in_dy{[](const RunArgs& a) { return a.dy; }, false};
 
-    emit_fc(low->fwd, dag, take, "dyn_fc1", G1, C / G1, 1, 1, TV / G1, false, w1, in_x, ws_at(ol), false, act + ab + 2.0 * nw1, fl1, true);
+    emit_fc(low->fwd, dag, take, "dyn_fc1", G1, C / G1, 1, 1, TVa / G1, false, w1, in_x, ws_at(ol), false, act + ab + 2.0 * nw1, fl1, true);
     if (soft)
         low->fwd.push_back({"dyn_softmax", 2.0 * ab, 0, [=](const RunArgs& a) {
-                                ref::softmax_fwd((const float*)(a.ws + ol), (float*)(a.ws + oa), N, TV, 1, Pn, 1, a.stream);
+                                ref::softmax_fwd((const float*)(a.ws + ol), (float*)(a.ws + oa), N, TVa, 1, Pn, 1, a.stream);
                             }});
     low->fwd.push_back({"dyn_apply", 2.0 * act + ab, fld, [=](const RunArgs& a) {
                             dyn::Params Q = D;
@@ -139,12 +145,12 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
                         }});
     if (soft)
         low->bwd.push_back({"dyn_softmax_bwd", 3.0 * ab, 0, [=](const RunArgs& a) {
-                                ref::softmax_bwd((const float*)(a.ws + oa), (const float*)(a.ws + oda), (float*)(a.ws + odl), N, TV, 1, Pn, 1, 0,
+                                ref::softmax_bwd((const float*)(a.ws + oa), (const float*)(a.ws + oda), (float*)(a.ws + odl), N, TVa, 1, Pn, 1, 0,
                                                  a.stream);
                             }});
-    emit_wgrad(low->bwd, dag, take, "dyn_fc1_wgrad", G1, C / G1, 1, 1, TV / G1, w1, in_x, FcOperand{ws_at(odl), true}, act + ab, fl1);
+    emit_wgrad(low->bwd, dag, take, "dyn_fc1_wgrad", G1, C / G1, 1, 1, TVa / G1, w1, in_x, FcOperand{ws_at(odl), true}, act + ab, fl1);
     // the data gradient of FC1 adds to the dx that dyn_apply_dx has written
-    emit_fc(low->bwd, dag, take, "dyn_fc1_dgrad", G1, TV / G1, 1, 1, C / G1, true, w1, FcOperand{ws_at(odl), true},
+    emit_fc(low->bwd, dag, take, "dyn_fc1_dgrad", G1, TVa / G1, 1, 1, C / G1, true, w1, FcOperand{ws_at(odl), true},
             [](const RunArgs& a) { return (const void*)a.dx; }, true, 2.0 * act + ab + 2.0 * nw1, fl1);
     low->ws_bytes = off;
     return low;

@@ -26,6 +26,7 @@ const char* op_name(Op op) {
     case Op::Binary: return "binary";
     case Op::Softmax: return "softmax";
     case Op::Fold: return "fold";
+    case Op::Group: return "group";
     default: return "input";
     }
 }
@@ -193,9 +194,16 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             const Node B = dag.nodes[nd.b];
             L.bytes = 4.0 * (dag.numel(nd.a) + dag.numel(nd.b) + dag.numel(k));
             const int Pn = dag.Pk(k), PL = dag.Pk(nd.a);
+            // a common Group dim: (image, group) pairs are independent, each blends [CL/G, TL] onto [CR/G, TR]
+            const int Gb = nd.bgroups;
             L.run = [=](const RunArgs& a) {
-                ref::binary_fwd(val(a, nd.a), val(a, nd.b), valw(a, k), N, A.C, A.T, B.C, B.T, Pn, PL, nd.kind, a.stream);
+                ref::binary_fwd(val(a, nd.a), val(a, nd.b), valw(a, k), N * Gb, A.C / Gb, A.T, B.C / Gb, B.T, Pn, PL, nd.kind, a.stream);
             };
+            break;
+        }
+        case Op::Group: {  // (live only as the output: a copy of the viewed tensor)
+            int64_t ne = dag.numel(k);
+            L.run = [=](const RunArgs& a) { ref::copy_f32(val(a, nd.a), valw(a, k), ne, a.stream); };
             break;
         }
         case Op::Softmax:
@@ -326,9 +334,9 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             // LHS first, then RHS (which may be the same tensor and then accumulates)
             L.name = "node_binary_bwd_lhs";
             L.bytes = 4.0 * (dag.numel(nd.a) * (1 + acc) + dag.numel(k) * (nd.kind == kAdd || nd.kind == kSub ? 1 : 2));
-            const int Pn = dag.Pk(k), PL = dag.Pk(nd.a);
+            const int Pn = dag.Pk(k), PL = dag.Pk(nd.a), Gb = nd.bgroups;
             L.run = [=](const RunArgs& a) {
-                ref::binary_bwd_lhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.a), N, A.C, A.T, B.C, B.T, Pn, PL, nd.kind, acc, a.stream);
+                ref::binary_bwd_lhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.a), N * Gb, A.C / Gb, A.T, B.C / Gb, B.T, Pn, PL, nd.kind, acc, a.stream);
             };
             low->bwd.push_back(std::move(L));
             written[nd.a] = true;
@@ -337,11 +345,16 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             R.name = "node_binary_bwd_rhs";
             R.bytes = 4.0 * (dag.numel(nd.b) * (1 + acc_r) + dag.numel(k) + (nd.kind == kAdd || nd.kind == kSub ? 0 : dag.numel(nd.a)));
             R.run = [=](const RunArgs& a) {
-                ref::binary_bwd_rhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.b), N, A.C, A.T, B.C, B.T, Pn, PL, nd.kind, acc_r, a.stream);
+                ref::binary_bwd_rhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.b), N * Gb, A.C / Gb, A.T, B.C / Gb, B.T, Pn, PL, nd.kind, acc_r, a.stream);
             };
             low->bwd.push_back(std::move(R));
             written[nd.b] = true;
             continue;
+        }
+        case Op::Group: {  // a shift by nothing: copies, or adds to, the gradient of the viewed tensor
+            const int Pn = dag.Pk(k);
+            L.run = [=](const RunArgs& a) { ref::shift(grad(a, k), grad(a, nd.a), N, nd.C, nd.T, 1, Pn, 0, 0, 0, 0, acc, a.stream); };
+            break;
         }
         case Op::Softmax:
             L.bytes += 4.0 * dag.numel(k);

@@ -110,10 +110,16 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
         if (id >= kMaxNodes) return fail(err, lineno, "too many nodes", kUnsupported);
         Node nd;
         if (!parse_ref(l.pos[3], nd.a) || nd.a >= id) return fail(err, lineno, "operand must be an earlier node", kInvalidBlob);
-        const Node& A = dag.nodes[nd.a];
+        const Node A = dag.nodes[nd.a];  // shape and view as named; the data is that of the viewed tensor
+        auto viewed = [&](int k) {
+            while (dag.nodes[k].op == Op::Group) k = dag.nodes[k].a;
+            return k;
+        };
+        nd.a = viewed(nd.a);
         const std::string& op = l.pos[2];
         bool present;
         nd.pooled = A.pooled;  // (binary takes the RHS's below)
+        nd.grp = A.grp;        // (likewise)
         if ((op == "unfold" || op == "shift") && A.pooled) return fail(err, lineno, op + " needs the spatial dims", kShapeMismatch);
         if (op == "unfold") {
             nd.op = Op::Unfold;
@@ -134,10 +140,19 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             if (nd.c0 < 0 || nd.c1 > A.C || nd.c0 > nd.c1) return fail(err, lineno, "shift slice outside the channels", kShapeMismatch);
             nd.C = A.C;
             nd.T = A.T;
+        } else if (op == "group") {
+            nd.op = Op::Group;
+            if (!get_int(l, "groups", nd.grp, true, present)) return fail(err, lineno, "group needs groups=", kInvalidBlob);
+            if (nd.grp < 1 || A.C % nd.grp) return fail(err, lineno, "group: groups must divide the channels", kShapeMismatch);
+            nd.C = A.C;
+            nd.T = A.T;
         } else if (op == "fc") {
             nd.op = Op::Fc;
-            if (!get_int(l, "groups", nd.groups, true, present) || !get_int(l, "out", nd.out, true, present))
-                return fail(err, lineno, "fc needs groups= and out=", kInvalidBlob);
+            nd.groups = A.grp;  // a grouped operand: the FC works inside each group
+            if (!get_int(l, "groups", nd.groups, false, present) || !get_int(l, "out", nd.out, true, present))
+                return fail(err, lineno, "fc needs [groups=] and out=", kInvalidBlob);
+            if (l.attr.count("groups") && A.grp > 1 && nd.groups != A.grp)
+                return fail(err, lineno, "fc groups= contradicts the Group view of its operand", kShapeMismatch);
             if (nd.groups < 1 || nd.out < 1 || A.C % nd.groups || nd.out % nd.groups)
                 return fail(err, lineno, "fc groups must divide input and output channels", kShapeMismatch);
             nd.C = nd.out;
@@ -171,10 +186,15 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             else if (it->second == "min") nd.kind = kBinMin;
             else if (it->second == "max") nd.kind = kBinMax;
             else return fail(err, lineno, "unknown binary op '" + it->second + "'", kUnknownOp);
-            const Node& B = dag.nodes[nd.b];
-            bool legal = (A.C == B.C) ? (B.T % A.T == 0) : (((int64_t)B.C * B.T) % ((int64_t)A.C * A.T) == 0);
+            const Node B = dag.nodes[nd.b];
+            nd.b = viewed(nd.b);
+            // the same Group view on both sides is a common leading dim: the rule applies to [C / G, T] inside each group
+            nd.bgroups = A.grp == B.grp ? A.grp : 1;
+            const int CLg = A.C / nd.bgroups, CRg = B.C / nd.bgroups;
+            bool legal = (CLg == CRg) ? (B.T % A.T == 0) : (((int64_t)CRg * B.T) % ((int64_t)CLg * A.T) == 0);
             if (!A.pooled && B.pooled) legal = false;  // a pooled LHS is replicated over the pixels, not the reverse
             nd.pooled = B.pooled;
+            nd.grp = B.grp;
             if (!legal) return fail(err, lineno, "broadcast: LHS size does not divide RHS size", kShapeMismatch);
             nd.C = B.C;
             nd.T = B.T;
@@ -207,6 +227,7 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
                 if (nd.groups < 1 || A.C % nd.groups) return fail(err, lineno, "fold axis=C: groups must divide the channels", kShapeMismatch);
                 nd.C = nd.groups;
                 nd.T = A.T;
+                nd.grp = 1;
             } else if (nd.axis_hw) {
                 if (A.pooled) return fail(err, lineno, "fold axis=HW: the spatial dims are already folded", kShapeMismatch);
                 nd.T = A.T;
@@ -231,6 +252,24 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             if (dag.nodes[k].b >= 0) dag.nodes[dag.nodes[k].b].live = true;
         }
     return kOk;
+}
+
+Dag without_dead_views(const Dag& dag) {
+    Dag out = dag;
+    out.nodes.clear();
+    std::vector<int> id(dag.nodes.size(), -1);
+    for (size_t k = 0; k < dag.nodes.size(); k++) {
+        const Node& nd = dag.nodes[k];
+        if (nd.op == Op::Group && !nd.live) continue;
+        id[k] = (int)out.nodes.size();
+        Node c = nd;
+        if (c.a >= 0) c.a = id[c.a];
+        if (c.b >= 0) c.b = id[c.b];
+        out.nodes.push_back(c);
+    }
+    out.out = id[dag.out];
+    for (auto& w : out.weight_node) w = id[w];
+    return out;
 }
 
 }  // namespace canvas

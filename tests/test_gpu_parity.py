@@ -71,6 +71,15 @@ PRIMS = [
     ("%1 = unfold %0 kh=3 kw=3\n%2 = binary %0 %1 op=max\noutput %2\n", []),
     ("%1 = unfold %0 kh=3 kw=1\n%2 = fc %0 groups=3 out=6\n%3 = binary %2 %1 op=min\n%4 = fold %3 op=avg\noutput %4\n", [(3, 2, 4)]),
     ("%1 = unary %0 op=gelu\n%2 = binary %1 %0 op=min\n%3 = binary %0 %2 op=sub\noutput %3\n", []),
+    # Group as a node: the view alone, depth-wise 3x3, grouped Involution, a grouped blend with fan-out, mixed views
+    ("%1 = group %0 groups=3\noutput %1\n", []),
+    ("%1 = group %0 groups=12\n%2 = unfold %1 kh=3 kw=3\n%3 = fc %2 out=12\noutput %3\n", [(12, 1, 9)]),
+    ("%1 = group %0 groups=3\n%2 = fc %1 out=27\n%3 = softmax %2 axis=C\n%4 = unfold %1 kh=3 kw=3\n%5 = binary %3 %4 op=mul\n"
+     "%6 = fold %5 op=sum\n%7 = fc %6 out=6\noutput %7\n", [(3, 9, 4), (3, 2, 4)]),
+    ("%1 = group %0 groups=2\n%2 = fc %1 out=4\n%3 = unary %2 op=gelu\n%4 = unfold %1 kh=1 kw=3\n%5 = binary %3 %4 op=sub\n"
+     "%6 = binary %2 %5 op=max\n%7 = fold %6 op=avg\n%8 = binary %7 %0 op=add\noutput %8\n", [(2, 2, 6)]),
+    ("%1 = group %0 groups=4\n%2 = fc %1 out=8\n%3 = group %2 groups=2\n%4 = fc %3 out=6\n%5 = binary %4 %1 op=mul\n%6 = group %5 groups=6\noutput %6\n",
+     [(4, 2, 3), (2, 3, 4)]),
 ]
 
 
@@ -220,6 +229,35 @@ def test_fused_dynamic_window_weights_variants(harness, oracle, idx):
     case = _mk(body, (N, C, H, W), "bf16", 400 + idx, wshapes, f"dyn{idx}")
     res, r, dy = harness.run_case(case)
     assert r.info.fused == 1, "the fused lowering was not selected"
+    check_against_oracle(oracle, case, res, dy)
+    r.close()
+
+
+GROUPED_DYN = [
+    # (window, G, softmax, fold, out of FC2, N, C, H, W): the Involution of Section 5 with G groups of per-pixel window weights
+    (3, 4, True, "sum", 32, 2, 32, 9, 11),
+    (3, 16, False, "avg", 64, 3, 64, 14, 14),   # many small groups (4 channels each)
+    (5, 2, True, "sum", 24, 2, 24, 7, 6),
+    (3, 8, True, "sum", 8, 1, 8, 5, 8),         # one channel per group
+    (7, 3, False, "sum", 12, 2, 12, 6, 9),      # window outside the fused family: per-node lowering
+]
+
+
+@pytest.mark.parametrize("flags", [0, B.CANVAS_OPT_NO_FUSION])
+@pytest.mark.parametrize("idx", range(len(GROUPED_DYN)))
+def test_grouped_involution(harness, oracle, idx, flags):
+    k, G, soft, fold, o2, N, C, H, W = GROUPED_DYN[idx]
+    body = f"%1 = group %0 groups={G}\n%2 = fc %1 out={G * k * k}\n"
+    a = 2
+    if soft:
+        body += "%3 = softmax %2 axis=C\n"
+        a = 3
+    body += (f"%{a + 1} = unfold %1 kh={k} kw={k}\n%{a + 2} = binary %{a} %{a + 1} op=mul\n%{a + 3} = fold %{a + 2} op={fold}\n"
+             f"%{a + 4} = fc %{a + 3} out={o2}\noutput %{a + 4}\n")
+    wshapes = [(G, k * k, C // G), (G, o2 // G, C // G)]
+    case = _mk(body, (N, C, H, W), "bf16", 450 + idx, wshapes, f"gdyn{idx}")
+    res, r, dy = harness.run_case(case, flags)
+    assert r.info.fused == (1 if flags == 0 and k <= 5 and C // G != k * k else 0)
     check_against_oracle(oracle, case, res, dy)
     r.close()
 

@@ -220,3 +220,37 @@ def test_inference_plan_moves_weight_only_launches_out_of_forward(lib):
     hi = B.canvas_dag_compile(wl.blob_sampled(64), (2, 64, 14, 14), B.CANVAS_BF16, B.CANVAS_OPT_INFERENCE)
     assert B.canvas_dag_query(hi).n_launches_prepare >= 1
     B.canvas_dag_destroy(hi)
+
+
+def test_group_views_shapes_and_legality(lib, oracle):
+    """Group nodes: shapes and weight shapes equal the oracle's, the same blobs are refused, and a Group node
+    costs no launch unless it is the output."""
+    H_ = wl.HEADER
+    ok = ["%1 = group %0 groups=4\n%2 = unfold %1 kh=3 kw=3\n%3 = fold %2 op=max axis=HW\n%4 = fc %3 out=12\noutput %4\n",
+          "%1 = group %0 groups=2\n%2 = fc %1 out=18\n%3 = unfold %1 kh=3 kw=3\n%4 = binary %2 %3 op=mul\n%5 = fold %4 op=sum\noutput %5\n",
+          "%1 = group %0 groups=8\n%2 = unfold %1 kh=3 kw=3\n%3 = fc %2 out=8\n%4 = group %3 groups=2\n%5 = fc %4 groups=2 out=4\noutput %5\n",
+          "%1 = group %0 groups=2\n%2 = fold %1 op=sum axis=C groups=4\n%3 = fc %2 out=4\noutput %3\n",
+          "%1 = group %0 groups=2\noutput %1\n",
+          "%1 = group %0 groups=2\n%2 = fc %1 out=4\n%3 = binary %2 %0 op=add\noutput %3\n"]
+    for body in ok:
+        ns, out, ws = oracle.infer(H_ + body, (2, 8, 5, 6))
+        for flags in (0, B.CANVAS_OPT_NO_FUSION):
+            h = B.canvas_dag_compile(H_ + body, (2, 8, 5, 6), B.CANVAS_BF16, flags)
+            info = B.canvas_dag_query(h)
+            assert info.n_nodes == len(ns) and info.out_node == out and info.n_weights == len(ws)
+            for k, s_ in enumerate(ns):
+                assert list(info.node_shape[k]) == [2] + s_
+            for k, s_ in enumerate(ws):
+                assert list(info.weight_shape[k]) == s_
+            names = [B.canvas_dag_launch_desc(h, 0, i)["name"] for i in range(info.n_launches_fwd)]
+            assert ("node_group_fwd" in names) == body.endswith("groups=2\noutput %1\n")
+            B.canvas_dag_destroy(h)
+    bad = ["%1 = group %0 groups=3\noutput %1\n", "%1 = group %0\noutput %1\n", "%1 = group %0 groups=0\noutput %1\n",
+           "%1 = group %0 groups=2\n%2 = fc %1 groups=4 out=8\noutput %2\n",
+           "%1 = group %0 groups=2\n%2 = fc %1 out=6\n%3 = binary %2 %1 op=add\noutput %3\n"]
+    for body in bad:
+        with pytest.raises(Exception):
+            oracle.infer(H_ + body, (2, 8, 5, 6))
+        with pytest.raises(B.CanvasError) as e:
+            B.canvas_dag_compile(H_ + body, (2, 8, 5, 6), B.CANVAS_BF16)
+        assert e.value.status in (-1, -3)
