@@ -35,6 +35,10 @@
  *                                       replicated over the pixels of a full-size RHS; axis=C groups=G folds the
  *                                       C/G channels of each of G groups: the result has G channels)
  *     %7 = softmax %6 axis=C           (C | T | CT: over channels, over taps, or over both jointly)
+ *     %9 = binary %a %b op=mul lhs=pixels   (a pooled LHS [H*W, 1, 1, 1] whose channels are laid over the
+ *                                       pixels of a full-size RHS: out(c,t,h,w) = op(LHS(h*W+w), RHS(c,t,h,w));
+ *                                       Section 8's kernel that pools to [C], maps to H x W with an FC and
+ *                                       multiplies the input with the result)
  *     %8 = group %7 groups=4           (the Group primitive as a node of its own: the same data seen as
  *                                       [G, C/G, T, H, W]; groups=C makes every channel a group.  The view
  *                                       travels through unfold, shift, unary, softmax, fold over T / HW and
@@ -76,6 +80,7 @@ typedef struct {
     int axis_c;         /* fold: 1 = over the C / groups channels of each of `groups` channel groups */
     int widx;           /* fc: index into the weight list */
     int grp;            /* Group view of the channel dim: [grp, C/grp]; 1 = not grouped */
+    int lhs_pixels;     /* binary: the pooled LHS's H*W channels are laid over the pixels of the RHS */
 } Node;
 
 typedef struct {
@@ -305,6 +310,18 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 else if (!strcmp(k2, "max")) nd->kind = BIN_MAX;
                 else { set_err(err, errlen, "unknown binary op", lineno); goto done; }
                 B = &d->node[nd->b];
+                {
+                    const char *al = find_attr(tok, ntok, "lhs");
+                    if (al && strcmp(al, "pixels")) { set_err(err, errlen, "binary lhs= must be pixels", lineno); goto done; }
+                    nd->lhs_pixels = al != NULL;
+                }
+                if (nd->lhs_pixels) {
+                    /* the dim lists [X] and [C, T, H, W] share the suffix once X is read as [H, W] */
+                    if (!A->pooled || B->pooled || (long)A->C * A->T != (long)H * W) {
+                        set_err(err, errlen, "binary lhs=pixels needs a pooled LHS with H*W elements and a full-size RHS", lineno);
+                        goto done;
+                    }
+                } else
                 if (!(A->grp == B->grp && A->grp > 1 ? broadcast_legal_g(A->grp, A->C, A->T, B->C, B->T)
                                                      : broadcast_legal(A->C, A->T, B->C, B->T)) ||
                     (!A->pooled && B->pooled)) {
@@ -454,6 +471,16 @@ static void fwd_unary(const Dag *d, const Node *nd, int k, const double *in, dou
     }
 }
 
+static double blend(int kind, double a, double b) {
+    switch (kind) {
+    case BIN_ADD: return a + b;
+    case BIN_MUL: return a * b;
+    case BIN_SUB: return a - b;
+    case BIN_MIN: return a <= b ? a : b;
+    default: return a >= b ? a : b;
+    }
+}
+
 static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const double *rhs, double *out) {
     const Node *L = &d->node[nd->a];
     int P = node_P(d, nd), PL = node_P(d, L), c, t, p, cl, tl;  /* PL == 1 < P: the LHS is replicated over the pixels */
@@ -461,19 +488,15 @@ static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
         for (t = 0; t < nd->T; t++) {
             const double *lrow, *rrow = rhs + ((size_t)c * nd->T + t) * P;
             double *orow = out + ((size_t)c * nd->T + t) * P;
+            if (nd->lhs_pixels) {  /* LHS element p meets pixel p of every channel and tap */
+                for (p = 0; p < P; p++) orow[p] = blend(nd->kind, lhs[p], rrow[p]);
+                continue;
+            }
             if (L->grp == nd->grp && nd->grp > 1) broadcast_index_g(nd->grp, L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             else broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             lrow = lhs + ((size_t)cl * L->T + tl) * PL;
             for (p = 0; p < P; p++) {
-                double a = lrow[PL == 1 ? 0 : p], b = rrow[p], y = 0.0;
-                switch (nd->kind) {
-                case BIN_ADD: y = a + b; break;
-                case BIN_MUL: y = a * b; break;
-                case BIN_SUB: y = a - b; break;
-                case BIN_MIN: y = a <= b ? a : b; break;
-                case BIN_MAX: y = a >= b ? a : b; break;
-                }
-                orow[p] = y;
+                orow[p] = blend(nd->kind, lrow[PL == 1 ? 0 : p], rrow[p]);
             }
         }
 }
@@ -628,11 +651,12 @@ static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
     for (c = 0; c < nd->C; c++)
         for (t = 0; t < nd->T; t++) {
             size_t ro = ((size_t)c * nd->T + t) * P, lo;
-            if (L->grp == nd->grp && nd->grp > 1) broadcast_index_g(nd->grp, L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
+            if (nd->lhs_pixels) { cl = 0; tl = 0; }
+            else if (L->grp == nd->grp && nd->grp > 1) broadcast_index_g(nd->grp, L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             else broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             lo = ((size_t)cl * L->T + tl) * PL;
             for (p = 0; p < P; p++) {
-                size_t lp = lo + (PL == 1 ? 0 : p);
+                size_t lp = nd->lhs_pixels ? (size_t)p : lo + (PL == 1 ? 0 : p);
                 double g = gout[ro + p], a = lhs[lp], b = rhs[ro + p];
                 switch (nd->kind) {
                 case BIN_ADD: glhs[lp] += g; grhs[ro + p] += g; break;

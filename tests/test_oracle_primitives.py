@@ -164,6 +164,9 @@ FD_BODIES = [
     ("%1 = group %0 groups=2\n%2 = fc %1 out=6\n%3 = softmax %2 axis=C\n%4 = unfold %1 kh=3 kw=1\n%5 = binary %3 %4 op=mul\n"
      "%6 = fold %5 op=sum\n%7 = fc %6 out=4\noutput %7\n", [(2, 3, 2), (2, 2, 2)]),
     ("%1 = group %0 groups=4\n%2 = unfold %1 kh=3 kw=3\n%3 = fc %2 out=8\n%4 = unary %3 op=gelu\n%5 = binary %1 %4 op=mul\noutput %5\n", [(4, 2, 9)]),
+    # spatial aggregation and kernel spanning: pool to [C], FC to H*W (= 20 here), laid over the pixels of x
+    ("%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=20\n%3 = unary %2 op=gelu\n%4 = binary %3 %0 op=mul lhs=pixels\noutput %4\n", [(1, 20, 4)]),
+    ("%1 = unfold %0 kh=1 kw=3\n%2 = fold %0 op=max axis=HW\n%3 = fc %2 groups=2 out=20\n%4 = binary %3 %1 op=max lhs=pixels\n%5 = fold %4 op=sum\noutput %5\n", [(2, 10, 2)]),
 ]
 
 
@@ -628,6 +631,38 @@ def test_group_view_legality_and_propagation(oracle):
     assert ws == [[1, 4, 4]]
     ns, _, ws = oracle.infer(H_ + "%1 = group %0 groups=4\n%2 = unfold %1 kh=3 kw=3\n%3 = fold %2 op=max axis=HW\n%4 = fc %3 out=12\noutput %4\n", (1, 8, 3, 3))
     assert ws == [[4, 3, 18]] and ns[4] == [12, 1, 1, 1]
+
+
+def test_pooled_vector_laid_over_the_pixels(oracle):
+    """Section 8, the kernel with spatial aggregation and kernel spanning: pool [C,H,W] to [C], an FC to H*W
+    outputs, multiplied with the input: y(c,h,w) = x(c,h,w) * (W mean_hw x)(h*W+w); the gradient of the
+    vector sums over channels (and taps)."""
+    rng = np.random.default_rng(80)
+    N, C, H, W = 2, 3, 4, 5
+    x = rng.standard_normal((N, C, H, W))
+    w = rng.standard_normal((1, H * W, C))
+    body = f"%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out={H * W}\n%3 = binary %2 %0 op=mul lhs=pixels\noutput %3\n"
+    dy = rng.standard_normal((N, C, H, W))
+    r = run1(oracle, body, x, [w], dy)
+    v = np.einsum("oc,nc->no", w[0], x.mean(axis=(2, 3))).reshape(N, 1, H, W)
+    np.testing.assert_allclose(r["y"], x * v, atol=1e-14)
+    dv = (dy * x).sum(axis=1).reshape(N, H * W)                     # gradient of the vector
+    np.testing.assert_allclose(r["dw"][0][0], np.einsum("no,nc->oc", dv, x.mean(axis=(2, 3))), atol=1e-12)
+    dx = dy * v + np.einsum("no,oc->nc", dv, w[0])[:, :, None, None] / (H * W)
+    np.testing.assert_allclose(r["dx"], dx, atol=1e-12)
+    # operand order and taps: tile(LHS) - RHS on an unfolded RHS
+    u = run1(oracle, "%1 = unfold %0 kh=3 kw=1\noutput %1\n", x)["y"]
+    got = run1(oracle, f"%1 = unfold %0 kh=3 kw=1\n%2 = fold %0 op=sum axis=HW\n%3 = fc %2 groups=1 out={H * W}\n"
+                       "%4 = binary %3 %1 op=sub lhs=pixels\noutput %4\n", x, [w])["y"]
+    vec = np.einsum("oc,nc->no", w[0], x.sum(axis=(2, 3))).reshape(N, 1, 1, H, W)
+    np.testing.assert_allclose(got, vec - u, atol=1e-12)
+    # legality: the LHS must be pooled and have exactly H*W elements, the RHS must have its pixels
+    for bad in (f"%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out={H * W + 1}\n%3 = binary %2 %0 op=mul lhs=pixels\noutput %3\n",
+                f"%1 = fc %0 groups=1 out={H * W}\n%2 = binary %1 %0 op=mul lhs=pixels\noutput %2\n",
+                f"%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out={H * W}\n%3 = binary %2 %1 op=mul lhs=pixels\noutput %3\n",
+                f"%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out={H * W}\n%3 = binary %2 %0 op=mul lhs=channels\noutput %3\n"):
+        with pytest.raises(Exception):
+            run1(oracle, bad, x, [rng.standard_normal((1, H * W + 1, C))])
 
 
 def test_fan_out_gradients_add(oracle):
