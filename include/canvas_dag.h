@@ -16,7 +16,7 @@
  *     %2 = fc %1 groups=8 out=64
  *     %3 = unary %2 op=gelu            relu | abs | gelu | sin | expclip lo=<f> hi=<f>
  *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
- *     %5 = binary %0 %4 op=mul         first operand LHS, second RHS; add | sub | mul | min | max
+ *     %5 = binary %0 %4 op=mul         first operand LHS, second RHS; add | sub | mul | min | max [lhs=pixels]
  *     %6 = fold %5 op=avg              sum | avg | max [axis=T | HW | C [groups=<G>]]
  *     %7 = softmax %6 axis=C           C | T | CT
  *     %8 = group %7 groups=4           a view [G, C/G] of the channels; groups=C: every channel a group
@@ -38,6 +38,9 @@
  *            lhs t = t mod T_L); otherwise the LHS is replicated along the
  *            flattened (c*T_R + t) index modulo C_L*T_L.  The LHS size must
  *            divide the RHS size.  op: add, sub (tile(LHS) - RHS), mul, min, max.
+ *            With lhs=pixels a pooled LHS of exactly H*W elements is laid over the
+ *            pixels instead: out(c,t,h,w) = op(LHS(h*W+w), RHS(c,t,h,w)) (Section 8,
+ *            the kernel that pools to [C], maps to H x W with an FC and multiplies x).
  *   softmax  along C (per n,t,h,w), along T (per n,c,h,w) or along both jointly
  *            (axis=CT, per n,h,w) (Section 5, Softmax over contiguous dims).
  *   fold     sum, avg or max over T; T disappears (Section 5, Folding).  Max

@@ -29,6 +29,7 @@ struct Node {
     int axis_c = 0;              // fold: 1 = over the C / groups channels of each of `groups` channel groups
     bool pooled = false;         // the spatial dims have been folded away: shape [N, C, T, 1, 1]
     int grp = 1;                 // Group view of the channel dim, [grp, C / grp] (1 = none)
+    bool lhs_pixels = false;     // binary: the pooled LHS has H*W elements, element p meets pixel p of every channel and tap
     int bgroups = 1;             // binary: > 1 when both operands carry this same view, the blend then runs inside each group
     int C = 0, T = 1;            // inferred shape
     int widx = -1;               // fc: index into the weight list

@@ -196,8 +196,10 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             const int Pn = dag.Pk(k), PL = dag.Pk(nd.a);
             // a common Group dim: (image, group) pairs are independent, each blends [CL/G, TL] onto [CR/G, TR]
             const int Gb = nd.bgroups;
+            // lhs=pixels: the [H*W, 1, 1, 1] LHS is a one-channel full-size tensor to the kernel
+            const int CLk = nd.lhs_pixels ? 1 : A.C / Gb, TLk = nd.lhs_pixels ? 1 : A.T, PLk = nd.lhs_pixels ? Pn : PL;
             L.run = [=](const RunArgs& a) {
-                ref::binary_fwd(val(a, nd.a), val(a, nd.b), valw(a, k), N * Gb, A.C / Gb, A.T, B.C / Gb, B.T, Pn, PL, nd.kind, a.stream);
+                ref::binary_fwd(val(a, nd.a), val(a, nd.b), valw(a, k), N * Gb, CLk, TLk, B.C / Gb, B.T, Pn, PLk, nd.kind, a.stream);
             };
             break;
         }
@@ -335,8 +337,9 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             L.name = "node_binary_bwd_lhs";
             L.bytes = 4.0 * (dag.numel(nd.a) * (1 + acc) + dag.numel(k) * (nd.kind == kAdd || nd.kind == kSub ? 1 : 2));
             const int Pn = dag.Pk(k), PL = dag.Pk(nd.a), Gb = nd.bgroups;
+            const int CLk = nd.lhs_pixels ? 1 : A.C / Gb, TLk = nd.lhs_pixels ? 1 : A.T, PLk = nd.lhs_pixels ? Pn : PL;
             L.run = [=](const RunArgs& a) {
-                ref::binary_bwd_lhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.a), N * Gb, A.C / Gb, A.T, B.C / Gb, B.T, Pn, PL, nd.kind, acc, a.stream);
+                ref::binary_bwd_lhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.a), N * Gb, CLk, TLk, B.C / Gb, B.T, Pn, PLk, nd.kind, acc, a.stream);
             };
             low->bwd.push_back(std::move(L));
             written[nd.a] = true;
@@ -345,7 +348,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             R.name = "node_binary_bwd_rhs";
             R.bytes = 4.0 * (dag.numel(nd.b) * (1 + acc_r) + dag.numel(k) + (nd.kind == kAdd || nd.kind == kSub ? 0 : dag.numel(nd.a)));
             R.run = [=](const RunArgs& a) {
-                ref::binary_bwd_rhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.b), N * Gb, A.C / Gb, A.T, B.C / Gb, B.T, Pn, PL, nd.kind, acc_r, a.stream);
+                ref::binary_bwd_rhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.b), N * Gb, CLk, TLk, B.C / Gb, B.T, Pn, PLk, nd.kind, acc_r, a.stream);
             };
             low->bwd.push_back(std::move(R));
             written[nd.b] = true;

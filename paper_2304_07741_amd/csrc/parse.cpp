@@ -193,6 +193,14 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             const int CLg = A.C / nd.bgroups, CRg = B.C / nd.bgroups;
             bool legal = (CLg == CRg) ? (B.T % A.T == 0) : (((int64_t)CRg * B.T) % ((int64_t)CLg * A.T) == 0);
             if (!A.pooled && B.pooled) legal = false;  // a pooled LHS is replicated over the pixels, not the reverse
+            auto al = l.attr.find("lhs");
+            if (al != l.attr.end()) {
+                if (al->second != "pixels") return fail(err, lineno, "binary lhs= must be pixels", kInvalidBlob);
+                // [X] read as [H, W]: a common suffix with the RHS; nothing of the LHS is left to replicate along channels
+                nd.lhs_pixels = true;
+                nd.bgroups = 1;
+                legal = A.pooled && !B.pooled && (int64_t)A.C * A.T == (int64_t)dag.H * dag.W;
+            }
             nd.pooled = B.pooled;
             nd.grp = B.grp;
             if (!legal) return fail(err, lineno, "broadcast: LHS size does not divide RHS size", kShapeMismatch);

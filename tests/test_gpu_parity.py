@@ -71,6 +71,10 @@ PRIMS = [
     ("%1 = unfold %0 kh=3 kw=3\n%2 = binary %0 %1 op=max\noutput %2\n", []),
     ("%1 = unfold %0 kh=3 kw=1\n%2 = fc %0 groups=3 out=6\n%3 = binary %2 %1 op=min\n%4 = fold %3 op=avg\noutput %4\n", [(3, 2, 4)]),
     ("%1 = unary %0 op=gelu\n%2 = binary %1 %0 op=min\n%3 = binary %0 %2 op=sub\noutput %3\n", []),
+    # pooled vector laid over the pixels (spatial aggregation and kernel spanning, Section 8); 9 x 11 = 99 pixels
+    ("%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=99\n%3 = binary %2 %0 op=mul lhs=pixels\noutput %3\n", [(1, 99, 12)]),
+    ("%1 = unfold %0 kh=1 kw=3\n%2 = fold %0 op=max axis=HW\n%3 = fc %2 groups=3 out=99\n%4 = unary %3 op=gelu\n"
+     "%5 = binary %4 %1 op=sub lhs=pixels\n%6 = fold %5 op=avg\n%7 = binary %0 %6 op=min\noutput %7\n", [(3, 33, 4)]),
     # Group as a node: the view alone, depth-wise 3x3, grouped Involution, a grouped blend with fan-out, mixed views
     ("%1 = group %0 groups=3\noutput %1\n", []),
     ("%1 = group %0 groups=12\n%2 = unfold %1 kh=3 kw=3\n%3 = fc %2 out=12\noutput %3\n", [(12, 1, 9)]),

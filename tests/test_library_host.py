@@ -254,3 +254,19 @@ def test_group_views_shapes_and_legality(lib, oracle):
         with pytest.raises(B.CanvasError) as e:
             B.canvas_dag_compile(H_ + body, (2, 8, 5, 6), B.CANVAS_BF16)
         assert e.value.status in (-1, -3)
+
+
+def test_pixel_aligned_blend_legality(lib, oracle):
+    H_ = wl.HEADER
+    good = "%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=30\n%3 = binary %2 %0 op=mul lhs=pixels\noutput %3\n"
+    ns, out, ws = oracle.infer(H_ + good, (2, 8, 5, 6))
+    h = B.canvas_dag_compile(H_ + good, (2, 8, 5, 6), B.CANVAS_BF16)
+    info = B.canvas_dag_query(h)
+    assert [list(info.node_shape[k]) for k in range(info.n_nodes)] == [[2] + s_ for s_ in ns] and list(info.out_shape) == [2, 8, 1, 5, 6]
+    B.canvas_dag_destroy(h)
+    for bad in (good.replace("out=30", "out=15"), good.replace("%2 %0 op=mul", "%2 %1 op=mul"), good.replace("lhs=pixels", "lhs=rows"),
+                "%1 = fc %0 groups=1 out=30\n%2 = binary %1 %0 op=mul lhs=pixels\noutput %2\n"):
+        with pytest.raises(Exception):
+            oracle.infer(H_ + bad, (2, 8, 5, 6))
+        with pytest.raises(B.CanvasError):
+            B.canvas_dag_compile(H_ + bad, (2, 8, 5, 6), B.CANVAS_BF16)
