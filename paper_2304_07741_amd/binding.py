@@ -19,6 +19,11 @@ STATUS = {0: "OK", -1: "INVALID_BLOB", -2: "UNKNOWN_OP", -3: "SHAPE_MISMATCH", -
 EXPORTS = ["canvas_dag_compile", "canvas_dag_query", "canvas_dag_launch_desc", "canvas_dag_forward",
            "canvas_dag_backward", "canvas_dag_prepare", "canvas_dag_set_timing", "canvas_dag_get_timing", "canvas_dag_destroy",
            "canvas_last_error"]
+# include/canvas_template.h (host only)
+TEMPLATE_EXPORTS = ["canvas_template_parse", "canvas_template_query", "canvas_template_node_shape", "canvas_template_substitutions",
+                    "canvas_template_substitute", "canvas_group_candidates", "canvas_template_solve",
+                    "canvas_template_instantiate", "canvas_template_destroy"]
+CANVAS_MAX_VARS = 8
 
 
 class CanvasOptions(ctypes.Structure):
@@ -37,6 +42,19 @@ class CanvasDagInfo(ctypes.Structure):
         ("workspace_bytes", ctypes.c_uint64),
         ("fc_flops_fwd", ctypes.c_double), ("min_bytes_fwd", ctypes.c_double), ("min_bytes_bwd", ctypes.c_double),
     ]
+
+
+class CanvasTarget(ctypes.Structure):
+    _fields_ = [("C", ctypes.c_int64), ("KH", ctypes.c_int64), ("KW", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64)]
+
+
+class CanvasTemplateInfo(ctypes.Structure):
+    _fields_ = [("n_nodes", ctypes.c_int32), ("out_node", ctypes.c_int32), ("n_fc", ctypes.c_int32), ("n_free", ctypes.c_int32),
+                ("free_var", ctypes.c_int32 * CANVAS_MAX_VARS), ("uses_G", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
+
+
+class CanvasSolveResult(ctypes.Structure):
+    _fields_ = [("flops", ctypes.c_double), ("params", ctypes.c_double), ("rounds", ctypes.c_int32), ("reserved", ctypes.c_int32 * 7)]
 
 
 class CanvasLaunchDesc(ctypes.Structure):
@@ -72,6 +90,19 @@ def load():
         lib.canvas_dag_destroy.argtypes = [vp]
         lib.canvas_dag_destroy.restype = None
         lib.canvas_last_error.restype = ctypes.c_char_p
+        ip, szp = ctypes.POINTER(ctypes.c_int), ctypes.POINTER(sz)
+        lib.canvas_template_parse.argtypes = [ctypes.c_char_p, sz, ctypes.POINTER(vp)]
+        lib.canvas_template_query.argtypes = [vp, ctypes.POINTER(CanvasTemplateInfo)]
+        lib.canvas_template_node_shape.argtypes = [vp, ctypes.c_int, ctypes.c_char_p, sz, szp]
+        lib.canvas_template_substitutions.argtypes = [vp, ctypes.c_int, ip, ip, ctypes.c_char_p, sz, szp]
+        lib.canvas_template_substitute.argtypes = [vp, ctypes.c_int, ctypes.c_char_p]
+        lib.canvas_group_candidates.argtypes = [ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ip]
+        lib.canvas_template_solve.argtypes = [vp, ctypes.POINTER(CanvasTarget), ctypes.c_int, ctypes.c_int64, ctypes.c_double,
+                                              ctypes.c_double, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(CanvasSolveResult)]
+        lib.canvas_template_instantiate.argtypes = [vp, ctypes.POINTER(CanvasTarget), ctypes.c_int64, ctypes.POINTER(ctypes.c_int64),
+                                                    ctypes.c_char_p, sz, szp]
+        lib.canvas_template_destroy.argtypes = [vp]
+        lib.canvas_template_destroy.restype = None
         _lib = lib
     return _lib
 
@@ -147,3 +178,85 @@ def canvas_dag_get_timing(handle, backward, n):
 
 def canvas_dag_destroy(handle):
     load().canvas_dag_destroy(handle)
+
+
+# ---------------------------------------------------------------- templates (include/canvas_template.h), host only
+
+def _text(call):
+    """Run call(buf, len, needed_ptr) with a buffer that is grown once if the library asks for more."""
+    n = 4096
+    for _ in range(2):
+        buf = ctypes.create_string_buffer(n)
+        needed = ctypes.c_size_t(0)
+        rc = call(buf, n, ctypes.byref(needed))
+        if rc == 0:
+            return buf.value.decode()
+        if needed.value <= n:
+            break
+        n = needed.value
+    _check(rc)
+
+
+def canvas_template_parse(blob):
+    b = blob.encode() if isinstance(blob, str) else bytes(blob)
+    h = ctypes.c_void_p()
+    _check(load().canvas_template_parse(b, len(b), ctypes.byref(h)))
+    return h
+
+
+def canvas_template_query(handle):
+    info = CanvasTemplateInfo()
+    _check(load().canvas_template_query(handle, ctypes.byref(info)))
+    return info
+
+
+def canvas_template_node_shape(handle, node):
+    return _text(lambda buf, n, need: load().canvas_template_node_shape(handle, int(node), buf, n, need))
+
+
+def canvas_template_substitutions(handle, node):
+    """Returns (j of the LHS variable x_j, list of substitution expressions)."""
+    var, count = ctypes.c_int(0), ctypes.c_int(0)
+    text = _text(lambda buf, n, need: load().canvas_template_substitutions(handle, int(node), ctypes.byref(var), ctypes.byref(count), buf, n, need))
+    subs = text.split("\n")[:-1] if text else []
+    assert len(subs) == count.value
+    return var.value, subs
+
+
+def canvas_template_substitute(handle, var, expr):
+    _check(load().canvas_template_substitute(handle, int(var), expr.encode()))
+
+
+def canvas_group_candidates(channels):
+    c = (ctypes.c_int64 * len(channels))(*[int(v) for v in channels])
+    out = (ctypes.c_int64 * 4096)()
+    n = ctypes.c_int(0)
+    _check(load().canvas_group_candidates(c, len(channels), out, 4096, ctypes.byref(n)))
+    return [int(out[i]) for i in range(n.value)]
+
+
+def _targets(targets):
+    arr = (CanvasTarget * len(targets))()
+    for i, t in enumerate(targets):
+        arr[i] = CanvasTarget(*[int(t[k]) for k in ("C", "KH", "KW", "H", "W")])
+    return arr
+
+
+def canvas_template_solve(handle, targets, G, flops_budget=0.0, params_budget=0.0):
+    """targets: list of dicts with C, KH, KW, H, W.  Returns (x[i] = {j: x_ij}, flops, params, rounds)."""
+    arr = _targets(targets)
+    x = (ctypes.c_int64 * (len(targets) * CANVAS_MAX_VARS))()
+    res = CanvasSolveResult()
+    _check(load().canvas_template_solve(handle, arr, len(targets), int(G), float(flops_budget), float(params_budget), x, ctypes.byref(res)))
+    xs = [{j + 1: int(x[i * CANVAS_MAX_VARS + j]) for j in range(CANVAS_MAX_VARS) if x[i * CANVAS_MAX_VARS + j]} for i in range(len(targets))]
+    return xs, res.flops, res.params, res.rounds
+
+
+def canvas_template_instantiate(handle, target, G, x):
+    arr = _targets([target])
+    xv = (ctypes.c_int64 * CANVAS_MAX_VARS)(*[int(x.get(j + 1, 0)) for j in range(CANVAS_MAX_VARS)])
+    return _text(lambda buf, n, need: load().canvas_template_instantiate(handle, arr, int(G), xv, buf, n, need))
+
+
+def canvas_template_destroy(handle):
+    load().canvas_template_destroy(handle)

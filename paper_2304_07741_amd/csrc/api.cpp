@@ -22,18 +22,22 @@ struct canvas_dag {
     bool timed_once[2] = {false, false};
 };
 
-namespace canvas {
-thread_local TimingEvents g_timing;
+namespace {
+thread_local std::string g_err;
 }
 
-namespace {
-
-thread_local std::string g_err;
-
-int set_err(int code, const std::string& msg) {
+namespace canvas {
+thread_local TimingEvents g_timing;
+// the message canvas_last_error() returns, for the other translation units of the C ABI
+int set_last_error(int code, const std::string& msg) {
     g_err = msg;
     return code;
 }
+}  // namespace canvas
+
+namespace {
+
+int set_err(int code, const std::string& msg) { return canvas::set_last_error(code, msg); }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -265,3 +265,74 @@ def config5(seed, attempt=0, N=16, C=96, H=32):
     blob, wshapes = fuzz_dag(seed, attempt, C)
     stds = [1.0 / math.sqrt(s[2]) for s in wshapes]
     return _case(f"fuzz_{seed}_{attempt}", blob, (N, C, H, H), "bf16", seed * 7919 + attempt, wshapes, stds)
+
+
+# ----------------------------------------------------------------------------- kernel templates (symbolic sizes)
+
+TEMPLATE_HEADER = "canvas-template 1\n"
+
+# the two worked examples of the paper's solver sections, as templates
+TEMPLATE_SHAPE_MATCHING = (TEMPLATE_HEADER + "%1 = unfold %0 kh=KH kw=1\n%2 = fc %1 groups=1 out=x1\n%3 = unfold %2 kh=KH kw=1\n"
+                           "%4 = group %0 groups=G\n%5 = fc %4 out=x2\n%6 = unfold %5 kh=KH kw=KW\n%7 = binary %3 %6 op=mul\n"
+                           "%8 = fold %7 op=avg\n%9 = fc %8 out=C\noutput %9\n")
+TEMPLATE_CONSTRAINTS = (TEMPLATE_HEADER + "%1 = fc %0 groups=1 out=G*KH\n%2 = fc %0 groups=1 out=x1\n%3 = binary %1 %2 op=mul\n"
+                        "%4 = fc %3 groups=1 out=C\noutput %4\n")
+
+
+def fuzz_template(seed):
+    """A random kernel template (text).  Structure only: sizes are symbols, FC widths are new dynamic variables
+    or expressions; not every draw is legal, which is part of what the tests compare."""
+    rng = IntRng(seed * 7777 + 13)
+    lines = [TEMPLATE_HEADER]
+    n, nvar, cur = 0, 0, 0
+    depth = 3 + rng.below(7)
+
+    def emit(text):
+        nonlocal n, cur
+        n += 1
+        cur = n
+        lines.append(f"%{n} = {text}\n")
+
+    for _ in range(depth):
+        kind = rng.choice(["unfold", "shift", "group", "fc", "fc", "unary", "binary", "binary", "softmax", "fold"])
+        if kind == "unfold":
+            emit(f"unfold %{cur} kh={rng.choice(['KH', '1', '3'])} kw={rng.choice(['KW', '1', '3', 'KW'])}")
+        elif kind == "shift":
+            emit(f"shift %{cur} dh={rng.choice([0, 1, -1])} dw={rng.choice([0, 1, -1])}" + rng.choice(["", " c0=0 c1=C/2", ""]))
+        elif kind == "group":
+            emit(f"group %{cur} groups={rng.choice(['G', 'G', 'C', '2'])}")
+        elif kind == "fc":
+            if rng.below(2) == 0 and nvar < 8:
+                nvar += 1
+                out = f"x{nvar}"
+            else:
+                out = rng.choice(["C", "G*KH", "C/G", "2*C", "KH*KW", "G*KH*KW", "H*W", "C/2"])
+            emit(f"fc %{rng.choice([cur, 0])}{rng.choice(['', ' groups=1', ' groups=G', ''])} out={out}")
+        elif kind == "unary":
+            emit(f"unary %{cur} op={rng.choice(['relu', 'gelu', 'abs', 'sin'])}")
+        elif kind == "binary":
+            other = rng.below(n + 1)
+            a, b = (cur, other) if rng.below(2) else (other, cur)
+            emit(f"binary %{a} %{b} op={rng.choice(['add', 'mul', 'sub', 'max'])}" + (" lhs=pixels" if rng.below(12) == 0 else ""))
+        elif kind == "softmax":
+            emit(f"softmax %{cur} axis={rng.choice(['C', 'T', 'CT'])}")
+        else:
+            ax = rng.choice(["", "", " axis=HW", " axis=C groups=G", " axis=C"])
+            emit(f"fold %{cur} op={rng.choice(['sum', 'avg', 'max'])}{ax}")
+    emit(f"fold %{cur} op=avg")
+    emit(f"fc %{cur} out=C")
+    lines.append(f"output %{cur}\n")
+    return "".join(lines)
+
+
+def fuzz_targets(seed):
+    """Replacement targets (C, KH, KW, H, W) at ResNet-like sizes plus a group number dividing every C."""
+    rng = IntRng(seed * 31337 + 5)
+    nt = 1 + rng.below(4)
+    G = rng.choice([1, 2, 4, 8])
+    targets = []
+    for _ in range(nt):
+        k = rng.choice([1, 3, 3, 5, 7])
+        side = rng.choice([7, 14, 28, 56])
+        targets.append({"C": rng.choice([16, 24, 32, 48, 64, 96, 128, 256]), "KH": k, "KW": rng.choice([k, k, 1, 3]), "H": side, "W": side})
+    return targets, G
