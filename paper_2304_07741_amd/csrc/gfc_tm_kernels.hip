@@ -39,7 +39,7 @@ struct Group {
 };
 
 // KS > 1: the KS wavefronts that share a tile split its row chunks (chunk c goes to wavefront c % KS) and
-// their accumulators are added through LDS in wavefront order; for contractions with many channels on
+// their accumulators are added through LDS in a fixed order; for contractions with many channels on
 // few pixels, where one wavefront per tile would leave most SIMDs idle on a long serial K loop.
 template <int MO, int KH, int KW, bool DST_F32, int KS>
 __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
@@ -205,31 +205,50 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         }
     }
 
-    if constexpr (KS > 1) {
-        // wavefronts ks = 1 .. KS-1 hand their sums to wavefront 0 of the tile, one after the other
-        __shared__ float red[kWaves / KS][MO * 32][64];
+    // Output rows of the tile as T = 4 * MO "row slots" t = 4 * mo + j (output 16 * mo + 4 * r + j of this lane, 8 pixels
+    // each).  KS == 1: the wavefront owns them all.  KS > 1: wavefront f of the tile finishes slots
+    // [f * T / KS, (f + 1) * T / KS): in round v every wavefront w hands the slots of wavefront (w + v) % KS over
+    // through LDS, so each finisher adds its partners' sums in the fixed order own, w-1, w-2, ... and the
+    // additions and stores of a tile are spread over its KS wavefronts.
+    constexpr int T = 4 * MO, TF = T / KS;
+    static_assert(T % KS == 0, "row slots divide among the wavefronts of a tile");
+    float fin[TF][8];
+    int t0 = 0;
+    if constexpr (KS == 1) {
+#pragma unroll
+        for (int i = 0; i < TF; i++)
+#pragma unroll
+            for (int q = 0; q < 8; q++) fin[i][q] = acc[i >> 2][q][i & 3];
+    } else {
+        __shared__ float red[kWaves / KS][KS][TF * 8][64];
         const int sub = wave / KS;
+        t0 = ks * TF;
+#pragma unroll
+        for (int d = 0; d < KS; d++)
+            if (d == ks) {
+#pragma unroll
+                for (int i = 0; i < TF; i++)
+#pragma unroll
+                    for (int q = 0; q < 8; q++) fin[i][q] = acc[(d * TF + i) >> 2][q][(d * TF + i) & 3];
+            }
+#pragma unroll
         for (int v = 1; v < KS; v++) {
-            if (ks == v) {
+            const int dst = (ks + v) % KS;
 #pragma unroll
-                for (int mo = 0; mo < MO; mo++)
+            for (int d = 0; d < KS; d++)
+                if (d == dst) {
 #pragma unroll
-                    for (int q = 0; q < 8; q++)
+                    for (int i = 0; i < TF; i++)
 #pragma unroll
-                        for (int j = 0; j < 4; j++) red[sub][(mo * 8 + q) * 4 + j][lane] = acc[mo][q][j];
-            }
+                        for (int q = 0; q < 8; q++) red[sub][d][i * 8 + q][lane] = acc[(d * TF + i) >> 2][q][(d * TF + i) & 3];
+                }
             __syncthreads();
-            if (ks == 0) {
 #pragma unroll
-                for (int mo = 0; mo < MO; mo++)
+            for (int i = 0; i < TF; i++)
 #pragma unroll
-                    for (int q = 0; q < 8; q++)
-#pragma unroll
-                        for (int j = 0; j < 4; j++) acc[mo][q][j] += red[sub][(mo * 8 + q) * 4 + j][lane];
-            }
-            __syncthreads();
+                for (int q = 0; q < 8; q++) fin[i][q] += red[sub][ks][i * 8 + q][lane];
+            if (v + 1 < KS) __syncthreads();
         }
-        if (ks != 0) return;
     }
     if (!live) return;
     const int nvalid = min(8, P.P - p);
@@ -237,63 +256,62 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const int dst_elems = P.N * outs_img * P.P;
     const rsrc_t rd = make_rsrc(P.dst, dst_elems * (DST_F32 ? 4 : 2));
 #pragma unroll
-    for (int mo = 0; mo < MO; mo++)
+    for (int i = 0; i < TF; i++) {
+        const int t = t0 + i;
+        const int o = ot * 16 * MO + (t >> 2) * 16 + 4 * r + (t & 3);
+        if (o >= Om) continue;
+        const int e = (n * outs_img + gmi * P.gm * P.Og + o) * P.P + p;
+        float v[8];
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const int o = ot * 16 * MO + mo * 16 + 4 * r + j;
-            if (o >= Om) continue;
-            const int e = (n * outs_img + gmi * P.gm * P.Og + o) * P.P + p;
-            float v[8];
-#pragma unroll
-            for (int q = 0; q < 8; q++) v[q] = acc[mo][q][j];
-            if (nvalid == 8) {
-                if (DST_F32) {
-                    u32x4 lo, hi;
-                    if (P.acc) {
-                        lo = bload16(rd, e * 4);
-                        hi = bload16(rd, e * 4 + 16);
-#pragma unroll
-                        for (int k = 0; k < 4; k++) {
-                            v[k] += __uint_as_float(lo[k]);
-                            v[4 + k] += __uint_as_float(hi[k]);
-                        }
-                    }
+        for (int q = 0; q < 8; q++) v[q] = fin[i][q];
+        if (nvalid == 8) {
+            if (DST_F32) {
+                u32x4 lo, hi;
+                if (P.acc) {
+                    lo = bload16(rd, e * 4);
+                    hi = bload16(rd, e * 4 + 16);
 #pragma unroll
                     for (int k = 0; k < 4; k++) {
-                        lo[k] = __float_as_uint(v[k]);
-                        hi[k] = __float_as_uint(v[4 + k]);
+                        v[k] += __uint_as_float(lo[k]);
+                        v[4 + k] += __uint_as_float(hi[k]);
                     }
-                    bstore16(rd, e * 4, lo);
-                    bstore16(rd, e * 4 + 16, hi);
-                } else {
-                    if (P.addend) {  // bf16 tensor of the output's shape added before rounding
-                        const u32x4 ad = bload16(make_rsrc(P.addend, dst_elems * 2), e * 2);
-#pragma unroll
-                        for (int k = 0; k < 4; k++) {
-                            v[2 * k] += lo_f32(ad[k]);
-                            v[2 * k + 1] += hi_f32(ad[k]);
-                        }
-                    }
-                    u32x4 out;
-#pragma unroll
-                    for (int k = 0; k < 4; k++) out[k] = pack_bf16(v[2 * k], v[2 * k + 1]);
-                    bstore16(rd, e * 2, out);
                 }
-            } else {
 #pragma unroll
-                for (int q = 0; q < 8; q++) {
-                    if (q >= nvalid) break;
-                    if (DST_F32) {
-                        float* d = reinterpret_cast<float*>(P.dst) + e + q;
-                        *d = P.acc ? *d + v[q] : v[q];
-                    } else {
-                        float t = v[q];
-                        if (P.addend) t += __uint_as_float((uint32_t)P.addend[e + q] << 16);
-                        reinterpret_cast<uint16_t*>(P.dst)[e + q] = (uint16_t)(pack_bf16(t, 0.f) & 0xffffu);
+                for (int k = 0; k < 4; k++) {
+                    lo[k] = __float_as_uint(v[k]);
+                    hi[k] = __float_as_uint(v[4 + k]);
+                }
+                bstore16(rd, e * 4, lo);
+                bstore16(rd, e * 4 + 16, hi);
+            } else {
+                if (P.addend) {  // bf16 tensor of the output's shape added before rounding
+                    const u32x4 ad = bload16(make_rsrc(P.addend, dst_elems * 2), e * 2);
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        v[2 * k] += lo_f32(ad[k]);
+                        v[2 * k + 1] += hi_f32(ad[k]);
                     }
+                }
+                u32x4 out;
+#pragma unroll
+                for (int k = 0; k < 4; k++) out[k] = pack_bf16(v[2 * k], v[2 * k + 1]);
+                bstore16(rd, e * 2, out);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 8; q++) {
+                if (q >= nvalid) break;
+                if (DST_F32) {
+                    float* d = reinterpret_cast<float*>(P.dst) + e + q;
+                    *d = P.acc ? *d + v[q] : v[q];
+                } else {
+                    float tq = v[q];
+                    if (P.addend) tq += __uint_as_float((uint32_t)P.addend[e + q] << 16);
+                    reinterpret_cast<uint16_t*>(P.dst)[e + q] = (uint16_t)(pack_bf16(tq, 0.f) & 0xffffu);
                 }
             }
         }
+    }
 }
 
 // ----------------------------------------------------------------------------------- weight gradient
