@@ -86,39 +86,27 @@ __device__ __forceinline__ void split2(float a, float b, Pair8& v, int k) {
     v.hi[k] = hi;
     v.lo[k] = pack_bf16(a - lo_f32(hi), b - hi_f32(hi));
 }
+// 8 consecutive elements as bf16 hi (+ lo for fp32 sources) pairs.  check_ends (wave-uniform): the 16-byte
+// accesses of this wavefront may straddle an end of the buffer of `bytes` bytes -- the hardware drops such an
+// access as a whole, so the lanes concerned re-read it element by element.
 template <bool F32>
-__device__ __forceinline__ Pair8 load8(rsrc_t r, int e, bool ok) {
+__device__ __forceinline__ Pair8 load8(rsrc_t r, int e, bool ok, bool check_ends, int bytes) {
     Pair8 v;
     if (!F32) {
         v.hi = bload16(r, ok ? e * 2 : kOob);
+        if (check_ends) reload_if_partial(v.hi, r, ok ? e * 2 : kOob, bytes);
         v.lo = u32x4{0u, 0u, 0u, 0u};
         return v;
     }
-    const u32x4 a = bload16(r, ok ? e * 4 : kOob), b = bload16(r, ok ? e * 4 + 16 : kOob);
+    u32x4 a = bload16(r, ok ? e * 4 : kOob), b = bload16(r, ok ? e * 4 + 16 : kOob);
+    if (check_ends) {
+        reload_f32x4_if_partial(a, r, ok ? e * 4 : kOob, bytes);
+        reload_f32x4_if_partial(b, r, ok ? e * 4 + 16 : kOob, bytes);
+    }
     split2(__uint_as_float(a[0]), __uint_as_float(a[1]), v, 0);
     split2(__uint_as_float(a[2]), __uint_as_float(a[3]), v, 1);
     split2(__uint_as_float(b[0]), __uint_as_float(b[1]), v, 2);
     split2(__uint_as_float(b[2]), __uint_as_float(b[3]), v, 3);
-    return v;
-}
-// Same, element by element: used where the 16-byte accesses could be partly outside the buffer (the
-// hardware then drops them as a whole) -- only for tiles at the two ends of a tensor.
-template <bool F32>
-__device__ __forceinline__ Pair8 load8_slow(rsrc_t r, int e, bool ok) {
-    Pair8 v;
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
-        if (F32) {
-            const float a = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, ok ? (e + 2 * k) * 4 : kOob, 0, 0));
-            const float b = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, ok ? (e + 2 * k + 1) * 4 : kOob, 0, 0));
-            split2(a, b, v, k);
-        } else {
-            const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(r, ok ? (e + 2 * k) * 2 : kOob, 0, 0);
-            const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(r, ok ? (e + 2 * k + 1) * 2 : kOob, 0, 0);
-            v.hi[k] = lo | (hi << 16);
-            v.lo[k] = 0u;
-        }
-    }
     return v;
 }
 
@@ -210,8 +198,13 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
             if (SRC_F32) {
                 c.a[j] = bload16(rs, ok ? e * 4 : kOob);
                 c.b[j & (SRC_F32 ? 3 : 0)] = bload16(rs, ok ? e * 4 + 16 : kOob);
+                if (near_ends) {  // tiles at the two ends of the tensor: lanes whose access is partly outside re-read it
+                    reload_f32x4_if_partial(c.a[j], rs, ok ? e * 4 : kOob, src_elems * esz);
+                    reload_f32x4_if_partial(c.b[j & (SRC_F32 ? 3 : 0)], rs, ok ? e * 4 + 16 : kOob, src_elems * esz);
+                }
             } else {
                 c.a[j] = bload16(rs, ok ? e * 2 : kOob);
+                if (near_ends) reload_if_partial(c.a[j], rs, ok ? e * 2 : kOob, src_elems * esz);
             }
         }
     };
@@ -234,19 +227,6 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 xl[j] = v.lo;
             } else {
                 xs[j] = cur.a[j];
-            }
-        }
-        if (near_ends) {
-            // tiles at the two ends of the tensor: a 16-byte access that is partly outside was dropped
-            // as a whole by the hardware, so re-read element by element
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const int k = k0 + 4 * r + j;
-                uint32_t bits;
-                const int e = row_elem(k, bits);
-                const Pair8 v = load8_slow<SRC_F32>(rs, e, live && k < P.K);
-                xs[j] = v.hi;
-                xl[j] = v.lo;
             }
         }
         if (TAPS) {
@@ -400,7 +380,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
             const int o = obase + mo * 16 + s;
             const bool ok = live && o < P.Og;
             const int e = ((n * P.G + g) * P.Og + o) * P.P + p;
-            a[mo] = near_ends ? load8_slow<DY_F32>(rdy, e, ok) : load8<DY_F32>(rdy, e, ok);
+            a[mo] = load8<DY_F32>(rdy, e, ok, near_ends, P.N * P.G * P.Og * P.P * (DY_F32 ? 4 : 2));
             a[mo].hi = a[mo].hi & mvalid;
             a[mo].lo = a[mo].lo & mvalid;
         }
@@ -408,7 +388,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
         for (int nk = 0; nk < NK; nk++) {
             const bool ok = live && kok[nk];
             const int e = (row0 + krow[nk]) * P.P + p + koff[nk];
-            b[nk] = near_ends ? load8_slow<SRC_F32>(rs, e, ok) : load8<SRC_F32>(rs, e, ok);
+            b[nk] = load8<SRC_F32>(rs, e, ok, near_ends, src_elems * (SRC_F32 ? 4 : 2));
             if (TAPS) {
                 const u32x4 m = mask_of(live ? tap_bits_direct(P, p, khi[nk] - P.KH / 2, kwi[nk] - P.KW / 2) : 0u);
                 b[nk].hi = b[nk].hi & m;

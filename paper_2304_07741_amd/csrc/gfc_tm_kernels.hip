@@ -75,7 +75,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const bool padrows = (Rm & 15) != 0;
 
     // wave-uniform: could a multi-byte access of this tile straddle an end of the source tensor?  (the
-    // hardware drops such an access as a whole, so those tiles read element by element)
+    // hardware drops such an access as a whole; the lanes concerned re-read element by element)
     const int n_first = (int)div_magic((uint32_t)min(tile * 16, total_units - 1), P.magicUpi);
     const int n_last = (int)div_magic((uint32_t)min(tile * 16 + 15, total_units - 1), P.magicUpi);
     const int maxoff = HH * P.W + 2;
@@ -126,22 +126,25 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         for (int j = 0; j < 4; j++) {
             const int e = ebase + eoff + j * P.P;
             const bool ok = valid && (!padrows || rc * 16 + 4 * r + j < Rm);
-            if (!near_ends) {
-                const u32x4 m = bload16(rs, ok ? e * 2 : kOob);
-#pragma unroll
-                for (int k = 0; k < 4; k++) b.d[j][k + E0 / 2] = m[k];
+            const int bo = ok ? e * 2 : kOob;
+            u32x4 m = bload16(rs, bo);
+            uint32_t h0 = 0, h5 = 0;
+            if constexpr (HALO) {
+                h0 = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? bo - 4 : kOob, 0, 0);
+                h5 = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? bo + 16 : kOob, 0, 0);
+            }
+            if (near_ends) {  // only lanes whose access is partly outside re-read, element by element
+                reload_if_partial(m, rs, bo, src_elems * 2);
                 if constexpr (HALO) {
-                    b.d[j][0] = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? (e - 2) * 2 : kOob, 0, 0);
-                    b.d[j][5] = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? (e + 8) * 2 : kOob, 0, 0);
+                    reload_pair_if_partial(h0, rs, ok ? bo - 4 : kOob, src_elems * 2);
+                    reload_pair_if_partial(h5, rs, ok ? bo + 16 : kOob, src_elems * 2);
                 }
-            } else {
+            }
 #pragma unroll
-                for (int k = 0; k < ND; k++) {
-                    const int i = 2 * k - E0;
-                    const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? (e + i) * 2 : kOob, 0, 0);
-                    const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? (e + i + 1) * 2 : kOob, 0, 0);
-                    b.d[j][k] = (lo & 0xffffu) | (hi << 16);
-                }
+            for (int k = 0; k < 4; k++) b.d[j][k + E0 / 2] = m[k];
+            if constexpr (HALO) {
+                b.d[j][0] = h0;
+                b.d[j][5] = h5;
             }
         }
 #pragma unroll
@@ -411,7 +414,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
 
     auto issue = [&](int n, bool valid, Step<MO, KH, KW>& st) {
         // wave-uniform: could a multi-byte access of this step straddle an end of a tensor?  (the hardware
-        // drops such an access as a whole; those steps read element by element)
+        // drops such an access as a whole; the lanes concerned re-read element by element)
         const int xrow0 = n * rows_img + grow0 + rc * 16, yrow0 = n * outs_img + gout0 + ot * 16 * MO;
         const bool near_ends = xrow0 * P.P + pc * 32 - maxoff < 0 || (xrow0 + 16) * P.P + pc * 32 + 48 + maxoff > src_elems ||
                                (yrow0 + 16 * MO) * P.P + pc * 32 + 40 > dy_elems;
@@ -420,35 +423,25 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
         for (int mo = 0; mo < MO; mo++) {
             const bool ok = valid && dyok[mo];
             const int e = ny + edy[mo];
-            if (!near_ends) {
-                st.dy[mo] = bload16(rdy, ok ? e * 2 : kOob);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(rdy, ok ? (e + 2 * k) * 2 : kOob, 0, 0);
-                    const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(rdy, ok ? (e + 2 * k + 1) * 2 : kOob, 0, 0);
-                    st.dy[mo][k] = (lo & 0xffffu) | (hi << 16);
-                }
-            }
+            st.dy[mo] = bload16(rdy, ok ? e * 2 : kOob);
+            if (near_ends) reload_if_partial(st.dy[mo], rdy, ok ? e * 2 : kOob, dy_elems * 2);
         }
 #pragma unroll
         for (int kh = 0; kh < KH; kh++) {
             const bool ok = valid && xok;
-            const int e = nx + ex + (kh - HH) * P.W;
-            if (!near_ends) {
-                const u32x4 m = bload16(rs, ok ? e * 2 : kOob);
-#pragma unroll
-                for (int k = 0; k < 4; k++) st.x[kh][k + 1] = m[k];
-                st.x[kh][0] = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? (e - 2) * 2 : kOob, 0, 0);
-                st.x[kh][5] = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? (e + 8) * 2 : kOob, 0, 0);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 6; k++) {
-                    const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? (e + 2 * k - 2) * 2 : kOob, 0, 0);
-                    const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? (e + 2 * k - 1) * 2 : kOob, 0, 0);
-                    st.x[kh][k] = (lo & 0xffffu) | (hi << 16);
-                }
+            const int bo = ok ? (nx + ex + (kh - HH) * P.W) * 2 : kOob;
+            u32x4 m = bload16(rs, bo);
+            uint32_t h0 = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? bo - 4 : kOob, 0, 0);
+            uint32_t h5 = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? bo + 16 : kOob, 0, 0);
+            if (near_ends) {  // only lanes whose access is partly outside re-read, element by element
+                reload_if_partial(m, rs, bo, src_elems * 2);
+                reload_pair_if_partial(h0, rs, ok ? bo - 4 : kOob, src_elems * 2);
+                reload_pair_if_partial(h5, rs, ok ? bo + 16 : kOob, src_elems * 2);
             }
+#pragma unroll
+            for (int k = 0; k < 4; k++) st.x[kh][k + 1] = m[k];
+            st.x[kh][0] = h0;
+            st.x[kh][5] = h5;
         }
     };
 

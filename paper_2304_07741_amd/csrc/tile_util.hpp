@@ -27,18 +27,37 @@ __device__ __forceinline__ void bstore16(rsrc_t r, int byte_off, u32x4 v) { __bu
 __device__ __forceinline__ u32x4 bload16_nt(rsrc_t r, int byte_off) { return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 2); }
 __device__ __forceinline__ void bstore16_nt(rsrc_t r, int byte_off, u32x4 v) { __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, 2); }
 
-// The hardware drops a 16-byte access as a whole when any part of it is out of range.  Only a shifted
-// access at the very start or end of a tensor can be partly out of range while holding valid pixels;
-// such a register is re-read element by element (2-byte accesses are either inside or outside).
+// A 16-byte access that begins before the buffer is dropped as a whole by the hardware; one that runs past
+// the end keeps the dwords that lie completely inside and loses the rest, including a bf16 element that
+// shares its dword with the end (measured on gfx950).  Only a shifted access at the very start or end of a
+// tensor can be partly out of range while holding valid pixels; the lanes concerned re-read such a register
+// element by element (an element is either inside or outside).
+__device__ __forceinline__ bool straddles_an_end(int byte_off, int len, int bytes) {
+    return (byte_off < 0 && byte_off + len > 0) || (byte_off < bytes && byte_off + len > bytes);
+}
+// One element of `len` bytes at byte offset o, 0 when it is outside the buffer.  The offset handed to the
+// hardware is either inside or the fixed out-of-range value: a negative base plus an immediate is never
+// left to the instruction's own offset arithmetic.
+__device__ __forceinline__ uint32_t elem_b16(rsrc_t r, int o, int bytes) {
+    return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, (o >= 0 && o + 2 <= bytes) ? o : kOob, 0, 0) & 0xffffu;
+}
+__device__ __forceinline__ uint32_t elem_b32(rsrc_t r, int o, int bytes) {
+    return __builtin_amdgcn_raw_buffer_load_b32(r, (o >= 0 && o + 4 <= bytes) ? o : kOob, 0, 0);
+}
 __device__ __forceinline__ void reload_if_partial(u32x4& v, rsrc_t r, int byte_off, int bytes) {
-    const bool partial = (byte_off < 0 && byte_off > -16) || (byte_off < bytes && byte_off + 16 > bytes);
-    if (partial) {
+    if (straddles_an_end(byte_off, 16, bytes)) {
 #pragma unroll
-        for (int k = 0; k < 4; k++) {
-            const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(r, byte_off + 4 * k, 0, 0);
-            const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b16(r, byte_off + 4 * k + 2, 0, 0);
-            v[k] = lo | (hi << 16);
-        }
+        for (int k = 0; k < 4; k++) v[k] = elem_b16(r, byte_off + 4 * k, bytes) | (elem_b16(r, byte_off + 4 * k + 2, bytes) << 16);
+    }
+}
+// The same for a 4-byte access of two bf16 elements, and for a 16-byte access of four fp32 elements.
+__device__ __forceinline__ void reload_pair_if_partial(uint32_t& v, rsrc_t r, int byte_off, int bytes) {
+    if (straddles_an_end(byte_off, 4, bytes)) v = elem_b16(r, byte_off, bytes) | (elem_b16(r, byte_off + 2, bytes) << 16);
+}
+__device__ __forceinline__ void reload_f32x4_if_partial(u32x4& v, rsrc_t r, int byte_off, int bytes) {
+    if (straddles_an_end(byte_off, 16, bytes)) {
+#pragma unroll
+        for (int k = 0; k < 4; k++) v[k] = elem_b32(r, byte_off + 4 * k, bytes);
     }
 }
 
