@@ -5,8 +5,9 @@
 
 namespace canvas {
 
-void emit_fc(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
+void emit_fc(Lowering& low, bool backward, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
              bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32) {
+    std::vector<Launch>& list = backward ? low.bwd : low.fwd;
     const int64_t nw = (int64_t)G * Og * R * kh * kw;
     // (1x1 contractions with enough tiles to fill the chip stay on the generic kernel: measured faster there)
     if (!src.f32 && gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W) &&
@@ -14,10 +15,24 @@ void emit_fc(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, cons
         const gfctm::Params T = gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
         const bool identity = !transposed && T.TV == 1 && T.gm == 1 && T.Rp == R && T.Omp == Og;
         const int64_t opk = identity ? -1 : take((uint64_t)gfctm::packed_elems(T) * 2);
-        if (!identity)
-            list.push_back({name + "_pack_w", 2.0 * nw + 2.0 * gfctm::packed_elems(T), 0, [=](const RunArgs& a) {
-                                gfctm::pack_weights((const uint16_t*)a.w[widx], (uint16_t*)(a.ws + opk), T, transposed, a.stream);
-                            }, true});
+        if (!identity) {
+            WeightJob j;
+            j.job.kind = 0;
+            j.job.G = T.G;
+            j.job.R = T.R;
+            j.job.Og = T.Og;
+            j.job.TV = T.TV;
+            j.job.gm = T.gm;
+            j.job.Gm = T.Gm;
+            j.job.Rp = T.Rp;
+            j.job.Omp = T.Omp;
+            j.job.transposed = transposed ? 1 : 0;
+            j.job.total = gfctm::packed_elems(T);
+            j.widx = widx;
+            j.off = opk;
+            j.bytes = 2.0 * nw + 2.0 * gfctm::packed_elems(T);
+            low.wjobs.push_back(j);
+        }
         list.push_back({name, bytes, flops, [=](const RunArgs& a) {
                             gfctm::Params Q = T;
                             Q.src = (const uint16_t*)src.ptr(a);
@@ -34,10 +49,19 @@ void emit_fc(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, cons
     F.dst_f32 = dst_f32 ? 1 : 0;
     gfc::prepare_forward(F);
     const int64_t owt = transposed ? take((uint64_t)nw * 2) : -1;
-    if (transposed)  // (R, Og) are the swapped dims: the FC's own weights are [G][R][Og][taps]
-        list.push_back({name + "_transpose_w", 4.0 * nw, 0, [=](const RunArgs& a) {
-                            gfc::transpose_weights((const uint16_t*)a.w[widx], (uint16_t*)(a.ws + owt), G, R, Og, kh * kw, a.stream);
-                        }});
+    if (transposed) {  // (R, Og) are the swapped dims: the FC's own weights are [G][R][Og][taps]
+        WeightJob j;
+        j.job.kind = 1;
+        j.job.G = G;
+        j.job.Og = R;  // (the job reads [G][its Og][its R][TV]: the FC's own output and row counts)
+        j.job.R = Og;
+        j.job.TV = kh * kw;
+        j.job.total = nw;
+        j.widx = widx;
+        j.off = owt;
+        j.bytes = 4.0 * nw;
+        low.wjobs.push_back(j);
+    }
     list.push_back({name, bytes, flops, [=](const RunArgs& a) {
                         gfc::Params Q = F;
                         Q.src = src.ptr(a);
@@ -48,8 +72,9 @@ void emit_fc(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, cons
                     }});
 }
 
-void emit_wgrad(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
+void emit_wgrad(Lowering& low, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
                 int widx, FcOperand src, FcOperand dy, double operand_bytes, double flops) {
+    std::vector<Launch>& list = low.bwd;
     const int64_t nw = (int64_t)G * Og * R * kh * kw;
     if (kh * kw > 1 && !src.f32 && !dy.f32 && gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W)) {
         gfctm::Params T = gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);

@@ -1,5 +1,5 @@
 // Launch lists of one FC-shaped contraction on the MFMA kernels, shared by the fused lowerings: picks the
-// tap-major kernels (with their weight-packing launch) where they apply, else the generic kernels.
+// tap-major kernels (with their packed weights) where they apply, else the generic kernels.
 #pragma once
 #include <functional>
 #include <string>
@@ -22,11 +22,12 @@ struct FcOperand {
 // then (R, Og) are the swapped dims and the FC's own weights [G][R][Og][taps] are read transposed with the
 // taps flipped.  `addend_is_dst`: dst (bf16) already holds a tensor that the result is added to.
 // dst is bf16 unless dst_f32.
-void emit_fc(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
+// The launch goes to low.fwd or (backward) low.bwd; derived weight copies are registered in low.wjobs.
+void emit_fc(Lowering& low, bool backward, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
              bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32 = false);
 
 // dw[widx] = sum over (image, pixel) of dy (x) rows of src (through the window kh x kw); partials + fixed-order reduce.
-void emit_wgrad(std::vector<Launch>& list, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
+void emit_wgrad(Lowering& low, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
                 int widx, FcOperand src, FcOperand dy, double operand_bytes, double flops);
 
 }  // namespace canvas

@@ -1,16 +1,44 @@
 // Lowering selection.
 #include "lowering.hpp"
 
+#include <algorithm>
+#include <iterator>
+
 namespace canvas {
 
 std::unique_ptr<Lowering> lower(const Dag& full, bool bf16, bool no_fusion) {
     const Dag dag = without_dead_views(full);
+    std::unique_ptr<Lowering> l;
     if (!no_fusion) {
-        if (auto l = lower_sgfc(dag, bf16)) return l;
-        if (auto l = lower_ufc(dag, bf16)) return l;
-        if (auto l = lower_dyn(dag, bf16)) return l;
+        l = lower_sgfc(dag, bf16);
+        if (!l) l = lower_ufc(dag, bf16);
+        if (!l) l = lower_dyn(dag, bf16);
     }
-    return lower_per_node(dag, bf16);
+    if (!l) l = lower_per_node(dag, bf16);
+    batch_weight_jobs(*l);
+    return l;
+}
+
+void batch_weight_jobs(Lowering& low) {
+    std::vector<Launch> head;
+    for (size_t first = 0; first < low.wjobs.size(); first += wprep::kMaxJobs) {
+        const std::vector<WeightJob> part(low.wjobs.begin() + first,
+                                          low.wjobs.begin() + std::min(low.wjobs.size(), first + (size_t)wprep::kMaxJobs));
+        double bytes = 0;
+        for (const auto& j : part) bytes += j.bytes;
+        head.push_back({"weight_prep", bytes, 0, [part](const RunArgs& a) {
+                            wprep::Jobs J;
+                            for (const auto& j : part) {
+                                wprep::Job& d = J.j[J.n++];
+                                d = j.job;
+                                d.w = (const uint16_t*)a.w[j.widx];
+                                d.out = (uint16_t*)(a.ws + j.off);
+                            }
+                            wprep::run(J, a.stream);
+                        }, true});
+    }
+    low.fwd.insert(low.fwd.begin(), std::make_move_iterator(head.begin()), std::make_move_iterator(head.end()));
+    low.wjobs.clear();
 }
 
 void make_inference_plan(Lowering& low) {

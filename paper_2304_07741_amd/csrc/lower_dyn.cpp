@@ -111,7 +111,7 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
     const FcOperand in_x{[](const RunArgs& a) { return a.x; }, false};
     const FcOperand in_dy{[](const RunArgs& a) { return a.dy; }, false};
 
-    emit_fc(low->fwd, dag, take, "dyn_fc1", G1, C / G1, 1, 1, TVa / G1, false, w1, in_x, ws_at(ol), false, act + ab + 2.0 * nw1, fl1, true);
+    emit_fc(*low, false, dag, take, "dyn_fc1", G1, C / G1, 1, 1, TVa / G1, false, w1, in_x, ws_at(ol), false, act + ab + 2.0 * nw1, fl1, true);
     if (soft)
         low->fwd.push_back({"dyn_softmax", 2.0 * ab, 0, [=](const RunArgs& a) {
                                 ref::softmax_fwd((const float*)(a.ws + ol), (float*)(a.ws + oa), N, TVa, 1, Pn, 1, a.stream);
@@ -123,12 +123,12 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
                             Q.u = (uint16_t*)(a.ws + ou);
                             dyn::forward(Q, a.stream);
                         }});
-    emit_fc(low->fwd, dag, take, "dyn_fc2", G2, C / G2, 1, 1, O2 / G2, false, w2, FcOperand{ws_at(ou), false},
+    emit_fc(*low, false, dag, take, "dyn_fc2", G2, C / G2, 1, 1, O2 / G2, false, w2, FcOperand{ws_at(ou), false},
             [](const RunArgs& a) { return (const void*)a.y; }, false, act + outb + 2.0 * nw2, fl2);
 
     // backward (forward must have run with the same workspace: a and u are read back)
-    emit_wgrad(low->bwd, dag, take, "dyn_fc2_wgrad", G2, C / G2, 1, 1, O2 / G2, w2, FcOperand{ws_at(ou), false}, in_dy, act + outb, fl2);
-    emit_fc(low->bwd, dag, take, "dyn_fc2_dgrad", G2, O2 / G2, 1, 1, C / G2, true, w2, in_dy, ws_at(odu), false, act + outb + 2.0 * nw2, fl2);
+    emit_wgrad(*low, dag, take, "dyn_fc2_wgrad", G2, C / G2, 1, 1, O2 / G2, w2, FcOperand{ws_at(ou), false}, in_dy, act + outb, fl2);
+    emit_fc(*low, true, dag, take, "dyn_fc2_dgrad", G2, O2 / G2, 1, 1, C / G2, true, w2, in_dy, ws_at(odu), false, act + outb + 2.0 * nw2, fl2);
     low->bwd.push_back({"dyn_apply_dx", 2.0 * act + ab, fld, [=](const RunArgs& a) {
                             dyn::Params Q = D;
                             Q.a = (const float*)(a.ws + oa);
@@ -148,9 +148,9 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
                                 ref::softmax_bwd((const float*)(a.ws + oa), (const float*)(a.ws + oda), (float*)(a.ws + odl), N, TVa, 1, Pn, 1, 0,
                                                  a.stream);
                             }});
-    emit_wgrad(low->bwd, dag, take, "dyn_fc1_wgrad", G1, C / G1, 1, 1, TVa / G1, w1, in_x, FcOperand{ws_at(odl), true}, act + ab, fl1);
+    emit_wgrad(*low, dag, take, "dyn_fc1_wgrad", G1, C / G1, 1, 1, TVa / G1, w1, in_x, FcOperand{ws_at(odl), true}, act + ab, fl1);
     // the data gradient of FC1 adds to the dx that dyn_apply_dx has written
-    emit_fc(low->bwd, dag, take, "dyn_fc1_dgrad", G1, TVa / G1, 1, 1, C / G1, true, w1, FcOperand{ws_at(odl), true},
+    emit_fc(*low, true, dag, take, "dyn_fc1_dgrad", G1, TVa / G1, 1, 1, C / G1, true, w1, FcOperand{ws_at(odl), true},
             [](const RunArgs& a) { return (const void*)a.dx; }, true, 2.0 * act + ab + 2.0 * nw1, fl1);
     low->ws_bytes = off;
     return low;

@@ -122,7 +122,7 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
     const FcOperand in_x{[](const RunArgs& a) { return a.x; }, false};
     const FcOperand in_dy{[](const RunArgs& a) { return a.dy; }, false};
     auto ws_at = [](int64_t o) { return [=](const RunArgs& a) { return (const void*)(a.ws + o); }; };
-    emit_fc(low->fwd, dag, takef, TV > 1 ? "ufc_fc1_unfold" : "ufc_fc1", G1, C / G1, KH, KW, C / G1, false, w1, in_x, ws_at(oz), false,
+    emit_fc(*low, false, dag, takef, TV > 1 ? "ufc_fc1_unfold" : "ufc_fc1", G1, C / G1, KH, KW, C / G1, false, w1, in_x, ws_at(oz), false,
             2.0 * act + 2.0 * nw1, fl1);
     low->fwd.push_back({"ufc_mid_fwd", 3.0 * act, 0, [=](const RunArgs& a) {
                             ufc::MidParams R = M;
@@ -131,12 +131,12 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
                             R.v = (uint16_t*)(a.ws + ov);
                             ufc::mid_forward(R, a.stream);
                         }});
-    emit_fc(low->fwd, dag, takef, "ufc_fc2", G2, C / G2, 1, 1, O2 / G2, false, w2, FcOperand{ws_at(ov), false},
+    emit_fc(*low, false, dag, takef, "ufc_fc2", G2, C / G2, 1, 1, O2 / G2, false, w2, FcOperand{ws_at(ov), false},
             [](const RunArgs& a) { return (const void*)a.y; }, false, act + outb + 2.0 * nw2, fl2);
 
     // backward (forward must have run with the same workspace: z and v are read back, and left intact)
-    emit_wgrad(low->bwd, dag, takef, "ufc_fc2_wgrad", G2, C / G2, 1, 1, O2 / G2, w2, FcOperand{ws_at(ov), false}, in_dy, act + outb, fl2);
-    emit_fc(low->bwd, dag, takef, "ufc_fc2_dgrad", G2, O2 / G2, 1, 1, C / G2, true, w2, in_dy, ws_at(odv), false, act + outb + 2.0 * nw2, fl2);
+    emit_wgrad(*low, dag, takef, "ufc_fc2_wgrad", G2, C / G2, 1, 1, O2 / G2, w2, FcOperand{ws_at(ov), false}, in_dy, act + outb, fl2);
+    emit_fc(*low, true, dag, takef, "ufc_fc2_dgrad", G2, O2 / G2, 1, 1, C / G2, true, w2, in_dy, ws_at(odv), false, act + outb + 2.0 * nw2, fl2);
     low->bwd.push_back({"ufc_mid_bwd", (M.bin ? 5.0 : 4.0) * act, 0, [=](const RunArgs& a) {
                             ufc::MidParams R = M;
                             R.x = (const uint16_t*)a.x;
@@ -146,10 +146,10 @@ std::unique_ptr<Lowering> lower_ufc(const Dag& dag, bool bf16) {
                             R.dx1 = (uint16_t*)a.dx;  // completed by the data gradient of FC1 below
                             ufc::mid_backward(R, a.stream);
                         }});
-    emit_wgrad(low->bwd, dag, takef, TV > 1 ? "ufc_fc1_wgrad_unfold" : "ufc_fc1_wgrad", G1, C / G1, KH, KW, C / G1, w1, in_x,
+    emit_wgrad(*low, dag, takef, TV > 1 ? "ufc_fc1_wgrad_unfold" : "ufc_fc1_wgrad", G1, C / G1, KH, KW, C / G1, w1, in_x,
                FcOperand{ws_at(odz), false}, 2.0 * act, fl1);
     // mid_backward left dx_direct in dx; the data gradient of FC1 (through the Unfold adjoint) adds to it
-    emit_fc(low->bwd, dag, takef, TV > 1 ? "ufc_fc1_dgrad_unfold" : "ufc_fc1_dgrad", G1, C / G1, KH, KW, C / G1, true, w1,
+    emit_fc(*low, true, dag, takef, TV > 1 ? "ufc_fc1_dgrad_unfold" : "ufc_fc1_dgrad", G1, C / G1, KH, KW, C / G1, true, w1,
             FcOperand{ws_at(odz), false}, [](const RunArgs& a) { return (const void*)a.dx; }, true, 3.0 * act + 2.0 * nw1, fl1);
     low->ws_bytes = off;
     return low;

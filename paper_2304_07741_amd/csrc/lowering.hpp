@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "dag.hpp"
+#include "wprep_kernels.hpp"
 
 namespace canvas {
 
@@ -31,12 +32,25 @@ struct Launch {
     bool prep = false;  // touches only the weights (packing, widening): an inference plan runs it once, ahead of the forward calls
 };
 
+// A derived copy of the weights of FC number widx, written at byte offset `off` of the workspace.
+struct WeightJob {
+    wprep::Job job;  // geometry; the pointers are filled at run time
+    int widx = 0;
+    int64_t off = 0;
+    double bytes = 0;
+};
+
 struct Lowering {
     bool fused = false;
     uint64_t ws_bytes = 0;
     std::vector<Launch> fwd, bwd;
+    std::vector<WeightJob> wjobs;  // collected while lowering; batch_weight_jobs turns them into launches
     std::vector<Launch> prep;  // inference plans only: the weight-only launches taken out of fwd
 };
+
+// Puts the collected weight jobs, of forward and backward alike, into one launch at the head of the forward
+// list (backward runs on the weights and the workspace of the preceding forward).
+void batch_weight_jobs(Lowering& low);
 
 // Turns a lowering into a forward-only plan: weight-only launches move to `prep`, the backward list is dropped.
 void make_inference_plan(Lowering& low);

@@ -138,7 +138,9 @@ def test_lowering_selection(lib):
     assert _compile_info(wl.blob_shift_residual(64), (2, 64, 13, 13))[0] == 0
     # config 4: unfold -> FC -> gelu -> shift -> * x -> fold(1 tap) -> FC; windowed contractions on the tap-major kernels
     fused, ws, (fwd, bwd) = _compile_info(wl.blob_sampled(64), (128, 64, 56, 56))
-    assert fused == 1 and "ufc_fc1_unfold_pack_w" in fwd and "ufc_mid_fwd" in fwd and fwd[-1] == "ufc_fc2"
+    # (all derived weight copies, of forward and backward, in one launch at the head of the forward list)
+    assert fused == 1 and fwd == ["weight_prep", "ufc_fc1_unfold", "ufc_mid_fwd", "ufc_fc2"]
+    assert not any("pack" in n or "transpose" in n for n in bwd)
     assert bwd[-1] == "ufc_fc1_dgrad_unfold" and "ufc_mid_bwd" in bwd and "ufc_fc1_wgrad_unfold_reduce" in bwd
     assert 4 * 128 * 64 * 56 * 56 * 2 <= ws < 5 * 128 * 64 * 56 * 56 * 2   # z, v, dv, dz + partials and packed weights
     # a unary whose decisions bf16 rounding could change keeps fp32 intermediates
@@ -207,7 +209,7 @@ def test_inference_plan_moves_weight_only_launches_out_of_forward(lib):
             tn = [B.canvas_dag_launch_desc(ht, 0, i)["name"] for i in range(it.n_launches_fwd)]
             inn = [B.canvas_dag_launch_desc(hi, 0, i)["name"] for i in range(ii.n_launches_fwd)]
             assert [n for n in tn if n in inn] == inn  # same kernels, same order
-            assert all("pack" in n or "widen" in n for n in tn if n not in inn)
+            assert all("weight_prep" in n or "widen" in n for n in tn if n not in inn)
             arr = (ctypes.c_void_p * 4)(0x1000, 0x1000, 0x1000, 0x1000)
             assert lib.canvas_dag_backward(hi, 0x1000, arr, 0x2000, 0x4000, arr, 0x3000, 1 << 40, None) == -6
             assert lib.canvas_dag_prepare(ht, arr, 0x3000, 1 << 40, None) == -4  # not an inference plan
