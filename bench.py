@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # Valid only for the kernel sources they were taken on (hash below), otherwise `traffic` is null.
 TRAFFIC_SOURCES = ["paper_2304_07741_amd/csrc/sgfc_kernels.hip", "paper_2304_07741_amd/csrc/tile_util.hpp",
                    "paper_2304_07741_amd/csrc/lower_sgfc.cpp"]
-TRAFFIC_SHA256 = "8a50509db51e6768d03ef4feb5974bf152f9d752da909be02562e032c20ced47"
-TRAFFIC_KIB = {("shift_residual", "sgfc_bwd"): (26386.3 * 1.998, 25913.5), ("shift_residual", "sgfc_fwd"): (14401.7 * 1.998, 25088.4)}
+TRAFFIC_SHA256 = "85f5cd49ad9d645defc73f2211fa19ebaec35cf5cf1d1246f1b1c66b132d7640"
+TRAFFIC_KIB = {("shift_residual", "sgfc_bwd"): (26403.5 * 1.998, 25900.3), ("shift_residual", "sgfc_fwd"): (14405.3 * 1.998, 25089.0)}
 
 
 def measured_traffic(workload, kernel):
