@@ -445,6 +445,37 @@ def test_inference_forward_replays_from_a_hip_graph(harness, which):
         r.close()
 
 
+@pytest.mark.parametrize("which", ["shape_matching", "constraints"])
+def test_template_to_executor_end_to_end(harness, oracle, which):
+    """A kernel template goes through the two solvers, is instantiated for two replacement targets and each
+    concrete micro-DAG runs forward and backward on the GPU against the DAG oracle (the paper's pipeline from a
+    sampled template to a trained kernel, Sections 6 and 7, without the sampler)."""
+    import math
+
+    if which == "shape_matching":
+        t = B.canvas_template_parse(wl.TEMPLATE_SHAPE_MATCHING)
+        var, subs = B.canvas_template_substitutions(t, 7)
+        assert "KW*x2" in subs
+        B.canvas_template_substitute(t, var, "KW*x2")
+        targets, G = [dict(C=32, KH=3, KW=3, H=14, W=14), dict(C=64, KH=3, KW=3, H=9, W=11)], 4
+    else:
+        t = B.canvas_template_parse(wl.TEMPLATE_CONSTRAINTS)
+        targets, G = [dict(C=64, KH=3, KW=3, H=14, W=14), dict(C=256, KH=5, KW=5, H=7, W=7)], 4
+    xs, flops, params, rounds = B.canvas_template_solve(t, targets, G, flops_budget=6.0e7)
+    assert rounds >= 1
+    for tg, x in zip(targets, xs):
+        blob = B.canvas_template_instantiate(t, tg, G, x)
+        shape = (3, tg["C"], tg["H"], tg["W"])
+        _, _, wshapes = oracle.infer(blob, shape)
+        wshapes = [tuple(s_) for s_ in wshapes]
+        case = wl._case(f"tmpl_{which}_{tg['C']}", blob, shape, "bf16", 900 + tg["C"], wshapes, [1.0 / math.sqrt(s_[2]) for s_ in wshapes])
+        res, r, dy = harness.run_case(case)
+        check_against_oracle(oracle, case, res, dy, what=blob)
+        assert list(r.out_shape) == [3, tg["C"], 1, tg["H"], tg["W"]]   # a template maps [C, H, W] to [C, H, W]
+        r.close()
+    B.canvas_template_destroy(t)
+
+
 def test_runtime_argument_checks(harness):
     import torch
 
