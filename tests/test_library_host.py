@@ -272,3 +272,21 @@ def test_pixel_aligned_blend_legality(lib, oracle):
             oracle.infer(H_ + bad, (2, 8, 5, 6))
         with pytest.raises(B.CanvasError):
             B.canvas_dag_compile(H_ + bad, (2, 8, 5, 6), B.CANVAS_BF16)
+
+
+def test_tensors_beyond_32_bit_offsets_take_the_per_node_lowering(lib):
+    """The fused kernels address tensors through 32-bit byte offsets; a batch whose tensors reach 2 GiB compiles
+    to the per-node lowering (64-bit indexing), reports its workspace, and smaller batches stay fused."""
+    for blob, C, H, n_ok, n_big in ((wl.blob_shift_residual(64), 64, 56, 4096, 8192), (wl.blob_sampled(64), 64, 56, 4096, 8192),
+                                    (wl.blob_involution(128), 128, 28, 8192, 20000)):
+        h = B.canvas_dag_compile(blob, (n_ok, C, H, H), B.CANVAS_BF16)
+        assert B.canvas_dag_query(h).fused == 1
+        B.canvas_dag_destroy(h)
+        h = B.canvas_dag_compile(blob, (n_big, C, H, H), B.CANVAS_BF16)
+        info = B.canvas_dag_query(h)
+        assert info.fused == 0 and info.workspace_bytes > 4 * n_big * C * H * H
+        assert list(info.out_shape) == [n_big, C, 1, H, H]
+        B.canvas_dag_destroy(h)
+    with pytest.raises(B.CanvasError) as e:     # more than 2^40 elements in one tensor
+        B.canvas_dag_compile(wl.blob_conv(3, 1, 16), (1 << 20, 1 << 10, 64, 64), B.CANVAS_BF16)
+    assert e.value.status == -6
