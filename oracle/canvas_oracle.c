@@ -29,10 +29,11 @@
  *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
  *     %5 = binary %0 %4 op=mul         (first operand LHS, second RHS; add | sub | mul | min | max;
  *                                       sub is tile(LHS) - RHS; a tie of min / max sends the gradient to the LHS)
- *     %6 = fold %5 op=avg              (sum | avg | max; axis=T (default) folds the taps, axis=HW folds the
- *                                       pixels: the result is a [C, T, 1, 1] tensor, which FC, unary, softmax,
- *                                       fold over T and binary accept; as the LHS of a binary it is
- *                                       replicated over the pixels of a full-size RHS; axis=C groups=G folds the
+ *     %6 = fold %5 op=avg              (sum | avg | max; axis=T (default) folds the taps; axis=HW folds the
+ *                                       pixels, axis=H / axis=W one spatial dim: the result is a [C, T, 1, 1],
+ *                                       [C, T, 1, W] or [C, T, H, 1] tensor, which FC, unary, softmax, the
+ *                                       other folds and binary accept; as the LHS of a binary it is
+ *                                       replicated along its folded dims onto an RHS that has them; axis=C groups=G folds the
  *                                       C/G channels of each of G groups: the result has G channels)
  *     %7 = softmax %6 axis=C           (C | T | CT: over channels, over taps, or over both jointly)
  *     %9 = binary %a %b op=mul lhs=pixels   (a pooled LHS [H*W, 1, 1, 1] whose channels are laid over the
@@ -75,8 +76,8 @@ typedef struct {
     int kind;           /* unary / binary / fold kind, softmax axis */
     double lo, hi;      /* expclip */
     int C, T;           /* inferred shape [C, T, H, W] */
-    int pooled;         /* 1: the spatial dims have been folded away, shape [C, T, 1, 1] */
-    int axis_hw;        /* fold: 1 = over the pixels, 0 = over the taps */
+    int pooled;         /* mask of folded spatial dims: 1 = H (shape [C, T, 1, W]), 2 = W ([C, T, H, 1]), 3 = both */
+    int axis_hw;        /* fold: mask of the spatial dims folded by this node (1 = H, 2 = W, 3 = both), 0 = over the taps */
     int axis_c;         /* fold: 1 = over the C / groups channels of each of `groups` channel groups */
     int widx;           /* fc: index into the weight list */
     int grp;            /* Group view of the channel dim: [grp, C/grp]; 1 = not grouped */
@@ -317,14 +318,14 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 }
                 if (nd->lhs_pixels) {
                     /* the dim lists [X] and [C, T, H, W] share the suffix once X is read as [H, W] */
-                    if (!A->pooled || B->pooled || (long)A->C * A->T != (long)H * W) {
+                    if (A->pooled != 3 || B->pooled || (long)A->C * A->T != (long)H * W) {
                         set_err(err, errlen, "binary lhs=pixels needs a pooled LHS with H*W elements and a full-size RHS", lineno);
                         goto done;
                     }
                 } else
                 if (!(A->grp == B->grp && A->grp > 1 ? broadcast_legal_g(A->grp, A->C, A->T, B->C, B->T)
                                                      : broadcast_legal(A->C, A->T, B->C, B->T)) ||
-                    (!A->pooled && B->pooled)) {
+                    (A->pooled & B->pooled) != B->pooled) {  /* a dim folded on the RHS must be folded on the LHS */
                     set_err(err, errlen, "broadcast: LHS size does not divide RHS size", lineno);
                     goto done;
                 }
@@ -350,9 +351,11 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 else { set_err(err, errlen, "fold needs op=sum|avg|max", lineno); goto done; }
                 {
                     const char *ax = find_attr(tok, ntok, "axis");
-                    if (ax && !strcmp(ax, "HW")) nd->axis_hw = 1;
+                    if (ax && !strcmp(ax, "HW")) nd->axis_hw = 3;
+                    else if (ax && !strcmp(ax, "H")) nd->axis_hw = 1;
+                    else if (ax && !strcmp(ax, "W")) nd->axis_hw = 2;
                     else if (ax && !strcmp(ax, "C")) nd->axis_c = 1;
-                    else if (ax && strcmp(ax, "T")) { set_err(err, errlen, "fold axis must be T, HW or C", lineno); goto done; }
+                    else if (ax && strcmp(ax, "T")) { set_err(err, errlen, "fold axis must be T, H, W, HW or C", lineno); goto done; }
                 }
                 nd->C = A->C;
                 if (nd->axis_c) {
@@ -365,9 +368,9 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                     nd->T = A->T;
                     nd->grp = 1;
                 } else if (nd->axis_hw) {
-                    if (A->pooled) { set_err(err, errlen, "fold axis=HW: the spatial dims are already folded", lineno); goto done; }
+                    if (A->pooled & nd->axis_hw) { set_err(err, errlen, "fold: that spatial dim is already folded", lineno); goto done; }
                     nd->T = A->T;
-                    nd->pooled = 1;
+                    nd->pooled = A->pooled | nd->axis_hw;
                 } else {
                     nd->T = 1;
                 }
@@ -388,7 +391,10 @@ done:
 
 /* ------------------------------------------------------- forward, one image */
 
-static int node_P(const Dag *d, const Node *nd) { return nd->pooled ? 1 : d->H * d->W; }
+/* pooled is a mask of the spatial dims that have been folded away: 1 = H, 2 = W, 3 = both */
+static int node_H(const Dag *d, const Node *nd) { return (nd->pooled & 1) ? 1 : d->H; }
+static int node_W(const Dag *d, const Node *nd) { return (nd->pooled & 2) ? 1 : d->W; }
+static int node_P(const Dag *d, const Node *nd) { return node_H(d, nd) * node_W(d, nd); }
 static size_t node_numel(const Dag *d, int k) { return (size_t)d->node[k].C * d->node[k].T * node_P(d, &d->node[k]); }
 
 /* Unfold (Section 5): U(c, kh, kw, h, w) = I(c, h + kh, w + kw) with the window
@@ -471,6 +477,13 @@ static void fwd_unary(const Dag *d, const Node *nd, int k, const double *in, dou
     }
 }
 
+/* Pixel of the LHS that meets pixel p of the result: a spatial dim that the LHS has folded away is
+ * replicated (index 0), the others are common dims. */
+static int lhs_pixel(const Dag *d, const Node *L, const Node *R, int p) {
+    int Wr = node_W(d, R), h = p / Wr, w = p % Wr;
+    return ((L->pooled & 1) ? 0 : h) * node_W(d, L) + ((L->pooled & 2) ? 0 : w);
+}
+
 static double blend(int kind, double a, double b) {
     switch (kind) {
     case BIN_ADD: return a + b;
@@ -483,7 +496,7 @@ static double blend(int kind, double a, double b) {
 
 static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const double *rhs, double *out) {
     const Node *L = &d->node[nd->a];
-    int P = node_P(d, nd), PL = node_P(d, L), c, t, p, cl, tl;  /* PL == 1 < P: the LHS is replicated over the pixels */
+    int P = node_P(d, nd), PL = node_P(d, L), c, t, p, cl, tl;  /* PL < P: the LHS is replicated along its folded spatial dims */
     for (c = 0; c < nd->C; c++)
         for (t = 0; t < nd->T; t++) {
             const double *lrow, *rrow = rhs + ((size_t)c * nd->T + t) * P;
@@ -496,7 +509,7 @@ static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
             else broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             lrow = lhs + ((size_t)cl * L->T + tl) * PL;
             for (p = 0; p < P; p++) {
-                orow[p] = blend(nd->kind, lrow[PL == 1 ? 0 : p], rrow[p]);
+                orow[p] = blend(nd->kind, lrow[lhs_pixel(d, L, nd, p)], rrow[p]);
             }
         }
 }
@@ -545,17 +558,24 @@ static void fwd_fold(const Dag *d, const Node *nd, const double *in, double *out
                 }
         return;
     }
-    if (nd->axis_hw) {  /* over the pixels of every (channel, tap) plane */
-        for (c = 0; c < nd->C * T; c++) {
-            double acc = in[(size_t)c * P];
-            for (p = 1; p < P; p++) {
-                double v = in[(size_t)c * P + p];
-                if (nd->kind == FOLD_MAX) { if (v > acc) acc = v; }
-                else acc += v;
-            }
-            if (nd->kind == FOLD_AVG) acc /= P;
-            out[c] = acc;
-        }
+    if (nd->axis_hw) {  /* over H, over W or over both, of every (channel, tap) plane; scan order h, then w */
+        int Hi = node_H(d, A), Wi = node_W(d, A), Ho = node_H(d, nd), Wo = node_W(d, nd), ho, wo, h, w;
+        for (c = 0; c < nd->C * T; c++)
+            for (ho = 0; ho < Ho; ho++)
+                for (wo = 0; wo < Wo; wo++) {
+                    int h0 = (nd->axis_hw & 1) ? 0 : ho, h1 = (nd->axis_hw & 1) ? Hi : ho + 1;
+                    int w0 = (nd->axis_hw & 2) ? 0 : wo, w1 = (nd->axis_hw & 2) ? Wi : wo + 1, first = 1;
+                    double acc = 0.0;
+                    for (h = h0; h < h1; h++)
+                        for (w = w0; w < w1; w++) {
+                            double v = in[((size_t)c * Hi + h) * Wi + w];
+                            if (first) { acc = v; first = 0; }
+                            else if (nd->kind == FOLD_MAX) { if (v > acc) acc = v; }
+                            else acc += v;
+                        }
+                    if (nd->kind == FOLD_AVG) acc /= (double)((h1 - h0) * (w1 - w0));
+                    out[((size_t)c * Ho + ho) * Wo + wo] = acc;
+                }
         return;
     }
     for (c = 0; c < nd->C; c++)
@@ -656,7 +676,7 @@ static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
             else broadcast_index(L->C, L->T, nd->C, nd->T, c, t, &cl, &tl);
             lo = ((size_t)cl * L->T + tl) * PL;
             for (p = 0; p < P; p++) {
-                size_t lp = nd->lhs_pixels ? (size_t)p : lo + (PL == 1 ? 0 : p);
+                size_t lp = nd->lhs_pixels ? (size_t)p : lo + (size_t)lhs_pixel(d, L, nd, p);
                 double g = gout[ro + p], a = lhs[lp], b = rhs[ro + p];
                 switch (nd->kind) {
                 case BIN_ADD: glhs[lp] += g; grhs[ro + p] += g; break;
@@ -709,19 +729,26 @@ static void bwd_fold(const Dag *d, const Node *nd, const double *in, const doubl
                 }
         return;
     }
-    if (nd->axis_hw) {  /* max: to the first maximal pixel (lowest flat index) only */
-        for (c = 0; c < nd->C * T; c++) {
-            double g = gout[c];
-            if (nd->kind == FOLD_MAX) {
-                int best = 0;
-                for (p = 1; p < P; p++)
-                    if (in[(size_t)c * P + p] > in[(size_t)c * P + best]) best = p;
-                gin[(size_t)c * P + best] += g;
-            } else {
-                if (nd->kind == FOLD_AVG) g /= P;
-                for (p = 0; p < P; p++) gin[(size_t)c * P + p] += g;
-            }
-        }
+    if (nd->axis_hw) {  /* max: to the first maximal pixel in scan order (h, then w) only */
+        int Hi = node_H(d, A), Wi = node_W(d, A), Ho = node_H(d, nd), Wo = node_W(d, nd), ho, wo, h, w;
+        for (c = 0; c < nd->C * T; c++)
+            for (ho = 0; ho < Ho; ho++)
+                for (wo = 0; wo < Wo; wo++) {
+                    int h0 = (nd->axis_hw & 1) ? 0 : ho, h1 = (nd->axis_hw & 1) ? Hi : ho + 1;
+                    int w0 = (nd->axis_hw & 2) ? 0 : wo, w1 = (nd->axis_hw & 2) ? Wi : wo + 1;
+                    double g = gout[((size_t)c * Ho + ho) * Wo + wo];
+                    if (nd->kind == FOLD_MAX) {
+                        size_t best = ((size_t)c * Hi + h0) * Wi + w0;
+                        for (h = h0; h < h1; h++)
+                            for (w = w0; w < w1; w++)
+                                if (in[((size_t)c * Hi + h) * Wi + w] > in[best]) best = ((size_t)c * Hi + h) * Wi + w;
+                        gin[best] += g;
+                    } else {
+                        if (nd->kind == FOLD_AVG) g /= (double)((h1 - h0) * (w1 - w0));
+                        for (h = h0; h < h1; h++)
+                            for (w = w0; w < w1; w++) gin[((size_t)c * Hi + h) * Wi + w] += g;
+                    }
+                }
         return;
     }
     for (c = 0; c < nd->C; c++)
@@ -753,8 +780,8 @@ int canvas_oracle_infer(const char *blob, size_t len, const int64_t in_shape[4],
     for (k = 0; k < d.n_nodes; k++) {
         shapes[4 * k + 0] = d.node[k].C;
         shapes[4 * k + 1] = d.node[k].T;
-        shapes[4 * k + 2] = d.node[k].pooled ? 1 : d.H;
-        shapes[4 * k + 3] = d.node[k].pooled ? 1 : d.W;
+        shapes[4 * k + 2] = node_H(&d, &d.node[k]);
+        shapes[4 * k + 3] = node_W(&d, &d.node[k]);
         if (d.node[k].op == OP_FC) {
             const Node *A = &d.node[d.node[k].a];
             int wi = d.node[k].widx;

@@ -164,6 +164,9 @@ FD_BODIES = [
     ("%1 = group %0 groups=2\n%2 = fc %1 out=6\n%3 = softmax %2 axis=C\n%4 = unfold %1 kh=3 kw=1\n%5 = binary %3 %4 op=mul\n"
      "%6 = fold %5 op=sum\n%7 = fc %6 out=4\noutput %7\n", [(2, 3, 2), (2, 2, 2)]),
     ("%1 = group %0 groups=4\n%2 = unfold %1 kh=3 kw=3\n%3 = fc %2 out=8\n%4 = unary %3 op=gelu\n%5 = binary %1 %4 op=mul\noutput %5\n", [(4, 2, 9)]),
+    # folds over one spatial dim: a row profile gates the columns, a column profile is subtracted
+    ("%1 = fold %0 op=avg axis=H\n%2 = unary %1 op=gelu\n%3 = binary %2 %0 op=mul\n%4 = fold %0 op=max axis=W\n%5 = binary %4 %3 op=sub\noutput %5\n", []),
+    ("%1 = unfold %0 kh=3 kw=1\n%2 = fold %1 op=max axis=W\n%3 = fold %2 op=sum axis=H\n%4 = softmax %3 axis=T\n%5 = binary %4 %1 op=mul\n%6 = fold %5 op=sum\noutput %6\n", []),
     # spatial aggregation and kernel spanning: pool to [C], FC to H*W (= 20 here), laid over the pixels of x
     ("%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=20\n%3 = unary %2 op=gelu\n%4 = binary %3 %0 op=mul lhs=pixels\noutput %4\n", [(1, 20, 4)]),
     ("%1 = unfold %0 kh=1 kw=3\n%2 = fold %0 op=max axis=HW\n%3 = fc %2 groups=2 out=20\n%4 = binary %3 %1 op=max lhs=pixels\n%5 = fold %4 op=sum\noutput %5\n", [(2, 10, 2)]),
@@ -631,6 +634,70 @@ def test_group_view_legality_and_propagation(oracle):
     assert ws == [[1, 4, 4]]
     ns, _, ws = oracle.infer(H_ + "%1 = group %0 groups=4\n%2 = unfold %1 kh=3 kw=3\n%3 = fold %2 op=max axis=HW\n%4 = fc %3 out=12\noutput %4\n", (1, 8, 3, 3))
     assert ws == [[4, 3, 18]] and ns[4] == [12, 1, 1, 1]
+
+
+def test_folds_over_one_spatial_dim(oracle):
+    """Section 5, Folding removes any one dim: axis=H and axis=W against numpy reductions, their gradients in
+    closed form, the first-maximum rule, H then W equals HW, and replication of the folded result along the dim
+    it lost (numpy broadcasting)."""
+    rng = np.random.default_rng(90)
+    N, C, H, W = 2, 3, 4, 5
+    x = rng.standard_normal((N, C, H, W))
+    for axis, ax in (("H", 2), ("W", 3)):
+        shape = (N, C, 1, W) if axis == "H" else (N, C, H, 1)
+        dy = rng.standard_normal(shape)
+        for op, fn in (("sum", np.sum), ("avg", np.mean), ("max", np.max)):
+            r = run1(oracle, f"%1 = fold %0 op={op} axis={axis}\noutput %1\n", x, [], dy)
+            np.testing.assert_allclose(r["y"], fn(x, axis=ax, keepdims=True), atol=1e-14)
+            if op == "max":
+                g = np.zeros_like(x)
+                idx = np.argmax(x, axis=ax)      # numpy's argmax is the first maximum as well
+                if axis == "H":
+                    for n in range(N):
+                        for c in range(C):
+                            for w in range(W):
+                                g[n, c, idx[n, c, w], w] = dy[n, c, 0, w]
+                else:
+                    for n in range(N):
+                        for c in range(C):
+                            for h in range(H):
+                                g[n, c, h, idx[n, c, h]] = dy[n, c, h, 0]
+            else:
+                g = np.broadcast_to(dy, x.shape) / (1 if op == "sum" else x.shape[ax])
+            np.testing.assert_allclose(r["dx"], g, atol=1e-14)
+    # ties: constant input, the gradient goes to index 0 of the folded dim
+    r = run1(oracle, "%1 = fold %0 op=max axis=W\noutput %1\n", np.ones((1, 1, 2, 3)), [], np.array([[[[5.0], [7.0]]]]))
+    np.testing.assert_array_equal(r["dx"][0, 0], [[5, 0, 0], [7, 0, 0]])
+    # H then W (and W then H) is the fold over both
+    for op in ("sum", "avg", "max"):
+        both = run1(oracle, f"%1 = fold %0 op={op} axis=HW\noutput %1\n", x)["y"]
+        for a, b in (("H", "W"), ("W", "H")):
+            two = run1(oracle, f"%1 = fold %0 op={op} axis={a}\n%2 = fold %1 op={op} axis={b}\noutput %2\n", x)["y"]
+            np.testing.assert_allclose(two, both, atol=1e-13)
+    # replication along the folded dim: a row profile [C, 1, W] onto [C, H, W]; its gradient sums over H
+    dy = rng.standard_normal((N, C, H, W))
+    r = run1(oracle, "%1 = fold %0 op=avg axis=H\n%2 = binary %1 %0 op=mul\noutput %2\n", x, [], dy)
+    prof = x.mean(axis=2, keepdims=True)
+    np.testing.assert_allclose(r["y"], prof * x, atol=1e-14)
+    np.testing.assert_allclose(r["dx"], dy * prof + (dy * x).sum(axis=2, keepdims=True) / H, atol=1e-13)
+    # a column profile [C, H, 1] minus an unfolded tensor [C, 3, H, W]
+    u = run1(oracle, "%1 = unfold %0 kh=1 kw=3\noutput %1\n", x)["y"]
+    got = run1(oracle, "%1 = unfold %0 kh=1 kw=3\n%2 = fold %0 op=max axis=W\n%3 = binary %2 %1 op=sub\noutput %3\n", x)["y"]
+    np.testing.assert_allclose(got, x.max(axis=3, keepdims=True)[:, :, None] - u, atol=1e-14)
+    # shapes and legality
+    ns, _, _ = oracle.infer(H_ + "%1 = fold %0 op=sum axis=W\n%2 = fc %1 groups=1 out=7\n%3 = fold %2 op=max axis=H\noutput %3\n", (1, C, H, W))
+    assert ns[1] == [C, 1, H, 1] and ns[2] == [7, 1, H, 1] and ns[3] == [7, 1, 1, 1]
+    for bad in ("%1 = fold %0 op=sum axis=H\n%2 = fold %1 op=sum axis=H\noutput %2\n",
+                "%1 = fold %0 op=sum axis=H\n%2 = fold %1 op=sum axis=HW\noutput %2\n",
+                "%1 = fold %0 op=sum axis=H\n%2 = fold %0 op=sum axis=W\n%3 = binary %1 %2 op=add\noutput %3\n",   # [C,1,W] onto [C,H,1]
+                "%1 = fold %0 op=sum axis=W\n%2 = binary %0 %1 op=add\noutput %2\n",                               # full-size onto folded
+                "%1 = fold %0 op=sum axis=W\n%2 = unfold %1 kh=3 kw=1\noutput %2\n",
+                "%1 = fold %0 op=sum axis=H\n%2 = shift %1 dh=0 dw=1\noutput %2\n",
+                "%1 = fold %0 op=sum axis=X\noutput %1\n"):
+        with pytest.raises(Exception):
+            run1(oracle, bad, x)
+    # a tensor folded over both dims is an LHS for one folded over one
+    run1(oracle, "%1 = fold %0 op=sum axis=HW\n%2 = fold %0 op=sum axis=W\n%3 = binary %1 %2 op=add\noutput %3\n", x)
 
 
 def test_pooled_vector_laid_over_the_pixels(oracle):
