@@ -17,7 +17,7 @@
  *     %3 = unary %2 op=gelu            relu | abs | gelu | sin | expclip lo=<f> hi=<f>
  *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
  *     %5 = binary %0 %4 op=mul         first operand LHS, second RHS; add | sub | mul | min | max [lhs=pixels]
- *     %6 = fold %5 op=avg              sum | avg | max [axis=T | HW | C [groups=<G>]]
+ *     %6 = fold %5 op=avg              sum | avg | max [axis=T | H | W | HW | C [groups=<G>]]
  *     %7 = softmax %6 axis=C           C | T | CT
  *     %8 = group %7 groups=4           a view [G, C/G] of the channels; groups=C: every channel a group
  *     output %8
@@ -45,10 +45,13 @@
  *            (axis=CT, per n,h,w) (Section 5, Softmax over contiguous dims).
  *   fold     sum, avg or max over T; T disappears (Section 5, Folding).  Max
  *            sends its gradient to the first maximal tap.  With axis=HW the
- *            pixels are folded instead (global pooling): the result is
- *            [N, C, T, 1, 1]; fc, unary, softmax, fold over T and binary accept
- *            such a tensor (unfold and shift do not), and as the LHS of a
- *            binary it is replicated over the pixels of a full-size RHS.  With
+ *            pixels are folded instead (global pooling), with axis=H or axis=W
+ *            one spatial dim: the result is [N, C, T, 1, 1], [N, C, T, 1, W] or
+ *            [N, C, T, H, 1] (first maximum in the order h, then w); fc, unary,
+ *            softmax, the remaining folds and binary accept such a tensor
+ *            (unfold and shift do not), and as the LHS of a binary it is
+ *            replicated along the dims it has folded onto an RHS that still has
+ *            them (an RHS may not have folded a dim that the LHS keeps).  With
  *            axis=C groups=G (default 1) the C/G channels of each of G channel
  *            groups are folded: G channels remain.
  *   group    the Group primitive as a node (Section 5, Group: [.., X, ..] => [.., G, X/G, ..]

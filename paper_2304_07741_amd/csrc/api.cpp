@@ -125,7 +125,7 @@ int canvas_dag_compile(const void* blob, size_t blob_len, const int64_t in_shape
         double wbytes = 0, wcount = 0;
         for (int k = 0; k < I.n_nodes; k++) {
             const canvas::Node& nd = g.nodes[k];
-            int64_t s[5] = {g.N, nd.C, nd.T, nd.pooled ? 1 : g.H, nd.pooled ? 1 : g.W};
+            int64_t s[5] = {g.N, nd.C, nd.T, (nd.pooled & 1) ? 1 : g.H, (nd.pooled & 2) ? 1 : g.W};
             std::memcpy(I.node_shape[k], s, sizeof s);
             if (nd.op == canvas::Op::Fc) {
                 const canvas::Node& A = g.nodes[nd.a];

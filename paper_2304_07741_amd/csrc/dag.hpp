@@ -25,9 +25,9 @@ struct Node {
     int groups = 1, out = 0;     // fc
     int kind = 0;                // UnaryKind / BinaryKind / AxisKind / FoldKind
     float lo = 0.f, hi = 0.f;    // expclip bounds
-    int axis_hw = 0;             // fold: 1 = over the pixels (the result is pooled), 0 = over the taps
+    int axis_hw = 0;             // fold: mask of the spatial dims folded by this node (1 = H, 2 = W, 3 = both), 0 = over the taps
     int axis_c = 0;              // fold: 1 = over the C / groups channels of each of `groups` channel groups
-    bool pooled = false;         // the spatial dims have been folded away: shape [N, C, T, 1, 1]
+    int pooled = 0;              // mask of the spatial dims folded away so far: 1 = H ([N, C, T, 1, W]), 2 = W, 3 = both
     int grp = 1;                 // Group view of the channel dim, [grp, C / grp] (1 = none)
     bool lhs_pixels = false;     // binary: the pooled LHS has H*W elements, element p meets pixel p of every channel and tap
     int bgroups = 1;             // binary: > 1 when both operands carry this same view, the blend then runs inside each group
@@ -44,7 +44,9 @@ struct Dag {
     std::vector<int> weight_node;
 
     int P() const { return H * W; }
-    int Pk(int k) const { return nodes[k].pooled ? 1 : H * W; }  // pixels of node k
+    int Hk(int k) const { return (nodes[k].pooled & 1) ? 1 : H; }
+    int Wk(int k) const { return (nodes[k].pooled & 2) ? 1 : W; }
+    int Pk(int k) const { return Hk(k) * Wk(k); }  // pixels of node k
     int64_t numel(int k) const { return (int64_t)N * nodes[k].C * nodes[k].T * Pk(k); }
 };
 

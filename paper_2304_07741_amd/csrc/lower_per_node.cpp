@@ -198,8 +198,11 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             const int Gb = nd.bgroups;
             // lhs=pixels: the [H*W, 1, 1, 1] LHS is a one-channel full-size tensor to the kernel
             const int CLk = nd.lhs_pixels ? 1 : A.C / Gb, TLk = nd.lhs_pixels ? 1 : A.T, PLk = nd.lhs_pixels ? Pn : PL;
+            // an LHS that has folded away one spatial dim the result still has is replicated along it
+            const int lost = A.pooled & ~nd.pooled, Wd = dag.Wk(k);
+            const int rep = nd.lhs_pixels || lost == 3 || lost == 0 ? 0 : lost;
             L.run = [=](const RunArgs& a) {
-                ref::binary_fwd(val(a, nd.a), val(a, nd.b), valw(a, k), N * Gb, CLk, TLk, B.C / Gb, B.T, Pn, PLk, nd.kind, a.stream);
+                ref::binary_fwd(val(a, nd.a), val(a, nd.b), valw(a, k), N * Gb, CLk, TLk, B.C / Gb, B.T, Pn, PLk, rep, Wd, nd.kind, a.stream);
             };
             break;
         }
@@ -220,9 +223,18 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
                 const int Cg = A.C / nd.groups;
                 L.name = "node_cfold_fwd";
                 L.run = [=](const RunArgs& a) { ref::cfold_fwd(val(a, nd.a), valw(a, k), N * nd.groups, Cg, TP, nd.kind, a.stream); };
+            } else if (nd.axis_hw == 1) {
+                // over H alone: the H rows of a plane are "channels" of Wi elements each to the channel-fold kernel
+                const int Hi = dag.Hk(nd.a), Wi = dag.Wk(nd.a);
+                L.name = "node_hfold_fwd";
+                L.run = [=](const RunArgs& a) { ref::cfold_fwd(val(a, nd.a), valw(a, k), N * A.C * A.T, Hi, Wi, nd.kind, a.stream); };
             } else if (nd.axis_hw) {
+                // over W alone: every image row is a plane of Wi pixels; over both: every (channel, tap) plane
+                const int Hi = dag.Hk(nd.a), Wi = dag.Wk(nd.a);
+                const int64_t rows = N * A.C * A.T * (nd.axis_hw == 2 ? Hi : 1);
+                const int len = nd.axis_hw == 2 ? Wi : Hi * Wi;
                 L.name = "node_pool_fwd";
-                L.run = [=](const RunArgs& a) { ref::pool_fwd(val(a, nd.a), valw(a, k), N * A.C * A.T, P, nd.kind, a.stream); };
+                L.run = [=](const RunArgs& a) { ref::pool_fwd(val(a, nd.a), valw(a, k), rows, len, nd.kind, a.stream); };
             } else {
                 const int Pn = dag.Pk(k);
                 L.run = [=](const RunArgs& a) { ref::fold_fwd(val(a, nd.a), valw(a, k), N * A.C, A.T, Pn, nd.kind, a.stream); };
@@ -338,8 +350,10 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             L.bytes = 4.0 * (dag.numel(nd.a) * (1 + acc) + dag.numel(k) * (nd.kind == kAdd || nd.kind == kSub ? 1 : 2));
             const int Pn = dag.Pk(k), PL = dag.Pk(nd.a), Gb = nd.bgroups;
             const int CLk = nd.lhs_pixels ? 1 : A.C / Gb, TLk = nd.lhs_pixels ? 1 : A.T, PLk = nd.lhs_pixels ? Pn : PL;
+            const int lost = A.pooled & ~nd.pooled, Wd = dag.Wk(k);
+            const int rep = nd.lhs_pixels || lost == 3 || lost == 0 ? 0 : lost;
             L.run = [=](const RunArgs& a) {
-                ref::binary_bwd_lhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.a), N * Gb, CLk, TLk, B.C / Gb, B.T, Pn, PLk, nd.kind, acc, a.stream);
+                ref::binary_bwd_lhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.a), N * Gb, CLk, TLk, B.C / Gb, B.T, Pn, PLk, rep, Wd, nd.kind, acc, a.stream);
             };
             low->bwd.push_back(std::move(L));
             written[nd.a] = true;
@@ -348,7 +362,7 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
             R.name = "node_binary_bwd_rhs";
             R.bytes = 4.0 * (dag.numel(nd.b) * (1 + acc_r) + dag.numel(k) + (nd.kind == kAdd || nd.kind == kSub ? 0 : dag.numel(nd.a)));
             R.run = [=](const RunArgs& a) {
-                ref::binary_bwd_rhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.b), N * Gb, CLk, TLk, B.C / Gb, B.T, Pn, PLk, nd.kind, acc_r, a.stream);
+                ref::binary_bwd_rhs(val(a, nd.a), val(a, nd.b), grad(a, k), grad(a, nd.b), N * Gb, CLk, TLk, B.C / Gb, B.T, Pn, PLk, rep, Wd, nd.kind, acc_r, a.stream);
             };
             low->bwd.push_back(std::move(R));
             written[nd.b] = true;
@@ -373,9 +387,16 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
                 const int Cg = A.C / nd.groups;
                 L.name = "node_cfold_bwd";
                 L.run = [=](const RunArgs& a) { ref::cfold_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * nd.groups, Cg, TP, nd.kind, acc, a.stream); };
+            } else if (nd.axis_hw == 1) {
+                const int Hi = dag.Hk(nd.a), Wi = dag.Wk(nd.a);
+                L.name = "node_hfold_bwd";
+                L.run = [=](const RunArgs& a) { ref::cfold_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * A.C * A.T, Hi, Wi, nd.kind, acc, a.stream); };
             } else if (nd.axis_hw) {
+                const int Hi = dag.Hk(nd.a), Wi = dag.Wk(nd.a);
+                const int64_t rows = N * A.C * A.T * (nd.axis_hw == 2 ? Hi : 1);
+                const int len = nd.axis_hw == 2 ? Wi : Hi * Wi;
                 L.name = "node_pool_bwd";
-                L.run = [=](const RunArgs& a) { ref::pool_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * A.C * A.T, P, nd.kind, acc, a.stream); };
+                L.run = [=](const RunArgs& a) { ref::pool_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), rows, len, nd.kind, acc, a.stream); };
             } else {
                 const int Pn = dag.Pk(k);
                 L.run = [=](const RunArgs& a) { ref::fold_bwd(val(a, nd.a), grad(a, k), grad(a, nd.a), N * A.C, A.T, Pn, nd.kind, acc, a.stream); };

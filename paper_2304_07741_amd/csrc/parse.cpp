@@ -192,14 +192,14 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             nd.bgroups = A.grp == B.grp ? A.grp : 1;
             const int CLg = A.C / nd.bgroups, CRg = B.C / nd.bgroups;
             bool legal = (CLg == CRg) ? (B.T % A.T == 0) : (((int64_t)CRg * B.T) % ((int64_t)CLg * A.T) == 0);
-            if (!A.pooled && B.pooled) legal = false;  // a pooled LHS is replicated over the pixels, not the reverse
+            if ((A.pooled & B.pooled) != B.pooled) legal = false;  // the LHS is replicated along dims it has folded away, not the reverse
             auto al = l.attr.find("lhs");
             if (al != l.attr.end()) {
                 if (al->second != "pixels") return fail(err, lineno, "binary lhs= must be pixels", kInvalidBlob);
                 // [X] read as [H, W]: a common suffix with the RHS; nothing of the LHS is left to replicate along channels
                 nd.lhs_pixels = true;
                 nd.bgroups = 1;
-                legal = A.pooled && !B.pooled && (int64_t)A.C * A.T == (int64_t)dag.H * dag.W;
+                legal = A.pooled == 3 && !B.pooled && (int64_t)A.C * A.T == (int64_t)dag.H * dag.W;
             }
             nd.pooled = B.pooled;
             nd.grp = B.grp;
@@ -225,9 +225,11 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             else if (it->second == "max") nd.kind = kMax;
             else return fail(err, lineno, "unknown fold op '" + it->second + "'", kUnknownOp);
             auto ax = l.attr.find("axis");
-            if (ax != l.attr.end() && ax->second == "HW") nd.axis_hw = 1;
+            if (ax != l.attr.end() && ax->second == "HW") nd.axis_hw = 3;
+            else if (ax != l.attr.end() && ax->second == "H") nd.axis_hw = 1;
+            else if (ax != l.attr.end() && ax->second == "W") nd.axis_hw = 2;
             else if (ax != l.attr.end() && ax->second == "C") nd.axis_c = 1;
-            else if (ax != l.attr.end() && ax->second != "T") return fail(err, lineno, "fold axis must be T, HW or C", kUnknownOp);
+            else if (ax != l.attr.end() && ax->second != "T") return fail(err, lineno, "fold axis must be T, H, W, HW or C", kUnknownOp);
             nd.C = A.C;
             if (nd.axis_c) {
                 nd.groups = 1;
@@ -237,9 +239,9 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
                 nd.T = A.T;
                 nd.grp = 1;
             } else if (nd.axis_hw) {
-                if (A.pooled) return fail(err, lineno, "fold axis=HW: the spatial dims are already folded", kShapeMismatch);
+                if (A.pooled & nd.axis_hw) return fail(err, lineno, "fold: that spatial dim is already folded", kShapeMismatch);
                 nd.T = A.T;
-                nd.pooled = true;
+                nd.pooled = A.pooled | nd.axis_hw;
             } else {
                 nd.T = 1;
             }

@@ -186,9 +186,15 @@ __device__ inline void bsrc(int CL, int TL, int TR, int c, int t, int same_c, in
     }
 }
 
-// PL: pixels of the LHS, P or 1 (a pooled LHS is replicated over the pixels)
+// PL: pixels of the LHS.  rep says how pixel p of the result finds its LHS pixel: 0: p itself (PL == P) or the
+// one pixel of a fully pooled LHS (PL == 1); 1: p % Wd (the LHS has folded H away, PL == Wd); 2: p / Wd (the
+// LHS has folded W away, PL == P / Wd).  Wd: width of the result.
+__device__ __forceinline__ int lhs_pixel(int p, int PL, int rep, int Wd) {
+    return rep == 1 ? p % Wd : (rep == 2 ? p / Wd : (PL == 1 ? 0 : p));
+}
+
 __global__ void k_binary_fwd(const float* __restrict__ lhs, const float* __restrict__ rhs, float* __restrict__ out,
-                             int64_t total, int CL, int TL, int CR, int TR, int P, int PL, int kind) {
+                             int64_t total, int CL, int TL, int CR, int TR, int P, int PL, int rep, int Wd, int kind) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
     int p = (int)(i % P);
@@ -199,12 +205,13 @@ __global__ void k_binary_fwd(const float* __restrict__ lhs, const float* __restr
     int64_t n = r / CR;
     int cl, tl;
     bsrc(CL, TL, TR, c, t, CL == CR, cl, tl);
-    float a = lhs[((n * CL + cl) * TL + tl) * PL + (PL == 1 ? 0 : p)], b = rhs[i];
+    float a = lhs[((n * CL + cl) * TL + tl) * PL + lhs_pixel(p, PL, rep, Wd)], b = rhs[i];
     out[i] = binary_apply(kind, a, b);
 }
 
 __global__ void k_binary_bwd_rhs(const float* __restrict__ lhs, const float* __restrict__ rhs, const float* __restrict__ gout,
-                                 float* __restrict__ grhs, int64_t total, int CL, int TL, int CR, int TR, int P, int PL, int kind, int acc) {
+                                 float* __restrict__ grhs, int64_t total, int CL, int TL, int CR, int TR, int P, int PL, int rep, int Wd,
+                                 int kind, int acc) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
     float g = gout[i];
@@ -217,15 +224,16 @@ __global__ void k_binary_bwd_rhs(const float* __restrict__ lhs, const float* __r
         int64_t n = r / CR;
         int cl, tl;
         bsrc(CL, TL, TR, c, t, CL == CR, cl, tl);
-        g *= binary_grad_rhs(kind, lhs[((n * CL + cl) * TL + tl) * PL + (PL == 1 ? 0 : p)], rhs[i]);
+        g *= binary_grad_rhs(kind, lhs[((n * CL + cl) * TL + tl) * PL + lhs_pixel(p, PL, rep, Wd)], rhs[i]);
     }
     grhs[i] = acc ? grhs[i] + g : g;
 }
 
-// One thread per LHS element sums over the RHS elements it was replicated onto (channels / taps, and all
-// pixels when the LHS is pooled), in a fixed order.
+// One thread per LHS element sums over the RHS elements it was replicated onto (channels / taps, and the
+// pixels along the spatial dims the LHS has folded away), in a fixed order.
 __global__ void k_binary_bwd_lhs(const float* __restrict__ lhs, const float* __restrict__ rhs, const float* __restrict__ gout,
-                                 float* __restrict__ glhs, int64_t total, int CL, int TL, int CR, int TR, int P, int PL, int kind, int acc) {
+                                 float* __restrict__ glhs, int64_t total, int CL, int TL, int CR, int TR, int P, int PL, int rep, int Wd,
+                                 int kind, int acc) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
     int pl = (int)(i % PL);
@@ -235,18 +243,20 @@ __global__ void k_binary_bwd_lhs(const float* __restrict__ lhs, const float* __r
     int cl = (int)(r % CL);
     int64_t n = r / CL;
     const float a = lhs[i];
-    const int p0 = PL == 1 ? 0 : pl, p1 = PL == 1 ? P : pl + 1;
+    // the pixels of the result that read this LHS pixel: pcount of them from p0 in steps of pstep
+    const int p0 = rep == 2 ? pl * Wd : (PL == 1 ? 0 : pl);
+    const int pcount = rep == 1 ? P / Wd : (rep == 2 ? Wd : (PL == 1 ? P : 1)), pstep = rep == 1 ? Wd : 1;
     float s = 0.f;
     if (CL == CR) {
         for (int t = tl; t < TR; t += TL)
-            for (int p = p0; p < p1; p++) {
+            for (int pi = 0, p = p0; pi < pcount; pi++, p += pstep) {
                 int64_t j = ((n * CR + cl) * TR + t) * P + p;
                 s += kind == 0 ? gout[j] : gout[j] * binary_grad_lhs(kind, a, rhs[j]);
             }
     } else {
         long long L = (long long)CL * TL, R = (long long)CR * TR;
         for (long long f = (long long)cl * TL + tl; f < R; f += L)
-            for (int p = p0; p < p1; p++) {
+            for (int pi = 0, p = p0; pi < pcount; pi++, p += pstep) {
                 int64_t j = (n * R + f) * P + p;
                 s += kind == 0 ? gout[j] : gout[j] * binary_grad_lhs(kind, a, rhs[j]);
             }
@@ -504,20 +514,20 @@ void unary_fwd(const float* in, float* out, int64_t n, int kind, float lo, float
 void unary_bwd(const float* in, const float* gout, float* gin, int64_t n, int kind, float lo, float hi, int acc, hipStream_t s) {
     LAUNCH(k_unary_bwd, n, in, gout, gin, n, kind, lo, hi, acc);
 }
-void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int PL, int kind,
-                hipStream_t s) {
+void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int PL, int rep, int Wd,
+                int kind, hipStream_t s) {
     int64_t total = N * CR * TR * P;
-    LAUNCH(k_binary_fwd, total, lhs, rhs, out, total, CL, TL, CR, TR, P, PL, kind);
+    LAUNCH(k_binary_fwd, total, lhs, rhs, out, total, CL, TL, CR, TR, P, PL, rep, Wd, kind);
 }
 void binary_bwd_rhs(const float* lhs, const float* rhs, const float* gout, float* grhs, int64_t N, int CL, int TL, int CR, int TR, int P,
-                    int PL, int kind, int acc, hipStream_t s) {
+                    int PL, int rep, int Wd, int kind, int acc, hipStream_t s) {
     int64_t total = N * CR * TR * P;
-    LAUNCH(k_binary_bwd_rhs, total, lhs, rhs, gout, grhs, total, CL, TL, CR, TR, P, PL, kind, acc);
+    LAUNCH(k_binary_bwd_rhs, total, lhs, rhs, gout, grhs, total, CL, TL, CR, TR, P, PL, rep, Wd, kind, acc);
 }
 void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
-                    int PL, int kind, int acc, hipStream_t s) {
+                    int PL, int rep, int Wd, int kind, int acc, hipStream_t s) {
     int64_t total = N * CL * TL * PL;
-    LAUNCH(k_binary_bwd_lhs, total, lhs, rhs, gout, glhs, total, CL, TL, CR, TR, P, PL, kind, acc);
+    LAUNCH(k_binary_bwd_lhs, total, lhs, rhs, gout, glhs, total, CL, TL, CR, TR, P, PL, rep, Wd, kind, acc);
 }
 void cfold_fwd(const float* in, float* out, int64_t NG, int Cg, int64_t TP, int kind, hipStream_t s) {
     int64_t total = NG * TP;

@@ -21,13 +21,15 @@ void fc_dx(const float* gy, const float* wt, float* gx, int64_t N, int G, int Og
 void fc_dw(const float* gy, const float* x, float* dw, int64_t N, int G, int Og, int K, int P, hipStream_t s);
 void unary_fwd(const float* in, float* out, int64_t n, int kind, float lo, float hi, hipStream_t s);
 void unary_bwd(const float* in, const float* gout, float* gin, int64_t n, int kind, float lo, float hi, int acc, hipStream_t s);
-// P: pixels of the RHS / result; PL: pixels of the LHS (P, or 1 for a pooled LHS replicated over the pixels)
-void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int PL, int kind,
-                hipStream_t s);
+// P: pixels of the RHS / result, Wd its width; PL: pixels of the LHS; rep: 0 = the LHS has the pixels of the result
+// (PL == P) or a single one replicated over all (PL == 1), 1 = the LHS has folded H away (its pixel is p % Wd),
+// 2 = it has folded W away (p / Wd)
+void binary_fwd(const float* lhs, const float* rhs, float* out, int64_t N, int CL, int TL, int CR, int TR, int P, int PL, int rep, int Wd,
+                int kind, hipStream_t s);
 void binary_bwd_rhs(const float* lhs, const float* rhs, const float* gout, float* grhs, int64_t N, int CL, int TL, int CR, int TR, int P,
-                    int PL, int kind, int acc, hipStream_t s);
+                    int PL, int rep, int Wd, int kind, int acc, hipStream_t s);
 void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
-                    int PL, int kind, int acc, hipStream_t s);
+                    int PL, int rep, int Wd, int kind, int acc, hipStream_t s);
 // axis_c: 1 = over channels, 0 = over taps, 2 = over both jointly
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s);
 void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C, int T, int P, int axis_c, int acc,

@@ -75,6 +75,13 @@ PRIMS = [
     ("%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out=99\n%3 = binary %2 %0 op=mul lhs=pixels\noutput %3\n", [(1, 99, 12)]),
     ("%1 = unfold %0 kh=1 kw=3\n%2 = fold %0 op=max axis=HW\n%3 = fc %2 groups=3 out=99\n%4 = unary %3 op=gelu\n"
      "%5 = binary %4 %1 op=sub lhs=pixels\n%6 = fold %5 op=avg\n%7 = binary %0 %6 op=min\noutput %7\n", [(3, 33, 4)]),
+    # folds over one spatial dim and replication along it
+    ("%1 = fold %0 op=max axis=H\noutput %1\n", []),
+    ("%1 = fold %0 op=avg axis=W\noutput %1\n", []),
+    ("%1 = fold %0 op=avg axis=H\n%2 = unary %1 op=gelu\n%3 = binary %2 %0 op=mul\n%4 = fold %0 op=max axis=W\n%5 = binary %4 %3 op=sub\noutput %5\n", []),
+    ("%1 = unfold %0 kh=3 kw=1\n%2 = fold %1 op=max axis=W\n%3 = fc %2 groups=3 out=6\n%4 = fold %3 op=sum axis=H\n%5 = softmax %4 axis=C\n"
+     "%6 = fc %0 groups=1 out=6\n%7 = binary %5 %6 op=mul\n%8 = binary %3 %7 op=add\noutput %8\n", [(3, 2, 12), (1, 6, 12)]),
+    ("%1 = fold %0 op=sum axis=HW\n%2 = fold %0 op=max axis=W\n%3 = binary %1 %2 op=max\n%4 = fold %3 op=avg axis=H\n%5 = binary %4 %0 op=add\noutput %5\n", []),
     # Group as a node: the view alone, depth-wise 3x3, grouped Involution, a grouped blend with fan-out, mixed views
     ("%1 = group %0 groups=3\noutput %1\n", []),
     ("%1 = group %0 groups=12\n%2 = unfold %1 kh=3 kw=3\n%3 = fc %2 out=12\noutput %3\n", [(12, 1, 9)]),

@@ -290,3 +290,25 @@ def test_tensors_beyond_32_bit_offsets_take_the_per_node_lowering(lib):
     with pytest.raises(B.CanvasError) as e:     # more than 2^40 elements in one tensor
         B.canvas_dag_compile(wl.blob_conv(3, 1, 16), (1 << 20, 1 << 10, 64, 64), B.CANVAS_BF16)
     assert e.value.status == -6
+
+
+def test_single_dim_spatial_folds_shapes_and_legality(lib, oracle):
+    H_ = wl.HEADER
+    ok = ["%1 = fold %0 op=sum axis=W\n%2 = fc %1 groups=1 out=7\n%3 = fold %2 op=max axis=H\noutput %3\n",
+          "%1 = fold %0 op=avg axis=H\n%2 = binary %1 %0 op=mul\noutput %2\n",
+          "%1 = fold %0 op=sum axis=HW\n%2 = fold %0 op=sum axis=W\n%3 = binary %1 %2 op=add\noutput %3\n"]
+    for body in ok:
+        ns, out, ws = oracle.infer(H_ + body, (2, 8, 5, 6))
+        h = B.canvas_dag_compile(H_ + body, (2, 8, 5, 6), B.CANVAS_BF16)
+        info = B.canvas_dag_query(h)
+        assert [list(info.node_shape[k]) for k in range(info.n_nodes)] == [[2] + s_ for s_ in ns]
+        B.canvas_dag_destroy(h)
+    bad = ["%1 = fold %0 op=sum axis=H\n%2 = fold %1 op=sum axis=H\noutput %2\n", "%1 = fold %0 op=sum axis=H\n%2 = fold %1 op=sum axis=HW\noutput %2\n",
+           "%1 = fold %0 op=sum axis=H\n%2 = fold %0 op=sum axis=W\n%3 = binary %1 %2 op=add\noutput %3\n",
+           "%1 = fold %0 op=sum axis=W\n%2 = binary %0 %1 op=add\noutput %2\n", "%1 = fold %0 op=sum axis=W\n%2 = unfold %1 kh=3 kw=1\noutput %2\n",
+           "%1 = fold %0 op=sum axis=X\noutput %1\n"]
+    for body in bad:
+        with pytest.raises(Exception):
+            oracle.infer(H_ + body, (2, 8, 5, 6))
+        with pytest.raises(B.CanvasError):
+            B.canvas_dag_compile(H_ + body, (2, 8, 5, 6), B.CANVAS_BF16)
