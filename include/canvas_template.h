@@ -70,7 +70,7 @@ int canvas_template_parse(const void* blob, size_t blob_len, canvas_template** o
 int canvas_template_query(const canvas_template* t, canvas_template_info* info);
 
 /* Symbolic shape of node `node` as text "[C-dims | tap dims | H, W]", e.g.
- * "[G, x2/G | KH, KW | H, W]", "[x1 | H, W]" without taps; a pooled tensor ends in "| 1, 1]". */
+ * "[G, x2/G | KH, KW | H, W]", "[x1 | H, W]" without taps; a folded spatial dim reads 1 ("| 1, W]", "| 1, 1]"). */
 int canvas_template_node_shape(const canvas_template* t, int node, char* buf, size_t buf_len, size_t* needed);
 
 /* Shape-matching solver (Section 6.2).  node: a binary node whose LHS carries a

@@ -151,7 +151,7 @@ class Template:
         self.ones = []       # (monomial that must equal 1, node)
         for k, nd in enumerate(self.nodes):
             if nd["op"] == "input":
-                nd.update(C=mono(G=1, Cg=1), taps=[], pooled=False, grp=mono())
+                nd.update(C=mono(G=1, Cg=1), taps=[], pooled=0, grp=mono())   # pooled: mask of folded spatial dims, 1 = H, 2 = W
                 continue
             A = self.nodes[nd["a"]]
             C, taps, pooled, grp = A["C"], list(A["taps"]), A["pooled"], A["grp"]
@@ -189,12 +189,12 @@ class Template:
                 C, taps = out, []
             elif op == "binary":
                 B = self.nodes[nd["b"]]
-                if not pooled and B["pooled"]:
-                    raise ValueError(f"node {k}: full-size LHS onto pooled RHS")
+                if (pooled & B["pooled"]) != B["pooled"]:
+                    raise ValueError(f"node {k}: the RHS has folded a spatial dim that the LHS keeps")
                 lhs, rhs = mul(C, prod(taps)), mul(B["C"], prod(B["taps"]))
                 al = self.attr(nd, "lhs")
                 if al is not None:
-                    if al != "pixels" or not pooled or B["pooled"]:
+                    if al != "pixels" or pooled != 3 or B["pooled"]:
                         raise ValueError(f"node {k}: bad lhs=")
                     self.ones.append((div(mono(H=1, W=1), lhs), k))
                 else:
@@ -204,10 +204,11 @@ class Template:
                 axis = self.attr(nd, "axis") or "T"
                 if axis == "T":
                     taps = []
-                elif axis == "HW":
-                    if pooled:
-                        raise ValueError(f"node {k}: already pooled")
-                    pooled = True
+                elif axis in ("HW", "H", "W"):
+                    m = {"HW": 3, "H": 1, "W": 2}[axis]
+                    if pooled & m:
+                        raise ValueError(f"node {k}: already folded")
+                    pooled |= m
                 elif axis == "C":
                     g = self.attr(nd, "groups") or mono()
                     if variables(g):
@@ -241,7 +242,7 @@ class Template:
         nd = self.nodes[k]
         c = to_text(nd["C"]) if nd["grp"] == mono() else to_text(nd["grp"]) + ", " + to_text(div(nd["C"], nd["grp"]))
         t = (" " + ", ".join(to_text(m) for m in nd["taps"]) + " |") if nd["taps"] else ""
-        return f"[{c} |{t} " + ("1, 1]" if nd["pooled"] else "H, W]")
+        return f"[{c} |{t} " + ("1" if nd["pooled"] & 1 else "H") + ", " + ("1" if nd["pooled"] & 2 else "W") + "]"
 
     # ------------------------------------------------------------ Section 6.2: shape matching
 
@@ -309,7 +310,7 @@ class Template:
                 if w.denominator != 1:
                     raise ValueError("weight shape is no integer")
                 params += w
-                flops += w * (1 if A["pooled"] else b["H"] * b["W"])
+                flops += w * (1 if A["pooled"] & 1 else b["H"]) * (1 if A["pooled"] & 2 else b["W"])
         return flops, params
 
     def solve(self, targets, G, flops_budget=0, params_budget=0):

@@ -38,7 +38,7 @@ struct TNode {
     // inferred
     Mono C;
     std::vector<Mono> taps;
-    bool pooled = false;
+    int pooled = 0;  // mask of folded spatial dims: 1 = H, 2 = W
     Mono grp;  // 1 = no Group view
     Mono groups_used;  // fc / fold over channels / group: the group count that applies
 
@@ -103,7 +103,7 @@ int infer(Template& t) {
         if (nd.op == TOp::Input) {
             nd.C = Mono::channels();
             nd.taps.clear();
-            nd.pooled = false;
+            nd.pooled = 0;
             nd.grp = Mono::one();
             continue;
         }
@@ -169,11 +169,12 @@ int infer(Template& t) {
         case TOp::Softmax: break;
         case TOp::Binary: {
             const TNode& B = t.nodes[nd.b];
-            if (!A.pooled && B.pooled) return fail(CANVAS_SHAPE_MISMATCH, 0, "node " + std::to_string(id) + ": a full-size LHS onto a pooled RHS");
+            if ((A.pooled & B.pooled) != B.pooled)
+                return fail(CANVAS_SHAPE_MISMATCH, 0, "node " + std::to_string(id) + ": the RHS has folded a spatial dim that the LHS keeps");
             const Mono lhs = A.C * product(A.taps), rhs = B.C * product(B.taps);
             const Attr* al = nd.find("lhs");
             if (al) {
-                if (al->raw != "pixels" || !A.pooled || B.pooled)
+                if (al->raw != "pixels" || A.pooled != 3 || B.pooled)
                     return fail(CANVAS_SHAPE_MISMATCH, 0, "node " + std::to_string(id) + ": lhs=pixels needs a pooled LHS and a full-size RHS");
                 t.must_be_one.push_back({Mono::atom(sym::aH) * Mono::atom(sym::aW) / lhs, id});
             } else {
@@ -189,9 +190,10 @@ int infer(Template& t) {
             const Attr* ax = nd.find("axis");
             const std::string axis = ax ? ax->raw : "T";
             if (axis == "T") nd.taps.clear();
-            else if (axis == "HW") {
-                if (A.pooled) return fail(CANVAS_SHAPE_MISMATCH, 0, "node " + std::to_string(id) + ": the spatial dims are already folded");
-                nd.pooled = true;
+            else if (axis == "HW" || axis == "H" || axis == "W") {
+                const int m = axis == "HW" ? 3 : (axis == "H" ? 1 : 2);
+                if (A.pooled & m) return fail(CANVAS_SHAPE_MISMATCH, 0, "node " + std::to_string(id) + ": that spatial dim is already folded");
+                nd.pooled = A.pooled | m;
             } else if (axis == "C") {
                 Mono g = Mono::one();
                 need("groups", g);
@@ -201,7 +203,7 @@ int infer(Template& t) {
                 t.must_be_integer.push_back({A.C / g, id, "folded channels per group"});
                 nd.C = g;
                 nd.grp = Mono::one();
-            } else return fail(CANVAS_UNKNOWN_OP, 0, "node " + std::to_string(id) + ": fold axis must be T, HW or C");
+            } else return fail(CANVAS_UNKNOWN_OP, 0, "node " + std::to_string(id) + ": fold axis must be T, H, W, HW or C");
             break;
         }
         default: break;
@@ -303,7 +305,7 @@ std::string shape_text(const TNode& nd) {
     s += " |";
     for (size_t i = 0; i < nd.taps.size(); i++) s += (i ? ", " : " ") + sym::to_text(nd.taps[i]);
     if (!nd.taps.empty()) s += " |";
-    s += nd.pooled ? " 1, 1]" : " H, W]";
+    s += std::string(" ") + ((nd.pooled & 1) ? "1" : "H") + ", " + ((nd.pooled & 2) ? "1" : "W") + "]";
     return s;
 }
 
@@ -361,7 +363,7 @@ bool cost_of(const Template& t, const Binding& b, double& flops, double& params)
         int64_t p, q;
         if (!sym::evaluate(w, b, p, q) || q != 1) return false;
         params += (double)p;
-        flops += (double)p * (A.pooled ? 1.0 : (double)b.v[sym::aH] * (double)b.v[sym::aW]);
+        flops += (double)p * ((A.pooled & 1) ? 1.0 : (double)b.v[sym::aH]) * ((A.pooled & 2) ? 1.0 : (double)b.v[sym::aW]);
     }
     return true;
 }

@@ -317,7 +317,7 @@ def fuzz_template(seed):
         elif kind == "softmax":
             emit(f"softmax %{cur} axis={rng.choice(['C', 'T', 'CT'])}")
         else:
-            ax = rng.choice(["", "", " axis=HW", " axis=C groups=G", " axis=C"])
+            ax = rng.choice(["", "", " axis=HW", " axis=C groups=G", " axis=C", " axis=H", " axis=W"])
             emit(f"fold %{cur} op={rng.choice(['sum', 'avg', 'max'])}{ax}")
     emit(f"fold %{cur} op=avg")
     emit(f"fc %{cur} out=C")
