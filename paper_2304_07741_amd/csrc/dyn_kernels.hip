@@ -83,24 +83,31 @@ __device__ __forceinline__ Pix pixels(const Params& P, int p) {
     return g;
 }
 
-template <int KH, int KW>
+// One thread: 8 pixels of CPT consecutive channels of one image.  The window weights a (fp32, read by every
+// channel of the image) are loaded once per tap and used for the CPT channels: with one channel per thread
+// the re-reads of a from L2 set the time of these kernels.
+template <int KH, int KW, int CPT>
 __global__ __launch_bounds__(256) void k_fwd(Params P) {
     constexpr int HH = KH / 2, HW = KW / 2, TV = KH * KW;
+    const int CG = (P.C + CPT - 1) / CPT;
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)P.N * P.C * P.upi) return;
-    const int nc = (int)div_magic((uint32_t)idx, P.magicUpi);
-    const int p = ((int)idx - nc * P.upi) * 8;
-    const int n = nc / P.C;
+    if (idx >= (long long)P.N * CG * P.upi) return;
+    const int ng = (int)div_magic((uint32_t)idx, P.magicUpi);
+    const int p = ((int)idx - ng * P.upi) * 8;
+    const int n = ng / CG, c0 = (ng - n * CG) * CPT;
     const int xtotal = P.N * P.C * P.P, atotal = P.N * TV * P.P;
     const rsrc_t rx = make_rsrc(P.x, xtotal * 2), ra = make_rsrc(P.a, atotal * 4), ru = make_rsrc(P.u, xtotal * 2);
     const Pix g = pixels(P, p);
-    float acc[8];
+    float acc[CPT][8];
 #pragma unroll
-    for (int q = 0; q < 8; q++) acc[q] = 0.f;
+    for (int k = 0; k < CPT; k++)
+#pragma unroll
+        for (int q = 0; q < 8; q++) acc[k][q] = 0.f;
 #pragma unroll 1  // one window row at a time in flight: keeps the kernel small enough for several waves per SIMD
     for (int kh = 0; kh < KH; kh++) {
-        float xr[12];
-        load12(rx, nc * P.P + p + (kh - HH) * P.W, xtotal, xr);
+        float xr[CPT][12];
+#pragma unroll
+        for (int k = 0; k < CPT; k++) load12(rx, (n * P.C + min(c0 + k, P.C - 1)) * P.P + p + (kh - HH) * P.W, xtotal, xr[k]);
 #pragma unroll
         for (int kw = 0; kw < KW; kw++) {
             float a[8];
@@ -108,34 +115,44 @@ __global__ __launch_bounds__(256) void k_fwd(Params P) {
 #pragma unroll
             for (int q = 0; q < 8; q++) {
                 const bool v = (unsigned)(g.h[q] + kh - HH) < (unsigned)P.H && (unsigned)(g.w[q] + kw - HW) < (unsigned)P.W;
-                acc[q] += v ? a[q] * xr[q + kw - HW + 2] : 0.f;
+                const float aq = v ? a[q] : 0.f;
+#pragma unroll
+                for (int k = 0; k < CPT; k++) acc[k][q] += aq * xr[k][q + kw - HW + 2];
             }
         }
     }
 #pragma unroll
-    for (int q = 0; q < 8; q++) acc[q] *= P.scale;
-    store8_bf16(ru, P.u, nc * P.P + p, acc, min(8, P.P - p));
+    for (int k = 0; k < CPT; k++) {
+        if (c0 + k >= P.C) break;
+#pragma unroll
+        for (int q = 0; q < 8; q++) acc[k][q] *= P.scale;
+        store8_bf16(ru, P.u, (n * P.C + c0 + k) * P.P + p, acc[k], min(8, P.P - p));
+    }
 }
 
-template <int KH, int KW>
+template <int KH, int KW, int CPT>
 __global__ __launch_bounds__(256) void k_bwd_dx(Params P) {
     constexpr int HH = KH / 2, HW = KW / 2, TV = KH * KW;
+    const int CG = (P.C + CPT - 1) / CPT;
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)P.N * P.C * P.upi) return;
-    const int nc = (int)div_magic((uint32_t)idx, P.magicUpi);
-    const int p = ((int)idx - nc * P.upi) * 8;
-    const int n = nc / P.C;
+    if (idx >= (long long)P.N * CG * P.upi) return;
+    const int ng = (int)div_magic((uint32_t)idx, P.magicUpi);
+    const int p = ((int)idx - ng * P.upi) * 8;
+    const int n = ng / CG, c0 = (ng - n * CG) * CPT;
     const int xtotal = P.N * P.C * P.P, atotal = P.N * TV * P.P;
     const rsrc_t rdu = make_rsrc(P.du, xtotal * 2), ra = make_rsrc(P.a, atotal * 4), rdx = make_rsrc(P.dx, xtotal * 2);
     const Pix g = pixels(P, p);
-    float acc[8];
+    float acc[CPT][8];
 #pragma unroll
-    for (int q = 0; q < 8; q++) acc[q] = 0.f;
+    for (int k = 0; k < CPT; k++)
+#pragma unroll
+        for (int q = 0; q < 8; q++) acc[k][q] = 0.f;
 #pragma unroll 1
     for (int kh = 0; kh < KH; kh++) {
         // pixel p' receives tap t from the output pixel p' - off(t): that pixel must be inside the image
-        float dr[12];
-        load12(rdu, nc * P.P + p - (kh - HH) * P.W, xtotal, dr);
+        float dr[CPT][12];
+#pragma unroll
+        for (int k = 0; k < CPT; k++) load12(rdu, (n * P.C + min(c0 + k, P.C - 1)) * P.P + p - (kh - HH) * P.W, xtotal, dr[k]);
 #pragma unroll
         for (int kw = 0; kw < KW; kw++) {
             float a[8];
@@ -143,13 +160,19 @@ __global__ __launch_bounds__(256) void k_bwd_dx(Params P) {
 #pragma unroll
             for (int q = 0; q < 8; q++) {
                 const bool v = (unsigned)(g.h[q] - (kh - HH)) < (unsigned)P.H && (unsigned)(g.w[q] - (kw - HW)) < (unsigned)P.W;
-                acc[q] += v ? a[q] * dr[q - (kw - HW) + 2] : 0.f;
+                const float aq = v ? a[q] : 0.f;
+#pragma unroll
+                for (int k = 0; k < CPT; k++) acc[k][q] += aq * dr[k][q - (kw - HW) + 2];
             }
         }
     }
 #pragma unroll
-    for (int q = 0; q < 8; q++) acc[q] *= P.scale;
-    store8_bf16(rdx, P.dx, nc * P.P + p, acc, min(8, P.P - p));
+    for (int k = 0; k < CPT; k++) {
+        if (c0 + k >= P.C) break;
+#pragma unroll
+        for (int q = 0; q < 8; q++) acc[k][q] *= P.scale;
+        store8_bf16(rdx, P.dx, (n * P.C + c0 + k) * P.P + p, acc[k], min(8, P.P - p));
+    }
 }
 
 // block = 16 units x 16 channel slices (lane % 16 = slice: channels slice, slice + 16, ...) of one window row
@@ -229,18 +252,29 @@ void dispatch(const Params& P, F33 f33, F55 f55) {
 
 bool supported(int KH, int KW) { return (KH == 3 && KW == 3) || (KH == 5 && KW == 5); }
 
+// channels per thread: 4 where that still leaves a wavefront per SIMD, else 1
+static int channels_per_thread(const Params& P) { return (long long)P.N * ((P.C + 3) / 4) * P.upi >= 65536 ? 4 : 1; }
+
 void forward(const Params& P, hipStream_t s) {
-    const long long total = (long long)P.N * P.C * P.upi;
+    const int cpt = channels_per_thread(P);
+    const long long total = (long long)P.N * ((P.C + cpt - 1) / cpt) * P.upi;
     if (total == 0) return;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-    dispatch(P, [&] { CANVAS_LAUNCH((k_fwd<3, 3>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_fwd<5, 5>), grid, block, 0, s, P); });
+    if (cpt == 4)
+        dispatch(P, [&] { CANVAS_LAUNCH((k_fwd<3, 3, 4>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_fwd<5, 5, 4>), grid, block, 0, s, P); });
+    else
+        dispatch(P, [&] { CANVAS_LAUNCH((k_fwd<3, 3, 1>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_fwd<5, 5, 1>), grid, block, 0, s, P); });
 }
 
 void backward_dx(const Params& P, hipStream_t s) {
-    const long long total = (long long)P.N * P.C * P.upi;
+    const int cpt = channels_per_thread(P);
+    const long long total = (long long)P.N * ((P.C + cpt - 1) / cpt) * P.upi;
     if (total == 0) return;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-    dispatch(P, [&] { CANVAS_LAUNCH((k_bwd_dx<3, 3>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_bwd_dx<5, 5>), grid, block, 0, s, P); });
+    if (cpt == 4)
+        dispatch(P, [&] { CANVAS_LAUNCH((k_bwd_dx<3, 3, 4>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_bwd_dx<5, 5, 4>), grid, block, 0, s, P); });
+    else
+        dispatch(P, [&] { CANVAS_LAUNCH((k_bwd_dx<3, 3, 1>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_bwd_dx<5, 5, 1>), grid, block, 0, s, P); });
 }
 
 void backward_da(const Params& P, hipStream_t s) {

@@ -264,6 +264,8 @@ __global__ void k_binary_bwd_lhs(const float* __restrict__ lhs, const float* __r
     glhs[i] = acc ? glhs[i] + s : s;
 }
 
+constexpr int kSoftmaxRegs = 32;
+
 // One thread per (n, outer, p); the axis is strided by `stride`, `len` long.
 __global__ void k_softmax_fwd(const float* __restrict__ in, float* __restrict__ out, int64_t total, int C, int T, int P,
                               int axis_c) {
@@ -289,6 +291,25 @@ __global__ void k_softmax_fwd(const float* __restrict__ in, float* __restrict__ 
         int64_t n = r / outer;
         base = ((n * C + c) * T) * P + p;
         stride = P;
+    }
+    if (len <= kSoftmaxRegs) {  // short axis (the taps of a window): one read of the axis, kept in registers
+        float v[kSoftmaxRegs];
+#pragma unroll
+        for (int k = 0; k < kSoftmaxRegs; k++) v[k] = k < len ? in[base + k * stride] : -INFINITY;
+        float m = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < kSoftmaxRegs; k++) m = fmaxf(m, v[k]);
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < kSoftmaxRegs; k++) {
+            v[k] = expf(v[k] - m);
+            s += k < len ? v[k] : 0.f;
+        }
+        const float inv = 1.f / s;
+#pragma unroll
+        for (int k = 0; k < kSoftmaxRegs; k++)
+            if (k < len) out[base + k * stride] = v[k] * inv;
+        return;
     }
     float m = -INFINITY;
     for (int k = 0; k < len; k++) m = fmaxf(m, in[base + k * stride]);
@@ -322,6 +343,24 @@ __global__ void k_softmax_bwd(const float* __restrict__ y, const float* __restri
         int64_t n = r / C;
         base = ((n * C + c) * T) * P + p;
         stride = P;
+    }
+    if (len <= kSoftmaxRegs) {
+        float yv[kSoftmaxRegs], gv[kSoftmaxRegs];
+#pragma unroll
+        for (int k = 0; k < kSoftmaxRegs; k++) {
+            yv[k] = k < len ? y[base + k * stride] : 0.f;
+            gv[k] = k < len ? gout[base + k * stride] : 0.f;
+        }
+        float dot = 0.f;
+#pragma unroll
+        for (int k = 0; k < kSoftmaxRegs; k++) dot = fmaf(gv[k], yv[k], dot);
+#pragma unroll
+        for (int k = 0; k < kSoftmaxRegs; k++)
+            if (k < len) {
+                const float g = yv[k] * (gv[k] - dot);
+                gin[base + k * stride] = acc ? gin[base + k * stride] + g : g;
+            }
+        return;
     }
     float dot = 0.f;
     for (int k = 0; k < len; k++) dot = fmaf(gout[base + k * stride], y[base + k * stride], dot);
