@@ -259,7 +259,25 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const int dsz = DST_F32 ? 4 : 2;
     const rsrc_t rd = make_rsrc(P.dst, P.N * P.G * P.Og * P.P * dsz);
 #pragma unroll
-    for (int mo = 0; mo < MO; mo++)
+    for (int mo = 0; mo < MO; mo++) {
+        // What the four rows of this step are added to is read before any of them is stored: loads that follow
+        // a store to the same tensor are not moved ahead of it, and would cost a memory round trip per row.
+        u32x4 pre[4][2];
+        const rsrc_t rad = make_rsrc(P.addend, P.N * P.G * P.Og * P.P * 2);
+        if ((DST_F32 && P.acc) || (!DST_F32 && P.addend)) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int o = obase + mo * 16 + 4 * r + j;
+                const int e = ((n * P.G + g) * P.Og + o) * P.P + p;
+                const bool ok = o < P.Og && nvalid == 8;
+                if (DST_F32) {
+                    pre[j][0] = bload16(rd, ok ? e * 4 : kOob);
+                    pre[j][1] = bload16(rd, ok ? e * 4 + 16 : kOob);
+                } else {
+                    pre[j][0] = bload16(rad, ok ? e * 2 : kOob);
+                }
+            }
+        }
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             const int o = obase + mo * 16 + 4 * r + j;
@@ -272,8 +290,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 if (DST_F32) {
                     u32x4 lo, hi;
                     if (P.acc) {
-                        lo = bload16(rd, e * 4);
-                        hi = bload16(rd, e * 4 + 16);
+                        lo = pre[j][0];
+                        hi = pre[j][1];
 #pragma unroll
                         for (int k = 0; k < 4; k++) {
                             v[k] += __uint_as_float(lo[k]);
@@ -289,7 +307,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                     bstore16(rd, e * 4 + 16, hi);
                 } else {
                     if (P.addend) {  // bf16 tensor of the output's shape added before rounding
-                        const u32x4 ad = bload16(make_rsrc(P.addend, P.N * P.G * P.Og * P.P * 2), e * 2);
+                        const u32x4 ad = pre[j][0];
 #pragma unroll
                         for (int k = 0; k < 4; k++) {
                             v[2 * k] += lo_f32(ad[k]);
@@ -316,6 +334,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 }
             }
         }
+    }
 }
 
 // ----------------------------------------------------------------------------------- weight gradient

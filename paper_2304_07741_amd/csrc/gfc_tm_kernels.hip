@@ -258,8 +258,32 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const int outs_img = P.G * P.Og;
     const int dst_elems = P.N * outs_img * P.P;
     const rsrc_t rd = make_rsrc(P.dst, dst_elems * (DST_F32 ? 4 : 2));
+    // What the rows are added to is read, four rows at a time, before any of the four is stored: loads that
+    // follow a store to the same tensor are not moved ahead of it, and would cost a memory round trip per row.
+    constexpr int RB = TF < 4 ? TF : 4;
+    const rsrc_t rad = make_rsrc(P.addend, dst_elems * 2);
+    const bool adds = (DST_F32 && P.acc) || (!DST_F32 && P.addend);
 #pragma unroll
-    for (int i = 0; i < TF; i++) {
+    for (int i0 = 0; i0 < TF; i0 += RB) {
+    u32x4 pre[RB][2];
+    if (adds) {
+#pragma unroll
+        for (int b = 0; b < RB; b++) {
+            const int t = t0 + i0 + b;
+            const int o = ot * 16 * MO + (t >> 2) * 16 + 4 * r + (t & 3);
+            const int e = (n * outs_img + gmi * P.gm * P.Og + o) * P.P + p;
+            const bool ok = o < Om && nvalid == 8;
+            if (DST_F32) {
+                pre[b][0] = bload16(rd, ok ? e * 4 : kOob);
+                pre[b][1] = bload16(rd, ok ? e * 4 + 16 : kOob);
+            } else {
+                pre[b][0] = bload16(rad, ok ? e * 2 : kOob);
+            }
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < RB; b++) {
+        const int i = i0 + b;
         const int t = t0 + i;
         const int o = ot * 16 * MO + (t >> 2) * 16 + 4 * r + (t & 3);
         if (o >= Om) continue;
@@ -271,8 +295,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
             if (DST_F32) {
                 u32x4 lo, hi;
                 if (P.acc) {
-                    lo = bload16(rd, e * 4);
-                    hi = bload16(rd, e * 4 + 16);
+                    lo = pre[b][0];
+                    hi = pre[b][1];
 #pragma unroll
                     for (int k = 0; k < 4; k++) {
                         v[k] += __uint_as_float(lo[k]);
@@ -288,7 +312,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 bstore16(rd, e * 4 + 16, hi);
             } else {
                 if (P.addend) {  // bf16 tensor of the output's shape added before rounding
-                    const u32x4 ad = bload16(make_rsrc(P.addend, dst_elems * 2), e * 2);
+                    const u32x4 ad = pre[b][0];
 #pragma unroll
                     for (int k = 0; k < 4; k++) {
                         v[2 * k] += lo_f32(ad[k]);
@@ -314,6 +338,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 }
             }
         }
+    }
     }
 }
 
