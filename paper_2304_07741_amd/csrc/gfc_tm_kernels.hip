@@ -128,24 +128,19 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
             const bool ok = valid && (!padrows || rc * 16 + 4 * r + j < Rm);
             const int bo = ok ? e * 2 : kOob;
             u32x4 m = bload16(rs, bo);
-            uint32_t h0 = 0, h5 = 0;
+            // the two pixels on either side of the unit are the neighbouring lanes' registers (units are
+            // consecutive pixels), fetched by a lane shift when the group is consumed; only the first and the
+            // last lane of a row of 16 have no such neighbour and load them, both in one instruction
+            uint32_t edge = 0;
             if constexpr (HALO) {
-                h0 = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? bo - 4 : kOob, 0, 0);
-                h5 = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? bo + 16 : kOob, 0, 0);
+                const int eo = ok ? (s == 0 ? bo - 4 : (s == 15 ? bo + 16 : kOob)) : kOob;
+                edge = __builtin_amdgcn_raw_buffer_load_b32(rs, eo, 0, 0);
+                if (near_ends) reload_pair_if_partial(edge, rs, eo, src_elems * 2);
             }
-            if (near_ends) {  // only lanes whose access is partly outside re-read, element by element
-                reload_if_partial(m, rs, bo, src_elems * 2);
-                if constexpr (HALO) {
-                    reload_pair_if_partial(h0, rs, ok ? bo - 4 : kOob, src_elems * 2);
-                    reload_pair_if_partial(h5, rs, ok ? bo + 16 : kOob, src_elems * 2);
-                }
-            }
+            if (near_ends) reload_if_partial(m, rs, bo, src_elems * 2);  // only lanes whose access is partly outside re-read
 #pragma unroll
             for (int k = 0; k < 4; k++) b.d[j][k + E0 / 2] = m[k];
-            if constexpr (HALO) {
-                b.d[j][0] = h0;
-                b.d[j][5] = h5;
-            }
+            if constexpr (HALO) b.d[j][0] = edge;
         }
 #pragma unroll
         for (int kw = 0; kw < KW; kw++)
@@ -157,6 +152,15 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     };
 
     auto consume = [&](int kh, Group<MO, KW>& b) {
+        if constexpr (HALO) {
+            // row_shr:1 / row_shl:1 within the 16 lanes of a row; a lane without a source keeps the loaded edge value
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const uint32_t edge = b.d[j][0];
+                b.d[j][0] = (uint32_t)__builtin_amdgcn_update_dpp((int)edge, (int)b.d[j][4], 0x111, 0xf, 0xf, false);
+                b.d[j][5] = (uint32_t)__builtin_amdgcn_update_dpp((int)edge, (int)b.d[j][1], 0x101, 0xf, 0xf, false);
+            }
+        }
         if (needrow[kh]) {
 #pragma unroll
             for (int j = 0; j < 4; j++)
