@@ -460,21 +460,30 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
             const bool ok = valid && xok;
             const int bo = ok ? (nx + ex + (kh - HH) * P.W) * 2 : kOob;
             u32x4 m = bload16(rs, bo);
-            uint32_t h0 = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? bo - 4 : kOob, 0, 0);
-            uint32_t h5 = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? bo + 16 : kOob, 0, 0);
+            // the two pixels on either side of the lane's 8 are its neighbours' (lanes 16 below / above hold the
+            // adjacent pixels of the same row) and are fetched from them when the step is consumed; the first and
+            // the last quarter of the wavefront have no such neighbour and load them, both in one instruction
+            const int eo = ok ? (r == 0 ? bo - 4 : (r == 3 ? bo + 16 : kOob)) : kOob;
+            uint32_t edge = __builtin_amdgcn_raw_buffer_load_b32(rs, eo, 0, 0);
             if (near_ends) {  // only lanes whose access is partly outside re-read, element by element
                 reload_if_partial(m, rs, bo, src_elems * 2);
-                reload_pair_if_partial(h0, rs, ok ? bo - 4 : kOob, src_elems * 2);
-                reload_pair_if_partial(h5, rs, ok ? bo + 16 : kOob, src_elems * 2);
+                reload_pair_if_partial(edge, rs, eo, src_elems * 2);
             }
 #pragma unroll
             for (int k = 0; k < 4; k++) st.x[kh][k + 1] = m[k];
-            st.x[kh][0] = h0;
-            st.x[kh][5] = h5;
+            st.x[kh][0] = edge;
         }
     };
 
     auto consume = [&](Step<MO, KH, KW>& st) {
+#pragma unroll
+        for (int kh = 0; kh < KH; kh++) {
+            const uint32_t edge = st.x[kh][0];
+            const uint32_t below = (uint32_t)__builtin_amdgcn_ds_bpermute(((lane + 48) & 63) * 4, (int)st.x[kh][4]);  // lane - 16
+            const uint32_t above = (uint32_t)__builtin_amdgcn_ds_bpermute(((lane + 16) & 63) * 4, (int)st.x[kh][1]);  // lane + 16
+            st.x[kh][0] = r == 0 ? edge : below;
+            st.x[kh][5] = r == 3 ? edge : above;
+        }
 #pragma unroll
         for (int kh = 0; kh < KH; kh++)
             if (needrow[kh]) {
