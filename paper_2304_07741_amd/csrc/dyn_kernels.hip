@@ -16,13 +16,26 @@ using namespace canvas::tile;
 
 __device__ __forceinline__ uint32_t div_magic(uint32_t x, uint32_t magic) { return magic ? __umulhi(x, magic) : x; }
 
-// elements e-2 .. e+9 of a bf16 buffer of `total` elements, as floats (0 where outside the buffer)
+// elements e-2 .. e+9 of a bf16 buffer of `total` elements, as floats (0 where outside the buffer).  The two
+// elements on either side of the lane's own 8 are loaded as two more 4-byte accesses (NB = 0), or, where the
+// lanes 16 below / above hold the adjacent units (NB = 16), taken from their registers, and only the first and
+// last quarter of the wavefront load them.  Where a neighbour holds another plane the pixels concerned lie
+// outside the image and are never selected by the caller.
+template <int NB>
 __device__ __forceinline__ void load12(rsrc_t r, int e, int total, float (&f)[12]) {
     uint32_t d[6];
-    if (e - 2 >= 0 && e + 10 <= total) {
+    const int lane = threadIdx.x & 63;
+    const bool first = lane < 16, last = lane >= 48;
+    const bool inside = e - 2 >= 0 && e + 10 <= total;
+    uint32_t edge = 0;
+    if (inside) {
         const u32x4 m = bload16(r, e * 2);
-        d[0] = __builtin_amdgcn_raw_buffer_load_b32(r, (e - 2) * 2, 0, 0);
-        d[5] = __builtin_amdgcn_raw_buffer_load_b32(r, (e + 8) * 2, 0, 0);
+        if constexpr (NB == 0) {
+            d[0] = __builtin_amdgcn_raw_buffer_load_b32(r, (e - 2) * 2, 0, 0);
+            d[5] = __builtin_amdgcn_raw_buffer_load_b32(r, (e + 8) * 2, 0, 0);
+        } else {
+            edge = __builtin_amdgcn_raw_buffer_load_b32(r, first ? (e - 2) * 2 : (last ? (e + 8) * 2 : kOob), 0, 0);
+        }
 #pragma unroll
         for (int k = 0; k < 4; k++) d[k + 1] = m[k];
     } else {  // at an end of the tensor: a multi-byte access that straddles the end would be dropped as a whole
@@ -32,6 +45,17 @@ __device__ __forceinline__ void load12(rsrc_t r, int e, int total, float (&f)[12
             const uint32_t lo = (unsigned)i < (unsigned)total ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, i * 2, 0, 0) : 0u;
             const uint32_t hi = (unsigned)(i + 1) < (unsigned)total ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, (i + 1) * 2, 0, 0) : 0u;
             d[k] = (lo & 0xffffu) | (hi << 16);
+        }
+    }
+    if constexpr (NB == 16) {
+        // the last dword of the lane 16 below, the first dword of the lane 16 above
+        uint32_t below = (uint32_t)__builtin_amdgcn_ds_bpermute(((lane + 48) & 63) * 4, (int)d[4]);
+        uint32_t above = (uint32_t)__builtin_amdgcn_ds_bpermute(((lane + 16) & 63) * 4, (int)d[1]);
+        below = first ? edge : below;
+        above = last ? edge : above;
+        if (inside) {
+            d[0] = below;
+            d[5] = above;
         }
     }
 #pragma unroll
@@ -107,7 +131,7 @@ __global__ __launch_bounds__(256) void k_fwd(Params P) {
     for (int kh = 0; kh < KH; kh++) {
         float xr[CPT][12];
 #pragma unroll
-        for (int k = 0; k < CPT; k++) load12(rx, (n * P.C + min(c0 + k, P.C - 1)) * P.P + p + (kh - HH) * P.W, xtotal, xr[k]);
+        for (int k = 0; k < CPT; k++) load12<0>(rx, (n * P.C + min(c0 + k, P.C - 1)) * P.P + p + (kh - HH) * P.W, xtotal, xr[k]);
 #pragma unroll
         for (int kw = 0; kw < KW; kw++) {
             float a[8];
@@ -152,7 +176,7 @@ __global__ __launch_bounds__(256) void k_bwd_dx(Params P) {
         // pixel p' receives tap t from the output pixel p' - off(t): that pixel must be inside the image
         float dr[CPT][12];
 #pragma unroll
-        for (int k = 0; k < CPT; k++) load12(rdu, (n * P.C + min(c0 + k, P.C - 1)) * P.P + p - (kh - HH) * P.W, xtotal, dr[k]);
+        for (int k = 0; k < CPT; k++) load12<0>(rdu, (n * P.C + min(c0 + k, P.C - 1)) * P.P + p - (kh - HH) * P.W, xtotal, dr[k]);
 #pragma unroll
         for (int kw = 0; kw < KW; kw++) {
             float a[8];
@@ -198,8 +222,8 @@ __global__ __launch_bounds__(256) void k_bwd_da(Params P) {
         for (int c = cs; c < P.C; c += 16) {
             const int plane = (n * P.C + c) * P.P;
             float d[12], xr[12];
-            load12(rdu, plane + p, xtotal, d);
-            load12(rx, plane + p + (kh - HH) * P.W, xtotal, xr);
+            load12<16>(rdu, plane + p, xtotal, d);
+            load12<16>(rx, plane + p + (kh - HH) * P.W, xtotal, xr);
 #pragma unroll
             for (int kw = 0; kw < KW; kw++)
 #pragma unroll
