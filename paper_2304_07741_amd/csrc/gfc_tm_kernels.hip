@@ -70,6 +70,9 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const rsrc_t rw = make_rsrc(P.wp, P.Gm * P.Omp * TV * P.Rp * 2);
     const int grow0 = gmi * P.gm * P.R;                      // first row of the merged group within an image
     const int ebase = (n * rows_img + grow0 + 4 * r) * P.P + p;  // element (row 4r, pixel p) of this lane
+    // the same of the first and the last lane of this lane's row of 16 (their units may lie in other images)
+    const int eb_first = __builtin_amdgcn_ds_bpermute((lane & 48) * 4, ebase);
+    const int eb_last = __builtin_amdgcn_ds_bpermute(((lane & 48) + 15) * 4, ebase);
     const int wbase = ((gmi * P.Omp + ot * 16 * MO + s) * TV * P.Rp + 4 * r) * 2;
     const int nrc = P.Rp >> 4;
     const bool padrows = (Rm & 15) != 0;
@@ -128,19 +131,23 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
             const bool ok = valid && (!padrows || rc * 16 + 4 * r + j < Rm);
             const int bo = ok ? e * 2 : kOob;
             u32x4 m = bload16(rs, bo);
-            // the two pixels on either side of the unit are the neighbouring lanes' registers (units are
-            // consecutive pixels), fetched by a lane shift when the group is consumed; only the first and the
-            // last lane of a row of 16 have no such neighbour and load them, both in one instruction
-            uint32_t edge = 0;
-            if constexpr (HALO) {
-                const int eo = ok ? (s == 0 ? bo - 4 : (s == 15 ? bo + 16 : kOob)) : kOob;
-                edge = __builtin_amdgcn_raw_buffer_load_b32(rs, eo, 0, 0);
-                if (near_ends) reload_pair_if_partial(edge, rs, eo, src_elems * 2);
-            }
             if (near_ends) reload_if_partial(m, rs, bo, src_elems * 2);  // only lanes whose access is partly outside re-read
 #pragma unroll
             for (int k = 0; k < 4; k++) b.d[j][k + E0 / 2] = m[k];
-            if constexpr (HALO) b.d[j][0] = edge;
+        }
+        if constexpr (HALO) {
+            // The two pixels on either side of a unit are the neighbouring lanes' registers (units are consecutive
+            // pixels) and are fetched by a lane shift when the group is consumed; only the first and the last
+            // lane of a row of 16 have no such neighbour.  Their 2 x 4 values (left / right edge of the rows
+            // 4r .. 4r+3) are loaded by ONE instruction: lane s = j loads the left edge of row j, lane s = 8 + j
+            // the right edge, and the group's consumer hands them to lanes 0 and 15.
+            const int jl = s & 3;
+            const bool okl = valid && (!padrows || rc * 16 + 4 * r + jl < Rm);
+            const int el = (s < 4 ? eb_first - E0 : eb_last + 8) + eoff + jl * P.P;
+            const int eo = okl && (s < 4 || (s >= 8 && s < 12)) ? el * 2 : kOob;
+            uint32_t edge = __builtin_amdgcn_raw_buffer_load_b32(rs, eo, 0, 0);
+            if (near_ends) reload_pair_if_partial(edge, rs, eo, src_elems * 2);
+            b.d[0][0] = edge;
         }
 #pragma unroll
         for (int kw = 0; kw < KW; kw++)
@@ -154,9 +161,11 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     auto consume = [&](int kh, Group<MO, KW>& b) {
         if constexpr (HALO) {
             // row_shr:1 / row_shl:1 within the 16 lanes of a row; a lane without a source keeps the loaded edge value
+            const uint32_t loaded = b.d[0][0];
 #pragma unroll
             for (int j = 0; j < 4; j++) {
-                const uint32_t edge = b.d[j][0];
+                // lane 0 of the row takes the left edge of row j from lane j, lane 15 the right edge from lane 8 + j
+                const uint32_t edge = (uint32_t)__builtin_amdgcn_ds_bpermute(((lane & 48) + (s == 15 ? 8 : 0) + j) * 4, (int)loaded);
                 b.d[j][0] = (uint32_t)__builtin_amdgcn_update_dpp((int)edge, (int)b.d[j][4], 0x111, 0xf, 0xf, false);
                 b.d[j][5] = (uint32_t)__builtin_amdgcn_update_dpp((int)edge, (int)b.d[j][1], 0x101, 0xf, 0xf, false);
             }
