@@ -592,40 +592,50 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
 }
 
 // dw[g][o][row][tap] = sum over the workgroup partials of dwp[g / gm][(g % gm) * Og + o][tap][(g % gm) * R + row],
-// in a fixed order: 8 segments of partials per element, combined through LDS.
+// in a fixed order: SEGS segments of partials per element, combined through LDS.  Threads are numbered in the
+// packed order, so the elements of a segment read whole 128-byte lines of each partial (the element order of dw
+// has the tap innermost, which would put every lane on a line of its own); the padding of the packed
+// layout is skipped, and the small result is written scattered.  SEGS: 8 for many partials, 2 for few.
+template <int SEGS>
 __global__ __launch_bounds__(256) void k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ dw, int slices, int G, int R, int Og,
-                                                      int TV, int gm, int Omp, int Rp, long long packed) {
-    __shared__ float red[8][32];
-    const int el = threadIdx.x & 31, seg = threadIdx.x >> 5;
-    const long long e = (long long)blockIdx.x * 32 + el;
-    const long long elems = (long long)G * Og * R * TV;
+                                                      int TV, int gm, int Omp, int Rp, unsigned packed) {
+    constexpr int EL = 256 / SEGS;
+    __shared__ float red[SEGS][EL];
+    const int el = threadIdx.x % EL, seg = threadIdx.x / EL;
+    const unsigned idx = blockIdx.x * EL + el;
+    long long e = -1;  // element of dw, if this packed position holds one
+    if (idx < packed) {
+        const unsigned rp = idx % (unsigned)Rp;
+        unsigned t = idx / (unsigned)Rp;
+        const unsigned tap = t % (unsigned)TV;
+        t /= (unsigned)TV;
+        const int op = (int)(t % (unsigned)Omp), gmi = (int)(t / (unsigned)Omp);
+        const int sub = op / Og, o = op - sub * Og;
+        const int subr = (int)rp / R, row = (int)rp - subr * R;
+        const int g = gmi * gm + sub;
+        if (sub < gm && subr == sub && g < G) e = (((long long)g * Og + o) * R + row) * TV + tap;
+    }
     float sum = 0.f;
-    if (e < elems) {
-        const int tap = (int)(e % TV);
-        long long t = e / TV;
-        const int row = (int)(t % R);
-        t /= R;
-        const int o = (int)(t % Og), g = (int)(t / Og);
-        const int gmi = g / gm, sub = g - gmi * gm;
-        const long long idx = ((long long)(gmi * Omp + sub * Og + o) * TV + tap) * Rp + sub * R + row;
-        const int per = (slices + 7) / 8;
+    if (e >= 0) {
+        const int per = (slices + SEGS - 1) / SEGS;
         const int end = min(slices, (seg + 1) * per);
+        const float* src = partial + idx;
         int k = seg * per;
         for (; k + 4 <= end; k += 4) {  // four independent loads in flight, summed in slice order
             float v[4];
 #pragma unroll
-            for (int i = 0; i < 4; i++) v[i] = partial[(long long)(k + i) * packed + idx];
+            for (int i = 0; i < 4; i++) v[i] = src[(long long)(k + i) * packed];
 #pragma unroll
             for (int i = 0; i < 4; i++) sum += v[i];
         }
-        for (; k < end; k++) sum += partial[(long long)k * packed + idx];
+        for (; k < end; k++) sum += src[(long long)k * packed];
     }
     red[seg][el] = sum;
     __syncthreads();
-    if (seg == 0 && e < elems) {
+    if (seg == 0 && e >= 0) {
         float t = red[0][el];
 #pragma unroll
-        for (int i = 1; i < 8; i++) t += red[i][el];
+        for (int i = 1; i < SEGS; i++) t += red[i][el];
         dw[e] = t;
     }
 }
@@ -709,8 +719,10 @@ Params shape(int N, int G, int R, int KH, int KW, int Og, int H, int W) {
     const int64_t waves = (((int64_t)N * Q.upi + 15) / 16) * Q.Gm * Q.otiles;
     const int nrc = Q.Rp / 16;
     Q.ksplit = 1;
+    // (4 only while all wavefronts are resident at once, two per SIMD: a second round of wavefronts costs
+    // more than the longer K loop of a split by 2)
     if (waves < 2048 && nrc >= 2) Q.ksplit = 2;
-    if (waves < 1024 && nrc >= 4) Q.ksplit = 4;
+    if (waves * 4 <= 2048 && nrc >= 4) Q.ksplit = 4;
     Q.Omp = Q.otiles * 16 * Q.mo;
     auto magic = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); };
     Q.magicW = magic((uint32_t)W);
@@ -759,9 +771,15 @@ void wgrad_partial(const Params& P, hipStream_t s) {
 
 void wgrad_reduce(const Params& P, float* dw, hipStream_t s) {
     const long long elems = (long long)P.G * P.Og * P.R * P.TV;
-    if (elems > 0)
-        CANVAS_LAUNCH(k_wgrad_reduce, dim3((unsigned)((elems + 31) / 32)), dim3(256), 0, s, (const float*)P.partial, dw, wgrad_slices(P), P.G, P.R,
-                      P.Og, P.TV, P.gm, P.Omp, P.Rp, (long long)packed_elems(P));
+    if (elems <= 0) return;
+    const unsigned packed = (unsigned)packed_elems(P);
+    const int slices = wgrad_slices(P);
+    if (slices >= 32)
+        CANVAS_LAUNCH(k_wgrad_reduce<8>, dim3((packed + 31) / 32), dim3(256), 0, s, (const float*)P.partial, dw, slices, P.G, P.R, P.Og, P.TV, P.gm,
+                      P.Omp, P.Rp, packed);
+    else
+        CANVAS_LAUNCH(k_wgrad_reduce<2>, dim3((packed + 127) / 128), dim3(256), 0, s, (const float*)P.partial, dw, slices, P.G, P.R, P.Og, P.TV, P.gm,
+                      P.Omp, P.Rp, packed);
 }
 
 void forward(const Params& P, hipStream_t s) {
