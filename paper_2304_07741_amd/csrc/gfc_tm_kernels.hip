@@ -719,9 +719,9 @@ Params shape(int N, int G, int R, int KH, int KW, int Og, int H, int W) {
     const int64_t waves = (((int64_t)N * Q.upi + 15) / 16) * Q.Gm * Q.otiles;
     const int nrc = Q.Rp / 16;
     Q.ksplit = 1;
-    // (4 only while all wavefronts are resident at once, two per SIMD: a second round of wavefronts costs
-    // more than the longer K loop of a split by 2)
-    if (waves < 2048 && nrc >= 2) Q.ksplit = 2;
+    // (by 4, and by 2 for windows, only while all wavefronts are resident at once, two per SIMD: a second
+    // round of wavefronts costs more than the longer K loop)
+    if ((KH > 1 ? waves * 2 <= 2048 : waves < 2048) && nrc >= 2) Q.ksplit = 2;
     if (waves * 4 <= 2048 && nrc >= 4) Q.ksplit = 4;
     Q.Omp = Q.otiles * 16 * Q.mo;
     auto magic = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); };
