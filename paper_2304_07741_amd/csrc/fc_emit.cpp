@@ -89,11 +89,17 @@ void emit_wgrad(Lowering& low, const Dag& dag, const TakeFn& take, const std::st
                             Q.partial = (float*)(a.ws + opt);
                             gfctm::wgrad_partial(Q, a.stream);
                         }});
-        list.push_back({name + "_reduce", 4.0 * ts * pk + 4.0 * nw, 0, [=](const RunArgs& a) {
-                            gfctm::Params Q = T;
-                            Q.partial = (float*)(a.ws + opt);
-                            gfctm::wgrad_reduce(Q, (float*)a.dw[widx], a.stream);
-                        }});
+        ReduceJob rj;
+        rj.job.slices = ts;
+        rj.job.kind = 1;
+        rj.job.count = (unsigned)pk;
+        rj.job.G = T.G; rj.job.R = T.R; rj.job.Og = T.Og; rj.job.TV = T.TV;
+        rj.job.gm = T.gm; rj.job.Omp = T.Omp; rj.job.Rp = T.Rp;
+        wreduce::plan(rj.job);
+        rj.widx = widx;
+        rj.off = opt;
+        rj.bytes = 4.0 * ts * pk + 4.0 * nw;
+        low.rjobs.push_back(rj);
         return;
     }
     gfc::Params W = gfc::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
@@ -109,9 +115,15 @@ void emit_wgrad(Lowering& low, const Dag& dag, const TakeFn& take, const std::st
                         Q.partial = (float*)(a.ws + op);
                         gfc::wgrad_partial(Q, a.stream);
                     }});
-    list.push_back({name + "_reduce", 4.0 * (slices + 1) * nw, 0, [=](const RunArgs& a) {
-                        gfc::wgrad_reduce((const float*)(a.ws + op), (float*)a.dw[widx], slices, nw, a.stream);
-                    }});
+    ReduceJob rj;
+    rj.job.slices = slices;
+    rj.job.kind = 0;
+    rj.job.count = (unsigned)nw;
+    wreduce::plan(rj.job);
+    rj.widx = widx;
+    rj.off = op;
+    rj.bytes = 4.0 * (slices + 1) * nw;
+    low.rjobs.push_back(rj);
 }
 
 }  // namespace canvas

@@ -26,7 +26,8 @@ struct FcOperand {
 void emit_fc(Lowering& low, bool backward, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
              bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32 = false);
 
-// dw[widx] = sum over (image, pixel) of dy (x) rows of src (through the window kh x kw); partials + fixed-order reduce.
+// dw[widx] = sum over (image, pixel) of dy (x) rows of src (through the window kh x kw): the kernel that writes
+// one partial per workgroup goes to low.bwd, the fixed-order sum of the partials is registered in low.rjobs.
 void emit_wgrad(Lowering& low, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
                 int widx, FcOperand src, FcOperand dy, double operand_bytes, double flops);
 

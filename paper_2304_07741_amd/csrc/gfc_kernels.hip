@@ -472,35 +472,6 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
             }
 }
 
-// dw[e] = sum over slices, in a fixed order: 8 segments of slices per element, combined through LDS.
-__global__ __launch_bounds__(256) void k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ dw, int slices, long long elems) {
-    __shared__ float red[8][32];
-    const int el = threadIdx.x & 31, seg = threadIdx.x >> 5;
-    const long long e = (long long)blockIdx.x * 32 + el;
-    const int per = (slices + 7) / 8;
-    float s = 0.f;
-    if (e < elems) {
-        const int end = min(slices, (seg + 1) * per);
-        int k = seg * per;
-        for (; k + 4 <= end; k += 4) {  // four independent loads in flight, summed in slice order
-            float v[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) v[i] = partial[(long long)(k + i) * elems + e];
-#pragma unroll
-            for (int i = 0; i < 4; i++) s += v[i];
-        }
-        for (; k < end; k++) s += partial[(long long)k * elems + e];
-    }
-    red[seg][el] = s;
-    __syncthreads();
-    if (seg == 0 && e < elems) {
-        float t = red[0][el];
-#pragma unroll
-        for (int i = 1; i < 8; i++) t += red[i][el];
-        dw[e] = t;
-    }
-}
-
 __global__ void k_transpose_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt, int G, int Og, int R, int TV) {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     const long long total = (long long)G * R * Og * TV;
@@ -616,9 +587,6 @@ void wgrad_partial(const Params& P, hipStream_t s) {
 
 int wgrad_partials(const Params& P) { return (P.slices + kWaves - 1) / kWaves; }
 
-void wgrad_reduce(const float* partial, float* dw, int slices, int64_t elems, hipStream_t s) {
-    if (elems > 0) CANVAS_LAUNCH(k_wgrad_reduce, dim3((unsigned)((elems + 31) / 32)), dim3(256), 0, s, partial, dw, slices, (long long)elems);
-}
 
 void transpose_weights(const uint16_t* w, uint16_t* wt, int G, int Og, int R, int TV, hipStream_t s) {
     const long long total = (long long)G * R * Og * TV;

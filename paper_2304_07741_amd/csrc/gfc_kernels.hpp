@@ -34,10 +34,9 @@ inline uint32_t magic_u32(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint6
 void forward(const Params& P, hipStream_t s);
 // partial[wg][g][o][k] = sum over the (n, p) of the workgroup's four slices of dy[n, g*Og+o, p] * src_row(n, g, k)[p + off(k)]
 void wgrad_partial(const Params& P, hipStream_t s);
-// number of partials wgrad_partial writes (one per workgroup of four slices)
+// number of partials wgrad_partial writes (one per workgroup of four slices); dw[e] = sum_i partial[i][e] is a
+// job of wreduce_kernels.hpp
 int wgrad_partials(const Params& P);
-// dw[e] = sum_i partial[i][e], i < count
-void wgrad_reduce(const float* partial, float* dw, int count, int64_t elems, hipStream_t s);
 // wt[g][row][o*TV + tv] = w[g][o][row*TV + (TV-1-tv)]: the weights of the data-gradient contraction
 void transpose_weights(const uint16_t* w, uint16_t* wt, int G, int Og, int R, int TV, hipStream_t s);
 int choose_mo(int Og);

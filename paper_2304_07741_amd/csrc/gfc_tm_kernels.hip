@@ -592,55 +592,6 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
     }
 }
 
-// dw[g][o][row][tap] = sum over the workgroup partials of dwp[g / gm][(g % gm) * Og + o][tap][(g % gm) * R + row],
-// in a fixed order: SEGS segments of partials per element, combined through LDS.  Threads are numbered in the
-// packed order, so the elements of a segment read whole 128-byte lines of each partial (the element order of dw
-// has the tap innermost, which would put every lane on a line of its own); the padding of the packed
-// layout is skipped, and the small result is written scattered.  SEGS: 8 for many partials, 2 for few.
-template <int SEGS>
-__global__ __launch_bounds__(256) void k_wgrad_reduce(const float* __restrict__ partial, float* __restrict__ dw, int slices, int G, int R, int Og,
-                                                      int TV, int gm, int Omp, int Rp, unsigned packed) {
-    constexpr int EL = 256 / SEGS;
-    __shared__ float red[SEGS][EL];
-    const int el = threadIdx.x % EL, seg = threadIdx.x / EL;
-    const unsigned idx = blockIdx.x * EL + el;
-    long long e = -1;  // element of dw, if this packed position holds one
-    if (idx < packed) {
-        const unsigned rp = idx % (unsigned)Rp;
-        unsigned t = idx / (unsigned)Rp;
-        const unsigned tap = t % (unsigned)TV;
-        t /= (unsigned)TV;
-        const int op = (int)(t % (unsigned)Omp), gmi = (int)(t / (unsigned)Omp);
-        const int sub = op / Og, o = op - sub * Og;
-        const int subr = (int)rp / R, row = (int)rp - subr * R;
-        const int g = gmi * gm + sub;
-        if (sub < gm && subr == sub && g < G) e = (((long long)g * Og + o) * R + row) * TV + tap;
-    }
-    float sum = 0.f;
-    if (e >= 0) {
-        const int per = (slices + SEGS - 1) / SEGS;
-        const int end = min(slices, (seg + 1) * per);
-        const float* src = partial + idx;
-        int k = seg * per;
-        for (; k + 4 <= end; k += 4) {  // four independent loads in flight, summed in slice order
-            float v[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) v[i] = src[(long long)(k + i) * packed];
-#pragma unroll
-            for (int i = 0; i < 4; i++) sum += v[i];
-        }
-        for (; k < end; k++) sum += src[(long long)k * packed];
-    }
-    red[seg][el] = sum;
-    __syncthreads();
-    if (seg == 0 && e >= 0) {
-        float t = red[0][el];
-#pragma unroll
-        for (int i = 1; i < SEGS; i++) t += red[i][el];
-        dw[e] = t;
-    }
-}
-
 // wp[gmi][op][tap][rp]: block-diagonal over the gm merged groups, zero in the padding
 __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int G, int R, int Og, int TV, int gm, int Gm,
                                int Rp, int Omp, int transposed) {
@@ -768,19 +719,6 @@ void wgrad_partial(const Params& P, hipStream_t s) {
     } else {
         CANVAS_LAUNCH((k_wgrad<1, 5, 5>), grid, block, 0, s, P);
     }
-}
-
-void wgrad_reduce(const Params& P, float* dw, hipStream_t s) {
-    const long long elems = (long long)P.G * P.Og * P.R * P.TV;
-    if (elems <= 0) return;
-    const unsigned packed = (unsigned)packed_elems(P);
-    const int slices = wgrad_slices(P);
-    if (slices >= 32)
-        CANVAS_LAUNCH(k_wgrad_reduce<8>, dim3((packed + 31) / 32), dim3(256), 0, s, (const float*)P.partial, dw, slices, P.G, P.R, P.Og, P.TV, P.gm,
-                      P.Omp, P.Rp, packed);
-    else
-        CANVAS_LAUNCH(k_wgrad_reduce<2>, dim3((packed + 127) / 128), dim3(256), 0, s, (const float*)P.partial, dw, slices, P.G, P.R, P.Og, P.TV, P.gm,
-                      P.Omp, P.Rp, packed);
 }
 
 void forward(const Params& P, hipStream_t s) {

@@ -45,11 +45,11 @@ void pack_weights(const uint16_t* w, uint16_t* wp, const Params& P, bool transpo
 void forward(const Params& P, hipStream_t s);
 
 // Weight gradient of a windowed contraction (KH = KW = 3 or 5).  prepare_wgrad splits the work; the partials
-// buffer holds wgrad_slices(P) * packed_elems(P) floats; wgrad_reduce sums them into dw [G][Og][R][TV] (fp32).
+// buffer holds wgrad_slices(P) * packed_elems(P) floats, one partial in the packed layout per workgroup; their
+// fixed-order sum into dw [G][Og][R][TV] (fp32) is a job of wreduce_kernels.hpp.
 void prepare_wgrad(Params& P);
 int wgrad_slices(const Params& P);
 void wgrad_partial(const Params& P, hipStream_t s);
-void wgrad_reduce(const Params& P, float* dw, hipStream_t s);
 
 }  // namespace gfctm
 }  // namespace canvas

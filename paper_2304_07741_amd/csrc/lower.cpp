@@ -16,6 +16,7 @@ std::unique_ptr<Lowering> lower(const Dag& full, bool bf16, bool no_fusion) {
     }
     if (!l) l = lower_per_node(dag, bf16);
     batch_weight_jobs(*l);
+    batch_reduce_jobs(*l);
     return l;
 }
 
@@ -39,6 +40,26 @@ void batch_weight_jobs(Lowering& low) {
     }
     low.fwd.insert(low.fwd.begin(), std::make_move_iterator(head.begin()), std::make_move_iterator(head.end()));
     low.wjobs.clear();
+}
+
+void batch_reduce_jobs(Lowering& low) {
+    for (size_t first = 0; first < low.rjobs.size(); first += wreduce::kMaxJobs) {
+        const std::vector<ReduceJob> part(low.rjobs.begin() + first,
+                                          low.rjobs.begin() + std::min(low.rjobs.size(), first + (size_t)wreduce::kMaxJobs));
+        double bytes = 0;
+        for (const auto& j : part) bytes += j.bytes;
+        low.bwd.push_back({"wgrad_reduce", bytes, 0, [part](const RunArgs& a) {
+                               wreduce::Jobs J;
+                               for (const auto& j : part) {
+                                   wreduce::Job& d = J.j[J.n++];
+                                   d = j.job;
+                                   d.partial = (const float*)(a.ws + j.off);
+                                   d.dw = (float*)a.dw[j.widx];
+                               }
+                               wreduce::run(J, a.stream);
+                           }});
+    }
+    low.rjobs.clear();
 }
 
 void make_inference_plan(Lowering& low) {

@@ -284,9 +284,15 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16) {
                                     R.partial = (float*)(a.ws + poff);
                                     gfc::wgrad_partial(R, a.stream);
                                 }});
-            low->bwd.push_back({"gfc_wgrad_reduce", 4.0 * (slices + 1) * nw, 0, [=](const RunArgs& a) {
-                                    gfc::wgrad_reduce((const float*)(a.ws + poff), (float*)a.dw[widx], slices, nw, a.stream);
-                                }});
+            ReduceJob rj;  // (one launch at the end of the backward pass sums the partials of every FC)
+            rj.job.slices = slices;
+            rj.job.kind = 0;
+            rj.job.count = (unsigned)nw;
+            wreduce::plan(rj.job);
+            rj.widx = widx;
+            rj.off = poff;
+            rj.bytes = 4.0 * (slices + 1) * nw;
+            low->rjobs.push_back(rj);
             // data gradient: the same contraction on dy with transposed, tap-flipped weights; it writes the
             // gradient of the FC's source tensor directly (the Unfold adjoint is part of it)
             gfc::Params D = gfc::data_gradient_of(Q);

@@ -10,6 +10,7 @@
 
 #include "dag.hpp"
 #include "wprep_kernels.hpp"
+#include "wreduce_kernels.hpp"
 
 namespace canvas {
 
@@ -40,17 +41,30 @@ struct WeightJob {
     double bytes = 0;
 };
 
+// The fixed-order sum of the weight-gradient partials of FC number widx (at byte offset `off` of the workspace).
+struct ReduceJob {
+    wreduce::Job job;  // geometry; the pointers are filled at run time
+    int widx = 0;
+    int64_t off = 0;
+    double bytes = 0;
+};
+
 struct Lowering {
     bool fused = false;
     uint64_t ws_bytes = 0;
     std::vector<Launch> fwd, bwd;
     std::vector<WeightJob> wjobs;  // collected while lowering; batch_weight_jobs turns them into launches
+    std::vector<ReduceJob> rjobs;  // likewise; batch_reduce_jobs
     std::vector<Launch> prep;  // inference plans only: the weight-only launches taken out of fwd
 };
 
 // Puts the collected weight jobs, of forward and backward alike, into one launch at the head of the forward
 // list (backward runs on the weights and the workspace of the preceding forward).
 void batch_weight_jobs(Lowering& low);
+
+// Puts the collected sums of weight-gradient partials into one launch at the end of the backward list (every
+// weight-gradient kernel owns its block of the workspace, so its partials stay intact until then).
+void batch_reduce_jobs(Lowering& low);
 
 // Turns a lowering into a forward-only plan: weight-only launches move to `prep`, the backward list is dropped.
 void make_inference_plan(Lowering& low);
