@@ -32,16 +32,24 @@ __device__ __forceinline__ uint32_t div_magic(uint32_t x, uint32_t magic) { retu
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <int MO, int KW>
+template <int MO, int KW, bool WL>
 struct Group {
-    uint32_t d[4][KW > 1 ? 6 : 4];  // per row: [pixels -2,-1] pixels 0..7 [pixels 8,9]
-    short4_t a[KW][MO];             // weights of the KW taps of this window row
+    uint32_t d[4][KW > 1 ? 6 : 4];      // per row: [pixels -2,-1] pixels 0..7 [pixels 8,9]
+    short4_t a[WL ? 1 : KW][WL ? 1 : MO];  // weights of the KW taps of this window row (WL: read from LDS when used)
 };
+
+// Dynamic LDS of k_fwd: the weight tile of the workgroup (WL) and, after the K loop, the split-K sums (KS > 1).
+extern __shared__ __align__(16) unsigned char lds_dyn[];
 
 // KS > 1: the KS wavefronts that share a tile split its row chunks (chunk c goes to wavefront c % KS) and
 // their accumulators are added through LDS in a fixed order; for contractions with many channels on
 // few pixels, where one wavefront per tile would leave most SIMDs idle on a long serial K loop.
-template <int MO, int KH, int KW, bool DST_F32, int KS>
+// WL: the workgroup first copies its weight tile (16*MO outputs x all taps and rows of the merged group: one
+// contiguous block of the packed layout) into LDS with coalesced 16-byte loads, and the MFMA A operands are
+// read from there.  Read straight from memory, an A operand load touches 16 lines for 512 bytes, and those
+// loads were a third of the kernel time of the many-channel shapes.  Rows are padded by 16 bytes in LDS: the
+// 16 rows that one read touches then fall into different banks.
+template <int MO, int KH, int KW, bool DST_F32, int KS, bool WL>
 __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     constexpr int TV = KH * KW, HW = KW / 2, HH = KH / 2;
     constexpr bool HALO = KW > 1;
@@ -53,7 +61,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const int tile = blockIdx.x * (kWaves / KS) + wave / KS, ks = wave % KS;
     const int total_units = P.N * P.upi;
     const bool active = tile * 16 < total_units;
-    if constexpr (KS == 1) {
+    if constexpr (KS == 1 && !WL) {
         if (!active) return;
     }
     const int gmi = blockIdx.y / P.otiles, ot = blockIdx.y - gmi * P.otiles;
@@ -76,6 +84,32 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const int wbase = ((gmi * P.Omp + ot * 16 * MO + s) * TV * P.Rp + 4 * r) * 2;
     const int nrc = P.Rp >> 4;
     const bool padrows = (Rm & 15) != 0;
+    const int wstride = TV * P.Rp * 2 + 16;  // bytes per output row of the tile in LDS
+    if constexpr (WL) {
+        const int wrow16 = TV * P.Rp / 8;    // 16-byte pieces per output row
+        const int npieces = 16 * MO * wrow16;
+        const int tbase = (gmi * P.Omp + ot * 16 * MO) * TV * P.Rp * 2;
+        for (int i0 = (int)threadIdx.x; i0 < npieces; i0 += 4 * 64 * kWaves) {
+            u32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int i = i0 + u * 64 * kWaves;
+                v[u] = bload16(rw, i < npieces ? tbase + i * 16 : kOob);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int i = i0 + u * 64 * kWaves;
+                if (i < npieces) {
+                    const int row = (int)div_magic((uint32_t)i, P.magicW16);
+                    *reinterpret_cast<u32x4*>(lds_dyn + row * wstride + (i - row * wrow16) * 16) = v[u];
+                }
+            }
+        }
+        __syncthreads();
+        if constexpr (KS == 1) {
+            if (!active) return;
+        }
+    }
 
     // wave-uniform: could a multi-byte access of this tile straddle an end of the source tensor?  (the
     // hardware drops such an access as a whole; the lanes concerned re-read element by element)
@@ -122,7 +156,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
 
     // `valid` false (one group past the end): the loads touch no memory; with a window every buffer is
     // rewritten unconditionally so that no stale value has to stay live
-    auto issue = [&](int rc, int kh, bool valid, Group<MO, KW>& b) {
+    auto issue = [&](int rc, int kh, bool valid, Group<MO, KW, WL>& b) {
         if (KH == 1 && !valid) return;  // (wave-uniform; with a window the unconditional form measured faster)
         const int eoff = rc * 16 * P.P + (kh - HH) * P.W;
         const int rcw = min(rc, nrc - 1);
@@ -150,16 +184,31 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
             if (near_ends) reload_pair_if_partial(edge, rs, eo, src_elems * 2);
             b.d[0][0] = edge;
         }
+        if constexpr (!WL) {
+#pragma unroll
+            for (int kw = 0; kw < KW; kw++)
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++) {
+                    const auto t = __builtin_amdgcn_raw_buffer_load_b64(rw, wbase, ((mo * 16 * TV + kh * KW + kw) * P.Rp + rcw * 16) * 2, 0);
+                    b.a[kw][mo] = as_short4(t[0], t[1]);
+                }
+        }
+    };
+
+    auto consume = [&](int rc, int kh, Group<MO, KW, WL>& b) {
+        short4_t wa[KW][MO];  // A operands: outputs 16 * mo + s, rows 4r .. 4r+3 of the chunk, tap (kh, kw)
 #pragma unroll
         for (int kw = 0; kw < KW; kw++)
 #pragma unroll
             for (int mo = 0; mo < MO; mo++) {
-                const auto t = __builtin_amdgcn_raw_buffer_load_b64(rw, wbase, ((mo * 16 * TV + kh * KW + kw) * P.Rp + rcw * 16) * 2, 0);
-                b.a[kw][mo] = as_short4(t[0], t[1]);
+                if constexpr (WL) {
+                    const u32x2 t = *reinterpret_cast<const u32x2*>(lds_dyn + (mo * 16 + s) * wstride +
+                                                                     ((kh * KW + kw) * P.Rp + rc * 16 + 4 * r) * 2);
+                    wa[kw][mo] = as_short4(t[0], t[1]);
+                } else {
+                    wa[kw][mo] = b.a[kw][mo];
+                }
             }
-    };
-
-    auto consume = [&](int kh, Group<MO, KW>& b) {
         if constexpr (HALO) {
             // row_shr:1 / row_shl:1 within the 16 lanes of a row; a lane without a source keeps the loaded edge value
             const uint32_t loaded = b.d[0][0];
@@ -196,14 +245,14 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 }
                 const short4_t bq = as_short4(o[0], o[1]);
 #pragma unroll
-                for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(b.a[kw][mo], bq, acc[mo][q]);
+                for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[kw][mo], bq, acc[mo][q]);
             }
     };
 
     // groups g = (row chunk, kh); each statically unrolled slot owns one buffer, the next group's loads
     // are issued before the current group is multiplied
     constexpr int UNR = KH > 1 ? KH : 2;
-    Group<MO, KW> buf[UNR];
+    Group<MO, KW, WL> buf[UNR];
     const int nrc_mine = active && ks < nrc ? (nrc - ks + KS - 1) / KS : 0;  // this wavefront's chunks: ks, ks + KS, ...
     const int NG = nrc_mine * KH;
     issue(ks, 0, NG > 0, buf[0]);
@@ -216,7 +265,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 const int rcn = KH > 1 ? (u + 1 == KH ? it + 1 : it) : g + 1;  // index among this wavefront's chunks
                 issue(ks + rcn * KS, khn, g + 1 < NG, buf[(u + 1) % UNR]);
                 __builtin_amdgcn_sched_barrier(0);
-                consume(KH > 1 ? u : 0, buf[u]);
+                consume(ks + (KH > 1 ? it : g) * KS, KH > 1 ? u : 0, buf[u]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -237,7 +286,10 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
 #pragma unroll
             for (int q = 0; q < 8; q++) fin[i][q] = acc[i >> 2][q][i & 3];
     } else {
-        __shared__ float red[kWaves / KS][KS][TF * 8][64];
+        // (the sums reuse the LDS of the weight tile: every wavefront has left the K loop first)
+        typedef float Red[KS][TF * 8][64];
+        Red* red = reinterpret_cast<Red*>(lds_dyn);
+        if constexpr (WL) __syncthreads();
         const int sub = wave / KS;
         t0 = ks * TF;
 #pragma unroll
@@ -616,14 +668,25 @@ __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restr
 // walk over several tiles and issue the next tile's first loads early, with or without cache-line
 // touches ahead, were not faster than letting the hardware scheduler balance one-tile workgroups; nor was
 // a 1x1 variant that keeps three groups of loads in flight instead of one.)
-template <int MO, int KH, int KW, bool DST_F32>
-void launch_fwd_k(const Params& P, hipStream_t s) {
+template <int MO, int KH, int KW, bool DST_F32, bool WL>
+void launch_fwd_w(const Params& P, unsigned lds_w, hipStream_t s) {
     const int tiles = (P.N * P.upi + 15) / 16;
     const dim3 block(64 * kWaves);
     const unsigned gy = (unsigned)(P.Gm * P.otiles);
-    if (P.ksplit == 4) CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 4>), dim3((unsigned)tiles, gy), block, 0, s, P);
-    else if (P.ksplit == 2) CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 2>), dim3((unsigned)((tiles + 1) / 2), gy), block, 0, s, P);
-    else CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 1>), dim3((unsigned)((tiles + kWaves - 1) / kWaves), gy), block, 0, s, P);
+    // split-K sums: kWaves / KS tiles x KS wavefronts x (4 * MO / KS) row slots x 8 pixels x 64 lanes, fp32
+    const unsigned red = P.ksplit > 1 ? (unsigned)(kWaves * (4 * MO / P.ksplit) * 8 * 64 * 4) : 0u;
+    const unsigned lds = std::max(lds_w, red);
+    if (P.ksplit == 4) CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 4, WL>), dim3((unsigned)tiles, gy), block, lds, s, P);
+    else if (P.ksplit == 2) CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 2, WL>), dim3((unsigned)((tiles + 1) / 2), gy), block, lds, s, P);
+    else CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 1, WL>), dim3((unsigned)((tiles + kWaves - 1) / kWaves), gy), block, lds, s, P);
+}
+
+template <int MO, int KH, int KW, bool DST_F32>
+void launch_fwd_k(const Params& P, hipStream_t s) {
+    // the weight tile of a workgroup goes through LDS where two workgroups' tiles fit a compute unit
+    const unsigned lds_w = 16u * MO * (unsigned)(P.TV * P.Rp * 2 + 16);
+    if (lds_w <= 72u * 1024u) launch_fwd_w<MO, KH, KW, DST_F32, true>(P, lds_w, s);
+    else launch_fwd_w<MO, KH, KW, DST_F32, false>(P, 0u, s);
 }
 
 template <int MO, bool DST_F32>
@@ -679,6 +742,7 @@ Params shape(int N, int G, int R, int KH, int KW, int Og, int H, int W) {
     auto magic = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); };
     Q.magicW = magic((uint32_t)W);
     Q.magicUpi = magic((uint32_t)Q.upi);
+    Q.magicW16 = magic((uint32_t)(Q.TV * Q.Rp / 8));
     return Q;
 }
 
