@@ -472,6 +472,129 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
             }
 }
 
+// 64 x 64 tile of dW per wavefront for bf16 operands without a window, 64 pixels per step.  The operand rows are
+// loaded the way memory likes it -- one instruction covers 8 rows x 128 contiguous bytes -- and turned into the MFMA
+// layout (lane (r, s): row s, pixels 8r .. 8r+7 of a 32-pixel half) through a wavefront-private LDS tile of
+// 64 rows x (128 + 16) bytes, first dy, then x through the same rows.  (With the loads in the MFMA layout an
+// instruction touched 16 rows x 64 bytes, and the kernel was bound by the address pipeline: 27 -> 20 us for the
+// same bytes when only the shape of the loads was changed.)  The four wavefronts of a workgroup (consecutive
+// slices of the same tile) are summed through the same LDS in a fixed order: one partial per workgroup.
+__global__ __launch_bounds__(64 * kWaves) void k_wgrad64(Params P) {
+    constexpr int MO = 4, NK = 4, kRow = 144;
+    __shared__ __align__(16) unsigned char lds[kWaves * 64 * kRow];
+    static_assert(sizeof(lds) >= 2 * MO * NK * 4 * 64 * sizeof(float), "the cross-wavefront sum reuses the tiles");
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int slice = blockIdx.x * kWaves + wave;
+    const bool active = slice < P.slices;  // (no early exit: every wavefront takes part in the workgroup sum below)
+    const int g = blockIdx.z;
+    const int ot = blockIdx.y / P.ktiles, kt = blockIdx.y - ot * P.ktiles;
+    const int r = lane >> 4, s = lane & 15;
+    const int lrow = lane >> 3, lseg = lane & 7;  // shape of the loads: 8 rows x 8 pieces of 16 bytes
+    const int src_elems = P.N * P.G * P.R * P.P, dy_elems = P.N * P.G * P.Og * P.P;
+    const rsrc_t rs = make_rsrc(P.src, src_elems * 2);
+    const rsrc_t rdy = make_rsrc(P.dy, dy_elems * 2);
+    const int obase = ot * 64, kbase = kt * 64;
+    unsigned char* mine = lds + wave * 64 * kRow;
+
+    float4_t acc[MO][NK];
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+        for (int nk = 0; nk < NK; nk++) acc[mo][nk] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    // steps of 64 pixels: P.chunks32 counts them here
+    const int c_begin = active ? slice * P.per_slice : 0, c_end = active ? min(P.N * P.chunks32, c_begin + P.per_slice) : 0;
+    int n = (int)div_magic((uint32_t)c_begin, P.magicC32);
+    int pc = c_begin - n * P.chunks32;
+    for (int c = c_begin; c < c_end; c++) {
+        const int px0 = pc * 64;
+        const int row0 = (n * P.G + g) * P.R, orow0 = (n * P.G + g) * P.Og;
+        const bool near_ends = (row0 + P.R - 1) * P.P + px0 + 72 > src_elems || (orow0 + P.Og - 1) * P.P + px0 + 72 > dy_elems;
+        const int pl = px0 + lseg * 8;
+        u32x4 ra[8], rb[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const int o = obase + 8 * k + lrow;
+            ra[k] = load8<false>(rdy, (orow0 + o) * P.P + pl, pl < P.P && o < P.Og, near_ends, dy_elems * 2).hi;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const int kr = kbase + 8 * k + lrow;
+            rb[k] = load8<false>(rs, (row0 + kr) * P.P + pl, pl < P.P && kr < P.K, near_ends, src_elems * 2).hi;
+        }
+        u32x4 a[2][MO], b[2][NK];
+#pragma unroll
+        for (int k = 0; k < 8; k++) *reinterpret_cast<u32x4*>(mine + (8 * k + lrow) * kRow + lseg * 16) = ra[k];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            // (a 16-byte piece that begins inside the plane may run past its end into the next row: masked here, on dy)
+            const int nvalid = max(0, min(8, P.P - (px0 + h * 32 + 8 * r)));
+            const u32x4 mvalid = mask_of((1u << nvalid) - 1u);
+#pragma unroll
+            for (int mo = 0; mo < MO; mo++)
+                a[h][mo] = *reinterpret_cast<const u32x4*>(mine + (mo * 16 + s) * kRow + h * 64 + r * 16) & mvalid;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; k++) *reinterpret_cast<u32x4*>(mine + (8 * k + lrow) * kRow + lseg * 16) = rb[k];
+#pragma unroll
+        for (int h = 0; h < 2; h++)
+#pragma unroll
+            for (int nk = 0; nk < NK; nk++) b[h][nk] = *reinterpret_cast<const u32x4*>(mine + (nk * 16 + s) * kRow + h * 64 + r * 16);
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            if (h == 1 && px0 + 32 >= P.P) continue;  // (wave-uniform: the plane ends in the first half)
+#pragma unroll
+            for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+                for (int nk = 0; nk < NK; nk++) {
+                    float4_t t = acc[mo][nk];
+                    t = mfma16(as_short4(a[h][mo][0], a[h][mo][1]), as_short4(b[h][nk][0], b[h][nk][1]), t);
+                    t = mfma16(as_short4(a[h][mo][2], a[h][mo][3]), as_short4(b[h][nk][2], b[h][nk][3]), t);
+                    acc[mo][nk] = t;
+                }
+        }
+        if (++pc == P.chunks32) { pc = 0; n++; }
+    }
+    // sum of the four wavefronts in a fixed order, (w0 + w2) + (w1 + w3)
+    __syncthreads();  // every wavefront has left its tile
+    float (*red)[MO * NK * 4][64] = reinterpret_cast<float (*)[MO * NK * 4][64]>(lds);
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int nk = 0; nk < NK; nk++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) red[slot][(mo * NK + nk) * 4 + jj][lane] = acc[mo][nk][jj];
+    };
+    auto add = [&](int slot) {
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int nk = 0; nk < NK; nk++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) acc[mo][nk][jj] += red[slot][(mo * NK + nk) * 4 + jj][lane];
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) add(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave != 0) return;
+    add(0);
+    float* part = P.partial + (long long)blockIdx.x * P.G * P.Og * P.K;
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+        for (int nk = 0; nk < NK; nk++)
+#pragma unroll
+            for (int jj = 0; jj < 4; jj++) {
+                const int o = obase + mo * 16 + 4 * r + jj, k = kbase + nk * 16 + s;
+                if (o < P.Og && k < P.K) part[((long long)g * P.Og + o) * P.K + k] = acc[mo][nk][jj];
+            }
+}
+
 __global__ void k_transpose_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt, int G, int Og, int R, int TV) {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     const long long total = (long long)G * R * Og * TV;
@@ -537,7 +660,8 @@ void prepare_wgrad(Params& P) {
     P.wtile = (!P.src_f32 && !P.dy_f32 && P.TV == 1 && P.Og >= 64 && P.K >= 64) ? 4 : 2;
     P.otiles = (P.Og + 16 * P.wtile - 1) / (16 * P.wtile);
     P.ktiles = (P.K + 16 * P.wtile - 1) / (16 * P.wtile);
-    P.chunks32 = (P.P + 31) / 32;
+    const int chunk_px = P.wtile == 4 ? 64 : 32;  // pixels per step of a wavefront
+    P.chunks32 = (P.P + chunk_px - 1) / chunk_px;
     P.magicC32 = magic_u32(P.chunks32);
     const int64_t wnumel = (int64_t)P.G * P.Og * P.K;
     const int64_t tiles = (int64_t)P.G * P.otiles * P.ktiles;
@@ -577,7 +701,7 @@ void wgrad_partial(const Params& P, hipStream_t s) {
 #define GFC_WG(SF, DF) \
     do { if (taps) CANVAS_LAUNCH((k_wgrad<2, 2, SF, DF, true>), grid, block, 0, s, P); else CANVAS_LAUNCH((k_wgrad<2, 2, SF, DF, false>), grid, block, 0, s, P); } while (0)
     if (P.wtile == 4) {
-        CANVAS_LAUNCH((k_wgrad<4, 4, false, false, false>), grid, block, 0, s, P);
+        CANVAS_LAUNCH(k_wgrad64, grid, block, 0, s, P);
         return;
     }
     if (P.src_f32) { if (P.dy_f32) GFC_WG(true, true); else GFC_WG(true, false); }
