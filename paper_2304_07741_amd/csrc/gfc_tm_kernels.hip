@@ -89,15 +89,16 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         const int wrow16 = TV * P.Rp / 8;    // 16-byte pieces per output row
         const int npieces = 16 * MO * wrow16;
         const int tbase = (gmi * P.Omp + ot * 16 * MO) * TV * P.Rp * 2;
-        for (int i0 = (int)threadIdx.x; i0 < npieces; i0 += 4 * 64 * kWaves) {
-            u32x4 v[4];
+        constexpr int B = 8;  // loads in flight per thread
+        for (int i0 = (int)threadIdx.x; i0 < npieces; i0 += B * 64 * kWaves) {
+            u32x4 v[B];
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
+            for (int u = 0; u < B; u++) {
                 const int i = i0 + u * 64 * kWaves;
                 v[u] = bload16(rw, i < npieces ? tbase + i * 16 : kOob);
             }
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
+            for (int u = 0; u < B; u++) {
                 const int i = i0 + u * 64 * kWaves;
                 if (i < npieces) {
                     const int row = (int)div_magic((uint32_t)i, P.magicW16);
