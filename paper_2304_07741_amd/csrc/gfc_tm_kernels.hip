@@ -763,10 +763,10 @@ void prepare_wgrad(Params& P) {
     P.chunks = (P.P + 31) / 32;
     const int64_t tiles = (int64_t)P.Gm * (P.Omp / (16 * wgrad_mo(P))) * (P.Rp / 16);
     const int64_t packed = packed_elems(P);
-    // about 3.5 k wavefronts; partials at most max(8 MB, 30 % of the operand bytes)
+    // about 3.5 k wavefronts; partials at most max(4 MB, 30 % of the operand bytes)
     int64_t nsplit = std::max<int64_t>(1, std::min<int64_t>(P.N, (3584 + P.chunks * tiles - 1) / (P.chunks * tiles)));
     const int64_t operand_bytes = (int64_t)P.N * P.G * (P.R + P.Og) * P.P * 2;
-    const int64_t cap = std::max<int64_t>((int64_t)8 << 20, operand_bytes * 3 / 10);
+    const int64_t cap = std::max<int64_t>((int64_t)4 << 20, operand_bytes * 3 / 10);
     nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, kWaves * cap / (packed * 4 * P.chunks)));
     P.imgs_per_split = (int)((P.N + nsplit - 1) / nsplit);
     P.nsplit = (P.N + P.imgs_per_split - 1) / P.imgs_per_split;
