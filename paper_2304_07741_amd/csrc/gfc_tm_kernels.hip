@@ -250,6 +250,29 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
             }
     };
 
+    // Output rows of the tile as T = 4 * MO "row slots" t = 4 * mo + j (output 16 * mo + 4 * r + j of this lane, 8 pixels
+    // each); this wavefront finishes the TF slots from t0 on (all of them when KS == 1, see below).
+    constexpr int T = 4 * MO, TF = T / KS;
+    static_assert(T % KS == 0, "row slots divide among the wavefronts of a tile");
+    const int t0 = KS > 1 ? ks * TF : 0;
+    const int nvalid = min(8, P.P - p);
+    const int outs_img = P.G * P.Og;
+    const int dst_elems = P.N * outs_img * P.P;
+    const rsrc_t rad = make_rsrc(P.addend, dst_elems * 2);
+    // A bf16 tensor that is added to the result (windowed data gradients) is fetched now, so that it has arrived
+    // when the K loop ends; 3 x 3 windows only: there the registers do not cost a wavefront of occupancy.
+    constexpr bool EARLY = !DST_F32 && KH == 3 && TF <= 8;
+    u32x4 early[EARLY ? TF : 1];
+    if constexpr (EARLY) {
+#pragma unroll
+        for (int i = 0; i < TF; i++) {
+            const int t = t0 + i;
+            const int o = ot * 16 * MO + (t >> 2) * 16 + 4 * r + (t & 3);
+            const int e = (n * outs_img + gmi * P.gm * P.Og + o) * P.P + p;
+            early[i] = bload16(rad, P.addend && live && o < Om && nvalid == 8 ? e * 2 : kOob);
+        }
+    }
+
     // groups g = (row chunk, kh); each statically unrolled slot owns one buffer, the next group's loads
     // are issued before the current group is multiplied
     constexpr int UNR = KH > 1 ? KH : 2;
@@ -272,15 +295,11 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         }
     }
 
-    // Output rows of the tile as T = 4 * MO "row slots" t = 4 * mo + j (output 16 * mo + 4 * r + j of this lane, 8 pixels
-    // each).  KS == 1: the wavefront owns them all.  KS > 1: wavefront f of the tile finishes slots
+    // KS == 1: the wavefront owns all row slots.  KS > 1: wavefront f of the tile finishes slots
     // [f * T / KS, (f + 1) * T / KS): in round v every wavefront w hands the slots of wavefront (w + v) % KS over
     // through LDS, so each finisher adds its partners' sums in the fixed order own, w-1, w-2, ... and the
     // additions and stores of a tile are spread over its KS wavefronts.
-    constexpr int T = 4 * MO, TF = T / KS;
-    static_assert(T % KS == 0, "row slots divide among the wavefronts of a tile");
     float fin[TF][8];
-    int t0 = 0;
     if constexpr (KS == 1) {
 #pragma unroll
         for (int i = 0; i < TF; i++)
@@ -292,7 +311,6 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         Red* red = reinterpret_cast<Red*>(lds_dyn);
         if constexpr (WL) __syncthreads();
         const int sub = wave / KS;
-        t0 = ks * TF;
 #pragma unroll
         for (int d = 0; d < KS; d++)
             if (d == ks) {
@@ -321,15 +339,11 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         }
     }
     if (!live) return;
-    const int nvalid = min(8, P.P - p);
-    const int outs_img = P.G * P.Og;
-    const int dst_elems = P.N * outs_img * P.P;
     const rsrc_t rd = make_rsrc(P.dst, dst_elems * (DST_F32 ? 4 : 2));
     // What the rows are added to is read, four rows at a time, before any of the four is stored: loads that
     // follow a store to the same tensor are not moved ahead of it, and would cost a memory round trip per row.
     constexpr int RB = TF < 4 ? TF : 4;
-    const rsrc_t rad = make_rsrc(P.addend, dst_elems * 2);
-    const bool adds = (DST_F32 && P.acc) || (!DST_F32 && P.addend);
+    const bool adds = (DST_F32 && P.acc) || (!DST_F32 && !EARLY && P.addend);
 #pragma unroll
     for (int i0 = 0; i0 < TF; i0 += RB) {
     u32x4 pre[RB][2];
@@ -379,7 +393,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 bstore16(rd, e * 4 + 16, hi);
             } else {
                 if (P.addend) {  // bf16 tensor of the output's shape added before rounding
-                    const u32x4 ad = pre[b][0];
+                    const u32x4 ad = EARLY ? early[EARLY ? i : 0] : pre[b][0];
 #pragma unroll
                     for (int k = 0; k < 4; k++) {
                         v[2 * k] += lo_f32(ad[k]);
