@@ -304,6 +304,9 @@ UFC_VARIANTS = [
     (3, 3, "relu", [(0, -1, 0, 12)], "mul", False, 3, 48, 2, 24, 8, 16),           # 3 groups of 8 rows: the last merged pair is half empty
     (5, 5, "abs", [], "add", True, 1, 20, 1, 20, 9, 9),                             # groups of 4 rows: four merged, one left over
     (3, 2, "sin", [(0, 1, 0, 8)], "mul", False, 2, 16, 2, 16, 8, 8),                # a smooth unary outside the first four
+    # weight tiles too large for LDS (> 72 KB per workgroup): the MFMA operands are read from memory directly
+    (5, 1, "relu", [], "add", False, 1, 32, 2, 64, 9, 9),                           # 5x5 window on 64 rows: 32 x 25 x 64 weights per tile
+    (1, 1, "abs", [(0, 1, 0, 512)], "mul", False, 1, 64, 1, 1024, 4, 8),            # 1024 channels: 64 x 1024 weights per tile
 ]
 
 
