@@ -1,4 +1,4 @@
-"""GPU parity on seeded random shapes: the two fused lowerings and the MFMA grouped-FC kernels on sizes drawn
+"""GPU parity on 400 seeded random shapes: the two fused lowerings and the MFMA grouped-FC kernels on sizes drawn
 at random (odd widths, single rows, ragged 8-pixel tails, channel counts that are no multiple of 16, groups of
 1-32 rows, windows 1/3/5 also non-square), each case against the CPU oracle at the bf16 tolerance.
 
@@ -61,6 +61,38 @@ def _gate(rng):
     return body, (N, C, H, W), [(g1, C // g1, (C // g1) * k * k), (g2, o2 // g2, C // g2)]
 
 
+def _gate_wide(rng):
+    """The same family with 64-320 channels: 64 x 64 weight-gradient tiles, weight tiles in LDS, split K"""
+    k = rng.choice([1, 3, 3])
+    g1 = rng.choice([1, 2, 4, 8])
+    C = min(g1 * rng.choice([16, 24, 32, 64, 80]), 320 // g1 * g1)
+    g2 = rng.choice([1, 1, 2])
+    if C % g2:
+        g2 = 1
+    o2 = g2 * rng.choice([64, 72, 128, 136])
+    N, H, W = rng.randint(1, 6), rng.randint(2, 15), rng.randint(4, 17)
+    act = rng.choice([None, "relu", "gelu"])
+    lines = []
+
+    def emit(text):
+        lines.append(f"%{len(lines) + 1} = {text}")
+        return len(lines)
+
+    cur = 0
+    if k > 1:
+        cur = emit(f"unfold %0 kh={k} kw={k}")
+    cur = emit(f"fc %{cur} groups={g1} out={C}")
+    if act:
+        cur = emit(f"unary %{cur} op={act}")
+    if rng.random() < 0.5:
+        c0 = rng.randrange(0, C)
+        cur = emit(f"shift %{cur} dh={rng.randint(-1, 1)} dw={rng.randint(-2, 2)} c0={c0} c1={rng.randint(c0 + 1, C)}")
+    cur = emit(f"binary %0 %{cur} op={rng.choice(['add', 'mul'])}")
+    cur = emit(f"fc %{cur} groups={g2} out={o2}")
+    body = "\n".join(lines) + f"\noutput %{cur}\n"
+    return body, (N, C, H, W), [(g1, C // g1, (C // g1) * k * k), (g2, o2 // g2, C // g2)]
+
+
 def _window_weights(rng):
     """FC -> [softmax] -> broadcast-mul onto Unfold(x) -> Fold over the taps -> FC"""
     k = rng.choice([3, 3, 5])
@@ -93,7 +125,7 @@ def _single_fc(rng):
     return body, (N, G * R, H, W), [(G, Og, R * kh * kw)]
 
 
-FAMILIES = {"gate": _gate, "window_weights": _window_weights, "single_fc": _single_fc}
+FAMILIES = {"gate": _gate, "gate_wide": _gate_wide, "window_weights": _window_weights, "single_fc": _single_fc}
 
 
 @pytest.mark.parametrize("block", range(4))
