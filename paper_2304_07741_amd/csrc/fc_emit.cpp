@@ -9,9 +9,7 @@ void emit_fc(Lowering& low, bool backward, const Dag& dag, const TakeFn& take, c
              bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32) {
     std::vector<Launch>& list = backward ? low.bwd : low.fwd;
     const int64_t nw = (int64_t)G * Og * R * kh * kw;
-    // (1x1 contractions with enough tiles to fill the chip stay on the generic kernel: measured faster there)
-    if (!src.f32 && gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W) &&
-        (kh * kw > 1 || gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W).ksplit > 1)) {
+    if (!src.f32 && gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W)) {
         const gfctm::Params T = gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W);
         const bool identity = !transposed && T.TV == 1 && T.gm == 1 && T.Rp == R && T.Omp == Og;
         const int64_t opk = identity ? -1 : take((uint64_t)gfctm::packed_elems(T) * 2);
