@@ -659,6 +659,222 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
     }
 }
 
+// The same for 3 x 3 windows on images whose rows fill most of one or several 32-pixel chunks: a wavefront owns
+// a chunk of COLUMNS and walks down the image rows (a step = one row of one image).  Row h + 1 of x at step
+// h is row h of step h + 1: after the first step of an image only ONE new x row is loaded per step, and the two
+// others are the previous step's registers (the kernel above fetches three row pieces per step, and its loads
+// were more than half of its time at 56 x 56).  A row is inside the image or not as a whole, so a row outside
+// is simply not loaded (zeros) and no vertical masks exist; columns beyond the row's end hold the next row's
+// pixels and are masked on dy together with the horizontal validity of each window column.
+template <int MO>
+__global__ __launch_bounds__(64 * kWaves) void k_wgrad_rows(Params P) {
+    constexpr int KH = 3, KW = 3, TV = 9, HW = 1;
+    constexpr int NE = MO * TV * 4;
+    __shared__ float red[2][NE][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane >> 4, s = lane & 15;
+    const int nrc = P.Rp >> 4;
+    const int rc = blockIdx.y % nrc;
+    const int got = blockIdx.y / nrc;
+    const int otiles = P.Omp / (16 * MO);
+    const int gmi = got / otiles, ot = got - gmi * otiles;
+    const int gcount = min(P.gm, P.G - gmi * P.gm);
+    const int Rm = gcount * P.R, Om = gcount * P.Og;
+    const int items = P.chunks * P.nsplit;  // column chunks x ranges of (image, row) steps
+    const int item = blockIdx.x * kWaves + wave;
+    const bool active = item < items;
+    const int isplit = active ? item / P.chunks : 0;
+    const int qc = active ? item - isplit * P.chunks : 0;
+    const int t0 = isplit * P.imgs_per_split;
+    const int t1 = active ? min(P.N * P.H, t0 + P.imgs_per_split) : t0;
+
+    const int rows_img = P.G * P.R, outs_img = P.G * P.Og;
+    const int src_elems = P.N * rows_img * P.P, dy_elems = P.N * outs_img * P.P;
+    const rsrc_t rs = make_rsrc(P.src, src_elems * 2);
+    const rsrc_t rdy = make_rsrc(P.dy, dy_elems * 2);
+    const int grow0 = gmi * P.gm * P.R, gout0 = gmi * P.gm * P.Og;
+    const int c = qc * 32 + 8 * r;  // first column of this lane
+    const bool livepx = c < P.W;
+
+    int edy[MO];
+    bool dyok[MO];
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++) {
+        const int o = ot * 16 * MO + mo * 16 + s;
+        dyok[mo] = livepx && o < Om;
+        edy[mo] = (gout0 + o) * P.P + c;
+    }
+    const int row = rc * 16 + s;
+    const bool xok = livepx && row < Rm;
+    const int ex = (grow0 + row) * P.P + c;
+
+    u32x4 dymask[KW];  // column exists and its source column under window column kw is inside the image
+#pragma unroll
+    for (int kw = 0; kw < KW; kw++) {
+        uint32_t bits = 0;
+#pragma unroll
+        for (int q = 0; q < 8; q++)
+            if (c + q < P.W && (unsigned)(c + q + kw - HW) < (unsigned)P.W) bits |= 1u << q;
+        dymask[kw] = mask_of(bits);
+    }
+
+    float4_t acc[MO][TV];
+#pragma unroll
+    for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+        for (int t = 0; t < TV; t++) acc[mo][t] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    struct RowStep {
+        u32x4 dy[MO];
+        uint32_t x[KH][6];  // per window row: [2 pixels left | the lane's 8 pixels | 2 pixels right]
+    };
+
+    // x row `hr` of image n (a row outside the image: zeros) -> its 8 pixels in x[1..4], the edge pixels of the first /
+    // last quarter of the wavefront in x[0] (see the kernel above)
+    auto load_row = [&](int n, int hr, bool valid, bool near_ends, uint32_t (&x)[6]) {
+        const bool ok = valid && xok && (unsigned)hr < (unsigned)P.H;
+        const int bo = ok ? (n * rows_img * P.P + ex + hr * P.W) * 2 : kOob;
+        u32x4 m = bload16(rs, bo);
+        const int eo = ok ? (r == 0 ? bo - 4 : (r == 3 ? bo + 16 : kOob)) : kOob;
+        uint32_t edge = __builtin_amdgcn_raw_buffer_load_b32(rs, eo, 0, 0);
+        if (near_ends) {  // only lanes whose access is partly outside re-read, element by element
+            reload_if_partial(m, rs, bo, src_elems * 2);
+            reload_pair_if_partial(edge, rs, eo, src_elems * 2);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; k++) x[k + 1] = m[k];
+        x[0] = edge;
+    };
+    // `first`: the step opens an image (or the wavefront's range): all three x rows are loaded; else rows h - 1 and h
+    // are the previous step's rows h and h + 1
+    auto issue = [&](int t, bool valid, bool first, RowStep& st, const RowStep& prev) {
+        const int n = (int)div_magic((uint32_t)t, P.magicH), h = t - n * P.H;
+        // wave-uniform: could an access of this step straddle an end of a tensor?
+        const int xrow0 = n * rows_img + grow0 + rc * 16, yrow0 = n * outs_img + gout0 + ot * 16 * MO;
+        const int px = h * P.W + qc * 32;
+        const bool near_ends = xrow0 * P.P + px - P.W - 2 < 0 || (xrow0 + 16) * P.P + px + P.W + 48 > src_elems ||
+                               (yrow0 + 16 * MO) * P.P + px + 40 > dy_elems;
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++) {
+            const bool ok = valid && dyok[mo];
+            const int bo = ok ? (n * outs_img * P.P + edy[mo] + h * P.W) * 2 : kOob;
+            st.dy[mo] = bload16(rdy, bo);
+            if (near_ends) reload_if_partial(st.dy[mo], rdy, bo, dy_elems * 2);
+        }
+        if (first) {
+            load_row(n, h - 1, valid, near_ends, st.x[0]);
+            load_row(n, h, valid, near_ends, st.x[1]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 6; k++) {
+                st.x[0][k] = prev.x[1][k];
+                st.x[1][k] = prev.x[2][k];
+            }
+        }
+        load_row(n, h + 1, valid, near_ends, st.x[2]);
+    };
+    // the two pixels on either side of the lane's 8: its neighbours' (lanes 16 below / above), or the loaded edge
+    auto halo = [&](uint32_t (&x)[6]) {
+        const uint32_t edge = x[0];
+        const uint32_t below = (uint32_t)__builtin_amdgcn_ds_bpermute(((lane + 48) & 63) * 4, (int)x[4]);
+        const uint32_t above = (uint32_t)__builtin_amdgcn_ds_bpermute(((lane + 16) & 63) * 4, (int)x[1]);
+        x[0] = r == 0 ? edge : below;
+        x[5] = r == 3 ? edge : above;
+    };
+    auto finish = [&](bool first, RowStep& st) {
+        if (first) {
+            halo(st.x[0]);
+            halo(st.x[1]);
+        }
+        halo(st.x[2]);
+    };
+    auto multiply = [&](RowStep& st) {
+#pragma unroll
+        for (int kw = 0; kw < KW; kw++) {
+            u32x4 a[MO];
+#pragma unroll
+            for (int mo = 0; mo < MO; mo++) a[mo] = st.dy[mo] & dymask[kw];
+#pragma unroll
+            for (int kh = 0; kh < KH; kh++) {
+                const int dw = kw - HW;
+                uint32_t xs[4];
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const int e0 = 2 * k + 2 + dw;  // first element of output dword k (element index of pixel 0 is 2)
+                    xs[k] = (e0 & 1) ? __builtin_amdgcn_alignbit(st.x[kh][(e0 >> 1) + 1], st.x[kh][e0 >> 1], 16) : st.x[kh][e0 >> 1];
+                }
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++) {
+                    float4_t cc = acc[mo][kh * KW + kw];
+                    cc = mfma16(as_short4(a[mo][0], a[mo][1]), as_short4(xs[0], xs[1]), cc);
+                    cc = mfma16(as_short4(a[mo][2], a[mo][3]), as_short4(xs[2], xs[3]), cc);
+                    acc[mo][kh * KW + kw] = cc;
+                }
+            }
+        }
+    };
+    auto opens_image = [&](int t) { return t - (int)div_magic((uint32_t)t, P.magicH) * P.H == 0; };
+
+    // two steps per trip: the loads of the next step are in flight while this one is multiplied
+    RowStep st[2];
+    bool first0 = true, first1 = false;
+    issue(t0, t0 < t1, true, st[0], st[0]);
+    for (int t = t0; t < t1; t += 2) {
+        finish(first0, st[0]);
+        first1 = opens_image(t + 1);
+        issue(t + 1, t + 1 < t1, first1, st[1], st[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(st[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < t1) {
+            finish(first1, st[1]);
+            first0 = opens_image(t + 2);
+            issue(t + 2, t + 2 < t1, first0, st[0], st[1]);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(st[1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // sum of the workgroup's four wavefronts in a fixed order: (w0 + w2) + (w1 + w3), through LDS
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int t = 0; t < TV; t++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) red[slot][(mo * TV + t) * 4 + jj][lane] = acc[mo][t][jj];
+    };
+    auto add = [&](int slot) {
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int t = 0; t < TV; t++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) acc[mo][t][jj] += red[slot][(mo * TV + t) * 4 + jj][lane];
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) add(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave == 0) {
+        add(0);
+        float* part = P.partial + (long long)blockIdx.x * P.Gm * P.Omp * TV * P.Rp;
+#pragma unroll
+        for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+            for (int t = 0; t < TV; t++)
+#pragma unroll
+                for (int jj = 0; jj < 4; jj++) {
+                    const int o = ot * 16 * MO + mo * 16 + 4 * r + jj;
+                    part[((long long)(gmi * P.Omp + o) * TV + t) * P.Rp + rc * 16 + s] = acc[mo][t][jj];
+                }
+    }
+}
+
 // wp[gmi][op][tap][rp]: block-diagonal over the gm merged groups, zero in the padding
 __global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int G, int R, int Og, int TV, int gm, int Gm,
                                int Rp, int Omp, int transposed) {
@@ -758,6 +974,7 @@ Params shape(int N, int G, int R, int KH, int KW, int Og, int H, int W) {
     Q.magicW = magic((uint32_t)W);
     Q.magicUpi = magic((uint32_t)Q.upi);
     Q.magicW16 = magic((uint32_t)(Q.TV * Q.Rp / 8));
+    Q.magicH = magic((uint32_t)H);
     return Q;
 }
 
@@ -774,16 +991,21 @@ void pack_weights(const uint16_t* w, uint16_t* wp, const Params& P, bool transpo
 static int wgrad_mo(const Params& P) { return P.KH == 3 && P.Omp % 32 == 0 ? 2 : 1; }
 
 void prepare_wgrad(Params& P) {
-    P.chunks = (P.P + 31) / 32;
+    // 3 x 3 windows on rows that fill at least 3/4 of their 32-column chunks: by image rows (k_wgrad_rows), where a
+    // step is one row of one image; else by 32-pixel positions, where a step is one image
+    const int qchunks = (P.W + 31) / 32;
+    P.rows = P.KH == 3 && P.KW == 3 && P.W >= 24 && 4 * P.W >= 3 * 32 * qchunks ? 1 : 0;
+    P.chunks = P.rows ? qchunks : (P.P + 31) / 32;
+    const int64_t steps = P.rows ? (int64_t)P.N * P.H : P.N;
     const int64_t tiles = (int64_t)P.Gm * (P.Omp / (16 * wgrad_mo(P))) * (P.Rp / 16);
     const int64_t packed = packed_elems(P);
     // about 3.5 k wavefronts; partials at most max(4 MB, 30 % of the operand bytes)
-    int64_t nsplit = std::max<int64_t>(1, std::min<int64_t>(P.N, (3584 + P.chunks * tiles - 1) / (P.chunks * tiles)));
+    int64_t nsplit = std::max<int64_t>(1, std::min<int64_t>(steps, (3584 + P.chunks * tiles - 1) / (P.chunks * tiles)));
     const int64_t operand_bytes = (int64_t)P.N * P.G * (P.R + P.Og) * P.P * 2;
     const int64_t cap = std::max<int64_t>((int64_t)4 << 20, operand_bytes * 3 / 10);
     nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, kWaves * cap / (packed * 4 * P.chunks)));
-    P.imgs_per_split = (int)((P.N + nsplit - 1) / nsplit);
-    P.nsplit = (P.N + P.imgs_per_split - 1) / P.imgs_per_split;
+    P.imgs_per_split = (int)((steps + nsplit - 1) / nsplit);
+    P.nsplit = (int)((steps + P.imgs_per_split - 1) / P.imgs_per_split);
 }
 
 int wgrad_slices(const Params& P) { return (P.chunks * P.nsplit + kWaves - 1) / kWaves; }
@@ -792,7 +1014,10 @@ void wgrad_partial(const Params& P, hipStream_t s) {
     const int mo = wgrad_mo(P);
     const dim3 grid((unsigned)wgrad_slices(P), (unsigned)(P.Gm * (P.Omp / (16 * mo)) * (P.Rp / 16)));
     const dim3 block(64 * kWaves);
-    if (P.KH == 3) {
+    if (P.rows) {
+        if (mo == 1) CANVAS_LAUNCH((k_wgrad_rows<1>), grid, block, 0, s, P);
+        else CANVAS_LAUNCH((k_wgrad_rows<2>), grid, block, 0, s, P);
+    } else if (P.KH == 3) {
         if (mo == 1) CANVAS_LAUNCH((k_wgrad<1, 3, 3>), grid, block, 0, s, P);
         else CANVAS_LAUNCH((k_wgrad<2, 3, 3>), grid, block, 0, s, P);
     } else {

@@ -30,7 +30,8 @@ struct Params {
     int ksplit = 1;                    // forward: wavefronts that share one tile and split its row chunks (1, 2, 4)
     int dst_f32 = 0, acc = 0;
     int nsplit = 1, chunks = 0, imgs_per_split = 0;  // weight gradient: work items = chunks (32-pixel positions) x nsplit (image ranges)
-    uint32_t magicW = 0, magicUpi = 0, magicW16 = 0;  // exact division by W, upi, and by the 16-byte pieces of a weight row
+    int rows = 0;                      // weight gradient by image rows: chunks = 32-column chunks of a row, ranges of (image, row) steps
+    uint32_t magicW = 0, magicUpi = 0, magicW16 = 0, magicH = 0;  // exact division by W, upi, the 16-byte pieces of a weight row, H
 };
 
 // Whether the fast path covers a contraction of this geometry (bf16 operands are the caller's business).

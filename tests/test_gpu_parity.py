@@ -304,6 +304,11 @@ UFC_VARIANTS = [
     (3, 3, "relu", [(0, -1, 0, 12)], "mul", False, 3, 48, 2, 24, 8, 16),           # 3 groups of 8 rows: the last merged pair is half empty
     (5, 5, "abs", [], "add", True, 1, 20, 1, 20, 9, 9),                             # groups of 4 rows: four merged, one left over
     (3, 2, "sin", [(0, 1, 0, 8)], "mul", False, 2, 16, 2, 16, 8, 8),                # a smooth unary outside the first four
+    # rows of 24 pixels and more: the 3x3 weight gradient walks down the image rows (one or two 32-column chunks)
+    (3, 2, "relu", [(0, 1, 0, 8)], "mul", False, 1, 16, 3, 16, 5, 25),              # odd width, one chunk, ragged 16-byte pieces at the row ends
+    (3, 8, "gelu", [], "add", False, 1, 32, 2, 64, 7, 48),                          # two chunks, groups of 8 rows merged in pairs
+    (3, 1, None, [(1, 0, 0, 40)], "mul", False, 2, 24, 2, 40, 3, 64),               # rows of exactly two chunks, 40 rows: 16 + 16 + 8
+    (3, 4, "abs", [], "add", False, 1, 8, 1, 32, 30, 31),                           # one image, odd width, more rows than steps per wavefront
     # weight tiles too large for LDS (> 72 KB per workgroup): the MFMA operands are read from memory directly
     (5, 1, "relu", [], "add", False, 1, 32, 2, 64, 9, 9),                           # 5x5 window on 64 rows: 32 x 25 x 64 weights per tile
     (1, 1, "abs", [(0, 1, 0, 512)], "mul", False, 1, 64, 1, 1024, 4, 8),            # 1024 channels: 64 x 1024 weights per tile
