@@ -999,13 +999,26 @@ void prepare_wgrad(Params& P) {
     const int64_t steps = P.rows ? (int64_t)P.N * P.H : P.N;
     const int64_t tiles = (int64_t)P.Gm * (P.Omp / (16 * wgrad_mo(P))) * (P.Rp / 16);
     const int64_t packed = packed_elems(P);
-    // about 3.5 k wavefronts; partials at most max(4 MB, 30 % of the operand bytes)
-    int64_t nsplit = std::max<int64_t>(1, std::min<int64_t>(steps, (3584 + P.chunks * tiles - 1) / (P.chunks * tiles)));
+    // about 3.5 k wavefronts (by rows: 2 k, measured); partials at most max(4 MB, 30 % of the operand bytes)
+    const int64_t waves = P.rows ? 2048 : 3584;
+    int64_t nsplit = std::max<int64_t>(1, std::min<int64_t>(steps, (waves + P.chunks * tiles - 1) / (P.chunks * tiles)));
     const int64_t operand_bytes = (int64_t)P.N * P.G * (P.R + P.Og) * P.P * 2;
     const int64_t cap = std::max<int64_t>((int64_t)4 << 20, operand_bytes * 3 / 10);
     nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, kWaves * cap / (packed * 4 * P.chunks)));
-    P.imgs_per_split = (int)((steps + nsplit - 1) / nsplit);
-    P.nsplit = (int)((steps + P.imgs_per_split - 1) / P.imgs_per_split);
+    int64_t per = (steps + nsplit - 1) / nsplit;
+    if (P.rows) {
+        // a range of steps that begins inside an image reloads its three rows: ranges are whole images, or the
+        // smallest divisor of the image height that is at least the number wanted, so that none straddles two images
+        if (per >= P.H) {
+            per = (per + P.H / 2) / P.H * P.H;
+        } else {
+            int64_t d = per;
+            while (P.H % d) d++;
+            per = d;
+        }
+    }
+    P.imgs_per_split = (int)per;
+    P.nsplit = (int)((steps + per - 1) / per);
 }
 
 int wgrad_slices(const Params& P) { return (P.chunks * P.nsplit + kWaves - 1) / kWaves; }
