@@ -666,10 +666,10 @@ void prepare_wgrad(Params& P) {
     const int64_t wnumel = (int64_t)P.G * P.Og * P.K;
     const int64_t tiles = (int64_t)P.G * P.otiles * P.ktiles;
     const int64_t steps = (int64_t)P.N * P.chunks32;
-    // at most 1024 slices per tile and about 4 k wavefronts in all (more, shorter slices measured slower);
+    // at most 2048 slices per tile and about 4 k wavefronts in all;
     // one partial per workgroup of kWaves slices, at most 8 MB of partials (16 MB measured slower: the
     // partials are written once and read once more by the sum)
-    int64_t slices = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(steps, 1024), (4096 + tiles - 1) / std::max<int64_t>(1, tiles)));
+    int64_t slices = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(steps, 2048), (4096 + tiles - 1) / std::max<int64_t>(1, tiles)));
     slices = std::max<int64_t>(1, std::min<int64_t>(slices, kWaves * (((int64_t)8 << 20) / std::max<int64_t>(1, wnumel * 4))));
     const int64_t per = std::max<int64_t>(1, (steps + slices - 1) / slices);
     P.per_slice = (int)per;

@@ -45,7 +45,7 @@ int choose_mo(int Og);
 // `rows` rows per group seen through a KH x KW window; the three `prepare_*` calls complete it for one launch kind.
 Params shape(int N, int G, int rows, int KH, int KW, int Og, int H, int W);
 void prepare_forward(Params& P);
-// Splits the N * ceil(P/32) pixel chunks over at most 1024 slices (one partial per four slices, at most 8 MB).
+// Splits the N * ceil(P/32) pixel chunks over at most 2048 slices per tile (one partial per four slices, at most 8 MB).
 void prepare_wgrad(Params& P);
 // Forward geometry -> geometry of the data gradient (rows and outputs swapped); use with transposed weights.
 Params data_gradient_of(const Params& fwd);
