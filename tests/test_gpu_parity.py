@@ -370,8 +370,14 @@ def test_config5_fuzz(harness, oracle, block):
             r.close()
 
 
-def test_backward_is_deterministic(harness):
-    case = wl.config4(64, 14, N=4)
+DETERMINISM_CASES = [lambda: wl.config4(64, 14, N=4), lambda: wl.config4(64, 56, N=2), lambda: wl.config4(128, 28, N=3),
+                     lambda: wl.config4(512, 7, N=8), lambda: wl.config3(N=2, H=28), lambda: wl.config2(N=2, H=56)]
+
+
+@pytest.mark.parametrize("idx", range(len(DETERMINISM_CASES)))
+def test_backward_is_deterministic(harness, idx):
+    """Two runs give the same bits: every reduction (split K, weight-gradient partials, their sums) has a fixed order."""
+    case = DETERMINISM_CASES[idx]()
     a, r1, dy = harness.run_case(case)
     b, r2, _ = harness.run_case(case, dy=dy)
     assert np.array_equal(a["dx"], b["dx"]) and np.array_equal(a["y"], b["y"])
