@@ -144,6 +144,37 @@ def cpu_baseline(case, budget_s=12.0):
                       f"gcc {' '.join(canvas_oracle.CFLAGS[:2])}, OpenMP over the batch index"}
 
 
+def copy_reference(args):
+    """A plain copy of one activation tensor of the workload, rotating over enough buffer pairs to stay cold."""
+    import torch
+
+    case = make_case(args.workload)
+    n = 1
+    for d in case["shape"]:
+        n *= d
+    esz = 2 if case["dtype"] == "bf16" else 4
+    sets = max(2, min(16, int(2 * (512 << 20) / (2 * n * esz)) + 1))
+    dt = torch.bfloat16 if esz == 2 else torch.float32
+    src = [torch.randn(n, device="cuda").to(dt) for _ in range(sets)]
+    dst = [torch.empty(n, device="cuda", dtype=dt) for _ in range(sets)]
+    for i in range(args.warmup):
+        dst[i % sets].copy_(src[i % sets])
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(ev):
+        a.record()
+        dst[i % sets].copy_(src[i % sets])
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in ev)
+    med = ms[len(ms) // 2]
+    print(json.dumps({"metric": "plain device copy (torch copy kernel), bytes read + written per second", "value": 2 * n * esz / med / 1e6,
+                      "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": med,
+                      "higher_is_better": True, "dtype": case["dtype"], "data": "synthetic",
+                      "config": {"workload": "copy of one activation tensor of " + args.workload, "bytes_in": n * esz, "bytes_out": n * esz,
+                                 "buffer_pairs": sets, "ms_min": ms[0]}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,11 +185,16 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--infer", type=int, default=0, metavar="BATCH",
                     help="instead of the training step: forward-only latency of the inference plan at this batch size")
+    ap.add_argument("--copy-ref", action="store_true",
+                    help="instead of a micro-DAG: the rate of a plain device copy of one activation tensor of the workload "
+                         "(torch's copy kernel, cold buffers), the reference that kernel times are compared with")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
     if args.infer:
         return infer_latency(args)
+    if args.copy_ref:
+        return copy_reference(args)
 
     import torch
 
