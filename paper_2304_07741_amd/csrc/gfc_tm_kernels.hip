@@ -875,26 +875,6 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad_rows(Params P) {
     }
 }
 
-// wp[gmi][op][tap][rp]: block-diagonal over the gm merged groups, zero in the padding
-__global__ void k_pack_weights(const uint16_t* __restrict__ w, uint16_t* __restrict__ wp, int G, int R, int Og, int TV, int gm, int Gm,
-                               int Rp, int Omp, int transposed) {
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    const long long total = (long long)Gm * Omp * TV * Rp;
-    if (i >= total) return;
-    const int rp = (int)(i % Rp);
-    long long t = i / Rp;
-    const int tap = (int)(t % TV);
-    t /= TV;
-    const int op = (int)(t % Omp), gmi = (int)(t / Omp);
-    const int sub = op / Og, o = op - sub * Og;
-    const int subr = rp / R, row = rp - subr * R;
-    const int g = gmi * gm + sub;
-    uint16_t v = 0;
-    if (sub < gm && subr == sub && g < G)
-        v = transposed ? w[(((long long)g * R + row) * Og + o) * TV + (TV - 1 - tap)] : w[(((long long)g * Og + o) * R + row) * TV + tap];
-    wp[i] = v;
-}
-
 // One tile per wavefront (KS = 1) or per KS wavefronts.  (Measured on MI355X: persistent wavefronts that
 // walk over several tiles and issue the next tile's first loads early, with or without cache-line
 // touches ahead, were not faster than letting the hardware scheduler balance one-tile workgroups; nor was
@@ -989,13 +969,6 @@ Params shape(int N, int G, int R, int KH, int KW, int Og, int H, int W) {
 }
 
 Params data_gradient_of(const Params& f) { return shape(f.N, f.G, f.Og, f.KH, f.KW, f.R, f.H, f.W); }
-
-void pack_weights(const uint16_t* w, uint16_t* wp, const Params& P, bool transposed, hipStream_t s) {
-    const long long total = packed_elems(P);
-    if (total > 0)
-        CANVAS_LAUNCH(k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, w, wp, P.G, P.R, P.Og, P.TV, P.gm, P.Gm, P.Rp,
-                      P.Omp, transposed ? 1 : 0);
-}
 
 // outputs per wavefront tile of the weight gradient, in units of 16 (its accumulators are MO x taps)
 static int wgrad_mo(const Params& P) { return P.KH == 3 && P.Omp % 32 == 0 ? 2 : 1; }

@@ -41,11 +41,12 @@ Params shape(int N, int G, int R, int KH, int KW, int Og, int H, int W);
 Params data_gradient_of(const Params& fwd);
 inline int64_t packed_elems(const Params& P) { return (int64_t)P.Gm * P.Omp * P.TV * P.Rp; }
 
-// wp <- w [G][Og][R][TV] (transposed: the FC's own weights [G][R][Og][TV], read with rows/outputs swapped and taps flipped)
-void pack_weights(const uint16_t* w, uint16_t* wp, const Params& P, bool transposed, hipStream_t s);
+// y = FC(src) on the packed weights P.wp (packed by a job of wprep_kernels.hpp; `transposed` there gives the data
+// gradient).  The weight tile of a workgroup goes through LDS where it fits (<= 72 KB).
 void forward(const Params& P, hipStream_t s);
 
-// Weight gradient of a windowed contraction (KH = KW = 3 or 5).  prepare_wgrad splits the work; the partials
+// Weight gradient of a windowed contraction (KH = KW = 3 or 5): by image rows for 3 x 3 windows on rows of 24 pixels
+// and more, else by 32-pixel positions.  prepare_wgrad chooses and splits the work; the partials
 // buffer holds wgrad_slices(P) * packed_elems(P) floats, one partial in the packed layout per workgroup; their
 // fixed-order sum into dw [G][Og][R][TV] (fp32) is a job of wreduce_kernels.hpp.
 void prepare_wgrad(Params& P);
