@@ -6,7 +6,7 @@
 namespace canvas {
 
 void emit_fc(Lowering& low, bool backward, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
-             bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32) {
+             bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32, bool softmax) {
     std::vector<Launch>& list = backward ? low.bwd : low.fwd;
     const int64_t nw = (int64_t)G * Og * R * kh * kw;
     if (!src.f32 && gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W)) {
@@ -37,6 +37,7 @@ void emit_fc(Lowering& low, bool backward, const Dag& dag, const TakeFn& take, c
                             Q.wp = identity ? (const uint16_t*)a.w[widx] : (const uint16_t*)(a.ws + opk);
                             Q.dst = const_cast<void*>(dst(a));
                             Q.dst_f32 = dst_f32 ? 1 : 0;
+                            Q.softmax = softmax ? 1 : 0;
                             Q.addend = addend_is_dst ? (const uint16_t*)dst(a) : nullptr;  // each lane reads the elements it then overwrites
                             gfctm::forward(Q, a.stream);
                         }});
@@ -68,6 +69,11 @@ void emit_fc(Lowering& low, bool backward, const Dag& dag, const TakeFn& take, c
                         Q.addend = addend_is_dst ? (const uint16_t*)dst(a) : nullptr;
                         gfc::forward(Q, a.stream);
                     }});
+}
+
+bool fc_softmax_fusable(const Dag& dag, int G, int R, int kh, int kw, int Og, const FcOperand& src) {
+    return !src.f32 && gfctm::supported(dag.N, G, R, kh, kw, Og, dag.H, dag.W) &&
+           gfctm::softmax_fusable(gfctm::shape(dag.N, G, R, kh, kw, Og, dag.H, dag.W));
 }
 
 void emit_wgrad(Lowering& low, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,

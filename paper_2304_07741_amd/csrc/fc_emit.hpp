@@ -21,10 +21,13 @@ struct FcOperand {
 // y = FC(src) (forward), or, with `transposed`, the data gradient src = dy -> dst = d(source of the FC):
 // then (R, Og) are the swapped dims and the FC's own weights [G][R][Og][taps] are read transposed with the
 // taps flipped.  `addend_is_dst`: dst (bf16) already holds a tensor that the result is added to.
-// dst is bf16 unless dst_f32.
+// dst is bf16 unless dst_f32.  softmax (see fc_softmax_fusable): dst receives the softmax over the outputs of each pixel.
 // The launch goes to low.fwd or (backward) low.bwd; derived weight copies are registered in low.wjobs.
 void emit_fc(Lowering& low, bool backward, const Dag& dag, const TakeFn& take, const std::string& name, int G, int R, int kh, int kw, int Og,
-             bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32 = false);
+             bool transposed, int widx, FcOperand src, PtrFn dst, bool addend_is_dst, double bytes, double flops, bool dst_f32 = false,
+             bool softmax = false);
+// Whether emit_fc can be asked (softmax = true, dst_f32) for the softmax over the FC's outputs instead of the outputs.
+bool fc_softmax_fusable(const Dag& dag, int G, int R, int kh, int kw, int Og, const FcOperand& src);
 
 // dw[widx] = sum over (image, pixel) of dy (x) rows of src (through the window kh x kw): the kernel that writes
 // one partial per workgroup goes to low.bwd, the fixed-order sum of the partials is registered in low.rjobs.

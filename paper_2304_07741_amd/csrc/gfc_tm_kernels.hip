@@ -49,8 +49,14 @@ extern __shared__ __align__(16) unsigned char lds_dyn[];
 // read from there.  Read straight from memory, an A operand load touches 16 lines for 512 bytes, and those
 // loads were a third of the kernel time of the many-channel shapes.  Rows are padded by 16 bytes in LDS: the
 // 16 rows that one read touches then fall into different banks.
-template <int MO, int KH, int KW, bool DST_F32, int KS, bool WL>
+// SM (16 outputs at most, fp32 result, no window): the result is the softmax over the outputs of each pixel instead
+// of the sums themselves -- the per-pixel window weights of an Involution-like kernel (Section 5 of the paper) are
+// an FC followed by a softmax over its few channels, and the softmax alone was a launch as long as the FC.  One
+// wavefront of the tile then collects all of its sums (they are 4 x 8 values per lane), the outputs of a pixel sit
+// in the lanes 16 and 32 apart, and maximum and sum cross them by lane exchanges.
+template <int MO, int KH, int KW, bool DST_F32, int KS, bool WL, bool SM = false>
 __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
+    static_assert(!SM || (MO == 1 && KH == 1 && KW == 1 && DST_F32), "softmax epilogue: one output tile, fp32, no window");
     constexpr int TV = KH * KW, HW = KW / 2, HH = KH / 2;
     constexpr bool HALO = KW > 1;
     constexpr int ND = HALO ? 6 : 4;   // dwords per row
@@ -252,9 +258,9 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
 
     // Output rows of the tile as T = 4 * MO "row slots" t = 4 * mo + j (output 16 * mo + 4 * r + j of this lane, 8 pixels
     // each); this wavefront finishes the TF slots from t0 on (all of them when KS == 1, see below).
-    constexpr int T = 4 * MO, TF = T / KS;
+    constexpr int T = 4 * MO, TF = SM ? T : T / KS;
     static_assert(T % KS == 0, "row slots divide among the wavefronts of a tile");
-    const int t0 = KS > 1 ? ks * TF : 0;
+    const int t0 = KS > 1 && !SM ? ks * TF : 0;
     const int nvalid = min(8, P.P - p);
     const int outs_img = P.G * P.Og;
     const int dst_elems = P.N * outs_img * P.P;
@@ -300,7 +306,30 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     // through LDS, so each finisher adds its partners' sums in the fixed order own, w-1, w-2, ... and the
     // additions and stores of a tile are spread over its KS wavefronts.
     float fin[TF][8];
-    if constexpr (KS == 1) {
+    if constexpr (SM && KS > 1) {
+        // the first wavefront of the tile adds its partners' sums in the fixed order 1, 2, ... and finishes all rows
+        typedef float Red[KS - 1][T * 8][64];
+        Red* red = reinterpret_cast<Red*>(lds_dyn);
+        if constexpr (WL) __syncthreads();
+        const int sub = wave / KS;
+        if (ks > 0) {
+#pragma unroll
+            for (int i = 0; i < T; i++)
+#pragma unroll
+                for (int q = 0; q < 8; q++) red[sub][ks - 1][i * 8 + q][lane] = acc[i >> 2][q][i & 3];
+        }
+        __syncthreads();
+        if (ks > 0) return;
+#pragma unroll
+        for (int i = 0; i < T; i++)
+#pragma unroll
+            for (int q = 0; q < 8; q++) {
+                float t = acc[i >> 2][q][i & 3];
+#pragma unroll
+                for (int d = 0; d < KS - 1; d++) t += red[sub][d][i * 8 + q][lane];
+                fin[i][q] = t;
+            }
+    } else if constexpr (KS == 1) {
 #pragma unroll
         for (int i = 0; i < TF; i++)
 #pragma unroll
@@ -339,6 +368,30 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         }
     }
     if (!live) return;
+    if constexpr (SM) {
+        // row slot i of lane (r, s) is output 4r + i of the unit's pixels: the Om outputs of a pixel are spread over the
+        // lanes r = 0..3 of the same s (16 and 32 lanes apart)
+#pragma unroll
+        for (int q = 0; q < 8; q++) {
+            float m = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < T; i++)
+                if (4 * r + i < Om) m = fmaxf(m, fin[i][q]);
+            m = fmaxf(m, __shfl_xor(m, 16));
+            m = fmaxf(m, __shfl_xor(m, 32));
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < T; i++) {
+                fin[i][q] = 4 * r + i < Om ? expf(fin[i][q] - m) : 0.f;
+                sum += fin[i][q];
+            }
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+            const float inv = 1.f / sum;
+#pragma unroll
+            for (int i = 0; i < T; i++) fin[i][q] *= inv;
+        }
+    }
     const rsrc_t rd = make_rsrc(P.dst, dst_elems * (DST_F32 ? 4 : 2));
     // What the rows are added to is read, four rows at a time, before any of the four is stored: loads that
     // follow a store to the same tensor are not moved ahead of it, and would cost a memory round trip per row.
@@ -892,6 +945,20 @@ void launch_fwd_w(const Params& P, unsigned lds_w, hipStream_t s) {
     else CANVAS_LAUNCH((k_fwd<MO, KH, KW, DST_F32, 1, WL>), dim3((unsigned)((tiles + kWaves - 1) / kWaves), gy), block, lds, s, P);
 }
 
+// FC + softmax over its (at most 16) outputs: one output tile, fp32 result, no window
+template <bool WL>
+void launch_fwd_softmax_w(const Params& P, unsigned lds_w, hipStream_t s) {
+    const int tiles = (P.N * P.upi + 15) / 16;
+    const dim3 block(64 * kWaves);
+    const unsigned gy = (unsigned)(P.Gm * P.otiles);
+    // the partners' sums: kWaves / KS tiles x (KS - 1) wavefronts x 4 row slots x 8 pixels x 64 lanes, fp32
+    const unsigned red = P.ksplit > 1 ? (unsigned)(kWaves / P.ksplit * (P.ksplit - 1) * 32 * 64 * 4) : 0u;
+    const unsigned lds = std::max(lds_w, red);
+    if (P.ksplit == 4) CANVAS_LAUNCH((k_fwd<1, 1, 1, true, 4, WL, true>), dim3((unsigned)tiles, gy), block, lds, s, P);
+    else if (P.ksplit == 2) CANVAS_LAUNCH((k_fwd<1, 1, 1, true, 2, WL, true>), dim3((unsigned)((tiles + 1) / 2), gy), block, lds, s, P);
+    else CANVAS_LAUNCH((k_fwd<1, 1, 1, true, 1, WL, true>), dim3((unsigned)((tiles + kWaves - 1) / kWaves), gy), block, lds, s, P);
+}
+
 template <int MO, int KH, int KW, bool DST_F32>
 void launch_fwd_k(const Params& P, hipStream_t s) {
     // the weight tile of a workgroup goes through LDS where two workgroups' tiles fit a compute unit
@@ -1021,8 +1088,16 @@ void wgrad_partial(const Params& P, hipStream_t s) {
     }
 }
 
+bool softmax_fusable(const Params& P) { return P.G == 1 && P.Og <= 16 && P.KH == 1 && P.KW == 1; }
+
 void forward(const Params& P, hipStream_t s) {
     if ((int64_t)P.N * P.G * P.Og * P.P == 0) return;
+    if (P.softmax) {  // (the caller has checked softmax_fusable and set dst_f32)
+        const unsigned lds_w = 16u * (unsigned)(P.TV * P.Rp * 2 + 16);
+        if (lds_w <= 72u * 1024u) launch_fwd_softmax_w<true>(P, lds_w, s);
+        else launch_fwd_softmax_w<false>(P, 0u, s);
+        return;
+    }
     if (P.dst_f32) {
         switch (P.mo) {
         case 1: launch_fwd<1, true>(P, s); break;

@@ -29,6 +29,7 @@ struct Params {
     int mo = 1, otiles = 1;            // 16*mo outputs per wavefront, Omp = 16*mo*otiles
     int ksplit = 1;                    // forward: wavefronts that share one tile and split its row chunks (1, 2, 4)
     int dst_f32 = 0, acc = 0;
+    int softmax = 0;                   // forward: the result is the softmax over the outputs of each pixel (see softmax_fusable)
     int nsplit = 1, chunks = 0, imgs_per_split = 0;  // weight gradient: work items = chunks (32-pixel positions) x nsplit (image ranges)
     int rows = 0;                      // weight gradient by image rows: chunks = 32-column chunks of a row, ranges of (image, row) steps
     uint32_t magicW = 0, magicUpi = 0, magicW16 = 0, magicH = 0;  // exact division by W, upi, the 16-byte pieces of a weight row, H
@@ -44,6 +45,9 @@ inline int64_t packed_elems(const Params& P) { return (int64_t)P.Gm * P.Omp * P.
 // y = FC(src) on the packed weights P.wp (packed by a job of wprep_kernels.hpp; `transposed` there gives the data
 // gradient).  The weight tile of a workgroup goes through LDS where it fits (<= 72 KB).
 void forward(const Params& P, hipStream_t s);
+// Whether forward can apply a softmax over the outputs of each pixel to its result (P.softmax = 1, fp32 destination):
+// one group, at most 16 outputs, no window.
+bool softmax_fusable(const Params& P);
 
 // Weight gradient of a windowed contraction (KH = KW = 3 or 5): by image rows for 3 x 3 windows on rows of 24 pixels
 // and more, else by 32-pixel positions.  prepare_wgrad chooses and splits the work; the partials

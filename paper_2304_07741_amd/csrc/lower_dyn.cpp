@@ -111,8 +111,11 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
     const FcOperand in_x{[](const RunArgs& a) { return a.x; }, false};
     const FcOperand in_dy{[](const RunArgs& a) { return a.dy; }, false};
 
-    emit_fc(*low, false, dag, take, "dyn_fc1", G1, C / G1, 1, 1, TVa / G1, false, w1, in_x, ws_at(ol), false, act + ab + 2.0 * nw1, fl1, true);
-    if (soft)
+    // the softmax over the few channels of FC1 is the epilogue of FC1 where all of them are in one tile
+    const bool sm_in_fc1 = soft && fc_softmax_fusable(dag, G1, C / G1, 1, 1, TVa / G1, in_x);
+    emit_fc(*low, false, dag, take, sm_in_fc1 ? "dyn_fc1_softmax" : "dyn_fc1", G1, C / G1, 1, 1, TVa / G1, false, w1, in_x,
+            ws_at(sm_in_fc1 ? oa : ol), false, act + ab + 2.0 * nw1, fl1, true, sm_in_fc1);
+    if (soft && !sm_in_fc1)
         low->fwd.push_back({"dyn_softmax", 2.0 * ab, 0, [=](const RunArgs& a) {
                                 ref::softmax_fwd((const float*)(a.ws + ol), (float*)(a.ws + oa), N, TVa, 1, Pn, 1, a.stream);
                             }});
