@@ -101,6 +101,9 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
     const int64_t ol = take((uint64_t)ab), oa = isoft >= 0 ? take((uint64_t)ab) : ol;  // logits, softmax output (fp32)
     const int64_t ou = take((uint64_t)act), odu = take((uint64_t)act);
     const int64_t oda = take((uint64_t)ab), odl = isoft >= 0 ? take((uint64_t)ab) : oda;
+    // the gradient of the logits once more in bf16: the data gradient of FC1 then runs on the bf16 MFMA kernel (its
+    // result is rounded to bf16 anyway); the weight gradient keeps the fp32 copy
+    const int64_t odl16 = isoft >= 0 ? take((uint64_t)(ab / 2)) : -1;
     const int w1 = fc1.widx, w2 = fc2.widx;
     const int64_t nw1 = (int64_t)TVa * (C / G1), nw2 = (int64_t)O2 * (C / G2);
     const double fl1 = 2.0 * dag.N * Pn * (double)nw1, fl2 = 2.0 * dag.N * Pn * (double)nw2;
@@ -149,11 +152,12 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
     if (soft)
         low->bwd.push_back({"dyn_softmax_bwd", 3.0 * ab, 0, [=](const RunArgs& a) {
                                 ref::softmax_bwd((const float*)(a.ws + oa), (const float*)(a.ws + oda), (float*)(a.ws + odl), N, TVa, 1, Pn, 1, 0,
-                                                 a.stream);
+                                                 a.stream, (uint16_t*)(a.ws + odl16));
                             }});
     emit_wgrad(*low, dag, take, "dyn_fc1_wgrad", G1, C / G1, 1, 1, TVa / G1, w1, in_x, FcOperand{ws_at(odl), true}, act + ab, fl1);
     // the data gradient of FC1 adds to the dx that dyn_apply_dx has written
-    emit_fc(*low, true, dag, take, "dyn_fc1_dgrad", G1, TVa / G1, 1, 1, C / G1, true, w1, FcOperand{ws_at(odl), true},
+    emit_fc(*low, true, dag, take, "dyn_fc1_dgrad", G1, TVa / G1, 1, 1, C / G1, true, w1,
+            soft ? FcOperand{ws_at(odl16), false} : FcOperand{ws_at(odl), true},
             [](const RunArgs& a) { return (const void*)a.dx; }, true, 2.0 * act + ab + 2.0 * nw1, fl1);
     low->ws_bytes = off;
     return low;

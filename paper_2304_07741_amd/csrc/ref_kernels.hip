@@ -319,8 +319,9 @@ __global__ void k_softmax_fwd(const float* __restrict__ in, float* __restrict__ 
     for (int k = 0; k < len; k++) out[base + k * stride] = expf(in[base + k * stride] - m) * inv;
 }
 
+// gin16 (optional): the result once more, rounded to bf16 (for a consumer that takes bf16 operands)
 __global__ void k_softmax_bwd(const float* __restrict__ y, const float* __restrict__ gout, float* __restrict__ gin,
-                              int64_t total, int C, int T, int P, int axis_c, int acc) {
+                              uint16_t* __restrict__ gin16, int64_t total, int C, int T, int P, int axis_c, int acc) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
     int p = (int)(i % P);
@@ -357,8 +358,10 @@ __global__ void k_softmax_bwd(const float* __restrict__ y, const float* __restri
 #pragma unroll
         for (int k = 0; k < kSoftmaxRegs; k++)
             if (k < len) {
-                const float g = yv[k] * (gv[k] - dot);
-                gin[base + k * stride] = acc ? gin[base + k * stride] + g : g;
+                float g = yv[k] * (gv[k] - dot);
+                if (acc) g += gin[base + k * stride];
+                gin[base + k * stride] = g;
+                if (gin16) gin16[base + k * stride] = f32_to_bf16(g);
             }
         return;
     }
@@ -366,7 +369,9 @@ __global__ void k_softmax_bwd(const float* __restrict__ y, const float* __restri
     for (int k = 0; k < len; k++) dot = fmaf(gout[base + k * stride], y[base + k * stride], dot);
     for (int k = 0; k < len; k++) {
         float g = y[base + k * stride] * (gout[base + k * stride] - dot);
-        gin[base + k * stride] = acc ? gin[base + k * stride] + g : g;
+        if (acc) g += gin[base + k * stride];
+        gin[base + k * stride] = g;
+        if (gin16) gin16[base + k * stride] = f32_to_bf16(g);
     }
 }
 
@@ -587,9 +592,9 @@ void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, in
     LAUNCH(k_softmax_fwd, total, in, out, total, C, T, P, axis_c);
 }
 void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C, int T, int P, int axis_c, int acc,
-                 hipStream_t s) {
+                 hipStream_t s, uint16_t* gin16) {
     int64_t total = N * (axis_c == 2 ? 1 : (axis_c ? T : C)) * P;
-    LAUNCH(k_softmax_bwd, total, y, gout, gin, total, C, T, P, axis_c, acc);
+    LAUNCH(k_softmax_bwd, total, y, gout, gin, gin16, total, C, T, P, axis_c, acc);
 }
 void fold_fwd(const float* in, float* out, int64_t NC, int T, int P, int kind, hipStream_t s) {
     int64_t total = NC * P;

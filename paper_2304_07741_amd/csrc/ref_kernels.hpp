@@ -32,8 +32,9 @@ void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float
                     int PL, int rep, int Wd, int kind, int acc, hipStream_t s);
 // axis_c: 1 = over channels, 0 = over taps, 2 = over both jointly
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s);
+// gin16 (optional): the same result once more, rounded to bf16
 void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C, int T, int P, int axis_c, int acc,
-                 hipStream_t s);
+                 hipStream_t s, uint16_t* gin16 = nullptr);
 void fold_fwd(const float* in, float* out, int64_t NC, int T, int P, int kind, hipStream_t s);
 void fold_bwd(const float* in, const float* gout, float* gin, int64_t NC, int T, int P, int kind, int acc, hipStream_t s);
 // Fold over the Cg channels of each of NG (image, group) pairs; a channel is TP = taps * pixels elements
