@@ -466,6 +466,49 @@ def test_inference_forward_replays_from_a_hip_graph(harness, which):
         r.close()
 
 
+@pytest.mark.parametrize("which", ["config2", "config3", "config4", "config4_rows"])
+def test_training_step_replays_from_a_hip_graph(harness, which):
+    """Forward and backward of a training plan are fixed lists of kernel launches too: a captured HIP graph of the
+    step gives the eager y, dx and dW (bit for bit: every reduction has a fixed order) on every replay, with
+    other work and new inputs between the replays."""
+    import torch
+
+    case = {"config2": lambda: wl.config2(N=4, H=28), "config3": lambda: wl.config3(N=2, H=14),
+            "config4": lambda: wl.config4(256, 14, N=4), "config4_rows": lambda: wl.config4(64, 28, N=2)}[which]()
+    r = harness.DagRunner(case["blob"], case["shape"], case["dtype"])
+    try:
+        rng = np.random.default_rng(5)
+        dy = rng.standard_normal(tuple(r.dy.shape)).astype(np.float32)
+        r.load(case["x"], case["weights"], dy)
+        r.forward()
+        r.backward()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            r.forward()
+            r.backward()
+            with torch.cuda.graph(g, stream=side):
+                r.forward()
+                r.backward()
+        torch.cuda.synchronize()
+        for rep in range(3):
+            r.x.copy_(torch.roll(r.x, rep + 1, dims=0) * (1.0 + 0.25 * rep))  # eager work on new inputs
+            r.dy.copy_(torch.roll(r.dy, rep + 1, dims=1))
+            r.forward()
+            r.backward()
+            want = [r.y.clone(), r.dx.clone()] + [t.clone() for t in r.dw]
+            r.poison_outputs()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for k, (got, w) in enumerate(zip([r.y, r.dx, *r.dw], want)):
+                assert torch.equal(got, w), f"replay {rep}, tensor {k}"
+    finally:
+        r.close()
+
+
 @pytest.mark.parametrize("which", ["shape_matching", "constraints"])
 def test_template_to_executor_end_to_end(harness, oracle, which):
     """A kernel template goes through the two solvers, is instantiated for two replacement targets and each
