@@ -126,21 +126,15 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const bool near_ends = (n_first * rows_img + grow0) * P.P - maxoff < 0 ||
                            (n_last * rows_img + grow0 + P.Rp) * P.P + 16 + maxoff > src_elems;
 
-    // vertical validity of the source pixels -2..9 of this lane's unit, per window row; horizontal
+    // vertical validity of the source pixels -2..9 of this lane's unit, per window row (below); horizontal
     // validity of the output pixels 0..7, per window column
-    uint32_t rm[KH][ND];
+    // (rows: only whether any lane of the wavefront needs a mask is kept; the masks themselves are built where they
+    // are applied, in the few tiles that touch the first or last image rows)
     bool needrow[KH];
 #pragma unroll
     for (int kh = 0; kh < KH; kh++) {
-        bool any = false;
-#pragma unroll
-        for (int k = 0; k < ND; k++) {
-            const int i = 2 * k - E0;
-            const bool lo = (unsigned)(p + i + (kh - HH) * P.W) < (unsigned)P.P;
-            const bool hi = (unsigned)(p + i + 1 + (kh - HH) * P.W) < (unsigned)P.P;
-            rm[kh][k] = (lo ? 0x0000ffffu : 0u) | (hi ? 0xffff0000u : 0u);
-            any = any || !lo || !hi;
-        }
+        const int dk = (kh - HH) * P.W;
+        const bool any = p - E0 + dk < 0 || p + 2 * ND - E0 - 1 + dk >= P.P;
         needrow[kh] = kh != HH && __builtin_amdgcn_ballot_w64(any) != 0;
     }
     uint32_t cm[8][KW];
@@ -229,9 +223,13 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         }
         if (needrow[kh]) {
 #pragma unroll
-            for (int j = 0; j < 4; j++)
+            for (int k = 0; k < ND; k++) {
+                const int i = 2 * k - E0 + (kh - HH) * P.W;
+                const bool lo = (unsigned)(p + i) < (unsigned)P.P, hi = (unsigned)(p + i + 1) < (unsigned)P.P;
+                const uint32_t m = (lo ? 0x0000ffffu : 0u) | (hi ? 0xffff0000u : 0u);
 #pragma unroll
-                for (int k = 0; k < ND; k++) b.d[j][k] &= rm[kh][k];
+                for (int j = 0; j < 4; j++) b.d[j][k] &= m;
+            }
         }
         // operand of source pixel i = t - E0: rows 4r..4r+3 of that pixel
         u32x2 op[2 * ND];
