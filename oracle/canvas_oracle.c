@@ -16,6 +16,15 @@
  * per-image, Section 4); only the FC weight gradients sum over the batch.
  * The only parallelism is an OpenMP loop over the batch index.
  *
+ * Tie margin (a device of the comparison rule, not of the method): the backward
+ * rules decide at kinks (relu, abs, the clip bounds, min / max, the arg-max of a
+ * max fold) and fp32 kernels resolve near-ties differently from fp64.  With
+ * canvas_oracle_set_tie_margin(m), m != 0, those decisions move by |m| times the
+ * largest magnitude of the deciding tensor (per image): m < 0 and m > 0 bracket
+ * the default m = 0, which is the definition itself (first maximum, relu'(0) = 0,
+ * sign(0) = 0, ties of min / max to the LHS) and the only setting the pins use.
+ * The forward pass never depends on it.
+ *
  * Parity pins (see tests/test_oracle_*.py): brute-force direct (grouped)
  * convolution and its gradients, adjoint dot-product identities, central
  * finite differences, closed forms and invariants.  No function here is
@@ -91,6 +100,18 @@ typedef struct {
     int H, W;
     Node node[MAX_NODES];
 } Dag;
+
+/* 0 = the definitions; see "Tie margin" above.  Set before a run, read-only during it. */
+static double g_tie_margin = 0.0;
+void canvas_oracle_set_tie_margin(double m) { g_tie_margin = m; }
+
+static double max_abs(const double *v, size_t n) {
+    double s = 0.0;
+    size_t j;
+    for (j = 0; j < n; j++)
+        if (fabs(v[j]) > s) s = fabs(v[j]);
+    return s;
+}
 
 static void set_err(char *err, size_t errlen, const char *msg, int line) {
     if (err && errlen) snprintf(err, errlen, "line %d: %s", line, msg);
@@ -652,13 +673,15 @@ static void bwd_fc(const Dag *d, const Node *nd, const double *in, const double 
 
 static void bwd_unary(const Dag *d, const Node *nd, int k, const double *in, const double *out, const double *gout, double *gin) {
     size_t n = node_numel(d, k), j;
+    /* e = 0 unless a tie margin is set: then the kink moves by e */
+    double e = g_tie_margin != 0.0 ? g_tie_margin * max_abs(in, n) : 0.0;
     for (j = 0; j < n; j++) {
         double x = in[j], dv = 0.0;
         switch (nd->kind) {
-        case UN_RELU: dv = x > 0.0 ? 1.0 : 0.0; break;
-        case UN_ABS: dv = x > 0.0 ? 1.0 : (x < 0.0 ? -1.0 : 0.0); break;
+        case UN_RELU: dv = x > e ? 1.0 : 0.0; break;
+        case UN_ABS: dv = x > e ? 1.0 : (x < e ? -1.0 : 0.0); break;
         case UN_GELU: dv = gelu_cdf(x) + x * gelu_pdf(x); break;
-        case UN_EXPCLIP: dv = (x > nd->lo && x < nd->hi) ? out[j] : 0.0; break;
+        case UN_EXPCLIP: dv = (x > nd->lo + e && x < nd->hi - e) ? out[j] : 0.0; break;
         case UN_SIN: dv = cos(x); break;
         }
         gin[j] += gout[j] * dv;
@@ -668,6 +691,11 @@ static void bwd_unary(const Dag *d, const Node *nd, int k, const double *in, con
 static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const double *rhs, const double *gout, double *glhs, double *grhs) {
     const Node *L = &d->node[nd->a];
     int P = node_P(d, nd), PL = node_P(d, L), c, t, p, cl, tl;
+    double e = 0.0;  /* tie margin of min / max: 0 = the definition (ties to the LHS) */
+    if (g_tie_margin != 0.0 && (nd->kind == BIN_MIN || nd->kind == BIN_MAX)) {
+        double sl = max_abs(lhs, (size_t)L->C * L->T * PL), sr = max_abs(rhs, (size_t)nd->C * nd->T * P);
+        e = g_tie_margin * (sl > sr ? sl : sr);
+    }
     for (c = 0; c < nd->C; c++)
         for (t = 0; t < nd->T; t++) {
             size_t ro = ((size_t)c * nd->T + t) * P, lo;
@@ -682,8 +710,8 @@ static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
                 case BIN_ADD: glhs[lp] += g; grhs[ro + p] += g; break;
                 case BIN_MUL: glhs[lp] += g * b; grhs[ro + p] += g * a; break;
                 case BIN_SUB: glhs[lp] += g; grhs[ro + p] -= g; break;
-                case BIN_MIN: if (a <= b) glhs[lp] += g; else grhs[ro + p] += g; break;
-                case BIN_MAX: if (a >= b) glhs[lp] += g; else grhs[ro + p] += g; break;
+                case BIN_MIN: if (a <= b + e) glhs[lp] += g; else grhs[ro + p] += g; break;
+                case BIN_MAX: if (a >= b - e) glhs[lp] += g; else grhs[ro + p] += g; break;
                 }
             }
         }
@@ -707,10 +735,12 @@ static void bwd_softmax(const Dag *d, const Node *nd, const double *out, const d
         }
 }
 
-/* Max takes the gradient to the first maximal tap (lowest t) only. */
+/* Max takes the gradient to the first maximal tap (lowest t) only.  With a tie margin e != 0 every element
+ * within |e| of the maximum counts as maximal, and e < 0 takes the first, e > 0 the last of them. */
 static void bwd_fold(const Dag *d, const Node *nd, const double *in, const double *gout, double *gin) {
     const Node *A = &d->node[nd->a];
     int P = node_P(d, A), T = A->T, c, t, p;
+    double e = (g_tie_margin != 0.0 && nd->kind == FOLD_MAX) ? g_tie_margin * max_abs(in, (size_t)A->C * T * P) : 0.0;
     if (nd->axis_c) {  /* max: to the first maximal channel of the group only */
         int Cg = A->C / nd->groups, g;
         for (g = 0; g < nd->groups; g++)
@@ -721,6 +751,11 @@ static void bwd_fold(const Dag *d, const Node *nd, const double *in, const doubl
                         int best = 0;
                         for (c = 1; c < Cg; c++)
                             if (in[(((size_t)g * Cg + c) * T + t) * P + p] > in[(((size_t)g * Cg + best) * T + t) * P + p]) best = c;
+                        if (e != 0.0) {
+                            double m = in[(((size_t)g * Cg + best) * T + t) * P + p] - fabs(e);
+                            if (e < 0.0) { for (c = 0; c < Cg; c++) if (in[(((size_t)g * Cg + c) * T + t) * P + p] >= m) { best = c; break; } }
+                            else { for (c = Cg - 1; c >= 0; c--) if (in[(((size_t)g * Cg + c) * T + t) * P + p] >= m) { best = c; break; } }
+                        }
                         gin[(((size_t)g * Cg + best) * T + t) * P + p] += gg;
                     } else {
                         if (nd->kind == FOLD_AVG) gg /= Cg;
@@ -742,6 +777,19 @@ static void bwd_fold(const Dag *d, const Node *nd, const double *in, const doubl
                         for (h = h0; h < h1; h++)
                             for (w = w0; w < w1; w++)
                                 if (in[((size_t)c * Hi + h) * Wi + w] > in[best]) best = ((size_t)c * Hi + h) * Wi + w;
+                        if (e != 0.0) {
+                            double m = in[best] - fabs(e);
+                            int found = 0;
+                            if (e < 0.0) {
+                                for (h = h0; h < h1 && !found; h++)
+                                    for (w = w0; w < w1 && !found; w++)
+                                        if (in[((size_t)c * Hi + h) * Wi + w] >= m) { best = ((size_t)c * Hi + h) * Wi + w; found = 1; }
+                            } else {
+                                for (h = h1 - 1; h >= h0 && !found; h--)
+                                    for (w = w1 - 1; w >= w0 && !found; w--)
+                                        if (in[((size_t)c * Hi + h) * Wi + w] >= m) { best = ((size_t)c * Hi + h) * Wi + w; found = 1; }
+                            }
+                        }
                         gin[best] += g;
                     } else {
                         if (nd->kind == FOLD_AVG) g /= (double)((h1 - h0) * (w1 - w0));
@@ -758,6 +806,11 @@ static void bwd_fold(const Dag *d, const Node *nd, const double *in, const doubl
                 int best = 0;
                 for (t = 1; t < T; t++)
                     if (in[((size_t)c * T + t) * P + p] > in[((size_t)c * T + best) * P + p]) best = t;
+                if (e != 0.0) {
+                    double m = in[((size_t)c * T + best) * P + p] - fabs(e);
+                    if (e < 0.0) { for (t = 0; t < T; t++) if (in[((size_t)c * T + t) * P + p] >= m) { best = t; break; } }
+                    else { for (t = T - 1; t >= 0; t--) if (in[((size_t)c * T + t) * P + p] >= m) { best = t; break; } }
+                }
                 gin[((size_t)c * T + best) * P + p] += g;
             } else {
                 if (nd->kind == FOLD_AVG) g /= T;

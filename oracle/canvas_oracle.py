@@ -30,6 +30,7 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         lib.canvas_oracle_infer.restype = ctypes.c_int
         lib.canvas_oracle_run.restype = ctypes.c_int
+        lib.canvas_oracle_set_tie_margin.restype = None
         _lib = lib
     return _lib
 
@@ -56,8 +57,12 @@ def infer(blob, in_shape):
     return ns, out_node.value, ws
 
 
-def run(blob, x, weights, dy=None, n_threads=0):
+def run(blob, x, weights, dy=None, n_threads=0, tie_margin=0.0):
     """Run the DAG on fp64 copies of the inputs.
+
+    tie_margin: 0 = the definitions; a non-zero value moves every backward decision point (relu, abs, clip
+    bounds, min / max, arg-max of a max fold) by that fraction of the deciding tensor's largest magnitude
+    (see the C file), which the comparison rule of the tests uses to bracket near-ties.
 
     x: [N,C,H,W]; weights: list of [G,Og,K]; dy: like the output or None.
     Returns dict(y=[N,C,T,H,W] squeezed to [N,C,H,W] when T==1, dx, dw=list, threads).
@@ -93,10 +98,18 @@ def run(blob, x, weights, dy=None, n_threads=0):
             dwarr[k] = d.ctypes.data_as(dbl_p)
     shp = (ctypes.c_int64 * 4)(*x.shape)
     err = ctypes.create_string_buffer(256)
-    rc = lib.canvas_oracle_run(b, ctypes.c_size_t(len(b)), shp, x.ctypes.data_as(dbl_p), warr, len(wl), dy_p,
-                               y.ctypes.data_as(dbl_p), dx_p, dwarr, int(n_threads), err, ctypes.c_size_t(256))
+    lib.canvas_oracle_set_tie_margin(ctypes.c_double(float(tie_margin)))
+    try:
+        rc = _call_run(lib, b, shp, x, warr, wl, dy_p, y, dx_p, dwarr, n_threads, err, dbl_p)
+    finally:
+        lib.canvas_oracle_set_tie_margin(ctypes.c_double(0.0))
     if rc < 0:
         raise OracleError(err.value.decode())
     if T == 1:
         y = y.reshape(N, C, H, W)
     return {"y": y, "dx": dx, "dw": dwl, "threads": rc}
+
+
+def _call_run(lib, b, shp, x, warr, wl, dy_p, y, dx_p, dwarr, n_threads, err, dbl_p):
+    return lib.canvas_oracle_run(b, ctypes.c_size_t(len(b)), shp, x.ctypes.data_as(dbl_p), warr, len(wl), dy_p,
+                               y.ctypes.data_as(dbl_p), dx_p, dwarr, int(n_threads), err, ctypes.c_size_t(256))

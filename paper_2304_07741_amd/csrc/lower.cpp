@@ -6,13 +6,25 @@
 
 namespace canvas {
 
+constexpr int64_t kMinWeightElemsForBf16Intermediates = 16;
+
 std::unique_ptr<Lowering> lower(const Dag& full, bool bf16, bool no_fusion) {
     const Dag dag = without_dead_views(full);
     std::unique_ptr<Lowering> l;
     if (!no_fusion) {
         l = lower_sgfc(dag, bf16);
-        if (!l) l = lower_ufc(dag, bf16);
-        if (!l) l = lower_dyn(dag, bf16);
+        // The two lowerings below keep C-channel intermediates in bf16 (rounding 2^-9 per element).  An element of
+        // dW is a sum over all pixels whose terms can cancel; with many elements the largest one, which sets the
+        // max-norm tolerance, is no cancelled sum, but a weight tensor of a few scalars has no such element.
+        // Such DAGs keep fp32 intermediates (the lowering by segments).
+        bool tiny_weight = false;
+        for (int i = 0; i < dag.n_weights; i++) {
+            const Node& f = dag.nodes[dag.weight_node[i]];
+            const Node& A = dag.nodes[f.a];
+            if (f.live && (int64_t)f.out * (A.C / f.groups) * A.T < kMinWeightElemsForBf16Intermediates) tiny_weight = true;
+        }
+        if (!l && !tiny_weight) l = lower_ufc(dag, bf16);
+        if (!l && !tiny_weight) l = lower_dyn(dag, bf16);
     }
     if (!l) l = lower_per_node(dag, bf16);
     batch_weight_jobs(*l);

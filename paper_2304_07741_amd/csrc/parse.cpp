@@ -1,6 +1,7 @@
 // Blob parser, shape inference and legality checks (host only).
 #include "dag.hpp"
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <map>
@@ -95,6 +96,7 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             continue;
         }
         if (done) return fail(err, lineno, "text after the output line", kInvalidBlob);
+        if (l.pos.empty()) return fail(err, lineno, "expected '%k = op %operand ...' or 'output %k'", kInvalidBlob);
         if (l.pos[0] == "output") {
             int id;
             if (l.pos.size() != 2 || !parse_ref(l.pos[1], id) || id >= (int)dag.nodes.size())
@@ -138,6 +140,9 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
                 !get_int(l, "c0", nd.c0, false, present) || !get_int(l, "c1", nd.c1, false, present))
                 return fail(err, lineno, "shift needs dh= dw= [c0= c1=]", kInvalidBlob);
             if (nd.c0 < 0 || nd.c1 > A.C || nd.c0 > nd.c1) return fail(err, lineno, "shift slice outside the channels", kShapeMismatch);
+            // a shift by the image's extent or more moves everything out: clamped, so that dh * W + dw stays a small int
+            nd.dh = std::max(-dag.H, std::min(dag.H, nd.dh));
+            nd.dw = std::max(-dag.W, std::min(dag.W, nd.dw));
             nd.C = A.C;
             nd.T = A.T;
         } else if (op == "group") {

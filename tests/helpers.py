@@ -17,18 +17,30 @@ def rel_errors(got, ref, floor=1e-30):
     return d.max() / scale, l2, d
 
 
-def assert_close(got, ref, tol, what, kinks=False, floor=1e-30):
-    """||got-ref||_inf <= tol*||ref||_inf and ||got-ref||_2 <= tol*||ref||_2.
+TIE_MARGIN = 3e-5  # relative shift of the oracle's backward decision points in the two bracketing runs
+OUTLIER_LOG = []   # (what, numel, outliers against the definitions, outliers left after bracketing): printed by the tests
+
+
+def allowed_outliers(numel):
+    return max(1, int(1e-5 * numel))
+
+
+def assert_close(got, ref, tol, what, brackets=None, floor=1e-30):
+    """||got-ref||_inf <= tol*||ref||_inf and ||got-ref||_2 <= tol*||ref||_2, over ALL elements.
 
     `floor` guards tensors that are mathematically zero (e.g. the gradient through the mean of a
     softmax): there both sides hold only cancellation noise, a relative error means nothing, and the
     norms of ref are taken as at least floor (per element), which turns the test into an absolute one.
 
-    DAGs with decision points (relu, abs, max, clip) can hold exact mathematical ties that rounding
-    resolves differently in fp32 and fp64 (e.g. exp(a)*exp(b) against exp(c)*exp(d) with a+b == c+d);
-    either decision is a valid subgradient; and where values are squeezed into a narrow range (softmax of
-    softmax) fp32 cannot order neighbours that fp64 can.  For such DAGs up to max(8, 1e-4*numel) elements may
-    exceed the max-norm bound; they are counted, and both bounds must hold on all the others.
+    brackets (gradients of DAGs with decision points only): a callable that returns the same tensor from
+    two more oracle runs whose backward decisions (relu, abs, clip bounds, min / max, arg-max of a max
+    fold) are moved by -/+ TIE_MARGIN of the deciding tensor's magnitude.  It is called only when some
+    element misses the bound against the definitions; an element then counts with its distance to the
+    nearest of the three references, i.e. it passes if the kernel's value is what SOME resolution of a
+    near-tie gives (every resolution is a valid subgradient; fp32 and fp64 cannot agree on which).  At
+    most max(1, 1e-5*numel) elements may still miss the max-norm bound after that; the l2 bound holds
+    over all elements, outliers included.  Without brackets (y, and every tensor of a kink-free DAG) no
+    element may miss.
     """
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
@@ -37,17 +49,21 @@ def assert_close(got, ref, tol, what, kinks=False, floor=1e-30):
     if ref.size == 0:
         return 0.0, 0.0
     scale = max(np.abs(ref).max(), floor)
-    if kinks:
-        bad = d > tol * scale
-        nbad = int(bad.sum())
-        allowed = max(8, int(1e-4 * ref.size))
-        assert nbad <= allowed, f"{what}: {nbad} elements beyond {tol} (allowed {allowed}), max rel {einf:.3e}"
-        if nbad:
-            keep = ~bad
-            el2 = np.sqrt((d[keep] ** 2).sum()) / max(np.sqrt((ref[keep] ** 2).sum()), floor * np.sqrt(ref.size))
-            einf = d[keep].max() / scale
+    l2den = max(np.sqrt((ref * ref).sum()), floor * np.sqrt(ref.size))
+    n0 = int((d > tol * scale).sum())
+    if n0 and brackets is not None:
+        for alt in brackets():
+            d = np.minimum(d, np.abs(got - np.asarray(alt, dtype=np.float64).reshape(got.shape)))
+        n1 = int((d > tol * scale).sum())
+        OUTLIER_LOG.append((what, int(ref.size), n0, n1))
+        print(f"[outliers] {what}: numel {ref.size}, {n0} beyond {tol} against the definitions, {n1} after tie bracketing "
+              f"(allowed {allowed_outliers(ref.size)})")
+        assert n1 <= allowed_outliers(ref.size), \
+            f"{what}: {n1} elements beyond {tol} after tie bracketing ({n0} before; allowed {allowed_outliers(ref.size)}), max rel {einf:.3e}"
+        el2 = np.sqrt((d * d).sum()) / l2den
+        einf = float(np.sort(d.ravel())[-(n1 + 1)] / scale) if n1 < d.size else einf
     else:
-        assert einf <= tol, f"{what}: max-norm relative error {einf:.3e} > {tol}"
+        assert einf <= tol, f"{what}: max-norm relative error {einf:.3e} > {tol} ({n0} of {ref.size} elements)"
     assert el2 <= tol, f"{what}: l2 relative error {el2:.3e} > {tol}"
     return einf, el2
 
@@ -60,11 +76,20 @@ def check_against_oracle(oracle, case, res, dy, what=None):
     ref = oracle.run(case["blob"], case["x"], case["weights"], dy)
     tol = TOL[case["dtype"]]
     what = what or case["name"]
+    alts = []
+
+    def bracket_runs():
+        if not alts:
+            for m in (-TIE_MARGIN, TIE_MARGIN):
+                alts.append(oracle.run(case["blob"], case["x"], case["weights"], dy, tie_margin=m))
+        return alts
+
     kinks = has_kinks(case["blob"])
     # gradients below 1e-5 of the incoming gradient's magnitude are cancellation noise on both sides
     gfloor = 1e-5 * float(np.abs(dy).max())
-    out = {"y": assert_close(res["y"], ref["y"], tol, what + ":y", kinks),
-           "dx": assert_close(res["dx"], ref["dx"], tol, what + ":dx", kinks, gfloor)}
+    # the forward pass is continuous in every primitive: y gets no allowance
+    out = {"y": assert_close(res["y"], ref["y"], tol, what + ":y"),
+           "dx": assert_close(res["dx"], ref["dx"], tol, what + ":dx", (lambda: [a["dx"] for a in bracket_runs()]) if kinks else None, gfloor)}
     for k, (g, r) in enumerate(zip(res["dw"], ref["dw"])):
-        out[f"dw{k}"] = assert_close(g, r, tol, what + f":dw{k}", kinks, gfloor)
+        out[f"dw{k}"] = assert_close(g, r, tol, what + f":dw{k}", (lambda k=k: [a["dw"][k] for a in bracket_runs()]) if kinks else None, gfloor)
     return out, ref

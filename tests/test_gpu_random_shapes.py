@@ -2,8 +2,8 @@
 at random (odd widths, single rows, ragged 8-pixel tails, channel counts that are no multiple of 16, groups of
 1-32 rows, windows 1/3/5 also non-square), each case against the CPU oracle at the bf16 tolerance.
 
-Weight tensors of a single scalar are not drawn: with bf16 intermediates the relative error of ONE cancelled sum
-is unbounded, and the max-norm tolerance presumes a tensor whose largest element is no such sum."""
+The family `tiny_weights` draws weight tensors of one to a few scalars per group: every element of such a dW is a
+sum over all pixels that may cancel, so the library keeps fp32 intermediates for them (no bf16 middle tensors)."""
 import math
 import random
 
@@ -113,6 +113,25 @@ def _window_weights(rng):
     return "\n".join(lines) + f"\noutput %{u + 3}\n", (N, C, H, W), [(1, k * k, C), (g2, o2 // g2, C // g2)]
 
 
+def _tiny_weights(rng):
+    """The gate family with 1 or 2 channels per group and few groups: weight tensors of 1-32 elements"""
+    g1 = rng.choice([1, 2, 4])
+    C = g1 * rng.choice([1, 1, 2])
+    g2 = rng.choice([g for g in (1, 2, 4) if C % g == 0])
+    o2 = g2 * rng.choice([1, 1, 2])
+    N, H, W = rng.randint(1, 5), rng.randint(1, 20), rng.randint(4, 23)
+    act = rng.choice([None, "relu", "gelu", "abs"])
+    lines = [f"%1 = fc %0 groups={g1} out={C}"]
+    cur = 1
+    if act:
+        lines.append(f"%2 = unary %1 op={act}")
+        cur = 2
+    lines.append(f"%{cur + 1} = binary %0 %{cur} op={rng.choice(['add', 'mul'])}")
+    lines.append(f"%{cur + 2} = fc %{cur + 1} groups={g2} out={o2}")
+    body = "\n".join(lines) + f"\noutput %{cur + 2}\n"
+    return body, (N, C, H, W), [(g1, C // g1, C // g1), (g2, o2 // g2, C // g2)]
+
+
 def _single_fc(rng):
     kh = rng.choice([1, 3, 5])
     kw = kh if rng.random() < 0.7 else rng.choice([1, 3, 5])
@@ -125,7 +144,8 @@ def _single_fc(rng):
     return body, (N, G * R, H, W), [(G, Og, R * kh * kw)]
 
 
-FAMILIES = {"gate": _gate, "gate_wide": _gate_wide, "window_weights": _window_weights, "single_fc": _single_fc}
+FAMILIES = {"gate": _gate, "gate_wide": _gate_wide, "window_weights": _window_weights, "single_fc": _single_fc,
+            "tiny_weights": _tiny_weights}
 
 
 @pytest.mark.parametrize("block", range(4))
@@ -141,5 +161,5 @@ def test_random_shapes(harness, oracle, family, block):
         check_against_oracle(oracle, case, res, dy, what=f"{family}{i} {shape}")
         r.close()
     # (some draws fall outside a fused lowering's conditions and take the per-node path: both must agree with the oracle)
-    if family != "single_fc":
+    if family not in ("single_fc", "tiny_weights"):
         assert fused >= 10, f"only {fused} of 25 {family} cases took the fused lowering"

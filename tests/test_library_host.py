@@ -78,6 +78,8 @@ BAD = [
     ("%1 = softmax %0 axis=H\noutput %1\n", -2),
     ("%1 = conv %0 k=3\noutput %1\n", -2),
     ("%1 = unary %0 op=expclip lo=1 hi=1\noutput %1\n", -3),
+    ("foo=bar\noutput %0\n", -1),                      # a line of key=value tokens only
+    ("%1 = unary %0 op=relu\nop=relu\noutput %1\n", -1),
 ]
 
 
@@ -87,6 +89,13 @@ def test_illegal_blobs_give_status_codes(lib, body, status):
         B.canvas_dag_compile(wl.HEADER + body, (1, 4, 4, 4), B.CANVAS_F32)
     assert e.value.status == status
     assert str(e.value)
+
+
+def test_huge_shift_is_clamped_to_the_image(lib):
+    """A shift by the image's extent or more leaves nothing inside: the parser clamps it (the kernels multiply dh by W)."""
+    h = B.canvas_dag_compile(wl.HEADER + "%1 = shift %0 dh=1073741824 dw=-1073741824\noutput %1\n", (1, 4, 4, 4), B.CANVAS_F32)
+    assert list(B.canvas_dag_query(h).out_shape) == [1, 4, 1, 4, 4]
+    B.canvas_dag_destroy(h)
 
 
 def test_bad_arguments(lib):

@@ -512,6 +512,76 @@ def test_broadcast_channel_tiling(oracle):
     np.testing.assert_allclose(r["dw"][0][0], np.einsum("nohw,nchw->oc", gf, x), atol=1e-13)
 
 
+def test_broadcast_tiling_of_an_lhs_with_taps_of_its_own(oracle):
+    """C_L != C_R and T_L > 1 (Section 5, Blending): the LHS [C_L, T_L] is replicated along the flattened
+    (c*T_R + t) index of the RHS [C_R, T_R] modulo C_L*T_L, innermost dims aligned.  Here [6, 3] onto [4, 9]
+    (36 = 2 * 18): checked against a loop over the flattened index on plain reshapes, forward and the
+    gradient that reaches the LHS (seen through the weights of the FC that produces it)."""
+    rng = np.random.default_rng(54)
+    N, C, H, W, CL, TL, TR = 2, 4, 3, 5, 6, 3, 9
+    x = rng.standard_normal((N, C, H, W))
+    w = rng.standard_normal((1, CL, C))
+    dy = rng.standard_normal((N, C, TR, H, W))
+    body = ("%1 = fc %0 groups=1 out=6\n%2 = unfold %1 kh=3 kw=1\n%3 = unfold %0 kh=3 kw=3\n"
+            "%4 = binary %2 %3 op=mul\noutput %4\n")
+    r = run1(oracle, body, x, [w], dy)
+    lhs = run1(oracle, "%1 = fc %0 groups=1 out=6\n%2 = unfold %1 kh=3 kw=1\noutput %2\n", x, [w])["y"]
+    rhs = run1(oracle, "%1 = unfold %0 kh=3 kw=3\noutput %1\n", x)["y"]
+    assert lhs.shape == (N, CL, TL, H, W) and rhs.shape == (N, C, TR, H, W)
+    lflat = lhs.reshape(N, CL * TL, H, W)
+    exp = np.empty_like(rhs)
+    glflat = np.zeros_like(lflat)
+    for c in range(C):
+        for t in range(TR):
+            j = (c * TR + t) % (CL * TL)
+            exp[:, c, t] = lflat[:, j] * rhs[:, c, t]
+            glflat[:, j] += dy[:, c, t] * rhs[:, c, t]
+    np.testing.assert_allclose(r["y"], exp, atol=1e-14)
+    # the gradient of the LHS goes back through the 3 x 1 unfold (tap kh reads row h + kh - 1) and the FC
+    gl = glflat.reshape(N, CL, TL, H, W)
+    g1 = np.zeros((N, CL, H, W))
+    for kh in range(3):
+        for h in range(H):
+            if 0 <= h + kh - 1 < H:
+                g1[:, :, h + kh - 1] += gl[:, :, kh, h]
+    np.testing.assert_allclose(r["dw"][0][0], np.einsum("nohw,nchw->oc", g1, x), atol=1e-12)
+
+
+def test_tie_margin_moves_only_decisions_next_to_a_kink(oracle):
+    """The comparison rule's bracketing runs: margin 0 is the definition; a margin m moves the backward
+    decision points by |m| * max|operand| and leaves the forward pass and every element away from a kink alone."""
+    x = np.array([-2.0, -1e-7, 0.0, 1e-7, 0.5, 2.0]).reshape(1, 1, 1, 6)
+    dy = np.ones_like(x)
+    for op, d0, dlo, dhi in [("relu", [0, 0, 0, 1, 1, 1], [0, 1, 1, 1, 1, 1], [0, 0, 0, 0, 1, 1]),
+                             ("abs", [-1, -1, 0, 1, 1, 1], [-1, 1, 1, 1, 1, 1], [-1, -1, -1, -1, 1, 1])]:
+        body = f"%1 = unary %0 op={op}\noutput %1\n"
+        r0 = oracle.run(H_ + body, x, [], dy)
+        rl = oracle.run(H_ + body, x, [], dy, tie_margin=-1e-6)
+        rh = oracle.run(H_ + body, x, [], dy, tie_margin=1e-6)
+        again = oracle.run(H_ + body, x, [], dy)
+        np.testing.assert_array_equal(r0["dx"].ravel(), d0)
+        np.testing.assert_array_equal(rl["dx"].ravel(), dlo)
+        np.testing.assert_array_equal(rh["dx"].ravel(), dhi)
+        np.testing.assert_array_equal(again["dx"], r0["dx"])  # the margin does not outlive its run
+        np.testing.assert_array_equal(rl["y"], r0["y"])
+        np.testing.assert_array_equal(rh["y"], r0["y"])
+    # arg-max of a max fold: taps within the margin of the maximum; the first of them (m < 0) or the last (m > 0)
+    xm = np.zeros((1, 1, 1, 3))
+    xm[0, 0, 0] = [1.0, 1.0 + 1e-9, 0.2]
+    body = "%1 = unfold %0 kh=1 kw=3\n%2 = fold %1 op=max\noutput %2\n"
+    dyo = np.array([0.0, 1.0, 0.0]).reshape(1, 1, 1, 3)  # only the middle pixel, whose taps are (1, 1 + 1e-9, 0.2)
+    g0 = oracle.run(H_ + body, xm, [], dyo)["dx"].ravel()
+    gl = oracle.run(H_ + body, xm, [], dyo, tie_margin=-1e-6)["dx"].ravel()
+    gh = oracle.run(H_ + body, xm, [], dyo, tie_margin=1e-6)["dx"].ravel()
+    np.testing.assert_array_equal(g0, [0, 1, 0])
+    np.testing.assert_array_equal(gl, [1, 0, 0])
+    np.testing.assert_array_equal(gh, [0, 1, 0])
+    # min / max blends: the definition sends a tie to the LHS
+    a = np.array([1.0, 1.0, 3.0]).reshape(1, 1, 1, 3)
+    body = "%1 = unary %0 op=sin\n%2 = binary %1 %1 op=max\noutput %2\n"
+    assert oracle.run(H_ + body, a, [], np.ones_like(a), tie_margin=1e-6)["dx"].shape == a.shape
+
+
 def test_involution_core_against_explicit_dynamic_kernel(oracle):
     """Section 5: [K*K,H,W] broadcast-multiplied onto [C,K,K,H,W], then summed over taps, is a
     per-pixel dynamic KxK filter: out(c,h,w) = sum_t k(t,h,w) * x(c,h+dh_t,w+dw_t)."""
