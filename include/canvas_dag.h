@@ -161,6 +161,20 @@ int canvas_dag_launch_desc(const canvas_dag* dag, int backward, int idx, canvas_
 int canvas_dag_forward(canvas_dag* dag, const void* x, const void* const* weights, void* y, void* workspace,
                        size_t workspace_bytes, void* stream);
 
+/* canvas_dag_forward for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same kernels, with the workspace taken from a
+ * static device array of CANVAS_STATIC_WORKSPACE_BYTES that is part of the library (every GPU the library
+ * runs on holds one copy until the process ends).  Calls no hipMalloc / hipFree and no allocating library
+ * routine.  x, weights, y, stream as canvas_dag_forward.  An inference plan runs its weight-only launches
+ * with every call (nothing is kept in the static workspace between calls), so canvas_dag_prepare is not
+ * needed; no canvas_dag_backward can follow, since that reads the workspace of its forward call.
+ * All calls on one GPU, of any plan, share the one array: calls that overlap on a GPU (different streams
+ * or host threads) race; calls enqueued on one stream are ordered and safe.
+ * Errors: WORKSPACE_TOO_SMALL when the plan's workspace_bytes exceeds CANVAS_STATIC_WORKSPACE_BYTES
+ * (nothing is launched), BAD_ARG, HIP_ERROR. */
+#define CANVAS_STATIC_WORKSPACE_BYTES (64u << 20)
+int canvas_dag_forward_static(canvas_dag* dag, const void* x, const void* const* weights, void* y, void* stream);
+
 /* Inference plans (CANVAS_OPT_INFERENCE) only: enqueue the weight-only work of the forward pass
  * (repacking into MFMA operand order, widening) on `stream`; its results live in the workspace, so
  * call it once before the first canvas_dag_forward on that workspace and again whenever the weights

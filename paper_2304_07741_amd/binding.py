@@ -16,7 +16,8 @@ CANVAS_OPT_INFERENCE = 2
 CANVAS_MAX_NODES = 64
 STATUS = {0: "OK", -1: "INVALID_BLOB", -2: "UNKNOWN_OP", -3: "SHAPE_MISMATCH", -4: "BAD_ARG",
           -5: "WORKSPACE_TOO_SMALL", -6: "UNSUPPORTED", -7: "HIP_ERROR"}
-EXPORTS = ["canvas_dag_compile", "canvas_dag_query", "canvas_dag_launch_desc", "canvas_dag_forward",
+CANVAS_STATIC_WORKSPACE_BYTES = 64 << 20
+EXPORTS = ["canvas_dag_compile", "canvas_dag_query", "canvas_dag_launch_desc", "canvas_dag_forward", "canvas_dag_forward_static",
            "canvas_dag_backward", "canvas_dag_prepare", "canvas_dag_set_timing", "canvas_dag_get_timing", "canvas_dag_destroy",
            "canvas_last_error"]
 # include/canvas_template.h (host only)
@@ -83,6 +84,7 @@ def load():
         lib.canvas_dag_query.argtypes = [vp, ctypes.POINTER(CanvasDagInfo)]
         lib.canvas_dag_launch_desc.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(CanvasLaunchDesc)]
         lib.canvas_dag_forward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, sz, vp]
+        lib.canvas_dag_forward_static.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp]
         lib.canvas_dag_backward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, ctypes.POINTER(vp), vp, sz, vp]
         lib.canvas_dag_prepare.argtypes = [vp, ctypes.POINTER(vp), vp, sz, vp]
         lib.canvas_dag_set_timing.argtypes = [vp, ctypes.c_int]
@@ -151,6 +153,11 @@ def _stream():
 def canvas_dag_forward(handle, x, weights, y, workspace):
     _check(load().canvas_dag_forward(handle, x.data_ptr(), _ptrs(weights), y.data_ptr(), workspace.data_ptr(),
                                      workspace.numel() * workspace.element_size(), _stream()))
+
+
+def canvas_dag_forward_static(handle, x, weights, y):
+    """canvas_dag_forward on the library's static workspace (no allocation anywhere)."""
+    _check(load().canvas_dag_forward_static(handle, x.data_ptr(), _ptrs(weights), y.data_ptr(), _stream()))
 
 
 def canvas_dag_backward(handle, x, weights, dy, dx, dweights, workspace):

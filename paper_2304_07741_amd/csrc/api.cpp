@@ -3,6 +3,7 @@
 
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -25,6 +26,12 @@ struct canvas_dag {
 namespace {
 thread_local std::string g_err;
 }
+
+// Workspace of canvas_dag_forward_static: one array per GPU, part of the library's code object, so that
+// callers that may not allocate device memory still have somewhere to put the derived weights and the
+// intermediates of a forward pass.  In host code this name is only a handle: the device address comes from
+// hipGetSymbolAddress (static_scratch_of below) and only that address is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[CANVAS_STATIC_WORKSPACE_BYTES];
 
 namespace canvas {
 thread_local TimingEvents g_timing;
@@ -74,6 +81,28 @@ void run_launches(canvas_dag* d, int backward, const canvas::RunArgs& a) {
     }
     canvas::g_timing = canvas::TimingEvents();
     d->timed_once[backward] = true;
+}
+
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return set_err(CANVAS_HIP_ERROR, std::string("hipGetDevice failed: ") + hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return set_err(CANVAS_UNSUPPORTED, "device ordinal beyond the static workspace table");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return set_err(CANVAS_HIP_ERROR, std::string("hipGetSymbolAddress(static workspace) failed: ") + hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CANVAS_OK;
 }
 
 void drop_events(canvas_dag* d) {
@@ -179,6 +208,33 @@ int canvas_dag_forward(canvas_dag* dag, const void* x, const void* const* weight
     a.ws = (char*)workspace;
     a.stream = (hipStream_t)stream;
     (void)hipGetLastError();
+    run_launches(dag, 0, a);
+    return finish_launches();
+}
+
+int canvas_dag_forward_static(canvas_dag* dag, const void* x, const void* const* weights, void* y, void* stream) {
+    if (!dag) return set_err(CANVAS_BAD_ARG, "null dag handle");
+    if (dag->low->ws_bytes > (uint64_t)CANVAS_STATIC_WORKSPACE_BYTES)
+        return set_err(CANVAS_WORKSPACE_TOO_SMALL, "this plan needs " + std::to_string(dag->low->ws_bytes) +
+                                                       " workspace bytes, the static workspace holds " +
+                                                       std::to_string((uint64_t)CANVAS_STATIC_WORKSPACE_BYTES) +
+                                                       ": use canvas_dag_forward with a workspace of the caller");
+    void* ws = nullptr;
+    int rc = static_scratch_of_current_device(&ws);
+    if (rc) return rc;
+    rc = check_common(dag, x, weights, ws, (size_t)CANVAS_STATIC_WORKSPACE_BYTES);
+    if (rc) return rc;
+    if (!y || !aligned16(y)) return set_err(CANVAS_BAD_ARG, "y must be a non-null, 16-byte aligned device pointer");
+    canvas::RunArgs a;
+    a.x = x;
+    a.w = weights;
+    a.y = y;
+    a.ws = (char*)ws;
+    a.stream = (hipStream_t)stream;
+    (void)hipGetLastError();
+    // an inference plan keeps its weight-only launches apart: here they run with every call, as the static
+    // workspace is shared by all plans and calls on this GPU and keeps nothing between them
+    for (const auto& l : dag->low->prep) l.run(a);
     run_launches(dag, 0, a);
     return finish_launches();
 }
