@@ -25,6 +25,13 @@
  * sign(0) = 0, ties of min / max to the LHS) and the only setting the pins use.
  * The forward pass never depends on it.
  *
+ * Decisions of the backward pass (which operand of a max was the larger, the
+ * sign at a relu) are taken on the operands rounded to fp32, the precision in
+ * which the kernels decide: fp64 rounding noise then cannot order what is an
+ * exact tie mathematically and in fp32 (e.g. the zero-padded taps of a max fold
+ * downstream of a softmax), and the first-maximum rule applies to it instead.
+ * Values are never rounded.
+ *
  * Parity pins (see tests/test_oracle_*.py): brute-force direct (grouped)
  * convolution and its gradients, adjoint dot-product identities, central
  * finite differences, closed forms and invariants.  No function here is
@@ -676,12 +683,12 @@ static void bwd_unary(const Dag *d, const Node *nd, int k, const double *in, con
     /* e = 0 unless a tie margin is set: then the kink moves by e */
     double e = g_tie_margin != 0.0 ? g_tie_margin * max_abs(in, n) : 0.0;
     for (j = 0; j < n; j++) {
-        double x = in[j], dv = 0.0;
+        double x = in[j], dv = 0.0, xd = (double)(float)x;  /* xd: what the decisions look at */
         switch (nd->kind) {
-        case UN_RELU: dv = x > e ? 1.0 : 0.0; break;
-        case UN_ABS: dv = x > e ? 1.0 : (x < e ? -1.0 : 0.0); break;
+        case UN_RELU: dv = xd > e ? 1.0 : 0.0; break;
+        case UN_ABS: dv = xd > e ? 1.0 : (xd < e ? -1.0 : 0.0); break;
         case UN_GELU: dv = gelu_cdf(x) + x * gelu_pdf(x); break;
-        case UN_EXPCLIP: dv = (x > nd->lo + e && x < nd->hi - e) ? out[j] : 0.0; break;
+        case UN_EXPCLIP: dv = (xd > (double)(float)nd->lo + e && xd < (double)(float)nd->hi - e) ? out[j] : 0.0; break;
         case UN_SIN: dv = cos(x); break;
         }
         gin[j] += gout[j] * dv;
@@ -710,8 +717,8 @@ static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
                 case BIN_ADD: glhs[lp] += g; grhs[ro + p] += g; break;
                 case BIN_MUL: glhs[lp] += g * b; grhs[ro + p] += g * a; break;
                 case BIN_SUB: glhs[lp] += g; grhs[ro + p] -= g; break;
-                case BIN_MIN: if (a <= b + e) glhs[lp] += g; else grhs[ro + p] += g; break;
-                case BIN_MAX: if (a >= b - e) glhs[lp] += g; else grhs[ro + p] += g; break;
+                case BIN_MIN: if ((double)(float)a <= (double)(float)b + e) glhs[lp] += g; else grhs[ro + p] += g; break;
+                case BIN_MAX: if ((double)(float)a >= (double)(float)b - e) glhs[lp] += g; else grhs[ro + p] += g; break;
                 }
             }
         }
@@ -737,6 +744,7 @@ static void bwd_softmax(const Dag *d, const Node *nd, const double *out, const d
 
 /* Max takes the gradient to the first maximal tap (lowest t) only.  With a tie margin e != 0 every element
  * within |e| of the maximum counts as maximal, and e < 0 takes the first, e > 0 the last of them. */
+#define DEC(v) ((double)(float)(v)) /* the operand as a decision sees it */
 static void bwd_fold(const Dag *d, const Node *nd, const double *in, const double *gout, double *gin) {
     const Node *A = &d->node[nd->a];
     int P = node_P(d, A), T = A->T, c, t, p;
@@ -750,11 +758,11 @@ static void bwd_fold(const Dag *d, const Node *nd, const double *in, const doubl
                     if (nd->kind == FOLD_MAX) {
                         int best = 0;
                         for (c = 1; c < Cg; c++)
-                            if (in[(((size_t)g * Cg + c) * T + t) * P + p] > in[(((size_t)g * Cg + best) * T + t) * P + p]) best = c;
+                            if (DEC(in[(((size_t)g * Cg + c) * T + t) * P + p]) > DEC(in[(((size_t)g * Cg + best) * T + t) * P + p])) best = c;
                         if (e != 0.0) {
-                            double m = in[(((size_t)g * Cg + best) * T + t) * P + p] - fabs(e);
-                            if (e < 0.0) { for (c = 0; c < Cg; c++) if (in[(((size_t)g * Cg + c) * T + t) * P + p] >= m) { best = c; break; } }
-                            else { for (c = Cg - 1; c >= 0; c--) if (in[(((size_t)g * Cg + c) * T + t) * P + p] >= m) { best = c; break; } }
+                            double m = DEC(in[(((size_t)g * Cg + best) * T + t) * P + p]) - fabs(e);
+                            if (e < 0.0) { for (c = 0; c < Cg; c++) if (DEC(in[(((size_t)g * Cg + c) * T + t) * P + p]) >= m) { best = c; break; } }
+                            else { for (c = Cg - 1; c >= 0; c--) if (DEC(in[(((size_t)g * Cg + c) * T + t) * P + p]) >= m) { best = c; break; } }
                         }
                         gin[(((size_t)g * Cg + best) * T + t) * P + p] += gg;
                     } else {
@@ -776,18 +784,18 @@ static void bwd_fold(const Dag *d, const Node *nd, const double *in, const doubl
                         size_t best = ((size_t)c * Hi + h0) * Wi + w0;
                         for (h = h0; h < h1; h++)
                             for (w = w0; w < w1; w++)
-                                if (in[((size_t)c * Hi + h) * Wi + w] > in[best]) best = ((size_t)c * Hi + h) * Wi + w;
+                                if (DEC(in[((size_t)c * Hi + h) * Wi + w]) > DEC(in[best])) best = ((size_t)c * Hi + h) * Wi + w;
                         if (e != 0.0) {
-                            double m = in[best] - fabs(e);
+                            double m = DEC(in[best]) - fabs(e);
                             int found = 0;
                             if (e < 0.0) {
                                 for (h = h0; h < h1 && !found; h++)
                                     for (w = w0; w < w1 && !found; w++)
-                                        if (in[((size_t)c * Hi + h) * Wi + w] >= m) { best = ((size_t)c * Hi + h) * Wi + w; found = 1; }
+                                        if (DEC(in[((size_t)c * Hi + h) * Wi + w]) >= m) { best = ((size_t)c * Hi + h) * Wi + w; found = 1; }
                             } else {
                                 for (h = h1 - 1; h >= h0 && !found; h--)
                                     for (w = w1 - 1; w >= w0 && !found; w--)
-                                        if (in[((size_t)c * Hi + h) * Wi + w] >= m) { best = ((size_t)c * Hi + h) * Wi + w; found = 1; }
+                                        if (DEC(in[((size_t)c * Hi + h) * Wi + w]) >= m) { best = ((size_t)c * Hi + h) * Wi + w; found = 1; }
                             }
                         }
                         gin[best] += g;
@@ -805,11 +813,11 @@ static void bwd_fold(const Dag *d, const Node *nd, const double *in, const doubl
             if (nd->kind == FOLD_MAX) {
                 int best = 0;
                 for (t = 1; t < T; t++)
-                    if (in[((size_t)c * T + t) * P + p] > in[((size_t)c * T + best) * P + p]) best = t;
+                    if (DEC(in[((size_t)c * T + t) * P + p]) > DEC(in[((size_t)c * T + best) * P + p])) best = t;
                 if (e != 0.0) {
-                    double m = in[((size_t)c * T + best) * P + p] - fabs(e);
-                    if (e < 0.0) { for (t = 0; t < T; t++) if (in[((size_t)c * T + t) * P + p] >= m) { best = t; break; } }
-                    else { for (t = T - 1; t >= 0; t--) if (in[((size_t)c * T + t) * P + p] >= m) { best = t; break; } }
+                    double m = DEC(in[((size_t)c * T + best) * P + p]) - fabs(e);
+                    if (e < 0.0) { for (t = 0; t < T; t++) if (DEC(in[((size_t)c * T + t) * P + p]) >= m) { best = t; break; } }
+                    else { for (t = T - 1; t >= 0; t--) if (DEC(in[((size_t)c * T + t) * P + p]) >= m) { best = t; break; } }
                 }
                 gin[((size_t)c * T + best) * P + p] += g;
             } else {

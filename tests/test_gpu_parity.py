@@ -268,7 +268,8 @@ def test_grouped_involution(harness, oracle, idx, flags):
     wshapes = [(G, k * k, C // G), (G, o2 // G, C // G)]
     case = _mk(body, (N, C, H, W), "bf16", 450 + idx, wshapes, f"gdyn{idx}")
     res, r, dy = harness.run_case(case, flags)
-    assert r.info.fused == (1 if flags == 0 and k <= 5 and C // G != k * k else 0)
+    tiny = min(G * k * k * (C // G), o2 * (C // G)) < 16  # weight tensors of a few scalars keep fp32 intermediates
+    assert r.info.fused == (1 if flags == 0 and k <= 5 and C // G != k * k and not tiny else 0)
     check_against_oracle(oracle, case, res, dy)
     r.close()
 

@@ -567,15 +567,19 @@ def test_tie_margin_moves_only_decisions_next_to_a_kink(oracle):
         np.testing.assert_array_equal(rh["y"], r0["y"])
     # arg-max of a max fold: taps within the margin of the maximum; the first of them (m < 0) or the last (m > 0)
     xm = np.zeros((1, 1, 1, 3))
-    xm[0, 0, 0] = [1.0, 1.0 + 1e-9, 0.2]
+    xm[0, 0, 0] = [1.0, 1.0 + 1e-6, 0.2]
     body = "%1 = unfold %0 kh=1 kw=3\n%2 = fold %1 op=max\noutput %2\n"
-    dyo = np.array([0.0, 1.0, 0.0]).reshape(1, 1, 1, 3)  # only the middle pixel, whose taps are (1, 1 + 1e-9, 0.2)
+    dyo = np.array([0.0, 1.0, 0.0]).reshape(1, 1, 1, 3)  # only the middle pixel, whose taps are (1, 1 + 1e-6, 0.2)
     g0 = oracle.run(H_ + body, xm, [], dyo)["dx"].ravel()
-    gl = oracle.run(H_ + body, xm, [], dyo, tie_margin=-1e-6)["dx"].ravel()
-    gh = oracle.run(H_ + body, xm, [], dyo, tie_margin=1e-6)["dx"].ravel()
+    gl = oracle.run(H_ + body, xm, [], dyo, tie_margin=-1e-5)["dx"].ravel()
+    gh = oracle.run(H_ + body, xm, [], dyo, tie_margin=1e-5)["dx"].ravel()
     np.testing.assert_array_equal(g0, [0, 1, 0])
     np.testing.assert_array_equal(gl, [1, 0, 0])
     np.testing.assert_array_equal(gh, [0, 1, 0])
+    # decisions look at the operands in fp32, the kernels' precision: what differs only beyond that is a tie, first tap wins
+    xm[0, 0, 0] = [1.0, 1.0 + 1e-12, 0.2]
+    np.testing.assert_array_equal(oracle.run(H_ + body, xm, [], dyo)["dx"].ravel(), [1, 0, 0])
+    np.testing.assert_array_equal(oracle.run(H_ + body, xm, [])["y"].ravel()[1], 1.0 + 1e-12)  # values are not rounded
     # min / max blends: the definition sends a tie to the LHS
     a = np.array([1.0, 1.0, 3.0]).reshape(1, 1, 1, 3)
     body = "%1 = unary %0 op=sin\n%2 = binary %1 %1 op=max\noutput %2\n"
