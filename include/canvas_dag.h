@@ -115,9 +115,9 @@ typedef struct canvas_dag_info {
     int32_t out_node;
     int32_t n_weights;                        /* number of fc nodes */
     int32_t n_launches_fwd, n_launches_bwd;   /* kernels enqueued per call */
-    int32_t fused;                            /* 1 when a fused lowering was chosen, 0 for the per-node lowering */
+    int32_t fused;                            /* 1 when one of the whole-DAG kernel families was chosen, else 0 (lowering by units) */
     int32_t n_launches_prepare;               /* inference plans: kernels canvas_dag_prepare enqueues, else 0 */
-    int32_t reserved0[1];
+    int32_t n_fused_chains;                   /* lowering by units: chains of memory-bound nodes fused into one kernel each */
     int64_t out_shape[5];                     /* N, C, T, H, W */
     int64_t node_shape[CANVAS_MAX_NODES][5];  /* N, C, T, H, W per node */
     int64_t weight_shape[CANVAS_MAX_NODES][3];/* G, C_out/G, (C_in/G)*T per fc node, in node order */
@@ -126,6 +126,8 @@ typedef struct canvas_dag_info {
     double fc_flops_fwd;                      /* 2*M*C_out*(C_in/G)*T summed over fc nodes (block-diagonal only) */
     double min_bytes_fwd;                     /* x read + y written + weights read, once each */
     double min_bytes_bwd;                     /* x, dy read + dx written + weights read + dW written */
+    int32_t n_fused_nodes;                    /* nodes inside those chains (none of them is materialised unless a later unit reads it) */
+    int32_t reserved1;
 } canvas_dag_info;
 
 typedef struct canvas_launch_desc {

@@ -35,13 +35,14 @@ class CanvasDagInfo(ctypes.Structure):
     _fields_ = [
         ("n_nodes", ctypes.c_int32), ("out_node", ctypes.c_int32), ("n_weights", ctypes.c_int32),
         ("n_launches_fwd", ctypes.c_int32), ("n_launches_bwd", ctypes.c_int32), ("fused", ctypes.c_int32),
-        ("n_launches_prepare", ctypes.c_int32), ("reserved0", ctypes.c_int32 * 1),
+        ("n_launches_prepare", ctypes.c_int32), ("n_fused_chains", ctypes.c_int32),
         ("out_shape", ctypes.c_int64 * 5),
         ("node_shape", (ctypes.c_int64 * 5) * CANVAS_MAX_NODES),
         ("weight_shape", (ctypes.c_int64 * 3) * CANVAS_MAX_NODES),
         ("weight_node", ctypes.c_int32 * CANVAS_MAX_NODES),
         ("workspace_bytes", ctypes.c_uint64),
         ("fc_flops_fwd", ctypes.c_double), ("min_bytes_fwd", ctypes.c_double), ("min_bytes_bwd", ctypes.c_double),
+        ("n_fused_nodes", ctypes.c_int32), ("reserved1", ctypes.c_int32),
     ]
 
 

@@ -150,6 +150,8 @@ int canvas_dag_compile(const void* blob, size_t blob_len, const int64_t in_shape
         I.n_launches_bwd = (int32_t)d->low->bwd.size();
         I.n_launches_prepare = (int32_t)d->low->prep.size();
         I.fused = d->low->fused ? 1 : 0;
+        I.n_fused_chains = d->low->chain_units;
+        I.n_fused_nodes = d->low->chain_nodes;
         const double esz = d->bf16 ? 2.0 : 4.0;
         double wbytes = 0, wcount = 0;
         for (int k = 0; k < I.n_nodes; k++) {

@@ -1,0 +1,668 @@
+// Planner of the fused-chain kernels (host only).
+//
+// The unit's nodes are first expanded into an instance graph: an instance is "the value of node k as seen through a
+// position context", the context being the stencil offsets (Shift terms, at most one Unfold window) collected on the
+// way down from a consumer.  A Shift or Unfold node itself only adds to the context of its operand and masks what
+// falls outside the image; the loads at the leaves carry the total offset.  Reductions (Fold, Softmax) are only
+// legal in the empty context: a stencil above a reduction would need the reduction's result at other pixels.
+// Code is then emitted by demand-driven recursion, with full recomputation instead of saved values: forward
+// emit_eval(instance), backward emit_grad(instance) = sum over its users of their local adjoint applied to
+// emit_grad(user).  A Softmax over channels splits a program into passes over the channel range (statistics first;
+// in the backward program also the sum of gradient x output that its adjoint needs).
+#include "chain_plan.hpp"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <map>
+#include <sstream>
+#include <tuple>
+
+#include "chain_kernels.hpp"
+
+namespace canvas {
+namespace chain {
+
+namespace {
+
+struct Fail {
+    std::string why;
+};
+
+struct Ctx {
+    std::vector<Term> terms;
+    bool win = false;
+    int kh = 1, kw = 1;
+    bool empty() const { return terms.empty() && !win; }
+    std::string key() const {
+        std::ostringstream os;
+        for (const Term& t : terms) os << t.dh << ',' << t.dw << ',' << t.c0 << ',' << t.c1 << ';';
+        if (win) os << 'w' << kh << 'x' << kw;
+        return os.str();
+    }
+    int reach_rows() const {
+        int r = win ? kh / 2 : 0;
+        for (const Term& t : terms) r += std::abs((int)t.dh);
+        return r;
+    }
+};
+
+enum InstKind { kExt, kIdent, kStencil, kUnaryI, kBinaryI, kSmT, kSmC, kFoldI };
+
+struct Inst {
+    int node = -1, ctx = 0, lanes = 1;
+    InstKind kind = kExt;
+    int opnd[2] = {-1, -1};
+    std::vector<std::pair<int, int>> users;  // (instance, operand slot)
+    int level = 0;                           // softmax-over-channels instances at or below this one (longest chain)
+    int down = -1;                           // such instances above it (memo)
+};
+
+class Graph {
+   public:
+    Graph(const Dag& d, const std::vector<bool>& in_unit, const std::vector<bool>& is_output)
+        : dag(d), in_unit_(in_unit), is_output_(is_output) {
+        ctxs.push_back(Ctx());
+        ctx_ids[""] = 0;
+    }
+
+    int ctx_id(const Ctx& c) {
+        const std::string k = c.key();
+        auto it = ctx_ids.find(k);
+        if (it != ctx_ids.end()) return it->second;
+        ctxs.push_back(c);
+        return ctx_ids[k] = (int)ctxs.size() - 1;
+    }
+
+    int natural_lanes(int node, int ctx) const { return ctxs[ctx].win ? ctxs[ctx].kh * ctxs[ctx].kw : dag.nodes[node].T; }
+
+    // the instance of `node` in context `ctx`; want > 0: an external tensor with fewer taps is read with lane t -> tap t % T
+    int build(int node, int ctx, int want = 0) {
+        const Node& nd = dag.nodes[node];
+        if (ctxs[ctx].win && nd.T != 1) throw Fail{"a window over a tensor that has taps"};
+        int lanes = natural_lanes(node, ctx);
+        const bool external = !in_unit_[node];
+        if (external && want > lanes && lanes > 1) {
+            if (want % lanes) throw Fail{"tap counts of a blend do not divide"};
+            lanes = want;
+        }
+        const auto key = std::make_tuple(node, ctx, lanes);
+        auto it = memo.find(key);
+        if (it != memo.end()) return it->second;
+        Inst I;
+        I.node = node;
+        I.ctx = ctx;
+        I.lanes = lanes;
+        if (external) {
+            I.kind = kExt;
+            return add(key, I);
+        }
+        const bool reduction = nd.op == Op::Softmax || nd.op == Op::Fold;
+        if (reduction && !ctxs[ctx].empty()) throw Fail{"a stencil above a reduction"};
+        switch (nd.op) {
+        case Op::Unfold: {
+            if (ctxs[ctx].win) throw Fail{"nested windows"};
+            Ctx c2 = ctxs[ctx];
+            c2.win = true;
+            c2.kh = nd.kh;
+            c2.kw = nd.kw;
+            I.kind = kStencil;
+            I.opnd[0] = build(nd.a, ctx_id(c2));
+            break;
+        }
+        case Op::Shift: {
+            if ((nd.dh == 0 && nd.dw == 0) || nd.c0 >= nd.c1) {
+                I.kind = kIdent;
+                I.opnd[0] = build(nd.a, ctx);
+            } else {
+                Ctx c2 = ctxs[ctx];
+                Term t;
+                t.dh = (int16_t)nd.dh;
+                t.dw = (int16_t)nd.dw;
+                t.c0 = (uint16_t)nd.c0;
+                t.c1 = (uint16_t)nd.c1;
+                c2.terms.push_back(t);
+                I.kind = kStencil;
+                I.opnd[0] = build(nd.a, ctx_id(c2));
+            }
+            break;
+        }
+        case Op::Unary:
+            I.kind = kUnaryI;
+            I.opnd[0] = build(nd.a, ctx);
+            break;
+        case Op::Softmax:
+            I.kind = nd.kind == kAxisC ? kSmC : kSmT;
+            I.opnd[0] = build(nd.a, ctx);
+            break;
+        case Op::Fold:
+            I.kind = kFoldI;
+            I.opnd[0] = build(nd.a, ctx);
+            break;
+        case Op::Binary: {
+            I.kind = kBinaryI;
+            I.opnd[1] = build(nd.b, ctx);
+            const int tr = insts[I.opnd[1]].lanes;
+            if (tr != lanes) throw Fail{"blend: RHS lanes"};
+            I.opnd[0] = build(nd.a, ctx, tr);
+            const int tl = insts[I.opnd[0]].lanes;
+            if (tl != 1 && tl != tr) throw Fail{"blend: an LHS inside the unit with fewer taps than the RHS"};
+            break;
+        }
+        default: throw Fail{"not a chain primitive"};
+        }
+        return add(key, I);
+    }
+
+    int add(const std::tuple<int, int, int>& key, Inst I) {
+        int lvl = 0;
+        for (int s = 0; s < 2; s++)
+            if (I.opnd[s] >= 0) lvl = std::max(lvl, insts[I.opnd[s]].level);
+        I.level = lvl + (I.kind == kSmC ? 1 : 0);
+        insts.push_back(I);
+        const int id = (int)insts.size() - 1;
+        for (int s = 0; s < 2; s++)
+            if (I.opnd[s] >= 0) insts[I.opnd[s]].users.push_back({id, s});
+        memo[key] = id;
+        return id;
+    }
+
+    // softmax-over-channels instances on the longest way from instance i up to an output (i itself not counted)
+    int down(int i) {
+        if (insts[i].down >= 0) return insts[i].down;
+        int d = 0;
+        for (auto& u : insts[i].users) d = std::max(d, down(u.first) + (insts[u.first].kind == kSmC ? 1 : 0));
+        return insts[i].down = d;
+    }
+
+    const Dag& dag;
+    std::vector<Ctx> ctxs;
+    std::map<std::string, int> ctx_ids;
+    std::vector<Inst> insts;
+    std::map<std::tuple<int, int, int>, int> memo;
+    std::vector<bool> in_unit_, is_output_;
+};
+
+class Emitter {
+   public:
+    Emitter(Graph& g, int tm) : G(g), NR(regs_for(tm)), used(regs_for(tm), false) { pg.tm = tm; }
+
+    void emit(const Instr& I) {
+        if (pg.n_instr >= kMaxInstr) throw Fail{"too many instructions"};
+        pg.ins[pg.n_instr++] = I;
+    }
+    int alloc() {
+        for (int r = 0; r < NR; r++)
+            if (!used[r]) {
+                used[r] = true;
+                return r;
+            }
+        throw Fail{"out of registers"};
+    }
+    void release(int r) { used[r] = false; }
+    int persist(int n) {
+        const int a = pg.n_persist;
+        pg.n_persist += n;
+        return a;
+    }
+    int ext_slot(int node, ExtRole role) {
+        for (size_t i = 0; i < ext.size(); i++)
+            if (ext[i].node == node && ext[i].role == role) return (int)i;
+        if ((int)ext.size() >= kMaxExt) throw Fail{"too many external tensors"};
+        ExtRef e;
+        e.node = node;
+        e.role = role;
+        ext.push_back(e);
+        pg.ext[ext.size() - 1].T = G.dag.nodes[node].T;
+        pg.n_ext = (int)ext.size();
+        return (int)ext.size() - 1;
+    }
+    uint16_t terms(int ctx) {
+        auto it = term_of.find(ctx);
+        if (it != term_of.end()) return it->second;
+        const Ctx& c = G.ctxs[ctx];
+        if (pg.n_terms + (int)c.terms.size() > kMaxTerms) throw Fail{"too many stencil offsets"};
+        const int first = pg.n_terms;
+        for (const Term& t : c.terms) pg.term[pg.n_terms++] = t;
+        return term_of[ctx] = (uint16_t)((first << 8) | (int)c.terms.size());
+    }
+    Instr positional(Opcode op, int ctx, int lanes) {
+        Instr I;
+        I.op = op;
+        I.T = (uint8_t)lanes;
+        I.b = terms(ctx);
+        const Ctx& c = G.ctxs[ctx];
+        if (c.win) {
+            I.kind |= kWin;
+            I.r = (uint8_t)((c.kh << 4) | c.kw);
+        }
+        return I;
+    }
+    static Instr simple(Opcode op, int T, int r = 0, int kind = 0, int a = 0) {
+        Instr I;
+        I.op = op;
+        I.T = (uint8_t)T;
+        I.r = (uint8_t)r;
+        I.kind = (uint8_t)kind;
+        I.a = (uint16_t)a;
+        return I;
+    }
+
+    // ---------------------------------------------------------------- forward values
+    void eval(int i) {
+        const Inst& I = G.insts[i];
+        const Node& nd = G.dag.nodes[I.node];
+        switch (I.kind) {
+        case kExt: {
+            Instr ld = positional(OP_LD, I.ctx, I.lanes);
+            ld.a = (uint16_t)ext_slot(I.node, kValueIn);
+            if (nd.T > 1) ld.kind |= kExtTaps;
+            emit(ld);
+            break;
+        }
+        case kIdent: eval(I.opnd[0]); break;
+        case kStencil: {
+            eval(I.opnd[0]);
+            const Inst& S = G.insts[I.opnd[0]];
+            if (S.kind != kExt) emit(positional(OP_MASK, S.ctx, I.lanes));  // (a load checks its own position)
+            break;
+        }
+        case kUnaryI: {
+            eval(I.opnd[0]);
+            Instr u = simple(OP_UN, I.lanes, 0, nd.kind);
+            u.f0 = nd.lo;
+            u.f1 = nd.hi;
+            emit(u);
+            break;
+        }
+        case kBinaryI: {
+            const int tl = G.insts[I.opnd[0]].lanes;
+            eval(I.opnd[0]);
+            const int r = alloc();
+            emit(simple(OP_MOVR, tl, r));
+            eval(I.opnd[1]);
+            emit(simple(OP_BIN, I.lanes, r, nd.kind | kBinRegIsLhs | (tl == 1 && I.lanes > 1 ? kBinRegScalar : 0)));
+            release(r);
+            break;
+        }
+        case kSmT:
+            eval(I.opnd[0]);
+            emit(simple(OP_SMT, I.lanes));
+            break;
+        case kSmC:
+            eval(I.opnd[0]);
+            emit(simple(OP_SMCAPPLY, I.lanes, 0, 0, stat_slot(i)));
+            break;
+        case kFoldI:
+            eval(I.opnd[0]);
+            emit(simple(OP_FOLD, G.insts[I.opnd[0]].lanes, 0, nd.kind));
+            break;
+        }
+    }
+
+    int stat_slot(int i) {
+        auto it = stats.find(i);
+        if (it != stats.end()) return it->second;
+        return stats[i] = persist(2 * G.insts[i].lanes);
+    }
+    int dot_slot(int i) {
+        auto it = dots.find(i);
+        if (it != dots.end()) return it->second;
+        return dots[i] = persist(G.insts[i].lanes);
+    }
+
+    // ---------------------------------------------------------------- gradients
+    // leaves d loss / d instance i in A (lanes of i)
+    void grad(int i) {
+        const Inst& I = G.insts[i];
+        bool first = true;
+        int held = -1;
+        auto begin_term = [&]() {
+            if (!first) {
+                held = alloc();
+                emit(simple(OP_MOVR, I.lanes, held));
+            }
+        };
+        auto end_term = [&]() {
+            if (!first) {
+                emit(simple(OP_BIN, I.lanes, held, kAdd | kBinRegIsLhs));
+                release(held);
+            }
+            first = false;
+        };
+        if (I.kind != kExt && I.ctx == 0 && G.is_output_[I.node] && I.lanes == G.dag.nodes[I.node].T) {
+            begin_term();
+            Instr ld = positional(OP_LD, 0, I.lanes);
+            ld.a = (uint16_t)ext_slot(I.node, kGradIn);
+            if (I.lanes > 1) ld.kind |= kExtTaps;
+            emit(ld);
+            end_term();
+        }
+        for (const auto& u : I.users) {
+            begin_term();
+            contribution(u.first, u.second, i);
+            end_term();
+        }
+        if (first) throw Fail{"internal: an instance without users"};
+    }
+
+    // d loss / d (operand `slot` of user instance u), which is instance i
+    void contribution(int u, int slot, int i) {
+        const Inst& U = G.insts[u];
+        const Inst& I = G.insts[i];
+        const Node& un = G.dag.nodes[U.node];
+        grad(u);  // A = gradient of u, U.lanes lanes
+        switch (U.kind) {
+        case kIdent: break;
+        case kStencil:
+            if (I.kind != kExt) emit(positional(OP_MASK, I.ctx, U.lanes));
+            break;
+        case kUnaryI: {
+            const int r = alloc();
+            emit(simple(OP_MOVR, U.lanes, r));
+            eval(i);
+            Instr b = simple(OP_UNBX, U.lanes, r, un.kind);
+            b.f0 = un.lo;
+            b.f1 = un.hi;
+            emit(b);
+            release(r);
+            break;
+        }
+        case kBinaryI: {
+            const int other = U.opnd[1 - slot];
+            const int tl = G.insts[U.opnd[0]].lanes;
+            const bool lhs_scalar = tl == 1 && U.lanes > 1;
+            if (un.kind == kAdd || (un.kind == kSub && slot == 0)) {
+            } else if (un.kind == kSub) {
+                emit(simple(OP_UN, U.lanes, 0, kUnNeg));
+            } else if (un.kind == kMul) {
+                const int r = alloc();
+                emit(simple(OP_MOVR, U.lanes, r));
+                eval(other);
+                // A (the other operand) times the gradient in R[r]; the other operand is a scalar when it is the 1-lane LHS
+                emit(simple(OP_BIN, U.lanes, r, kMul | (slot == 1 && lhs_scalar ? kBinAccScalar : 0)));
+                release(r);
+            } else {  // min / max: the indicator needs both operands
+                const int rg = alloc();
+                emit(simple(OP_MOVR, U.lanes, rg));
+                eval(U.opnd[0]);
+                const int rl = alloc();
+                emit(simple(OP_MOVR, tl, rl));
+                eval(U.opnd[1]);
+                emit(simple(OP_BING, U.lanes, rl, un.kind | (slot == 1 ? kBingRhsSide : 0) | (lhs_scalar ? kBingLhsScalar : 0)));
+                emit(simple(OP_BIN, U.lanes, rg, kMul));
+                release(rl);
+                release(rg);
+            }
+            if (slot == 0 && lhs_scalar) emit(simple(OP_FOLD, U.lanes, 0, kSum));  // the replicated LHS collects all lanes
+            break;
+        }
+        case kSmT: {
+            const int r = alloc();
+            emit(simple(OP_MOVR, U.lanes, r));
+            eval(u);
+            emit(simple(OP_SMTBX, U.lanes, r));
+            release(r);
+            break;
+        }
+        case kSmC: {
+            const int r = alloc();
+            emit(simple(OP_MOVR, U.lanes, r));
+            eval(u);
+            emit(simple(OP_SMCBX, U.lanes, r, 0, dot_slot(u)));
+            release(r);
+            break;
+        }
+        case kFoldI: {
+            const int r = alloc();
+            emit(simple(OP_MOVR, 1, r));
+            if (un.kind == kMax) eval(i);
+            emit(simple(OP_FOLDBX, I.lanes, r, un.kind));
+            release(r);
+            break;
+        }
+        case kExt: throw Fail{"internal: an external tensor as a user"};
+        }
+    }
+
+    void begin_pass() {
+        if (pg.n_pass >= kMaxPass) throw Fail{"too many passes"};
+        pg.pass[pg.n_pass].pro_begin = (uint16_t)pg.n_instr;
+    }
+    void begin_body() { pg.pass[pg.n_pass].pro_end = pg.pass[pg.n_pass].body_begin = (uint16_t)pg.n_instr; }
+    void end_pass() { pg.pass[pg.n_pass++].body_end = (uint16_t)pg.n_instr; }
+
+    // the passes that collect the statistics of every softmax over channels, lowest first
+    void stat_passes(const std::vector<int>& smc) {
+        int top = 0;
+        for (int i : smc) top = std::max(top, G.insts[i].level);
+        for (int lvl = 1; lvl <= top; lvl++) {
+            begin_pass();
+            for (int i : smc)
+                if (G.insts[i].level == lvl) {
+                    Instr m = simple(OP_PSET, G.insts[i].lanes, 0, 0, stat_slot(i));
+                    m.f0 = -INFINITY;
+                    emit(m);
+                    emit(simple(OP_PSET, G.insts[i].lanes, 0, 0, stat_slot(i) + G.insts[i].lanes));
+                }
+            begin_body();
+            for (int i : smc)
+                if (G.insts[i].level == lvl) {
+                    eval(G.insts[i].opnd[0]);
+                    emit(simple(OP_SMCSTAT, G.insts[i].lanes, 0, 0, stat_slot(i)));
+                }
+            end_pass();
+        }
+    }
+
+    Graph& G;
+    Program pg;
+    std::vector<ExtRef> ext;
+    int NR;
+    std::vector<bool> used;
+    std::map<int, uint16_t> term_of;
+    std::map<int, int> stats, dots;
+};
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Workgroup shape: rows per tile, halo, channel range, threads.  Throws when the image rows do not fit.
+void set_geometry(Program& pg, const Dag& dag, int C, int halo, bool all_channels) {
+    pg.N = dag.N;
+    pg.C = C;
+    pg.H = dag.H;
+    pg.W = dag.W;
+    pg.halo_rows = halo;
+    const int maxthr = max_threads_for(pg.tm);
+    const int H = dag.H, W = dag.W;
+    if ((int64_t)W * (1 + 2 * halo) > maxthr) throw Fail{"image rows too wide for one workgroup"};
+    int rows;
+    if (halo == 0) {
+        // no recomputed rows: small workgroups (latency hiding comes from many of them); with all channels in one
+        // workgroup the spatial tiles are the only parallelism besides the batch
+        const int target = all_channels ? 128 : 256;
+        rows = std::max(1, std::min(H, target / W));
+    } else {
+        const int most = maxthr / W - 2 * halo;
+        rows = ceil_div(H, ceil_div(H, most));
+    }
+    auto threads_of = [&](int r) { return ceil_div((r + 2 * halo) * W, 64) * 64; };
+    while (rows > 1 && (size_t)(pg.n_persist + 2) * threads_of(rows) * sizeof(float) > kMaxLdsBytes) rows--;
+    pg.tile_rows = rows;
+    pg.threads = threads_of(rows);
+    if (lds_bytes(pg) > kMaxLdsBytes) throw Fail{"persistent state does not fit the LDS"};
+    pg.tiles = ceil_div(H, rows);
+    if (all_channels) {
+        pg.chunk = C;
+        pg.chunks = 1;
+    } else {
+        const int64_t wgs = (int64_t)dag.N * pg.tiles;
+        int chunks = (int)std::min<int64_t>(C, std::max<int64_t>(1, ceil_div(2048, (int)std::min<int64_t>(wgs, 2048))));
+        pg.chunk = ceil_div(C, chunks);
+        pg.chunks = ceil_div(C, pg.chunk);
+    }
+    if ((int64_t)dag.N * pg.tiles * pg.chunks >= ((int64_t)1 << 31)) throw Fail{"too many workgroups"};
+}
+
+}  // namespace
+
+bool chain_candidate(const Dag& dag, int k) {
+    const Node& nd = dag.nodes[k];
+    if (k == 0 || !nd.live || nd.pooled || nd.T > 25 || nd.C > 65535 || dag.W > 1024) return false;
+    const Node& A = dag.nodes[nd.a];
+    if (A.pooled || A.T > 25) return false;
+    switch (nd.op) {
+    case Op::Unfold: return A.T == 1 && nd.kh * nd.kw <= 25;
+    case Op::Shift: return std::abs(nd.dh) < 32768 && std::abs(nd.dw) < 32768;
+    case Op::Unary: return true;
+    case Op::Binary: {
+        const Node& B = dag.nodes[nd.b];
+        return nd.bgroups == 1 && !nd.lhs_pixels && !B.pooled && A.C == B.C && B.T <= 25 && B.T % A.T == 0;
+    }
+    case Op::Softmax: return nd.kind == kAxisC || nd.kind == kAxisT;
+    case Op::Fold: return !nd.axis_hw && !nd.axis_c;
+    default: return false;
+    }
+}
+
+bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vector<bool>& is_output, UnitPlan& out, std::string& why) {
+    try {
+        if (nodes.empty()) throw Fail{"empty unit"};
+        std::vector<bool> in_unit(dag.nodes.size(), false);
+        for (int k : nodes) in_unit[k] = true;
+        const int C = dag.nodes[nodes[0]].C;
+        for (int k : nodes)
+            if (dag.nodes[k].C != C) throw Fail{"channel counts differ inside the unit"};
+        Graph G(dag, in_unit, is_output);
+        out = UnitPlan();
+        out.nodes = nodes;
+        std::vector<int> out_inst;
+        for (int k : nodes)
+            if (is_output[k]) {
+                out.outputs.push_back(k);
+                out_inst.push_back(G.build(k, 0));
+            }
+        if (out.outputs.empty()) throw Fail{"unit without an output"};
+        int lanes = 1;
+        std::vector<int> smc, leaves;
+        for (size_t i = 0; i < G.insts.size(); i++) {
+            lanes = std::max(lanes, G.insts[i].lanes);
+            if (G.insts[i].kind == kSmC) smc.push_back((int)i);
+            if (G.insts[i].kind == kExt) {
+                leaves.push_back((int)i);
+                if (std::find(out.inputs.begin(), out.inputs.end(), G.insts[i].node) == out.inputs.end()) out.inputs.push_back(G.insts[i].node);
+            }
+        }
+        std::sort(out.inputs.begin(), out.inputs.end());
+        for (int e : out.inputs)
+            if (dag.nodes[e].C != C) throw Fail{"an external tensor with another channel count"};
+        if (lanes > 25) throw Fail{"more than 25 taps"};
+        const int tm = lanes <= 1 ? 1 : (lanes <= 9 ? 9 : 25);
+
+        // ------------------------------------------------------------ forward program
+        {
+            Emitter E(G, tm);
+            E.stat_passes(smc);
+            E.begin_pass();
+            E.begin_body();
+            for (size_t o = 0; o < out.outputs.size(); o++) {
+                E.eval(out_inst[o]);
+                Instr st = Emitter::simple(OP_ST, dag.nodes[out.outputs[o]].T, 0, 0, E.ext_slot(out.outputs[o], kValueOut));
+                E.ext[st.a].store_instr = E.pg.n_instr;
+                E.emit(st);
+            }
+            E.end_pass();
+            set_geometry(E.pg, dag, C, 0, !smc.empty());
+            out.fwd = E.pg;
+            out.fwd_ext = E.ext;
+        }
+        // ------------------------------------------------------------ backward program
+        {
+            Emitter E(G, tm);
+            E.stat_passes(smc);
+            int deepest = 0;
+            for (int i : smc) deepest = std::max(deepest, G.down(i));
+            for (int d = 0; d <= deepest && !smc.empty(); d++) {  // the sums of gradient x output, outermost softmax first
+                E.begin_pass();
+                for (int i : smc)
+                    if (G.down(i) == d) E.emit(Emitter::simple(OP_PSET, G.insts[i].lanes, 0, 0, E.dot_slot(i)));
+                E.begin_body();
+                for (int i : smc)
+                    if (G.down(i) == d) {
+                        E.grad(i);
+                        const int r = E.alloc();
+                        E.emit(Emitter::simple(OP_MOVR, G.insts[i].lanes, r));
+                        E.eval(i);
+                        E.emit(Emitter::simple(OP_SMCDOT, G.insts[i].lanes, r, 0, E.dot_slot(i)));
+                        E.release(r);
+                    }
+                E.end_pass();
+            }
+            E.begin_pass();
+            E.begin_body();
+            int halo = 0;
+            for (int e : out.inputs) {
+                std::vector<int> mine;
+                for (int i : leaves)
+                    if (G.insts[i].node == e) mine.push_back(i);
+                const int Te = dag.nodes[e].T;
+                const int slot = E.ext_slot(e, kGradOut);
+                const bool direct = mine.size() == 1 && G.insts[mine[0]].ctx == 0 && G.insts[mine[0]].lanes == Te;
+                int acc = -1;
+                if (!direct) {
+                    acc = E.persist(Te);
+                    E.emit(Emitter::simple(OP_PSET, Te, 0, 0, acc));
+                }
+                for (int i : mine) {
+                    const Inst& L = G.insts[i];
+                    E.grad(i);
+                    if (direct) break;
+                    if (L.ctx == 0) {
+                        Instr p = Emitter::simple(OP_PADD, L.lanes, 0, 0, acc);
+                        p.b = (uint16_t)Te;
+                        E.emit(p);
+                    } else {
+                        if (!G.ctxs[L.ctx].win && L.lanes != Te) throw Fail{"a shifted read of an external tensor with replicated taps"};
+                        Instr x = E.positional(OP_XADD, L.ctx, L.lanes);
+                        x.a = (uint16_t)acc;
+                        if (Te > 1) x.kind |= kExtTaps;
+                        E.emit(x);
+                        halo = std::max(halo, G.ctxs[L.ctx].reach_rows());
+                    }
+                }
+                if (!direct) E.emit(Emitter::simple(OP_PLD, Te, 0, 0, acc));
+                Instr st = Emitter::simple(OP_ST, Te, 0, 0, slot);
+                E.ext[slot].store_instr = E.pg.n_instr;
+                E.emit(st);
+            }
+            E.end_pass();
+            set_geometry(E.pg, dag, C, halo, !smc.empty());
+            out.bwd = E.pg;
+            out.bwd_ext = E.ext;
+        }
+        return true;
+    } catch (const Fail& f) {
+        why = f.why;
+        return false;
+    }
+}
+
+std::string dump(const Program& pg) {
+    static const char* names[] = {"LD", "MASK", "UN", "MOVR", "MOVA", "BIN", "FOLD", "SMT", "ST", "UNBX", "BING", "SMTBX", "FOLDBX",
+                                  "PSET", "PADD", "PLD", "SMCSTAT", "SMCAPPLY", "SMCDOT", "SMCBX", "XADD"};
+    std::ostringstream os;
+    os << "program: C=" << pg.C << " HxW=" << pg.H << "x" << pg.W << " tile_rows=" << pg.tile_rows << " halo=" << pg.halo_rows << " tiles=" << pg.tiles
+       << " chunk=" << pg.chunk << " threads=" << pg.threads << " persist=" << pg.n_persist << " lanes=" << pg.tm << "\n";
+    for (int p = 0; p < pg.n_pass; p++) {
+        os << " pass " << p << "\n";
+        for (int i = pg.pass[p].pro_begin; i < pg.pass[p].body_end; i++) {
+            const Instr& I = pg.ins[i];
+            os << (i < pg.pass[p].pro_end ? "  pro  " : "  body ") << i << ": " << (I.op < OP_COUNT ? names[I.op] : "?") << " T=" << (int)I.T
+               << " kind=" << (int)I.kind << " r=" << (int)I.r << " a=" << I.a << " b=" << I.b << " f0=" << I.f0 << "\n";
+        }
+    }
+    return os.str();
+}
+
+}  // namespace chain
+}  // namespace canvas

@@ -26,7 +26,7 @@ std::unique_ptr<Lowering> lower(const Dag& full, bool bf16, bool no_fusion) {
         if (!l && !tiny_weight) l = lower_ufc(dag, bf16);
         if (!l && !tiny_weight) l = lower_dyn(dag, bf16);
     }
-    if (!l) l = lower_per_node(dag, bf16);
+    if (!l) l = lower_per_node(dag, bf16, !no_fusion);
     batch_weight_jobs(*l);
     batch_reduce_jobs(*l);
     return l;

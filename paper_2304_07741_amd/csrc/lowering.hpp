@@ -50,7 +50,9 @@ struct ReduceJob {
 };
 
 struct Lowering {
-    bool fused = false;
+    bool fused = false;            // one of the whole-DAG kernel families
+    int chain_units = 0;           // fused chains in the forward list (each is one kernel forward, one backward)
+    int chain_nodes = 0;           // nodes inside them
     uint64_t ws_bytes = 0;
     std::vector<Launch> fwd, bwd;
     std::vector<WeightJob> wjobs;  // collected while lowering; batch_weight_jobs turns them into launches
@@ -71,8 +73,9 @@ void make_inference_plan(Lowering& low);
 
 inline uint64_t align_up(uint64_t v, uint64_t a = 256) { return (v + a - 1) / a * a; }
 
-// One kernel per node, fp32 intermediates.  Handles every legal DAG.
-std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16);
+// Lowering by units: fused chains of memory-bound primitives between the FC nodes (fuse_chains), one kernel per
+// node for whatever no chain takes; fp32 tensors between units.  Handles every legal DAG.
+std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16, bool fuse_chains);
 
 // Fused shift -> grouped FC -> unary chain -> (+ input); nullptr when the DAG is not of that form.
 std::unique_ptr<Lowering> lower_sgfc(const Dag& dag, bool bf16);

@@ -91,6 +91,58 @@ def test_illegal_blobs_give_status_codes(lib, body, status):
     assert str(e.value)
 
 
+def test_random_dags_are_lowered_to_fused_chains(lib):
+    """Lowering by units on the 200 random DAGs of config 5 (host logic only): the runs of memory-bound primitives
+    between FC nodes become fused chains, few launches remain, and switching fusion off gives one kernel per node."""
+    chains, fwd, bwd, fully = 0, 0, 0, 0
+    for seed in range(100, 300):
+        case = wl.config5(seed)
+        h = B.canvas_dag_compile(case["blob"], case["shape"], B.CANVAS_BF16)
+        info = B.canvas_dag_query(h)
+        names = [B.canvas_dag_launch_desc(h, 0, i)["name"] for i in range(info.n_launches_fwd)]
+        n_nonfc = sum(1 for line in case["blob"].splitlines() if " = " in line and " fc " not in line)
+        assert info.n_fused_nodes <= n_nonfc and info.n_fused_chains <= info.n_fused_nodes
+        assert names.count("chain_fwd") == info.n_fused_chains
+        chains += 1 if info.n_fused_chains else 0
+        fully += 1 if info.n_fused_chains and not any(n.startswith("node_") and "fc" not in n for n in names) else 0
+        fwd += info.n_launches_fwd
+        bwd += info.n_launches_bwd
+        B.canvas_dag_destroy(h)
+        h = B.canvas_dag_compile(case["blob"], case["shape"], B.CANVAS_BF16, B.CANVAS_OPT_NO_FUSION)
+        assert B.canvas_dag_query(h).n_fused_chains == 0
+        B.canvas_dag_destroy(h)
+    assert chains >= 185 and fully >= 170, (chains, fully)
+    assert fwd / 200 <= 3.0 and bwd / 200 <= 6.0, (fwd / 200, bwd / 200)
+
+
+def test_chain_boundaries(lib):
+    """What ends a fused chain: a stencil above a reduction, an FC, a blend across channel counts."""
+    H = wl.HEADER
+
+    def plan(body, shape=(2, 96, 16, 16)):
+        h = B.canvas_dag_compile(H + body, shape, B.CANVAS_BF16)
+        info = B.canvas_dag_query(h)
+        names = [B.canvas_dag_launch_desc(h, 0, i)["name"] for i in range(info.n_launches_fwd)]
+        B.canvas_dag_destroy(h)
+        return info.n_fused_chains, info.n_fused_nodes, names
+
+    # element-wise work, shifts and an unfold that is folded again: one kernel, x read and y written in place
+    assert plan("%1 = unary %0 op=relu\n%2 = unfold %1 kh=3 kw=3\n%3 = softmax %2 axis=T\n%4 = binary %3 %2 op=mul\n"
+                "%5 = unary %4 op=gelu\n%6 = fold %5 op=sum\noutput %6\n") == (1, 6, ["chain_fwd"])
+    # a softmax over channels inside a chain (statistics in a pass of their own), stencils above element-wise work
+    assert plan("%1 = shift %0 dh=0 dw=2 c0=0 c1=96\n%2 = unary %1 op=expclip lo=-4 hi=4\n%3 = binary %0 %2 op=add\n"
+                "%4 = shift %3 dh=-2 dw=0 c0=0 c1=48\n%5 = softmax %4 axis=C\noutput %5\n") == (1, 5, ["chain_fwd"])
+    # an unfold of a folded (reduced) tensor starts a new chain: the reduction would be needed at other pixels
+    assert plan("%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=sum\n%3 = unfold %2 kh=5 kw=5\n%4 = binary %2 %3 op=mul\n"
+                "%5 = fold %4 op=avg\noutput %5\n") == (2, 5, ["chain_fwd", "chain_fwd"])
+    # FC nodes cut; an unfold that only FCs read is never a node of a chain (the contraction reads it in place)
+    assert plan("%1 = unary %0 op=abs\n%2 = unfold %1 kh=3 kw=3\n%3 = fc %2 groups=4 out=96\n%4 = unary %3 op=gelu\noutput %4\n") \
+        == (2, 2, ["chain_fwd", "gfc_fwd_unfold", "chain_fwd"])
+    # a blend across channel counts keeps a kernel of its own
+    n_chains, n_nodes, names = plan("%1 = fc %0 groups=1 out=48\n%2 = binary %1 %0 op=mul\n%3 = unary %2 op=relu\noutput %3\n")
+    assert "node_binary_fwd" in names and n_chains == 1 and n_nodes == 1
+
+
 def test_huge_shift_is_clamped_to_the_image(lib):
     """A shift by the image's extent or more leaves nothing inside: the parser clamps it (the kernels multiply dh by W)."""
     h = B.canvas_dag_compile(wl.HEADER + "%1 = shift %0 dh=1073741824 dw=-1073741824\noutput %1\n", (1, 4, 4, 4), B.CANVAS_F32)
