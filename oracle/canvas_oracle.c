@@ -23,6 +23,10 @@
  * largest magnitude of the deciding tensor (per image): m < 0 and m > 0 bracket
  * the default m = 0, which is the definition itself (first maximum, relu'(0) = 0,
  * sign(0) = 0, ties of min / max to the LHS) and the only setting the pins use.
+ * A rule selects which decisions move: 0 all, 1 / 2 those at even / odd flat
+ * element index (so that of two near-ties that feed one output element the
+ * bracketing runs also cover "one moved, the other not"), 3 all, and a max fold
+ * takes the runner-up inside the margin instead of the first / last one.
  * The forward pass never depends on it.
  *
  * Decisions of the backward pass (which operand of a max was the larger, the
@@ -110,7 +114,11 @@ typedef struct {
 
 /* 0 = the definitions; see "Tie margin" above.  Set before a run, read-only during it. */
 static double g_tie_margin = 0.0;
+static int g_tie_rule = 0;
 void canvas_oracle_set_tie_margin(double m) { g_tie_margin = m; }
+void canvas_oracle_set_tie_rule(int r) { g_tie_rule = r; }
+/* does the margin apply to the decision at flat element index j? */
+static int tie_applies(size_t j) { return g_tie_rule == 1 ? (j & 1) == 0 : (g_tie_rule == 2 ? (j & 1) == 1 : 1); }
 
 static double max_abs(const double *v, size_t n) {
     double s = 0.0;
@@ -684,11 +692,12 @@ static void bwd_unary(const Dag *d, const Node *nd, int k, const double *in, con
     double e = g_tie_margin != 0.0 ? g_tie_margin * max_abs(in, n) : 0.0;
     for (j = 0; j < n; j++) {
         double x = in[j], dv = 0.0, xd = (double)(float)x;  /* xd: what the decisions look at */
+        double ej = (e != 0.0 && tie_applies(j)) ? e : 0.0;
         switch (nd->kind) {
-        case UN_RELU: dv = xd > e ? 1.0 : 0.0; break;
-        case UN_ABS: dv = xd > e ? 1.0 : (xd < e ? -1.0 : 0.0); break;
+        case UN_RELU: dv = xd > ej ? 1.0 : 0.0; break;
+        case UN_ABS: dv = xd > ej ? 1.0 : (xd < ej ? -1.0 : 0.0); break;
         case UN_GELU: dv = gelu_cdf(x) + x * gelu_pdf(x); break;
-        case UN_EXPCLIP: dv = (xd > (double)(float)nd->lo + e && xd < (double)(float)nd->hi - e) ? out[j] : 0.0; break;
+        case UN_EXPCLIP: dv = (xd > (double)(float)nd->lo + ej && xd < (double)(float)nd->hi - ej) ? out[j] : 0.0; break;
         case UN_SIN: dv = cos(x); break;
         }
         gin[j] += gout[j] * dv;
@@ -717,8 +726,8 @@ static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
                 case BIN_ADD: glhs[lp] += g; grhs[ro + p] += g; break;
                 case BIN_MUL: glhs[lp] += g * b; grhs[ro + p] += g * a; break;
                 case BIN_SUB: glhs[lp] += g; grhs[ro + p] -= g; break;
-                case BIN_MIN: if ((double)(float)a <= (double)(float)b + e) glhs[lp] += g; else grhs[ro + p] += g; break;
-                case BIN_MAX: if ((double)(float)a >= (double)(float)b - e) glhs[lp] += g; else grhs[ro + p] += g; break;
+                case BIN_MIN: if ((double)(float)a <= (double)(float)b + (tie_applies(ro + p) ? e : 0.0)) glhs[lp] += g; else grhs[ro + p] += g; break;
+                case BIN_MAX: if ((double)(float)a >= (double)(float)b - (tie_applies(ro + p) ? e : 0.0)) glhs[lp] += g; else grhs[ro + p] += g; break;
                 }
             }
         }
@@ -814,9 +823,15 @@ static void bwd_fold(const Dag *d, const Node *nd, const double *in, const doubl
                 int best = 0;
                 for (t = 1; t < T; t++)
                     if (DEC(in[((size_t)c * T + t) * P + p]) > DEC(in[((size_t)c * T + best) * P + p])) best = t;
-                if (e != 0.0) {
+                if (e != 0.0 && tie_applies((size_t)c * P + p)) {
                     double m = DEC(in[((size_t)c * T + best) * P + p]) - fabs(e);
-                    if (e < 0.0) { for (t = 0; t < T; t++) if (DEC(in[((size_t)c * T + t) * P + p]) >= m) { best = t; break; } }
+                    if (g_tie_rule == 3) {  /* the runner-up, if it is inside the margin */
+                        int second = -1;
+                        for (t = 0; t < T; t++)
+                            if (t != best && (second < 0 || DEC(in[((size_t)c * T + t) * P + p]) > DEC(in[((size_t)c * T + second) * P + p]))) second = t;
+                        if (second >= 0 && DEC(in[((size_t)c * T + second) * P + p]) >= m) best = second;
+                    }
+                    else if (e < 0.0) { for (t = 0; t < T; t++) if (DEC(in[((size_t)c * T + t) * P + p]) >= m) { best = t; break; } }
                     else { for (t = T - 1; t >= 0; t--) if (DEC(in[((size_t)c * T + t) * P + p]) >= m) { best = t; break; } }
                 }
                 gin[((size_t)c * T + best) * P + p] += g;

@@ -31,6 +31,7 @@ def _load():
         lib.canvas_oracle_infer.restype = ctypes.c_int
         lib.canvas_oracle_run.restype = ctypes.c_int
         lib.canvas_oracle_set_tie_margin.restype = None
+        lib.canvas_oracle_set_tie_rule.restype = None
         _lib = lib
     return _lib
 
@@ -57,12 +58,13 @@ def infer(blob, in_shape):
     return ns, out_node.value, ws
 
 
-def run(blob, x, weights, dy=None, n_threads=0, tie_margin=0.0):
+def run(blob, x, weights, dy=None, n_threads=0, tie_margin=0.0, tie_rule=0):
     """Run the DAG on fp64 copies of the inputs.
 
     tie_margin: 0 = the definitions; a non-zero value moves every backward decision point (relu, abs, clip
     bounds, min / max, arg-max of a max fold) by that fraction of the deciding tensor's largest magnitude
-    (see the C file), which the comparison rule of the tests uses to bracket near-ties.
+    (see the C file), which the comparison rule of the tests uses to bracket near-ties; tie_rule selects which
+    decisions move (0 all, 1 / 2 even / odd element index, 3 runner-up of a max fold).
 
     x: [N,C,H,W]; weights: list of [G,Og,K]; dy: like the output or None.
     Returns dict(y=[N,C,T,H,W] squeezed to [N,C,H,W] when T==1, dx, dw=list, threads).
@@ -99,10 +101,12 @@ def run(blob, x, weights, dy=None, n_threads=0, tie_margin=0.0):
     shp = (ctypes.c_int64 * 4)(*x.shape)
     err = ctypes.create_string_buffer(256)
     lib.canvas_oracle_set_tie_margin(ctypes.c_double(float(tie_margin)))
+    lib.canvas_oracle_set_tie_rule(ctypes.c_int(int(tie_rule)))
     try:
         rc = _call_run(lib, b, shp, x, warr, wl, dy_p, y, dx_p, dwarr, n_threads, err, dbl_p)
     finally:
         lib.canvas_oracle_set_tie_margin(ctypes.c_double(0.0))
+        lib.canvas_oracle_set_tie_rule(ctypes.c_int(0))
     if rc < 0:
         raise OracleError(err.value.decode())
     if T == 1:

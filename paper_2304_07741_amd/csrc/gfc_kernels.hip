@@ -209,10 +209,9 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         }
     };
 
-    for (int k0 = 0; k0 < P.K; k0 += 16) {
-        RawChunk<SRC_F32> cur;
-        short4_t wa[MO];
-        load_raw(k0, cur, wa);
+    // One chunk of 16 contraction rows as MFMA operands: bs[q] for pixel q of the lane's unit (and bl[q], the low
+    // halves of fp32 rows)
+    auto operands = [&](int k0, const RawChunk<SRC_F32>& cur, short4_t (&bs)[8], short4_t (&bl)[8]) {
         u32x4 xs[4], xl[4];
 #pragma unroll
         for (int j = 0; j < 4; j++) {
@@ -239,18 +238,34 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 if (SRC_F32) xl[j] = xl[j] & m;
             }
         }
-        short4_t b[8];
-        gather_all(xs, b);
-#pragma unroll
-        for (int q = 0; q < 8; q++)
-#pragma unroll
-            for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[mo], b[q], acc[mo][q]);
-        if (SRC_F32) {
-            gather_all(xl, b);
+        gather_all(xs, bs);
+        if (SRC_F32) gather_all(xl, bl);
+    };
+    if (SRC_F32) {
+        // fp32 rows: the high and the low bf16 halves of a chunk meet the same weights: one K = 32 step, w | w against hi | lo
+        for (int k0 = 0; k0 < P.K; k0 += 16) {
+            RawChunk<SRC_F32> cur;
+            short4_t wa[MO], bs[8], bl[8];
+            load_raw(k0, cur, wa);
+            operands(k0, cur, bs, bl);
 #pragma unroll
             for (int q = 0; q < 8; q++)
 #pragma unroll
-                for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[mo], b[q], acc[mo][q]);
+                for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma32(wa[mo], wa[mo], bs[q], bl[q], acc[mo][q]);
+        }
+    } else {
+        // bf16 rows: two chunks of 16 rows per K = 32 step (rows beyond K load as zeros, weights too)
+        for (int k0 = 0; k0 < P.K; k0 += 32) {
+            RawChunk<SRC_F32> c0, c1;
+            short4_t w0[MO], w1[MO], b0[8], b1[8], unused[8];
+            load_raw(k0, c0, w0);
+            load_raw(k0 + 16, c1, w1);
+            operands(k0, c0, b0, unused);
+            operands(k0 + 16, c1, b1, unused);
+#pragma unroll
+            for (int q = 0; q < 8; q++)
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma32(w0[mo], w1[mo], b0[q], b1[q], acc[mo][q]);
         }
     }
 
@@ -418,17 +433,10 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
         for (int mo = 0; mo < MO; mo++)
 #pragma unroll
             for (int nk = 0; nk < NK; nk++) {
-                float4_t c = acc[mo][nk];
-                c = mfma16(as_short4(a[mo].hi[0], a[mo].hi[1]), as_short4(b[nk].hi[0], b[nk].hi[1]), c);
-                c = mfma16(as_short4(a[mo].hi[2], a[mo].hi[3]), as_short4(b[nk].hi[2], b[nk].hi[3]), c);
-                if (DY_F32) {
-                    c = mfma16(as_short4(a[mo].lo[0], a[mo].lo[1]), as_short4(b[nk].hi[0], b[nk].hi[1]), c);
-                    c = mfma16(as_short4(a[mo].lo[2], a[mo].lo[3]), as_short4(b[nk].hi[2], b[nk].hi[3]), c);
-                }
-                if (SRC_F32) {
-                    c = mfma16(as_short4(a[mo].hi[0], a[mo].hi[1]), as_short4(b[nk].lo[0], b[nk].lo[1]), c);
-                    c = mfma16(as_short4(a[mo].hi[2], a[mo].hi[3]), as_short4(b[nk].lo[2], b[nk].lo[3]), c);
-                }
+                float4_t c = acc[mo][nk];  // (8 pixels per lane and operand: one K = 32 step each)
+                c = mfma32(a[mo].hi, b[nk].hi, c);
+                if (DY_F32) c = mfma32(a[mo].lo, b[nk].hi, c);
+                if (SRC_F32) c = mfma32(a[mo].hi, b[nk].lo, c);
                 acc[mo][nk] = c;
             }
         if (++pc == P.chunks32) { pc = 0; n++; }
@@ -549,8 +557,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad64(Params P) {
 #pragma unroll
                 for (int nk = 0; nk < NK; nk++) {
                     float4_t t = acc[mo][nk];
-                    t = mfma16(as_short4(a[h][mo][0], a[h][mo][1]), as_short4(b[h][nk][0], b[h][nk][1]), t);
-                    t = mfma16(as_short4(a[h][mo][2], a[h][mo][3]), as_short4(b[h][nk][2], b[h][nk][3]), t);
+                    t = mfma32(a[h][mo], b[h][nk], t);
                     acc[mo][nk] = t;
                 }
         }

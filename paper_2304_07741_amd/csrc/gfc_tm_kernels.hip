@@ -196,7 +196,11 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
         }
     };
 
-    auto consume = [&](int rc, int kh, Group<MO, KW, WL>& b) {
+    struct Pending {
+        short4_t wa[MO];
+        short4_t b[8];
+    } pend;
+    auto consume = [&](int rc, int kh, Group<MO, KW, WL>& b, int phase) {
         short4_t wa[KW][MO];  // A operands: outputs 16 * mo + s, rows 4r .. 4r+3 of the chunk, tap (kh, kw)
 #pragma unroll
         for (int kw = 0; kw < KW; kw++)
@@ -239,19 +243,83 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
             op[t][0] = __builtin_amdgcn_perm(b.d[1][t >> 1], b.d[0][t >> 1], sel);
             op[t][1] = __builtin_amdgcn_perm(b.d[3][t >> 1], b.d[2][t >> 1], sel);
         }
-#pragma unroll
-        for (int kw = 0; kw < KW; kw++)
-#pragma unroll
-            for (int q = 0; q < 8; q++) {
-                u32x2 o = op[q + kw - HW + E0];
-                if (kw != HW) {
-                    o[0] &= cm[q][kw];
-                    o[1] &= cm[q][kw];
-                }
-                const short4_t bq = as_short4(o[0], o[1]);
-#pragma unroll
-                for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[kw][mo], bq, acc[mo][q]);
+        // operand of output pixel q for window column kw (its source pixel q + kw - HW, zero where that leaves the image row)
+        auto bop = [&](int q, int kw) {
+            u32x2 o = op[q + kw - HW + E0];
+            if (kw != HW) {
+                o[0] &= cm[q][kw];
+                o[1] &= cm[q][kw];
             }
+            return as_short4(o[0], o[1]);
+        };
+        if constexpr (KW == 1) {
+            // no window: two row chunks of 16 make one K = 32 step.  phase 0 keeps this chunk's operands, phase 1
+            // multiplies the kept chunk and this one, phase 2 (a last chunk without a partner) multiplies alone.
+            if (phase == 0) {
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++) pend.wa[mo] = wa[0][mo];
+#pragma unroll
+                for (int q = 0; q < 8; q++) pend.b[q] = bop(q, 0);
+            } else if (phase == 1) {
+#pragma unroll
+                for (int q = 0; q < 8; q++) {
+                    const short4_t bq = bop(q, 0);
+#pragma unroll
+                    for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma32(pend.wa[mo], wa[0][mo], pend.b[q], bq, acc[mo][q]);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 8; q++)
+#pragma unroll
+                    for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma32(wa[0][mo], short4_t{0, 0, 0, 0}, bop(q, 0), short4_t{0, 0, 0, 0}, acc[mo][q]);
+            }
+        } else {
+            // every accumulator is complete before, and is first used after, a stretch of wait states longer than the
+            // longest MFMA takes to write its result (the empty asm statements tie the accumulators to this point
+            // without stopping the scheduler from moving loads across)
+            auto shape_fence = [&]() {
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+                    for (int q = 0; q < 8; q++) asm volatile("" : "+v"(acc[mo][q]));
+                asm volatile("s_nop 15\n\ts_nop 7");
+#pragma unroll
+                for (int mo = 0; mo < MO; mo++)
+#pragma unroll
+                    for (int q = 0; q < 8; q++) asm volatile("" : "+v"(acc[mo][q]));
+            };
+            if constexpr (KW == 3) {
+                // a 3-wide window row: columns 0 and 1 are one K = 32 step (same 16 rows, two taps), column 2 a K = 16
+                // step.  An accumulator that went from one of the two MFMA shapes straight into the other came back
+                // wrong (measured on gfx950 with this compiler: y of every 3 x 3 contraction off by tens of percent;
+                // correct as soon as the two were apart).  So all K = 16 steps come first, then all K = 32 steps, and
+                // each block is fenced (below).
+                shape_fence();
+#pragma unroll
+                for (int q = 0; q < 8; q++) {
+                    const short4_t b2 = bop(q, 2);
+#pragma unroll
+                    for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[2][mo], b2, acc[mo][q]);
+                }
+                shape_fence();
+#pragma unroll
+                for (int q = 0; q < 8; q++) {
+                    const short4_t b0 = bop(q, 0), b1 = bop(q, 1);
+#pragma unroll
+                    for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma32(wa[0][mo], wa[1][mo], b0, b1, acc[mo][q]);
+                }
+            } else {
+                // (5 x 5: the wider operands would cost the registers that keep two wavefronts per SIMD)
+#pragma unroll
+                for (int q = 0; q < 8; q++)
+#pragma unroll
+                    for (int kw = 0; kw < KW; kw++) {
+                        const short4_t bq = bop(q, kw);
+#pragma unroll
+                        for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[kw][mo], bq, acc[mo][q]);
+                    }
+            }
+        }
     };
 
     // Output rows of the tile as T = 4 * MO "row slots" t = 4 * mo + j (output 16 * mo + 4 * r + j of this lane, 8 pixels
@@ -293,7 +361,8 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
                 const int rcn = KH > 1 ? (u + 1 == KH ? it + 1 : it) : g + 1;  // index among this wavefront's chunks
                 issue(ks + rcn * KS, khn, g + 1 < NG, buf[(u + 1) % UNR]);
                 __builtin_amdgcn_sched_barrier(0);
-                consume(ks + (KH > 1 ? it : g) * KS, KH > 1 ? u : 0, buf[u]);
+                // (no window: UNR == 2, the chunks of an iteration are the two halves of a K = 32 step)
+                consume(ks + (KH > 1 ? it : g) * KS, KH > 1 ? u : 0, buf[u], KW > 1 ? 2 : (u == 0 ? (g + 1 < NG ? 0 : 2) : 1));
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -641,8 +710,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad(Params P) {
 #pragma unroll
                 for (int mo = 0; mo < MO; mo++) {
                     float4_t c = acc[mo][kh * KW + kw];
-                    c = mfma16(as_short4(a[mo][0], a[mo][1]), as_short4(xs[0], xs[1]), c);
-                    c = mfma16(as_short4(a[mo][2], a[mo][3]), as_short4(xs[2], xs[3]), c);
+                    c = mfma32(as_short4(a[mo][0], a[mo][1]), as_short4(a[mo][2], a[mo][3]), as_short4(xs[0], xs[1]), as_short4(xs[2], xs[3]), c);
                     acc[mo][kh * KW + kw] = c;
                 }
             }
@@ -858,8 +926,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_wgrad_rows(Params P) {
 #pragma unroll
                 for (int mo = 0; mo < MO; mo++) {
                     float4_t cc = acc[mo][kh * KW + kw];
-                    cc = mfma16(as_short4(a[mo][0], a[mo][1]), as_short4(xs[0], xs[1]), cc);
-                    cc = mfma16(as_short4(a[mo][2], a[mo][3]), as_short4(xs[2], xs[3]), cc);
+                    cc = mfma32(as_short4(a[mo][0], a[mo][1]), as_short4(a[mo][2], a[mo][3]), as_short4(xs[0], xs[1]), as_short4(xs[2], xs[3]), cc);
                     acc[mo][kh * KW + kw] = cc;
                 }
             }

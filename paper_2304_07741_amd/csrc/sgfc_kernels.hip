@@ -154,7 +154,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
 #pragma unroll
         for (int q = 0; q < 8; q++)
 #pragma unroll
-            for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[mo][kc], b[q], acc[mo][q]);
+            for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[mo][kc], b[q], acc[mo][q]);  // (a group contracts 16 channels: K = 16 is the whole depth)
     }
     const int yo = ((n * Cout + g * OG) * P.P) * 2;
 #pragma unroll
@@ -308,8 +308,7 @@ __device__ __forceinline__ void bwd_tile(const Params& P, rsrc_t rx, rsrc_t rdy,
 #pragma unroll
             for (int kc = 0; kc < KC; kc++) {
                 const u32x4 xb = lds_x[(kc * 16 + s) * kLdsRow + 4 * m + r];
-                dwacc[mo][kc] = mfma16(as_short4(dzb[0], dzb[1]), as_short4(xb[0], xb[1]), dwacc[mo][kc]);
-                dwacc[mo][kc] = mfma16(as_short4(dzb[2], dzb[3]), as_short4(xb[2], xb[3]), dwacc[mo][kc]);
+                dwacc[mo][kc] = mfma32(as_short4(dzb[0], dzb[1]), as_short4(dzb[2], dzb[3]), as_short4(xb[0], xb[1]), as_short4(xb[2], xb[3]), dwacc[mo][kc]);
             }
         }
 }

@@ -105,6 +105,25 @@ __device__ __forceinline__ float4_t mfma16(short4_t a, short4_t b, float4_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
 }
 
+// The gfx950 form with twice the contraction depth: 8 bf16 per lane and operand, K = 32.  Lane l holds row (column)
+// l % 16 and the 8 contraction indices of lane group l / 16, in both operands alike, so two K = 16 operand pairs
+// (a0, b0) and (a1, b1) that add into one accumulator are one K = 32 step: a0 | a1 against b0 | b1.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ float4_t mfma32(short4_t a0, short4_t a1, short4_t b0, short4_t b1, float4_t c) {
+    const short4_t av[2] = {a0, a1}, bv[2] = {b0, b1};
+    bf16x8_t a, b;
+    __builtin_memcpy(&a, av, 16);
+    __builtin_memcpy(&b, bv, 16);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+// Eight bf16 in four dwords against eight bf16 in four dwords.
+__device__ __forceinline__ float4_t mfma32(const u32x4& a, const u32x4& b, float4_t c) {
+    bf16x8_t av, bv;
+    __builtin_memcpy(&av, &a, 16);
+    __builtin_memcpy(&bv, &b, 16);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, c, 0, 0, 0);
+}
+
 // kMaskLut.m[b] = the four dword masks that keep the bf16 elements whose bit is set in the 8-bit pattern b.
 struct alignas(16) MaskLut {
     uint32_t m[256][4];
