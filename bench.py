@@ -2,7 +2,11 @@
 of its dominant kernel and the CPU oracle timed beside it.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload shift_residual|involution|sampled_cC_hH]
+    python bench.py --workload fuzz [--seeds 100:300]  (config 5: geometric mean over the random DAGs, chain kernels vs HBM)
+    python bench.py --fc-micro                         (grouped-FC kernels of config 4, operands in cache, vs MFMA peak)
     python bench.py --infer BATCH [--workload ...]     (forward-only latency of the inference plan, not the headline)
+
+The default run measures config 2 (`value`) and adds `per_config`: config 3 and the four shapes of config 4.
 
 One step = one forward + one backward of the whole micro-DAG over one batch resident in HBM.  Buffer
 sets are rotated so that consecutive steps do not find their operands in the 256 MB last-level cache.
@@ -175,42 +179,21 @@ def copy_reference(args):
                                  "buffer_pairs": sets, "ms_min": ms[0]}}))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="shift_residual")
-    ap.add_argument("--no-fusion", action="store_true", help="per-node lowering (for comparison)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--infer", type=int, default=0, metavar="BATCH",
-                    help="instead of the training step: forward-only latency of the inference plan at this batch size")
-    ap.add_argument("--copy-ref", action="store_true",
-                    help="instead of a micro-DAG: the rate of a plain device copy of one activation tensor of the workload "
-                         "(torch's copy kernel, cold buffers), the reference that kernel times are compared with")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        raise SystemExit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
-    if args.infer:
-        return infer_latency(args)
-    if args.copy_ref:
-        return copy_reference(args)
-
+def measure(case, flags, steps, warmup, rotate=True, kernel_steps=50):
+    """W warm-up + K timed steps (forward + backward) of one workload, then the same steps with HIP events around every
+    launch.  Returns ms per step, the per-launch list and the first runner's plan info."""
     import torch
 
     from paper_2304_07741_amd import binding as B
     from paper_2304_07741_amd import harness
     from paper_2304_07741_amd import workloads as wl
 
-    case = make_case(args.workload)
-    N = case["shape"][0]
-    flags = B.CANVAS_OPT_NO_FUSION if args.no_fusion else 0
     first = harness.DagRunner(case["blob"], case["shape"], case["dtype"], flags)
     oshape = first.out_shape if first.out_shape[2] != 1 else (first.out_shape[0], first.out_shape[1], *first.out_shape[3:])
     dy = wl.make_dy(case, oshape)
-    # rotate buffer sets: > 2x the last-level cache in total, at most 8 sets
+    # rotate buffer sets: > 2x the last-level cache in total, at most 8 sets (rotate=False: operands stay in cache)
     per_set = sum(t.numel() * t.element_size() for t in (first.x, first.y, first.dy, first.dx)) + int(first.info.workspace_bytes)
-    n_sets = max(2, min(8, -(-600_000_000 // per_set)))
+    n_sets = max(2, min(8, -(-600_000_000 // per_set))) if rotate else 1
     runners = [first] + [harness.DagRunner(case["blob"], case["shape"], case["dtype"], flags) for _ in range(n_sets - 1)]
     for r in runners:
         r.load(case["x"], case["weights"], dy)
@@ -221,22 +204,20 @@ def main():
         r.forward()
         r.backward()
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
+    ms_per_step = 1e3 * (time.perf_counter() - t0) / steps
 
-    # per-kernel durations: the same steps again with HIP events around every launch
     nf, nb = first.info.n_launches_fwd, first.info.n_launches_bwd
     for r in runners:
         B.canvas_dag_set_timing(r.handle, 1)
     acc = [[0.0] * nf, [0.0] * nb]
-    psteps = min(args.steps, 50)
+    psteps = max(1, min(steps, kernel_steps))
     for i in range(psteps):
         r = runners[i % n_sets]
         r.forward()
@@ -249,25 +230,151 @@ def main():
     launches = []
     for b in (0, 1):
         for k, d in enumerate(first.launches(b)):
-            launches.append({"phase": "bwd" if b else "fwd", "name": d["name"], "ms": acc[b][k], "bytes": d["bytes"],
-                             "flops": d["flops"]})
+            launches.append({"phase": "bwd" if b else "fwd", "name": d["name"], "ms": acc[b][k], "bytes": d["bytes"], "flops": d["flops"]})
+    info = {"fused": bool(first.info.fused), "chains": int(first.info.n_fused_chains), "chain_nodes": int(first.info.n_fused_nodes),
+            "buffer_sets": n_sets, "launches_fwd": nf, "launches_bwd": nb, "workspace_bytes": int(first.info.workspace_bytes),
+            "min_bytes": first.info.min_bytes_fwd + first.info.min_bytes_bwd}
+    for r in runners:
+        r.close()
+    del runners, first
+    torch.cuda.empty_cache()
+    return ms_per_step, launches, info
+
+
+def roofline_of(launches, workload, fused):
+    """The slowest launch against the roof that binds it (its own algorithmic bytes / flops)."""
     dom = max(launches, key=lambda l: l["ms"])
     hbm_t = dom["bytes"] / (HBM_PEAK_GBS * 1e9)
     mfma_t = dom["flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if mfma_t > hbm_t:
         ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+        roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None}
     else:
         ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                "traffic": None}
-    if roof["bound"] == "hbm" and not args.no_fusion:
-        roof["traffic"] = measured_traffic(args.workload, dom["name"])
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+    if fused:
+        roof["traffic"] = measured_traffic(workload, dom["name"])
     roof["kernel"] = f"{dom['name']} ({dom['phase']})"
     roof["kernel_ms"] = dom["ms"]
     roof["algorithmic_bytes"] = dom["bytes"]
+    roof["algorithmic_flops"] = dom["flops"]
+    return roof
 
+
+def kernel_rows(launches):
+    return [{"phase": l["phase"], "name": l["name"], "ms": round(l["ms"], 5), "GBps": round(l["bytes"] / max(l["ms"], 1e-9) / 1e6, 1),
+             "TFLOPps": round(l["flops"] / max(l["ms"], 1e-9) / 1e9, 2)} for l in launches]
+
+
+PER_CONFIG = ["involution", "sampled_c64_h56", "sampled_c128_h28", "sampled_c256_h14", "sampled_c512_h7"]
+
+
+def fuzz_bench(args):
+    """Config 5: the 200 random micro-DAGs (seeds 100-299), each timed for a few steps; geometric mean of images/s, how
+    much of it runs in fused chains, and what the chain kernels reach against their algorithmic bytes."""
+    import math
+
+    from paper_2304_07741_amd import binding as B
+    from paper_2304_07741_amd import workloads as wl
+
+    lo, hi = (int(v) for v in args.seeds.split(":"))
+    flags = B.CANVAS_OPT_NO_FUSION if args.no_fusion else 0
+    logs, chain_ms, chain_bytes, all_ms, nf, nb, fully, with_chain = 0.0, 0.0, 0.0, 0.0, 0, 0, 0, 0
+    slowest = None
+    for seed in range(lo, hi):
+        case = wl.config5(seed)
+        ms, launches, info = measure(case, flags, args.steps, args.warmup, kernel_steps=min(args.steps, 10))
+        logs += math.log(case["shape"][0] / (ms * 1e-3))
+        for l in launches:
+            all_ms += l["ms"]
+            if l["name"].startswith("chain_"):
+                chain_ms += l["ms"]
+                chain_bytes += l["bytes"]
+        nf += info["launches_fwd"]
+        nb += info["launches_bwd"]
+        with_chain += 1 if info["chains"] else 0
+        fully += 1 if info["chains"] and not any(l["name"].startswith("node_") and "fc" not in l["name"] for l in launches) else 0
+        if slowest is None or ms > slowest[1]:
+            slowest = (seed, ms)
+    n = hi - lo
+    gm = math.exp(logs / n)
+    frac = chain_bytes / max(chain_ms * 1e-3, 1e-12) / (HBM_PEAK_GBS * 1e9)
+    out = {
+        "metric": "micro-DAG fwd+bwd images/sec at ResNet layer shapes; % HBM / MFMA roofline",
+        "value": gm, "unit": "images/s (geometric mean over the DAGs)", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 16.0 / gm * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"fuzz: random micro-DAGs, seeds {lo}-{hi - 1}, N=16 C=96 H=W=32 bf16", "dags": n, "with_fused_chains": with_chain,
+                   "fully_fused": fully, "mean_launches_fwd": nf / n, "mean_launches_bwd": nb / n, "fusion": not args.no_fusion,
+                   "slowest_seed": slowest[0], "slowest_ms": slowest[1]},
+        "roofline": {"bound": "hbm", "achieved": frac * HBM_PEAK_GBS, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": frac, "traffic": None,
+                     "kernel": "chain_fwd + chain_bwd, all DAGs (algorithmic bytes of every chain launch / summed kernel time)",
+                     "kernel_ms": chain_ms / n, "algorithmic_bytes": chain_bytes / n},
+        "chain_time_share": chain_ms / max(all_ms, 1e-12),
+    }
+    print(json.dumps(out))
+
+
+def fc_micro(args):
+    """Grouped FC with its operands in cache: the contraction launches of config 4 at its four shapes, the same buffers
+    every step (6-50 MB, far below the 256 MB last-level cache), each against the bf16 MFMA peak."""
+    rows = []
+    for name in PER_CONFIG[1:]:
+        case = make_case(name)
+        ms, launches, info = measure(case, 0, args.steps, args.warmup, rotate=False)
+        for l in launches:
+            if l["flops"] > 0:
+                tf = l["flops"] / (l["ms"] * 1e-3) / 1e12
+                rows.append({"workload": name, "phase": l["phase"], "kernel": l["name"], "ms": round(l["ms"], 5), "GFLOP": round(l["flops"] / 1e9, 3),
+                             "TFLOPps": round(tf, 1), "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)})
+    best = max(rows, key=lambda r: r["TFLOPps"])
+    print(json.dumps({"metric": "grouped-FC contraction kernels, operands in cache: TFLOP/s against the bf16 MFMA peak", "value": best["TFLOPps"],
+                      "unit": "TFLOP/s (best kernel)", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": best["ms"],
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "FC launches of the sampled DAG at (C,H) in (64,56) (128,28) (256,14) (512,7), N=128, no buffer rotation"},
+                      "roofline": {"bound": "mfma", "achieved": best["TFLOPps"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": best["TFLOPps"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": f"{best['kernel']} ({best['workload']})"},
+                      "kernels": rows}))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="shift_residual",
+                    help="shift_residual (config 2, the headline), involution (config 3), sampled_cC_hH (config 4), fuzz (config 5)")
+    ap.add_argument("--seeds", default="100:300", help="fuzz: range of seeds lo:hi")
+    ap.add_argument("--no-fusion", action="store_true", help="per-node lowering (for comparison)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true", help="headline workload only: skip the per_config runs of configs 3 and 4")
+    ap.add_argument("--infer", type=int, default=0, metavar="BATCH",
+                    help="instead of the training step: forward-only latency of the inference plan at this batch size")
+    ap.add_argument("--copy-ref", action="store_true",
+                    help="instead of a micro-DAG: the rate of a plain device copy of one activation tensor of the workload "
+                         "(torch's copy kernel, cold buffers), the reference that kernel times are compared with")
+    ap.add_argument("--fc-micro", action="store_true", help="instead: the grouped-FC kernels of config 4 with their operands in cache")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
+    if args.infer:
+        return infer_latency(args)
+    if args.copy_ref:
+        return copy_reference(args)
+    if args.fc_micro:
+        return fc_micro(args)
+    if args.workload == "fuzz":
+        if args.steps == 200:
+            args.steps, args.warmup = 10, 3
+        return fuzz_bench(args)
+
+    from paper_2304_07741_amd import binding as B
+
+    case = make_case(args.workload)
+    N = case["shape"][0]
+    flags = B.CANVAS_OPT_NO_FUSION if args.no_fusion else 0
+    ms_per_step, launches, info = measure(case, flags, args.steps, args.warmup)
+    roof = roofline_of(launches, args.workload, not args.no_fusion)
     out = {
         "metric": "micro-DAG fwd+bwd images/sec at ResNet layer shapes; % HBM / MFMA roofline",
         "value": N / (ms_per_step * 1e-3), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -275,15 +382,29 @@ def main():
         "dtype": case["dtype"], "data": "synthetic",
         "config": {"workload": f"{case['name']} N={case['shape'][0]} C={case['shape'][1]} H=W={case['shape'][2]} "
                                f"{case['dtype']} (seed {case['seed']})",
-                   "fused": bool(first.info.fused), "buffer_sets": n_sets,
-                   "launches_fwd": nf, "launches_bwd": nb, "workspace_bytes": int(first.info.workspace_bytes)},
+                   "fused": info["fused"], "fused_chains": info["chains"], "buffer_sets": info["buffer_sets"],
+                   "launches_fwd": info["launches_fwd"], "launches_bwd": info["launches_bwd"], "workspace_bytes": info["workspace_bytes"]},
         "roofline": roof,
-        "kernels": [{"phase": l["phase"], "name": l["name"], "ms": round(l["ms"], 5),
-                     "GBps": round(l["bytes"] / max(l["ms"], 1e-9) / 1e6, 1),
-                     "TFLOPps": round(l["flops"] / max(l["ms"], 1e-9) / 1e9, 2)} for l in launches],
-        "min_bytes_fwd_bwd": first.info.min_bytes_fwd + first.info.min_bytes_bwd,
-        "whole_dag_hbm_frac": (first.info.min_bytes_fwd + first.info.min_bytes_bwd) / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
+        "kernels": kernel_rows(launches),
+        "min_bytes_fwd_bwd": info["min_bytes"],
+        "whole_dag_hbm_frac": info["min_bytes"] / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
     }
+    if args.workload == "shift_residual" and not args.no_per_config and not args.no_fusion:
+        # the other configurations of the metric (ResNet-50 layer shapes and the dynamic-window DAG): fewer steps each
+        per = []
+        for name in PER_CONFIG:
+            c = make_case(name)
+            k = max(10, min(args.steps, 60))
+            ms, ls, inf = measure(c, 0, k, max(3, min(args.warmup, 10)))
+            r = roofline_of(ls, name, True)
+            per.append({"workload": f"{c['name']} N={c['shape'][0]} C={c['shape'][1]} H=W={c['shape'][2]} {c['dtype']} (seed {c['seed']})",
+                        "steps": k, "ms_per_step": ms, "images_per_s": c["shape"][0] / (ms * 1e-3), "launches_fwd": inf["launches_fwd"],
+                        "launches_bwd": inf["launches_bwd"], "dominant_kernel": r["kernel"], "kernel_ms": r["kernel_ms"], "bound": r["bound"],
+                        "achieved": r["achieved"], "unit": r["unit"], "frac": r["frac"], "traffic": r["traffic"],
+                        "algorithmic_bytes": r["algorithmic_bytes"], "algorithmic_flops": r["algorithmic_flops"],
+                        "whole_dag_hbm_frac": inf["min_bytes"] / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9),
+                        "fc_tflops": sum(l["flops"] for l in ls) / (ms * 1e-3) / 1e12})
+        out["per_config"] = per
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case)
     print(json.dumps(out))

@@ -5,9 +5,10 @@
 // forward and ONE backward kernel.  Both interpret a short program that the host planner (chain_plan.cpp) writes
 // and that travels in the kernel arguments, so control flow is uniform over the whole workgroup.
 //
-// Machine model, per thread = per pixel of one image:
-//   A            accumulator, a vector over the taps (T <= TM lanes; lane 0 only for tensors without taps)
-//   R[0..NR)     registers of the same shape (operands kept while another value is computed)
+// Machine model, per thread = `vec` consecutive pixels of one image plane (every lane below is `vec` floats wide):
+//   A            accumulator, a vector over the taps (T <= TM lanes; lane 0 only for tensors without taps), in vector registers
+//   R[0..n_regs) registers of the same shape (operands kept while another value is computed), in LDS: only A is live
+//                across the interpreter's dispatch, so the compiler has no register state to shuffle between the cases
 //   P[...]       persistent floats of the thread, in LDS: softmax statistics and sums that run across the channel
 //                loop, gradient accumulators of an external tensor within one channel
 // A program is a list of passes; a pass has a prologue (run once) and a body (run for every channel of the
@@ -16,15 +17,17 @@
 // stencil may only sit above element-wise work.  In the backward direction the gradient of a shifted load belongs
 // to another pixel: XADD hands it over through LDS (a gather, fixed order, deterministic).
 #pragma once
+#include <cstddef>
 #include <cstdint>
 
 namespace canvas {
 namespace chain {
 
-constexpr int kMaxInstr = 192;
+constexpr int kMaxInstr = 184;
 constexpr int kMaxTerms = 32;
 constexpr int kMaxExt = 12;
 constexpr int kMaxPass = 8;
+constexpr int kMaxRed = 12;
 
 enum Opcode : uint8_t {
     OP_LD = 0,     // A[t] = ext[a](channel, tap, pixel + offset(b) [+ window tap t]) or 0 outside the image
@@ -85,29 +88,54 @@ struct Ext {
     int32_t T = 1;         // taps of the tensor (its channel count is the program's C)
     int32_t bf16 = 0;      // element type: 1 = bf16, 0 = fp32
 };
+static_assert(sizeof(Ext) == 16, "tensor descriptor size");
 
 struct Pass {
     uint16_t pro_begin = 0, pro_end = 0, body_begin = 0, body_end = 0;
+    uint16_t red_begin = 0, red_end = 0;  // what the channel slices of a workgroup combine when the pass ends
+    uint16_t pad[2] = {0, 0};
+};
+
+// A quantity that runs across the channel loop.  The channels of a workgroup are dealt out to `slices` groups of
+// threads (slice s takes channels s, s + slices, ...), each with its own partial result in P; when the pass ends the
+// partials of a pixel are combined and every slice gets the total.
+struct Red {
+    uint16_t slot = 0;
+    uint8_t T = 1;
+    uint8_t kind = 0;  // 0: softmax statistics (maximum at slot, rescaled sum at slot + T); 1: plain sums at slot
 };
 
 struct Program {
-    // geometry
+    // geometry.  A thread owns `vec` consecutive pixels of one image plane (H * W is a multiple of vec, vec <= W); the
+    // plane is dealt out in tiles of `own_threads` such threads, and a workgroup computes `halo_threads` more on either
+    // side of its tile (backward programs: the gradient hand-over of OP_XADD reads what neighbouring pixels computed).
     int32_t N = 0, C = 0, H = 0, W = 0;
-    int32_t tile_rows = 0;     // image rows a workgroup owns
-    int32_t halo_rows = 0;     // rows above and below that it recomputes for the gradient hand-over
-    int32_t tiles = 0;         // workgroups per image plane = ceil(H / tile_rows)
+    int32_t vec = 1;           // pixels per thread (1, 2, 4 or 8)
+    int32_t own_threads = 0;   // pixel threads of a tile whose results are stored
+    int32_t halo_threads = 0;  // recomputed pixel threads on either side
+    int32_t tiles = 0;         // workgroups per image plane = ceil(H * W / vec / own_threads)
     int32_t chunk = 0;         // channels per workgroup
     int32_t chunks = 0;        // ceil(C / chunk)
-    int32_t threads = 0;       // workgroup size (a multiple of 64, >= (tile_rows + 2 * halo_rows) * W)
-    int32_t n_persist = 0;     // floats of P per thread
+    int32_t threads = 0;       // workgroup size = slices * pix_threads
+    int32_t slices = 1;        // channel slices per workgroup
+    int32_t pix_threads = 0;   // threads per slice: a multiple of 64, >= own_threads + 2 * halo_threads
+    int32_t n_red = 0;
+    int32_t n_persist = 0;     // floats of P per pixel
+    int32_t xadd_lanes = 0;    // most lanes any OP_XADD hands over (0: the program has none)
     int32_t n_pass = 0, n_ext = 0, n_instr = 0, n_terms = 0;
     int32_t tm = 1;            // lanes the kernel instance must have (1, 9 or 25)
+    int32_t fast_math = 0;     // 1: every tensor of the DAG is bf16, transcendental functions may be accurate to 1e-6 only
+    int32_t n_regs = 0;        // registers R the program uses
+    int32_t pad0 = 0;
     Pass pass[kMaxPass];
+    Red red[kMaxRed];
     Ext ext[kMaxExt];
     Term term[kMaxTerms];
     Instr ins[kMaxInstr];
 };
 static_assert(sizeof(Program) <= 3968, "the program must fit the kernel argument buffer");
+static_assert(sizeof(Program) % 16 == 0 && sizeof(Instr) == 16 && offsetof(Program, ins) % 16 == 0,
+              "the kernels copy the program in 16-byte pieces");
 
 }  // namespace chain
 }  // namespace canvas

@@ -1,9 +1,13 @@
-// Fused-chain kernels: one workgroup = one image x one tile of rows (plus halo rows in backward programs) x one
-// range of channels; one thread = one pixel; the program (chain_isa.hpp) arrives in the kernel arguments and is
-// interpreted with workgroup-uniform control flow.  Loads are coalesced along W (the innermost dim of NCHW);
-// stencil offsets are address offsets of those loads; reductions over taps stay in registers; the statistics of a
-// softmax over channels and the gradient hand-over of shifted loads live in LDS.
+// Fused-chain kernels: one workgroup = one image x one tile of the image plane (plus a halo in backward programs) x one
+// range of channels; one thread = V consecutive pixels; the program (chain_isa.hpp) arrives in the kernel arguments and
+// is interpreted with workgroup-uniform control flow.  A tensor access is one vector access of V elements per thread,
+// coalesced along the plane (the innermost dims of NCHW); stencil offsets are address offsets of those accesses;
+// reductions over taps stay in registers; the statistics of a softmax over channels and the gradient hand-over of
+// shifted loads live in LDS.
 #include "chain_kernels.hpp"
+
+#include <algorithm>
+#include <cstddef>
 
 #include "chain_vm.hpp"
 #include "launch.hpp"
@@ -13,74 +17,143 @@ namespace chain {
 
 namespace {
 
-template <int TM, int NR>
-__global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program pg) {
-    extern __shared__ float lds[];
-    const int threads = pg.threads;
-    float* const xbuf = lds;                                  // 2 x threads: hand-over buffers of OP_XADD
-    float* const Pm = lds + 2 * threads + threadIdx.x;         // this thread's persistent floats, stride `threads`
-    // blockIdx.x = (image * tiles + tile) * chunks + chunk
-    const int chunk_id = blockIdx.x % pg.chunks;
-    const int tile = (blockIdx.x / pg.chunks) % pg.tiles;
-    Thread th;
-    th.tid = threadIdx.x;
-    th.n = blockIdx.x / (pg.chunks * pg.tiles);
-    const int rows = pg.tile_rows + 2 * pg.halo_rows;
-    const int row_first = tile * pg.tile_rows - pg.halo_rows;
-    const int lr = th.tid / pg.W;
-    th.col = th.tid - lr * pg.W;
-    th.row = row_first + lr;
-    th.active = lr < rows;
-    th.own = th.active && lr >= pg.halo_rows && lr < pg.halo_rows + pg.tile_rows && th.row < pg.H;
-    const int c_begin = chunk_id * pg.chunk;
-    const int c_end = c_begin + pg.chunk < pg.C ? c_begin + pg.chunk : pg.C;
-    State<TM, NR> st;
+// The program arrives in the kernel argument buffer, which is read through the scalar cache one line at a time (and
+// may live in host memory): interpreting it from there cost microseconds per instruction.  The workgroup copies what
+// it needs (header, tables, the n_instr instructions in use) into LDS with one parallel round trip and interprets that.
+__device__ __forceinline__ const Program& stage_program(unsigned char* sprog) {
+    const uint4* src = (const uint4*)__builtin_amdgcn_kernarg_segment_ptr();
+    const int n_instr = ((const int*)src)[offsetof(Program, n_instr) / 4];
+    const int pieces = (int)(offsetof(Program, ins) / 16) + n_instr;
+    for (int i = threadIdx.x; i < pieces; i += blockDim.x) ((uint4*)sprog)[i] = src[i];
+    __syncthreads();
+    return *(const Program*)sprog;
+}
+
+template <int TM, int V>
+__global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program) {
+    __shared__ __align__(16) unsigned char sprog[sizeof(Program)];
+    const Program& pg = stage_program(sprog);
+    extern __shared__ __align__(16) float lds[];
+    // (geometry: read once, as scalars)
+    const Geo g = vm_geo(pg);
+    const int threads = vm_u(pg.threads), PT = vm_u(pg.pix_threads), S = vm_u(pg.slices);
+    const int chunks = vm_u(pg.chunks), tiles = vm_u(pg.tiles), chunk = vm_u(pg.chunk);
+    const int own_threads = vm_u(pg.own_threads), halo_threads = vm_u(pg.halo_threads), n_pass = vm_u(pg.n_pass);
+    const int xfloats = vm_u(pg.xadd_lanes) * g.npx;             // hand-over buffer of a slice (OP_XADD)
+    // LDS: registers (16-byte pieces, see vm_reg_read) | hand-over buffers | persistent floats (float k of pixel v of thread i at [(k * V + v) * threads + i])
+    const int rstride = threads * 4;
+    float* const Rm = lds + threadIdx.x * 4;
+    float* const xbase = lds + vm_u(pg.n_regs) * reg_pieces(TM, V) * rstride;
+    float* const Pbase = xbase + S * xfloats;
+    float* const Pm = Pbase + threadIdx.x;
+    const int slice = __builtin_amdgcn_readfirstlane(threadIdx.x / PT);  // (PT is a multiple of 64: uniform in a wavefront)
+    float* const xbuf = xbase + slice * xfloats;
+    State<TM, V> st;
 #pragma unroll
-    for (int t = 0; t < TM; t++) st.A[t] = 0.f;
-#pragma unroll
-    for (int r = 0; r < NR; r++)
-#pragma unroll
-        for (int t = 0; t < TM; t++) st.R[r][t] = 0.f;
-    unsigned parity = 0;
-    for (int ps = 0; ps < pg.n_pass; ps++) {
-        const Pass pass = pg.pass[ps];
-        for (int i = pass.pro_begin; i < pass.pro_end; i++) vm_exec<TM, NR>(pg, pg.ins[i], c_begin, th, st, Pm, threads);
-        for (int c = c_begin; c < c_end; c++) {
-            for (int i = pass.body_begin; i < pass.body_end; i++) {
-                const Instr I = pg.ins[i];
-                if (I.op != OP_XADD) {
-                    vm_exec<TM, NR>(pg, I, c, th, st, Pm, threads);
-                    continue;
-                }
-                int dh, dw;
-                vm_offset(pg, I.b, c, dh, dw);
-#pragma unroll
-                for (int t = 0; t < TM; t++)
-                    if (t < I.T) {
-                        float* buf = xbuf + (parity & 1u) * threads;
-                        parity++;
-                        buf[th.tid] = st.A[t];
-                        __syncthreads();
-                        const int src = vm_xadd_source(pg, I, dh, dw, t, th, row_first, rows);
-                        if (src >= 0) Pm[(I.a + ((I.kind & kExtTaps) ? t : 0)) * threads] += buf[src];
+    for (int e = 0; e < TM * V; e++) st.A[e] = 0.f;
+    // The workgroup stays and walks over its share of the work items (image, tile, channel range): the program is staged
+    // once per workgroup, not once per item.  item = (image * tiles + tile) * chunks + chunk
+    const int items = g.N * tiles * chunks;
+    for (int item = blockIdx.x; item < items; item += gridDim.x) {
+        const int chunk_id = item % chunks;
+        const int tile = (item / chunks) % tiles;
+        // the workgroup's threads: `slices` groups of PT threads; a group is one thread per V pixels of the tile (+ halo)
+        Thread th;
+        th.ptid = threadIdx.x - slice * PT;
+        th.n = item / (chunks * tiles);
+        th.p0 = (tile * own_threads - halo_threads + th.ptid) * V;
+        th.active = th.p0 >= 0 && th.p0 < g.HW;
+        th.row0 = th.active ? th.p0 / g.W : 0;
+        th.col0 = th.active ? th.p0 - th.row0 * g.W : 0;
+        th.own = th.active && th.ptid >= halo_threads && th.ptid < halo_threads + own_threads;
+        const int c_begin = chunk_id * chunk;
+        const int c_end = c_begin + chunk < g.C ? c_begin + chunk : g.C;
+        for (int ps = 0; ps < n_pass; ps++) {
+            uint32_t pw[4];
+            __builtin_memcpy(pw, &pg.pass[ps], 16);
+            const int pro_begin = vm_u((int)pw[0]) & 0xffff, pro_end = (int)((uint32_t)vm_u((int)pw[0]) >> 16);
+            const int body_begin = vm_u((int)pw[1]) & 0xffff, body_end = (int)((uint32_t)vm_u((int)pw[1]) >> 16);
+            const int red_begin = vm_u((int)pw[2]) & 0xffff, red_end = (int)((uint32_t)vm_u((int)pw[2]) >> 16);
+            // trip -1 is the prologue (every slice, once); then slice s takes channels c_begin + s, + slices, ...: every
+            // slice makes the same number of trips (the hand-over of OP_XADD synchronises the workgroup), a trip past the
+            // last channel only keeps the barriers company
+            for (int c0 = c_begin - S; c0 < c_end; c0 += S) {
+                const bool pro = c0 < c_begin;
+                const int c = pro ? c_begin : c0 + slice;
+                const bool has = c < c_end;
+                const int i_begin = pro ? pro_begin : body_begin, i_end = pro ? pro_end : body_end;
+                if (i_begin >= i_end) continue;
+                uint4 next = *(const uint4*)&pg.ins[i_begin];
+                for (int i = i_begin; i < i_end; i++) {
+                    const Instr I = vm_uniform(next);
+                    if (i + 1 < i_end) next = *(const uint4*)&pg.ins[i + 1];  // (on its way while this instruction runs)
+                    if (I.op != OP_XADD) {
+                        if (has) vm_exec<TM, V>(pg, g, I, c, th, st, Pm, threads, Rm, rstride);
+                        continue;
                     }
+                    int dh = 0, dw = 0;
+                    if (has) vm_offset(pg, I.b, c, dh, dw);
+                    __syncthreads();  // the previous hand-over has been read
+                    vm_xadd_write<TM, V>(g, I, th, st.A, xbuf);
+                    __syncthreads();
+                    if (has) vm_xadd_gather<TM, V>(g, I, dh, dw, th, xbuf, Pm, threads);
+                }
+            }
+            // the slices' partial statistics and sums of this pass become totals, for every slice
+            if (S > 1 && red_end > red_begin) {
+                __syncthreads();  // the partials are complete
+                for (int k = red_begin; k < red_end; k++) {
+                    uint32_t rw;
+                    __builtin_memcpy(&rw, &pg.red[k], 4);
+                    rw = (uint32_t)vm_u((int)rw);
+                    Red R;
+                    __builtin_memcpy(&R, &rw, 4);
+                    for (int e = 0; e < R.T * V; e++) {
+                        float v0, v1;
+                        vm_combine<V>(R, e, S, PT, Pbase, threads, th.ptid, v0, v1);
+                        __syncthreads();  // everyone has read the partials of this lane
+                        Pm[(R.slot * V + e) * threads] = v0;
+                        if (R.kind == 0) Pm[((R.slot + R.T) * V + e) * threads] = v1;
+                    }
+                }
+                __syncthreads();  // the totals are written before the next pass adds to anything
             }
         }
     }
 }
 
-template <int TM>
+// Workgroups of a launch: every item its own workgroup while they all fit the chip at once (256 compute units, 2048
+// threads each), else a grid of that size whose workgroups take equal shares.
+inline unsigned grid_for(const Program& pg) {
+    const int64_t items = (int64_t)pg.N * pg.tiles * pg.chunks;
+    const int64_t resident = 256 * (int64_t)std::max(1, 2048 / pg.threads);
+    if (items <= resident) return (unsigned)items;
+    const int64_t per = (items + resident - 1) / resident;
+    return (unsigned)((items + per - 1) / per);
+}
+
+template <int TM, int V>
 void launch(const Program& pg, hipStream_t stream) {
-    const dim3 grid((unsigned)((int64_t)pg.N * pg.tiles * pg.chunks));
-    CANVAS_LAUNCH((k_chain<TM, regs_for(TM)>), grid, dim3((unsigned)pg.threads), lds_bytes(pg), stream, pg);
+    const dim3 grid(grid_for(pg));
+    CANVAS_LAUNCH((k_chain<TM, V>), grid, dim3((unsigned)pg.threads), lds_bytes(pg), stream, pg);
 }
 
 }  // namespace
 
 void run(const Program& pg, hipStream_t stream) {
-    if (pg.tm <= 1) launch<1>(pg, stream);
-    else if (pg.tm <= 9) launch<9>(pg, stream);
-    else launch<25>(pg, stream);
+    const int v = pg.vec;
+    if (pg.tm <= 1) {
+        if (v == 16) launch<1, 16>(pg, stream);
+        else if (v == 8) launch<1, 8>(pg, stream);
+        else if (v == 4) launch<1, 4>(pg, stream);
+        else if (v == 2) launch<1, 2>(pg, stream);
+        else launch<1, 1>(pg, stream);
+    } else if (pg.tm <= 9) {
+        if (v == 2) launch<9, 2>(pg, stream);
+        else launch<9, 1>(pg, stream);
+    } else {
+        launch<25, 1>(pg, stream);
+    }
 }
 
 }  // namespace chain

@@ -14,6 +14,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <map>
 #include <sstream>
 #include <tuple>
@@ -40,9 +41,10 @@ struct Ctx {
         if (win) os << 'w' << kh << 'x' << kw;
         return os.str();
     }
-    int reach_rows() const {
-        int r = win ? kh / 2 : 0;
-        for (const Term& t : terms) r += std::abs((int)t.dh);
+    // how far (in pixels of the flattened plane) a read through this context can lie from the reading pixel
+    int64_t reach_px(int W) const {
+        int64_t r = win ? (int64_t)(kh / 2) * W + kw / 2 : 0;
+        for (const Term& t : terms) r += (int64_t)std::abs((int)t.dh) * W + std::abs((int)t.dw);
         return r;
     }
 };
@@ -195,6 +197,7 @@ class Emitter {
         for (int r = 0; r < NR; r++)
             if (!used[r]) {
                 used[r] = true;
+                pg.n_regs = std::max(pg.n_regs, r + 1);
                 return r;
             }
         throw Fail{"out of registers"};
@@ -428,6 +431,17 @@ class Emitter {
     void begin_pass() {
         if (pg.n_pass >= kMaxPass) throw Fail{"too many passes"};
         pg.pass[pg.n_pass].pro_begin = (uint16_t)pg.n_instr;
+        pg.pass[pg.n_pass].red_begin = pg.pass[pg.n_pass].red_end = (uint16_t)pg.n_red;
+    }
+    // a quantity of the current pass that runs across the channel loop (the slices of a workgroup combine it at the end)
+    void reduce(int slot, int T, int kind) {
+        if (pg.n_red >= kMaxRed) throw Fail{"too many reductions across channels"};
+        Red r;
+        r.slot = (uint16_t)slot;
+        r.T = (uint8_t)T;
+        r.kind = (uint8_t)kind;
+        pg.red[pg.n_red++] = r;
+        pg.pass[pg.n_pass].red_end = (uint16_t)pg.n_red;
     }
     void begin_body() { pg.pass[pg.n_pass].pro_end = pg.pass[pg.n_pass].body_begin = (uint16_t)pg.n_instr; }
     void end_pass() { pg.pass[pg.n_pass++].body_end = (uint16_t)pg.n_instr; }
@@ -444,6 +458,7 @@ class Emitter {
                     m.f0 = -INFINITY;
                     emit(m);
                     emit(simple(OP_PSET, G.insts[i].lanes, 0, 0, stat_slot(i) + G.insts[i].lanes));
+                    reduce(stat_slot(i), G.insts[i].lanes, 0);
                 }
             begin_body();
             for (int i : smc)
@@ -466,53 +481,96 @@ class Emitter {
 
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Workgroup shape: rows per tile, halo, channel range, threads.  Throws when the image rows do not fit.
-void set_geometry(Program& pg, const Dag& dag, int C, int halo, bool all_channels) {
+// Workgroup shape for V pixels per thread: tile and halo, channel range and slices.  False when it does not fit.
+bool geometry_for(Program& pg, const Dag& dag, int C, int64_t reach_px, bool all_channels, int V) {
+    const int HW = dag.H * dag.W;
+    pg.vec = V;
+    const int PP = HW / V;                                   // pixel threads of a plane
+    const int64_t HT = (reach_px + V - 1) / V;               // halo, in pixel threads
+    const int per_thread = std::max<int>(1, (int)lds_bytes_per_thread(pg));
+    const int cap = (int)(std::min<int64_t>(max_threads_for(pg.tm), (int64_t)kMaxLdsBytes / per_thread) / 64 * 64);
+    if (cap < 64) return false;
+    int pt, own;
+    if (HT == 0) {
+        pt = 64;
+        own = 64;
+    } else if (PP + 2 * HT <= cap) {  // the whole plane in one tile
+        own = PP;
+        pt = ceil_div(PP + 2 * (int)HT, 64) * 64;
+    } else {
+        // recomputed pixels are lost work: the largest workgroup there is, its tiles evened out over the plane
+        if (2 * HT >= cap) return false;
+        const int tiles = ceil_div(PP, cap - 2 * (int)HT);
+        own = ceil_div(PP, tiles);
+        pt = ceil_div(own + 2 * (int)HT, 64) * 64;
+    }
+    pg.pix_threads = pt;
+    pg.own_threads = own;
+    pg.halo_threads = (int)HT;
+    pg.tiles = ceil_div(PP, own);
+    // channel slices: the loads of different channels are independent, so threads are worth more than trips
+    const int max_slices = std::max(1, cap / pt);
+    if (all_channels) {
+        pg.chunk = C;
+        pg.chunks = 1;
+        pg.slices = std::min(max_slices, std::min(C, 16));
+    } else {
+        // one wavefront-trip = one channel of 64 pixel threads; a few trips per thread once the chip is full
+        const int64_t trips_total = (int64_t)dag.N * pg.tiles * (pt / 64) * C;
+        int trips = (int)std::max<int64_t>(1, std::min<int64_t>(4, trips_total / 16384));
+        int S = std::max(1, std::min(std::min(max_slices, 4), C));
+        const int chunks = ceil_div(C, S * trips);
+        pg.chunk = ceil_div(C, chunks);
+        pg.chunks = ceil_div(C, pg.chunk);
+        pg.slices = std::min(S, pg.chunk);
+    }
+    pg.threads = pg.slices * pg.pix_threads;
+    return lds_bytes(pg) <= kMaxLdsBytes && (int64_t)dag.N * pg.tiles * pg.chunks < ((int64_t)1 << 31);
+}
+
+// Pixels per thread: the widest vector that still puts enough threads on the chip (a program that keeps all channels of
+// a pixel in one workgroup has only pixels and slices to spread), else whatever gives the most threads.
+void set_geometry(Program& pg, const Dag& dag, int C, int64_t reach_px, bool all_channels) {
     pg.N = dag.N;
     pg.C = C;
     pg.H = dag.H;
     pg.W = dag.W;
-    pg.halo_rows = halo;
-    const int maxthr = max_threads_for(pg.tm);
-    const int H = dag.H, W = dag.W;
-    if ((int64_t)W * (1 + 2 * halo) > maxthr) throw Fail{"image rows too wide for one workgroup"};
-    int rows;
-    if (halo == 0) {
-        // no recomputed rows: small workgroups (latency hiding comes from many of them); with all channels in one
-        // workgroup the spatial tiles are the only parallelism besides the batch
-        const int target = all_channels ? 128 : 256;
-        rows = std::max(1, std::min(H, target / W));
-    } else {
-        const int most = maxthr / W - 2 * halo;
-        rows = ceil_div(H, ceil_div(H, most));
+    pg.xadd_lanes = 0;
+    for (int i = 0; i < pg.n_instr; i++)
+        if (pg.ins[i].op == OP_XADD) pg.xadd_lanes = std::max<int>(pg.xadd_lanes, pg.ins[i].T);
+    const int HW = dag.H * dag.W;
+    // (CANVAS_CHAIN_THREADS overrides the threshold: 0 always takes the widest vector)
+    static const int64_t kEnoughThreads = std::getenv("CANVAS_CHAIN_THREADS") ? std::atoll(std::getenv("CANVAS_CHAIN_THREADS")) : 96 * 1024;
+    Program best;
+    int64_t best_threads = -1;
+    for (int V = max_vec_for(pg.tm); V >= 1; V /= 2) {
+        if (HW % V != 0 || dag.W < V) continue;
+        Program q = pg;
+        if (!geometry_for(q, dag, C, reach_px, all_channels, V)) continue;
+        // threads that do useful work
+        const int64_t n = (int64_t)dag.N * (HW / V) * q.chunks * q.slices;
+        if (n >= kEnoughThreads) {
+            pg = q;
+            return;
+        }
+        if (n > best_threads) {
+            best_threads = n;
+            best = q;
+        }
     }
-    auto threads_of = [&](int r) { return ceil_div((r + 2 * halo) * W, 64) * 64; };
-    while (rows > 1 && (size_t)(pg.n_persist + 2) * threads_of(rows) * sizeof(float) > kMaxLdsBytes) rows--;
-    pg.tile_rows = rows;
-    pg.threads = threads_of(rows);
-    if (lds_bytes(pg) > kMaxLdsBytes) throw Fail{"persistent state does not fit the LDS"};
-    pg.tiles = ceil_div(H, rows);
-    if (all_channels) {
-        pg.chunk = C;
-        pg.chunks = 1;
-    } else {
-        const int64_t wgs = (int64_t)dag.N * pg.tiles;
-        int chunks = (int)std::min<int64_t>(C, std::max<int64_t>(1, ceil_div(2048, (int)std::min<int64_t>(wgs, 2048))));
-        pg.chunk = ceil_div(C, chunks);
-        pg.chunks = ceil_div(C, pg.chunk);
-    }
-    if ((int64_t)dag.N * pg.tiles * pg.chunks >= ((int64_t)1 << 31)) throw Fail{"too many workgroups"};
+    if (best_threads < 0) throw Fail{"tile, halo and persistent state do not fit one workgroup"};
+    pg = best;
 }
 
 }  // namespace
 
 bool chain_candidate(const Dag& dag, int k) {
     const Node& nd = dag.nodes[k];
-    if (k == 0 || !nd.live || nd.pooled || nd.T > 25 || nd.C > 65535 || dag.W > 1024) return false;
+    if (k == 0 || !nd.live || nd.pooled || nd.T > 25 || nd.C > 65535) return false;
     const Node& A = dag.nodes[nd.a];
     if (A.pooled || A.T > 25) return false;
     switch (nd.op) {
-    case Op::Unfold: return A.T == 1 && nd.kh * nd.kw <= 25;
+    case Op::Unfold: return A.T == 1 && nd.kh * nd.kw <= 25 && (nd.kw == 1 || nd.kw == 3 || nd.kw == 5);
     case Op::Shift: return std::abs(nd.dh) < 32768 && std::abs(nd.dw) < 32768;
     case Op::Unary: return true;
     case Op::Binary: {
@@ -556,6 +614,11 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
         std::sort(out.inputs.begin(), out.inputs.end());
         for (int e : out.inputs)
             if (dag.nodes[e].C != C) throw Fail{"an external tensor with another channel count"};
+        auto fits32 = [&](int k) { return (int64_t)dag.N * C * std::max(dag.nodes[k].T, 1) * dag.H * dag.W * 4 < ((int64_t)1 << 31); };
+        for (int k : nodes)
+            if (!fits32(k)) throw Fail{"a tensor beyond 32-bit byte offsets"};
+        for (int k : out.inputs)
+            if (!fits32(k)) throw Fail{"a tensor beyond 32-bit byte offsets"};
         if (lanes > 25) throw Fail{"more than 25 taps"};
         const int tm = lanes <= 1 ? 1 : (lanes <= 9 ? 9 : 25);
 
@@ -585,7 +648,10 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
             for (int d = 0; d <= deepest && !smc.empty(); d++) {  // the sums of gradient x output, outermost softmax first
                 E.begin_pass();
                 for (int i : smc)
-                    if (G.down(i) == d) E.emit(Emitter::simple(OP_PSET, G.insts[i].lanes, 0, 0, E.dot_slot(i)));
+                    if (G.down(i) == d) {
+                        E.emit(Emitter::simple(OP_PSET, G.insts[i].lanes, 0, 0, E.dot_slot(i)));
+                        E.reduce(E.dot_slot(i), G.insts[i].lanes, 1);
+                    }
                 E.begin_body();
                 for (int i : smc)
                     if (G.down(i) == d) {
@@ -600,7 +666,7 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
             }
             E.begin_pass();
             E.begin_body();
-            int halo = 0;
+            int64_t halo = 0;
             for (int e : out.inputs) {
                 std::vector<int> mine;
                 for (int i : leaves)
@@ -627,7 +693,7 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
                         x.a = (uint16_t)acc;
                         if (Te > 1) x.kind |= kExtTaps;
                         E.emit(x);
-                        halo = std::max(halo, G.ctxs[L.ctx].reach_rows());
+                        halo = std::max(halo, G.ctxs[L.ctx].reach_px(dag.W));
                     }
                 }
                 if (!direct) E.emit(Emitter::simple(OP_PLD, Te, 0, 0, acc));
@@ -651,8 +717,9 @@ std::string dump(const Program& pg) {
     static const char* names[] = {"LD", "MASK", "UN", "MOVR", "MOVA", "BIN", "FOLD", "SMT", "ST", "UNBX", "BING", "SMTBX", "FOLDBX",
                                   "PSET", "PADD", "PLD", "SMCSTAT", "SMCAPPLY", "SMCDOT", "SMCBX", "XADD"};
     std::ostringstream os;
-    os << "program: C=" << pg.C << " HxW=" << pg.H << "x" << pg.W << " tile_rows=" << pg.tile_rows << " halo=" << pg.halo_rows << " tiles=" << pg.tiles
-       << " chunk=" << pg.chunk << " threads=" << pg.threads << " persist=" << pg.n_persist << " lanes=" << pg.tm << "\n";
+    os << "program: C=" << pg.C << " HxW=" << pg.H << "x" << pg.W << " vec=" << pg.vec << " own=" << pg.own_threads << " halo=" << pg.halo_threads
+       << " tiles=" << pg.tiles << " chunk=" << pg.chunk << " slices=" << pg.slices << " threads=" << pg.threads << " persist=" << pg.n_persist
+       << " lanes=" << pg.tm << "\n";
     for (int p = 0; p < pg.n_pass; p++) {
         os << " pass " << p << "\n";
         for (int i = pg.pass[p].pro_begin; i < pg.pass[p].body_end; i++) {

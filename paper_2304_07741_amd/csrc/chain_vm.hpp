@@ -1,14 +1,23 @@
-// Per-thread execution of the fused-chain instruction set (see chain_isa.hpp).  Everything here is plain
-// per-pixel arithmetic on the thread's own state; the one instruction that moves data between threads (OP_XADD)
-// is driven by the kernel around two helpers of this file.  Primitive definitions: Canvas paper, Section 5;
-// subgradient choices: relu'(0) = 0, sign(0) = 0, clipped exp flat outside the open interval, first maximum
-// of a max fold, ties of min / max to the LHS.
+// Per-thread execution of the fused-chain instruction set (see chain_isa.hpp).  A thread owns V consecutive pixels of
+// one image plane; a value is T x V floats (lane t * V + v = tap t of pixel v), so one interpreted instruction works
+// on 8 to 25 elements and every tensor access is one vector access of V elements.  Everything here is per-pixel
+// arithmetic on the thread's own state; the one instruction that moves data between threads (OP_XADD) is driven by the
+// kernel around two helpers of this file.  Primitive definitions: Canvas paper, Section 5; subgradient choices:
+// relu'(0) = 0, sign(0) = 0, clipped exp flat outside the open interval, first maximum of a max fold, ties of
+// min / max to the LHS.
+//
+// The file compiles for the device (raw buffer accesses) and for the host (checked scalar accesses), so that the
+// interpreter can be run on the CPU, workgroup by workgroup, against the same programs.
 #pragma once
 #include <cmath>
 #include <cstdint>
 #include <cstring>
 
 #include "chain_isa.hpp"
+
+#if defined(__HIP_DEVICE_COMPILE__)
+#include "tile_util.hpp"
+#endif
 
 #if defined(__HIPCC__)
 #define CHAIN_HD __host__ __device__ __forceinline__
@@ -19,18 +28,73 @@
 namespace canvas {
 namespace chain {
 
-template <int TM, int NR>
+template <int TM, int V>
 struct State {
-    float A[TM];
-    float R[NR][TM];
+    float A[TM * V];
 };
 
-// What a thread knows about its pixel.  Threads of the halo rows may sit outside the image (row < 0 or >= H);
-// threads beyond the workgroup's rows have active == false.  Only `own` pixels are stored.
+// 16-byte pieces of a register R[r] (TM * V floats, rounded up); piece q of register r of thread i is at float
+// ((r * pieces + q) * threads + i) * 4 of the register area, so that a wavefront's access is one contiguous run.
+constexpr int reg_pieces(int tm, int v) { return (tm * v + 3) / 4; }
+
+// What a thread knows about its pixels.  p0 is the plane index of its first pixel (a multiple of V; threads of the
+// halo may lie before the plane or behind it: active == false); only `own` threads store.
 struct Thread {
-    int tid = 0, n = 0, row = 0, col = 0;
+    int ptid = 0, n = 0, p0 = 0, row0 = 0, col0 = 0;
     bool active = false, own = false;
 };
+
+// Geometry in uniform registers.
+struct Geo {
+    int H = 0, W = 0, C = 0, HW = 0, N = 0;
+    int npx = 0;  // pixels a slice of the workgroup computes = pix_threads * V
+};
+
+// Each case of the dispatch begins with an empty volatile asm statement: the cases are small, and without it the
+// compiler executes the arithmetic of ALL of them for every instruction and selects the result.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define CHAIN_CASE asm volatile("")
+#else
+#define CHAIN_CASE ((void)0)
+#endif
+
+// The program is interpreted from LDS, whose loads land in vector registers: the compiler cannot know that every
+// lane read the same word.  vm_u() tells it (one v_readfirstlane), so that instruction fields, tensor descriptors and
+// geometry live in scalar registers and the dispatch on them is a scalar branch.
+#if defined(__HIP_DEVICE_COMPILE__)
+CHAIN_HD int vm_u(int v) { return __builtin_amdgcn_readfirstlane(v); }
+#else
+CHAIN_HD int vm_u(int v) { return v; }
+#endif
+// A 16-byte instruction, made uniform.
+CHAIN_HD Instr vm_fetch(const Instr& src) {
+    uint32_t w[4];
+    memcpy(w, &src, 16);
+    for (int k = 0; k < 4; k++) w[k] = (uint32_t)vm_u((int)w[k]);
+    Instr I;
+    memcpy(&I, w, 16);
+    return I;
+}
+#if defined(__HIPCC__)
+// The same for an instruction that has already been read as four dwords.
+__device__ __forceinline__ Instr vm_uniform(const uint4& raw) {
+    uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    for (int k = 0; k < 4; k++) w[k] = (uint32_t)vm_u((int)w[k]);
+    Instr I;
+    memcpy(&I, w, 16);
+    return I;
+}
+#endif
+CHAIN_HD Geo vm_geo(const Program& pg) {
+    Geo g;
+    g.H = vm_u(pg.H);
+    g.W = vm_u(pg.W);
+    g.C = vm_u(pg.C);
+    g.N = vm_u(pg.N);
+    g.HW = g.H * g.W;
+    g.npx = vm_u(pg.pix_threads) * vm_u(pg.vec);
+    return g;
+}
 
 CHAIN_HD float vm_bf16_to_f32(uint16_t h) {
     uint32_t u = (uint32_t)h << 16;
@@ -38,56 +102,200 @@ CHAIN_HD float vm_bf16_to_f32(uint16_t h) {
     memcpy(&f, &u, 4);
     return f;
 }
-
-CHAIN_HD uint16_t vm_f32_to_bf16(float f) {  // round to nearest even; NaN stays NaN
+CHAIN_HD float vm_bits_to_f32(uint32_t u) {
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+CHAIN_HD uint32_t vm_f32_to_bits(float f) {
     uint32_t u;
     memcpy(&u, &f, 4);
+    return u;
+}
+
+CHAIN_HD uint16_t vm_f32_to_bf16(float f) {  // round to nearest even; NaN stays NaN
+    uint32_t u = vm_f32_to_bits(f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
 
-CHAIN_HD float vm_unary(int kind, float x, float lo, float hi) {
-    switch (kind) {
-    case 0: return fmaxf(x, 0.f);
-    case 1: return fabsf(x);
-    case 2: return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
-    case 4: return sinf(x);
-    case kUnNeg: return -x;
-    default: return expf(fminf(fmaxf(x, lo), hi));
+// ---------------------------------------------------------------------------------------------------- tensors
+// A tensor of the program in uniform registers.  Element indices are 32-bit (the planner only admits tensors below
+// 2^31 bytes) and may lie outside the tensor (a shifted access at the first or last image): such elements read as
+// zero on the device and as NaN on the host, and are masked by the caller either way.
+struct Tensor {
+#if defined(__HIP_DEVICE_COMPILE__)
+    tile::rsrc_t rs;
+#else
+    void* ptr = nullptr;
+#endif
+    int bytes = 0;
+    int T = 1;
+    int bf16 = 0;
+};
+
+CHAIN_HD Tensor vm_tensor(const Program& pg, const Geo& g, int a) {
+    uint32_t w[4];
+    memcpy(w, &pg.ext[a], 16);
+    for (int k = 0; k < 4; k++) w[k] = (uint32_t)vm_u((int)w[k]);
+    Tensor t;
+    t.T = (int)w[2];
+    t.bf16 = (int)w[3];
+    t.bytes = g.N * g.C * t.T * g.HW * (t.bf16 ? 2 : 4);
+    void* p = (void*)(((uint64_t)w[1] << 32) | w[0]);
+#if defined(__HIP_DEVICE_COMPILE__)
+    t.rs = tile::make_rsrc(p, t.bytes);
+#else
+    t.ptr = p;
+#endif
+    return t;
+}
+
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef uint32_t vm_u32x2 __attribute__((ext_vector_type(2)));
+
+// V elements that begin at element `elem`.  ALIGNED: elem is a multiple of V (so is every tensor's size), the access
+// is wholly inside or wholly outside the tensor and no piece of it needs a second look.
+template <int V, bool ALIGNED>
+__device__ __forceinline__ void vm_load(const Tensor& e, int elem, float* out) {
+    if (e.bf16) {
+        const int o = elem * 2;
+        if (V % 8 == 0) {
+#pragma unroll
+            for (int q = 0; q < V / 8; q++) {
+                tile::u32x4 d = tile::bload16(e.rs, o + 16 * q);
+                if (!ALIGNED) tile::reload_if_partial(d, e.rs, o + 16 * q, e.bytes);
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    out[8 * q + 2 * k] = tile::lo_f32(d[k]);
+                    out[8 * q + 2 * k + 1] = tile::hi_f32(d[k]);
+                }
+            }
+        } else if (V == 4) {
+            vm_u32x2 d = __builtin_amdgcn_raw_buffer_load_b64(e.rs, o, 0, 0);
+            if (!ALIGNED && tile::straddles_an_end(o, 8, e.bytes)) {
+#pragma unroll
+                for (int k = 0; k < 2; k++) d[k] = tile::elem_b16(e.rs, o + 4 * k, e.bytes) | (tile::elem_b16(e.rs, o + 4 * k + 2, e.bytes) << 16);
+            }
+#pragma unroll
+            for (int k = 0; k < 2; k++) {
+                out[2 * k] = tile::lo_f32(d[k]);
+                out[2 * k + 1] = tile::hi_f32(d[k]);
+            }
+        } else if (V == 2) {
+            uint32_t d = __builtin_amdgcn_raw_buffer_load_b32(e.rs, o, 0, 0);
+            if (!ALIGNED) tile::reload_pair_if_partial(d, e.rs, o, e.bytes);
+            out[0] = tile::lo_f32(d);
+            out[1] = tile::hi_f32(d);
+        } else {
+#pragma unroll
+            for (int v = 0; v < V; v++) out[v] = tile::lo_f32(tile::elem_b16(e.rs, o + 2 * v, e.bytes));
+        }
+    } else {
+        const int o = elem * 4;
+        if (V % 4 == 0) {
+#pragma unroll
+            for (int q = 0; q < V / 4; q++) {
+                tile::u32x4 d = tile::bload16(e.rs, o + 16 * q);
+                if (!ALIGNED) tile::reload_f32x4_if_partial(d, e.rs, o + 16 * q, e.bytes);
+#pragma unroll
+                for (int k = 0; k < 4; k++) out[4 * q + k] = __uint_as_float(d[k]);
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < V; v++) out[v] = __uint_as_float(tile::elem_b32(e.rs, o + 4 * v, e.bytes));
+        }
     }
 }
 
-CHAIN_HD float vm_unary_grad(int kind, float x, float lo, float hi) {
-    switch (kind) {
-    case 0: return x > 0.f ? 1.f : 0.f;
-    case 1: return x > 0.f ? 1.f : (x < 0.f ? -1.f : 0.f);
-    case 2: return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.39894228040143268f * expf(-0.5f * x * x);
-    case 4: return cosf(x);
-    case kUnNeg: return -1.f;
-    default: return (x > lo && x < hi) ? expf(x) : 0.f;
+// V elements to element `elem` (always inside the tensor and a multiple of V: only owned pixels are stored).
+template <int V>
+__device__ __forceinline__ void vm_store(const Tensor& e, int elem, const float* in, bool add) {
+    if (e.bf16) {
+        const int o = elem * 2;
+        if (V % 8 == 0) {
+#pragma unroll
+            for (int q = 0; q < V / 8; q++) {
+                tile::u32x4 d;
+#pragma unroll
+                for (int k = 0; k < 4; k++) d[k] = tile::pack_bf16(in[8 * q + 2 * k], in[8 * q + 2 * k + 1]);
+                tile::bstore16(e.rs, o + 16 * q, d);
+            }
+        } else if (V == 4) {
+            vm_u32x2 d;
+#pragma unroll
+            for (int k = 0; k < 2; k++) d[k] = tile::pack_bf16(in[2 * k], in[2 * k + 1]);
+            __builtin_amdgcn_raw_buffer_store_b64(d, e.rs, o, 0, 0);
+        } else if (V == 2) {
+            __builtin_amdgcn_raw_buffer_store_b32(tile::pack_bf16(in[0], in[1]), e.rs, o, 0, 0);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b16((uint16_t)(tile::pack_bf16(in[0], 0.f) & 0xffffu), e.rs, o, 0, 0);
+        }
+    } else {
+        const int o = elem * 4;
+        float v[V];
+        if (add) {
+            vm_load<V, true>(e, elem, v);
+#pragma unroll
+            for (int k = 0; k < V; k++) v[k] += in[k];
+        } else {
+#pragma unroll
+            for (int k = 0; k < V; k++) v[k] = in[k];
+        }
+        if (V % 4 == 0) {
+#pragma unroll
+            for (int q = 0; q < V / 4; q++) {
+                tile::u32x4 d;
+#pragma unroll
+                for (int k = 0; k < 4; k++) d[k] = __float_as_uint(v[4 * q + k]);
+                tile::bstore16(e.rs, o + 16 * q, d);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < V; k++) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[k]), e.rs, o + 4 * k, 0, 0);
+        }
     }
 }
+#else
+// Host: element by element, checked.  An element outside the tensor reads as NaN, so that a missing mask shows in
+// the results; a store outside the tensor is a bug of the planner and aborts.
+#include <cstdio>
+#include <cstdlib>
+template <int V, bool ALIGNED>
+inline void vm_load(const Tensor& e, int elem, float* out) {
+    const int64_t n = e.bytes / (e.bf16 ? 2 : 4);
+    if (ALIGNED && elem % V != 0) {
+        std::fprintf(stderr, "chain vm: an aligned load of %d elements at %d\n", V, elem);
+        std::abort();
+    }
+    for (int v = 0; v < V; v++) {
+        const int64_t i = (int64_t)elem + v;
+        if (i < 0 || i >= n) out[v] = NAN;
+        else out[v] = e.bf16 ? vm_bf16_to_f32(((const uint16_t*)e.ptr)[i]) : ((const float*)e.ptr)[i];
+    }
+}
+template <int V>
+inline void vm_store(const Tensor& e, int elem, const float* in, bool add) {
+    const int64_t n = e.bytes / (e.bf16 ? 2 : 4);
+    if (elem < 0 || (int64_t)elem + V > n || elem % V) {
+        std::fprintf(stderr, "chain vm: store of %d elements at %d outside a tensor of %lld\n", V, elem, (long long)n);
+        std::abort();
+    }
+    for (int v = 0; v < V; v++) {
+        if (e.bf16) ((uint16_t*)e.ptr)[elem + v] = vm_f32_to_bf16(in[v]);
+        else if (add) ((float*)e.ptr)[elem + v] += in[v];
+        else ((float*)e.ptr)[elem + v] = in[v];
+    }
+}
+#endif
 
-CHAIN_HD float vm_blend(int kind, float a, float b) {
-    switch (kind) {
-    case 0: return a + b;
-    case 1: return a * b;
-    case 2: return a - b;
-    case 3: return a <= b ? a : b;
-    default: return a >= b ? a : b;
-    }
-}
-
-CHAIN_HD float vm_blend_grad(int kind, bool rhs_side, float a, float b) {
-    switch (kind) {
-    case 0: return 1.f;
-    case 1: return rhs_side ? a : b;
-    case 2: return rhs_side ? -1.f : 1.f;
-    case 3: return (a <= b) != rhs_side ? 1.f : 0.f;
-    default: return (a >= b) != rhs_side ? 1.f : 0.f;
-    }
-}
+// ---------------------------------------------------------------------------------------------------- arithmetic
+// The element-wise functions, one per kind: the dispatch on the kind happens once per instruction, outside the loops
+// over the lanes (a switch inside the loop costs a scalar branch tree per element).
+CHAIN_HD float vm_gelu(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
+CHAIN_HD float vm_gelu_grad(float x) { return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.39894228040143268f * expf(-0.5f * x * x); }
+CHAIN_HD float vm_sign(float x) { return x > 0.f ? 1.f : (x < 0.f ? -1.f : 0.f); }
 
 // Sum of the offsets of a position for channel c: terms [b >> 8, (b >> 8) + (b & 255)) that cover c.
 CHAIN_HD void vm_offset(const Program& pg, uint16_t b, int c, int& dh, int& dw) {
@@ -95,227 +303,464 @@ CHAIN_HD void vm_offset(const Program& pg, uint16_t b, int c, int& dh, int& dw) 
     dw = 0;
     const int first = b >> 8, cnt = b & 255;
     for (int k = 0; k < cnt; k++) {
-        const Term& t = pg.term[first + k];
-        if (c >= (int)t.c0 && c < (int)t.c1) {
-            dh += t.dh;
-            dw += t.dw;
+        uint32_t w[2];
+        memcpy(w, &pg.term[first + k], 8);
+        const int off = vm_u((int)w[0]), rng = vm_u((int)w[1]);  // (dh, dw) and (c0, c1) as packed halves
+        if (c >= (rng & 0xffff) && c < (int)((uint32_t)rng >> 16)) {
+            dh += (int16_t)(off & 0xffff);
+            dw += (int16_t)((uint32_t)off >> 16);
         }
     }
 }
 
-#if defined(CHAIN_VM_BOUNDS)  // host builds of the interpreter only: every access checked against the tensor's size
-#include <cstdio>
-#include <cstdlib>
-#define CHAIN_VM_CHECK(pg, e, idx)                                                                            \
-    do {                                                                                                      \
-        if ((idx) < 0 || (idx) >= (int64_t)(pg).N * (pg).C * (e).T * (pg).H * (pg).W) {                       \
-            std::fprintf(stderr, "chain vm: index %lld outside a tensor of %d taps\n", (long long)(idx), (int)(e).T); \
-            std::abort();                                                                                     \
-        }                                                                                                     \
-    } while (0)
-#else
-#define CHAIN_VM_CHECK(pg, e, idx) ((void)0)
-#endif
-
-CHAIN_HD float vm_load(const Program& pg, const Ext& e, int64_t idx) {
-    CHAIN_VM_CHECK(pg, e, idx);
-    return e.bf16 ? vm_bf16_to_f32(((const uint16_t*)e.ptr)[idx]) : ((const float*)e.ptr)[idx];
+// Row and column of tap t of a KH x KW window (t is a compile-time constant after unrolling, KW is uniform: the
+// windows the planner admits are 1, 3 or 5 wide).
+CHAIN_HD void vm_tap(int t, int KH, int KW, int& oh, int& ow) {
+    const int kh = KW == 3 ? t / 3 : (KW == 5 ? t / 5 : t);
+    oh = kh - KH / 2;
+    ow = t - kh * KW - KW / 2;
 }
 
-#define CHAIN_LANES(T) _Pragma("unroll") for (int t = 0; t < TM; t++) if (t < (T))
-
-// Runs `body` with X bound to register r (r is uniform: one branch, no dynamic register indexing).
-#define CHAIN_WITH_REG(st, r, X, ...)                                    \
-    do {                                                                 \
-        _Pragma("unroll") for (int rr_ = 0; rr_ < NR; rr_++) if (rr_ == (int)(r)) { \
-            float* X = (st).R[rr_];                                      \
-            __VA_ARGS__                                                  \
-        }                                                                \
+// Lanes [0, T * V) of a value: T is uniform (1, or the taps of a window).
+#define CHAIN_EACH(T, e, ...)                                                             \
+    do {                                                                                  \
+        if (TM == 1 || (T) == 1) {                                                        \
+            _Pragma("unroll") for (int e = 0; e < V; e++) { __VA_ARGS__ }                 \
+        } else {                                                                          \
+            _Pragma("unroll") for (int t_ = 0; t_ < TM; t_++) if (t_ < (T)) {             \
+                _Pragma("unroll") for (int v_ = 0; v_ < V; v_++) {                        \
+                    const int e = t_ * V + v_;                                            \
+                    __VA_ARGS__                                                           \
+                }                                                                         \
+            }                                                                             \
+        }                                                                                 \
     } while (0)
 
-// Every instruction except OP_XADD.  Pm: this thread's persistent floats, element k at Pm[k * pstride].
-template <int TM, int NR>
-CHAIN_HD void vm_exec(const Program& pg, const Instr& I, int c, const Thread& th, State<TM, NR>& st, float* Pm, int pstride) {
-    float* A = st.A;
+// Register r (uniform) <-> X.  Rm: piece 0 of register 0 of this thread; rstride: floats between pieces (threads * 4).
+template <int TM, int V>
+CHAIN_HD void vm_reg_read(const float* Rm, int rstride, int r, int T, float* X) {
+    constexpr int Q = reg_pieces(TM, V);
+    const float* src = Rm + r * Q * rstride;
+#pragma unroll
+    for (int q = 0; q < Q; q++)
+        if (q * 4 < T * V) {
+            float w[4];
+            memcpy(w, src + q * rstride, 16);
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+                if (q * 4 + k < TM * V) X[q * 4 + k] = w[k];
+        }
+}
+template <int TM, int V>
+CHAIN_HD void vm_reg_write(float* Rm, int rstride, int r, int T, const float* X) {
+    constexpr int Q = reg_pieces(TM, V);
+    float* dst = Rm + r * Q * rstride;
+#pragma unroll
+    for (int q = 0; q < Q; q++)
+        if (q * 4 < T * V) {
+            float w[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++) w[k] = q * 4 + k < TM * V ? X[q * 4 + k] : 0.f;
+            memcpy(dst + q * rstride, w, 16);
+        }
+}
+
+// Which of the thread's V pixels see the image at offset (oh, ow): bit v of the result.
+template <int V>
+CHAIN_HD uint32_t vm_valid(const Geo& g, const Thread& th, int oh, int ow) {
+    uint32_t m = 0;
+    if (!th.active) return 0;
+#pragma unroll
+    for (int v = 0; v < V; v++) {
+        int c = th.col0 + v, r = th.row0;
+        if (c >= g.W) {
+            c -= g.W;
+            r++;
+        }
+        r += oh;
+        c += ow;
+        if ((unsigned)r < (unsigned)g.H && (unsigned)c < (unsigned)g.W) m |= 1u << v;
+    }
+    return m;
+}
+
+// out[v] = tensor(plane, pixel p0 + v displaced by (oh, ow)), 0 outside the image.  Without displacement nothing is
+// masked: what a thread outside the plane reads (zeros, or pixels of another plane) is never stored nor handed over.
+template <int V>
+CHAIN_HD void vm_load_at(const Tensor& e, const Geo& g, const Thread& th, int plane, int oh, int ow, float* out) {
+    if (oh == 0 && ow == 0) {
+        vm_load<V, true>(e, plane * g.HW + th.p0, out);
+    } else {
+        float raw[V];
+        vm_load<V, false>(e, plane * g.HW + th.p0 + oh * g.W + ow, raw);
+        const uint32_t m = vm_valid<V>(g, th, oh, ow);
+#pragma unroll
+        for (int v = 0; v < V; v++) out[v] = ((m >> v) & 1u) ? raw[v] : 0.f;
+    }
+}
+
+// Every instruction except OP_XADD.  Pm: this thread's persistent floats, float k of pixel v at Pm[(k * V + v) * pstride];
+// Rm, rstride: its registers (vm_reg_read).
+template <int TM, int V>
+CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, int c, const Thread& th, State<TM, V>& st, float* Pm, int pstride, float* Rm,
+                      int rstride) {
+    auto& A = st.A;
     const int T = I.T;
-    const int H = pg.H, W = pg.W;
+    float X[TM * V];
     switch (I.op) {
     case OP_LD: {
+        CHAIN_CASE;
         int dh, dw;
         vm_offset(pg, I.b, c, dh, dw);
-        const Ext& e = pg.ext[I.a];
-        const int64_t plane = (int64_t)H * W;
-        const int64_t base = ((int64_t)th.n * pg.C + c) * e.T;
+        const Tensor e = vm_tensor(pg, g, I.a);
+        const int chan = (th.n * g.C + c) * e.T;  // first plane of (image, channel): uniform
         if (I.kind & kWin) {
             const int KH = I.r >> 4, KW = I.r & 15;
-            CHAIN_LANES(T) {
-                const int hh = th.row + dh + t / KW - KH / 2, ww = th.col + dw + t % KW - KW / 2;
-                const bool in = th.active && hh >= 0 && hh < H && ww >= 0 && ww < W;
-                A[t] = in ? vm_load(pg, e, base * plane + (int64_t)hh * W + ww) : 0.f;
-            }
+#pragma unroll
+            for (int t = 0; t < TM; t++)
+                if (t < T) {
+                    int oh, ow;
+                    vm_tap(t, KH, KW, oh, ow);
+                    float ld[V];
+                    vm_load_at<V>(e, g, th, chan, dh + oh, dw + ow, ld);
+#pragma unroll
+                    for (int v = 0; v < V; v++) A[t * V + v] = ld[v];
+                }
         } else {
-            const int hh = th.row + dh, ww = th.col + dw;
-            const bool in = th.active && hh >= 0 && hh < H && ww >= 0 && ww < W;
-            const int64_t pix = (int64_t)hh * W + ww;
-            CHAIN_LANES(T) {
-                const int te = (I.kind & kExtTaps) ? (t < e.T ? t : t % e.T) : 0;
-                A[t] = in ? vm_load(pg, e, (base + te) * plane + pix) : 0.f;
-            }
+#pragma unroll
+            for (int t = 0; t < TM; t++)
+                if (t < T) {
+                    const int te = (I.kind & kExtTaps) ? (t < e.T ? t : t % e.T) : 0;
+                    float ld[V];
+                    vm_load_at<V>(e, g, th, chan + te, dh, dw, ld);
+#pragma unroll
+                    for (int v = 0; v < V; v++) A[t * V + v] = ld[v];
+                }
         }
         break;
     }
     case OP_MASK: {
+        CHAIN_CASE;
         int dh, dw;
         vm_offset(pg, I.b, c, dh, dw);
         if (I.kind & kWin) {
             const int KH = I.r >> 4, KW = I.r & 15;
-            CHAIN_LANES(T) {
-                const int hh = th.row + dh + t / KW - KH / 2, ww = th.col + dw + t % KW - KW / 2;
-                if (!(hh >= 0 && hh < H && ww >= 0 && ww < W)) A[t] = 0.f;
-            }
+#pragma unroll
+            for (int t = 0; t < TM; t++)
+                if (t < T) {
+                    int oh, ow;
+                    vm_tap(t, KH, KW, oh, ow);
+                    const uint32_t m = vm_valid<V>(g, th, dh + oh, dw + ow);
+#pragma unroll
+                    for (int v = 0; v < V; v++)
+                        if (!((m >> v) & 1u)) A[t * V + v] = 0.f;
+                }
         } else {
-            const int hh = th.row + dh, ww = th.col + dw;
-            if (!(hh >= 0 && hh < H && ww >= 0 && ww < W)) CHAIN_LANES(T) A[t] = 0.f;
+            const uint32_t m = vm_valid<V>(g, th, dh, dw);
+            CHAIN_EACH(T, e, if (!((m >> (e % V)) & 1u)) A[e] = 0.f;);
         }
         break;
     }
     case OP_UN:
-        CHAIN_LANES(T) A[t] = vm_unary(I.kind, A[t], I.f0, I.f1);
+        switch (I.kind) {
+        case 0: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = fmaxf(A[e], 0.f);); break;
+        case 1: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = fabsf(A[e]);); break;
+        case 2: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = vm_gelu(A[e]);); break;
+        case 4: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = sinf(A[e]);); break;
+        case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = -A[e];); break;
+        default: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = expf(fminf(fmaxf(A[e], I.f0), I.f1));); break;
+        }
         break;
     case OP_MOVR:
-        CHAIN_WITH_REG(st, I.r, X, CHAIN_LANES(T) X[t] = A[t];);
+        CHAIN_CASE;
+        CHAIN_EACH(T, e, X[e] = A[e];);
+        vm_reg_write<TM, V>(Rm, rstride, I.r, T, X);
         break;
     case OP_MOVA:
-        CHAIN_WITH_REG(st, I.r, X, CHAIN_LANES(T) A[t] = X[t];);
+        CHAIN_CASE;
+        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
+        CHAIN_EACH(T, e, A[e] = X[e];);
         break;
     case OP_BIN: {
+        CHAIN_CASE;
         const int kind = I.kind & 7;
         const bool reg_lhs = I.kind & kBinRegIsLhs, reg_sc = I.kind & kBinRegScalar, acc_sc = I.kind & kBinAccScalar;
-        const float a0 = A[0];
-        CHAIN_WITH_REG(st, I.r, X, CHAIN_LANES(T) {
-            const float rv = reg_sc ? X[0] : X[t], av = acc_sc ? a0 : A[t];
-            A[t] = reg_lhs ? vm_blend(kind, rv, av) : vm_blend(kind, av, rv);
-        });
+        vm_reg_read<TM, V>(Rm, rstride, I.r, reg_sc ? 1 : T, X);
+        if (TM > 1 && reg_sc) CHAIN_EACH(T, e, X[e] = X[e % V];);
+        if (TM > 1 && acc_sc) CHAIN_EACH(T, e, A[e] = A[e % V];);
+        // (min and max return the same value whichever side is the LHS; the sides matter for sub only)
+        switch (kind) {
+        case 0: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] + A[e];); break;
+        case 1: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] * A[e];); break;
+        case 2:
+            CHAIN_CASE;
+            if (reg_lhs) CHAIN_EACH(T, e, A[e] = X[e] - A[e];);
+            else CHAIN_EACH(T, e, A[e] = A[e] - X[e];);
+            break;
+        case 3: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] <= A[e] ? X[e] : A[e];); break;
+        default: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] >= A[e] ? X[e] : A[e];); break;
+        }
         break;
     }
     case OP_FOLD: {
-        float s = A[0];
-        _Pragma("unroll") for (int t = 1; t < TM; t++) if (t < T) {
-            if (I.kind == 2) s = A[t] > s ? A[t] : s;
-            else s += A[t];
+        CHAIN_CASE;
+        if (I.kind == 2) {
+#pragma unroll
+            for (int t = 1; t < TM; t++)
+                if (t < T) {
+#pragma unroll
+                    for (int v = 0; v < V; v++) A[v] = A[t * V + v] > A[v] ? A[t * V + v] : A[v];
+                }
+        } else {
+#pragma unroll
+            for (int t = 1; t < TM; t++)
+                if (t < T) {
+#pragma unroll
+                    for (int v = 0; v < V; v++) A[v] += A[t * V + v];
+                }
+            if (I.kind == 1) {
+                const float inv = (float)T;
+#pragma unroll
+                for (int v = 0; v < V; v++) A[v] /= inv;
+            }
         }
-        if (I.kind == 1) s /= (float)T;
-        A[0] = s;
         break;
     }
     case OP_SMT: {
-        float m = A[0];
-        _Pragma("unroll") for (int t = 1; t < TM; t++) if (t < T) m = fmaxf(m, A[t]);
-        float z = 0.f;
-        CHAIN_LANES(T) {
-            A[t] = expf(A[t] - m);
-            z += A[t];
+        CHAIN_CASE;
+#pragma unroll
+        for (int v = 0; v < V; v++) {
+            float m = A[v];
+#pragma unroll
+            for (int t = 1; t < TM; t++)
+                if (t < T) m = fmaxf(m, A[t * V + v]);
+            float z = 0.f;
+#pragma unroll
+            for (int t = 0; t < TM; t++)
+                if (t < T) {
+                    A[t * V + v] = expf(A[t * V + v] - m);
+                    z += A[t * V + v];
+                }
+#pragma unroll
+            for (int t = 0; t < TM; t++)
+                if (t < T) A[t * V + v] = A[t * V + v] / z;
         }
-        CHAIN_LANES(T) A[t] = A[t] / z;
         break;
     }
     case OP_ST: {
+        CHAIN_CASE;
         if (!th.own) break;
-        const Ext& e = pg.ext[I.a];
-        const int64_t plane = (int64_t)H * W;
-        const int64_t base = ((int64_t)th.n * pg.C + c) * e.T;
-        const int64_t pix = (int64_t)th.row * W + th.col;
-        CHAIN_LANES(T) {
-            const int64_t idx = (base + t) * plane + pix;
-            CHAIN_VM_CHECK(pg, e, idx);
-            if (e.bf16) ((uint16_t*)e.ptr)[idx] = vm_f32_to_bf16(A[t]);
-            else if (I.kind & kStAdd) ((float*)e.ptr)[idx] += A[t];
-            else ((float*)e.ptr)[idx] = A[t];
-        }
+        const Tensor e = vm_tensor(pg, g, I.a);
+        const int chan = (th.n * g.C + c) * e.T;
+#pragma unroll
+        for (int t = 0; t < TM; t++)
+            if (t < T) {
+                float sv[V];
+#pragma unroll
+                for (int v = 0; v < V; v++) sv[v] = A[t * V + v];
+                vm_store<V>(e, (chan + t) * g.HW + th.p0, sv, (I.kind & kStAdd) != 0);
+            }
         break;
     }
     case OP_UNBX:
-        CHAIN_WITH_REG(st, I.r, X, CHAIN_LANES(T) A[t] = X[t] * vm_unary_grad(I.kind, A[t], I.f0, I.f1););
+        CHAIN_CASE;
+        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
+        switch (I.kind) {
+        case 0: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = A[e] > 0.f ? X[e] : 0.f;); break;
+        case 1: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] * vm_sign(A[e]);); break;
+        case 2: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] * vm_gelu_grad(A[e]);); break;
+        case 4: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] * cosf(A[e]);); break;
+        case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = -X[e];); break;
+        default: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = (A[e] > I.f0 && A[e] < I.f1) ? X[e] * expf(A[e]) : 0.f;); break;
+        }
         break;
     case OP_BING: {
+        CHAIN_CASE;
         const int kind = I.kind & 7;
         const bool rhs_side = I.kind & kBingRhsSide, l_sc = I.kind & kBingLhsScalar, r_sc = I.kind & kBingRhsScalar;
-        const float a0 = A[0];
-        CHAIN_WITH_REG(st, I.r, X, CHAIN_LANES(T) A[t] = vm_blend_grad(kind, rhs_side, l_sc ? X[0] : X[t], r_sc ? a0 : A[t]););
+        vm_reg_read<TM, V>(Rm, rstride, I.r, l_sc ? 1 : T, X);
+        if (TM > 1 && l_sc) CHAIN_EACH(T, e, X[e] = X[e % V];);
+        if (TM > 1 && r_sc) CHAIN_EACH(T, e, A[e] = A[e % V];);
+        // X: the LHS value, A: the RHS value; the result is d blend / d side (a tie of min / max belongs to the LHS)
+        switch (kind) {
+        case 0: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = 1.f;); break;
+        case 1:
+            CHAIN_CASE;
+            if (!rhs_side) break;  // d (l * r) / d l = r, which A holds
+            CHAIN_EACH(T, e, A[e] = X[e];);
+            break;
+        case 2:
+            CHAIN_CASE;
+            if (rhs_side) CHAIN_EACH(T, e, A[e] = -1.f;);
+            else CHAIN_EACH(T, e, A[e] = 1.f;);
+            break;
+        case 3:
+            CHAIN_CASE;
+            if (rhs_side) CHAIN_EACH(T, e, A[e] = X[e] <= A[e] ? 0.f : 1.f;);
+            else CHAIN_EACH(T, e, A[e] = X[e] <= A[e] ? 1.f : 0.f;);
+            break;
+        default:
+            CHAIN_CASE;
+            if (rhs_side) CHAIN_EACH(T, e, A[e] = X[e] >= A[e] ? 0.f : 1.f;);
+            else CHAIN_EACH(T, e, A[e] = X[e] >= A[e] ? 1.f : 0.f;);
+            break;
+        }
         break;
     }
     case OP_SMTBX:
-        CHAIN_WITH_REG(st, I.r, X, {
+        CHAIN_CASE;
+        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
+#pragma unroll
+        for (int v = 0; v < V; v++) {
             float dot = 0.f;
-            CHAIN_LANES(T) dot += X[t] * A[t];
-            CHAIN_LANES(T) A[t] = A[t] * (X[t] - dot);
-        });
-        break;
-    case OP_FOLDBX:
-        CHAIN_WITH_REG(st, I.r, X, {
-            const float g = X[0];
-            if (I.kind == 2) {
-                int best = 0;
-                float m = A[0];
-                _Pragma("unroll") for (int t = 1; t < TM; t++) if (t < T && A[t] > m) {
-                    m = A[t];
-                    best = t;
-                }
-                CHAIN_LANES(T) A[t] = t == best ? g : 0.f;
-            } else {
-                const float v = I.kind == 1 ? g / (float)T : g;
-                CHAIN_LANES(T) A[t] = v;
-            }
-        });
-        break;
-    case OP_PSET:
-        CHAIN_LANES(T) Pm[(I.a + t) * pstride] = I.f0;
-        break;
-    case OP_PADD:
-        CHAIN_LANES(T) Pm[(I.a + (t < (int)I.b ? t : t % (int)I.b)) * pstride] += A[t];
-        break;
-    case OP_PLD:
-        CHAIN_LANES(T) A[t] = Pm[(I.a + t) * pstride];
-        break;
-    case OP_SMCSTAT:
-        CHAIN_LANES(T) {
-            float& m = Pm[(I.a + t) * pstride];
-            float& z = Pm[(I.a + T + t) * pstride];
-            const float v = A[t];
-            if (v > m) {
-                z = z * expf(m - v) + 1.f;  // (m = -inf at the first channel: z = 0 * 0 + 1)
-                m = v;
-            } else {
-                z += expf(v - m);
-            }
+#pragma unroll
+            for (int t = 0; t < TM; t++)
+                if (t < T) dot += X[t * V + v] * A[t * V + v];
+#pragma unroll
+            for (int t = 0; t < TM; t++)
+                if (t < T) A[t * V + v] = A[t * V + v] * (X[t * V + v] - dot);
         }
         break;
+    case OP_FOLDBX:
+        CHAIN_CASE;
+        vm_reg_read<TM, V>(Rm, rstride, I.r, 1, X);
+        if (I.kind == 2) {
+#pragma unroll
+            for (int v = 0; v < V; v++) {
+                const float gr = X[v];
+                int best = 0;
+                float m = A[v];
+#pragma unroll
+                for (int t = 1; t < TM; t++)
+                    if (t < T && A[t * V + v] > m) {
+                        m = A[t * V + v];
+                        best = t;
+                    }
+#pragma unroll
+                for (int t = 0; t < TM; t++)
+                    if (t < T) A[t * V + v] = t == best ? gr : 0.f;
+            }
+        } else {
+            if (I.kind == 1) {
+#pragma unroll
+                for (int v = 0; v < V; v++) X[v] = X[v] / (float)T;
+            }
+            CHAIN_EACH(T, e, A[e] = X[e % V];);
+        }
+        break;
+    case OP_PSET:
+        CHAIN_CASE;
+        CHAIN_EACH(T, e, Pm[(I.a * V + e) * pstride] = I.f0;);
+        break;
+    case OP_PADD: {
+        CHAIN_CASE;
+        const int Tb = I.b;
+#pragma unroll
+        for (int t = 0; t < TM; t++)
+            if (t < T) {
+                const int tp = t < Tb ? t : t % Tb;
+#pragma unroll
+                for (int v = 0; v < V; v++) Pm[((I.a + tp) * V + v) * pstride] += A[t * V + v];
+            }
+        break;
+    }
+    case OP_PLD:
+        CHAIN_CASE;
+        CHAIN_EACH(T, e, A[e] = Pm[(I.a * V + e) * pstride];);
+        break;
+    case OP_SMCSTAT:
+        CHAIN_CASE;
+        CHAIN_EACH(T, e, {
+            float& m = Pm[(I.a * V + e) * pstride];
+            float& z = Pm[((I.a + T) * V + e) * pstride];
+            const float val = A[e];
+            if (val > m) {
+                z = z * expf(m - val) + 1.f;  // (m = -inf at the first channel: z = 0 * 0 + 1)
+                m = val;
+            } else {
+                z += expf(val - m);
+            }
+        });
+        break;
     case OP_SMCAPPLY:
-        CHAIN_LANES(T) A[t] = expf(A[t] - Pm[(I.a + t) * pstride]) / Pm[(I.a + T + t) * pstride];
+        CHAIN_CASE;
+        CHAIN_EACH(T, e, A[e] = expf(A[e] - Pm[(I.a * V + e) * pstride]) / Pm[((I.a + T) * V + e) * pstride];);
         break;
     case OP_SMCDOT:
-        CHAIN_WITH_REG(st, I.r, X, CHAIN_LANES(T) Pm[(I.a + t) * pstride] += A[t] * X[t];);
+        CHAIN_CASE;
+        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
+        CHAIN_EACH(T, e, Pm[(I.a * V + e) * pstride] += A[e] * X[e];);
         break;
     case OP_SMCBX:
-        CHAIN_WITH_REG(st, I.r, X, CHAIN_LANES(T) A[t] = A[t] * (X[t] - Pm[(I.a + t) * pstride]););
+        CHAIN_CASE;
+        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
+        CHAIN_EACH(T, e, A[e] = A[e] * (X[e] - Pm[(I.a * V + e) * pstride]););
         break;
     default: break;
     }
 }
 
-// OP_XADD, lane t: the thread index (inside the workgroup) whose load at offset [+ window tap t] read this
-// thread's pixel, or -1 when there is none (outside the image, or outside the rows the workgroup computes: the
-// planner sizes the halo so that this never happens to a pixel the workgroup owns).
-CHAIN_HD int vm_xadd_source(const Program& pg, const Instr& I, int dh, int dw, int t, const Thread& th, int row_first, int rows) {
-    int oh = dh, ow = dw;
-    if (I.kind & kWin) {
-        const int KH = I.r >> 4, KW = I.r & 15;
-        oh += t / KW - KH / 2;
-        ow += t % KW - KW / 2;
+// OP_XADD, first half: the thread's lanes go to the hand-over buffer of its slice (lane t of local pixel q at
+// buf[t * npx + q]).
+template <int TM, int V, class AT>
+CHAIN_HD void vm_xadd_write(const Geo& g, const Instr& I, const Thread& th, const AT& A, float* buf) {
+#pragma unroll
+    for (int t = 0; t < TM; t++)
+        if (t < I.T) {
+#pragma unroll
+            for (int v = 0; v < V; v++) buf[t * g.npx + th.ptid * V + v] = A[t * V + v];
+        }
+}
+
+// OP_XADD, second half (after a barrier): P[a (+ t)] of every pixel of the thread collects lane t of the pixel whose
+// load at offset (dh, dw) [+ window tap t] read it, if that pixel is inside the image and inside the pixels the slice
+// computes (the planner sizes the halo so that an owned pixel never misses one).  Fixed order: deterministic.
+template <int TM, int V>
+CHAIN_HD void vm_xadd_gather(const Geo& g, const Instr& I, int dh, int dw, const Thread& th, const float* buf, float* Pm, int pstride) {
+#pragma unroll
+    for (int t = 0; t < TM; t++)
+        if (t < I.T) {
+            int oh = dh, ow = dw;
+            if (I.kind & kWin) {
+                int th_, tw_;
+                vm_tap(t, I.r >> 4, I.r & 15, th_, tw_);
+                oh += th_;
+                ow += tw_;
+            }
+            // the source of pixel (r, c) is pixel (r - oh, c - ow)
+            const uint32_t m = vm_valid<V>(g, th, -oh, -ow);
+            const int slot = I.a + ((I.kind & kExtTaps) ? t : 0);
+#pragma unroll
+            for (int v = 0; v < V; v++) {
+                const int src = th.ptid * V + v - (oh * g.W + ow);
+                if (((m >> v) & 1u) && src >= 0 && src < g.npx) Pm[(slot * V + v) * pstride] += buf[t * g.npx + src];
+            }
+        }
+}
+
+// Combination of the slices' partial results of lane e (= t * V + v) of a Red (see chain_isa.hpp) for the pixels of
+// thread `ptid`: float k of slice s is at Pbase[(k * V + v) * pstride + s * pix_threads + ptid].  kind 0 returns the
+// total maximum and sum.
+template <int V>
+CHAIN_HD void vm_combine(const Red& R, int e, int S, int PT, const float* Pbase, int pstride, int ptid, float& v0, float& v1) {
+    const float* p0 = Pbase + (R.slot * V + e) * pstride + ptid;
+    if (R.kind == 0) {
+        const float* p1 = Pbase + ((R.slot + R.T) * V + e) * pstride + ptid;
+        float m = -INFINITY;
+        for (int s = 0; s < S; s++) m = fmaxf(m, p0[s * PT]);
+        float z = 0.f;
+        for (int s = 0; s < S; s++) {
+            const float zs = p1[s * PT];
+            if (zs > 0.f) z += zs * expf(p0[s * PT] - m);  // (a slice without channels has no sum and no maximum)
+        }
+        v0 = m;
+        v1 = z;
+    } else {
+        float d = 0.f;
+        for (int s = 0; s < S; s++) d += p0[s * PT];
+        v0 = d;
+        v1 = 0.f;
     }
-    const int sr = th.row - oh, sc = th.col - ow;
-    if (!th.active || sc < 0 || sc >= pg.W || sr < 0 || sr >= pg.H || sr < row_first || sr >= row_first + rows) return -1;
-    return (sr - row_first) * pg.W + sc;
 }
 
 }  // namespace chain
