@@ -126,7 +126,7 @@ struct Program {
     int32_t tm = 1;            // lanes the kernel instance must have (1, 9 or 25)
     int32_t fast_math = 0;     // 1: every tensor of the DAG is bf16, transcendental functions may be accurate to 1e-6 only
     int32_t n_regs = 0;        // registers R the program uses
-    int32_t pad0 = 0;
+    int32_t unroll = 1;        // channels a thread works on per trip through a pass's body (side by side, like wider lanes)
     Pass pass[kMaxPass];
     Red red[kMaxRed];
     Ext ext[kMaxExt];

@@ -29,7 +29,7 @@ __device__ __forceinline__ const Program& stage_program(unsigned char* sprog) {
     return *(const Program*)sprog;
 }
 
-template <int TM, int V>
+template <int TM, int V, int U>
 __global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program) {
     __shared__ __align__(16) unsigned char sprog[sizeof(Program)];
     const Program& pg = stage_program(sprog);
@@ -43,14 +43,18 @@ __global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program) {
     // LDS: registers (16-byte pieces, see vm_reg_read) | hand-over buffers | persistent floats (float k of pixel v of thread i at [(k * V + v) * threads + i])
     const int rstride = threads * 4;
     float* const Rm = lds + threadIdx.x * 4;
-    float* const xbase = lds + vm_u(pg.n_regs) * reg_pieces(TM, V) * rstride;
+    float* const xbase = lds + vm_u(pg.n_regs) * reg_pieces(U * TM * V) * rstride;
     float* const Pbase = xbase + S * xfloats;
     float* const Pm = Pbase + threadIdx.x;
     const int slice = __builtin_amdgcn_readfirstlane(threadIdx.x / PT);  // (PT is a multiple of 64: uniform in a wavefront)
     float* const xbuf = xbase + slice * xfloats;
-    State<TM, V> st;
+    State<TM, V, U> st;
 #pragma unroll
-    for (int e = 0; e < TM * V; e++) st.A[e] = 0.f;
+    for (int e = 0; e < U * TM * V; e++) st.A[e] = 0.f;
+    Env ev;
+    ev.np = vm_u(pg.n_persist);
+    ev.pstride = threads;
+    ev.rstride = rstride;
     // The workgroup stays and walks over its share of the work items (image, tile, channel range): the program is staged
     // once per workgroup, not once per item.  item = (image * tiles + tile) * chunks + chunk
     const int items = g.N * tiles * chunks;
@@ -74,29 +78,32 @@ __global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program) {
             const int pro_begin = vm_u((int)pw[0]) & 0xffff, pro_end = (int)((uint32_t)vm_u((int)pw[0]) >> 16);
             const int body_begin = vm_u((int)pw[1]) & 0xffff, body_end = (int)((uint32_t)vm_u((int)pw[1]) >> 16);
             const int red_begin = vm_u((int)pw[2]) & 0xffff, red_end = (int)((uint32_t)vm_u((int)pw[2]) >> 16);
-            // trip -1 is the prologue (every slice, once); then slice s takes channels c_begin + s, + slices, ...: every
-            // slice makes the same number of trips (the hand-over of OP_XADD synchronises the workgroup), a trip past the
-            // last channel only keeps the barriers company
-            for (int c0 = c_begin - S; c0 < c_end; c0 += S) {
-                const bool pro = c0 < c_begin;
-                const int c = pro ? c_begin : c0 + slice;
-                const bool has = c < c_end;
-                const int i_begin = pro ? pro_begin : body_begin, i_end = pro ? pro_end : body_end;
+            // trip -1 is the prologue (every slice, once); then slice s takes channels c_begin + s * U ... + U - 1, the next
+            // slices * U, ...: every slice makes the same number of trips (the hand-over of OP_XADD synchronises the
+            // workgroup), a trip past the last channel only keeps the barriers company
+            for (int c0 = c_begin - S * U; c0 < c_end; c0 += S * U) {
+                ev.pro = c0 < c_begin;
+                ev.c = ev.pro ? c_begin : c0 + slice * U;
+                ev.h = ev.pro ? 1 : (c_end - ev.c < 0 ? 0 : (c_end - ev.c < U ? c_end - ev.c : U));
+                const int i_begin = ev.pro ? pro_begin : body_begin, i_end = ev.pro ? pro_end : body_end;
                 if (i_begin >= i_end) continue;
                 uint4 next = *(const uint4*)&pg.ins[i_begin];
                 for (int i = i_begin; i < i_end; i++) {
                     const Instr I = vm_uniform(next);
                     if (i + 1 < i_end) next = *(const uint4*)&pg.ins[i + 1];  // (on its way while this instruction runs)
                     if (I.op != OP_XADD) {
-                        if (has) vm_exec<TM, V>(pg, g, I, c, th, st, Pm, threads, Rm, rstride);
+                        if (ev.h > 0) vm_exec<TM, V, U>(pg, g, I, ev, th, st, Pm, Rm);
                         continue;
                     }
-                    int dh = 0, dw = 0;
-                    if (has) vm_offset(pg, I.b, c, dh, dw);
-                    __syncthreads();  // the previous hand-over has been read
-                    vm_xadd_write<TM, V>(g, I, th, st.A, xbuf);
-                    __syncthreads();
-                    if (has) vm_xadd_gather<TM, V>(g, I, dh, dw, th, xbuf, Pm, threads);
+#pragma unroll
+                    for (int u = 0; u < U; u++) {
+                        int dh = 0, dw = 0;
+                        if (u < ev.h) vm_offset(pg, I.b, ev.c + u, dh, dw);
+                        __syncthreads();  // the previous hand-over has been read
+                        vm_xadd_write<TM, V>(g, I, th, st.A + u * TM * V, xbuf);
+                        __syncthreads();
+                        if (u < ev.h) vm_xadd_gather<TM, V>(g, I, dh, dw, th, xbuf, Pm + u * ev.np * V * threads, threads);
+                    }
                 }
             }
             // the slices' partial statistics and sums of this pass become totals, for every slice
@@ -126,7 +133,8 @@ __global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program) {
 // threads each), else a grid of that size whose workgroups take equal shares.
 inline unsigned grid_for(const Program& pg) {
     const int64_t items = (int64_t)pg.N * pg.tiles * pg.chunks;
-    const int64_t resident = 256 * (int64_t)std::max(1, 2048 / pg.threads);
+    const int64_t by_lds = std::max<int64_t>(1, (160 * 1024) / (int64_t)(lds_bytes(pg) + sizeof(Program) + 256));
+    const int64_t resident = 256 * std::min<int64_t>(std::max(1, 2048 / pg.threads), by_lds);
     if (items <= resident) return (unsigned)items;
     const int64_t per = (items + resident - 1) / resident;
     return (unsigned)((items + per - 1) / per);
@@ -134,8 +142,12 @@ inline unsigned grid_for(const Program& pg) {
 
 template <int TM, int V>
 void launch(const Program& pg, hipStream_t stream) {
+    constexpr int U = unroll_for(TM, V);
+    // (more than 64 KB of dynamic LDS must be asked for, once per kernel)
+    static const hipError_t lds_ok = hipFuncSetAttribute((const void*)k_chain<TM, V, U>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLdsBytes);
+    (void)lds_ok;
     const dim3 grid(grid_for(pg));
-    CANVAS_LAUNCH((k_chain<TM, V>), grid, dim3((unsigned)pg.threads), lds_bytes(pg), stream, pg);
+    CANVAS_LAUNCH((k_chain<TM, V, U>), grid, dim3((unsigned)pg.threads), lds_bytes(pg), stream, pg);
 }
 
 }  // namespace

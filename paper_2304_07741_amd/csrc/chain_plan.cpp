@@ -15,7 +15,10 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <functional>
 #include <map>
+#include <memory>
+#include <set>
 #include <sstream>
 #include <tuple>
 
@@ -251,8 +254,39 @@ class Emitter {
         return I;
     }
 
+    // ---------------------------------------------------------------- values kept for another use
+    // A value (key 2 * instance) or a gradient (key 2 * instance + 1) that `keep` names is stored in a register the
+    // first time a pass body computes it and fetched from there afterwards.  `stats` records, per key, how often it was
+    // computed and how many instructions one computation took: what the choice of `keep` is made from.
+    struct Stat {
+        int computed = 0, cost = 0;
+    };
+    void cached(int key, int lanes, void (Emitter::*raw)(int), int i) {
+        auto it = held.find(key);
+        if (it != held.end()) {
+            emit(simple(OP_MOVA, lanes, it->second));
+            return;
+        }
+        const int before = pg.n_instr;
+        (this->*raw)(i);
+        Stat& st = stats[key];
+        st.computed++;
+        st.cost = std::max(st.cost, pg.n_instr - before);
+        if (keep.count(key)) {
+            const int r = alloc();
+            emit(simple(OP_MOVR, lanes, r));
+            held[key] = r;
+        }
+    }
+    void forget() {  // (a register's content does not outlive the body it was written in)
+        for (auto& kv : held) release(kv.second);
+        held.clear();
+    }
+    void eval(int i) { cached(2 * i, G.insts[i].lanes, &Emitter::eval_raw, i); }
+    void grad(int i) { cached(2 * i + 1, G.insts[i].lanes, &Emitter::grad_raw, i); }
+
     // ---------------------------------------------------------------- forward values
-    void eval(int i) {
+    void eval_raw(int i) {
         const Inst& I = G.insts[i];
         const Node& nd = G.dag.nodes[I.node];
         switch (I.kind) {
@@ -304,19 +338,19 @@ class Emitter {
     }
 
     int stat_slot(int i) {
-        auto it = stats.find(i);
-        if (it != stats.end()) return it->second;
-        return stats[i] = persist(2 * G.insts[i].lanes);
+        auto it = stat_slots.find(i);
+        if (it != stat_slots.end()) return it->second;
+        return stat_slots[i] = persist(2 * G.insts[i].lanes);
     }
     int dot_slot(int i) {
-        auto it = dots.find(i);
-        if (it != dots.end()) return it->second;
-        return dots[i] = persist(G.insts[i].lanes);
+        auto it = dot_slots.find(i);
+        if (it != dot_slots.end()) return it->second;
+        return dot_slots[i] = persist(G.insts[i].lanes);
     }
 
     // ---------------------------------------------------------------- gradients
     // leaves d loss / d instance i in A (lanes of i)
-    void grad(int i) {
+    void grad_raw(int i) {
         const Inst& I = G.insts[i];
         bool first = true;
         int held = -1;
@@ -444,7 +478,10 @@ class Emitter {
         pg.pass[pg.n_pass].red_end = (uint16_t)pg.n_red;
     }
     void begin_body() { pg.pass[pg.n_pass].pro_end = pg.pass[pg.n_pass].body_begin = (uint16_t)pg.n_instr; }
-    void end_pass() { pg.pass[pg.n_pass++].body_end = (uint16_t)pg.n_instr; }
+    void end_pass() {
+        pg.pass[pg.n_pass++].body_end = (uint16_t)pg.n_instr;
+        forget();
+    }
 
     // the passes that collect the statistics of every softmax over channels, lowest first
     void stat_passes(const std::vector<int>& smc) {
@@ -476,33 +513,32 @@ class Emitter {
     int NR;
     std::vector<bool> used;
     std::map<int, uint16_t> term_of;
-    std::map<int, int> stats, dots;
+    std::map<int, int> stat_slots, dot_slots;
+    std::set<int> keep;
+    std::map<int, int> held;
+    std::map<int, Stat> stats;
+    std::map<int, int64_t> reach_of;  // per OP_XADD instruction: how far (in pixels) its sources can lie
 };
 
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Workgroup shape for V pixels per thread: tile and halo, channel range and slices.  False when it does not fit.
-bool geometry_for(Program& pg, const Dag& dag, int C, int64_t reach_px, bool all_channels, int V) {
+// Workgroup shape for V pixels per thread and `pt` threads per slice: tile and halo, channel range and slices.
+// Returns the estimated cost of the launch (arbitrary units, see set_geometry) or a negative number when it does not fit.
+double geometry_for(Program& pg, const Dag& dag, int C, int64_t reach_px, bool all_channels, int V, int pt, int trips) {
     const int HW = dag.H * dag.W;
     pg.vec = V;
+    pg.unroll = unroll_for(pg.tm, V);
     const int PP = HW / V;                                   // pixel threads of a plane
     const int64_t HT = (reach_px + V - 1) / V;               // halo, in pixel threads
     const int per_thread = std::max<int>(1, (int)lds_bytes_per_thread(pg));
     const int cap = (int)(std::min<int64_t>(max_threads_for(pg.tm), (int64_t)kMaxLdsBytes / per_thread) / 64 * 64);
-    if (cap < 64) return false;
-    int pt, own;
-    if (HT == 0) {
-        pt = 64;
-        own = 64;
-    } else if (PP + 2 * HT <= cap) {  // the whole plane in one tile
+    if (cap < 64 || pt > cap || 2 * HT >= pt) return -1;
+    int own = pt - 2 * (int)HT;
+    if (own >= PP) {  // the whole plane in one tile
+        if (ceil_div(PP + 2 * (int)HT, 64) * 64 != pt) return -1;  // (counted once, at its own size)
         own = PP;
-        pt = ceil_div(PP + 2 * (int)HT, 64) * 64;
     } else {
-        // recomputed pixels are lost work: the largest workgroup there is, its tiles evened out over the plane
-        if (2 * HT >= cap) return false;
-        const int tiles = ceil_div(PP, cap - 2 * (int)HT);
-        own = ceil_div(PP, tiles);
-        pt = ceil_div(own + 2 * (int)HT, 64) * 64;
+        own = ceil_div(PP, ceil_div(PP, own));  // tiles evened out over the plane
     }
     pg.pix_threads = pt;
     pg.own_threads = own;
@@ -513,23 +549,27 @@ bool geometry_for(Program& pg, const Dag& dag, int C, int64_t reach_px, bool all
     if (all_channels) {
         pg.chunk = C;
         pg.chunks = 1;
-        pg.slices = std::min(max_slices, std::min(C, 16));
+        pg.slices = std::min(max_slices, std::min(ceil_div(C, pg.unroll), 16));
     } else {
-        // one wavefront-trip = one channel of 64 pixel threads; a few trips per thread once the chip is full
-        const int64_t trips_total = (int64_t)dag.N * pg.tiles * (pt / 64) * C;
-        int trips = (int)std::max<int64_t>(1, std::min<int64_t>(4, trips_total / 16384));
-        int S = std::max(1, std::min(std::min(max_slices, 4), C));
-        const int chunks = ceil_div(C, S * trips);
+        const int S = std::max(1, std::min(std::min(max_slices, 4), ceil_div(C, pg.unroll)));
+        const int chunks = ceil_div(C, S * pg.unroll * trips);
         pg.chunk = ceil_div(C, chunks);
         pg.chunks = ceil_div(C, pg.chunk);
-        pg.slices = std::min(S, pg.chunk);
+        pg.slices = std::min(S, ceil_div(pg.chunk, pg.unroll));
     }
     pg.threads = pg.slices * pg.pix_threads;
-    return lds_bytes(pg) <= kMaxLdsBytes && (int64_t)dag.N * pg.tiles * pg.chunks < ((int64_t)1 << 31);
+    if (lds_bytes(pg) > kMaxLdsBytes || (int64_t)dag.N * pg.tiles * pg.chunks >= ((int64_t)1 << 31)) return -1;
+    // cost: trips of a thread x what a trip costs (a fixed part for fetching and dispatching the instructions, worth
+    // about eight pixels of arithmetic, plus per channel the pixels and about four pixels' worth for its narrow memory
+    // accesses) x how many times over the launch fills the chip (256 compute units, about 1024 resident threads each)
+    const double trips_per_thread = (double)ceil_div(pg.chunk, pg.slices * pg.unroll);
+    const double threads_total = (double)dag.N * pg.tiles * pg.chunks * pg.threads;
+    const double wgs_per_cu = std::max(1.0, std::min(1024.0 / pg.threads, std::floor(160.0 * 1024.0 / (double)(lds_bytes(pg) + 4352))));
+    const double rounds = std::max(1.0, threads_total / (256.0 * wgs_per_cu * pg.threads));
+    return trips_per_thread * (8.0 + (V + 4.0) * pg.unroll) * rounds + 4.0;  // (+ the workgroup's start-up)
 }
 
-// Pixels per thread: the widest vector that still puts enough threads on the chip (a program that keeps all channels of
-// a pixel in one workgroup has only pixels and slices to spread), else whatever gives the most threads.
+// Pixels per thread, threads per slice and trips per thread: whatever the estimate likes best.
 void set_geometry(Program& pg, const Dag& dag, int C, int64_t reach_px, bool all_channels) {
     pg.N = dag.N;
     pg.C = C;
@@ -539,26 +579,22 @@ void set_geometry(Program& pg, const Dag& dag, int C, int64_t reach_px, bool all
     for (int i = 0; i < pg.n_instr; i++)
         if (pg.ins[i].op == OP_XADD) pg.xadd_lanes = std::max<int>(pg.xadd_lanes, pg.ins[i].T);
     const int HW = dag.H * dag.W;
-    // (CANVAS_CHAIN_THREADS overrides the threshold: 0 always takes the widest vector)
-    static const int64_t kEnoughThreads = std::getenv("CANVAS_CHAIN_THREADS") ? std::atoll(std::getenv("CANVAS_CHAIN_THREADS")) : 96 * 1024;
     Program best;
-    int64_t best_threads = -1;
+    double best_cost = -1;
     for (int V = max_vec_for(pg.tm); V >= 1; V /= 2) {
         if (HW % V != 0 || dag.W < V) continue;
-        Program q = pg;
-        if (!geometry_for(q, dag, C, reach_px, all_channels, V)) continue;
-        // threads that do useful work
-        const int64_t n = (int64_t)dag.N * (HW / V) * q.chunks * q.slices;
-        if (n >= kEnoughThreads) {
-            pg = q;
-            return;
-        }
-        if (n > best_threads) {
-            best_threads = n;
-            best = q;
-        }
+        for (int pt = 64; pt <= max_threads_for(pg.tm); pt += 64)
+            for (int trips = 1; trips <= (all_channels ? 1 : 4); trips *= 2) {
+                Program q = pg;
+                const double cost = geometry_for(q, dag, C, reach_px, all_channels, V, pt, trips);
+                if (cost < 0) continue;
+                if (best_cost < 0 || cost < best_cost * 0.999) {  // (ties: the wider vector, the smaller workgroup, fewer trips)
+                    best_cost = cost;
+                    best = q;
+                }
+            }
     }
-    if (best_threads < 0) throw Fail{"tile, halo and persistent state do not fit one workgroup"};
+    if (best_cost < 0) throw Fail{"tile, halo and persistent state do not fit one workgroup"};
     pg = best;
 }
 
@@ -622,9 +658,8 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
         if (lanes > 25) throw Fail{"more than 25 taps"};
         const int tm = lanes <= 1 ? 1 : (lanes <= 9 ? 9 : 25);
 
-        // ------------------------------------------------------------ forward program
-        {
-            Emitter E(G, tm);
+        // ------------------------------------------------------------ the two programs
+        auto emit_fwd = [&](Emitter& E) {
             E.stat_passes(smc);
             E.begin_pass();
             E.begin_body();
@@ -635,13 +670,8 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
                 E.emit(st);
             }
             E.end_pass();
-            set_geometry(E.pg, dag, C, 0, !smc.empty());
-            out.fwd = E.pg;
-            out.fwd_ext = E.ext;
-        }
-        // ------------------------------------------------------------ backward program
-        {
-            Emitter E(G, tm);
+        };
+        auto emit_bwd = [&](Emitter& E) {
             E.stat_passes(smc);
             int deepest = 0;
             for (int i : smc) deepest = std::max(deepest, G.down(i));
@@ -666,7 +696,6 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
             }
             E.begin_pass();
             E.begin_body();
-            int64_t halo = 0;
             for (int e : out.inputs) {
                 std::vector<int> mine;
                 for (int i : leaves)
@@ -692,8 +721,8 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
                         Instr x = E.positional(OP_XADD, L.ctx, L.lanes);
                         x.a = (uint16_t)acc;
                         if (Te > 1) x.kind |= kExtTaps;
+                        E.reach_of[E.pg.n_instr] = G.ctxs[L.ctx].reach_px(dag.W);
                         E.emit(x);
-                        halo = std::max(halo, G.ctxs[L.ctx].reach_px(dag.W));
                     }
                 }
                 if (!direct) E.emit(Emitter::simple(OP_PLD, Te, 0, 0, acc));
@@ -702,9 +731,52 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
                 E.emit(st);
             }
             E.end_pass();
-            set_geometry(E.pg, dag, C, halo, !smc.empty());
-            out.bwd = E.pg;
-            out.bwd_ext = E.ext;
+        };
+        // A program is emitted with full recomputation first; then, greedily, the value or gradient whose repeated
+        // computation costs the most instructions is kept in a register, as long as that shortens the program and the
+        // registers last.  Returns the emitter of the shortest program that could be emitted.
+        auto shortest = [&](const std::function<void(Emitter&)>& emit_program) {
+            std::set<int> keep;
+            auto best = std::make_shared<Emitter>(G, tm);
+            emit_program(*best);  // (throws when even the plain program does not fit)
+            for (int round = 0; round < regs_for(tm); round++) {
+                int pick = -1, gain = 1;
+                for (const auto& kv : best->stats) {
+                    const int g = (kv.second.computed - 1) * (kv.second.cost - 1) - 1;  // (- the store)
+                    if (!keep.count(kv.first) && g > gain) {
+                        gain = g;
+                        pick = kv.first;
+                    }
+                }
+                if (pick < 0) break;
+                keep.insert(pick);
+                try {
+                    auto E = std::make_shared<Emitter>(G, tm);
+                    E->keep = keep;
+                    emit_program(*E);
+                    if (E->pg.n_instr >= best->pg.n_instr) break;
+                    best = E;
+                } catch (const Fail&) {
+                    break;
+                }
+            }
+            return best;
+        };
+        {
+            auto E = shortest(emit_fwd);
+            set_geometry(E->pg, dag, C, 0, !smc.empty());
+            out.fwd = E->pg;
+            out.fwd_ext = E->ext;
+        }
+        {
+            auto E = shortest(emit_bwd);
+            int64_t halo = 0;
+            for (int i = 0; i < E->pg.n_instr; i++)  // (the reach of the hand-overs of the program that was chosen)
+                if (E->pg.ins[i].op == OP_XADD) halo = std::max(halo, E->reach_of[i]);
+            set_geometry(E->pg, dag, C, halo, !smc.empty());
+            out.bwd = E->pg;
+            out.bwd_ext = E->ext;
+            out.cost = program_cost(out.fwd) + program_cost(out.bwd);
         }
         return true;
     } catch (const Fail& f) {
@@ -713,12 +785,35 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
     }
 }
 
+double program_cost(const Program& pg) {
+    double sum = 0;
+    for (int p = 0; p < pg.n_pass; p++)
+        for (int i = pg.pass[p].body_begin; i < pg.pass[p].body_end; i++) {
+            const Instr& I = pg.ins[i];
+            double w = 1;
+            switch (I.op) {
+            case OP_LD:
+            case OP_ST: w = 4; break;
+            case OP_XADD: w = 6; break;
+            case OP_UN:
+            case OP_UNBX: w = (I.kind == 0 || I.kind == 1 || I.kind == kUnNeg) ? 1 : 6; break;
+            case OP_SMT:
+            case OP_SMTBX:
+            case OP_SMCSTAT:
+            case OP_SMCAPPLY: w = 6; break;
+            default: break;
+            }
+            sum += w * I.T;
+        }
+    return sum * (double)pg.pix_threads / std::max(1, pg.own_threads + (pg.halo_threads > 0 ? 0 : pg.pix_threads - pg.own_threads));
+}
+
 std::string dump(const Program& pg) {
     static const char* names[] = {"LD", "MASK", "UN", "MOVR", "MOVA", "BIN", "FOLD", "SMT", "ST", "UNBX", "BING", "SMTBX", "FOLDBX",
                                   "PSET", "PADD", "PLD", "SMCSTAT", "SMCAPPLY", "SMCDOT", "SMCBX", "XADD"};
     std::ostringstream os;
     os << "program: C=" << pg.C << " HxW=" << pg.H << "x" << pg.W << " vec=" << pg.vec << " own=" << pg.own_threads << " halo=" << pg.halo_threads
-       << " tiles=" << pg.tiles << " chunk=" << pg.chunk << " slices=" << pg.slices << " threads=" << pg.threads << " persist=" << pg.n_persist
+       << " unroll=" << pg.unroll << " tiles=" << pg.tiles << " chunk=" << pg.chunk << " slices=" << pg.slices << " threads=" << pg.threads << " persist=" << pg.n_persist
        << " lanes=" << pg.tm << "\n";
     for (int p = 0; p < pg.n_pass; p++) {
         os << " pass " << p << "\n";

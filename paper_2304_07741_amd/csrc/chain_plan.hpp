@@ -30,7 +30,7 @@ struct UnitPlan {
     std::vector<int> outputs;   // nodes of the unit that are stored, ascending
     Program fwd, bwd;
     std::vector<ExtRef> fwd_ext, bwd_ext;  // one per ext slot of the program
-    double fwd_bytes_elems = 0;  // (unused by the kernels) elements read + written, for the launch description
+    double cost = 0;            // estimated work of both programs per pixel and channel (see program_cost)
 };
 
 // True when node k can be part of a fused chain at all (op, shapes, attributes).
@@ -40,6 +40,12 @@ bool chain_candidate(const Dag& dag, int k);
 // stored (it is the DAG's output or something outside the unit reads it).  Returns false (and says why) when the
 // unit does not fit the machine: a stencil above a reduction, too many instructions, registers, passes, LDS ...
 bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vector<bool>& is_output, UnitPlan& out, std::string& why);
+
+// Estimated work of a program per pixel and channel of the unit, in units of one cheap lane operation: a lane of a
+// tensor access counts 4, of a gradient hand-over 6, of a transcendental function 6; the whole is scaled by the pixels a
+// workgroup computes per pixel it owns (the halo of backward programs).  The lowering lets a node join a chain only
+// while the grown chain is not much dearer than the two chains apart.
+double program_cost(const Program& pg);
 
 // Text form of a program (for CANVAS_LOG and debugging).
 std::string dump(const Program& pg);

@@ -28,14 +28,14 @@
 namespace canvas {
 namespace chain {
 
-template <int TM, int V>
+template <int TM, int V, int U>
 struct State {
-    float A[TM * V];
+    float A[U * TM * V];
 };
 
-// 16-byte pieces of a register R[r] (TM * V floats, rounded up); piece q of register r of thread i is at float
+// 16-byte pieces of a register R[r] (lanes floats, rounded up); piece q of register r of thread i is at float
 // ((r * pieces + q) * threads + i) * 4 of the register area, so that a wavefront's access is one contiguous run.
-constexpr int reg_pieces(int tm, int v) { return (tm * v + 3) / 4; }
+constexpr int reg_pieces(int lanes) { return (lanes + 3) / 4; }
 
 // What a thread knows about its pixels.  p0 is the plane index of its first pixel (a multiple of V; threads of the
 // halo may lie before the plane or behind it: active == false); only `own` threads store.
@@ -321,48 +321,68 @@ CHAIN_HD void vm_tap(int t, int KH, int KW, int& oh, int& ow) {
     ow = t - kh * KW - KW / 2;
 }
 
-// Lanes [0, T * V) of a value: T is uniform (1, or the taps of a window).
-#define CHAIN_EACH(T, e, ...)                                                             \
+// Lanes of a value: channel u < U of the trip, tap t < T (T is uniform: 1, or the taps of a window), pixel v < V.
+// The body sees e = (u * TM + t) * V + v and l = t * V + v.
+#define CHAIN_EACH(T, e, l, ...)                                                          \
     do {                                                                                  \
         if (TM == 1 || (T) == 1) {                                                        \
-            _Pragma("unroll") for (int e = 0; e < V; e++) { __VA_ARGS__ }                 \
-        } else {                                                                          \
-            _Pragma("unroll") for (int t_ = 0; t_ < TM; t_++) if (t_ < (T)) {             \
-                _Pragma("unroll") for (int v_ = 0; v_ < V; v_++) {                        \
-                    const int e = t_ * V + v_;                                            \
+            _Pragma("unroll") for (int u_ = 0; u_ < U; u_++) {                            \
+                _Pragma("unroll") for (int l = 0; l < V; l++) {                           \
+                    const int e = u_ * TM * V + l;                                        \
                     __VA_ARGS__                                                           \
+                }                                                                         \
+            }                                                                             \
+        } else {                                                                          \
+            _Pragma("unroll") for (int u_ = 0; u_ < U; u_++) {                            \
+                _Pragma("unroll") for (int t_ = 0; t_ < TM; t_++) if (t_ < (T)) {         \
+                    _Pragma("unroll") for (int v_ = 0; v_ < V; v_++) {                    \
+                        const int l = t_ * V + v_;                                        \
+                        const int e = u_ * TM * V + l;                                    \
+                        __VA_ARGS__                                                       \
+                    }                                                                     \
                 }                                                                         \
             }                                                                             \
         }                                                                                 \
     } while (0)
 
-// Register r (uniform) <-> X.  Rm: piece 0 of register 0 of this thread; rstride: floats between pieces (threads * 4).
-template <int TM, int V>
+// Register r (uniform) of all U channels <-> X: lanes [0, T * V) of every channel.  Rm: piece 0 of register 0 of this
+// thread; rstride: floats between pieces (threads * 4); a register is its U * TM * V lanes in pieces of four.
+template <int TM, int V, int U>
 CHAIN_HD void vm_reg_read(const float* Rm, int rstride, int r, int T, float* X) {
-    constexpr int Q = reg_pieces(TM, V);
+    constexpr int L = U * TM * V, Q = reg_pieces(L);
     const float* src = Rm + r * Q * rstride;
 #pragma unroll
-    for (int q = 0; q < Q; q++)
-        if (q * 4 < T * V) {
+    for (int q = 0; q < Q; q++) {
+        bool needed = false;
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+            if (q * 4 + k < L && (q * 4 + k) % (TM * V) < T * V) needed = true;
+        if (needed) {
             float w[4];
             memcpy(w, src + q * rstride, 16);
 #pragma unroll
             for (int k = 0; k < 4; k++)
-                if (q * 4 + k < TM * V) X[q * 4 + k] = w[k];
+                if (q * 4 + k < L) X[q * 4 + k] = w[k];
         }
+    }
 }
-template <int TM, int V>
+template <int TM, int V, int U>
 CHAIN_HD void vm_reg_write(float* Rm, int rstride, int r, int T, const float* X) {
-    constexpr int Q = reg_pieces(TM, V);
+    constexpr int L = U * TM * V, Q = reg_pieces(L);
     float* dst = Rm + r * Q * rstride;
 #pragma unroll
-    for (int q = 0; q < Q; q++)
-        if (q * 4 < T * V) {
+    for (int q = 0; q < Q; q++) {
+        bool needed = false;
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+            if (q * 4 + k < L && (q * 4 + k) % (TM * V) < T * V) needed = true;
+        if (needed) {
             float w[4];
 #pragma unroll
-            for (int k = 0; k < 4; k++) w[k] = q * 4 + k < TM * V ? X[q * 4 + k] : 0.f;
+            for (int k = 0; k < 4; k++) w[k] = q * 4 + k < L ? X[q * 4 + k] : 0.f;
             memcpy(dst + q * rstride, w, 16);
         }
+    }
 }
 
 // Which of the thread's V pixels see the image at offset (oh, ow): bit v of the result.
@@ -399,129 +419,152 @@ CHAIN_HD void vm_load_at(const Tensor& e, const Geo& g, const Thread& th, int pl
     }
 }
 
-// Every instruction except OP_XADD.  Pm: this thread's persistent floats, float k of pixel v at Pm[(k * V + v) * pstride];
-// Rm, rstride: its registers (vm_reg_read).
-template <int TM, int V>
-CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, int c, const Thread& th, State<TM, V>& st, float* Pm, int pstride, float* Rm,
-                      int rstride) {
-    auto& A = st.A;
+// What an instruction needs besides its own fields.
+struct Env {
+    int c = 0;        // first channel of the trip; channel u of the thread is c + u
+    int h = 0;        // channels of the trip that exist (0 .. U)
+    bool pro = false; // the prologue of a pass (once per workgroup item, not per channel)
+    int np = 0;       // persistent floats per pixel and channel
+    int pstride = 0;  // floats between consecutive persistent floats of a thread (the workgroup's size)
+    int rstride = 0;  // floats between consecutive register pieces of a thread
+};
+
+// Every instruction except OP_XADD.  Pm: this thread's persistent floats.  A float that lives across the channel loop
+// (softmax statistics, the sums of a softmax's adjoint: written by the prologue and the OP_SMC instructions) exists once,
+// float k of pixel v at Pm[(k * V + v) * pstride]; an accumulator of one channel (OP_PSET in a body, OP_PADD, OP_PLD,
+// OP_XADD) once per channel u of the trip, at Pm[((u * np + k) * V + v) * pstride].  Rm: its registers (vm_reg_read).
+template <int TM, int V, int U>
+CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env& ev, const Thread& th, State<TM, V, U>& st, float* Pm, float* Rm) {
+    float* A = st.A;
     const int T = I.T;
-    float X[TM * V];
+    const int pstride = ev.pstride, rstride = ev.rstride;
+    constexpr int TV = TM * V;
+    float X[U * TV];
     switch (I.op) {
     case OP_LD: {
         CHAIN_CASE;
-        int dh, dw;
-        vm_offset(pg, I.b, c, dh, dw);
         const Tensor e = vm_tensor(pg, g, I.a);
-        const int chan = (th.n * g.C + c) * e.T;  // first plane of (image, channel): uniform
-        if (I.kind & kWin) {
-            const int KH = I.r >> 4, KW = I.r & 15;
 #pragma unroll
-            for (int t = 0; t < TM; t++)
-                if (t < T) {
-                    int oh, ow;
-                    vm_tap(t, KH, KW, oh, ow);
-                    float ld[V];
-                    vm_load_at<V>(e, g, th, chan, dh + oh, dw + ow, ld);
+        for (int u = 0; u < U; u++)
+            if (u < ev.h) {
+                int dh, dw;
+                vm_offset(pg, I.b, ev.c + u, dh, dw);
+                const int chan = (th.n * g.C + ev.c + u) * e.T;  // first plane of (image, channel): uniform
+                if (I.kind & kWin) {
+                    const int KH = I.r >> 4, KW = I.r & 15;
 #pragma unroll
-                    for (int v = 0; v < V; v++) A[t * V + v] = ld[v];
+                    for (int t = 0; t < TM; t++)
+                        if (t < T) {
+                            int oh, ow;
+                            vm_tap(t, KH, KW, oh, ow);
+                            vm_load_at<V>(e, g, th, chan, dh + oh, dw + ow, A + u * TV + t * V);
+                        }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < TM; t++)
+                        if (t < T) {
+                            const int te = (I.kind & kExtTaps) ? (t < e.T ? t : t % e.T) : 0;
+                            vm_load_at<V>(e, g, th, chan + te, dh, dw, A + u * TV + t * V);
+                        }
                 }
-        } else {
-#pragma unroll
-            for (int t = 0; t < TM; t++)
-                if (t < T) {
-                    const int te = (I.kind & kExtTaps) ? (t < e.T ? t : t % e.T) : 0;
-                    float ld[V];
-                    vm_load_at<V>(e, g, th, chan + te, dh, dw, ld);
-#pragma unroll
-                    for (int v = 0; v < V; v++) A[t * V + v] = ld[v];
-                }
-        }
+            }
         break;
     }
     case OP_MASK: {
         CHAIN_CASE;
-        int dh, dw;
-        vm_offset(pg, I.b, c, dh, dw);
-        if (I.kind & kWin) {
-            const int KH = I.r >> 4, KW = I.r & 15;
 #pragma unroll
-            for (int t = 0; t < TM; t++)
-                if (t < T) {
-                    int oh, ow;
-                    vm_tap(t, KH, KW, oh, ow);
-                    const uint32_t m = vm_valid<V>(g, th, dh + oh, dw + ow);
+        for (int u = 0; u < U; u++)
+            if (u < ev.h) {
+                int dh, dw;
+                vm_offset(pg, I.b, ev.c + u, dh, dw);
+                if (I.kind & kWin) {
+                    const int KH = I.r >> 4, KW = I.r & 15;
 #pragma unroll
-                    for (int v = 0; v < V; v++)
-                        if (!((m >> v) & 1u)) A[t * V + v] = 0.f;
+                    for (int t = 0; t < TM; t++)
+                        if (t < T) {
+                            int oh, ow;
+                            vm_tap(t, KH, KW, oh, ow);
+                            const uint32_t m = vm_valid<V>(g, th, dh + oh, dw + ow);
+#pragma unroll
+                            for (int v = 0; v < V; v++)
+                                if (!((m >> v) & 1u)) A[u * TV + t * V + v] = 0.f;
+                        }
+                } else {
+                    const uint32_t m = vm_valid<V>(g, th, dh, dw);
+#pragma unroll
+                    for (int t = 0; t < TM; t++)
+                        if (t < T) {
+#pragma unroll
+                            for (int v = 0; v < V; v++)
+                                if (!((m >> v) & 1u)) A[u * TV + t * V + v] = 0.f;
+                        }
                 }
-        } else {
-            const uint32_t m = vm_valid<V>(g, th, dh, dw);
-            CHAIN_EACH(T, e, if (!((m >> (e % V)) & 1u)) A[e] = 0.f;);
-        }
+            }
         break;
     }
     case OP_UN:
         switch (I.kind) {
-        case 0: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = fmaxf(A[e], 0.f);); break;
-        case 1: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = fabsf(A[e]);); break;
-        case 2: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = vm_gelu(A[e]);); break;
-        case 4: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = sinf(A[e]);); break;
-        case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = -A[e];); break;
-        default: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = expf(fminf(fmaxf(A[e], I.f0), I.f1));); break;
+        case 0: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = fmaxf(A[e], 0.f);); break;
+        case 1: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = fabsf(A[e]);); break;
+        case 2: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = vm_gelu(A[e]);); break;
+        case 4: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = sinf(A[e]);); break;
+        case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = -A[e];); break;
+        default: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = expf(fminf(fmaxf(A[e], I.f0), I.f1));); break;
         }
         break;
     case OP_MOVR:
         CHAIN_CASE;
-        CHAIN_EACH(T, e, X[e] = A[e];);
-        vm_reg_write<TM, V>(Rm, rstride, I.r, T, X);
+        vm_reg_write<TM, V, U>(Rm, rstride, I.r, T, A);
         break;
     case OP_MOVA:
         CHAIN_CASE;
-        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
-        CHAIN_EACH(T, e, A[e] = X[e];);
+        vm_reg_read<TM, V, U>(Rm, rstride, I.r, T, A);
         break;
     case OP_BIN: {
         CHAIN_CASE;
         const int kind = I.kind & 7;
         const bool reg_lhs = I.kind & kBinRegIsLhs, reg_sc = I.kind & kBinRegScalar, acc_sc = I.kind & kBinAccScalar;
-        vm_reg_read<TM, V>(Rm, rstride, I.r, reg_sc ? 1 : T, X);
-        if (TM > 1 && reg_sc) CHAIN_EACH(T, e, X[e] = X[e % V];);
-        if (TM > 1 && acc_sc) CHAIN_EACH(T, e, A[e] = A[e % V];);
+        vm_reg_read<TM, V, U>(Rm, rstride, I.r, reg_sc ? 1 : T, X);
+        if (TM > 1 && reg_sc) CHAIN_EACH(T, e, l, X[e] = X[e - l + l % V];);
+        if (TM > 1 && acc_sc) CHAIN_EACH(T, e, l, A[e] = A[e - l + l % V];);
         // (min and max return the same value whichever side is the LHS; the sides matter for sub only)
         switch (kind) {
-        case 0: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] + A[e];); break;
-        case 1: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] * A[e];); break;
+        case 0: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] + A[e];); break;
+        case 1: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * A[e];); break;
         case 2:
             CHAIN_CASE;
-            if (reg_lhs) CHAIN_EACH(T, e, A[e] = X[e] - A[e];);
-            else CHAIN_EACH(T, e, A[e] = A[e] - X[e];);
+            if (reg_lhs) CHAIN_EACH(T, e, l, A[e] = X[e] - A[e];);
+            else CHAIN_EACH(T, e, l, A[e] = A[e] - X[e];);
             break;
-        case 3: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] <= A[e] ? X[e] : A[e];); break;
-        default: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] >= A[e] ? X[e] : A[e];); break;
+        case 3: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] <= A[e] ? X[e] : A[e];); break;
+        default: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] >= A[e] ? X[e] : A[e];); break;
         }
         break;
     }
     case OP_FOLD: {
         CHAIN_CASE;
-        if (I.kind == 2) {
 #pragma unroll
-            for (int t = 1; t < TM; t++)
-                if (t < T) {
+        for (int u = 0; u < U; u++) {
+            float* Au = A + u * TV;
+            if (I.kind == 2) {
 #pragma unroll
-                    for (int v = 0; v < V; v++) A[v] = A[t * V + v] > A[v] ? A[t * V + v] : A[v];
+                for (int t = 1; t < TM; t++)
+                    if (t < T) {
+#pragma unroll
+                        for (int v = 0; v < V; v++) Au[v] = Au[t * V + v] > Au[v] ? Au[t * V + v] : Au[v];
+                    }
+            } else {
+#pragma unroll
+                for (int t = 1; t < TM; t++)
+                    if (t < T) {
+#pragma unroll
+                        for (int v = 0; v < V; v++) Au[v] += Au[t * V + v];
+                    }
+                if (I.kind == 1) {
+                    const float inv = (float)T;
+#pragma unroll
+                    for (int v = 0; v < V; v++) Au[v] /= inv;
                 }
-        } else {
-#pragma unroll
-            for (int t = 1; t < TM; t++)
-                if (t < T) {
-#pragma unroll
-                    for (int v = 0; v < V; v++) A[v] += A[t * V + v];
-                }
-            if (I.kind == 1) {
-                const float inv = (float)T;
-#pragma unroll
-                for (int v = 0; v < V; v++) A[v] /= inv;
             }
         }
         break;
@@ -529,21 +572,25 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, int c, co
     case OP_SMT: {
         CHAIN_CASE;
 #pragma unroll
-        for (int v = 0; v < V; v++) {
-            float m = A[v];
+        for (int u = 0; u < U; u++) {
+            float* Au = A + u * TV;
 #pragma unroll
-            for (int t = 1; t < TM; t++)
-                if (t < T) m = fmaxf(m, A[t * V + v]);
-            float z = 0.f;
+            for (int v = 0; v < V; v++) {
+                float m = Au[v];
 #pragma unroll
-            for (int t = 0; t < TM; t++)
-                if (t < T) {
-                    A[t * V + v] = expf(A[t * V + v] - m);
-                    z += A[t * V + v];
-                }
+                for (int t = 1; t < TM; t++)
+                    if (t < T) m = fmaxf(m, Au[t * V + v]);
+                float z = 0.f;
 #pragma unroll
-            for (int t = 0; t < TM; t++)
-                if (t < T) A[t * V + v] = A[t * V + v] / z;
+                for (int t = 0; t < TM; t++)
+                    if (t < T) {
+                        Au[t * V + v] = expf(Au[t * V + v] - m);
+                        z += Au[t * V + v];
+                    }
+#pragma unroll
+                for (int t = 0; t < TM; t++)
+                    if (t < T) Au[t * V + v] = Au[t * V + v] / z;
+            }
         }
         break;
     }
@@ -551,172 +598,212 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, int c, co
         CHAIN_CASE;
         if (!th.own) break;
         const Tensor e = vm_tensor(pg, g, I.a);
-        const int chan = (th.n * g.C + c) * e.T;
 #pragma unroll
-        for (int t = 0; t < TM; t++)
-            if (t < T) {
-                float sv[V];
+        for (int u = 0; u < U; u++)
+            if (u < ev.h) {
+                const int chan = (th.n * g.C + ev.c + u) * e.T;
 #pragma unroll
-                for (int v = 0; v < V; v++) sv[v] = A[t * V + v];
-                vm_store<V>(e, (chan + t) * g.HW + th.p0, sv, (I.kind & kStAdd) != 0);
+                for (int t = 0; t < TM; t++)
+                    if (t < T) vm_store<V>(e, (chan + t) * g.HW + th.p0, A + u * TV + t * V, (I.kind & kStAdd) != 0);
             }
         break;
     }
     case OP_UNBX:
         CHAIN_CASE;
-        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
+        vm_reg_read<TM, V, U>(Rm, rstride, I.r, T, X);
         switch (I.kind) {
-        case 0: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = A[e] > 0.f ? X[e] : 0.f;); break;
-        case 1: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] * vm_sign(A[e]);); break;
-        case 2: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] * vm_gelu_grad(A[e]);); break;
-        case 4: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = X[e] * cosf(A[e]);); break;
-        case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = -X[e];); break;
-        default: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = (A[e] > I.f0 && A[e] < I.f1) ? X[e] * expf(A[e]) : 0.f;); break;
+        case 0: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = A[e] > 0.f ? X[e] : 0.f;); break;
+        case 1: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * vm_sign(A[e]);); break;
+        case 2: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * vm_gelu_grad(A[e]);); break;
+        case 4: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * cosf(A[e]);); break;
+        case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = -X[e];); break;
+        default: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = (A[e] > I.f0 && A[e] < I.f1) ? X[e] * expf(A[e]) : 0.f;); break;
         }
         break;
     case OP_BING: {
         CHAIN_CASE;
         const int kind = I.kind & 7;
         const bool rhs_side = I.kind & kBingRhsSide, l_sc = I.kind & kBingLhsScalar, r_sc = I.kind & kBingRhsScalar;
-        vm_reg_read<TM, V>(Rm, rstride, I.r, l_sc ? 1 : T, X);
-        if (TM > 1 && l_sc) CHAIN_EACH(T, e, X[e] = X[e % V];);
-        if (TM > 1 && r_sc) CHAIN_EACH(T, e, A[e] = A[e % V];);
+        vm_reg_read<TM, V, U>(Rm, rstride, I.r, l_sc ? 1 : T, X);
+        if (TM > 1 && l_sc) CHAIN_EACH(T, e, l, X[e] = X[e - l + l % V];);
+        if (TM > 1 && r_sc) CHAIN_EACH(T, e, l, A[e] = A[e - l + l % V];);
         // X: the LHS value, A: the RHS value; the result is d blend / d side (a tie of min / max belongs to the LHS)
         switch (kind) {
-        case 0: CHAIN_CASE; CHAIN_EACH(T, e, A[e] = 1.f;); break;
+        case 0: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = 1.f;); break;
         case 1:
             CHAIN_CASE;
             if (!rhs_side) break;  // d (l * r) / d l = r, which A holds
-            CHAIN_EACH(T, e, A[e] = X[e];);
+            CHAIN_EACH(T, e, l, A[e] = X[e];);
             break;
         case 2:
             CHAIN_CASE;
-            if (rhs_side) CHAIN_EACH(T, e, A[e] = -1.f;);
-            else CHAIN_EACH(T, e, A[e] = 1.f;);
+            if (rhs_side) CHAIN_EACH(T, e, l, A[e] = -1.f;);
+            else CHAIN_EACH(T, e, l, A[e] = 1.f;);
             break;
         case 3:
             CHAIN_CASE;
-            if (rhs_side) CHAIN_EACH(T, e, A[e] = X[e] <= A[e] ? 0.f : 1.f;);
-            else CHAIN_EACH(T, e, A[e] = X[e] <= A[e] ? 1.f : 0.f;);
+            if (rhs_side) CHAIN_EACH(T, e, l, A[e] = X[e] <= A[e] ? 0.f : 1.f;);
+            else CHAIN_EACH(T, e, l, A[e] = X[e] <= A[e] ? 1.f : 0.f;);
             break;
         default:
             CHAIN_CASE;
-            if (rhs_side) CHAIN_EACH(T, e, A[e] = X[e] >= A[e] ? 0.f : 1.f;);
-            else CHAIN_EACH(T, e, A[e] = X[e] >= A[e] ? 1.f : 0.f;);
+            if (rhs_side) CHAIN_EACH(T, e, l, A[e] = X[e] >= A[e] ? 0.f : 1.f;);
+            else CHAIN_EACH(T, e, l, A[e] = X[e] >= A[e] ? 1.f : 0.f;);
             break;
         }
         break;
     }
     case OP_SMTBX:
         CHAIN_CASE;
-        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
+        vm_reg_read<TM, V, U>(Rm, rstride, I.r, T, X);
 #pragma unroll
-        for (int v = 0; v < V; v++) {
-            float dot = 0.f;
+        for (int u = 0; u < U; u++) {
+            float* Au = A + u * TV;
+            const float* Xu = X + u * TV;
 #pragma unroll
-            for (int t = 0; t < TM; t++)
-                if (t < T) dot += X[t * V + v] * A[t * V + v];
+            for (int v = 0; v < V; v++) {
+                float dot = 0.f;
 #pragma unroll
-            for (int t = 0; t < TM; t++)
-                if (t < T) A[t * V + v] = A[t * V + v] * (X[t * V + v] - dot);
+                for (int t = 0; t < TM; t++)
+                    if (t < T) dot += Xu[t * V + v] * Au[t * V + v];
+#pragma unroll
+                for (int t = 0; t < TM; t++)
+                    if (t < T) Au[t * V + v] = Au[t * V + v] * (Xu[t * V + v] - dot);
+            }
         }
         break;
     case OP_FOLDBX:
         CHAIN_CASE;
-        vm_reg_read<TM, V>(Rm, rstride, I.r, 1, X);
+        vm_reg_read<TM, V, U>(Rm, rstride, I.r, 1, X);
         if (I.kind == 2) {
 #pragma unroll
-            for (int v = 0; v < V; v++) {
-                const float gr = X[v];
-                int best = 0;
-                float m = A[v];
+            for (int u = 0; u < U; u++) {
+                float* Au = A + u * TV;
 #pragma unroll
-                for (int t = 1; t < TM; t++)
-                    if (t < T && A[t * V + v] > m) {
-                        m = A[t * V + v];
-                        best = t;
-                    }
+                for (int v = 0; v < V; v++) {
+                    const float gr = X[u * TV + v];
+                    int best = 0;
+                    float m = Au[v];
 #pragma unroll
-                for (int t = 0; t < TM; t++)
-                    if (t < T) A[t * V + v] = t == best ? gr : 0.f;
+                    for (int t = 1; t < TM; t++)
+                        if (t < T && Au[t * V + v] > m) {
+                            m = Au[t * V + v];
+                            best = t;
+                        }
+#pragma unroll
+                    for (int t = 0; t < TM; t++)
+                        if (t < T) Au[t * V + v] = t == best ? gr : 0.f;
+                }
             }
         } else {
             if (I.kind == 1) {
 #pragma unroll
-                for (int v = 0; v < V; v++) X[v] = X[v] / (float)T;
+                for (int u = 0; u < U; u++)
+#pragma unroll
+                    for (int v = 0; v < V; v++) X[u * TV + v] = X[u * TV + v] / (float)T;
             }
-            CHAIN_EACH(T, e, A[e] = X[e % V];);
+            CHAIN_EACH(T, e, l, A[e] = X[e - l + l % V];);
         }
         break;
     case OP_PSET:
         CHAIN_CASE;
-        CHAIN_EACH(T, e, Pm[(I.a * V + e) * pstride] = I.f0;);
+        if (ev.pro) {
+#pragma unroll
+            for (int t = 0; t < TM; t++)
+                if (t < T) {
+#pragma unroll
+                    for (int v = 0; v < V; v++) Pm[((I.a + t) * V + v) * pstride] = I.f0;
+                }
+        } else {
+            CHAIN_EACH(T, e, l, Pm[(((e - l) / TV * ev.np + I.a) * V + l) * pstride] = I.f0;);
+        }
         break;
     case OP_PADD: {
         CHAIN_CASE;
         const int Tb = I.b;
 #pragma unroll
-        for (int t = 0; t < TM; t++)
-            if (t < T) {
-                const int tp = t < Tb ? t : t % Tb;
+        for (int u = 0; u < U; u++)
 #pragma unroll
-                for (int v = 0; v < V; v++) Pm[((I.a + tp) * V + v) * pstride] += A[t * V + v];
-            }
+            for (int t = 0; t < TM; t++)
+                if (t < T) {
+                    const int tp = t < Tb ? t : t % Tb;
+#pragma unroll
+                    for (int v = 0; v < V; v++) Pm[((u * ev.np + I.a + tp) * V + v) * pstride] += A[u * TV + t * V + v];
+                }
         break;
     }
     case OP_PLD:
         CHAIN_CASE;
-        CHAIN_EACH(T, e, A[e] = Pm[(I.a * V + e) * pstride];);
+        CHAIN_EACH(T, e, l, A[e] = Pm[(((e - l) / TV * ev.np + I.a) * V + l) * pstride];);
         break;
     case OP_SMCSTAT:
         CHAIN_CASE;
-        CHAIN_EACH(T, e, {
-            float& m = Pm[(I.a * V + e) * pstride];
-            float& z = Pm[((I.a + T) * V + e) * pstride];
-            const float val = A[e];
-            if (val > m) {
-                z = z * expf(m - val) + 1.f;  // (m = -inf at the first channel: z = 0 * 0 + 1)
-                m = val;
-            } else {
-                z += expf(val - m);
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            if (u < ev.h) {
+#pragma unroll
+                for (int t = 0; t < TM; t++)
+                    if (t < T) {
+#pragma unroll
+                        for (int v = 0; v < V; v++) {
+                            float& m = Pm[((I.a + t) * V + v) * pstride];
+                            float& z = Pm[((I.a + T + t) * V + v) * pstride];
+                            const float val = A[u * TV + t * V + v];
+                            if (val > m) {
+                                z = z * expf(m - val) + 1.f;  // (m = -inf at the first channel: z = 0 * 0 + 1)
+                                m = val;
+                            } else {
+                                z += expf(val - m);
+                            }
+                        }
+                    }
             }
-        });
         break;
     case OP_SMCAPPLY:
         CHAIN_CASE;
-        CHAIN_EACH(T, e, A[e] = expf(A[e] - Pm[(I.a * V + e) * pstride]) / Pm[((I.a + T) * V + e) * pstride];);
+        CHAIN_EACH(T, e, l, A[e] = expf(A[e] - Pm[(I.a * V + l) * pstride]) / Pm[((I.a + T) * V + l) * pstride];);
         break;
     case OP_SMCDOT:
         CHAIN_CASE;
-        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
-        CHAIN_EACH(T, e, Pm[(I.a * V + e) * pstride] += A[e] * X[e];);
+        vm_reg_read<TM, V, U>(Rm, rstride, I.r, T, X);
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            if (u < ev.h) {
+#pragma unroll
+                for (int t = 0; t < TM; t++)
+                    if (t < T) {
+#pragma unroll
+                        for (int v = 0; v < V; v++) Pm[((I.a + t) * V + v) * pstride] += A[u * TV + t * V + v] * X[u * TV + t * V + v];
+                    }
+            }
         break;
     case OP_SMCBX:
         CHAIN_CASE;
-        vm_reg_read<TM, V>(Rm, rstride, I.r, T, X);
-        CHAIN_EACH(T, e, A[e] = A[e] * (X[e] - Pm[(I.a * V + e) * pstride]););
+        vm_reg_read<TM, V, U>(Rm, rstride, I.r, T, X);
+        CHAIN_EACH(T, e, l, A[e] = A[e] * (X[e] - Pm[(I.a * V + l) * pstride]););
         break;
     default: break;
     }
 }
 
-// OP_XADD, first half: the thread's lanes go to the hand-over buffer of its slice (lane t of local pixel q at
-// buf[t * npx + q]).
-template <int TM, int V, class AT>
-CHAIN_HD void vm_xadd_write(const Geo& g, const Instr& I, const Thread& th, const AT& A, float* buf) {
+// OP_XADD of channel u, first half: the thread's lanes go to the hand-over buffer of its slice (lane t of local pixel q
+// at buf[t * npx + q]).
+template <int TM, int V>
+CHAIN_HD void vm_xadd_write(const Geo& g, const Instr& I, const Thread& th, const float* Au, float* buf) {
 #pragma unroll
     for (int t = 0; t < TM; t++)
         if (t < I.T) {
 #pragma unroll
-            for (int v = 0; v < V; v++) buf[t * g.npx + th.ptid * V + v] = A[t * V + v];
+            for (int v = 0; v < V; v++) buf[t * g.npx + th.ptid * V + v] = Au[t * V + v];
         }
 }
 
-// OP_XADD, second half (after a barrier): P[a (+ t)] of every pixel of the thread collects lane t of the pixel whose
-// load at offset (dh, dw) [+ window tap t] read it, if that pixel is inside the image and inside the pixels the slice
-// computes (the planner sizes the halo so that an owned pixel never misses one).  Fixed order: deterministic.
+// OP_XADD of channel u, second half (after a barrier): P[a (+ t)] of every pixel of the thread collects lane t of the
+// pixel whose load at offset (dh, dw) [+ window tap t] read it, if that pixel is inside the image and inside the pixels
+// the slice computes (the planner sizes the halo so that an owned pixel never misses one).  Fixed order: deterministic.
+// Pu: the persistent floats of this thread and channel.
 template <int TM, int V>
-CHAIN_HD void vm_xadd_gather(const Geo& g, const Instr& I, int dh, int dw, const Thread& th, const float* buf, float* Pm, int pstride) {
+CHAIN_HD void vm_xadd_gather(const Geo& g, const Instr& I, int dh, int dw, const Thread& th, const float* buf, float* Pu, int pstride) {
 #pragma unroll
     for (int t = 0; t < TM; t++)
         if (t < I.T) {
@@ -733,7 +820,7 @@ CHAIN_HD void vm_xadd_gather(const Geo& g, const Instr& I, int dh, int dw, const
 #pragma unroll
             for (int v = 0; v < V; v++) {
                 const int src = th.ptid * V + v - (oh * g.W + ow);
-                if (((m >> v) & 1u) && src >= 0 && src < g.npx) Pm[(slot * V + v) * pstride] += buf[t * g.npx + src];
+                if (((m >> v) & 1u) && src >= 0 && src < g.npx) Pu[(slot * V + v) * pstride] += buf[t * g.npx + src];
             }
         }
 }

@@ -198,6 +198,45 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16, bool fuse_ch
             unit_of[k] = (int)units.size() - 1;
         }
     }
+    // Full recomputation makes a long chain dearer than its parts (every unary's adjoint evaluates its operand again,
+    // every softmax over channels adds passes).  A grown chain is therefore cut in two, at the place that pays most,
+    // while the halves together cost less than four fifths of the whole, and the halves are looked at again.  A cut
+    // materialises what crosses it: across a tensor with taps (an unfolded tensor, which a chain otherwise never
+    // writes) it is only made when the halves cost less than two fifths of the whole, which in practice means a
+    // softmax over channels of an unfolded tensor, whose passes each recompute the whole window.
+    for (size_t u = 0; u < units.size(); u++) {
+        if (!units[u].chain || units[u].nodes.size() < 2) continue;
+        std::string why;
+        chain::UnitPlan whole;
+        if (!chain::compile_unit(dag, units[u].nodes, outputs_of(units[u].nodes), whole, why)) continue;
+        const std::vector<int> nodes = units[u].nodes;
+        double best = whole.cost;
+        size_t cut = 0;
+        for (size_t i = 1; i < nodes.size(); i++) {
+            const std::vector<int> A(nodes.begin(), nodes.begin() + i), Bn(nodes.begin() + i, nodes.end());
+            bool taps = false;
+            for (int k : Bn)
+                for (int o : {dag.nodes[k].a, dag.nodes[k].b})
+                    if (o > 0 && std::find(A.begin(), A.end(), o) != A.end() && dag.nodes[o].T != 1) taps = true;
+            chain::UnitPlan pa, pb;
+            if (!chain::compile_unit(dag, A, outputs_of(A), pa, why) || !chain::compile_unit(dag, Bn, outputs_of(Bn), pb, why)) continue;
+            const double apart = (pa.cost + pb.cost) / (taps ? 0.4 : 0.8);  // (as if the whole had to be that much dearer)
+            if (apart < best) {
+                best = apart;
+                cut = i;
+            }
+        }
+        if (cut == 0) continue;
+        if (log) std::fprintf(stderr, "canvas: chain %zu cut after %zu of %zu nodes: weighted cost %.0f apart, %.0f whole\n", u, cut, nodes.size(), best, whole.cost);
+        Unit B;
+        B.chain = true;
+        B.nodes.assign(nodes.begin() + cut, nodes.end());
+        units[u].nodes.assign(nodes.begin(), nodes.begin() + cut);
+        units.insert(units.begin() + u + 1, B);
+        for (size_t v = 0; v < units.size(); v++)
+            for (int k : units[v].nodes) unit_of[k] = (int)v;
+        u--;  // (the first half again, then the second)
+    }
     // a unit was last compiled when it last grew, against the consumers known then; later nodes may have joined
     // other units, which never removes an output, but a later joiner of THIS unit may have: compile the final sets
     for (Unit& U : units)

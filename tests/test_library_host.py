@@ -130,8 +130,11 @@ def test_chain_boundaries(lib):
     assert plan("%1 = unary %0 op=relu\n%2 = unfold %1 kh=3 kw=3\n%3 = softmax %2 axis=T\n%4 = binary %3 %2 op=mul\n"
                 "%5 = unary %4 op=gelu\n%6 = fold %5 op=sum\noutput %6\n") == (1, 6, ["chain_fwd"])
     # a softmax over channels inside a chain (statistics in a pass of their own), stencils above element-wise work
+    assert plan("%1 = shift %0 dh=0 dw=2 c0=0 c1=96\n%2 = unary %1 op=relu\n%3 = softmax %2 axis=C\noutput %3\n") == (1, 3, ["chain_fwd"])
+    # ... but every pass of that softmax computes what precedes it again: behind a dear prefix (two transcendental
+    # functions per element here) the chain is cut where the halves together are cheaper than the whole
     assert plan("%1 = shift %0 dh=0 dw=2 c0=0 c1=96\n%2 = unary %1 op=expclip lo=-4 hi=4\n%3 = binary %0 %2 op=add\n"
-                "%4 = shift %3 dh=-2 dw=0 c0=0 c1=48\n%5 = softmax %4 axis=C\noutput %5\n") == (1, 5, ["chain_fwd"])
+                "%4 = shift %3 dh=-2 dw=0 c0=0 c1=48\n%5 = softmax %4 axis=C\noutput %5\n") == (2, 5, ["chain_fwd", "chain_fwd"])
     # an unfold of a folded (reduced) tensor starts a new chain: the reduction would be needed at other pixels
     assert plan("%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=sum\n%3 = unfold %2 kh=5 kw=5\n%4 = binary %2 %3 op=mul\n"
                 "%5 = fold %4 op=avg\noutput %5\n") == (2, 5, ["chain_fwd", "chain_fwd"])
