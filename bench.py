@@ -2,6 +2,8 @@
 of its dominant kernel and the CPU oracle timed beside it.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload shift_residual|involution|sampled_cC_hH]
+    python bench.py --workload chain_gate|chain_relu|chain_shift_residual|chain_box3|chain_softmax_c[_cC_hH]
+                                                       (an FC-free fused chain at a ResNet layer shape, N=128, vs the HBM roof)
     python bench.py --workload fuzz [--seeds 100:300]  (config 5: geometric mean over the random DAGs, chain kernels vs HBM)
     python bench.py --fc-micro                         (grouped-FC kernels of config 4, operands in cache, vs MFMA peak)
     python bench.py --infer BATCH [--workload ...]     (forward-only latency of the inference plan, not the headline)
@@ -27,27 +29,42 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-# HBM bytes per launch from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then WRITE_SIZE, KiB per
-# dispatch; a plain 25 088 KiB copy reads FETCH_SIZE 12 554 -> factor 1.998, WRITE_SIZE 25 088 -> factor 1.0).
-# Valid only for the kernel sources they were taken on (hash below), otherwise `traffic` is null.
-TRAFFIC_SOURCES = ["paper_2304_07741_amd/csrc/sgfc_kernels.hip", "paper_2304_07741_amd/csrc/tile_util.hpp",
-                   "paper_2304_07741_amd/csrc/lower_sgfc.cpp"]
-TRAFFIC_SHA256 = "85f5cd49ad9d645defc73f2211fa19ebaec35cf5cf1d1246f1b1c66b132d7640"
-TRAFFIC_KIB = {("shift_residual", "sgfc_bwd"): (26403.5 * 1.998, 25900.3), ("shift_residual", "sgfc_fwd"): (14405.3 * 1.998, 25089.0)}
+# HBM bytes per launch from two `rocprofv3 --pmc` runs of this file per workload (FETCH_SIZE, then WRITE_SIZE, averages
+# per dispatch; the runtime's plain copy of 25 088 KiB reads FETCH_SIZE 12 557 -> units of 1.998 KiB, and WRITE_SIZE
+# 25 088 -> KiB; commands and tables in profiles/).  A set of figures is valid only for the kernel sources it was taken
+# on (hash below), otherwise `traffic` is null; a kernel instance that runs both the forward and the backward program
+# of a workload has one average for the two and is left out.
+_SGFC_SOURCES = ['paper_2304_07741_amd/csrc/sgfc_kernels.hip', 'paper_2304_07741_amd/csrc/tile_util.hpp', 'paper_2304_07741_amd/csrc/lower_sgfc.cpp']
+_CHAIN_SOURCES = ['paper_2304_07741_amd/csrc/chain_kernels.hip', 'paper_2304_07741_amd/csrc/chain_vm.hpp', 'paper_2304_07741_amd/csrc/chain_isa.hpp', 'paper_2304_07741_amd/csrc/chain_plan.cpp', 'paper_2304_07741_amd/csrc/chain_kernels.hpp', 'paper_2304_07741_amd/csrc/tile_util.hpp']
+TRAFFIC = {
+    "shift_residual": {"sources": _SGFC_SOURCES, "sha256": "fe8f2974588d17783936b636e312ae4f4cb6d53379a506182549f977b5faee74",
+                       "kib": {"sgfc_fwd": (14410.8 * 1.998, 25089.9), "sgfc_bwd": (26402.4 * 1.998, 25898.1)}},
+    "chain_gate": {"sources": _CHAIN_SOURCES, "sha256": "47489a2135be27722312a623bceb5a73333905647120c688b68db889eaa67a4b",
+                   "kib": {"chain_fwd": (25774.9 * 1.998, 50176.0), "chain_bwd": (55192.2 * 1.998, 50178.9)}},
+    "chain_shift_residual": {"sources": _CHAIN_SOURCES, "sha256": "47489a2135be27722312a623bceb5a73333905647120c688b68db889eaa67a4b",
+                             "kib": {"chain_fwd": (25863.5 * 1.998, 50176.0), "chain_bwd": (54357.5 * 1.998, 50176.0)}},
+}
 
 
-def measured_traffic(workload, kernel):
+def traffic_hash(sources):
     import hashlib
 
     h = hashlib.sha256()
+    for f in sources:
+        h.update(open(os.path.join(ROOT, f), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload, kernel):
+    t = TRAFFIC.get(workload)
+    if t is None or kernel not in t["kib"]:
+        return None
     try:
-        for f in TRAFFIC_SOURCES:
-            h.update(open(os.path.join(ROOT, f), "rb").read())
+        if traffic_hash(t["sources"]) != t["sha256"]:
+            return None
     except OSError:
         return None
-    if h.hexdigest() != TRAFFIC_SHA256 or (workload, kernel) not in TRAFFIC_KIB:
-        return None
-    fetch, write = TRAFFIC_KIB[(workload, kernel)]
+    fetch, write = t["kib"][kernel]
     return (fetch + write) * 1024.0
 
 
@@ -62,6 +79,16 @@ def make_case(name, batch=None):
     if name.startswith("sampled_c"):
         c, h = name[len("sampled_c"):].split("_h")
         return wl.config4(int(c), int(h), **kw)
+    if name.startswith("chain_"):  # chain_<body>[_cC_hH]: an FC-free chain of memory-bound primitives
+        import re
+
+        body, c, h = name[len("chain_"):], 64, 56
+        m = re.fullmatch(r"(.*)_c(\d+)_h(\d+)", body)
+        if m:
+            body, c, h = m.group(1), int(m.group(2)), int(m.group(3))
+        if body not in wl.CHAIN_BODIES:
+            raise SystemExit(f"unknown chain {body}: one of {sorted(wl.CHAIN_BODIES)}")
+        return wl.chain(body, C=c, H=h, **kw)
     raise SystemExit(f"unknown workload {name}")
 
 

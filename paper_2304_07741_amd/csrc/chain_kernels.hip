@@ -53,6 +53,7 @@ __global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program) {
     for (int e = 0; e < U * TM * V; e++) st.A[e] = 0.f;
     Env ev;
     ev.np = vm_u(pg.n_persist);
+    ev.fast = vm_u(pg.fast_math) != 0;
     ev.pstride = threads;
     ev.rstride = rstride;
     // The workgroup stays and walks over its share of the work items (image, tile, channel range): the program is staged

@@ -805,7 +805,11 @@ double program_cost(const Program& pg) {
             }
             sum += w * I.T;
         }
-    return sum * (double)pg.pix_threads / std::max(1, pg.own_threads + (pg.halo_threads > 0 ? 0 : pg.pix_threads - pg.own_threads));
+    // pixels computed per pixel owned (the halo), and the serial walk over the channels where the workgroup's shape leaves
+    // a thread more than 16 trips (a program that keeps all channels in one workgroup and has no LDS left for slices)
+    const double halo = (double)pg.pix_threads / std::max(1, pg.own_threads + (pg.halo_threads > 0 ? 0 : pg.pix_threads - pg.own_threads));
+    const double trips = std::ceil((double)pg.chunk / std::max(1, pg.slices * pg.unroll));
+    return sum * halo * std::max(1.0, trips / 16.0);
 }
 
 std::string dump(const Program& pg) {

@@ -43,7 +43,8 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
 
 // Estimated work of a program per pixel and channel of the unit, in units of one cheap lane operation: a lane of a
 // tensor access counts 4, of a gradient hand-over 6, of a transcendental function 6; the whole is scaled by the pixels a
-// workgroup computes per pixel it owns (the halo of backward programs).  The lowering lets a node join a chain only
+// workgroup computes per pixel it owns (the halo of backward programs) and by the length of a thread's serial walk over
+// the channels beyond 16 trips.  The lowering lets a node join a chain only
 // while the grown chain is not much dearer than the two chains apart.
 double program_cost(const Program& pg);
 

@@ -296,6 +296,28 @@ inline void vm_store(const Tensor& e, int elem, const float* in, bool add) {
 CHAIN_HD float vm_gelu(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
 CHAIN_HD float vm_gelu_grad(float x) { return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.39894228040143268f * expf(-0.5f * x * x); }
 CHAIN_HD float vm_sign(float x) { return x > 0.f ? 1.f : (x < 0.f ? -1.f : 0.f); }
+// Normal CDF and density for programs of bf16 DAGs (Program::fast_math): erfc by the rational-times-Gaussian
+// approximation of Abramowitz and Stegun, formula 7.1.26 (absolute error of erf below 1.5e-7, five orders below the
+// tolerance of a bf16 DAG); the Gaussian is shared with the density, so gelu or its derivative costs one exponential
+// and one division.  fp32 DAGs keep erff.
+CHAIN_HD void vm_normal_parts(float z, float& cdf, float& pdf) {
+    const float t = 1.f / (1.f + 0.3275911f * 0.70710678f * fabsf(z));
+    const float e = expf(-0.5f * z * z);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float tail = 0.5f * poly * e;  // 0.5 * erfc(|z| / sqrt 2)
+    cdf = z >= 0.f ? 1.f - tail : tail;
+    pdf = 0.39894228f * e;
+}
+CHAIN_HD float vm_gelu_fast(float x) {
+    float cdf, pdf;
+    vm_normal_parts(x, cdf, pdf);
+    return x * cdf;
+}
+CHAIN_HD float vm_gelu_grad_fast(float x) {
+    float cdf, pdf;
+    vm_normal_parts(x, cdf, pdf);
+    return cdf + x * pdf;
+}
 
 // Sum of the offsets of a position for channel c: terms [b >> 8, (b >> 8) + (b & 255)) that cover c.
 CHAIN_HD void vm_offset(const Program& pg, uint16_t b, int c, int& dh, int& dw) {
@@ -424,6 +446,7 @@ struct Env {
     int c = 0;        // first channel of the trip; channel u of the thread is c + u
     int h = 0;        // channels of the trip that exist (0 .. U)
     bool pro = false; // the prologue of a pass (once per workgroup item, not per channel)
+    bool fast = false; // Program::fast_math
     int np = 0;       // persistent floats per pixel and channel
     int pstride = 0;  // floats between consecutive persistent floats of a thread (the workgroup's size)
     int rstride = 0;  // floats between consecutive register pieces of a thread
@@ -506,7 +529,11 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env
         switch (I.kind) {
         case 0: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = fmaxf(A[e], 0.f);); break;
         case 1: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = fabsf(A[e]);); break;
-        case 2: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = vm_gelu(A[e]);); break;
+        case 2:
+            CHAIN_CASE;
+            if (ev.fast) CHAIN_EACH(T, e, l, A[e] = vm_gelu_fast(A[e]););
+            else CHAIN_EACH(T, e, l, A[e] = vm_gelu(A[e]););
+            break;
         case 4: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = sinf(A[e]);); break;
         case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = -A[e];); break;
         default: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = expf(fminf(fmaxf(A[e], I.f0), I.f1));); break;
@@ -614,7 +641,11 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env
         switch (I.kind) {
         case 0: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = A[e] > 0.f ? X[e] : 0.f;); break;
         case 1: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * vm_sign(A[e]);); break;
-        case 2: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * vm_gelu_grad(A[e]);); break;
+        case 2:
+            CHAIN_CASE;
+            if (ev.fast) CHAIN_EACH(T, e, l, A[e] = X[e] * vm_gelu_grad_fast(A[e]););
+            else CHAIN_EACH(T, e, l, A[e] = X[e] * vm_gelu_grad(A[e]););
+            break;
         case 4: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * cosf(A[e]);); break;
         case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = -X[e];); break;
         default: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = (A[e] > I.f0 && A[e] < I.f1) ? X[e] * expf(A[e]) : 0.f;); break;

@@ -62,6 +62,7 @@ struct Binding {
 
 void run_program(const chain::Program& pg0, const std::vector<Binding>& bind, bool bf16, const RunArgs& a) {
     chain::Program pg = pg0;
+    pg.fast_math = bf16 ? 1 : 0;
     for (size_t i = 0; i < bind.size(); i++) {
         const Binding& b = bind[i];
         switch (b.where) {

@@ -159,6 +159,22 @@ def config4(C, H, N=128):
 FUZZ_FC_LIMIT = 96 * 25 * 192  # largest (K * C_out) a random FC may have
 
 
+# FC-free chains of memory-bound primitives at ResNet layer shapes: what the fused-chain kernels are measured on against
+# the HBM roof (the gate of config 4 without its two FCs; a shifted residual; an unfold folded again; a channel softmax).
+CHAIN_BODIES = {
+    "gate": "%1 = unary %0 op=gelu\n%2 = shift %1 dh=0 dw=1 c0={half} c1={C}\n%3 = binary %0 %2 op=mul\noutput %3\n",
+    "relu": "%1 = unary %0 op=relu\noutput %1\n",
+    "shift_residual": "%1 = shift %0 dh=1 dw=0 c0=0 c1={half}\n%2 = shift %1 dh=0 dw=-1 c0={half} c1={C}\n%3 = unary %2 op=relu\n"
+                      "%4 = binary %0 %3 op=add\noutput %4\n",
+    "box3": "%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=avg\noutput %2\n",
+    "softmax_c": "%1 = softmax %0 axis=C\noutput %1\n",
+}
+
+
+def chain(name, N=128, C=64, H=56, dtype="bf16"):
+    return _case(f"chain_{name}", HEADER + CHAIN_BODIES[name].format(C=C, half=C // 2), (N, C, H, H), dtype, 6, [], [])
+
+
 def _bcast_ok(CL, TL, CR, TR):
     if CL == CR:
         return TR % TL == 0

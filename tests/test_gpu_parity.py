@@ -371,6 +371,27 @@ def test_config5_fuzz(harness, oracle, block):
             r.close()
 
 
+# FC-free chains (one fused kernel each way) at the shapes bench.py times them on, and at planes that leave a ragged
+# tail for every vector width the kernels have (7x7: one pixel per thread and 16 channels side by side; 14x14: four
+# pixels; 13x11: odd sizes; 28x28 and 56x56: sixteen pixels, a vector may straddle two image rows), both dtypes
+CHAIN_SHAPES = [(128, 64, 56), (8, 128, 28), (4, 256, 14), (5, 40, 7), (3, 24, 13), (2, 6, 20)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,C,H", CHAIN_SHAPES)
+@pytest.mark.parametrize("body", sorted(wl.CHAIN_BODIES))
+def test_fused_chain_workloads(harness, oracle, body, N, C, H, dtype):
+    if dtype == "f32" and N > 8:
+        pytest.skip("the full batch is checked in bf16, the dtype it is timed in")
+    case = wl.chain(body, N=N, C=C, H=H, dtype=dtype)
+    res, r, dy = harness.run_case(case)
+    try:
+        assert r.info.n_fused_chains == 1 and r.info.n_launches_fwd == 1 and r.info.n_launches_bwd == 1
+        check_against_oracle(oracle, case, res, dy, what=f"{case['name']} {case['shape']} {dtype}")
+    finally:
+        r.close()
+
+
 DETERMINISM_CASES = [lambda: wl.config4(64, 14, N=4), lambda: wl.config4(64, 56, N=2), lambda: wl.config4(128, 28, N=3),
                      lambda: wl.config4(512, 7, N=8), lambda: wl.config3(N=2, H=28), lambda: wl.config2(N=2, H=56)]
 
