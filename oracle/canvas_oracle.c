@@ -55,7 +55,9 @@
  *                                       other folds and binary accept; as the LHS of a binary it is
  *                                       replicated along its folded dims onto an RHS that has them; axis=C groups=G folds the
  *                                       C/G channels of each of G groups: the result has G channels)
- *     %7 = softmax %6 axis=C           (C | T | CT: over channels, over taps, or over both jointly)
+ *     %7 = softmax %6 axis=C           (C | T | CT: over channels, over taps, or over both jointly; H | W | HW: over one
+ *                                       spatial dim or over both jointly, of every (channel, tap) plane: the table of
+ *                                       primitives allows Softmax at any continuous dims)
  *     %9 = binary %a %b op=mul lhs=pixels   (a pooled LHS [H*W, 1, 1, 1] whose channels are laid over the
  *                                       pixels of a full-size RHS: out(c,t,h,w) = op(LHS(h*W+w), RHS(c,t,h,w));
  *                                       Section 8's kernel that pools to [C], maps to H x W with an FC and
@@ -84,7 +86,7 @@
 enum { OP_INPUT = 0, OP_UNFOLD, OP_SHIFT, OP_FC, OP_UNARY, OP_BINARY, OP_SOFTMAX, OP_FOLD, OP_GROUP };
 enum { UN_RELU = 0, UN_ABS, UN_GELU, UN_EXPCLIP, UN_SIN };
 enum { BIN_ADD = 0, BIN_MUL, BIN_SUB, BIN_MIN, BIN_MAX };
-enum { AXIS_C = 0, AXIS_T, AXIS_CT };
+enum { AXIS_C = 0, AXIS_T, AXIS_CT, AXIS_H, AXIS_W, AXIS_HW };
 enum { FOLD_SUM = 0, FOLD_AVG, FOLD_MAX };
 
 typedef struct {
@@ -375,7 +377,10 @@ static int parse_dag(const char *blob, size_t len, int C0, int H, int W, Dag *d,
                 if (k2 && !strcmp(k2, "C")) nd->kind = AXIS_C;
                 else if (k2 && !strcmp(k2, "T")) nd->kind = AXIS_T;
                 else if (k2 && !strcmp(k2, "CT")) nd->kind = AXIS_CT;
-                else { set_err(err, errlen, "softmax needs axis=C|T", lineno); goto done; }
+                else if (k2 && !strcmp(k2, "H")) nd->kind = AXIS_H;
+                else if (k2 && !strcmp(k2, "W")) nd->kind = AXIS_W;
+                else if (k2 && !strcmp(k2, "HW")) nd->kind = AXIS_HW;
+                else { set_err(err, errlen, "softmax needs axis=C|T|CT|H|W|HW", lineno); goto done; }
                 nd->C = A->C;
                 nd->T = A->T;
             } else if (!strcmp(opn, "fold")) {
@@ -553,6 +558,27 @@ static void fwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
 /* Softmax along channels, along taps, or along both jointly (the [C, T] block is contiguous), every other index fixed. */
 static void fwd_softmax(const Dag *d, const Node *nd, const double *in, double *out) {
     int P = node_P(d, nd), C = nd->C, T = nd->T;
+    if (nd->kind >= AXIS_H) {  /* along H, along W or along both, of every (channel, tap) plane */
+        int Hn = node_H(d, nd), Wn = node_W(d, nd), overH = nd->kind != AXIS_W, overW = nd->kind != AXIS_H, c, ho, wo, h, w;
+        for (c = 0; c < C * T; c++)
+            for (ho = 0; ho < (overH ? 1 : Hn); ho++)
+                for (wo = 0; wo < (overW ? 1 : Wn); wo++) {
+                    int h0 = overH ? 0 : ho, h1 = overH ? Hn : ho + 1, w0 = overW ? 0 : wo, w1 = overW ? Wn : wo + 1;
+                    double m = -INFINITY, sum = 0.0;
+                    for (h = h0; h < h1; h++)
+                        for (w = w0; w < w1; w++)
+                            if (in[((size_t)c * Hn + h) * Wn + w] > m) m = in[((size_t)c * Hn + h) * Wn + w];
+                    for (h = h0; h < h1; h++)
+                        for (w = w0; w < w1; w++) {
+                            size_t idx = ((size_t)c * Hn + h) * Wn + w;
+                            out[idx] = exp(in[idx] - m);
+                            sum += out[idx];
+                        }
+                    for (h = h0; h < h1; h++)
+                        for (w = w0; w < w1; w++) out[((size_t)c * Hn + h) * Wn + w] /= sum;
+                }
+        return;
+    }
     int len = nd->kind == AXIS_C ? C : (nd->kind == AXIS_T ? T : C * T), outer = nd->kind == AXIS_C ? T : (nd->kind == AXIS_T ? C : 1);
     int o, p, k;
     for (o = 0; o < outer; o++)
@@ -735,6 +761,23 @@ static void bwd_binary(const Dag *d, const Node *nd, const double *lhs, const do
 
 static void bwd_softmax(const Dag *d, const Node *nd, const double *out, const double *gout, double *gin) {
     int P = node_P(d, nd), C = nd->C, T = nd->T;
+    if (nd->kind >= AXIS_H) {
+        int Hn = node_H(d, nd), Wn = node_W(d, nd), overH = nd->kind != AXIS_W, overW = nd->kind != AXIS_H, c, ho, wo, h, w;
+        for (c = 0; c < C * T; c++)
+            for (ho = 0; ho < (overH ? 1 : Hn); ho++)
+                for (wo = 0; wo < (overW ? 1 : Wn); wo++) {
+                    int h0 = overH ? 0 : ho, h1 = overH ? Hn : ho + 1, w0 = overW ? 0 : wo, w1 = overW ? Wn : wo + 1;
+                    double dot = 0.0;
+                    for (h = h0; h < h1; h++)
+                        for (w = w0; w < w1; w++) dot += gout[((size_t)c * Hn + h) * Wn + w] * out[((size_t)c * Hn + h) * Wn + w];
+                    for (h = h0; h < h1; h++)
+                        for (w = w0; w < w1; w++) {
+                            size_t idx = ((size_t)c * Hn + h) * Wn + w;
+                            gin[idx] += out[idx] * (gout[idx] - dot);
+                        }
+                }
+        return;
+    }
     int len = nd->kind == AXIS_C ? C : (nd->kind == AXIS_T ? T : C * T), outer = nd->kind == AXIS_C ? T : (nd->kind == AXIS_T ? C : 1);
     int o, p, k;
     for (o = 0; o < outer; o++)

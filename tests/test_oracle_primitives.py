@@ -417,6 +417,51 @@ def test_joint_softmax_over_channels_and_taps(oracle):
     np.testing.assert_allclose(r["dx"], run1(oracle, "%1 = unfold %0 kh=3 kw=1\noutput %1\n", x, (), gu)["dx"], atol=1e-14)
 
 
+@pytest.mark.parametrize("axis", ["H", "W", "HW"])
+def test_softmax_over_spatial_dims(oracle, axis):
+    """Softmax "at any continuous dims" (table of primitives): along H, along W, or over both jointly, of every
+    (channel, tap) plane.  Pinned by the closed form on a non-square plane with taps (a swapped h / w or a softmax that
+    ran across taps or channels fails), by the normalisation and shift invariance, by the closed-form Jacobian-vector
+    product through the unfold adjoint, by finite differences, and by the transposed image."""
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((2, 3, 4, 5))
+    dims = {"H": (3,), "W": (4,), "HW": (3, 4)}[axis]
+    body = f"%1 = unfold %0 kh=1 kw=3\n%2 = softmax %1 axis={axis}\noutput %2\n"
+    u = run1(oracle, "%1 = unfold %0 kh=1 kw=3\noutput %1\n", x)["y"]  # [N, C, T, H, W]
+    y = run1(oracle, body, x)["y"]
+    e = np.exp(u - u.max(axis=dims, keepdims=True))
+    np.testing.assert_allclose(y, e / e.sum(axis=dims, keepdims=True), atol=1e-15)
+    np.testing.assert_allclose(y.sum(axis=dims), 1.0, atol=1e-14)
+    # no unfold: plain [N, C, H, W]; adding a constant per plane changes nothing
+    plain = f"%1 = softmax %0 axis={axis}\noutput %1\n"
+    y0 = run1(oracle, plain, x)["y"]
+    d0 = tuple(d - 1 for d in dims)
+    e0 = np.exp(x)
+    np.testing.assert_allclose(y0, e0 / e0.sum(axis=d0, keepdims=True), atol=1e-14)
+    np.testing.assert_allclose(run1(oracle, plain, x + rng.standard_normal((2, 3, 1, 1)))["y"], y0, atol=1e-14)
+    # backward: dx_j = y_j (g_j - sum_k g_k y_k) along the axis; its sum along the axis is zero
+    g = rng.standard_normal(y.shape)
+    r = run1(oracle, body, x, (), g)
+    gu = y * (g - (g * y).sum(axis=dims, keepdims=True))
+    np.testing.assert_allclose(r["dx"], run1(oracle, "%1 = unfold %0 kh=1 kw=3\noutput %1\n", x, (), gu)["dx"], atol=1e-14)
+    g0 = rng.standard_normal(x.shape)
+    np.testing.assert_allclose(run1(oracle, plain, x, (), g0)["dx"].sum(axis=d0), 0.0, atol=1e-14)
+    fd_check(oracle, body, x, ())
+    # the transposed image: softmax along H of x equals softmax along W of x^T, transposed back
+    if axis != "HW":
+        other = "W" if axis == "H" else "H"
+        yt = run1(oracle, f"%1 = softmax %0 axis={other}\noutput %1\n", np.ascontiguousarray(x.transpose(0, 1, 3, 2)))["y"]
+        np.testing.assert_allclose(y0, yt.transpose(0, 1, 3, 2), atol=1e-15)
+    else:
+        # jointly over H and W is not H then W
+        hw = run1(oracle, "%1 = softmax %0 axis=H\n%2 = softmax %1 axis=W\noutput %2\n", x)["y"]
+        assert np.abs(hw - y0).max() > 1e-3
+        # but on a one-row image it is the softmax along W (and along H it is all ones)
+        x1 = x[:, :, :1]
+        np.testing.assert_array_equal(run1(oracle, plain, x1)["y"], run1(oracle, "%1 = softmax %0 axis=W\noutput %1\n", x1)["y"])
+        np.testing.assert_array_equal(run1(oracle, "%1 = softmax %0 axis=H\noutput %1\n", x1)["y"], np.ones_like(x1))
+
+
 def test_softmax_over_single_tap_is_all_ones_with_zero_gradient(oracle):
     x = np.random.default_rng(31).standard_normal((1, 3, 2, 2))
     r = run1(oracle, "%1 = softmax %0 axis=T\noutput %1\n", x, (), np.ones((1, 3, 2, 2)))
