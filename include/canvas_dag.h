@@ -18,7 +18,7 @@
  *     %4 = shift %3 dh=0 dw=1 c0=32 c1=64
  *     %5 = binary %0 %4 op=mul         first operand LHS, second RHS; add | sub | mul | min | max [lhs=pixels]
  *     %6 = fold %5 op=avg              sum | avg | max [axis=T | H | W | HW | C [groups=<G>]]
- *     %7 = softmax %6 axis=C           C | T | CT
+ *     %7 = softmax %6 axis=C           C | T | CT | H | W | HW
  *     %8 = group %7 groups=4           a view [G, C/G] of the channels; groups=C: every channel a group
  *     output %8
  *
@@ -42,7 +42,9 @@
  *            pixels instead: out(c,t,h,w) = op(LHS(h*W+w), RHS(c,t,h,w)) (Section 8,
  *            the kernel that pools to [C], maps to H x W with an FC and multiplies x).
  *   softmax  along C (per n,t,h,w), along T (per n,c,h,w) or along both jointly
- *            (axis=CT, per n,h,w) (Section 5, Softmax over contiguous dims).
+ *            (axis=CT, per n,h,w); along H (per n,c,t,w), along W (per n,c,t,h) or
+ *            over both jointly (axis=HW, per n,c,t) (Section 5, Softmax at any
+ *            continuous dims).
  *   fold     sum, avg or max over T; T disappears (Section 5, Folding).  Max
  *            sends its gradient to the first maximal tap.  With axis=HW the
  *            pixels are folded instead (global pooling), with axis=H or axis=W

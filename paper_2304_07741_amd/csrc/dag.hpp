@@ -13,7 +13,7 @@ namespace canvas {
 enum class Op : int { Input = 0, Unfold, Shift, Fc, Unary, Binary, Softmax, Fold, Group };
 enum UnaryKind : int { kRelu = 0, kAbs, kGelu, kExpClip, kSin };
 enum BinaryKind : int { kAdd = 0, kMul, kSub, kBinMin, kBinMax };
-enum AxisKind : int { kAxisC = 0, kAxisT, kAxisCT };
+enum AxisKind : int { kAxisC = 0, kAxisT, kAxisCT, kAxisH, kAxisW, kAxisHW };
 enum FoldKind : int { kSum = 0, kAvg, kMax };
 
 struct Node {

@@ -478,6 +478,13 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16, bool fuse_ch
         case Op::Softmax:
             {
                 const int Pn = dag.Pk(k);
+                if (nd.kind >= kAxisH) {  // rows of every (image, channel, tap) plane: along W or the whole plane contiguous, along H strided by W
+                    const int Hn = dag.Hk(k), Wn = dag.Wk(k);
+                    const int len = nd.kind == kAxisH ? Hn : (nd.kind == kAxisW ? Wn : Hn * Wn), inner = nd.kind == kAxisH ? Wn : 1;
+                    const int64_t rows = (int64_t)N * nd.C * nd.T * Pn / len;
+                    L.run = [=](const RunArgs& a) { ref::softmax_rows_fwd(val(a, nd.a), valw(a, k), rows, len, inner, a.stream); };
+                    break;
+                }
                 L.run = [=](const RunArgs& a) { ref::softmax_fwd(val(a, nd.a), valw(a, k), N, nd.C, nd.T, Pn, nd.kind == kAxisCT ? 2 : (nd.kind == kAxisC ? 1 : 0), a.stream); };
             }
             break;
@@ -660,6 +667,13 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16, bool fuse_ch
             L.bytes += 4.0 * dag.numel(k);
             {
                 const int Pn = dag.Pk(k);
+                if (nd.kind >= kAxisH) {
+                    const int Hn = dag.Hk(k), Wn = dag.Wk(k);
+                    const int len = nd.kind == kAxisH ? Hn : (nd.kind == kAxisW ? Wn : Hn * Wn), inner = nd.kind == kAxisH ? Wn : 1;
+                    const int64_t rows = (int64_t)N * nd.C * nd.T * Pn / len;
+                    L.run = [=](const RunArgs& a) { ref::softmax_rows_bwd(val(a, k), grad(a, k), grad(a, nd.a), rows, len, inner, acc, a.stream); };
+                    break;
+                }
                 L.run = [=](const RunArgs& a) { ref::softmax_bwd(val(a, k), grad(a, k), grad(a, nd.a), N, nd.C, nd.T, Pn, nd.kind == kAxisCT ? 2 : (nd.kind == kAxisC ? 1 : 0), acc, a.stream); };
             }
             break;

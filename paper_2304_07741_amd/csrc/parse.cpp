@@ -218,7 +218,10 @@ int parse_dag(const char* blob, size_t len, const int64_t in_shape[4], Dag& dag,
             if (it->second == "C") nd.kind = kAxisC;
             else if (it->second == "T") nd.kind = kAxisT;
             else if (it->second == "CT") nd.kind = kAxisCT;
-            else return fail(err, lineno, "softmax axis must be C or T", kUnknownOp);
+            else if (it->second == "H") nd.kind = kAxisH;
+            else if (it->second == "W") nd.kind = kAxisW;
+            else if (it->second == "HW") nd.kind = kAxisHW;
+            else return fail(err, lineno, "softmax axis must be C, T, CT, H, W or HW", kUnknownOp);
             nd.C = A.C;
             nd.T = A.T;
         } else if (op == "fold") {

@@ -319,6 +319,49 @@ __global__ void k_softmax_fwd(const float* __restrict__ in, float* __restrict__ 
     for (int k = 0; k < len; k++) out[base + k * stride] = expf(in[base + k * stride] - m) * inv;
 }
 
+// Softmax along a spatial dim (Section 5, table of primitives: Softmax at any continuous dims): one wavefront per row,
+// lane l takes elements l, l + 64, ...; maximum and sums cross the lanes in a fixed butterfly, so the result does not
+// depend on the launch.
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+    return v;
+}
+__global__ __launch_bounds__(256) void k_softmax_rows_fwd(const float* __restrict__ in, float* __restrict__ out, int64_t rows, int len, int inner) {
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;  // (whole wavefronts leave: the shuffles below see all 64 lanes)
+    const int lane = threadIdx.x & 63;
+    const int64_t base = (r / inner) * (int64_t)len * inner + (r % inner);
+    float m = -INFINITY;
+    for (int k = lane; k < len; k += 64) m = fmaxf(m, in[base + (int64_t)k * inner]);
+    m = wave_max(m);
+    float z = 0.f;
+    for (int k = lane; k < len; k += 64) z += expf(in[base + (int64_t)k * inner] - m);
+    z = wave_sum(z);
+    const float inv = 1.f / z;
+    for (int k = lane; k < len; k += 64) out[base + (int64_t)k * inner] = expf(in[base + (int64_t)k * inner] - m) * inv;
+}
+__global__ __launch_bounds__(256) void k_softmax_rows_bwd(const float* __restrict__ y, const float* __restrict__ gout, float* __restrict__ gin,
+                                                          int64_t rows, int len, int inner, int acc) {
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t base = (r / inner) * (int64_t)len * inner + (r % inner);
+    float dot = 0.f;
+    for (int k = lane; k < len; k += 64) dot += gout[base + (int64_t)k * inner] * y[base + (int64_t)k * inner];
+    dot = wave_sum(dot);
+    for (int k = lane; k < len; k += 64) {
+        const int64_t i = base + (int64_t)k * inner;
+        const float g = y[i] * (gout[i] - dot);
+        gin[i] = acc ? gin[i] + g : g;
+    }
+}
+
 // gin16 (optional): the result once more, rounded to bf16 (for a consumer that takes bf16 operands)
 __global__ void k_softmax_bwd(const float* __restrict__ y, const float* __restrict__ gout, float* __restrict__ gin,
                               uint16_t* __restrict__ gin16, int64_t total, int C, int T, int P, int axis_c, int acc) {
@@ -586,6 +629,12 @@ void pool_fwd(const float* in, float* out, int64_t rows, int P, int kind, hipStr
 }
 void pool_bwd(const float* in, const float* gout, float* gin, int64_t rows, int P, int kind, int acc, hipStream_t s) {
     if (rows > 0) CANVAS_LAUNCH(k_pool_bwd, dim3((unsigned)rows), dim3(256), 0, s, in, gout, gin, P, kind, acc);
+}
+void softmax_rows_fwd(const float* in, float* out, int64_t rows, int len, int inner, hipStream_t s) {
+    if (rows > 0) CANVAS_LAUNCH(k_softmax_rows_fwd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, in, out, rows, len, inner);
+}
+void softmax_rows_bwd(const float* y, const float* gout, float* gin, int64_t rows, int len, int inner, int acc, hipStream_t s) {
+    if (rows > 0) CANVAS_LAUNCH(k_softmax_rows_bwd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, y, gout, gin, rows, len, inner, acc);
 }
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s) {
     int64_t total = N * (axis_c == 2 ? 1 : (axis_c ? T : C)) * P;

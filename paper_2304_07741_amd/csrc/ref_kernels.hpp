@@ -31,6 +31,11 @@ void binary_bwd_rhs(const float* lhs, const float* rhs, const float* gout, float
 void binary_bwd_lhs(const float* lhs, const float* rhs, const float* gout, float* glhs, int64_t N, int CL, int TL, int CR, int TR, int P,
                     int PL, int rep, int Wd, int kind, int acc, hipStream_t s);
 // axis_c: 1 = over channels, 0 = over taps, 2 = over both jointly
+// Softmax along a spatial dim of every plane: `rows` rows of `len` elements, element k of row r at
+// (r / inner) * len * inner + (r % inner) + k * inner (inner = 1: contiguous rows, i.e. along W or over a whole plane;
+// inner = W: along H).  One wavefront per row, sums in a fixed butterfly order.
+void softmax_rows_fwd(const float* in, float* out, int64_t rows, int len, int inner, hipStream_t s);
+void softmax_rows_bwd(const float* y, const float* gout, float* gin, int64_t rows, int len, int inner, int acc, hipStream_t s);
 void softmax_fwd(const float* in, float* out, int64_t N, int C, int T, int P, int axis_c, hipStream_t s);
 // gin16 (optional): the same result once more, rounded to bf16
 void softmax_bwd(const float* y, const float* gout, float* gin, int64_t N, int C, int T, int P, int axis_c, int acc,

@@ -91,6 +91,12 @@ PRIMS = [
      "%6 = binary %2 %5 op=max\n%7 = fold %6 op=avg\n%8 = binary %7 %0 op=add\noutput %8\n", [(2, 2, 6)]),
     ("%1 = group %0 groups=4\n%2 = fc %1 out=8\n%3 = group %2 groups=2\n%4 = fc %3 out=6\n%5 = binary %4 %1 op=mul\n%6 = group %5 groups=6\noutput %6\n",
      [(4, 2, 3), (2, 3, 4)]),
+    # softmax over the spatial dims: along H, along W, jointly; of an unfolded tensor; of a tensor with one dim folded
+    ("%1 = softmax %0 axis=H\noutput %1\n", []),
+    ("%1 = softmax %0 axis=W\noutput %1\n", []),
+    ("%1 = softmax %0 axis=HW\noutput %1\n", []),
+    ("%1 = unfold %0 kh=1 kw=3\n%2 = softmax %1 axis=HW\n%3 = binary %0 %2 op=mul\n%4 = fold %3 op=sum\noutput %4\n", []),
+    ("%1 = fold %0 op=avg axis=H\n%2 = softmax %1 axis=W\n%3 = binary %2 %0 op=mul\n%4 = softmax %3 axis=H\noutput %4\n", []),
 ]
 
 
@@ -369,6 +375,44 @@ def test_config5_fuzz(harness, oracle, block):
             check_against_oracle(oracle, case, res, dy, what=f"fuzz seed {seed}\n{case['blob']}")
         finally:
             r.close()
+
+
+# The primitives beyond the five configurations at planes larger than one workgroup pass (56 x 56 = 3136 pixels) and
+# at many channels with few pixels: folds over HW / H / W / C, a pooled LHS replicated over the pixels, lhs=pixels,
+# softmax over C and T jointly and over the spatial dims.
+BIG_PLANE_BODIES = [
+    ("%1 = fold %0 op=avg axis=HW\n%2 = binary %1 %0 op=mul\noutput %2\n", []),
+    ("%1 = fold %0 op=max axis=HW\n%2 = binary %1 %0 op=sub\noutput %2\n", []),
+    ("%1 = fold %0 op=sum axis=H\n%2 = fold %0 op=max axis=W\n%3 = binary %1 %0 op=add\n%4 = binary %2 %3 op=mul\noutput %4\n", []),
+    ("%1 = fold %0 op=avg axis=C groups=4\n%2 = fold %1 op=max axis=HW\noutput %2\n", []),
+    ("%1 = unfold %0 kh=3 kw=1\n%2 = softmax %1 axis=CT\n%3 = fold %2 op=sum\noutput %3\n", []),
+    ("%1 = softmax %0 axis=HW\n%2 = binary %1 %0 op=mul\noutput %2\n", []),
+    ("%1 = softmax %0 axis=H\n%2 = softmax %0 axis=W\n%3 = binary %1 %2 op=add\noutput %3\n", []),
+]
+
+
+@pytest.mark.parametrize("N,C,H", [(4, 64, 56), (4, 512, 7)])
+@pytest.mark.parametrize("idx", range(len(BIG_PLANE_BODIES)))
+def test_primitives_at_full_size_planes(harness, oracle, idx, N, C, H):
+    body, wshapes = BIG_PLANE_BODIES[idx]
+    case = _mk(body, (N, C, H, H), "bf16", 70 + idx, wshapes, name=f"big_plane_{idx}")
+    res, r, dy = harness.run_case(case)
+    try:
+        check_against_oracle(oracle, case, res, dy, what=f"{case['name']} {case['shape']}")
+    finally:
+        r.close()
+
+
+def test_pixel_aligned_lhs_at_a_full_size_plane(harness, oracle):
+    """The kernel with spatial aggregation and kernel spanning (Section 8): pool to [C], FC to H*W, lay it over the pixels."""
+    C, H = 64, 28
+    body = f"%1 = fold %0 op=avg axis=HW\n%2 = fc %1 groups=1 out={H * H}\n%3 = binary %2 %0 op=mul lhs=pixels\noutput %3\n"
+    case = _mk(body, (4, C, H, H), "bf16", 77, [(1, H * H, C)], name="spatial_aggregation")
+    res, r, dy = harness.run_case(case)
+    try:
+        check_against_oracle(oracle, case, res, dy, what="spatial aggregation 28x28")
+    finally:
+        r.close()
 
 
 # FC-free chains (one fused kernel each way) at the shapes bench.py times them on, and at planes that leave a ragged

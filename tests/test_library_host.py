@@ -75,7 +75,7 @@ BAD = [
     ("%1 = unary %0 op=relu\n", -1),
     ("%1 = unary %0\noutput %1\n", -1),
     ("%1 = unary %0 op=tanh\noutput %1\n", -2),
-    ("%1 = softmax %0 axis=H\noutput %1\n", -2),
+    ("%1 = softmax %0 axis=X\noutput %1\n", -2),
     ("%1 = conv %0 k=3\noutput %1\n", -2),
     ("%1 = unary %0 op=expclip lo=1 hi=1\noutput %1\n", -3),
     ("foo=bar\noutput %0\n", -1),                      # a line of key=value tokens only

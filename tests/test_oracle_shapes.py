@@ -90,7 +90,7 @@ def test_grouped_broadcast_alignment(oracle):
     "%2 = unary %0 op=relu\noutput %2\n",                # ids must be consecutive
     "%1 = unary %1 op=relu\noutput %1\n",                # operand must precede
     "%1 = unary %0 op=tanh\noutput %1\n",
-    "%1 = softmax %0 axis=H\noutput %1\n",
+    "%1 = softmax %0 axis=X\noutput %1\n",
     "%1 = unary %0 op=expclip lo=1 hi=1\noutput %1\n",
     "%1 = unary %0 op=relu\n",                           # no output
 ])
