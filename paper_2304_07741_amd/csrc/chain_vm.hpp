@@ -165,7 +165,14 @@ __device__ __forceinline__ void vm_load(const Tensor& e, int elem, float* out) {
 #pragma unroll
             for (int q = 0; q < V / 8; q++) {
                 tile::u32x4 d = tile::bload16(e.rs, o + 16 * q);
-                if (!ALIGNED) tile::reload_if_partial(d, e.rs, o + 16 * q, e.bytes);
+                if (!ALIGNED && tile::straddles_an_end(o + 16 * q, 16, e.bytes)) {
+                    // (rare: a shifted vector across the very start or end of the tensor; the empty asm keeps the
+                    // compiler from computing the element addresses of this branch ahead of it, for every access)
+                    int o2 = o + 16 * q;
+                    asm volatile("" : "+v"(o2));
+#pragma unroll
+                    for (int k = 0; k < 4; k++) d[k] = tile::elem_b16(e.rs, o2 + 4 * k, e.bytes) | (tile::elem_b16(e.rs, o2 + 4 * k + 2, e.bytes) << 16);
+                }
 #pragma unroll
                 for (int k = 0; k < 4; k++) {
                     out[8 * q + 2 * k] = tile::lo_f32(d[k]);
@@ -198,7 +205,12 @@ __device__ __forceinline__ void vm_load(const Tensor& e, int elem, float* out) {
 #pragma unroll
             for (int q = 0; q < V / 4; q++) {
                 tile::u32x4 d = tile::bload16(e.rs, o + 16 * q);
-                if (!ALIGNED) tile::reload_f32x4_if_partial(d, e.rs, o + 16 * q, e.bytes);
+                if (!ALIGNED && tile::straddles_an_end(o + 16 * q, 16, e.bytes)) {
+                    int o2 = o + 16 * q;
+                    asm volatile("" : "+v"(o2));
+#pragma unroll
+                    for (int k = 0; k < 4; k++) d[k] = tile::elem_b32(e.rs, o2 + 4 * k, e.bytes);
+                }
 #pragma unroll
                 for (int k = 0; k < 4; k++) out[4 * q + k] = __uint_as_float(d[k]);
             }
@@ -407,21 +419,25 @@ CHAIN_HD void vm_reg_write(float* Rm, int rstride, int r, int T, const float* X)
     }
 }
 
-// Which of the thread's V pixels see the image at offset (oh, ow): bit v of the result.
+// Which of the thread's V pixels see the image at offset (oh, ow): bit v of the result.  The thread's pixels are a run
+// of at most two image rows (V <= W), so the valid ones are at most two runs of bits: no per-pixel arithmetic.
+CHAIN_HD uint32_t vm_bits(int lo, int hi) {  // bits [lo, hi), 0 <= lo, hi <= 32
+    const uint32_t upto_hi = hi >= 32 ? 0xffffffffu : ((1u << hi) - 1u);
+    return hi > lo ? (upto_hi & ~((1u << lo) - 1u)) : 0u;
+}
+// x where bit v of m is set, else +0 (two bit operations instead of a compare and a select).
+CHAIN_HD float vm_keep(float x, uint32_t m, int v) { return vm_bits_to_f32(vm_f32_to_bits(x) & (0u - ((m >> v) & 1u))); }
 template <int V>
 CHAIN_HD uint32_t vm_valid(const Geo& g, const Thread& th, int oh, int ow) {
-    uint32_t m = 0;
     if (!th.active) return 0;
-#pragma unroll
-    for (int v = 0; v < V; v++) {
-        int c = th.col0 + v, r = th.row0;
-        if (c >= g.W) {
-            c -= g.W;
-            r++;
-        }
-        r += oh;
-        c += ow;
-        if ((unsigned)r < (unsigned)g.H && (unsigned)c < (unsigned)g.W) m |= 1u << v;
+    const int n1 = g.W - th.col0 < V ? g.W - th.col0 : V;  // pixels [0, n1) lie in row0, [n1, V) in row0 + 1
+    const int first = -(th.col0 + ow), behind = g.W - th.col0 - ow;  // pixel v of row0 has column v - first; valid for first <= v < behind
+    uint32_t m = 0;
+    if ((unsigned)(th.row0 + oh) < (unsigned)g.H) m |= vm_bits(first > 0 ? first : 0, behind < n1 ? behind : n1);
+    if (n1 < V && (unsigned)(th.row0 + 1 + oh) < (unsigned)g.H) {
+        // pixel v of row0 + 1 has column v - n1, displaced v - n1 + ow = v - behind + ... : valid for behind <= v < behind + W
+        const int lo2 = behind > n1 ? behind : n1, hi2 = behind + g.W < V ? behind + g.W : V;
+        m |= vm_bits(lo2, hi2);
     }
     return m;
 }
@@ -437,7 +453,7 @@ CHAIN_HD void vm_load_at(const Tensor& e, const Geo& g, const Thread& th, int pl
         vm_load<V, false>(e, plane * g.HW + th.p0 + oh * g.W + ow, raw);
         const uint32_t m = vm_valid<V>(g, th, oh, ow);
 #pragma unroll
-        for (int v = 0; v < V; v++) out[v] = ((m >> v) & 1u) ? raw[v] : 0.f;
+        for (int v = 0; v < V; v++) out[v] = vm_keep(raw[v], m, v);
     }
 }
 
@@ -509,8 +525,7 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env
                             vm_tap(t, KH, KW, oh, ow);
                             const uint32_t m = vm_valid<V>(g, th, dh + oh, dw + ow);
 #pragma unroll
-                            for (int v = 0; v < V; v++)
-                                if (!((m >> v) & 1u)) A[u * TV + t * V + v] = 0.f;
+                            for (int v = 0; v < V; v++) A[u * TV + t * V + v] = vm_keep(A[u * TV + t * V + v], m, v);
                         }
                 } else {
                     const uint32_t m = vm_valid<V>(g, th, dh, dw);
@@ -518,8 +533,7 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env
                     for (int t = 0; t < TM; t++)
                         if (t < T) {
 #pragma unroll
-                            for (int v = 0; v < V; v++)
-                                if (!((m >> v) & 1u)) A[u * TV + t * V + v] = 0.f;
+                            for (int v = 0; v < V; v++) A[u * TV + t * V + v] = vm_keep(A[u * TV + t * V + v], m, v);
                         }
                 }
             }
