@@ -181,6 +181,7 @@ class Graph {
     }
 
     const Dag& dag;
+    int root_ctx = 0;  // the context the unit's outputs are built in (not the empty one for a displaced unit)
     std::vector<Ctx> ctxs;
     std::map<std::string, int> ctx_ids;
     std::vector<Inst> insts;
@@ -190,7 +191,15 @@ class Graph {
 
 class Emitter {
    public:
-    Emitter(Graph& g, int tm) : G(g), NR(regs_for(tm)), used(regs_for(tm), false) { pg.tm = tm; }
+    Emitter(Graph& g, int tm) : G(&g), NR(regs_for(tm)), used(regs_for(tm), false) { pg.tm = tm; }
+
+    // Instructions may come from several instance graphs (the unit as it is, and the unit displaced by a stencil's
+    // offsets: see compile_unit); `gidx` tells their instances apart in the tables below.
+    void use(Graph& g, int idx) {
+        G = &g;
+        gidx = idx;
+    }
+    int gkey(int v) const { return gidx * (1 << 20) + v; }
 
     void emit(const Instr& I) {
         if (pg.n_instr >= kMaxInstr) throw Fail{"too many instructions"};
@@ -219,25 +228,25 @@ class Emitter {
         e.node = node;
         e.role = role;
         ext.push_back(e);
-        pg.ext[ext.size() - 1].T = G.dag.nodes[node].T;
+        pg.ext[ext.size() - 1].T = G->dag.nodes[node].T;
         pg.n_ext = (int)ext.size();
         return (int)ext.size() - 1;
     }
     uint16_t terms(int ctx) {
-        auto it = term_of.find(ctx);
+        auto it = term_of.find(gkey(ctx));
         if (it != term_of.end()) return it->second;
-        const Ctx& c = G.ctxs[ctx];
+        const Ctx& c = G->ctxs[ctx];
         if (pg.n_terms + (int)c.terms.size() > kMaxTerms) throw Fail{"too many stencil offsets"};
         const int first = pg.n_terms;
         for (const Term& t : c.terms) pg.term[pg.n_terms++] = t;
-        return term_of[ctx] = (uint16_t)((first << 8) | (int)c.terms.size());
+        return term_of[gkey(ctx)] = (uint16_t)((first << 8) | (int)c.terms.size());
     }
     Instr positional(Opcode op, int ctx, int lanes) {
         Instr I;
         I.op = op;
         I.T = (uint8_t)lanes;
         I.b = terms(ctx);
-        const Ctx& c = G.ctxs[ctx];
+        const Ctx& c = G->ctxs[ctx];
         if (c.win) {
             I.kind |= kWin;
             I.r = (uint8_t)((c.kh << 4) | c.kw);
@@ -261,7 +270,8 @@ class Emitter {
     struct Stat {
         int computed = 0, cost = 0;
     };
-    void cached(int key, int lanes, void (Emitter::*raw)(int), int i) {
+    void cached(int key0, int lanes, void (Emitter::*raw)(int), int i) {
+        const int key = gkey(key0);
         auto it = held.find(key);
         if (it != held.end()) {
             emit(simple(OP_MOVA, lanes, it->second));
@@ -278,17 +288,27 @@ class Emitter {
             held[key] = r;
         }
     }
+    void forget_graph(int idx) {  // (what a displaced copy kept is of no use to the next one)
+        for (auto it = held.begin(); it != held.end();) {
+            if (it->first / (1 << 20) == idx) {
+                release(it->second);
+                it = held.erase(it);
+            } else {
+                ++it;
+            }
+        }
+    }
     void forget() {  // (a register's content does not outlive the body it was written in)
         for (auto& kv : held) release(kv.second);
         held.clear();
     }
-    void eval(int i) { cached(2 * i, G.insts[i].lanes, &Emitter::eval_raw, i); }
-    void grad(int i) { cached(2 * i + 1, G.insts[i].lanes, &Emitter::grad_raw, i); }
+    void eval(int i) { cached(2 * i, G->insts[i].lanes, &Emitter::eval_raw, i); }
+    void grad(int i) { cached(2 * i + 1, G->insts[i].lanes, &Emitter::grad_raw, i); }
 
     // ---------------------------------------------------------------- forward values
     void eval_raw(int i) {
-        const Inst& I = G.insts[i];
-        const Node& nd = G.dag.nodes[I.node];
+        const Inst& I = G->insts[i];
+        const Node& nd = G->dag.nodes[I.node];
         switch (I.kind) {
         case kExt: {
             Instr ld = positional(OP_LD, I.ctx, I.lanes);
@@ -300,7 +320,7 @@ class Emitter {
         case kIdent: eval(I.opnd[0]); break;
         case kStencil: {
             eval(I.opnd[0]);
-            const Inst& S = G.insts[I.opnd[0]];
+            const Inst& S = G->insts[I.opnd[0]];
             if (S.kind != kExt) emit(positional(OP_MASK, S.ctx, I.lanes));  // (a load checks its own position)
             break;
         }
@@ -313,7 +333,7 @@ class Emitter {
             break;
         }
         case kBinaryI: {
-            const int tl = G.insts[I.opnd[0]].lanes;
+            const int tl = G->insts[I.opnd[0]].lanes;
             eval(I.opnd[0]);
             const int r = alloc();
             emit(simple(OP_MOVR, tl, r));
@@ -332,7 +352,7 @@ class Emitter {
             break;
         case kFoldI:
             eval(I.opnd[0]);
-            emit(simple(OP_FOLD, G.insts[I.opnd[0]].lanes, 0, nd.kind));
+            emit(simple(OP_FOLD, G->insts[I.opnd[0]].lanes, 0, nd.kind));
             break;
         }
     }
@@ -340,18 +360,18 @@ class Emitter {
     int stat_slot(int i) {
         auto it = stat_slots.find(i);
         if (it != stat_slots.end()) return it->second;
-        return stat_slots[i] = persist(2 * G.insts[i].lanes);
+        return stat_slots[i] = persist(2 * G->insts[i].lanes);
     }
     int dot_slot(int i) {
         auto it = dot_slots.find(i);
         if (it != dot_slots.end()) return it->second;
-        return dot_slots[i] = persist(G.insts[i].lanes);
+        return dot_slots[i] = persist(G->insts[i].lanes);
     }
 
     // ---------------------------------------------------------------- gradients
     // leaves d loss / d instance i in A (lanes of i)
     void grad_raw(int i) {
-        const Inst& I = G.insts[i];
+        const Inst& I = G->insts[i];
         bool first = true;
         int held = -1;
         auto begin_term = [&]() {
@@ -367,9 +387,9 @@ class Emitter {
             }
             first = false;
         };
-        if (I.kind != kExt && I.ctx == 0 && G.is_output_[I.node] && I.lanes == G.dag.nodes[I.node].T) {
+        if (I.kind != kExt && I.ctx == G->root_ctx && G->is_output_[I.node] && I.lanes == G->dag.nodes[I.node].T) {
             begin_term();
-            Instr ld = positional(OP_LD, 0, I.lanes);
+            Instr ld = positional(OP_LD, G->root_ctx, I.lanes);  // (a displaced unit reads the incoming gradient displaced)
             ld.a = (uint16_t)ext_slot(I.node, kGradIn);
             if (I.lanes > 1) ld.kind |= kExtTaps;
             emit(ld);
@@ -385,9 +405,9 @@ class Emitter {
 
     // d loss / d (operand `slot` of user instance u), which is instance i
     void contribution(int u, int slot, int i) {
-        const Inst& U = G.insts[u];
-        const Inst& I = G.insts[i];
-        const Node& un = G.dag.nodes[U.node];
+        const Inst& U = G->insts[u];
+        const Inst& I = G->insts[i];
+        const Node& un = G->dag.nodes[U.node];
         grad(u);  // A = gradient of u, U.lanes lanes
         switch (U.kind) {
         case kIdent: break;
@@ -407,7 +427,7 @@ class Emitter {
         }
         case kBinaryI: {
             const int other = U.opnd[1 - slot];
-            const int tl = G.insts[U.opnd[0]].lanes;
+            const int tl = G->insts[U.opnd[0]].lanes;
             const bool lhs_scalar = tl == 1 && U.lanes > 1;
             if (un.kind == kAdd || (un.kind == kSub && slot == 0)) {
             } else if (un.kind == kSub) {
@@ -486,28 +506,29 @@ class Emitter {
     // the passes that collect the statistics of every softmax over channels, lowest first
     void stat_passes(const std::vector<int>& smc) {
         int top = 0;
-        for (int i : smc) top = std::max(top, G.insts[i].level);
+        for (int i : smc) top = std::max(top, G->insts[i].level);
         for (int lvl = 1; lvl <= top; lvl++) {
             begin_pass();
             for (int i : smc)
-                if (G.insts[i].level == lvl) {
-                    Instr m = simple(OP_PSET, G.insts[i].lanes, 0, 0, stat_slot(i));
+                if (G->insts[i].level == lvl) {
+                    Instr m = simple(OP_PSET, G->insts[i].lanes, 0, 0, stat_slot(i));
                     m.f0 = -INFINITY;
                     emit(m);
-                    emit(simple(OP_PSET, G.insts[i].lanes, 0, 0, stat_slot(i) + G.insts[i].lanes));
-                    reduce(stat_slot(i), G.insts[i].lanes, 0);
+                    emit(simple(OP_PSET, G->insts[i].lanes, 0, 0, stat_slot(i) + G->insts[i].lanes));
+                    reduce(stat_slot(i), G->insts[i].lanes, 0);
                 }
             begin_body();
             for (int i : smc)
-                if (G.insts[i].level == lvl) {
-                    eval(G.insts[i].opnd[0]);
-                    emit(simple(OP_SMCSTAT, G.insts[i].lanes, 0, 0, stat_slot(i)));
+                if (G->insts[i].level == lvl) {
+                    eval(G->insts[i].opnd[0]);
+                    emit(simple(OP_SMCSTAT, G->insts[i].lanes, 0, 0, stat_slot(i)));
                 }
             end_pass();
         }
     }
 
-    Graph& G;
+    Graph* G;
+    int gidx = 0;
     Program pg;
     std::vector<ExtRef> ext;
     int NR;
@@ -658,6 +679,45 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
         if (lanes > 25) throw Fail{"more than 25 taps"};
         const int tm = lanes <= 1 ? 1 : (lanes <= 9 ? 9 : 25);
 
+        // ------------------------------------------------------------ displaced units
+        // The gradient of a leaf that reads an external tensor through Shift offsets belongs to another pixel.  Where the
+        // unit has no reduction, the pixel fetches it itself: the whole unit is instantiated once more, displaced by
+        // the negated offsets (every load of it, the incoming gradient included, moves with it), and the gradient of
+        // the same leaf in that copy, masked where the displaced pixel leaves the image, is what this pixel's tensor
+        // element receives.  No hand-over between threads, no halo, no barrier; windows keep the hand-over (OP_XADD),
+        // one displaced copy per tap would cost more than it saves.
+        struct Pull {
+            std::unique_ptr<Graph> g;
+            int leaf = -1, mask_ctx = -1;
+        };
+        std::map<int, Pull> pulls;  // by leaf instance of the unit's own graph
+        for (int i : leaves) {
+            const Ctx& c = G.ctxs[G.insts[i].ctx];
+            if (c.empty() || c.win) continue;
+            try {
+                Pull P;
+                P.g.reset(new Graph(dag, in_unit, is_output));
+                Ctx d;
+                for (const Term& t : c.terms) {
+                    Term n = t;
+                    n.dh = (int16_t)-t.dh;
+                    n.dw = (int16_t)-t.dw;
+                    d.terms.push_back(n);
+                }
+                P.g->root_ctx = P.g->ctx_id(d);
+                P.mask_ctx = P.g->root_ctx;
+                for (int k : out.outputs) P.g->build(k, P.g->root_ctx);
+                Ctx full = d;  // the same leaf in the displaced copy: the displacement, then the leaf's own offsets
+                for (const Term& t : c.terms) full.terms.push_back(t);
+                const int want_ctx = P.g->ctx_id(full);
+                for (size_t j = 0; j < P.g->insts.size(); j++)
+                    if (P.g->insts[j].kind == kExt && P.g->insts[j].node == G.insts[i].node && P.g->insts[j].ctx == want_ctx &&
+                        P.g->insts[j].lanes == G.insts[i].lanes)
+                        P.leaf = (int)j;
+                if (P.leaf >= 0) pulls[i] = std::move(P);
+            } catch (const Fail&) {
+            }
+        }
         // ------------------------------------------------------------ the two programs
         auto emit_fwd = [&](Emitter& E) {
             E.stat_passes(smc);
@@ -710,6 +770,20 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
                 }
                 for (int i : mine) {
                     const Inst& L = G.insts[i];
+                    auto pl = pulls.find(i);
+                    if (pl != pulls.end()) {  // fetched from the displaced copy of the unit
+                        int idx = 1;
+                        for (auto it = pulls.begin(); it != pl; ++it) idx++;
+                        E.use(*pl->second.g, idx);
+                        E.grad(pl->second.leaf);
+                        E.emit(E.positional(OP_MASK, pl->second.mask_ctx, L.lanes));
+                        E.forget_graph(idx);
+                        E.use(G, 0);
+                        Instr p = Emitter::simple(OP_PADD, L.lanes, 0, 0, acc);
+                        p.b = (uint16_t)Te;
+                        E.emit(p);
+                        continue;
+                    }
                     E.grad(i);
                     if (direct) break;
                     if (L.ctx == 0) {

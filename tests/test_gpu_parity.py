@@ -437,7 +437,8 @@ def test_fused_chain_workloads(harness, oracle, body, N, C, H, dtype):
 
 
 DETERMINISM_CASES = [lambda: wl.config4(64, 14, N=4), lambda: wl.config4(64, 56, N=2), lambda: wl.config4(128, 28, N=3),
-                     lambda: wl.config4(512, 7, N=8), lambda: wl.config3(N=2, H=28), lambda: wl.config2(N=2, H=56)]
+                     lambda: wl.config4(512, 7, N=8), lambda: wl.config3(N=2, H=28), lambda: wl.config2(N=2, H=56),
+                     lambda: wl.config5(157), lambda: wl.config5(130), lambda: wl.chain("shift_residual", N=8, C=64, H=28)]
 
 
 @pytest.mark.parametrize("idx", range(len(DETERMINISM_CASES)))
@@ -532,7 +533,7 @@ def test_inference_forward_replays_from_a_hip_graph(harness, which):
         r.close()
 
 
-@pytest.mark.parametrize("which", ["config2", "config3", "config4", "config4_rows"])
+@pytest.mark.parametrize("which", ["config2", "config3", "config4", "config4_rows", "chains_and_fcs", "chain_with_passes", "chain_gate"])
 def test_training_step_replays_from_a_hip_graph(harness, which):
     """Forward and backward of a training plan are fixed lists of kernel launches too: a captured HIP graph of the
     step gives the eager y, dx and dW (bit for bit: every reduction has a fixed order) on every replay, with
@@ -540,7 +541,11 @@ def test_training_step_replays_from_a_hip_graph(harness, which):
     import torch
 
     case = {"config2": lambda: wl.config2(N=4, H=28), "config3": lambda: wl.config3(N=2, H=14),
-            "config4": lambda: wl.config4(256, 14, N=4), "config4_rows": lambda: wl.config4(64, 28, N=2)}[which]()
+            "config4": lambda: wl.config4(256, 14, N=4), "config4_rows": lambda: wl.config4(64, 28, N=2),
+            # fused chains (the program travels in the kernel arguments), with FC nodes between them; a chain whose
+            # softmax over channels runs in passes and hands gradients over through LDS; a chain alone
+            "chains_and_fcs": lambda: wl.config5(135), "chain_with_passes": lambda: wl.config5(157),
+            "chain_gate": lambda: wl.chain("gate", N=4, C=32, H=28)}[which]()
     r = harness.DagRunner(case["blob"], case["shape"], case["dtype"])
     try:
         rng = np.random.default_rng(5)
