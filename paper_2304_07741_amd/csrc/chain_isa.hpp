@@ -51,6 +51,7 @@ enum Opcode : uint8_t {
     OP_SMCDOT,     // P[a + t] += A[t] * R[r][t]
     OP_SMCBX,      // A[t] = A[t] * (R[r][t] - P[a + t])                (A: softmax output, R[r]: gradient)
     OP_XADD,       // P[a (+ t)] += A[t] of the thread whose load at offset(b) [+ window tap t] read THIS pixel
+    OP_BINLD,      // A = blend_kind(loaded, A) or (A, loaded): OP_LD and OP_BIN in one, the loaded operand never visits a register
     OP_COUNT
 };
 
@@ -65,6 +66,10 @@ constexpr uint8_t kBingRhsScalar = 0x20;   // A has one lane
 // OP_LD / OP_MASK / OP_XADD flags (in `kind`)
 constexpr uint8_t kWin = 0x01;             // a window level is part of the position: r = (KH << 4) | KW, lane t is tap t
 constexpr uint8_t kExtTaps = 0x02;         // the external tensor has taps of its own: lane t reads tap t % T_ext
+// OP_BINLD: the two position flags of OP_LD, then
+constexpr int kBinLdKindShift = 2;          // the blend kind, three bits
+constexpr uint8_t kBinLdLoadedIsLhs = 0x20; // the loaded operand is the LHS (else A is)
+constexpr uint8_t kBinLdLoadedScalar = 0x40;  // the loaded operand has one lane, replicated over A's T lanes
 // OP_ST flags
 constexpr uint8_t kStAdd = 0x01;
 // extra unary kind for the planner (after the five of the DAG): negation

@@ -253,6 +253,17 @@ class Emitter {
         }
         return I;
     }
+    // OP_BINLD: A (lanes) blended with the external instance i, read in place (its own lanes: `lanes`, or 1 replicated)
+    Instr load_and_blend(int i, int lanes, int blend, bool loaded_is_lhs) {
+        const Inst& L = G->insts[i];
+        Instr I = positional(OP_BINLD, L.ctx, lanes);
+        I.a = (uint16_t)ext_slot(L.node, kValueIn);
+        if (G->dag.nodes[L.node].T > 1) I.kind |= kExtTaps;
+        I.kind |= (uint8_t)(blend << kBinLdKindShift);
+        if (loaded_is_lhs) I.kind |= kBinLdLoadedIsLhs;
+        if (L.lanes == 1 && lanes > 1) I.kind |= kBinLdLoadedScalar;
+        return I;
+    }
     static Instr simple(Opcode op, int T, int r = 0, int kind = 0, int a = 0) {
         Instr I;
         I.op = op;
@@ -334,6 +345,16 @@ class Emitter {
         }
         case kBinaryI: {
             const int tl = G->insts[I.opnd[0]].lanes;
+            if (G->insts[I.opnd[0]].kind == kExt) {  // the LHS comes straight from memory
+                eval(I.opnd[1]);
+                emit(load_and_blend(I.opnd[0], I.lanes, nd.kind, true));
+                break;
+            }
+            if (G->insts[I.opnd[1]].kind == kExt && tl == I.lanes) {  // the RHS does
+                eval(I.opnd[0]);
+                emit(load_and_blend(I.opnd[1], I.lanes, nd.kind, false));
+                break;
+            }
             eval(I.opnd[0]);
             const int r = alloc();
             emit(simple(OP_MOVR, tl, r));
@@ -432,6 +453,9 @@ class Emitter {
             if (un.kind == kAdd || (un.kind == kSub && slot == 0)) {
             } else if (un.kind == kSub) {
                 emit(simple(OP_UN, U.lanes, 0, kUnNeg));
+            } else if (un.kind == kMul && G->insts[other].kind == kExt) {
+                // the gradient in A times the other operand, which comes straight from memory
+                emit(load_and_blend(other, U.lanes, kMul, false));
             } else if (un.kind == kMul) {
                 const int r = alloc();
                 emit(simple(OP_MOVR, U.lanes, r));
@@ -763,13 +787,37 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
                 const int Te = dag.nodes[e].T;
                 const int slot = E.ext_slot(e, kGradOut);
                 const bool direct = mine.size() == 1 && G.insts[mine[0]].ctx == 0 && G.insts[mine[0]].lanes == Te;
-                int acc = -1;
-                if (!direct) {
+                // no hand-over among the leaves: their contributions are summed in a register instead of LDS floats
+                bool local = !direct;
+                for (int i : mine)
+                    if (G.insts[i].lanes != Te || (G.insts[i].ctx != 0 && !pulls.count(i))) local = false;
+                int acc = -1, racc = -1;
+                if (!direct && !local) {
                     acc = E.persist(Te);
                     E.emit(Emitter::simple(OP_PSET, Te, 0, 0, acc));
                 }
-                for (int i : mine) {
+                bool first_term = true;
+                auto add_term = [&](int lanes) {  // A holds one more contribution
+                    if (local) {
+                        if (!first_term) {
+                            E.emit(Emitter::simple(OP_BIN, Te, racc, kAdd | kBinRegIsLhs));
+                            E.release(racc);
+                            racc = -1;
+                        }
+                        first_term = false;
+                        return;
+                    }
+                    Instr p = Emitter::simple(OP_PADD, lanes, 0, 0, acc);
+                    p.b = (uint16_t)Te;
+                    E.emit(p);
+                };
+                for (size_t mi = 0; mi < mine.size(); mi++) {
+                    const int i = mine[mi];
                     const Inst& L = G.insts[i];
+                    if (local && !first_term) {  // (the sum so far waits in a register while the next term is computed)
+                        racc = E.alloc();
+                        E.emit(Emitter::simple(OP_MOVR, Te, racc));
+                    }
                     auto pl = pulls.find(i);
                     if (pl != pulls.end()) {  // fetched from the displaced copy of the unit
                         int idx = 1;
@@ -779,17 +827,13 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
                         E.emit(E.positional(OP_MASK, pl->second.mask_ctx, L.lanes));
                         E.forget_graph(idx);
                         E.use(G, 0);
-                        Instr p = Emitter::simple(OP_PADD, L.lanes, 0, 0, acc);
-                        p.b = (uint16_t)Te;
-                        E.emit(p);
+                        add_term(L.lanes);
                         continue;
                     }
                     E.grad(i);
                     if (direct) break;
                     if (L.ctx == 0) {
-                        Instr p = Emitter::simple(OP_PADD, L.lanes, 0, 0, acc);
-                        p.b = (uint16_t)Te;
-                        E.emit(p);
+                        add_term(L.lanes);
                     } else {
                         if (!G.ctxs[L.ctx].win && L.lanes != Te) throw Fail{"a shifted read of an external tensor with replicated taps"};
                         Instr x = E.positional(OP_XADD, L.ctx, L.lanes);
@@ -799,7 +843,7 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
                         E.emit(x);
                     }
                 }
-                if (!direct) E.emit(Emitter::simple(OP_PLD, Te, 0, 0, acc));
+                if (!direct && !local) E.emit(Emitter::simple(OP_PLD, Te, 0, 0, acc));
                 Instr st = Emitter::simple(OP_ST, Te, 0, 0, slot);
                 E.ext[slot].store_instr = E.pg.n_instr;
                 E.emit(st);
@@ -867,6 +911,7 @@ double program_cost(const Program& pg) {
             double w = 1;
             switch (I.op) {
             case OP_LD:
+            case OP_BINLD:
             case OP_ST: w = 4; break;
             case OP_XADD: w = 6; break;
             case OP_UN:
@@ -888,7 +933,7 @@ double program_cost(const Program& pg) {
 
 std::string dump(const Program& pg) {
     static const char* names[] = {"LD", "MASK", "UN", "MOVR", "MOVA", "BIN", "FOLD", "SMT", "ST", "UNBX", "BING", "SMTBX", "FOLDBX",
-                                  "PSET", "PADD", "PLD", "SMCSTAT", "SMCAPPLY", "SMCDOT", "SMCBX", "XADD"};
+                                  "PSET", "PADD", "PLD", "SMCSTAT", "SMCAPPLY", "SMCDOT", "SMCBX", "XADD", "BINLD"};
     std::ostringstream os;
     os << "program: C=" << pg.C << " HxW=" << pg.H << "x" << pg.W << " vec=" << pg.vec << " own=" << pg.own_threads << " halo=" << pg.halo_threads
        << " unroll=" << pg.unroll << " tiles=" << pg.tiles << " chunk=" << pg.chunk << " slices=" << pg.slices << " threads=" << pg.threads << " persist=" << pg.n_persist

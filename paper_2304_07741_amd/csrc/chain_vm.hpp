@@ -468,6 +468,54 @@ struct Env {
     int rstride = 0;  // floats between consecutive register pieces of a thread
 };
 
+// The loads of OP_LD / OP_BINLD: lanes [0, T) of every channel of the trip into dst.
+template <int TM, int V, int U>
+CHAIN_HD void vm_ld(const Program& pg, const Geo& g, const Instr& I, const Env& ev, const Thread& th, float* dst, int T) {
+    constexpr int TV = TM * V;
+    const Tensor e = vm_tensor(pg, g, I.a);
+#pragma unroll
+    for (int u = 0; u < U; u++)
+        if (u < ev.h) {
+            int dh, dw;
+            vm_offset(pg, I.b, ev.c + u, dh, dw);
+            const int chan = (th.n * g.C + ev.c + u) * e.T;  // first plane of (image, channel): uniform
+            if (I.kind & kWin) {
+                const int KH = I.r >> 4, KW = I.r & 15;
+#pragma unroll
+                for (int t = 0; t < TM; t++)
+                    if (t < T) {
+                        int oh, ow;
+                        vm_tap(t, KH, KW, oh, ow);
+                        vm_load_at<V>(e, g, th, chan, dh + oh, dw + ow, dst + u * TV + t * V);
+                    }
+            } else {
+#pragma unroll
+                for (int t = 0; t < TM; t++)
+                    if (t < T) {
+                        const int te = (I.kind & kExtTaps) ? (t < e.T ? t : t % e.T) : 0;
+                        vm_load_at<V>(e, g, th, chan + te, dh, dw, dst + u * TV + t * V);
+                    }
+            }
+        }
+}
+
+// A = blend(X, A) (x_lhs) or blend(A, X), lanes [0, T) of every channel.  min and max return the same value whichever
+// side is the LHS; the sides matter for sub only.
+template <int TM, int V, int U>
+CHAIN_HD void vm_blend_lanes(int kind, bool x_lhs, const float* X, float* A, int T) {
+    switch (kind) {
+    case 0: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] + A[e];); break;
+    case 1: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * A[e];); break;
+    case 2:
+        CHAIN_CASE;
+        if (x_lhs) CHAIN_EACH(T, e, l, A[e] = X[e] - A[e];);
+        else CHAIN_EACH(T, e, l, A[e] = A[e] - X[e];);
+        break;
+    case 3: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] <= A[e] ? X[e] : A[e];); break;
+    default: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] >= A[e] ? X[e] : A[e];); break;
+    }
+}
+
 // Every instruction except OP_XADD.  Pm: this thread's persistent floats.  A float that lives across the channel loop
 // (softmax statistics, the sums of a softmax's adjoint: written by the prologue and the OP_SMC instructions) exists once,
 // float k of pixel v at Pm[(k * V + v) * pstride]; an accumulator of one channel (OP_PSET in a body, OP_PADD, OP_PLD,
@@ -480,33 +528,16 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env
     constexpr int TV = TM * V;
     float X[U * TV];
     switch (I.op) {
-    case OP_LD: {
+    case OP_LD:
         CHAIN_CASE;
-        const Tensor e = vm_tensor(pg, g, I.a);
-#pragma unroll
-        for (int u = 0; u < U; u++)
-            if (u < ev.h) {
-                int dh, dw;
-                vm_offset(pg, I.b, ev.c + u, dh, dw);
-                const int chan = (th.n * g.C + ev.c + u) * e.T;  // first plane of (image, channel): uniform
-                if (I.kind & kWin) {
-                    const int KH = I.r >> 4, KW = I.r & 15;
-#pragma unroll
-                    for (int t = 0; t < TM; t++)
-                        if (t < T) {
-                            int oh, ow;
-                            vm_tap(t, KH, KW, oh, ow);
-                            vm_load_at<V>(e, g, th, chan, dh + oh, dw + ow, A + u * TV + t * V);
-                        }
-                } else {
-#pragma unroll
-                    for (int t = 0; t < TM; t++)
-                        if (t < T) {
-                            const int te = (I.kind & kExtTaps) ? (t < e.T ? t : t % e.T) : 0;
-                            vm_load_at<V>(e, g, th, chan + te, dh, dw, A + u * TV + t * V);
-                        }
-                }
-            }
+        vm_ld<TM, V, U>(pg, g, I, ev, th, A, T);
+        break;
+    case OP_BINLD: {
+        CHAIN_CASE;
+        const bool sc = I.kind & kBinLdLoadedScalar;
+        vm_ld<TM, V, U>(pg, g, I, ev, th, X, sc ? 1 : T);
+        if (TM > 1 && sc) CHAIN_EACH(T, e, l, X[e] = X[e - l + l % V];);
+        vm_blend_lanes<TM, V, U>((I.kind >> kBinLdKindShift) & 7, (I.kind & kBinLdLoadedIsLhs) != 0, X, A, T);
         break;
     }
     case OP_MASK: {
@@ -568,18 +599,7 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env
         vm_reg_read<TM, V, U>(Rm, rstride, I.r, reg_sc ? 1 : T, X);
         if (TM > 1 && reg_sc) CHAIN_EACH(T, e, l, X[e] = X[e - l + l % V];);
         if (TM > 1 && acc_sc) CHAIN_EACH(T, e, l, A[e] = A[e - l + l % V];);
-        // (min and max return the same value whichever side is the LHS; the sides matter for sub only)
-        switch (kind) {
-        case 0: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] + A[e];); break;
-        case 1: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * A[e];); break;
-        case 2:
-            CHAIN_CASE;
-            if (reg_lhs) CHAIN_EACH(T, e, l, A[e] = X[e] - A[e];);
-            else CHAIN_EACH(T, e, l, A[e] = A[e] - X[e];);
-            break;
-        case 3: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] <= A[e] ? X[e] : A[e];); break;
-        default: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] >= A[e] ? X[e] : A[e];); break;
-        }
+        vm_blend_lanes<TM, V, U>(kind, reg_lhs, X, A, T);
         break;
     }
     case OP_FOLD: {
