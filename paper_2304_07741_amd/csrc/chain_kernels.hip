@@ -162,7 +162,8 @@ void run(const Program& pg, hipStream_t stream) {
         else if (v == 2) launch<1, 2>(pg, stream);
         else launch<1, 1>(pg, stream);
     } else if (pg.tm <= 9) {
-        if (v == 2) launch<9, 2>(pg, stream);
+        if (v == 4) launch<9, 4>(pg, stream);
+        else if (v == 2) launch<9, 2>(pg, stream);
         else launch<9, 1>(pg, stream);
     } else {
         launch<25, 1>(pg, stream);

@@ -10,15 +10,15 @@ namespace chain {
 // Registers of the kernel instance with TM lanes (the planner must not use more).
 constexpr int regs_for(int tm) { return tm <= 1 ? 10 : (tm <= 9 ? 6 : 4); }
 
-// Pixels per thread the instances with TM lanes exist for: 16 ... 1 without taps, 2 or 1 up to 9 taps, 1 beyond.
-constexpr int max_vec_for(int tm) { return tm <= 1 ? 16 : (tm <= 9 ? 2 : 1); }
+// Pixels per thread the instances with TM lanes exist for: 16 ... 1 without taps, 4, 2 or 1 up to 9 taps, 1 beyond.
+constexpr int max_vec_for(int tm) { return tm <= 1 ? 16 : (tm <= 9 ? 4 : 1); }
 
 // Largest workgroup of that instance (the tap vectors of a thread live in registers: wider lanes, fewer threads).
 constexpr int max_threads_for(int) { return 512; }
 
 // Channels per trip of the instance with TM lanes and `vec` pixels per thread: 16 lanes in all without taps (so that a
 // thread with few pixels still has 16 independent loads in flight), 2 x 9 lanes up to 9 taps, one channel beyond.
-constexpr int unroll_for(int tm, int vec) { return tm <= 1 ? 16 / vec : (tm <= 9 ? 2 / vec : 1); }
+constexpr int unroll_for(int tm, int vec) { return tm <= 1 ? 16 / vec : (tm <= 9 && vec == 1 ? 2 : 1); }
 
 // 16-byte pieces of a register of the instance with `tm` lanes and `vec` pixels per thread (all its channels' lanes).
 constexpr int reg_pieces_of(int tm, int vec) { return ((tm <= 1 ? 1 : (tm <= 9 ? 9 : 25)) * vec * unroll_for(tm, vec) + 3) / 4; }
