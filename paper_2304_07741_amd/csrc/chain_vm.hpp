@@ -232,7 +232,7 @@ __device__ __forceinline__ void vm_store(const Tensor& e, int elem, const float*
                 tile::u32x4 d;
 #pragma unroll
                 for (int k = 0; k < 4; k++) d[k] = tile::pack_bf16(in[8 * q + 2 * k], in[8 * q + 2 * k + 1]);
-                tile::bstore16(e.rs, o + 16 * q, d);
+                tile::bstore16_nt(e.rs, o + 16 * q, d);
             }
         } else if (V == 4) {
             vm_u32x2 d;
@@ -261,7 +261,7 @@ __device__ __forceinline__ void vm_store(const Tensor& e, int elem, const float*
                 tile::u32x4 d;
 #pragma unroll
                 for (int k = 0; k < 4; k++) d[k] = __float_as_uint(v[4 * q + k]);
-                tile::bstore16(e.rs, o + 16 * q, d);
+                tile::bstore16_nt(e.rs, o + 16 * q, d);
             }
         } else {
 #pragma unroll
