@@ -610,8 +610,10 @@ double geometry_for(Program& pg, const Dag& dag, int C, int64_t reach_px, bool a
     const double trips_per_thread = (double)ceil_div(pg.chunk, pg.slices * pg.unroll);
     const double threads_total = (double)dag.N * pg.tiles * pg.chunks * pg.threads;
     const double wgs_per_cu = std::max(1.0, std::min(1024.0 / pg.threads, std::floor(160.0 * 1024.0 / (double)(lds_bytes(pg) + 4352))));
-    const double rounds = std::max(1.0, threads_total / (256.0 * wgs_per_cu * pg.threads));
-    return trips_per_thread * (8.0 + (V + 4.0) * pg.unroll) * rounds + 4.0;  // (+ the workgroup's start-up)
+    // (whole rounds: a round that a few left-over workgroups make takes as long as a full one)
+    const double rounds = std::max(1.0, std::ceil(threads_total / (256.0 * wgs_per_cu * pg.threads) - 0.05));
+    // (a work item also costs its set-up: the thread's position, the pass headers; worth about 6 of these units)
+    return (6.0 + trips_per_thread * (8.0 + (V + 4.0) * pg.unroll)) * rounds;
 }
 
 // Pixels per thread, threads per slice and trips per thread: whatever the estimate likes best.
@@ -629,7 +631,7 @@ void set_geometry(Program& pg, const Dag& dag, int C, int64_t reach_px, bool all
     for (int V = max_vec_for(pg.tm); V >= 1; V /= 2) {
         if (HW % V != 0 || dag.W < V) continue;
         for (int pt = 64; pt <= max_threads_for(pg.tm); pt += 64)
-            for (int trips = 1; trips <= (all_channels ? 1 : 4); trips *= 2) {
+            for (int trips = 1; trips <= (all_channels ? 1 : 8); trips *= 2) {
                 Program q = pg;
                 const double cost = geometry_for(q, dag, C, reach_px, all_channels, V, pt, trips);
                 if (cost < 0) continue;
