@@ -74,6 +74,9 @@ def make_case(name, batch=None):
     kw = {} if batch is None else {"N": int(batch)}
     if name == "shift_residual":
         return wl.config2(**kw)
+    if name.startswith("shift_residual_c"):  # shift_residual_cC_hH: the same DAG at another shape (C/4 channels per FC group)
+        c, h = name[len("shift_residual_c"):].split("_h")
+        return wl.config2(C=int(c), H=int(h), **kw)
     if name == "involution":
         return wl.config3(**kw)
     if name.startswith("sampled_c"):

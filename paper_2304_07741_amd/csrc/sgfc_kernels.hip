@@ -220,14 +220,14 @@ __device__ __forceinline__ void bwd_tile(const Params& P, rsrc_t rx, rsrc_t rdy,
             for (int j = 0; j < 4; j++)
                 reload_if_partial(dya[mo][j], rdy, liveA ? dyg + ((mo * 16 + 4 * r + j) * P.P + pA - off) * 2 : kOob, P.N * Cout * P.P * 2);
     }
-    if (RES) {
+    // (the unshifted dy of the residual: with one 16-channel block per group it is fetched with everything else; with
+    // more the registers are short, and each block's rows are fetched just ahead of its dx)
+    if (RES && KC == 1) {
 #pragma unroll
-        for (int kc = 0; kc < KC; kc++)
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                dyu[kc][j] = bload16_nt(rdy, liveA ? dyg + ((kc * 16 + 4 * r + j) * P.P + pA) * 2 : kOob);
-                pin(dyu[kc][j]);
-            }
+        for (int j = 0; j < 4; j++) {
+            dyu[0][j] = bload16_nt(rdy, liveA ? dyg + ((4 * r + j) * P.P + pA) * 2 : kOob);
+            pin(dyu[0][j]);
+        }
     }
     // x -> LDS rows (channel 4r+j, unit s) and -> MFMA operands
     short4_t xq[KC][8];
@@ -273,6 +273,11 @@ __device__ __forceinline__ void bwd_tile(const Params& P, rsrc_t rx, rsrc_t rdy,
     }
 #pragma unroll
     for (int kc = 0; kc < KC; kc++) {
+        if (RES && KC > 1) {
+            asm volatile("" ::: "memory");  // (not earlier: the registers are needed until here)
+#pragma unroll
+            for (int j = 0; j < 4; j++) dyu[kc][j] = bload16_nt(rdy, liveA ? dyg + ((kc * 16 + 4 * r + j) * P.P + pA) * 2 : kOob);
+        }
         float4_t dxs[8];
 #pragma unroll
         for (int q = 0; q < 8; q++) {
@@ -381,6 +386,11 @@ template <int KC, int MO, int ACT, bool RES>
 __global__ __launch_bounds__(64 * kWaves) void k_bwd_wide(Params P) {
     bwd_body<KC, MO, ACT, RES>(P);
 }
+// Groups of 32 channels: two wavefronts per SIMD is what the tile's registers allow.
+template <int KC, int MO, int ACT, bool RES>
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_bwd_two(Params P) {
+    bwd_body<KC, MO, ACT, RES>(P);
+}
 
 // dW[g][e] = sum over the group's partials, in order.  One block per (group, 8 elements): 128 segments of
 // partials are summed by 128 threads per element and combined by a fixed-order tree in LDS.
@@ -408,38 +418,39 @@ __global__ __launch_bounds__(1024) void k_dw_reduce(const float* __restrict__ pa
 
 }  // namespace
 
-bool supported(int KC, int MO) { return KC == 1 && MO == 1; }
+bool supported(int KC, int MO) { return KC == MO && (KC == 1 || KC == 2); }
 
 template <int ACT, bool RES>
-static void launch_fwd(const Params& P, hipStream_t s) {
+static void launch_fwd(const Params& P, int W, hipStream_t s) {
     const dim3 grid((unsigned)((P.chunks + kWaves - 1) / kWaves), (unsigned)P.G, (unsigned)P.N);
-    if (P.total_tiles) CANVAS_LAUNCH((k_fwd<1, 1, ACT, RES>), grid, dim3(64 * kWaves), 0, s, P);
+    if (!P.total_tiles) return;
+    if (W == 2) CANVAS_LAUNCH((k_fwd<2, 2, ACT, RES>), grid, dim3(64 * kWaves), 0, s, P);
+    else CANVAS_LAUNCH((k_fwd<1, 1, ACT, RES>), grid, dim3(64 * kWaves), 0, s, P);
 }
 template <int ACT, bool RES>
-static void launch_bwd(const Params& P, hipStream_t s) {
+static void launch_bwd(const Params& P, int W, hipStream_t s) {
     const dim3 grid((unsigned)P.wgs_per_group, (unsigned)P.G);
     if (!P.total_tiles) return;
-    if (ACT == 2 || ACT == 3) CANVAS_LAUNCH((k_bwd_wide<1, 1, ACT, RES>), grid, dim3(64 * kWaves), 0, s, P);
+    if (W == 2) CANVAS_LAUNCH((k_bwd_two<2, 2, ACT, RES>), grid, dim3(64 * kWaves), 0, s, P);
+    else if (ACT == 2 || ACT == 3) CANVAS_LAUNCH((k_bwd_wide<1, 1, ACT, RES>), grid, dim3(64 * kWaves), 0, s, P);
     else CANVAS_LAUNCH((k_bwd<1, 1, ACT, RES>), grid, dim3(64 * kWaves), 0, s, P);
 }
 
 #define SGFC_DISPATCH(fn)                                                        \
     switch (P.act) {                                                             \
-    case kActNone: P.residual ? fn<kActNone, true>(P, s) : fn<kActNone, false>(P, s); break; \
-    case 0: P.residual ? fn<0, true>(P, s) : fn<0, false>(P, s); break;          \
-    case 1: P.residual ? fn<1, true>(P, s) : fn<1, false>(P, s); break;          \
-    case 2: P.residual ? fn<2, true>(P, s) : fn<2, false>(P, s); break;          \
-    default: P.residual ? fn<3, true>(P, s) : fn<3, false>(P, s); break;         \
+    case kActNone: P.residual ? fn<kActNone, true>(P, KC, s) : fn<kActNone, false>(P, KC, s); break; \
+    case 0: P.residual ? fn<0, true>(P, KC, s) : fn<0, false>(P, KC, s); break;          \
+    case 1: P.residual ? fn<1, true>(P, KC, s) : fn<1, false>(P, KC, s); break;          \
+    case 2: P.residual ? fn<2, true>(P, KC, s) : fn<2, false>(P, KC, s); break;          \
+    default: P.residual ? fn<3, true>(P, KC, s) : fn<3, false>(P, KC, s); break;         \
     }
 
 void forward(const Params& P, int KC, int MO, hipStream_t s) {
-    (void)KC;
     (void)MO;
     SGFC_DISPATCH(launch_fwd)
 }
 
 void backward(const Params& P, int KC, int MO, hipStream_t s) {
-    (void)KC;
     (void)MO;
     SGFC_DISPATCH(launch_bwd)
 }

@@ -173,6 +173,30 @@ def test_fused_shift_fc_variants(harness, oracle, idx):
     r.close()
 
 
+@pytest.mark.parametrize("idx", range(len(SGFC_VARIANTS)))
+def test_fused_shift_fc_groups_of_32(harness, oracle, idx):
+    """The same family with 32 channels per FC group (two 16-channel blocks per group and side of the contraction)."""
+    offs, unary, res, N, H, W = SGFC_VARIANTS[idx]
+    lines, k = [], 0
+    for g, (dh, dw) in enumerate(offs):
+        lines.append(f"%{k + 1} = shift %{k} dh={dh} dw={dw} c0={32 * g} c1={32 * g + 32}\n")
+        k += 1
+    lines.append(f"%{k + 1} = fc %{k} groups=4 out=128\n")
+    k += 1
+    if unary:
+        lines.append(f"%{k + 1} = unary %{k} op={unary}\n")
+        k += 1
+    if res:
+        lines.append(f"%{k + 1} = binary %{k} %0 op=add\n")
+        k += 1
+    lines.append(f"output %{k}\n")
+    case = _mk("".join(lines), (N, 128, H, W), "bf16", 170 + idx, [(4, 32, 32)], f"sgfc32_{idx}")
+    res_, r, dy = harness.run_case(case)
+    assert r.info.fused == 1 and [d["name"] for d in r.launches(0)] == ["sgfc_fwd"], "the fused lowering was not selected"
+    check_against_oracle(oracle, case, res_, dy)
+    r.close()
+
+
 GFC_CASES = [
     # (body, weight shapes, input shape): the MFMA grouped-FC kernels on awkward sizes
     ("%1 = unfold %0 kh=3 kw=3\n%2 = fc %1 groups=1 out=40\noutput %2\n", [(1, 40, 180)], (5, 20, 7, 7)),      # 7x7 planes, odd K
