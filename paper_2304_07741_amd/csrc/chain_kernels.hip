@@ -11,6 +11,7 @@
 
 #include "chain_vm.hpp"
 #include "launch.hpp"
+#include "tile_util.hpp"
 
 namespace canvas {
 namespace chain {
@@ -59,7 +60,9 @@ __global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program) {
     // The workgroup stays and walks over its share of the work items (image, tile, channel range): the program is staged
     // once per workgroup, not once per item.  item = (image * tiles + tile) * chunks + chunk
     const int items = g.N * tiles * chunks;
-    for (int item = blockIdx.x; item < items; item += gridDim.x) {
+    unsigned first, unused;
+    tile::xcd_order(first, unused);  // (the tiles of an image share halos and window rows: an XCD takes neighbouring items)
+    for (int item = (int)first; item < items; item += gridDim.x) {
         const int chunk_id = item % chunks;
         const int tile = (item / chunks) % tiles;
         // the workgroup's threads: `slices` groups of PT threads; a group is one thread per V pixels of the tile (+ halo)

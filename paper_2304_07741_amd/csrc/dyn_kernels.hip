@@ -114,7 +114,9 @@ template <int KH, int KW, int CPT>
 __global__ __launch_bounds__(256) void k_fwd(Params P) {
     constexpr int HH = KH / 2, HW = KW / 2, TV = KH * KW;
     const int CG = (P.C + CPT - 1) / CPT;
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    unsigned bx, by;
+    xcd_order(bx, by);  // (neighbouring blocks read overlapping window rows)
+    const long long idx = (long long)bx * 256 + threadIdx.x;
     if (idx >= (long long)P.N * CG * P.upi) return;
     const int ng = (int)div_magic((uint32_t)idx, P.magicUpi);
     const int p = ((int)idx - ng * P.upi) * 8;
@@ -158,7 +160,9 @@ template <int KH, int KW, int CPT>
 __global__ __launch_bounds__(256) void k_bwd_dx(Params P) {
     constexpr int HH = KH / 2, HW = KW / 2, TV = KH * KW;
     const int CG = (P.C + CPT - 1) / CPT;
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    unsigned bx, by;
+    xcd_order(bx, by);  // (neighbouring blocks read overlapping window rows)
+    const long long idx = (long long)bx * 256 + threadIdx.x;
     if (idx >= (long long)P.N * CG * P.upi) return;
     const int ng = (int)div_magic((uint32_t)idx, P.magicUpi);
     const int p = ((int)idx - ng * P.upi) * 8;
@@ -204,7 +208,9 @@ template <int KH, int KW>
 __global__ __launch_bounds__(256) void k_bwd_da(Params P) {
     constexpr int HH = KH / 2, HW = KW / 2, TV = KH * KW;
     const int cs = threadIdx.x & 15;
-    const long long U = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
+    unsigned bx, kh_of_block;
+    xcd_order(bx, kh_of_block);  // (neighbouring blocks read overlapping window rows)
+    const long long U = (long long)bx * 16 + (threadIdx.x >> 4);
     const bool live = U < (long long)P.N * P.upi;
     const int n = live ? (int)div_magic((uint32_t)U, P.magicUpi) : 0;
     const int p = live ? ((int)U - n * P.upi) * 8 : 0;
@@ -213,7 +219,7 @@ __global__ __launch_bounds__(256) void k_bwd_da(Params P) {
     const Pix g = pixels(P, p);
     const int nvalid = min(8, P.P - p);
     {
-        const int kh = blockIdx.y;  // one window row per block: KH times the parallelism, the rows are independent
+        const int kh = (int)kh_of_block;  // one window row per block: KH times the parallelism, the rows are independent
         float acc[KW][8];
 #pragma unroll
         for (int kw = 0; kw < KW; kw++)

@@ -124,10 +124,12 @@ template <int MO, bool SRC_F32, bool DST_F32, bool TAPS>
 __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x * kWaves + wave;
+    unsigned bx, by;
+    xcd_order(bx, by);  // (neighbouring tiles share window halos, the output tiles of a group share their rows)
+    const int tile = (int)bx * kWaves + wave;
     const int total_units = P.N * P.upi;
     if (tile * 16 >= total_units) return;
-    const int g = blockIdx.y / P.otiles, ot = blockIdx.y - g * P.otiles;
+    const int g = (int)by / P.otiles, ot = (int)by - g * P.otiles;
     const int r = lane >> 4, s = lane & 15;
     const int U = tile * 16 + s;
     const bool live = U < total_units;

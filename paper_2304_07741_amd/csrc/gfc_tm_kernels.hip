@@ -64,13 +64,15 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     static_assert(HW <= 2, "halo of two pixels");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x * (kWaves / KS) + wave / KS, ks = wave % KS;
+    unsigned bx, by;
+    xcd_order(bx, by);  // (neighbouring tiles share window halos, the output tiles of a group share their rows)
+    const int tile = (int)bx * (kWaves / KS) + wave / KS, ks = wave % KS;
     const int total_units = P.N * P.upi;
     const bool active = tile * 16 < total_units;
     if constexpr (KS == 1 && !WL) {
         if (!active) return;
     }
-    const int gmi = blockIdx.y / P.otiles, ot = blockIdx.y - gmi * P.otiles;
+    const int gmi = (int)by / P.otiles, ot = (int)by - gmi * P.otiles;
     const int gcount = min(P.gm, P.G - gmi * P.gm);
     const int Rm = gcount * P.R, Om = gcount * P.Og;
     const int r = lane >> 4, s = lane & 15;

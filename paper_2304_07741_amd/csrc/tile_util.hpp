@@ -27,6 +27,19 @@ __device__ __forceinline__ void bstore16(rsrc_t r, int byte_off, u32x4 v) { __bu
 __device__ __forceinline__ u32x4 bload16_nt(rsrc_t r, int byte_off) { return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 2); }
 __device__ __forceinline__ void bstore16_nt(rsrc_t r, int byte_off, u32x4 v) { __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, 2); }
 
+// The chip's 8 XCDs (32 compute units and one L2 each) take the workgroups of a launch in turn: workgroup number b
+// (x fastest, then y) runs on XCD b % 8.  Kernels whose neighbouring tiles read common data (window halos, the same
+// rows for several output tiles) hand out their tiles in this order instead: XCD k works on one contiguous eighth of
+// the tile sequence, so what neighbours share is found in its own L2 instead of being fetched once per XCD.
+__device__ __forceinline__ void xcd_order(unsigned& bx, unsigned& by) {
+    const unsigned gx = gridDim.x, total = gx * gridDim.y;
+    const unsigned lin = blockIdx.y * gx + blockIdx.x;
+    const unsigned xcd = lin & 7u, idx = lin >> 3, per = total >> 3, rem = total & 7u;
+    const unsigned seq = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    by = seq / gx;
+    bx = seq - by * gx;
+}
+
 // A 16-byte access that begins before the buffer is dropped as a whole by the hardware; one that runs past
 // the end keeps the dwords that lie completely inside and loses the rest, including a bf16 element that
 // shares its dword with the end (measured on gfx950).  Only a shifted access at the very start or end of a
