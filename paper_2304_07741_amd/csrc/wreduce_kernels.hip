@@ -43,7 +43,14 @@ __global__ __launch_bounds__(256) void k_reduce(Jobs jobs) {
         const int end = min(J.slices, (seg + 1) * per);
         const float* src = J.partial + idx;
         int k = seg * per;
-        for (; k + 4 <= end; k += 4) {  // four independent loads in flight, summed in slice order
+        for (; k + 16 <= end; k += 16) {  // sixteen independent loads in flight (a round trip to memory each), summed in slice order
+            float v[16];
+#pragma unroll
+            for (int i = 0; i < 16; i++) v[i] = src[(long long)(k + i) * J.count];
+#pragma unroll
+            for (int i = 0; i < 16; i++) sum += v[i];
+        }
+        for (; k + 4 <= end; k += 4) {
             float v[4];
 #pragma unroll
             for (int i = 0; i < 4; i++) v[i] = src[(long long)(k + i) * J.count];
