@@ -1,7 +1,7 @@
 // One thread owns 8 consecutive pixels (a 16-byte bf16 access).  Window rows are read as the 8 pixels plus
 // two on either side; a tap is used only where its source pixel lies inside the image (a select, so what
 // the out-of-image positions hold never matters).  All three kernels are memory/latency-bound
-// element-wise passes; the channel sum of backward_da is a fixed-order butterfly over 16 lanes.
+// element-wise passes; the channel sum of the gradient of a is a fixed-order butterfly over 16 lanes.
 #include "dyn_kernels.hpp"
 
 #include "launch.hpp"
@@ -157,11 +157,9 @@ __global__ __launch_bounds__(256) void k_fwd(Params P) {
 }
 
 template <int KH, int KW, int CPT>
-__global__ __launch_bounds__(256) void k_bwd_dx(Params P) {
+__device__ __forceinline__ void bwd_dx_block(const Params& P, unsigned bx) {
     constexpr int HH = KH / 2, HW = KW / 2, TV = KH * KW;
     const int CG = (P.C + CPT - 1) / CPT;
-    unsigned bx, by;
-    xcd_order(bx, by);  // (neighbouring blocks read overlapping window rows)
     const long long idx = (long long)bx * 256 + threadIdx.x;
     if (idx >= (long long)P.N * CG * P.upi) return;
     const int ng = (int)div_magic((uint32_t)idx, P.magicUpi);
@@ -205,11 +203,9 @@ __global__ __launch_bounds__(256) void k_bwd_dx(Params P) {
 
 // block = 16 units x 16 channel slices (lane % 16 = slice: channels slice, slice + 16, ...) of one window row
 template <int KH, int KW>
-__global__ __launch_bounds__(256) void k_bwd_da(Params P) {
+__device__ __forceinline__ void bwd_da_block(const Params& P, unsigned bx, unsigned kh_of_block) {
     constexpr int HH = KH / 2, HW = KW / 2, TV = KH * KW;
     const int cs = threadIdx.x & 15;
-    unsigned bx, kh_of_block;
-    xcd_order(bx, kh_of_block);  // (neighbouring blocks read overlapping window rows)
     const long long U = (long long)bx * 16 + (threadIdx.x >> 4);
     const bool live = U < (long long)P.N * P.upi;
     const int n = live ? (int)div_magic((uint32_t)U, P.magicUpi) : 0;
@@ -272,6 +268,22 @@ __global__ __launch_bounds__(256) void k_bwd_da(Params P) {
     (void)atotal;
 }
 
+// The two gradients of the window product in one launch: dx = dyn^T(a, du) and da = sum_c du . U read the same du and
+// neither fills the chip alone.  The first da_blocks blocks of the sequence (units x window rows, the longer job) work
+// on da, the rest on dx.
+template <int KH, int KW, int CPT>
+__global__ __launch_bounds__(256) void k_bwd_dx_da(Params P, unsigned da_blocks_x) {
+    unsigned seq, unused;
+    xcd_order(seq, unused);  // (neighbouring blocks read overlapping window rows)
+    const unsigned da_blocks = da_blocks_x * KH;
+    if (seq < da_blocks) {
+        const unsigned kh = seq / da_blocks_x;
+        bwd_da_block<KH, KW>(P, seq - kh * da_blocks_x, kh);
+    } else {
+        bwd_dx_block<KH, KW, CPT>(P, seq - da_blocks);
+    }
+}
+
 template <typename F33, typename F55>
 void dispatch(const Params& P, F33 f33, F55 f55) {
     if (P.KH == 3) f33();
@@ -296,22 +308,19 @@ void forward(const Params& P, hipStream_t s) {
         dispatch(P, [&] { CANVAS_LAUNCH((k_fwd<3, 3, 1>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_fwd<5, 5, 1>), grid, block, 0, s, P); });
 }
 
-void backward_dx(const Params& P, hipStream_t s) {
+void backward_dx_da(const Params& P, hipStream_t s) {
     const int cpt = channels_per_thread(P);
     const long long total = (long long)P.N * ((P.C + cpt - 1) / cpt) * P.upi;
-    if (total == 0) return;
-    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-    if (cpt == 4)
-        dispatch(P, [&] { CANVAS_LAUNCH((k_bwd_dx<3, 3, 4>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_bwd_dx<5, 5, 4>), grid, block, 0, s, P); });
-    else
-        dispatch(P, [&] { CANVAS_LAUNCH((k_bwd_dx<3, 3, 1>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_bwd_dx<5, 5, 1>), grid, block, 0, s, P); });
-}
-
-void backward_da(const Params& P, hipStream_t s) {
     const long long units = (long long)P.N * P.upi;
-    if (units == 0) return;
-    const dim3 grid((unsigned)((units + 15) / 16), (unsigned)P.KH), block(256);
-    dispatch(P, [&] { CANVAS_LAUNCH((k_bwd_da<3, 3>), grid, block, 0, s, P); }, [&] { CANVAS_LAUNCH((k_bwd_da<5, 5>), grid, block, 0, s, P); });
+    if (total == 0) return;
+    const unsigned dx_blocks = (unsigned)((total + 255) / 256), da_x = (unsigned)((units + 15) / 16);
+    const dim3 grid(dx_blocks + da_x * (unsigned)P.KH), block(256);
+    if (cpt == 4)
+        dispatch(P, [&] { CANVAS_LAUNCH((k_bwd_dx_da<3, 3, 4>), grid, block, 0, s, P, da_x); },
+                 [&] { CANVAS_LAUNCH((k_bwd_dx_da<5, 5, 4>), grid, block, 0, s, P, da_x); });
+    else
+        dispatch(P, [&] { CANVAS_LAUNCH((k_bwd_dx_da<3, 3, 1>), grid, block, 0, s, P, da_x); },
+                 [&] { CANVAS_LAUNCH((k_bwd_dx_da<5, 5, 1>), grid, block, 0, s, P, da_x); });
 }
 
 }  // namespace dyn

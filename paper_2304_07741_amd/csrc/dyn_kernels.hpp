@@ -25,8 +25,10 @@ struct Params {
 
 bool supported(int KH, int KW);
 void forward(const Params& P, hipStream_t s);
-void backward_dx(const Params& P, hipStream_t s);  // dx[c](p') = scale * sum_t a[t](p' - off t) * du[c](p' - off t)
-void backward_da(const Params& P, hipStream_t s);  // da[t](p) = scale * sum_c du[c](p) * x[c](p + off t)
+// One launch for both gradients of the product (they read the same du and neither fills the chip alone):
+//     dx[c](p') = scale * sum_t a[t](p' - off t) * du[c](p' - off t)
+//     da[t](p)  = scale * sum_c du[c](p) * x[c](p + off t)
+void backward_dx_da(const Params& P, hipStream_t s);
 
 }  // namespace dyn
 }  // namespace canvas

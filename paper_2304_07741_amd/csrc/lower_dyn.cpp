@@ -6,7 +6,7 @@
 // tap t of the channels of group g; (image, group) pairs are then independent, and the kernels see N*G
 // "images" of C/G channels.  The unfolded tensor and the product m are never materialised:
 //     forward   l (fp32), a (fp32), u (bf16) -> y
-//     backward  dW2 = dy . u;  du = FC2^T dy;  dx = dyn^T(a, du);  da = sum_c du . U;  dl = softmax'(a, da);
+//     backward  dW2 = dy . u;  du = FC2^T dy;  dx = dyn^T(a, du) and da = sum_c du . U (one launch);  dl = softmax'(a, da);
 //               dW1 = dl . x;  dx += FC1^T dl
 #include <algorithm>
 
@@ -135,19 +135,14 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
     // backward (forward must have run with the same workspace: a and u are read back)
     emit_wgrad(*low, dag, take, "dyn_fc2_wgrad", G2, C / G2, 1, 1, O2 / G2, w2, FcOperand{ws_at(ou), false}, in_dy, act + outb, fl2);
     emit_fc(*low, true, dag, take, "dyn_fc2_dgrad", G2, O2 / G2, 1, 1, C / G2, true, w2, in_dy, ws_at(odu), false, act + outb + 2.0 * nw2, fl2);
-    low->bwd.push_back({"dyn_apply_dx", 2.0 * act + ab, fld, [=](const RunArgs& a) {
+    low->bwd.push_back({"dyn_apply_dx_da", 3.0 * act + 2.0 * ab, 2.0 * fld, [=](const RunArgs& a) {
                             dyn::Params Q = D;
+                            Q.x = (const uint16_t*)a.x;
                             Q.a = (const float*)(a.ws + oa);
                             Q.du = (const uint16_t*)(a.ws + odu);
                             Q.dx = (uint16_t*)a.dx;
-                            dyn::backward_dx(Q, a.stream);
-                        }});
-    low->bwd.push_back({"dyn_apply_da", 2.0 * act + ab, fld, [=](const RunArgs& a) {
-                            dyn::Params Q = D;
-                            Q.x = (const uint16_t*)a.x;
-                            Q.du = (const uint16_t*)(a.ws + odu);
                             Q.da = (float*)(a.ws + oda);
-                            dyn::backward_da(Q, a.stream);
+                            dyn::backward_dx_da(Q, a.stream);
                         }});
     if (soft)
         low->bwd.push_back({"dyn_softmax_bwd", 3.0 * ab, 0, [=](const RunArgs& a) {
@@ -155,7 +150,7 @@ std::unique_ptr<Lowering> lower_dyn(const Dag& dag, bool bf16) {
                                                  a.stream, (uint16_t*)(a.ws + odl16));
                             }});
     emit_wgrad(*low, dag, take, "dyn_fc1_wgrad", G1, C / G1, 1, 1, TVa / G1, w1, in_x, FcOperand{ws_at(odl), true}, act + ab, fl1);
-    // the data gradient of FC1 adds to the dx that dyn_apply_dx has written
+    // the data gradient of FC1 adds to the dx that dyn_apply_dx_da has written
     emit_fc(*low, true, dag, take, "dyn_fc1_dgrad", G1, TVa / G1, 1, 1, C / G1, true, w1,
             soft ? FcOperand{ws_at(odl16), false} : FcOperand{ws_at(odl), true},
             [](const RunArgs& a) { return (const void*)a.dx; }, true, 2.0 * act + ab + 2.0 * nw1, fl1);
