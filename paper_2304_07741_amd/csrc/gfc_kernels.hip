@@ -124,12 +124,14 @@ template <int MO, bool SRC_F32, bool DST_F32, bool TAPS>
 __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    unsigned bx, by;
-    xcd_order(bx, by);  // (neighbouring tiles share window halos, the output tiles of a group share their rows)
+    // (sequence of the workgroups: the output tiles of one pixel tile, which read the same rows, then the pixel tiles,
+    // whose neighbours share window halos, then the groups)
+    const unsigned seq = xcd_sequence();
+    const unsigned pt = seq / (unsigned)P.otiles, bx = pt % gridDim.x;
     const int tile = (int)bx * kWaves + wave;
     const int total_units = P.N * P.upi;
     if (tile * 16 >= total_units) return;
-    const int g = (int)by / P.otiles, ot = (int)by - g * P.otiles;
+    const int g = (int)(pt / gridDim.x), ot = (int)(seq - pt * (unsigned)P.otiles);
     const int r = lane >> 4, s = lane & 15;
     const int U = tile * 16 + s;
     const bool live = U < total_units;

@@ -64,15 +64,19 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     static_assert(HW <= 2, "halo of two pixels");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    unsigned bx, by;
-    xcd_order(bx, by);  // (neighbouring tiles share window halos, the output tiles of a group share their rows)
+    // Sequence of the workgroups: the output tiles of one pixel tile first (they read the same rows: with x fastest the
+    // 1x1 FC of 512 channels fetched its input 8 times, once per output tile), then the pixel tiles (neighbours share
+    // window halos), then the merged groups.
+    const unsigned seq = xcd_sequence();
+    const unsigned otiles_u = (unsigned)P.otiles, pt = seq / otiles_u;
+    const unsigned bx = pt % gridDim.x;
     const int tile = (int)bx * (kWaves / KS) + wave / KS, ks = wave % KS;
     const int total_units = P.N * P.upi;
     const bool active = tile * 16 < total_units;
     if constexpr (KS == 1 && !WL) {
         if (!active) return;
     }
-    const int gmi = (int)by / P.otiles, ot = (int)by - gmi * P.otiles;
+    const int gmi = (int)(pt / gridDim.x), ot = (int)(seq - pt * otiles_u);
     const int gcount = min(P.gm, P.G - gmi * P.gm);
     const int Rm = gcount * P.R, Om = gcount * P.Og;
     const int r = lane >> 4, s = lane & 15;

@@ -31,13 +31,16 @@ __device__ __forceinline__ void bstore16_nt(rsrc_t r, int byte_off, u32x4 v) { _
 // (x fastest, then y) runs on XCD b % 8.  Kernels whose neighbouring tiles read common data (window halos, the same
 // rows for several output tiles) hand out their tiles in this order instead: XCD k works on one contiguous eighth of
 // the tile sequence, so what neighbours share is found in its own L2 instead of being fetched once per XCD.
-__device__ __forceinline__ void xcd_order(unsigned& bx, unsigned& by) {
+__device__ __forceinline__ unsigned xcd_sequence() {  // this workgroup's place in that order, 0 .. gridDim.x * gridDim.y - 1
     const unsigned gx = gridDim.x, total = gx * gridDim.y;
     const unsigned lin = blockIdx.y * gx + blockIdx.x;
     const unsigned xcd = lin & 7u, idx = lin >> 3, per = total >> 3, rem = total & 7u;
-    const unsigned seq = xcd * per + (xcd < rem ? xcd : rem) + idx;
-    by = seq / gx;
-    bx = seq - by * gx;
+    return xcd * per + (xcd < rem ? xcd : rem) + idx;
+}
+__device__ __forceinline__ void xcd_order(unsigned& bx, unsigned& by) {  // the place as grid coordinates, x fastest
+    const unsigned seq = xcd_sequence();
+    by = seq / gridDim.x;
+    bx = seq - by * gridDim.x;
 }
 
 // A 16-byte access that begins before the buffer is dropped as a whole by the hardware; one that runs past
