@@ -277,8 +277,9 @@ __global__ __launch_bounds__(256) void k_bwd_dx_da(Params P, unsigned da_blocks_
     xcd_order(seq, unused);  // (neighbouring blocks read overlapping window rows)
     const unsigned da_blocks = da_blocks_x * KH;
     if (seq < da_blocks) {
-        const unsigned kh = seq / da_blocks_x;
-        bwd_da_block<KH, KW>(P, seq - kh * da_blocks_x, kh);
+        // (the KH blocks of the same units read the same du and overlapping rows of x: neighbours in the sequence)
+        const unsigned units = seq / KH;
+        bwd_da_block<KH, KW>(P, units, seq - units * KH);
     } else {
         bwd_dx_block<KH, KW, CPT>(P, seq - da_blocks);
     }
