@@ -29,43 +29,50 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-# HBM bytes per launch from two `rocprofv3 --pmc` runs of this file per workload (FETCH_SIZE, then WRITE_SIZE, averages
-# per dispatch; the runtime's plain copy of 25 088 KiB reads FETCH_SIZE 12 557 -> units of 1.998 KiB, and WRITE_SIZE
-# 25 088 -> KiB; commands and tables in profiles/).  A set of figures is valid only for the kernel sources it was taken
-# on (hash below), otherwise `traffic` is null; a kernel instance that runs both the forward and the backward program
-# of a workload has one average for the two and is left out.
-_SGFC_SOURCES = ['paper_2304_07741_amd/csrc/sgfc_kernels.hip', 'paper_2304_07741_amd/csrc/tile_util.hpp', 'paper_2304_07741_amd/csrc/lower_sgfc.cpp']
-_CHAIN_SOURCES = ['paper_2304_07741_amd/csrc/chain_kernels.hip', 'paper_2304_07741_amd/csrc/chain_vm.hpp', 'paper_2304_07741_amd/csrc/chain_isa.hpp', 'paper_2304_07741_amd/csrc/chain_plan.cpp', 'paper_2304_07741_amd/csrc/chain_kernels.hpp', 'paper_2304_07741_amd/csrc/tile_util.hpp']
-TRAFFIC = {
-    "shift_residual": {"sources": _SGFC_SOURCES, "sha256": "fe8f2974588d17783936b636e312ae4f4cb6d53379a506182549f977b5faee74",
-                       "kib": {"sgfc_fwd": (14410.8 * 1.998, 25089.9), "sgfc_bwd": (26402.4 * 1.998, 25898.1)}},
-    "chain_gate": {"sources": _CHAIN_SOURCES, "sha256": "47489a2135be27722312a623bceb5a73333905647120c688b68db889eaa67a4b",
-                   "kib": {"chain_fwd": (25774.9 * 1.998, 50176.0), "chain_bwd": (55192.2 * 1.998, 50178.9)}},
-    "chain_shift_residual": {"sources": _CHAIN_SOURCES, "sha256": "47489a2135be27722312a623bceb5a73333905647120c688b68db889eaa67a4b",
-                             "kib": {"chain_fwd": (25863.5 * 1.998, 50176.0), "chain_bwd": (54357.5 * 1.998, 50176.0)}},
+# HBM bytes per launch from two `rocprofv3 --pmc` runs of this file per workload (FETCH_SIZE, then WRITE_SIZE; the runtime's
+# plain copy of 25 088 KiB reads FETCH_SIZE 12 557 -> units of 1.998 KiB, and WRITE_SIZE 25 088 -> KiB; the dispatches of
+# a run are attributed to the launches of a step by position; commands and tables in profiles/).  The figures are valid
+# only for the kernel sources they were taken on (one hash over the library's source folder), otherwise `traffic` is null.
+TRAFFIC_SHA256 = "d6216fe1621e9dc68c9cff91abd5633e4406e7f00e05521a732fe33542c26995"
+TRAFFIC_KIB = {  # workload -> launch (phase:name) -> (KiB fetched, KiB written) per launch
+    'shift_residual': {'fwd:sgfc_fwd': (28790.8, 25089.1), 'bwd:sgfc_bwd': (52679.4, 25895.6), 'bwd:sgfc_dw_reduce': (3226.7, 4.0)},
+    'involution': {'fwd:weight_prep': (326.0, 40.0), 'fwd:dyn_fc1_softmax': (6732.3, 882.0), 'fwd:dyn_apply': (7266.3, 6272.0), 'fwd:dyn_fc2': (6990.8, 6272.0), 'bwd:dyn_fc2_wgrad': (15871.7, 6656.0), 'bwd:dyn_fc2_dgrad': (6990.8, 6272.0), 'bwd:dyn_apply_dx_da': (20213.4, 7154.3), 'bwd:dyn_softmax_bwd': (2088.0, 1323.0), 'bwd:dyn_fc1_wgrad': (10051.7, 900.0), 'bwd:dyn_fc1_dgrad': (7235.0, 6272.0), 'bwd:wgrad_reduce': (7617.2, 68.5)},
+    'sampled_c64_h56': {'fwd:weight_prep': (169.0, 44.0), 'fwd:ufc_fc1_unfold': (50565.9, 50176.0), 'fwd:ufc_mid_fwd': (101104.4, 50182.0), 'fwd:ufc_fc2': (50606.6, 50176.0), 'bwd:ufc_fc2_wgrad': (100519.1, 6272.0), 'bwd:ufc_fc2_dgrad': (50606.6, 50176.0), 'bwd:ufc_mid_bwd': (152854.8, 100352.0), 'bwd:ufc_fc1_wgrad_unfold': (105580.1, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (100802.3, 50176.0), 'bwd:wgrad_reduce': (10937.7, 104.0)},
+    'sampled_c128_h28': {'fwd:weight_prep': (531.7, 104.0), 'fwd:ufc_fc1_unfold': (25630.1, 25098.6), 'fwd:ufc_mid_fwd': (50596.5, 25088.3), 'fwd:ufc_fc2': (26676.1, 25102.4), 'bwd:ufc_fc2_wgrad': (65501.0, 6656.0), 'bwd:ufc_fc2_dgrad': (26712.0, 25096.1), 'bwd:ufc_mid_bwd': (76486.0, 50176.0), 'bwd:ufc_fc1_wgrad_unfold': (61011.2, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (50828.3, 25137.2), 'bwd:wgrad_reduce': (11321.3, 416.0)},
+    'sampled_c256_h14': {'fwd:weight_prep': (2214.1, 416.0), 'fwd:ufc_fc1_unfold': (13282.0, 12565.4), 'fwd:ufc_mid_fwd': (25905.0, 12857.1), 'fwd:ufc_fc2': (14591.9, 12592.0), 'bwd:ufc_fc2_wgrad': (25344.5, 8192.0), 'bwd:ufc_fc2_dgrad': (14591.8, 12592.0), 'bwd:ufc_mid_bwd': (38884.8, 25721.4), 'bwd:ufc_fc1_wgrad_unfold': (61694.4, 6624.0), 'bwd:ufc_fc1_dgrad_unfold': (26078.0, 12615.9), 'bwd:wgrad_reduce': (14869.6, 1104.0)},
+    'sampled_c512_h7': {'fwd:weight_prep': (6709.6, 1664.0), 'fwd:ufc_fc1_unfold': (7412.6, 6274.3), 'fwd:ufc_mid_fwd': (13052.3, 6322.6), 'fwd:ufc_fc2': (10616.9, 6272.0), 'bwd:ufc_fc2_wgrad': (12804.6, 8192.0), 'bwd:ufc_fc2_dgrad': (10616.9, 6272.0), 'bwd:ufc_mid_bwd': (19622.7, 12648.2), 'bwd:ufc_fc1_wgrad_unfold': (19712.4, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (13680.0, 6275.1), 'bwd:wgrad_reduce': (12855.7, 6656.0)},
+    'chain_relu': {'fwd:chain_fwd': (50471.5, 56703.8), 'bwd:chain_bwd': (100740.6, 56529.6)},
+    'chain_gate': {'fwd:chain_fwd': (50665.4, 62822.2), 'bwd:chain_bwd': (101126.7, 59739.7)},
+    'chain_shift_residual': {'fwd:chain_fwd': (50640.0, 60116.7), 'bwd:chain_bwd': (100827.7, 57121.6)},
+    'chain_box3': {'fwd:chain_fwd': (51165.8, 50554.8), 'bwd:chain_bwd': (50760.0, 50176.0)},
+    'chain_softmax_c': {'fwd:chain_fwd': (99376.3, 56149.8), 'bwd:chain_bwd': (251307.6, 53377.6)},
 }
 
 
-def traffic_hash(sources):
+def traffic_hash():
+    import glob
     import hashlib
 
     h = hashlib.sha256()
-    for f in sources:
-        h.update(open(os.path.join(ROOT, f), "rb").read())
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2304_07741_amd", "csrc", "*"))):
+        h.update(open(f, "rb").read())
     return h.hexdigest()
 
 
-def measured_traffic(workload, kernel):
-    t = TRAFFIC.get(workload)
-    if t is None or kernel not in t["kib"]:
+_traffic_valid = None
+
+
+def measured_traffic(workload, phase, kernel):
+    global _traffic_valid
+    t = TRAFFIC_KIB.get(workload, {}).get(f"{phase}:{kernel}")
+    if t is None:
         return None
-    try:
-        if traffic_hash(t["sources"]) != t["sha256"]:
-            return None
-    except OSError:
-        return None
-    fetch, write = t["kib"][kernel]
-    return (fetch + write) * 1024.0
+    if _traffic_valid is None:
+        try:
+            _traffic_valid = traffic_hash() == TRAFFIC_SHA256
+        except OSError:
+            _traffic_valid = False
+    return (t[0] + t[1]) * 1024.0 if _traffic_valid else None
 
 
 def make_case(name, batch=None):
@@ -284,7 +291,7 @@ def roofline_of(launches, workload, fused):
         ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
     if fused:
-        roof["traffic"] = measured_traffic(workload, dom["name"])
+        roof["traffic"] = measured_traffic(workload, dom["phase"], dom["name"])
     roof["kernel"] = f"{dom['name']} ({dom['phase']})"
     roof["kernel_ms"] = dom["ms"]
     roof["algorithmic_bytes"] = dom["bytes"]
