@@ -1080,22 +1080,21 @@ Params shape(int N, int G, int R, int KH, int KW, int Og, int H, int W) {
     Q.mo = Om <= 16 ? 1 : (Om <= 32 || KW > 1 ? 2 : 4);  // windows: the buffers of two groups leave room for 32 outputs
     if (Q.mo == 4) {
         // 64 outputs per wavefront need ~200 registers (two wavefronts per SIMD, 2 048 at once), 32 outputs ~124 (four,
-        // 4 096): where the launch with 64 would need a second round of wavefronts and the one with 32 fits at once,
-        // 32 are faster although the source is read once more (C=128, 28x28, N=128: 21.4 -> 19.6 us)
+        // 4 096): where the launch with 64 needs a second round of wavefronts and the one with 32 fits at once, 32 are
+        // faster although the source is read once more
         const int64_t tiles16 = ((int64_t)N * Q.upi + 15) / 16 * Q.Gm;
         const int64_t w4 = tiles16 * ((Om + 63) / 64), w2 = tiles16 * ((Om + 31) / 32);
-        const int nrc4 = Q.Rp / 16;
-        const int64_t split4 = w4 * 4 <= 2048 && nrc4 >= 4 ? 4 : (w4 < 2048 && nrc4 >= 2 ? 2 : 1);
-        if (w4 * split4 > 2048 && w2 <= 4096) Q.mo = 2;
+        if (w4 > 2048 && w2 <= 4096) Q.mo = 2;
     }
     Q.otiles = (Om + 16 * Q.mo - 1) / (16 * Q.mo);
     // few tiles with a long K loop: split the row chunks of a tile over 2 or 4 wavefronts
     const int64_t waves = (((int64_t)N * Q.upi + 15) / 16) * Q.Gm * Q.otiles;
     const int nrc = Q.Rp / 16;
     Q.ksplit = 1;
-    // (by 4, and by 2 for windows, only while all wavefronts are resident at once, two per SIMD: a second
-    // round of wavefronts costs more than the longer K loop)
-    if ((KH > 1 ? waves * 2 <= 2048 : waves < 2048) && nrc >= 2) Q.ksplit = 2;
+    // (only while all wavefronts are resident at once, two per SIMD: a second round of wavefronts costs more than the
+    // longer K loop; C=128, 28x28, N=128, 64 outputs per tile: 1 568 wavefronts unsplit 13.8 us, 3 136 split by two 17.1 us,
+    // 3 136 of 32 outputs 18.0 us)
+    if (waves * 2 <= 2048 && nrc >= 2) Q.ksplit = 2;
     if (waves * 4 <= 2048 && nrc >= 4) Q.ksplit = 4;
     Q.Omp = Q.otiles * 16 * Q.mo;
     auto magic = [](uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); };
