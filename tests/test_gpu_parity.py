@@ -137,6 +137,16 @@ def test_config2_shift_residual(harness, oracle, N, H, flags):
     r.close()
 
 
+@pytest.mark.parametrize("N,C,H", [(64, 128, 56), (16, 128, 28), (5, 128, 12)])
+def test_shift_residual_with_groups_of_32_at_full_size(harness, oracle, N, C, H):
+    """The same DAG with C / 4 = 32 channels per FC group, in the launch configuration the bench times (N=64, 56x56)."""
+    case = wl.config2(N=N, C=C, H=H)
+    res, r, dy = harness.run_case(case)
+    assert r.info.fused == 1 and [d["name"] for d in r.launches(1)] == ["sgfc_bwd", "sgfc_dw_reduce"]
+    check_against_oracle(oracle, case, res, dy)
+    r.close()
+
+
 SGFC_VARIANTS = [
     # (offsets per 16-channel group, unary, residual, N, H, W)
     ([(0, 1), (0, -1), (1, 0), (-1, 0)], "relu", True, 2, 28, 28),     # 8-pixel units straddle rows
@@ -462,7 +472,8 @@ def test_fused_chain_workloads(harness, oracle, body, N, C, H, dtype):
 
 DETERMINISM_CASES = [lambda: wl.config4(64, 14, N=4), lambda: wl.config4(64, 56, N=2), lambda: wl.config4(128, 28, N=3),
                      lambda: wl.config4(512, 7, N=8), lambda: wl.config3(N=2, H=28), lambda: wl.config2(N=2, H=56),
-                     lambda: wl.config5(157), lambda: wl.config5(130), lambda: wl.chain("shift_residual", N=8, C=64, H=28)]
+                     lambda: wl.config5(157), lambda: wl.config5(130), lambda: wl.chain("shift_residual", N=8, C=64, H=28),
+                     lambda: wl.config2(N=3, C=128, H=28), lambda: wl.config3(N=4, H=28)]
 
 
 @pytest.mark.parametrize("idx", range(len(DETERMINISM_CASES)))
