@@ -25,6 +25,8 @@ TEMPLATE_EXPORTS = ["canvas_template_parse", "canvas_template_query", "canvas_te
                     "canvas_template_substitute", "canvas_group_candidates", "canvas_template_solve",
                     "canvas_template_instantiate", "canvas_template_destroy"]
 CANVAS_MAX_VARS = 8
+# include/canvas_block.h
+BLOCK_EXPORTS = ["canvas_block_compile", "canvas_block_query", "canvas_block_forward", "canvas_block_backward", "canvas_block_destroy"]
 
 
 class CanvasOptions(ctypes.Structure):
@@ -44,6 +46,12 @@ class CanvasDagInfo(ctypes.Structure):
         ("fc_flops_fwd", ctypes.c_double), ("min_bytes_fwd", ctypes.c_double), ("min_bytes_bwd", ctypes.c_double),
         ("n_fused_nodes", ctypes.c_int32), ("reserved1", ctypes.c_int32),
     ]
+
+
+class CanvasBlockInfo(ctypes.Structure):
+    _fields_ = [("instances", ctypes.c_int32), ("expand", ctypes.c_int32), ("template_channels", ctypes.c_int64),
+                ("n_weights", ctypes.c_int32), ("reserved0", ctypes.c_int32), ("workspace_bytes", ctypes.c_uint64),
+                ("plan", CanvasDagInfo)]
 
 
 class CanvasTarget(ctypes.Structure):
@@ -106,6 +114,13 @@ def load():
                                                     ctypes.c_char_p, sz, szp]
         lib.canvas_template_destroy.argtypes = [vp]
         lib.canvas_template_destroy.restype = None
+        lib.canvas_block_compile.argtypes = [ctypes.c_char_p, sz, ctypes.POINTER(ctypes.c_int64), ctypes.c_int64, ctypes.c_int,
+                                             ctypes.POINTER(CanvasOptions), ctypes.POINTER(vp)]
+        lib.canvas_block_query.argtypes = [vp, ctypes.POINTER(CanvasBlockInfo)]
+        lib.canvas_block_forward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, sz, vp]
+        lib.canvas_block_backward.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, ctypes.POINTER(vp), vp, sz, vp]
+        lib.canvas_block_destroy.argtypes = [vp]
+        lib.canvas_block_destroy.restype = None
         _lib = lib
     return _lib
 
@@ -186,6 +201,39 @@ def canvas_dag_get_timing(handle, backward, n):
 
 def canvas_dag_destroy(handle):
     load().canvas_dag_destroy(handle)
+
+
+# ---------------------------------------------------------------- blocks with C_in != C_out (include/canvas_block.h)
+
+def canvas_block_compile(blob, in_shape, c_out, dtype, flags=0):
+    lib = load()
+    b = blob.encode() if isinstance(blob, str) else bytes(blob)
+    shp = (ctypes.c_int64 * 4)(*[int(v) for v in in_shape])
+    opt = CanvasOptions(flags=flags)
+    h = ctypes.c_void_p()
+    _check(lib.canvas_block_compile(b, len(b), shp, int(c_out), int(dtype), ctypes.byref(opt), ctypes.byref(h)))
+    return h
+
+
+def canvas_block_query(handle):
+    info = CanvasBlockInfo()
+    _check(load().canvas_block_query(handle, ctypes.byref(info)))
+    return info
+
+
+def canvas_block_forward(handle, x, weights, y, workspace):
+    """weights: flat list, instance-major (all weight tensors of instance 0 first)."""
+    _check(load().canvas_block_forward(handle, x.data_ptr(), _ptrs(weights), y.data_ptr(), workspace.data_ptr(),
+                                       workspace.numel() * workspace.element_size(), _stream()))
+
+
+def canvas_block_backward(handle, x, weights, dy, dx, dweights, workspace):
+    _check(load().canvas_block_backward(handle, x.data_ptr(), _ptrs(weights), dy.data_ptr(), dx.data_ptr(), _ptrs(dweights),
+                                        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def canvas_block_destroy(handle):
+    load().canvas_block_destroy(handle)
 
 
 # ---------------------------------------------------------------- templates (include/canvas_template.h), host only

@@ -131,6 +131,17 @@ def make_dy(case, out_shape):
     return rnd(normal(case["seed"], 1, out_shape))
 
 
+def block_case(name, blob, shape, c_out, dtype, seed, wshapes, wstds):
+    """Tensors for a block [C_in, H, W] => [C_out, H, W] composed of m = max / min instances of one template: x, dy
+    and one weight set per instance (inputs only; the composition itself is the library's and the oracle's business)."""
+    rnd = round_to_bf16 if dtype == "bf16" else (lambda a: np.ascontiguousarray(a, dtype=np.float32))
+    n, c_in, h, w = shape
+    m = max(c_in, c_out) // min(c_in, c_out)
+    weights = [[rnd(normal(seed, 100 + 16 * j + k, s, std)) for k, (s, std) in enumerate(zip(wshapes, wstds))] for j in range(m)]
+    return {"name": name, "blob": blob, "shape": tuple(shape), "c_out": int(c_out), "dtype": dtype, "seed": seed,
+            "x": rnd(normal(seed, 0, shape)), "dy": rnd(normal(seed, 1, (n, c_out, h, w))), "weights": weights}
+
+
 def config1():
     return _case("conv3x3_fp32", blob_conv(3, 1, 16), (1, 16, 8, 8), "f32", 0, [(1, 16, 144)], [1.0 / 12.0])
 

@@ -1,0 +1,71 @@
+"""GPU parity of blocks with C_in != C_out (include/canvas_block.h) against oracle/block_oracle.py, element by element.
+The composition rule is this library's reading of Section 4 of the paper (the figure is missing from the text): the
+oracle is pinned to that rule, not to a value the paper prints (parity unpinned by the paper)."""
+import math
+
+import numpy as np
+import pytest
+
+from helpers import TOL, assert_close, has_kinks
+from paper_2304_07741_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+GATE = (wl.HEADER + "%1 = shift %0 dh=0 dw=1 c0=0 c1={H2}\n%2 = fc %1 groups=2 out={C}\n%3 = unary %2 op=gelu\n"
+        "%4 = binary %0 %3 op=mul\noutput %4\n")
+
+
+def _cases():
+    out = []
+    for c_in, c_out in [(64, 128), (128, 64), (64, 64), (64, 192)]:     # the fused shift / FC / relu / residual family
+        out.append(("shift_residual", wl.blob_shift_residual(64), (3, c_in, 16, 16), c_out, "bf16", [(4, 16, 16)], [0.25]))
+    for c_in, c_out in [(10, 30), (30, 10)]:                             # fp32, slices that are no multiple of 16 bytes
+        out.append(("conv3", wl.blob_conv(3, 1, 10), (2, c_in, 9, 9), c_out, "f32", [(1, 10, 90)], [1.0 / math.sqrt(90)]))
+    for c_in, c_out in [(32, 128), (128, 32)]:                           # FC between two fused chains
+        out.append(("gate", GATE.format(C=32, H2=16), (2, c_in, 12, 12), c_out, "bf16", [(2, 16, 16)], [0.25]))
+    for c_in, c_out in [(32, 64), (64, 32)]:                             # per-pixel window weights
+        out.append(("involution", wl.blob_involution(32, 3), (2, c_in, 14, 14), c_out, "bf16", [(1, 9, 32), (1, 32, 32)],
+                    [0.09, 1.0 / math.sqrt(32)]))
+    out.append(("shift_residual_fullsize", wl.blob_shift_residual(64), (32, 64, 56, 56), 128, "bf16", [(4, 16, 16)], [0.25]))
+    return out
+
+
+CASES = _cases()
+
+
+@pytest.mark.parametrize("idx", range(len(CASES)))
+def test_block_against_the_oracle(idx):
+    from oracle import block_oracle
+    from paper_2304_07741_amd import harness
+
+    name, blob, shape, c_out, dtype, wshapes, wstds = CASES[idx]
+    case = wl.block_case(name, blob, shape, c_out, dtype, 300 + idx, wshapes, wstds)
+    r = harness.BlockRunner(blob, shape, c_out, dtype)
+    try:
+        m = max(shape[1], c_out) // min(shape[1], c_out)
+        assert r.info.instances == m and r.info.expand == (1 if c_out % shape[1] == 0 else 0)
+        r.load(case["x"], case["weights"], case["dy"])
+        res = r.run()
+        again = r.run()   # same workspace, same bits: the sums over the instances have a fixed order
+    finally:
+        r.close()
+    assert np.array_equal(res["y"], again["y"]) and np.array_equal(res["dx"], again["dx"])
+    ref = block_oracle.run_block(blob, case["x"], case["weights"], c_out, case["dy"])
+    alts = {}
+
+    def bracket(mg, variant):
+        if (mg, variant) not in alts:
+            alts[(mg, variant)] = block_oracle.run_block(blob, case["x"], case["weights"], c_out, case["dy"],
+                                                         tie_margin=variant[0] * mg, tie_rule=variant[1])
+        return alts[(mg, variant)]
+
+    kinks = has_kinks(blob)
+    tol = TOL[dtype]
+    gfloor = 1e-5 * float(np.abs(case["dy"]).max())
+    what = f"block {name} {shape[1]}->{c_out}"
+    assert_close(res["y"], ref["y"], tol, what + ":y")
+    assert_close(res["dx"], ref["dx"], tol, what + ":dx", (lambda mg, v: bracket(mg, v)["dx"]) if kinks else None, gfloor)
+    for j in range(m):
+        for k in range(len(wshapes)):
+            assert_close(res["dw"][j][k], ref["dw"][j][k], tol, what + f":dw{j}.{k}",
+                         (lambda mg, v, j=j, k=k: bracket(mg, v)["dw"][j][k]) if kinks else None, gfloor)
