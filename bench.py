@@ -4,6 +4,7 @@ of its dominant kernel and the CPU oracle timed beside it.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload shift_residual|involution|sampled_cC_hH]
     python bench.py --workload chain_gate|chain_relu|chain_shift_residual|chain_box3|chain_softmax_c[_cC_hH]
                                                        (an FC-free fused chain at a ResNet layer shape, N=128, vs the HBM roof)
+    python bench.py --workload block_64_256      (a block C_in=64 => C_out=256 composed of four shift_residual templates)
     python bench.py --workload fuzz [--seeds 100:300]  (config 5: geometric mean over the random DAGs, chain kernels vs HBM)
     python bench.py --fc-micro                         (grouped-FC kernels of config 4, operands in cache, vs MFMA peak)
     python bench.py --infer BATCH [--workload ...]     (forward-only latency of the inference plan, not the headline)
@@ -16,6 +17,7 @@ Prints one JSON line.
 """
 import argparse
 import json
+import math
 import os
 import statistics
 import sys
@@ -355,6 +357,71 @@ def fuzz_bench(args):
     print(json.dumps(out))
 
 
+def block_bench(args):
+    """A block with C_in != C_out composed from the shift + grouped FC + ReLU + residual template (include/canvas_block.h):
+    block_<C_in>_<C_out> at N=64, H=W=56, bf16.  A step is forward + backward of the whole block; the roofline entry is the
+    whole step against the bytes a block must move (x, dy read, y, dx written, once each), since the instances' launches
+    are timed together."""
+    import torch
+
+    from paper_2304_07741_amd import harness
+    from paper_2304_07741_amd import workloads as wl
+
+    c_in, c_out = (int(v) for v in args.workload[len("block_"):].split("_"))
+    c = min(c_in, c_out)
+    n, h = 64, 56
+    case = wl.block_case("block_shift_residual", wl.blob_shift_residual(c), (n, c_in, h, h), c_out, "bf16", 11,
+                         [(4, c // 4, c // 4)], [1.0 / math.sqrt(c // 4)])
+    act_bytes = 2.0 * n * h * h * (c_in + c_out)              # x and y (or dy and dx) once
+    sets = max(2, int(2 * 256e6 / (2 * act_bytes)) + 1)      # rotate over more than twice the last-level cache
+    runners = [harness.BlockRunner(case["blob"], case["shape"], c_out, "bf16") for _ in range(sets)]
+    for r in runners:
+        r.load(case["x"], case["weights"], case["dy"])
+    from paper_2304_07741_amd import binding as B
+
+    def step(r):
+        B.canvas_block_forward(r.handle, r.x, r.w, r.y, r.ws)
+        B.canvas_block_backward(r.handle, r.x, r.w, r.dy, r.dx, r.dw, r.ws)
+
+    for i in range(args.warmup):
+        step(runners[i % sets])
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for i in range(args.steps):
+        step(runners[i % sets])
+    t1.record()
+    torch.cuda.synchronize()
+    ms = t0.elapsed_time(t1) / args.steps
+    info = runners[0].info
+    alg = 2.0 * act_bytes
+    ach = alg / (ms * 1e-3) / 1e9
+    out = {"metric": "micro-DAG fwd+bwd images/sec at ResNet layer shapes; % HBM / MFMA roofline", "value": n / (ms * 1e-3), "unit": "images/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"block of {int(info.instances)} shift_residual templates, {'expand' if info.expand else 'reduce'}: "
+                                  f"N={n} C_in={c_in} C_out={c_out} H=W={h} bf16 (seed 11)",
+                      "instances": int(info.instances), "buffer_sets": sets, "workspace_bytes": int(info.workspace_bytes),
+                      "launches_per_instance_fwd": int(info.plan.n_launches_fwd), "launches_per_instance_bwd": int(info.plan.n_launches_bwd)},
+           "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                        "kernel": "whole step (all instances, slice copies and sums)", "kernel_ms": ms, "algorithmic_bytes": alg}}
+    if not args.no_cpu_baseline:
+        import time
+
+        from oracle import block_oracle
+
+        k = 4  # images of the batch: a bounded sample
+        x64 = case["x"][:k].astype("float64")
+        t = time.perf_counter()
+        block_oracle.run_block(case["blob"], x64, case["weights"], c_out, case["dy"][:k].astype("float64"))
+        dt = time.perf_counter() - t
+        out["cpu_baseline"] = {"value": k / dt, "unit": "images/s", "cores": os.cpu_count(), "kind": "oracle",
+                               "sample": f"{k} images of the batch, forward+backward of every instance, one run"}
+    for r in runners:
+        r.close()
+    print(json.dumps(out))
+
+
 def fc_micro(args):
     """Grouped FC with its operands in cache: the contraction launches of config 4 at its four shapes, the same buffers
     every step (6-50 MB, far below the 256 MB last-level cache), each against the bf16 MFMA peak."""
@@ -403,6 +470,8 @@ def main():
         return copy_reference(args)
     if args.fc_micro:
         return fc_micro(args)
+    if args.workload.startswith("block_"):
+        return block_bench(args)
     if args.workload == "fuzz":
         if args.steps == 200:
             args.steps, args.warmup = 10, 3

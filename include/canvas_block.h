@@ -12,8 +12,8 @@
  *                               outputs.  dx of instance j is channels [j * C, (j + 1) * C) of dx.
  *
  * The instances run one after the other through the plan of canvas_dag.h compiled for [N, C, H, W]; channel slices
- * are copied to and from dense tensors by the library's own kernels, sums over the instances are kept in fp32 and
- * rounded to the element type once.  (The normalisation that the paper's code generator inserts, Section 7, is a layer
+ * are regrouped into dense tensors and back by one launch of the library's own kernels per direction, the instances'
+ * results are added in fp32 in instance order and rounded to the element type once.  (The normalisation that the paper's code generator inserts, Section 7, is a layer
  * of the surrounding network and not part of a block.)
  *
  * Pointers: device pointers unless stated, owned by the caller, 16-byte aligned, contiguous NCHW.  All functions
@@ -36,7 +36,7 @@ typedef struct canvas_block_info {
     int64_t template_channels; /* C */
     int32_t n_weights;         /* weight tensors of ONE instance (their shapes: canvas_dag_info of the template plan) */
     int32_t reserved0;
-    uint64_t workspace_bytes;  /* device bytes forward/backward need: m plan workspaces + two dense tensors + one fp32 sum */
+    uint64_t workspace_bytes;  /* device bytes forward/backward need: m plan workspaces + 2 m dense tensors [N, C, H, W] */
     canvas_dag_info plan;      /* the template's plan at [N, C, H, W] */
 } canvas_block_info;
 
@@ -50,7 +50,8 @@ int canvas_block_compile(const void* blob, size_t blob_len, const int64_t in_sha
 int canvas_block_query(const canvas_block* block, canvas_block_info* info);
 
 /* x [N, C_in, H, W] read; weights: host array of instances * n_weights device pointers, instance-major (all weights of
- * instance 0 first); y [N, C_out, H, W] written; workspace: workspace_bytes bytes, carries what backward needs. */
+ * instance 0 first); y [N, C_out, H, W] written; workspace: workspace_bytes bytes, carries what backward needs
+ * (reduce blocks: also the dense slices of x), so it must stay untouched until the matching backward call. */
 int canvas_block_forward(canvas_block* block, const void* x, const void* const* weights, void* y, void* workspace,
                          size_t workspace_bytes, void* stream);
 

@@ -11,6 +11,7 @@
 #include "dag.hpp"
 #include "launch.hpp"
 #include "lowering.hpp"
+#include "plan_calls.hpp"
 
 struct canvas_dag {
     canvas::Dag dag;
@@ -200,18 +201,7 @@ int canvas_dag_launch_desc(const canvas_dag* dag, int backward, int idx, canvas_
 
 int canvas_dag_forward(canvas_dag* dag, const void* x, const void* const* weights, void* y, void* workspace,
                        size_t workspace_bytes, void* stream) {
-    int rc = check_common(dag, x, weights, workspace, workspace_bytes);
-    if (rc) return rc;
-    if (!y || !aligned16(y)) return set_err(CANVAS_BAD_ARG, "y must be a non-null, 16-byte aligned device pointer");
-    canvas::RunArgs a;
-    a.x = x;
-    a.w = weights;
-    a.y = y;
-    a.ws = (char*)workspace;
-    a.stream = (hipStream_t)stream;
-    (void)hipGetLastError();
-    run_launches(dag, 0, a);
-    return finish_launches();
+    return canvas::plan_forward(dag, x, weights, y, workspace, workspace_bytes, stream, 0, 0);
 }
 
 int canvas_dag_forward_static(canvas_dag* dag, const void* x, const void* const* weights, void* y, void* stream) {
@@ -258,6 +248,36 @@ int canvas_dag_prepare(canvas_dag* dag, const void* const* weights, void* worksp
 
 int canvas_dag_backward(canvas_dag* dag, const void* x, const void* const* weights, const void* dy, void* dx,
                         void* const* dweights, void* workspace, size_t workspace_bytes, void* stream) {
+    return canvas::plan_backward(dag, x, weights, dy, dx, dweights, workspace, workspace_bytes, stream, 0, 0);
+}
+
+}  // extern "C"
+
+namespace canvas {
+
+bool plan_takes_strided_io(const canvas_dag* dag) { return dag && dag->low->strided_io; }
+
+int plan_forward(canvas_dag* dag, const void* x, const void* const* weights, void* y, void* workspace, size_t workspace_bytes,
+                 void* stream, int64_t x_stride, int64_t y_stride) {
+    int rc = check_common(dag, x, weights, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (!y || !aligned16(y)) return set_err(CANVAS_BAD_ARG, "y must be a non-null, 16-byte aligned device pointer");
+    if ((x_stride || y_stride) && !dag->low->strided_io) return set_err(CANVAS_UNSUPPORTED, "this plan takes dense tensors only");
+    RunArgs a;
+    a.x = x;
+    a.w = weights;
+    a.y = y;
+    a.ws = (char*)workspace;
+    a.stream = (hipStream_t)stream;
+    a.x_stride = x_stride;
+    a.y_stride = y_stride;
+    (void)hipGetLastError();
+    run_launches(dag, 0, a);
+    return finish_launches();
+}
+
+int plan_backward(canvas_dag* dag, const void* x, const void* const* weights, const void* dy, void* dx, void* const* dweights,
+                  void* workspace, size_t workspace_bytes, void* stream, int64_t x_stride, int64_t y_stride) {
     if (dag && dag->inference) return set_err(CANVAS_UNSUPPORTED, "this plan was compiled for inference: it has no backward pass");
     int rc = check_common(dag, x, weights, workspace, workspace_bytes);
     if (rc) return rc;
@@ -275,10 +295,17 @@ int canvas_dag_backward(canvas_dag* dag, const void* x, const void* const* weigh
     a.dw = dweights;
     a.ws = (char*)workspace;
     a.stream = (hipStream_t)stream;
+    if ((x_stride || y_stride) && !dag->low->strided_io) return set_err(CANVAS_UNSUPPORTED, "this plan takes dense tensors only");
+    a.x_stride = x_stride;
+    a.y_stride = y_stride;
     (void)hipGetLastError();
     run_launches(dag, 1, a);
     return finish_launches();
 }
+
+}  // namespace canvas
+
+extern "C" {
 
 int canvas_dag_set_timing(canvas_dag* dag, int enable) {
     if (!dag) return set_err(CANVAS_BAD_ARG, "null dag handle");

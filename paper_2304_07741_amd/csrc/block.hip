@@ -2,8 +2,11 @@
 // m = max(C_in, C_out) / min(C_in, C_out) instances of the template's plan at [N, C, H, W], C = min(C_in, C_out).
 // Expand (C_out = m C): every instance reads x, instance j writes channel slice j of y, dx is the sum of the instances'
 // dx.  Reduce (C_in = m C): instance j reads channel slice j of x, y is the sum, instance j writes slice j of dx.
-// A channel slice of an NCHW batch is strided over the images, the plan's kernels take dense tensors: slices are
-// copied by the two kernels below (16-byte accesses), sums over the instances are kept in fp32 and rounded once.
+// A channel slice of an NCHW batch is strided over the images.  Plans whose kernels address their input and output through
+// an image stride (the fused shift / grouped FC / unary / residual family) read and write the slices in place; the other
+// plans take dense tensors: ONE launch
+// regroups [N, m, C P] into m dense tensors [N, C P] or back (16-byte accesses), ONE launch adds the m dense results of
+// the instances (in fp32 registers, in instance order, rounded once).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -13,6 +16,7 @@
 
 #include "../../include/canvas_block.h"
 #include "launch.hpp"
+#include "plan_calls.hpp"
 #include "tile_util.hpp"
 
 namespace canvas {
@@ -25,7 +29,8 @@ struct canvas_block {
     int64_t N = 0, C = 0, P = 0;
     int m = 1;
     bool expand = true, bf16 = false;
-    uint64_t plan_ws = 0, off_a = 0, off_b = 0, off_sum = 0;
+    bool direct = false;  // the plan's kernels take channel slices of the wide tensors as they are (image strides): no regrouping
+    uint64_t plan_ws = 0, dense = 0, off_a = 0, off_b = 0;  // workspace: m plan workspaces | m dense inputs | m dense results
 };
 
 namespace {
@@ -36,62 +41,58 @@ int set_err(int code, const std::string& msg) { return canvas::set_last_error(co
 uint64_t align_up(uint64_t v) { return (v + 255) / 256 * 256; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// dst image n (dst_stride bytes apart, from dst_off) = src image n (src_stride apart, from src_off), `bytes` each.
-// VEC: all of these are multiples of 16 and a thread moves 16 bytes; else a thread moves one 2-byte element.
+// sliced [N][m][unit] <-> dense [m][N][unit] (instance j's dense tensor starts at j * dense_stride bytes); a unit is one
+// image's slice, `upi` pieces of W bytes.  VEC: 16-byte pieces (every size a multiple of 16), else 2-byte elements.
 template <bool VEC>
-__global__ __launch_bounds__(256) void k_slice_copy(const unsigned char* __restrict__ src, unsigned char* __restrict__ dst, long long bytes,
-                                                    long long src_stride, long long dst_stride, long long src_off, long long dst_off,
-                                                    long long units_per_image, long long total_units) {
+__global__ __launch_bounds__(256) void k_regroup(const unsigned char* __restrict__ src, unsigned char* __restrict__ dst, long long upi, int m,
+                                                 long long n_images, long long dense_stride, int to_dense) {
     const long long u = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (u >= total_units) return;
-    const long long n = u / units_per_image, k = u - n * units_per_image;
+    if (u >= upi * m * n_images) return;
     constexpr int W = VEC ? 16 : 2;
-    const unsigned char* s = src + n * src_stride + src_off + k * W;
-    unsigned char* d = dst + n * dst_stride + dst_off + k * W;
+    // u walks the sliced tensor: ((n * m) + j) * upi + k
+    const long long nj = u / upi, k = u - nj * upi;
+    const long long n = nj / m, j = nj - n * m;
+    const long long sliced = u * W, dense = j * dense_stride + (n * upi + k) * W;
+    const unsigned char* s = src + (to_dense ? sliced : dense);
+    unsigned char* d = dst + (to_dense ? dense : sliced);
     if (VEC) *reinterpret_cast<u32x4*>(d) = *reinterpret_cast<const u32x4*>(s);
     else *reinterpret_cast<uint16_t*>(d) = *reinterpret_cast<const uint16_t*>(s);
-    (void)bytes;
 }
 
-// sum (fp32) = first ? part : sum + part; on the last instance the total is also written to `out` in the element type.
+// out[i] = parts[0][i] + parts[1][i] + ... (fp32, in that order), rounded to the element type once
 template <bool BF16>
-__global__ __launch_bounds__(256) void k_accumulate(const void* __restrict__ part, float* __restrict__ sum, void* __restrict__ out,
-                                                    long long count, int first, int last) {
+__global__ __launch_bounds__(256) void k_sum(const unsigned char* __restrict__ parts, long long part_stride, int m, void* __restrict__ out,
+                                             long long count) {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
-    float v;
-    if (BF16) v = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(part)[i] << 16);
-    else v = reinterpret_cast<const float*>(part)[i];
-    const float t = first ? v : sum[i] + v;
-    if (!last) {
-        sum[i] = t;
-    } else if (BF16) {
-        reinterpret_cast<uint16_t*>(out)[i] = (uint16_t)(canvas::tile::pack_bf16(t, 0.f) & 0xffffu);
-    } else {
-        reinterpret_cast<float*>(out)[i] = t;
+    float t = 0.f;
+    for (int j = 0; j < m; j++) {
+        const unsigned char* p = parts + j * part_stride;
+        const float v = BF16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(p)[i] << 16) : reinterpret_cast<const float*>(p)[i];
+        t = j == 0 ? v : t + v;
     }
+    if (BF16) reinterpret_cast<uint16_t*>(out)[i] = (uint16_t)(canvas::tile::pack_bf16(t, 0.f) & 0xffffu);
+    else reinterpret_cast<float*>(out)[i] = t;
 }
 
-// copies channel slice j of `sliced` ([N, m C, P]) to the dense `dense` ([N, C, P]) or back
-void slice_copy(const canvas_block* b, const void* src, void* dst, int j, bool to_dense, hipStream_t s) {
+// all m channel slices of `sliced` ([N, m C, P]) to the m dense tensors at `dense` or back
+void regroup(const canvas_block* b, const void* src, void* dst, bool to_dense, hipStream_t s) {
     const long long esz = b->bf16 ? 2 : 4;
-    const long long bytes = b->C * b->P * esz, wide = bytes * b->m;
+    const long long bytes = b->C * b->P * esz;
     const bool vec = bytes % 16 == 0;
-    const long long upi = vec ? bytes / 16 : bytes / 2, total = upi * b->N;
+    const long long upi = vec ? bytes / 16 : bytes / 2, total = upi * b->m * b->N;
     if (total == 0) return;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-    const long long so = to_dense ? j * bytes : 0, dof = to_dense ? 0 : j * bytes;
-    const long long ss = to_dense ? wide : bytes, ds = to_dense ? bytes : wide;
-    if (vec) CANVAS_LAUNCH(k_slice_copy<true>, grid, block, 0, s, (const unsigned char*)src, (unsigned char*)dst, bytes, ss, ds, so, dof, upi, total);
-    else CANVAS_LAUNCH(k_slice_copy<false>, grid, block, 0, s, (const unsigned char*)src, (unsigned char*)dst, bytes, ss, ds, so, dof, upi, total);
+    if (vec) CANVAS_LAUNCH(k_regroup<true>, grid, block, 0, s, (const unsigned char*)src, (unsigned char*)dst, upi, b->m, (long long)b->N, (long long)b->dense, to_dense ? 1 : 0);
+    else CANVAS_LAUNCH(k_regroup<false>, grid, block, 0, s, (const unsigned char*)src, (unsigned char*)dst, upi, b->m, (long long)b->N, (long long)b->dense, to_dense ? 1 : 0);
 }
 
-void accumulate(const canvas_block* b, const void* part, float* sum, void* out, bool first, bool last, hipStream_t s) {
+void sum_instances(const canvas_block* b, const void* parts, void* out, hipStream_t s) {
     const long long count = b->N * b->C * b->P;
     if (count == 0) return;
     const dim3 grid((unsigned)((count + 255) / 256)), block(256);
-    if (b->bf16) CANVAS_LAUNCH(k_accumulate<true>, grid, block, 0, s, part, sum, out, count, first ? 1 : 0, last ? 1 : 0);
-    else CANVAS_LAUNCH(k_accumulate<false>, grid, block, 0, s, part, sum, out, count, first ? 1 : 0, last ? 1 : 0);
+    if (b->bf16) CANVAS_LAUNCH(k_sum<true>, grid, block, 0, s, (const unsigned char*)parts, (long long)b->dense, b->m, out, count);
+    else CANVAS_LAUNCH(k_sum<false>, grid, block, 0, s, (const unsigned char*)parts, (long long)b->dense, b->m, out, count);
 }
 
 int check(const canvas_block* b, const void* x, const void* const* weights, const void* ws, size_t ws_bytes) {
@@ -143,17 +144,18 @@ int canvas_block_compile(const void* blob, size_t blob_len, const int64_t in_sha
     b->N = in_shape[0];
     b->P = in_shape[2] * in_shape[3];
     b->bf16 = dt == CANVAS_BF16;
-    const uint64_t dense = align_up((uint64_t)(b->N * b->C * b->P) * (b->bf16 ? 2 : 4));
+    b->dense = align_up((uint64_t)(b->N * b->C * b->P) * (b->bf16 ? 2 : 4));
     b->plan_ws = align_up(pi.workspace_bytes);
     b->off_a = b->plan_ws * (uint64_t)b->m;
-    b->off_b = b->off_a + dense;
-    b->off_sum = b->off_b + dense;
+    b->off_b = b->off_a + b->dense * (uint64_t)b->m;
+    // (in place: 32-bit byte offsets over the wide tensors)
+    b->direct = b->m > 1 && canvas::plan_takes_strided_io(b->plan) && b->N * b->C * b->m * b->P * (b->bf16 ? 2 : 4) < ((int64_t)1 << 31);
     b->info.instances = b->m;
     b->info.expand = b->expand ? 1 : 0;
     b->info.template_channels = b->C;
     b->info.n_weights = pi.n_weights;
     b->info.reserved0 = 0;
-    b->info.workspace_bytes = b->off_sum + align_up((uint64_t)(b->N * b->C * b->P) * 4);
+    b->info.workspace_bytes = b->off_b + b->dense * (uint64_t)b->m;
     *out = b.release();
     return CANVAS_OK;
 }
@@ -171,24 +173,26 @@ int canvas_block_forward(canvas_block* b, const void* x, const void* const* weig
     if (!y || !aligned16(y)) return set_err(CANVAS_BAD_ARG, "y must be a non-null, 16-byte aligned device pointer");
     char* ws = (char*)workspace;
     const hipStream_t s = (hipStream_t)stream;
-    void* ta = ws + b->off_a;
-    void* tb = ws + b->off_b;
+    char* A = ws + b->off_a;  // dense inputs of the instances (reduce: the slices of x, kept for backward)
+    char* R = ws + b->off_b;  // dense results of the instances
     const int nw = b->info.n_weights;
     (void)hipGetLastError();
+    const int64_t slice = b->C * b->P, wide = slice * b->m;      // elements of one image's slice / of one wide image
+    const int64_t sbytes = slice * (b->bf16 ? 2 : 4);
+    if (!b->expand && !b->direct) regroup(b, x, A, true, s);
     for (int j = 0; j < b->m; j++) {
         void* pws = ws + (uint64_t)j * b->plan_ws;
         const void* const* wj = weights ? weights + (size_t)j * nw : nullptr;
-        if (b->expand) {
-            // (one instance: the plan writes y itself)
-            rc = canvas_dag_forward(b->plan, x, wj, b->m == 1 ? y : ta, pws, b->plan_ws, stream);
-            if (rc) return rc;
-            if (b->m > 1) slice_copy(b, ta, y, j, false, s);
-        } else {
-            slice_copy(b, x, ta, j, true, s);
-            rc = canvas_dag_forward(b->plan, ta, wj, tb, pws, b->plan_ws, stream);
-            if (rc) return rc;
-            accumulate(b, tb, (float*)(ws + b->off_sum), y, j == 0, j == b->m - 1, s);
-        }
+        void* rj = R + (uint64_t)j * b->dense;
+        if (b->m == 1) rc = canvas_dag_forward(b->plan, x, wj, y, pws, b->plan_ws, stream);  // (the plan writes y itself)
+        else if (b->direct && b->expand) rc = canvas::plan_forward(b->plan, x, wj, (char*)y + j * sbytes, pws, b->plan_ws, stream, 0, wide);
+        else if (b->direct) rc = canvas::plan_forward(b->plan, (const char*)x + j * sbytes, wj, rj, pws, b->plan_ws, stream, wide, 0);
+        else rc = canvas_dag_forward(b->plan, b->expand ? x : (const void*)(A + (uint64_t)j * b->dense), wj, rj, pws, b->plan_ws, stream);
+        if (rc) return rc;
+    }
+    if (b->m > 1) {
+        if (!b->expand) sum_instances(b, R, y, s);
+        else if (!b->direct) regroup(b, R, y, false, s);
     }
     return finish();
 }
@@ -201,30 +205,34 @@ int canvas_block_backward(canvas_block* b, const void* x, const void* const* wei
     if (b->info.n_weights > 0 && !dweights) return set_err(CANVAS_BAD_ARG, "dweights array is null");
     char* ws = (char*)workspace;
     const hipStream_t s = (hipStream_t)stream;
-    void* ta = ws + b->off_a;
-    void* tb = ws + b->off_b;
+    char* A = ws + b->off_a;
+    char* R = ws + b->off_b;
     const int nw = b->info.n_weights;
     (void)hipGetLastError();
+    const int64_t slice = b->C * b->P, wide = slice * b->m;
+    const int64_t sbytes = slice * (b->bf16 ? 2 : 4);
+    if (b->expand && b->m > 1 && !b->direct) regroup(b, dy, A, true, s);  // (expand: the slices of dy; reduce: A still holds the slices of x)
     for (int j = 0; j < b->m; j++) {
         void* pws = ws + (uint64_t)j * b->plan_ws;
         const void* const* wj = weights ? weights + (size_t)j * nw : nullptr;
         void* const* dwj = dweights ? dweights + (size_t)j * nw : nullptr;
-        if (b->expand) {
-            if (b->m == 1) {
-                rc = canvas_dag_backward(b->plan, x, wj, dy, dx, dwj, pws, b->plan_ws, stream);
-                if (rc) return rc;
-                continue;
-            }
-            slice_copy(b, dy, ta, j, true, s);
-            rc = canvas_dag_backward(b->plan, x, wj, ta, tb, dwj, pws, b->plan_ws, stream);
-            if (rc) return rc;
-            accumulate(b, tb, (float*)(ws + b->off_sum), dx, j == 0, j == b->m - 1, s);
+        void* rj = R + (uint64_t)j * b->dense;
+        if (b->m == 1) {
+            rc = canvas_dag_backward(b->plan, x, wj, dy, dx, dwj, pws, b->plan_ws, stream);
+        } else if (b->direct && b->expand) {
+            rc = canvas::plan_backward(b->plan, x, wj, (const char*)dy + j * sbytes, rj, dwj, pws, b->plan_ws, stream, 0, wide);
+        } else if (b->direct) {
+            rc = canvas::plan_backward(b->plan, (const char*)x + j * sbytes, wj, dy, (char*)dx + j * sbytes, dwj, pws, b->plan_ws, stream, wide, 0);
         } else {
-            slice_copy(b, x, ta, j, true, s);
-            rc = canvas_dag_backward(b->plan, ta, wj, dy, tb, dwj, pws, b->plan_ws, stream);
-            if (rc) return rc;
-            slice_copy(b, tb, dx, j, false, s);
+            const void* xj = b->expand ? x : (const void*)(A + (uint64_t)j * b->dense);
+            const void* dyj = b->expand ? (const void*)(A + (uint64_t)j * b->dense) : dy;
+            rc = canvas_dag_backward(b->plan, xj, wj, dyj, rj, dwj, pws, b->plan_ws, stream);
         }
+        if (rc) return rc;
+    }
+    if (b->m > 1) {
+        if (b->expand) sum_instances(b, R, dx, s);
+        else if (!b->direct) regroup(b, R, dx, false, s);
     }
     return finish();
 }

@@ -88,14 +88,18 @@ std::unique_ptr<Lowering> lower_sgfc(const Dag& dag, bool bf16) {
 
     auto low = std::make_unique<Lowering>();
     low->fused = true;
+    low->strided_io = true;
     const int elems = OG * CG;
     low->ws_bytes = align_up((uint64_t)G * P.wgs_per_group * elems * 4);
     const int KC = CG / 16, MO = OG / 16;
     const int widx = fc.widx;
+    const int xs_dense = C * Pn, ys_dense = fc.out * Pn;
     const double act = 2.0 * dag.numel(0), wb = 2.0 * G * elems;
     const double flops = 2.0 * dag.N * Pn * fc.out * CG;
     low->fwd.push_back({"sgfc_fwd", act + 2.0 * dag.numel(dag.out) + wb, flops, [=](const RunArgs& a) {
                             sgfc::Params Q = P;
+                            Q.xs = a.x_stride ? (int)a.x_stride : xs_dense;
+                            Q.ys = a.y_stride ? (int)a.y_stride : ys_dense;
                             Q.x = (const uint16_t*)a.x;
                             Q.w = (const uint16_t*)a.w[widx];
                             Q.y = (uint16_t*)a.y;
@@ -104,6 +108,8 @@ std::unique_ptr<Lowering> lower_sgfc(const Dag& dag, bool bf16) {
     low->bwd.push_back({"sgfc_bwd", 2.0 * act + 2.0 * dag.numel(dag.out) + wb + 4.0 * G * P.wgs_per_group * elems, 3.0 * flops,
                         [=](const RunArgs& a) {
                             sgfc::Params Q = P;
+                            Q.xs = a.x_stride ? (int)a.x_stride : xs_dense;
+                            Q.ys = a.y_stride ? (int)a.y_stride : ys_dense;
                             Q.x = (const uint16_t*)a.x;
                             Q.w = (const uint16_t*)a.w[widx];
                             Q.dy = (const uint16_t*)a.dy;

@@ -23,6 +23,9 @@ struct RunArgs {
     void* const* dw = nullptr;
     char* ws = nullptr;
     hipStream_t stream = nullptr;
+    // Elements between consecutive images of x / dx and of y / dy; 0 = dense.  Only a lowering with `strided_io` reads
+    // them (its input and output may then be channel slices of wider tensors).
+    int64_t x_stride = 0, y_stride = 0;
 };
 
 struct Launch {
@@ -51,6 +54,7 @@ struct ReduceJob {
 
 struct Lowering {
     bool fused = false;            // one of the whole-DAG kernel families
+    bool strided_io = false;       // honours RunArgs::x_stride / y_stride
     int chain_units = 0;           // fused chains in the forward list (each is one kernel forward, one backward)
     int chain_nodes = 0;           // nodes inside them
     uint64_t ws_bytes = 0;

@@ -44,10 +44,12 @@ constexpr int kTilePx = 128;  // pixels per wavefront tile
 constexpr int kWaves = 4;     // wavefronts per workgroup
 constexpr int kActNone = -1;  // ACT template value: no unary node; otherwise a UnaryKind
 
-// True (wave-uniform) when a tile's shifted accesses [first plane, last plane] x [p0+off, p0+off+136) leave the tensor.
-__device__ __forceinline__ bool tile_near_ends(int first_plane, int last_plane, int Pn, int p0, int off, int total_elems) {
-    return first_plane * Pn + p0 + off < 0 || last_plane * Pn + p0 + off + kTilePx + 8 > total_elems;
+// True (wave-uniform) when a tile's shifted accesses, planes starting at elements [first, last] x [p0+off, p0+off+136), leave the tensor.
+__device__ __forceinline__ bool tile_near_ends(int first, int last, int p0, int off, int total_elems) {
+    return first + p0 + off < 0 || last + p0 + off + kTilePx + 8 > total_elems;
 }
+// Elements a tensor of N images spans: `stride` apart, `planes` planes of Pn each (the last image ends with its own planes).
+__device__ __forceinline__ int extent(int N, int stride, int planes, int Pn) { return (N - 1) * stride + planes * Pn; }
 
 // Validity of the 128 pixels of a tile under a shift: bit i is 1 when tile pixel i exists (p < P) and
 // its source pixel (h+dh, w+dw) lies inside the image.  magic = ceil(2^32 / W) gives h = p / W exactly.
@@ -101,13 +103,14 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     const int Cout = P.G * OG;
     const int p0 = chunk * kTilePx, p = p0 + 8 * s;
     const int dh = P.dh[g], dw = P.dw[g], off = dh * P.W + dw;
-    const rsrc_t rx = make_rsrc(P.x, P.N * P.C * P.P * 2);
-    const rsrc_t ry = make_rsrc(P.y, P.N * Cout * P.P * 2);
+    const int xelems = extent(P.N, P.xs, P.C, P.P), yelems = extent(P.N, P.ys, Cout, P.P);
+    const rsrc_t rx = make_rsrc(P.x, xelems * 2);
+    const rsrc_t ry = make_rsrc(P.y, yelems * 2);
     const TileMask tm = tile_mask(p0, lane, P, dh, dw);
     const bool live = p < P.P;
     const uint32_t bits = live ? unit_bits(tm, s) : 0u;
     const u32x4 msk = mask_of(bits);
-    const int xg = ((n * P.C + g * CG) * P.P) * 2;  // byte offset of the group's first input plane
+    const int xg = (n * P.xs + g * CG * P.P) * 2;  // byte offset of the group's first input plane
 
     // weights: A operand, lane holds W[g][mo*16 + s][kc*16 + 4r .. +3]
     short4_t wa[MO][KC];
@@ -121,16 +124,16 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
     for (int kc = 0; kc < KC; kc++)
 #pragma unroll
         for (int j = 0; j < 4; j++) xs[kc][j] = bload16(rx, live ? xg + ((kc * 16 + 4 * r + j) * P.P + p + off) * 2 : kOob);
-    if (tile_near_ends(n * P.C + g * CG, n * P.C + g * CG + CG - 1, P.P, p0, off, P.N * P.C * P.P)) {
+    if (tile_near_ends(xg / 2, xg / 2 + (CG - 1) * P.P, p0, off, xelems)) {
 #pragma unroll
         for (int kc = 0; kc < KC; kc++)
 #pragma unroll
             for (int j = 0; j < 4; j++)
-                reload_if_partial(xs[kc][j], rx, live ? xg + ((kc * 16 + 4 * r + j) * P.P + p + off) * 2 : kOob, P.N * P.C * P.P * 2);
+                reload_if_partial(xs[kc][j], rx, live ? xg + ((kc * 16 + 4 * r + j) * P.P + p + off) * 2 : kOob, xelems * 2);
     }
     u32x4 xr[MO][4];
     if (RES) {
-        const int xo = ((n * P.C + g * OG) * P.P) * 2;
+        const int xo = (n * P.xs + g * OG * P.P) * 2;
 #pragma unroll
         for (int mo = 0; mo < MO; mo++)
 #pragma unroll
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_fwd(Params P) {
 #pragma unroll
             for (int mo = 0; mo < MO; mo++) acc[mo][q] = mfma16(wa[mo][kc], b[q], acc[mo][q]);  // (a group contracts 16 channels: K = 16 is the whole depth)
     }
-    const int yo = ((n * Cout + g * OG) * P.P) * 2;
+    const int yo = (n * P.ys + g * OG * P.P) * 2;
 #pragma unroll
     for (int mo = 0; mo < MO; mo++)
 #pragma unroll
@@ -198,8 +201,8 @@ __device__ __forceinline__ void bwd_tile(const Params& P, rsrc_t rx, rsrc_t rdy,
     const int Cout = P.G * OG;
     const int pA = p0 + 8 * s;
     const bool liveA = pA < P.P;
-    const int xg = ((n * P.C + g * CG) * P.P) * 2;
-    const int dyg = ((n * Cout + g * OG) * P.P) * 2;
+    const int xg = (n * P.xs + g * CG * P.P) * 2;
+    const int dyg = (n * P.ys + g * OG * P.P) * 2;
     // dy is read at p - d: validity of the shifted source uses (-dh, -dw)
     const TileMask tm = tile_mask(p0, lane, P, -dh, -dw);
     const u32x4 msk = mask_of(liveA ? unit_bits(tm, s) : 0u);
@@ -213,12 +216,13 @@ __device__ __forceinline__ void bwd_tile(const Params& P, rsrc_t rx, rsrc_t rdy,
     for (int mo = 0; mo < MO; mo++)
 #pragma unroll
         for (int j = 0; j < 4; j++) dya[mo][j] = bload16(rdy, liveA ? dyg + ((mo * 16 + 4 * r + j) * P.P + pA - off) * 2 : kOob);
-    if (tile_near_ends(n * Cout + g * OG, n * Cout + g * OG + OG - 1, P.P, p0, -off, P.N * Cout * P.P)) {
+    if (tile_near_ends(dyg / 2, dyg / 2 + (OG - 1) * P.P, p0, -off, extent(P.N, P.ys, Cout, P.P))) {
+        const int dyelems = extent(P.N, P.ys, Cout, P.P);
 #pragma unroll
         for (int mo = 0; mo < MO; mo++)
 #pragma unroll
             for (int j = 0; j < 4; j++)
-                reload_if_partial(dya[mo][j], rdy, liveA ? dyg + ((mo * 16 + 4 * r + j) * P.P + pA - off) * 2 : kOob, P.N * Cout * P.P * 2);
+                reload_if_partial(dya[mo][j], rdy, liveA ? dyg + ((mo * 16 + 4 * r + j) * P.P + pA - off) * 2 : kOob, dyelems * 2);
     }
     // (the unshifted dy of the residual: with one 16-channel block per group it is fetched with everything else; with
     // more the registers are short, and each block's rows are fetched just ahead of its dx)
@@ -244,29 +248,31 @@ __device__ __forceinline__ void bwd_tile(const Params& P, rsrc_t rx, rsrc_t rdy,
 #pragma unroll
         for (int j = 0; j < 4; j++) dya[mo][j] = dya[mo][j] & msk;
         u32x4 dzrow[4];  // dz of channel 4r+j over the unit's 8 pixels, for the LDS tile
-        // two halves of four pixel offsets keep the live accumulators at 16 registers
+        // steps of QS pixel offsets keep the live accumulators at 4 * QS registers (16; 8 where a group has more than
+        // one 16-channel block and the tile's registers are short)
+        constexpr int QS = KC > 1 ? 2 : 4;
 #pragma unroll
-        for (int h = 0; h < 2; h++) {
-            float4_t z[4];
+        for (int h = 0; h < 8 / QS; h++) {
+            float4_t z[QS];
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
+            for (int q = 0; q < QS; q++) {
                 z[q] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kc = 0; kc < KC; kc++) z[q] = mfma16(wa[mo][kc], xq[kc][4 * h + q], z[q]);
+                for (int kc = 0; kc < KC; kc++) z[q] = mfma16(wa[mo][kc], xq[kc][QS * h + q], z[q]);
             }
-            float d[4][4];
+            float d[QS][4];
 #pragma unroll
             for (int j = 0; j < 4; j++) {
-                const uint32_t w0 = dya[mo][j][2 * h], w1 = dya[mo][j][2 * h + 1];
-                d[0][j] = act_dz<ACT>(P, z[0][j], lo_f32(w0));
-                d[1][j] = act_dz<ACT>(P, z[1][j], hi_f32(w0));
-                d[2][j] = act_dz<ACT>(P, z[2][j], lo_f32(w1));
-                d[3][j] = act_dz<ACT>(P, z[3][j], hi_f32(w1));
-                dzrow[j][2 * h] = pack_bf16(d[0][j], d[1][j]);
-                dzrow[j][2 * h + 1] = pack_bf16(d[2][j], d[3][j]);
+#pragma unroll
+                for (int q = 0; q < QS; q += 2) {
+                    const uint32_t w = dya[mo][j][(QS * h + q) / 2];
+                    d[q][j] = act_dz<ACT>(P, z[q][j], lo_f32(w));
+                    d[q + 1][j] = act_dz<ACT>(P, z[q + 1][j], hi_f32(w));
+                    dzrow[j][(QS * h + q) / 2] = pack_bf16(d[q][j], d[q + 1][j]);
+                }
             }
 #pragma unroll
-            for (int q = 0; q < 4; q++) dzq[mo][4 * h + q] = pack4(d[q][0], d[q][1], d[q][2], d[q][3]);
+            for (int q = 0; q < QS; q++) dzq[mo][QS * h + q] = pack4(d[q][0], d[q][1], d[q][2], d[q][3]);
         }
 #pragma unroll
         for (int j = 0; j < 4; j++) lds_dz[(mo * 16 + 4 * r + j) * kLdsRow + s] = dzrow[j];
@@ -328,9 +334,9 @@ __device__ __forceinline__ void bwd_body(const Params& P) {
     const int g = blockIdx.y;
     const int wg = blockIdx.x;
     const int Cout = P.G * OG;
-    const rsrc_t rx = make_rsrc(P.x, P.N * P.C * P.P * 2);
-    const rsrc_t rdx = make_rsrc(P.dx, P.N * P.C * P.P * 2);
-    const rsrc_t rdy = make_rsrc(P.dy, P.N * Cout * P.P * 2);
+    const rsrc_t rx = make_rsrc(P.x, extent(P.N, P.xs, P.C, P.P) * 2);
+    const rsrc_t rdx = make_rsrc(P.dx, extent(P.N, P.xs, P.C, P.P) * 2);
+    const rsrc_t rdy = make_rsrc(P.dy, extent(P.N, P.ys, Cout, P.P) * 2);
     u32x4* lds_x = lds[wave];
     u32x4* lds_dz = lds[wave] + KC * 16 * kLdsRow;
 

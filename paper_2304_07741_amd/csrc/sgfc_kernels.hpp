@@ -17,6 +17,8 @@ struct Params {
     uint16_t* dx = nullptr;
     float* partial = nullptr;      // [G, wgs_per_group, OG*CG] fp32 partial weight gradients, one per workgroup
     int N = 0, C = 0, H = 0, W = 0, P = 0, G = 0;
+    int xs = 0, ys = 0;            // elements between consecutive images of x / dx and of y / dy (C * P and G * OG * P when dense;
+                                   // larger when the tensor is a channel slice of a wider one)
     int chunks = 0;                // ceil(P / 128)
     long long total_tiles = 0;     // N * G * chunks
     int wgs_per_group = 0, tiles_per_wave = 1;  // backward work split
