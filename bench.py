@@ -35,20 +35,20 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # plain copy of 25 088 KiB reads FETCH_SIZE 12 557 -> units of 1.998 KiB, and WRITE_SIZE 25 088 -> KiB; the dispatches of
 # a run are attributed to the launches of a step by position; commands and tables in profiles/).  The figures are valid
 # only for the kernel sources they were taken on (one hash over the library's source folder), otherwise `traffic` is null.
-TRAFFIC_SHA256 = "871e69eea4539f909537f4ba24bf5f4a8a1c80f7654899d0db1a555438d9ac5b"
+TRAFFIC_SHA256 = "c81f2e0c9b21eabf07160bdc84106a47da094eac69de5febbce21305d9a1c9ad"
 TRAFFIC_KIB = {  # workload -> launch (phase:name) -> (KiB fetched, KiB written) per launch
-    'shift_residual': {'fwd:sgfc_fwd': (28791.9, 25089.6), 'bwd:sgfc_bwd': (52698.9, 25900.7), 'bwd:sgfc_dw_reduce': (3226.7, 4.0)},
-    'involution': {'fwd:weight_prep': (326.0, 40.0), 'fwd:dyn_fc1_softmax': (6732.3, 882.0), 'fwd:dyn_apply': (7266.3, 6272.0), 'fwd:dyn_fc2': (6990.8, 6272.0), 'bwd:dyn_fc2_wgrad': (15871.7, 6656.0), 'bwd:dyn_fc2_dgrad': (6990.7, 6272.0), 'bwd:dyn_apply_dx_da': (20213.3, 7154.2), 'bwd:dyn_softmax_bwd': (2088.0, 1323.0), 'bwd:dyn_fc1_wgrad': (10051.6, 900.0), 'bwd:dyn_fc1_dgrad': (7235.0, 6272.0), 'bwd:wgrad_reduce': (7617.1, 68.5)},
-    'sampled_c64_h56': {'fwd:weight_prep': (169.0, 44.0), 'fwd:ufc_fc1_unfold': (50563.7, 50176.0), 'fwd:ufc_mid_fwd': (101104.2, 50181.9), 'fwd:ufc_fc2': (50606.6, 50176.0), 'bwd:ufc_fc2_wgrad': (100518.9, 6272.0), 'bwd:ufc_fc2_dgrad': (50606.5, 50176.0), 'bwd:ufc_mid_bwd': (152854.5, 100352.0), 'bwd:ufc_fc1_wgrad_unfold': (105579.9, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (100855.2, 50176.0), 'bwd:wgrad_reduce': (10937.7, 104.0)},
-    'sampled_c128_h28': {'fwd:weight_prep': (531.7, 104.0), 'fwd:ufc_fc1_unfold': (25631.4, 25100.4), 'fwd:ufc_mid_fwd': (50596.4, 25089.6), 'fwd:ufc_fc2': (26279.8, 25095.3), 'bwd:ufc_fc2_wgrad': (65424.6, 6656.0), 'bwd:ufc_fc2_dgrad': (26279.8, 25088.0), 'bwd:ufc_mid_bwd': (76485.7, 50176.0), 'bwd:ufc_fc1_wgrad_unfold': (60958.7, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (50700.4, 25135.8), 'bwd:wgrad_reduce': (11321.3, 416.0)},
-    'sampled_c256_h14': {'fwd:weight_prep': (2214.1, 416.0), 'fwd:ufc_fc1_unfold': (13282.0, 12563.9), 'fwd:ufc_mid_fwd': (25905.0, 12873.0), 'fwd:ufc_fc2': (14591.8, 12592.0), 'bwd:ufc_fc2_wgrad': (25351.6, 8192.0), 'bwd:ufc_fc2_dgrad': (14591.7, 12592.0), 'bwd:ufc_mid_bwd': (38884.7, 25700.6), 'bwd:ufc_fc1_wgrad_unfold': (61697.5, 6624.0), 'bwd:ufc_fc1_dgrad_unfold': (26114.2, 12604.3), 'bwd:wgrad_reduce': (14869.6, 1104.0)},
-    'sampled_c512_h7': {'fwd:weight_prep': (6709.6, 1664.0), 'fwd:ufc_fc1_unfold': (7412.6, 6273.5), 'fwd:ufc_mid_fwd': (13052.3, 6322.5), 'fwd:ufc_fc2': (10616.9, 6272.0), 'bwd:ufc_fc2_wgrad': (12804.6, 8192.0), 'bwd:ufc_fc2_dgrad': (10616.9, 6272.0), 'bwd:ufc_mid_bwd': (19622.6, 12647.5), 'bwd:ufc_fc1_wgrad_unfold': (19711.7, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (13693.7, 6279.9), 'bwd:wgrad_reduce': (12855.7, 6656.0)},
-    'chain_relu': {'fwd:chain_fwd': (50471.2, 56946.6), 'bwd:chain_bwd': (100740.5, 56643.4)},
-    'chain_gate': {'fwd:chain_fwd': (50666.7, 62774.3), 'bwd:chain_bwd': (101160.5, 59605.0)},
-    'chain_shift_residual': {'fwd:chain_fwd': (50639.5, 60072.6), 'bwd:chain_bwd': (100841.3, 57078.2)},
-    'chain_box3': {'fwd:chain_fwd': (51170.4, 50556.6), 'bwd:chain_bwd': (50760.4, 50176.0)},
-    'chain_softmax_c': {'fwd:chain_fwd': (99258.4, 56119.7), 'bwd:chain_bwd': (251307.4, 53419.7)},
-    'fuzz': {'all:chain': (78628.7, 40464.6)},
+    'shift_residual': {'fwd:sgfc_fwd': (28778.7, 25089.8), 'bwd:sgfc_bwd': (52696.0, 25889.4), 'bwd:sgfc_dw_reduce': (3226.7, 4.0)},
+    'involution': {'fwd:weight_prep': (326.0, 40.0), 'fwd:dyn_fc1_softmax': (6732.3, 882.0), 'fwd:dyn_apply': (7266.3, 6272.0), 'fwd:dyn_fc2': (6990.8, 6272.0), 'bwd:dyn_fc2_wgrad': (15871.8, 6656.0), 'bwd:dyn_fc2_dgrad': (6990.8, 6272.0), 'bwd:dyn_apply_dx_da': (20213.4, 7154.2), 'bwd:dyn_softmax_bwd': (2088.0, 1323.0), 'bwd:dyn_fc1_wgrad': (10051.7, 900.0), 'bwd:dyn_fc1_dgrad': (7235.1, 6272.0), 'bwd:wgrad_reduce': (7617.2, 68.5)},
+    'sampled_c64_h56': {'fwd:weight_prep': (169.0, 44.0), 'fwd:ufc_fc1_unfold': (50563.6, 50176.0), 'fwd:ufc_mid_fwd': (101104.6, 50178.6), 'fwd:ufc_fc2': (50606.8, 50176.0), 'bwd:ufc_fc2_wgrad': (100519.4, 6272.0), 'bwd:ufc_fc2_dgrad': (50606.8, 50176.0), 'bwd:ufc_mid_bwd': (152855.2, 100352.0), 'bwd:ufc_fc1_wgrad_unfold': (105580.3, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (100700.7, 50176.0), 'bwd:wgrad_reduce': (10937.7, 104.0)},
+    'sampled_c128_h28': {'fwd:weight_prep': (531.7, 104.0), 'fwd:ufc_fc1_unfold': (25631.8, 25100.8), 'fwd:ufc_mid_fwd': (50596.7, 25090.3), 'fwd:ufc_fc2': (26279.9, 25094.1), 'bwd:ufc_fc2_wgrad': (65556.4, 6656.0), 'bwd:ufc_fc2_dgrad': (26279.9, 25088.0), 'bwd:ufc_mid_bwd': (76486.2, 50176.0), 'bwd:ufc_fc1_wgrad_unfold': (60955.6, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (50699.9, 25133.7), 'bwd:wgrad_reduce': (11321.3, 416.0)},
+    'sampled_c256_h14': {'fwd:weight_prep': (2214.1, 416.0), 'fwd:ufc_fc1_unfold': (13282.1, 12566.1), 'fwd:ufc_mid_fwd': (25905.1, 12866.3), 'fwd:ufc_fc2': (14592.0, 12592.0), 'bwd:ufc_fc2_wgrad': (25350.4, 8192.0), 'bwd:ufc_fc2_dgrad': (14591.8, 12592.0), 'bwd:ufc_mid_bwd': (38884.9, 25714.4), 'bwd:ufc_fc1_wgrad_unfold': (61694.4, 6624.0), 'bwd:ufc_fc1_dgrad_unfold': (26112.8, 12604.4), 'bwd:wgrad_reduce': (14869.7, 1104.0)},
+    'sampled_c512_h7': {'fwd:weight_prep': (6709.6, 1664.0), 'fwd:ufc_fc1_unfold': (7412.6, 6273.3), 'fwd:ufc_mid_fwd': (13052.4, 6322.4), 'fwd:ufc_fc2': (10616.9, 6272.0), 'bwd:ufc_fc2_wgrad': (12804.6, 8192.0), 'bwd:ufc_fc2_dgrad': (10616.9, 6272.0), 'bwd:ufc_mid_bwd': (19622.7, 12647.9), 'bwd:ufc_fc1_wgrad_unfold': (19711.8, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (13692.7, 6279.9), 'bwd:wgrad_reduce': (12855.8, 6656.0)},
+    'chain_relu': {'fwd:chain_fwd': (50471.4, 56721.3), 'bwd:chain_bwd': (100740.6, 56656.6)},
+    'chain_gate': {'fwd:chain_fwd': (50666.2, 62812.1), 'bwd:chain_bwd': (101160.6, 59575.7)},
+    'chain_shift_residual': {'fwd:chain_fwd': (50638.0, 60129.8), 'bwd:chain_bwd': (100841.1, 57027.2)},
+    'chain_box3': {'fwd:chain_fwd': (51173.3, 50557.4), 'bwd:chain_bwd': (50760.6, 50176.0)},
+    'chain_softmax_c': {'fwd:chain_fwd': (99251.8, 56137.7), 'bwd:chain_bwd': (251308.3, 53414.9)},
+    'fuzz': {'all:chain': (78630.7, 40470.6)},
 }
 
 
@@ -56,9 +56,13 @@ def traffic_hash():
     import glob
     import hashlib
 
+    # files of the source folder that hold no kernel and no launch logic of the workloads in the table (blocks composed
+    # of several plans, templates and their solvers) are left out
+    _NOT_MEASURED = {"block.hip", "plan_calls.hpp", "template.cpp", "symbolic.cpp", "symbolic.hpp"}
     h = hashlib.sha256()
     for f in sorted(glob.glob(os.path.join(ROOT, "paper_2304_07741_amd", "csrc", "*"))):
-        h.update(open(f, "rb").read())
+        if os.path.basename(f) not in _NOT_MEASURED:
+            h.update(open(f, "rb").read())
     return h.hexdigest()
 
 

@@ -33,6 +33,8 @@ struct canvas_block {
     uint64_t plan_ws = 0, dense = 0, off_a = 0, off_b = 0;  // workspace: m plan workspaces | m dense inputs | m dense results
 };
 
+namespace canvas {
+namespace block {
 namespace {
 
 using canvas::tile::u32x4;
@@ -59,20 +61,45 @@ __global__ __launch_bounds__(256) void k_regroup(const unsigned char* __restrict
     else *reinterpret_cast<uint16_t*>(d) = *reinterpret_cast<const uint16_t*>(s);
 }
 
-// out[i] = parts[0][i] + parts[1][i] + ... (fp32, in that order), rounded to the element type once
+// out[i] = parts[0][i] + parts[1][i] + ... (fp32, in that order), rounded to the element type once.  A thread takes 16 bytes
+// of every part (8 bf16 or 4 fp32 elements; `pieces` such pieces, the parts are 256-byte aligned); the elements past the
+// last whole piece go one per thread.
 template <bool BF16>
 __global__ __launch_bounds__(256) void k_sum(const unsigned char* __restrict__ parts, long long part_stride, int m, void* __restrict__ out,
-                                             long long count) {
+                                             long long count, long long pieces) {
+    constexpr int E = BF16 ? 8 : 4;
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= count) return;
+    if (i < pieces) {
+        float t[E];
+        for (int j = 0; j < m; j++) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(parts + j * part_stride + i * 16);
+#pragma unroll
+            for (int e = 0; e < E; e++) {
+                float f;
+                if constexpr (BF16) f = (e & 1) ? canvas::tile::hi_f32(v[e >> 1]) : canvas::tile::lo_f32(v[e >> 1]);
+                else f = __uint_as_float(v[e]);
+                t[e] = j == 0 ? f : t[e] + f;
+            }
+        }
+        u32x4 o;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            if constexpr (BF16) o[k] = canvas::tile::pack_bf16(t[2 * k], t[2 * k + 1]);
+            else o[k] = __float_as_uint(t[k]);
+        }
+        *reinterpret_cast<u32x4*>((unsigned char*)out + i * 16) = o;
+        return;
+    }
+    const long long e = pieces * E + (i - pieces);
+    if (e >= count) return;
     float t = 0.f;
     for (int j = 0; j < m; j++) {
         const unsigned char* p = parts + j * part_stride;
-        const float v = BF16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(p)[i] << 16) : reinterpret_cast<const float*>(p)[i];
+        const float v = BF16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(p)[e] << 16) : reinterpret_cast<const float*>(p)[e];
         t = j == 0 ? v : t + v;
     }
-    if (BF16) reinterpret_cast<uint16_t*>(out)[i] = (uint16_t)(canvas::tile::pack_bf16(t, 0.f) & 0xffffu);
-    else reinterpret_cast<float*>(out)[i] = t;
+    if (BF16) reinterpret_cast<uint16_t*>(out)[e] = (uint16_t)(canvas::tile::pack_bf16(t, 0.f) & 0xffffu);
+    else reinterpret_cast<float*>(out)[e] = t;
 }
 
 // all m channel slices of `sliced` ([N, m C, P]) to the m dense tensors at `dense` or back
@@ -90,9 +117,10 @@ void regroup(const canvas_block* b, const void* src, void* dst, bool to_dense, h
 void sum_instances(const canvas_block* b, const void* parts, void* out, hipStream_t s) {
     const long long count = b->N * b->C * b->P;
     if (count == 0) return;
-    const dim3 grid((unsigned)((count + 255) / 256)), block(256);
-    if (b->bf16) CANVAS_LAUNCH(k_sum<true>, grid, block, 0, s, (const unsigned char*)parts, (long long)b->dense, b->m, out, count);
-    else CANVAS_LAUNCH(k_sum<false>, grid, block, 0, s, (const unsigned char*)parts, (long long)b->dense, b->m, out, count);
+    const long long pieces = count / (b->bf16 ? 8 : 4), threads = pieces + (count - pieces * (b->bf16 ? 8 : 4));
+    const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+    if (b->bf16) CANVAS_LAUNCH(k_sum<true>, grid, block, 0, s, (const unsigned char*)parts, (long long)b->dense, b->m, out, count, pieces);
+    else CANVAS_LAUNCH(k_sum<false>, grid, block, 0, s, (const unsigned char*)parts, (long long)b->dense, b->m, out, count, pieces);
 }
 
 int check(const canvas_block* b, const void* x, const void* const* weights, const void* ws, size_t ws_bytes) {
@@ -111,6 +139,10 @@ int finish() {
 }
 
 }  // namespace
+}  // namespace block
+}  // namespace canvas
+
+using namespace canvas::block;
 
 extern "C" {
 
