@@ -660,7 +660,10 @@ bool chain_candidate(const Dag& dag, int k) {
         const Node& B = dag.nodes[nd.b];
         return nd.bgroups == 1 && !nd.lhs_pixels && !B.pooled && A.C == B.C && B.T <= 25 && B.T % A.T == 0;
     }
-    case Op::Softmax: return nd.kind == kAxisC || nd.kind == kAxisT;
+    // (a softmax over the channels of a tensor with taps stays a kernel of its own on the materialised tensor: each of
+    // its passes over the channel range would evaluate the whole window again, and backward hands T lanes over per channel
+    // and pass; measured on the 200 random DAGs such chains took 1.2-2.5 ms where the kernels per node take 0.1-0.4 ms)
+    case Op::Softmax: return (nd.kind == kAxisC && nd.T == 1) || nd.kind == kAxisT;
     case Op::Fold: return !nd.axis_hw && !nd.axis_c;
     default: return false;
     }

@@ -246,7 +246,12 @@ std::unique_ptr<Lowering> lower_per_node(const Dag& dag, bool bf16, bool fuse_ch
             if (!chain::compile_unit(dag, U.nodes, outputs_of(U.nodes), U.plan, why)) throw std::runtime_error("chain unit no longer compiles: " + why);
             low->chain_units++;
             low->chain_nodes += (int)U.nodes.size();
-            if (log) std::fprintf(stderr, "canvas: chain of %zu nodes\n%s%s", U.nodes.size(), chain::dump(U.plan.fwd).c_str(), chain::dump(U.plan.bwd).c_str());
+            if (log) {
+                std::string ids;
+                for (int k : U.nodes) ids += " " + std::to_string(k);
+                std::fprintf(stderr, "canvas: chain of %zu nodes [%s ] cost fwd %.1f bwd %.1f\n%s%s", U.nodes.size(), ids.c_str(),
+                             chain::program_cost(U.plan.fwd), chain::program_cost(U.plan.bwd), chain::dump(U.plan.fwd).c_str(), chain::dump(U.plan.bwd).c_str());
+            }
         }
     // materialised nodes: everything outside a chain, and the stored nodes of a chain
     std::vector<bool> mat(n, false);
