@@ -33,6 +33,22 @@ def _cases():
 CASES = _cases()
 
 
+def _random_template_cases():
+    """Random micro-DAGs (the generator of config 5; every one maps [C, H, W] to [C, H, W]) as templates: whatever the
+    plan is made of (chains, FC kernels, kernels per node), the block runs it on regrouped dense tensors."""
+    out = []
+    for k, seed in enumerate(range(100, 116)):
+        t = wl.config5(seed, N=2, C=48, H=12)
+        wstds = [1.0 / math.sqrt(s[2]) for s in t["wshapes"]]
+        m = 2 + k % 2
+        c_in, c_out = (48, 48 * m) if k % 4 < 2 else (48 * m, 48)
+        out.append((f"fuzz{seed}", t["blob"], (2, c_in, 12, 12), c_out, "bf16", t["wshapes"], wstds))
+    return out
+
+
+CASES += _random_template_cases()
+
+
 @pytest.mark.parametrize("idx", range(len(CASES)))
 def test_block_against_the_oracle(idx):
     from oracle import block_oracle
