@@ -5,7 +5,7 @@ of its dominant kernel and the CPU oracle timed beside it.
     python bench.py --workload chain_gate|chain_relu|chain_shift_residual|chain_box3|chain_softmax_c[_cC_hH]
                                                        (an FC-free fused chain at a ResNet layer shape, N=128, vs the HBM roof)
     python bench.py --workload block_64_256      (a block C_in=64 => C_out=256 composed of four shift_residual templates)
-    python bench.py --workload fuzz [--seeds 100:300]  (config 5: geometric mean over the random DAGs, chain kernels vs HBM)
+    python bench.py --workload fuzz [--seeds 100:300] [--compare]  (config 5: geometric mean over the random DAGs, chain kernels vs HBM)
     python bench.py --fc-micro                         (grouped-FC kernels of config 4, operands in cache, vs MFMA peak)
     python bench.py --infer BATCH [--workload ...]     (forward-only latency of the inference plan, not the headline)
 
@@ -326,9 +326,14 @@ def fuzz_bench(args):
     flags = B.CANVAS_OPT_NO_FUSION if args.no_fusion else 0
     logs, chain_ms, chain_bytes, all_ms, nf, nb, fully, with_chain = 0.0, 0.0, 0.0, 0.0, 0, 0, 0, 0
     slowest = None
+    ratio_logs, faster = 0.0, 0  # --compare: every DAG also with one kernel per node, right after the fused run
     for seed in range(lo, hi):
         case = wl.config5(seed)
         ms, launches, info = measure(case, flags, args.steps, args.warmup, kernel_steps=min(args.steps, 10))
+        if args.compare and not args.no_fusion:
+            ms_nodes, _, _ = measure(case, B.CANVAS_OPT_NO_FUSION, args.steps, args.warmup, kernel_steps=1)
+            ratio_logs += math.log(ms / ms_nodes)
+            faster += 1 if ms < ms_nodes else 0
         logs += math.log(case["shape"][0] / (ms * 1e-3))
         for l in launches:
             all_ms += l["ms"]
@@ -358,6 +363,8 @@ def fuzz_bench(args):
                      "kernel_ms": chain_ms / n, "algorithmic_bytes": chain_bytes / n},
         "chain_time_share": chain_ms / max(all_ms, 1e-12),
     }
+    if args.compare and not args.no_fusion:
+        out["against_one_kernel_per_node"] = {"geomean_step_time_ratio": math.exp(ratio_logs / n), "dags_faster": faster, "dags_slower": n - faster}
     print(json.dumps(out))
 
 
@@ -456,6 +463,7 @@ def main():
     ap.add_argument("--workload", default="shift_residual",
                     help="shift_residual (config 2, the headline), involution (config 3), sampled_cC_hH (config 4), fuzz (config 5)")
     ap.add_argument("--seeds", default="100:300", help="fuzz: range of seeds lo:hi")
+    ap.add_argument("--compare", action="store_true", help="fuzz: time every DAG with one kernel per node as well and report the ratio")
     ap.add_argument("--no-fusion", action="store_true", help="per-node lowering (for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true", help="headline workload only: skip the per_config runs of configs 3 and 4")
