@@ -52,13 +52,14 @@ struct Ctx {
     }
 };
 
-enum InstKind { kExt, kIdent, kStencil, kUnaryI, kBinaryI, kSmT, kSmC, kFoldI };
+enum InstKind { kExt, kIdent, kStencil, kUnaryI, kBinaryI, kSmT, kSmC, kFoldI, kBoxAdj };
 
 struct Inst {
     int node = -1, ctx = 0, lanes = 1;
     InstKind kind = kExt;
     int opnd[2] = {-1, -1};
     std::vector<std::pair<int, int>> users;  // (instance, operand slot)
+    int aux = -1;                            // kBoxAdj: the context of the window (see Graph::add_box_adjoints)
     int level = 0;                           // softmax-over-channels instances at or below this one (longest chain)
     int down = -1;                           // such instances above it (memo)
 };
@@ -170,6 +171,41 @@ class Graph {
             if (I.opnd[s] >= 0) insts[I.opnd[s]].users.push_back({id, s});
         memo[key] = id;
         return id;
+    }
+
+    // Unfold followed at once by a sum / avg Fold that is an output of the unit and feeds nothing inside it is a linear
+    // operator on the unfolded tensor's source (a box filter); its adjoint is the same filter applied to the incoming
+    // gradient (the window is symmetric), which the pixel reads itself: a window load of dy and a fold, no hand-over of
+    // T lanes to the neighbours.  Where EVERY Unfold of the unit is of that kind, each gets a pseudo user of its source's
+    // own-pixel instance that stands for this adjoint in the backward program, and the leaves read through windows drop
+    // out of it.  Returns whether that is so.
+    bool add_box_adjoints() {
+        std::vector<std::pair<int, int>> pairs;  // (unfold instance, fold instance)
+        for (size_t i = 0; i < insts.size(); i++) {
+            const Inst& U = insts[i];
+            if (U.kind != kStencil || dag.nodes[U.node].op != Op::Unfold) continue;
+            if (U.users.size() != 1) return false;
+            const Inst& F = insts[U.users[0].first];
+            const Node& fn = dag.nodes[F.node];
+            if (F.kind != kFoldI || (fn.kind != kSum && fn.kind != kAvg) || !F.users.empty() || !is_output_[F.node] || F.ctx != 0 || U.ctx != 0)
+                return false;
+            pairs.push_back({(int)i, U.users[0].first});
+        }
+        if (pairs.empty()) return false;
+        for (const auto& pr : pairs) {
+            const int win_ctx = insts[insts[pr.first].opnd[0]].ctx;
+            const int src = build(dag.nodes[insts[pr.first].node].a, insts[pr.first].ctx);
+            if (insts[src].lanes != 1) throw Fail{"internal: the source of an unfold with taps"};
+            Inst B;
+            B.node = insts[pr.second].node;
+            B.ctx = insts[pr.first].ctx;
+            B.lanes = 1;
+            B.kind = kBoxAdj;
+            B.opnd[0] = src;
+            B.aux = win_ctx;
+            add(std::make_tuple(-1 - B.node, B.ctx, 1), B);
+        }
+        return true;
     }
 
     // softmax-over-channels instances on the longest way from instance i up to an output (i itself not counted)
@@ -375,6 +411,7 @@ class Emitter {
             eval(I.opnd[0]);
             emit(simple(OP_FOLD, G->insts[I.opnd[0]].lanes, 0, nd.kind));
             break;
+        case kBoxAdj: throw Fail{"internal: the value of a box adjoint"};
         }
     }
 
@@ -429,6 +466,14 @@ class Emitter {
         const Inst& U = G->insts[u];
         const Inst& I = G->insts[i];
         const Node& un = G->dag.nodes[U.node];
+        if (U.kind == kBoxAdj) {  // the box filter's adjoint: the same filter over the incoming gradient of the fold's output
+            const Ctx& wc = G->ctxs[U.aux];
+            Instr ld = positional(OP_LD, U.aux, wc.kh * wc.kw);
+            ld.a = (uint16_t)ext_slot(U.node, kGradIn);
+            emit(ld);
+            emit(simple(OP_FOLD, wc.kh * wc.kw, 0, un.kind));
+            return;
+        }
         grad(u);  // A = gradient of u, U.lanes lanes
         switch (U.kind) {
         case kIdent: break;
@@ -502,6 +547,7 @@ class Emitter {
             release(r);
             break;
         }
+        case kBoxAdj: break;  // (handled above)
         case kExt: throw Fail{"internal: an external tensor as a user"};
         }
     }
@@ -687,13 +733,14 @@ bool compile_unit(const Dag& dag, const std::vector<int>& nodes, const std::vect
                 out_inst.push_back(G.build(k, 0));
             }
         if (out.outputs.empty()) throw Fail{"unit without an output"};
+        const bool box = G.add_box_adjoints();  // (backward only: the forward program never evaluates what this adds)
         int lanes = 1;
         std::vector<int> smc, leaves;
         for (size_t i = 0; i < G.insts.size(); i++) {
             lanes = std::max(lanes, G.insts[i].lanes);
             if (G.insts[i].kind == kSmC) smc.push_back((int)i);
             if (G.insts[i].kind == kExt) {
-                leaves.push_back((int)i);
+                if (!(box && G.ctxs[G.insts[i].ctx].win)) leaves.push_back((int)i);  // (a box adjoint replaces the way through its window)
                 if (std::find(out.inputs.begin(), out.inputs.end(), G.insts[i].node) == out.inputs.end()) out.inputs.push_back(G.insts[i].node);
             }
         }
