@@ -48,6 +48,7 @@ struct Thread {
 struct Geo {
     int H = 0, W = 0, C = 0, HW = 0, N = 0;
     int npx = 0;  // pixels a slice of the workgroup computes = pix_threads * V
+    bool whole_rows = false;  // W is a multiple of V: the V pixels of a thread never straddle two image rows
 };
 
 // Each case of the dispatch begins with an empty volatile asm statement: the cases are small, and without it the
@@ -93,6 +94,7 @@ CHAIN_HD Geo vm_geo(const Program& pg) {
     g.N = vm_u(pg.N);
     g.HW = g.H * g.W;
     g.npx = vm_u(pg.pix_threads) * vm_u(pg.vec);
+    g.whole_rows = g.W % vm_u(pg.vec) == 0;
     return g;
 }
 
@@ -430,6 +432,13 @@ CHAIN_HD float vm_keep(float x, uint32_t m, int v) { return vm_bits_to_f32(vm_f3
 template <int V>
 CHAIN_HD uint32_t vm_valid(const Geo& g, const Thread& th, int oh, int ow) {
     if (!th.active) return 0;
+    if (g.whole_rows) {
+        // all V pixels lie in row0 (col0 is a multiple of V): the row is inside or not as a whole, and columns fall off only
+        // at the row's first pixels (to the left) or last pixels (to the right)
+        if ((unsigned)(th.row0 + oh) >= (unsigned)g.H) return 0;
+        const int first = -(th.col0 + ow), behind = g.W - th.col0 - ow;
+        return vm_bits(first > 0 ? first : 0, behind < V ? behind : V);
+    }
     const int n1 = g.W - th.col0 < V ? g.W - th.col0 : V;  // pixels [0, n1) lie in row0, [n1, V) in row0 + 1
     const int first = -(th.col0 + ow), behind = g.W - th.col0 - ow;  // pixel v of row0 has column v - first; valid for first <= v < behind
     uint32_t m = 0;
@@ -481,6 +490,59 @@ CHAIN_HD void vm_ld(const Program& pg, const Geo& g, const Instr& I, const Env& 
             const int chan = (th.n * g.C + ev.c + u) * e.T;  // first plane of (image, channel): uniform
             if (I.kind & kWin) {
                 const int KH = I.r >> 4, KW = I.r & 15;
+#if defined(__HIP_DEVICE_COMPILE__)
+                if ((V == 4 || V == 2 || V == 1) && e.bf16) {
+                    // All loads of the window are issued before the first is looked at: one round trip to memory for the
+                    // T taps, not T (tap by tap, each load was followed by its own wait: the fix-up of an access that
+                    // straddles an end of the tensor may overwrite what was loaded).
+                    constexpr int D = V == 1 ? 1 : V / 2;
+                    uint32_t raw[TM][D];
+                    int off[TM];
+#pragma unroll
+                    for (int t = 0; t < TM; t++)
+                        if (t < T) {
+                            int oh, ow;
+                            vm_tap(t, KH, KW, oh, ow);
+                            off[t] = (chan * g.HW + th.p0 + (dh + oh) * g.W + dw + ow) * 2;
+                            // (each tap's offset in a register of its own: a negative base register plus the tap's
+                            // distance as the instruction's immediate offset is not what the bounds check expects)
+                            asm volatile("" : "+v"(off[t]));
+                            if (V == 4) {
+                                const vm_u32x2 d = __builtin_amdgcn_raw_buffer_load_b64(e.rs, off[t], 0, 0);
+                                raw[t][0] = d[0];
+                                raw[t][D - 1] = d[1];
+                            } else if (V == 2) {
+                                raw[t][0] = __builtin_amdgcn_raw_buffer_load_b32(e.rs, off[t], 0, 0);
+                            } else {  // (one element: inside the tensor or not)
+                                raw[t][0] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(e.rs, (unsigned)off[t] < (unsigned)e.bytes ? off[t] : tile::kOob, 0, 0);
+                            }
+                        }
+#pragma unroll
+                    for (int t = 0; t < TM; t++)
+                        if (t < T) {
+                            int oh, ow;
+                            vm_tap(t, KH, KW, oh, ow);
+                            if (V > 1 && tile::straddles_an_end(off[t], 2 * V, e.bytes)) {
+#pragma unroll
+                                for (int k = 0; k < D; k++)
+                                    raw[t][k] = tile::elem_b16(e.rs, off[t] + 4 * k, e.bytes) | (tile::elem_b16(e.rs, off[t] + 4 * k + 2, e.bytes) << 16);
+                            }
+                            const bool centre = dh + oh == 0 && dw + ow == 0;  // (uniform; without displacement nothing is masked)
+                            const uint32_t m = centre ? 0xffffffffu : vm_valid<V>(g, th, dh + oh, dw + ow);
+                            float* out = dst + u * TV + t * V;
+                            if (V == 1) {
+                                out[0] = vm_keep(tile::lo_f32(raw[t][0]), m, 0);
+                            } else {
+#pragma unroll
+                                for (int k = 0; k < V / 2; k++) {
+                                    out[2 * k] = vm_keep(tile::lo_f32(raw[t][k]), m, 2 * k);
+                                    out[2 * k + 1] = vm_keep(tile::hi_f32(raw[t][k]), m, 2 * k + 1);
+                                }
+                            }
+                        }
+                    continue;
+                }
+#endif
 #pragma unroll
                 for (int t = 0; t < TM; t++)
                     if (t < T) {
