@@ -466,6 +466,84 @@ CHAIN_HD void vm_load_at(const Tensor& e, const Geo& g, const Thread& th, int pl
     }
 }
 
+#if defined(__HIP_DEVICE_COMPILE__)
+// The T = KH * KW taps of a window of a bf16 tensor, displaced by (dh, dw), for the thread's V pixels of plane `chan`:
+// out[t * V + v], 0 outside the image.  All loads are issued before the first is looked at: one round trip to memory
+// for the T taps, not T (tap by tap, each load was followed by its own wait: the fix-up of an access that straddles an
+// end of the tensor may overwrite what was loaded).
+template <int TM, int V>
+__device__ __forceinline__ void vm_ld_window_bf16(const Tensor& e, const Geo& g, const Thread& th, int chan, int dh, int dw, int KH, int KW, int T,
+                                                  float* out) {
+    constexpr int D = V == 1 ? 1 : V / 2;
+    uint32_t raw[TM][D];
+    int off[TM];
+    // Threads that never cross an image row: a tap's row is inside the image or not as a whole (outside, the load is
+    // sent to the offset that reads zeros), and its columns fall off at the row's ends only.
+    const bool by_rows = g.whole_rows;
+#pragma unroll
+    for (int t = 0; t < TM; t++)
+        if (t < T) {
+            int oh, ow;
+            vm_tap(t, KH, KW, oh, ow);
+            off[t] = (chan * g.HW + th.p0 + (dh + oh) * g.W + dw + ow) * 2;
+            if (V == 1) {  // (one element: inside the image or not)
+                const bool inside = th.active && (unsigned)(th.row0 + dh + oh) < (unsigned)g.H && (unsigned)(th.col0 + dw + ow) < (unsigned)g.W;
+                off[t] = inside ? off[t] : tile::kOob;
+            } else if (by_rows) {
+                const bool row_inside = th.active && (unsigned)(th.row0 + dh + oh) < (unsigned)g.H;
+                off[t] = row_inside ? off[t] : tile::kOob;
+            }
+            // (each tap's offset in a register of its own: a negative base register plus the tap's distance as the
+            // instruction's immediate offset is not what the bounds check expects)
+            asm volatile("" : "+v"(off[t]));
+            if (V == 4) {
+                const vm_u32x2 d = __builtin_amdgcn_raw_buffer_load_b64(e.rs, off[t], 0, 0);
+                raw[t][0] = d[0];
+                raw[t][D - 1] = d[1];
+            } else if (V == 2) {
+                raw[t][0] = __builtin_amdgcn_raw_buffer_load_b32(e.rs, off[t], 0, 0);
+            } else {
+                raw[t][0] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(e.rs, off[t], 0, 0);
+            }
+        }
+#pragma unroll
+    for (int t = 0; t < TM; t++)
+        if (t < T) {
+            int oh, ow;
+            vm_tap(t, KH, KW, oh, ow);
+            if (V == 1) {
+                out[t] = tile::lo_f32(raw[t][0]);
+                continue;
+            }
+            if (tile::straddles_an_end(off[t], 2 * V, e.bytes)) {
+#pragma unroll
+                for (int k = 0; k < D; k++)
+                    raw[t][k] = tile::elem_b16(e.rs, off[t] + 4 * k, e.bytes) | (tile::elem_b16(e.rs, off[t] + 4 * k + 2, e.bytes) << 16);
+            }
+            if (by_rows) {
+                // pixel v is inside for first <= v < behind: a mask over the packed pairs, then the pairs are taken apart
+                const int first = -(th.col0 + dw + ow), behind = g.W - th.col0 - dw - ow;
+                const uint32_t m = vm_bits(first > 0 ? first : 0, behind < V ? behind : V);
+#pragma unroll
+                for (int k = 0; k < D; k++) {
+                    const uint32_t lo = (uint32_t)((int32_t)(m << (31 - 2 * k)) >> 31), hi = (uint32_t)((int32_t)(m << (30 - 2 * k)) >> 31);
+                    const uint32_t kept = raw[t][k] & ((lo & 0xffffu) | (hi & 0xffff0000u));
+                    out[t * V + 2 * k] = tile::lo_f32(kept);
+                    out[t * V + 2 * k + 1] = tile::hi_f32(kept);
+                }
+            } else {
+                const bool centre = dh + oh == 0 && dw + ow == 0;  // (uniform; without displacement nothing is masked)
+                const uint32_t m = centre ? 0xffffffffu : vm_valid<V>(g, th, dh + oh, dw + ow);
+#pragma unroll
+                for (int k = 0; k < D; k++) {
+                    out[t * V + 2 * k] = vm_keep(tile::lo_f32(raw[t][k]), m, 2 * k);
+                    out[t * V + 2 * k + 1] = vm_keep(tile::hi_f32(raw[t][k]), m, 2 * k + 1);
+                }
+            }
+        }
+}
+#endif
+
 // What an instruction needs besides its own fields.
 struct Env {
     int c = 0;        // first channel of the trip; channel u of the thread is c + u
@@ -492,54 +570,12 @@ CHAIN_HD void vm_ld(const Program& pg, const Geo& g, const Instr& I, const Env& 
                 const int KH = I.r >> 4, KW = I.r & 15;
 #if defined(__HIP_DEVICE_COMPILE__)
                 if ((V == 4 || V == 2 || V == 1) && e.bf16) {
-                    // All loads of the window are issued before the first is looked at: one round trip to memory for the
-                    // T taps, not T (tap by tap, each load was followed by its own wait: the fix-up of an access that
-                    // straddles an end of the tensor may overwrite what was loaded).
-                    constexpr int D = V == 1 ? 1 : V / 2;
-                    uint32_t raw[TM][D];
-                    int off[TM];
-#pragma unroll
-                    for (int t = 0; t < TM; t++)
-                        if (t < T) {
-                            int oh, ow;
-                            vm_tap(t, KH, KW, oh, ow);
-                            off[t] = (chan * g.HW + th.p0 + (dh + oh) * g.W + dw + ow) * 2;
-                            // (each tap's offset in a register of its own: a negative base register plus the tap's
-                            // distance as the instruction's immediate offset is not what the bounds check expects)
-                            asm volatile("" : "+v"(off[t]));
-                            if (V == 4) {
-                                const vm_u32x2 d = __builtin_amdgcn_raw_buffer_load_b64(e.rs, off[t], 0, 0);
-                                raw[t][0] = d[0];
-                                raw[t][D - 1] = d[1];
-                            } else if (V == 2) {
-                                raw[t][0] = __builtin_amdgcn_raw_buffer_load_b32(e.rs, off[t], 0, 0);
-                            } else {  // (one element: inside the tensor or not)
-                                raw[t][0] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(e.rs, (unsigned)off[t] < (unsigned)e.bytes ? off[t] : tile::kOob, 0, 0);
-                            }
-                        }
-#pragma unroll
-                    for (int t = 0; t < TM; t++)
-                        if (t < T) {
-                            int oh, ow;
-                            vm_tap(t, KH, KW, oh, ow);
-                            if (V > 1 && tile::straddles_an_end(off[t], 2 * V, e.bytes)) {
-#pragma unroll
-                                for (int k = 0; k < D; k++)
-                                    raw[t][k] = tile::elem_b16(e.rs, off[t] + 4 * k, e.bytes) | (tile::elem_b16(e.rs, off[t] + 4 * k + 2, e.bytes) << 16);
-                            }
-                            const bool centre = dh + oh == 0 && dw + ow == 0;  // (uniform; without displacement nothing is masked)
-                            const uint32_t m = centre ? 0xffffffffu : vm_valid<V>(g, th, dh + oh, dw + ow);
-                            float* out = dst + u * TV + t * V;
-                            if (V == 1) {
-                                out[0] = vm_keep(tile::lo_f32(raw[t][0]), m, 0);
-                            } else {
-#pragma unroll
-                                for (int k = 0; k < V / 2; k++) {
-                                    out[2 * k] = vm_keep(tile::lo_f32(raw[t][k]), m, 2 * k);
-                                    out[2 * k + 1] = vm_keep(tile::hi_f32(raw[t][k]), m, 2 * k + 1);
-                                }
-                            }
-                        }
+                    // (the common windows with their sizes as constants: tap geometry folds, taps of one window row share
+                    // the row test and taps of one window column the column masks)
+                    float* out = dst + u * TV;
+                    if (TM >= 9 && KH == 3 && KW == 3 && T == 9) vm_ld_window_bf16<TM, V>(e, g, th, chan, dh, dw, 3, 3, 9, out);
+                    else if (TM >= 25 && KH == 5 && KW == 5 && T == 25) vm_ld_window_bf16<TM, V>(e, g, th, chan, dh, dw, 5, 5, 25, out);
+                    else vm_ld_window_bf16<TM, V>(e, g, th, chan, dh, dw, KH, KW, T, out);
                     continue;
                 }
 #endif
