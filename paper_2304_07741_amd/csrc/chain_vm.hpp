@@ -470,22 +470,29 @@ CHAIN_HD void vm_load_at(const Tensor& e, const Geo& g, const Thread& th, int pl
 // The T = KH * KW taps of a window of a bf16 tensor, displaced by (dh, dw), for the thread's V pixels of plane `chan`:
 // out[t * V + v], 0 outside the image.  All loads are issued before the first is looked at: one round trip to memory
 // for the T taps, not T (tap by tap, each load was followed by its own wait: the fix-up of an access that straddles an
-// end of the tensor may overwrite what was loaded).
-template <int TM, int V>
+// end of the tensor may overwrite what was loaded).  KHC x KWC: the window as constants (tap geometry folds, the taps
+// of a window row share the row test and the taps of a window column the column mask), or 0 x 0 for the window (KH, KW).
+template <int TM, int V, int KHC, int KWC>
 __device__ __forceinline__ void vm_ld_window_bf16(const Tensor& e, const Geo& g, const Thread& th, int chan, int dh, int dw, int KH, int KW, int T,
                                                   float* out) {
     constexpr int D = V == 1 ? 1 : V / 2;
+    if (KHC > 0) {
+        KH = KHC;
+        KW = KWC;
+        T = KHC * KWC;
+    }
     uint32_t raw[TM][D];
     int off[TM];
     // Threads that never cross an image row: a tap's row is inside the image or not as a whole (outside, the load is
     // sent to the offset that reads zeros), and its columns fall off at the row's ends only.
     const bool by_rows = g.whole_rows;
+    const int centre_off = (chan * g.HW + th.p0) * 2;
 #pragma unroll
     for (int t = 0; t < TM; t++)
         if (t < T) {
             int oh, ow;
             vm_tap(t, KH, KW, oh, ow);
-            off[t] = (chan * g.HW + th.p0 + (dh + oh) * g.W + dw + ow) * 2;
+            off[t] = centre_off + ((dh + oh) * g.W + dw + ow) * 2;
             if (V == 1) {  // (one element: inside the image or not)
                 const bool inside = th.active && (unsigned)(th.row0 + dh + oh) < (unsigned)g.H && (unsigned)(th.col0 + dw + ow) < (unsigned)g.W;
                 off[t] = inside ? off[t] : tile::kOob;
@@ -506,32 +513,57 @@ __device__ __forceinline__ void vm_ld_window_bf16(const Tensor& e, const Geo& g,
                 raw[t][0] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(e.rs, off[t], 0, 0);
             }
         }
+    if (V == 1) {
 #pragma unroll
-    for (int t = 0; t < TM; t++)
-        if (t < T) {
-            int oh, ow;
-            vm_tap(t, KH, KW, oh, ow);
-            if (V == 1) {
-                out[t] = tile::lo_f32(raw[t][0]);
-                continue;
-            }
-            if (tile::straddles_an_end(off[t], 2 * V, e.bytes)) {
+        for (int t = 0; t < TM; t++)
+            if (t < T) out[t] = tile::lo_f32(raw[t][0]);
+        return;
+    }
+    // An access may straddle an end of the tensor only when the window of this thread reaches across that end: one
+    // test for all taps (false for nearly every thread), then tap by tap.
+    const int reach = (((KH >> 1) + (dh < 0 ? -dh : dh)) * g.W + (KW >> 1) + (dw < 0 ? -dw : dw)) * 2;
+    if (centre_off - reach < 0 || centre_off + reach + 2 * V > e.bytes) {
+#pragma unroll
+        for (int t = 0; t < TM; t++)
+            if (t < T && tile::straddles_an_end(off[t], 2 * V, e.bytes)) {
 #pragma unroll
                 for (int k = 0; k < D; k++)
                     raw[t][k] = tile::elem_b16(e.rs, off[t] + 4 * k, e.bytes) | (tile::elem_b16(e.rs, off[t] + 4 * k + 2, e.bytes) << 16);
             }
-            if (by_rows) {
-                // pixel v is inside for first <= v < behind: a mask over the packed pairs, then the pairs are taken apart
-                const int first = -(th.col0 + dw + ow), behind = g.W - th.col0 - dw - ow;
-                const uint32_t m = vm_bits(first > 0 ? first : 0, behind < V ? behind : V);
+    }
+    if (by_rows) {
+        // pixel v of a tap in window column j is inside for first <= v < behind: a mask over the packed pairs, then the
+        // pairs are taken apart
+        constexpr int NM = KWC > 0 ? KWC : 1;
+        uint32_t cm[NM][D];
+#pragma unroll
+        for (int t = 0; t < TM; t++)
+            if (t < T) {
+                int oh, ow;
+                vm_tap(t, KH, KW, oh, ow);
+                const int j = KWC > 0 ? ow + KWC / 2 : 0;
+                if (KWC == 0 || t < KWC) {  // (first window row: the masks of its columns serve the rows below)
+                    const int first = -(th.col0 + dw + ow), behind = g.W - th.col0 - dw - ow;
+                    const uint32_t m = vm_bits(first > 0 ? first : 0, behind < V ? behind : V);
+#pragma unroll
+                    for (int k = 0; k < D; k++) {
+                        const uint32_t lo = (uint32_t)((int32_t)(m << (31 - 2 * k)) >> 31), hi = (uint32_t)((int32_t)(m << (30 - 2 * k)) >> 31);
+                        cm[j][k] = (lo & 0xffffu) | (hi & 0xffff0000u);
+                    }
+                }
 #pragma unroll
                 for (int k = 0; k < D; k++) {
-                    const uint32_t lo = (uint32_t)((int32_t)(m << (31 - 2 * k)) >> 31), hi = (uint32_t)((int32_t)(m << (30 - 2 * k)) >> 31);
-                    const uint32_t kept = raw[t][k] & ((lo & 0xffffu) | (hi & 0xffff0000u));
+                    const uint32_t kept = raw[t][k] & cm[j][k];
                     out[t * V + 2 * k] = tile::lo_f32(kept);
                     out[t * V + 2 * k + 1] = tile::hi_f32(kept);
                 }
-            } else {
+            }
+    } else {
+#pragma unroll
+        for (int t = 0; t < TM; t++)
+            if (t < T) {
+                int oh, ow;
+                vm_tap(t, KH, KW, oh, ow);
                 const bool centre = dh + oh == 0 && dw + ow == 0;  // (uniform; without displacement nothing is masked)
                 const uint32_t m = centre ? 0xffffffffu : vm_valid<V>(g, th, dh + oh, dw + ow);
 #pragma unroll
@@ -540,7 +572,7 @@ __device__ __forceinline__ void vm_ld_window_bf16(const Tensor& e, const Geo& g,
                     out[t * V + 2 * k + 1] = vm_keep(tile::hi_f32(raw[t][k]), m, 2 * k + 1);
                 }
             }
-        }
+    }
 }
 #endif
 
@@ -573,9 +605,9 @@ CHAIN_HD void vm_ld(const Program& pg, const Geo& g, const Instr& I, const Env& 
                     // (the common windows with their sizes as constants: tap geometry folds, taps of one window row share
                     // the row test and taps of one window column the column masks)
                     float* out = dst + u * TV;
-                    if (TM >= 9 && KH == 3 && KW == 3 && T == 9) vm_ld_window_bf16<TM, V>(e, g, th, chan, dh, dw, 3, 3, 9, out);
-                    else if (TM >= 25 && KH == 5 && KW == 5 && T == 25) vm_ld_window_bf16<TM, V>(e, g, th, chan, dh, dw, 5, 5, 25, out);
-                    else vm_ld_window_bf16<TM, V>(e, g, th, chan, dh, dw, KH, KW, T, out);
+                    if (TM >= 9 && KH == 3 && KW == 3 && T == 9) vm_ld_window_bf16<TM, V, (TM >= 9 ? 3 : 0), (TM >= 9 ? 3 : 0)>(e, g, th, chan, dh, dw, 3, 3, 9, out);
+                    else if (TM >= 25 && KH == 5 && KW == 5 && T == 25) vm_ld_window_bf16<TM, V, (TM >= 25 ? 5 : 0), (TM >= 25 ? 5 : 0)>(e, g, th, chan, dh, dw, 5, 5, 25, out);
+                    else vm_ld_window_bf16<TM, V, 0, 0>(e, g, th, chan, dh, dw, KH, KW, T, out);
                     continue;
                 }
 #endif
@@ -720,9 +752,20 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env
                         for (int v = 0; v < V; v++) Au[v] += Au[t * V + v];
                     }
                 if (I.kind == 1) {
-                    const float inv = (float)T;
+                    // sum / T as a product with the reciprocal and one correction step from the remainder: the quotient
+                    // to within one unit in the last place, a fifth of the instructions of a division per pixel
+                    // (infinities and NaN come out as a division gives them)
+                    const float n = (float)T;
+#if defined(__HIP_DEVICE_COMPILE__)
+                    const float r = 1.f / n;
 #pragma unroll
-                    for (int v = 0; v < V; v++) Au[v] /= inv;
+                    for (int v = 0; v < V; v++) {
+                        const float q = Au[v] * r;
+                        Au[v] = __builtin_amdgcn_div_fixupf(fmaf(fmaf(-n, q, Au[v]), r, q), n, Au[v]);
+                    }
+#else
+                    for (int v = 0; v < V; v++) Au[v] /= n;
+#endif
                 }
             }
         }
