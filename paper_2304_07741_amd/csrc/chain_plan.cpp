@@ -655,7 +655,10 @@ double geometry_for(Program& pg, const Dag& dag, int C, int64_t reach_px, bool a
     // accesses) x how many times over the launch fills the chip (256 compute units, about 1024 resident threads each)
     const double trips_per_thread = (double)ceil_div(pg.chunk, pg.slices * pg.unroll);
     const double threads_total = (double)dag.N * pg.tiles * pg.chunks * pg.threads;
-    const double wgs_per_cu = std::max(1.0, std::min(1024.0 / pg.threads, std::floor(160.0 * 1024.0 / (double)(lds_bytes(pg) + 4352))));
+    // (the instances with 9 lanes x 4 pixels and with 25 lanes hold more than 128 vector registers: two wavefronts per
+    // SIMD, not four)
+    const double resident_threads = (pg.tm > 9 || (pg.tm > 1 && V >= 4)) ? 512.0 : 1024.0;
+    const double wgs_per_cu = std::max(1.0, std::min(resident_threads / pg.threads, std::floor(160.0 * 1024.0 / (double)(lds_bytes(pg) + 4352))));
     // (whole rounds: a round that a few left-over workgroups make takes as long as a full one)
     const double rounds = std::max(1.0, std::ceil(threads_total / (256.0 * wgs_per_cu * pg.threads) - 0.05));
     // (a work item also costs its set-up: the thread's position, the pass headers; worth about 6 of these units)
