@@ -92,11 +92,27 @@ __global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program) {
                 const int i_begin = ev.pro ? pro_begin : body_begin, i_end = ev.pro ? pro_end : body_end;
                 if (i_begin >= i_end) continue;
                 uint4 next = *(const uint4*)&pg.ins[i_begin];
+                if (ev.h <= 0) {
+                    // a trip past the last channel: nothing to compute, only the barriers of the hand-overs to keep.  (A loop
+                    // of its own: with this case inside the loop below, as a path on which the state passes an instruction
+                    // unchanged, the compiler kept the state in two sets of registers and copied it across for every
+                    // instruction.)
+                    for (int i = i_begin; i < i_end; i++) {
+                        const Instr I = vm_uniform(next);
+                        if (i + 1 < i_end) next = *(const uint4*)&pg.ins[i + 1];
+                        if (I.op != OP_XADD) continue;
+                        for (int u = 0; u < U; u++) {
+                            __syncthreads();
+                            __syncthreads();
+                        }
+                    }
+                    continue;
+                }
                 for (int i = i_begin; i < i_end; i++) {
                     const Instr I = vm_uniform(next);
                     if (i + 1 < i_end) next = *(const uint4*)&pg.ins[i + 1];  // (on its way while this instruction runs)
                     if (I.op != OP_XADD) {
-                        if (ev.h > 0) vm_exec<TM, V, U>(pg, g, I, ev, th, st, Pm, Rm);
+                        vm_exec<TM, V, U>(pg, g, I, ev, th, st, Pm, Rm);
                         continue;
                     }
 #pragma unroll
