@@ -470,6 +470,33 @@ def test_fused_chain_workloads(harness, oracle, body, N, C, H, dtype):
         r.close()
 
 
+# Windows whose taps reach across the first and last rows of the whole tensor (one image or few, few channels), on planes
+# for every pixels-per-thread width of the window instances: rows that are whole vectors (W = 8, 12, 16, 6 with two
+# pixels), vectors that straddle two rows (6x6 and 10x6 with four pixels), single pixels (odd sizes); after a shift, so
+# that the window load itself is displaced; 5x5; max, whose ties at the zero border go to the first tap
+WINDOW_END_BODIES = [
+    "%1 = unfold %0 kh=3 kw=3\n%2 = fold %1 op=sum\noutput %2\n",
+    "%1 = shift %0 dh=2 dw=-3\n%2 = unfold %1 kh=3 kw=3\n%3 = fold %2 op=max\noutput %3\n",
+    "%1 = unfold %0 kh=5 kw=5\n%2 = unary %1 op=abs\n%3 = fold %2 op=avg\noutput %3\n",
+    "%1 = unfold %0 kh=3 kw=3\n%2 = unary %1 op=gelu\n%3 = fold %2 op=avg\n%4 = shift %3 dh=-1 dw=1\n%5 = binary %0 %4 op=add\noutput %5\n",
+    "%1 = shift %0 dh=-1 dw=2\n%2 = unfold %1 kh=1 kw=3\n%3 = binary %0 %2 op=mul\n%4 = fold %3 op=sum\noutput %4\n",
+]
+WINDOW_END_SHAPES = [(1, 1, 4, 8), (2, 3, 5, 12), (1, 2, 6, 6), (1, 1, 3, 16), (2, 2, 9, 7), (1, 3, 10, 6), (1, 1, 1, 4), (3, 1, 2, 2)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", WINDOW_END_SHAPES)
+@pytest.mark.parametrize("idx", range(len(WINDOW_END_BODIES)))
+def test_window_chains_at_the_ends_of_the_tensor(harness, oracle, idx, shape, dtype):
+    case = _mk(WINDOW_END_BODIES[idx], shape, dtype, 900 + idx, [], f"window_ends{idx}")
+    res, r, dy = harness.run_case(case)
+    try:
+        assert r.info.n_fused_chains >= 1
+        check_against_oracle(oracle, case, res, dy, what=f"window chain {idx} at {shape} {dtype}")
+    finally:
+        r.close()
+
+
 DETERMINISM_CASES = [lambda: wl.config4(64, 14, N=4), lambda: wl.config4(64, 56, N=2), lambda: wl.config4(128, 28, N=3),
                      lambda: wl.config4(512, 7, N=8), lambda: wl.config3(N=2, H=28), lambda: wl.config2(N=2, H=56),
                      lambda: wl.config5(157), lambda: wl.config5(130), lambda: wl.chain("shift_residual", N=8, C=64, H=28),
