@@ -31,7 +31,7 @@ __device__ __forceinline__ const Program& stage_program(unsigned char* sprog) {
 }
 
 template <int TM, int V, int U>
-__global__ __launch_bounds__(max_threads_for(TM)) void k_chain(const Program) {
+__global__ __launch_bounds__(max_threads_for(TM), min_waves_for(TM, V)) void k_chain(const Program) {
     __shared__ __align__(16) unsigned char sprog[sizeof(Program)];
     const Program& pg = stage_program(sprog);
     extern __shared__ __align__(16) float lds[];

@@ -15,6 +15,9 @@ constexpr int max_vec_for(int tm) { return tm <= 1 ? 16 : (tm <= 9 ? 4 : 1); }
 
 // Largest workgroup of that instance (the tap vectors of a thread live in registers: wider lanes, fewer threads).
 constexpr int max_threads_for(int) { return 512; }
+// Wavefronts per SIMD that the register allocation of an instance leaves room for (1: no requirement).  The instance with
+// 9 lanes x 2 pixels came out one register above the 128 of four wavefronts; held to them it spills nothing.
+constexpr int min_waves_for(int tm, int vec) { return tm > 1 && tm <= 9 && vec == 2 ? 4 : 1; }
 
 // Channels per trip of the instance with TM lanes and `vec` pixels per thread: 16 lanes in all without taps (so that a
 // thread with few pixels still has 16 independent loads in flight), 2 x 9 lanes up to 9 taps, one channel beyond.

@@ -650,10 +650,11 @@ CHAIN_HD void vm_blend_lanes(int kind, bool x_lhs, const float* X, float* A, int
 // (softmax statistics, the sums of a softmax's adjoint: written by the prologue and the OP_SMC instructions) exists once,
 // float k of pixel v at Pm[(k * V + v) * pstride]; an accumulator of one channel (OP_PSET in a body, OP_PADD, OP_PLD,
 // OP_XADD) once per channel u of the trip, at Pm[((u * np + k) * V + v) * pstride].  Rm: its registers (vm_reg_read).
-template <int TM, int V, int U>
-CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env& ev, const Thread& th, State<TM, V, U>& st, float* Pm, float* Rm) {
+// TC: the lanes of the instruction as a constant (the loops over the taps then carry no test per tap), or 0 for I.T.
+template <int TM, int V, int U, int TC>
+CHAIN_HD void vm_exec_lanes(const Program& pg, const Geo& g, const Instr& I, const Env& ev, const Thread& th, State<TM, V, U>& st, float* Pm, float* Rm) {
     float* A = st.A;
-    const int T = I.T;
+    const int T = TC > 0 ? TC : I.T;
     const int pstride = ev.pstride, rstride = ev.rstride;
     constexpr int TV = TM * V;
     float X[U * TV];
@@ -990,6 +991,16 @@ CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env
         break;
     default: break;
     }
+}
+
+// An instruction over all TM lanes of the instance (the common case of a program with taps) runs the copy of the
+// dispatch whose tap loops are straight-line code.  (Not the one-pixel instances: the second copy cost them 16-18
+// registers and with those a wavefront per SIMD.)
+template <int TM, int V, int U>
+CHAIN_HD void vm_exec(const Program& pg, const Geo& g, const Instr& I, const Env& ev, const Thread& th, State<TM, V, U>& st, float* Pm, float* Rm) {
+    constexpr int TC = TM > 1 && V > 1 ? TM : 0;
+    if (TC > 0 && I.T == TM) vm_exec_lanes<TM, V, U, TC>(pg, g, I, ev, th, st, Pm, Rm);
+    else vm_exec_lanes<TM, V, U, 0>(pg, g, I, ev, th, st, Pm, Rm);
 }
 
 // OP_XADD of channel u, first half: the thread's lanes go to the hand-over buffer of its slice (lane t of local pixel q
