@@ -35,20 +35,20 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # plain copy of 25 088 KiB reads FETCH_SIZE 12 557 -> units of 1.998 KiB, and WRITE_SIZE 25 088 -> KiB; the dispatches of
 # a run are attributed to the launches of a step by position; commands and tables in profiles/).  The figures are valid
 # only for the kernel sources they were taken on (one hash over the library's source folder), otherwise `traffic` is null.
-TRAFFIC_SHA256 = "f1ecd8640294cb29f35f153340ed32845c23c6a09f10c4a737e6ad10423db4fe"
+TRAFFIC_SHA256 = "0c95bf2cb5087059b3ef527c17d33ab74abbd9bd659eda516057b45870099dae"
 TRAFFIC_KIB = {  # workload -> launch (phase:name) -> (KiB fetched, KiB written) per launch
-    'shift_residual': {'fwd:sgfc_fwd': (28776.6, 25090.0), 'bwd:sgfc_bwd': (52696.2, 25889.0), 'bwd:sgfc_dw_reduce': (3226.7, 4.0)},
-    'involution': {'fwd:weight_prep': (326.0, 40.0), 'fwd:dyn_fc1_softmax': (6732.3, 882.0), 'fwd:dyn_apply': (7266.3, 6272.0), 'fwd:dyn_fc2': (6990.8, 6272.0), 'bwd:dyn_fc2_wgrad': (15871.7, 6656.0), 'bwd:dyn_fc2_dgrad': (6990.8, 6272.0), 'bwd:dyn_apply_dx_da': (20213.3, 7154.2), 'bwd:dyn_softmax_bwd': (2088.0, 1323.0), 'bwd:dyn_fc1_wgrad': (10051.6, 900.0), 'bwd:dyn_fc1_dgrad': (7235.0, 6272.0), 'bwd:wgrad_reduce': (7617.1, 68.5)},
-    'sampled_c64_h56': {'fwd:weight_prep': (169.0, 44.0), 'fwd:ufc_fc1_unfold': (50563.3, 50176.0), 'fwd:ufc_mid_fwd': (101104.3, 50179.6), 'fwd:ufc_fc2': (50606.6, 50176.0), 'bwd:ufc_fc2_wgrad': (100519.0, 6272.0), 'bwd:ufc_fc2_dgrad': (50606.6, 50176.0), 'bwd:ufc_mid_bwd': (152854.7, 100352.0), 'bwd:ufc_fc1_wgrad_unfold': (105580.0, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (100700.6, 50176.0), 'bwd:wgrad_reduce': (10937.7, 104.0)},
-    'sampled_c128_h28': {'fwd:weight_prep': (531.7, 104.0), 'fwd:ufc_fc1_unfold': (25631.9, 25099.7), 'fwd:ufc_mid_fwd': (50596.5, 25089.6), 'fwd:ufc_fc2': (26279.9, 25092.9), 'bwd:ufc_fc2_wgrad': (65553.7, 6656.0), 'bwd:ufc_fc2_dgrad': (26279.8, 25088.0), 'bwd:ufc_mid_bwd': (76485.9, 50176.0), 'bwd:ufc_fc1_wgrad_unfold': (60956.6, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (50699.9, 25138.0), 'bwd:wgrad_reduce': (11321.3, 416.0)},
-    'sampled_c256_h14': {'fwd:weight_prep': (2214.1, 416.0), 'fwd:ufc_fc1_unfold': (13282.0, 12565.9), 'fwd:ufc_mid_fwd': (25905.0, 12868.5), 'fwd:ufc_fc2': (14591.9, 12592.0), 'bwd:ufc_fc2_wgrad': (25350.5, 8192.0), 'bwd:ufc_fc2_dgrad': (14591.7, 12592.0), 'bwd:ufc_mid_bwd': (38884.7, 25717.3), 'bwd:ufc_fc1_wgrad_unfold': (61693.5, 6624.0), 'bwd:ufc_fc1_dgrad_unfold': (26113.8, 12604.0), 'bwd:wgrad_reduce': (14869.6, 1104.0)},
-    'sampled_c512_h7': {'fwd:weight_prep': (6709.6, 1664.0), 'fwd:ufc_fc1_unfold': (7412.6, 6273.4), 'fwd:ufc_mid_fwd': (13052.3, 6322.4), 'fwd:ufc_fc2': (10616.9, 6272.0), 'bwd:ufc_fc2_wgrad': (12804.6, 8192.0), 'bwd:ufc_fc2_dgrad': (10616.9, 6272.0), 'bwd:ufc_mid_bwd': (19622.7, 12647.4), 'bwd:ufc_fc1_wgrad_unfold': (19711.7, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (13692.4, 6279.1), 'bwd:wgrad_reduce': (12855.7, 6656.0)},
-    'chain_relu': {'fwd:chain_fwd': (50474.3, 56947.9), 'bwd:chain_bwd': (100734.9, 55689.2)},
-    'chain_gate': {'fwd:chain_fwd': (50669.8, 62249.8), 'bwd:chain_bwd': (101132.0, 60083.7)},
-    'chain_shift_residual': {'fwd:chain_fwd': (50643.2, 60178.5), 'bwd:chain_bwd': (100812.9, 56928.4)},
-    'chain_box3': {'fwd:chain_fwd': (54203.5, 50434.7), 'bwd:chain_bwd': (54201.9, 50430.9)},
-    'chain_softmax_c': {'fwd:chain_fwd': (99359.8, 57452.8), 'bwd:chain_bwd': (251295.5, 54869.5)},
-    'fuzz': {'all:chain': (64523.6, 43691.0)},
+    'shift_residual': {'fwd:sgfc_fwd': (28781.3, 25090.2), 'bwd:sgfc_bwd': (52695.3, 25888.5), 'bwd:sgfc_dw_reduce': (3226.7, 4.0)},
+    'involution': {'fwd:weight_prep': (326.0, 40.0), 'fwd:dyn_fc1_softmax': (6732.3, 882.0), 'fwd:dyn_apply': (7266.3, 6272.0), 'fwd:dyn_fc2': (6990.8, 6272.0), 'bwd:dyn_fc2_wgrad': (15871.7, 6656.0), 'bwd:dyn_fc2_dgrad': (6990.8, 6272.0), 'bwd:dyn_apply_dx_da': (20213.4, 7154.2), 'bwd:dyn_softmax_bwd': (2088.0, 1323.0), 'bwd:dyn_fc1_wgrad': (10051.7, 900.0), 'bwd:dyn_fc1_dgrad': (7235.0, 6272.0), 'bwd:wgrad_reduce': (7617.2, 68.5)},
+    'sampled_c64_h56': {'fwd:weight_prep': (169.0, 44.0), 'fwd:ufc_fc1_unfold': (50563.5, 50176.0), 'fwd:ufc_mid_fwd': (101104.5, 50189.2), 'fwd:ufc_fc2': (50606.7, 50176.0), 'bwd:ufc_fc2_wgrad': (100519.2, 6272.0), 'bwd:ufc_fc2_dgrad': (50606.7, 50176.0), 'bwd:ufc_mid_bwd': (152855.0, 100352.0), 'bwd:ufc_fc1_wgrad_unfold': (105580.2, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (100797.7, 50176.0), 'bwd:wgrad_reduce': (10937.7, 104.0)},
+    'sampled_c128_h28': {'fwd:weight_prep': (531.7, 104.0), 'fwd:ufc_fc1_unfold': (25631.8, 25098.2), 'fwd:ufc_mid_fwd': (50596.6, 25096.1), 'fwd:ufc_fc2': (26279.9, 25093.7), 'bwd:ufc_fc2_wgrad': (65496.2, 6656.0), 'bwd:ufc_fc2_dgrad': (26279.9, 25088.0), 'bwd:ufc_mid_bwd': (76485.9, 50176.0), 'bwd:ufc_fc1_wgrad_unfold': (60958.4, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (50698.8, 25133.0), 'bwd:wgrad_reduce': (11321.3, 416.0)},
+    'sampled_c256_h14': {'fwd:weight_prep': (2214.1, 416.0), 'fwd:ufc_fc1_unfold': (13282.0, 12563.1), 'fwd:ufc_mid_fwd': (25905.1, 12865.7), 'fwd:ufc_fc2': (14591.9, 12592.0), 'bwd:ufc_fc2_wgrad': (25350.4, 8192.0), 'bwd:ufc_fc2_dgrad': (14591.8, 12592.0), 'bwd:ufc_mid_bwd': (38884.9, 25706.6), 'bwd:ufc_fc1_wgrad_unfold': (61697.5, 6624.0), 'bwd:ufc_fc1_dgrad_unfold': (26114.7, 12604.9), 'bwd:wgrad_reduce': (14869.7, 1104.0)},
+    'sampled_c512_h7': {'fwd:weight_prep': (6709.7, 1664.0), 'fwd:ufc_fc1_unfold': (7412.6, 6273.4), 'fwd:ufc_mid_fwd': (13052.4, 6322.5), 'fwd:ufc_fc2': (10616.9, 6272.0), 'bwd:ufc_fc2_wgrad': (12804.6, 8192.0), 'bwd:ufc_fc2_dgrad': (10616.9, 6272.0), 'bwd:ufc_mid_bwd': (19622.7, 12647.9), 'bwd:ufc_fc1_wgrad_unfold': (19711.7, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (13692.3, 6277.2), 'bwd:wgrad_reduce': (12855.8, 6656.0)},
+    'chain_relu': {'fwd:chain_fwd': (50474.2, 57373.7), 'bwd:chain_bwd': (100735.0, 55944.8)},
+    'chain_gate': {'fwd:chain_fwd': (50672.2, 62137.7), 'bwd:chain_bwd': (101129.3, 60244.7)},
+    'chain_shift_residual': {'fwd:chain_fwd': (50645.5, 60019.1), 'bwd:chain_bwd': (100812.6, 57114.3)},
+    'chain_box3': {'fwd:chain_fwd': (54333.9, 50412.8), 'bwd:chain_bwd': (54335.9, 50410.1)},
+    'chain_softmax_c': {'fwd:chain_fwd': (99497.3, 56915.3), 'bwd:chain_bwd': (251294.7, 54495.1)},
+    'fuzz': {'all:chain': (64542.7, 43693.7)},
 }
 
 
