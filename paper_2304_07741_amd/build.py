@@ -20,6 +20,7 @@ MAX_VGPRS = 256
 SCRATCH_ALLOWED = (
     r"sgfc.*5k_bwdILi1ELi1ELi2E",            # shift/FC backward, two tiles per wavefront under a 128-register cap (4 waves per SIMD)
     r"gfctm.*5k_fwdILi[12]ELi5ELi5ELb1ELi[24]ELb0E",  # 5x5 windows, fp32 destination, split K: 36 bytes of SGPR spill slots
+    r"chain.*7k_chainILi9ELi2ELi1E",          # 9 lanes x 2 pixels under its 128-register cap (4 waves per SIMD): one register, stored and reloaded once per work item, outside the channel loop
 )
 
 

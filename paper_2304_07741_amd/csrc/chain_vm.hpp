@@ -313,10 +313,19 @@ CHAIN_HD float vm_sign(float x) { return x > 0.f ? 1.f : (x < 0.f ? -1.f : 0.f);
 // Normal CDF and density for programs of bf16 DAGs (Program::fast_math): erfc by the rational-times-Gaussian
 // approximation of Abramowitz and Stegun, formula 7.1.26 (absolute error of erf below 1.5e-7, five orders below the
 // tolerance of a bf16 DAG); the Gaussian is shared with the density, so gelu or its derivative costs one exponential
-// and one division.  fp32 DAGs keep erff.
+// and one division.  fp32 DAGs keep erff.  Exponential and reciprocal of such programs are the hardware's (base-2
+// exponential of x * log2 e: relative error about 1e-7 * (1 + |x|), results below 2^-126 are 0; reciprocal to one unit
+// in the last place): a fifth of the instructions of expf and of a division.
+#if defined(__HIP_DEVICE_COMPILE__)
+CHAIN_HD float vm_exp_fast(float x) { return __expf(x); }
+CHAIN_HD float vm_rcp_fast(float x) { return __builtin_amdgcn_rcpf(x); }
+#else
+CHAIN_HD float vm_exp_fast(float x) { return expf(x); }
+CHAIN_HD float vm_rcp_fast(float x) { return 1.f / x; }
+#endif
 CHAIN_HD void vm_normal_parts(float z, float& cdf, float& pdf) {
-    const float t = 1.f / (1.f + 0.3275911f * 0.70710678f * fabsf(z));
-    const float e = expf(-0.5f * z * z);
+    const float t = vm_rcp_fast(1.f + 0.3275911f * 0.70710678f * fabsf(z));
+    const float e = vm_exp_fast(-0.5f * z * z);
     const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
     const float tail = 0.5f * poly * e;  // 0.5 * erfc(|z| / sqrt 2)
     cdf = z >= 0.f ? 1.f - tail : tail;
@@ -712,7 +721,11 @@ CHAIN_HD void vm_exec_lanes(const Program& pg, const Geo& g, const Instr& I, con
             break;
         case 4: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = sinf(A[e]);); break;
         case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = -A[e];); break;
-        default: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = expf(fminf(fmaxf(A[e], I.f0), I.f1));); break;
+        default:
+            CHAIN_CASE;
+            if (ev.fast) CHAIN_EACH(T, e, l, A[e] = vm_exp_fast(fminf(fmaxf(A[e], I.f0), I.f1)););
+            else CHAIN_EACH(T, e, l, A[e] = expf(fminf(fmaxf(A[e], I.f0), I.f1)););
+            break;
         }
         break;
     case OP_MOVR:
@@ -784,6 +797,19 @@ CHAIN_HD void vm_exec_lanes(const Program& pg, const Geo& g, const Instr& I, con
                 for (int t = 1; t < TM; t++)
                     if (t < T) m = fmaxf(m, Au[t * V + v]);
                 float z = 0.f;
+                if (ev.fast) {
+#pragma unroll
+                    for (int t = 0; t < TM; t++)
+                        if (t < T) {
+                            Au[t * V + v] = vm_exp_fast(Au[t * V + v] - m);
+                            z += Au[t * V + v];
+                        }
+                    const float rz = vm_rcp_fast(z);
+#pragma unroll
+                    for (int t = 0; t < TM; t++)
+                        if (t < T) Au[t * V + v] = Au[t * V + v] * rz;
+                    continue;
+                }
 #pragma unroll
                 for (int t = 0; t < TM; t++)
                     if (t < T) {
@@ -824,7 +850,11 @@ CHAIN_HD void vm_exec_lanes(const Program& pg, const Geo& g, const Instr& I, con
             break;
         case 4: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = X[e] * cosf(A[e]);); break;
         case kUnNeg: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = -X[e];); break;
-        default: CHAIN_CASE; CHAIN_EACH(T, e, l, A[e] = (A[e] > I.f0 && A[e] < I.f1) ? X[e] * expf(A[e]) : 0.f;); break;
+        default:
+            CHAIN_CASE;
+            if (ev.fast) CHAIN_EACH(T, e, l, A[e] = (A[e] > I.f0 && A[e] < I.f1) ? X[e] * vm_exp_fast(A[e]) : 0.f;);
+            else CHAIN_EACH(T, e, l, A[e] = (A[e] > I.f0 && A[e] < I.f1) ? X[e] * expf(A[e]) : 0.f;);
+            break;
         }
         break;
     case OP_BING: {
@@ -945,6 +975,31 @@ CHAIN_HD void vm_exec_lanes(const Program& pg, const Geo& g, const Instr& I, con
         break;
     case OP_SMCSTAT:
         CHAIN_CASE;
+        if (ev.fast) {
+            // the channels of the trip join the running maximum and sum together: one update of the pair per pixel and
+            // trip, U + 1 exponentials for U channels, no branch on the data
+#pragma unroll
+            for (int t = 0; t < TM; t++)
+                if (t < T) {
+#pragma unroll
+                    for (int v = 0; v < V; v++) {
+                        float& m = Pm[((I.a + t) * V + v) * pstride];
+                        float& z = Pm[((I.a + T + t) * V + v) * pstride];
+                        const float before = m;
+                        float top = before;
+#pragma unroll
+                        for (int u = 0; u < U; u++)
+                            if (u < ev.h) top = fmaxf(top, A[u * TV + t * V + v]);
+                        float sum = z * vm_exp_fast(before - top);  // (before = -inf at the first channel: 0 * 0)
+#pragma unroll
+                        for (int u = 0; u < U; u++)
+                            if (u < ev.h) sum += vm_exp_fast(A[u * TV + t * V + v] - top);
+                        m = top;
+                        z = sum;
+                    }
+                }
+            break;
+        }
 #pragma unroll
         for (int u = 0; u < U; u++)
             if (u < ev.h) {
@@ -968,7 +1023,8 @@ CHAIN_HD void vm_exec_lanes(const Program& pg, const Geo& g, const Instr& I, con
         break;
     case OP_SMCAPPLY:
         CHAIN_CASE;
-        CHAIN_EACH(T, e, l, A[e] = expf(A[e] - Pm[(I.a * V + l) * pstride]) / Pm[((I.a + T) * V + l) * pstride];);
+        if (ev.fast) CHAIN_EACH(T, e, l, A[e] = vm_exp_fast(A[e] - Pm[(I.a * V + l) * pstride]) * vm_rcp_fast(Pm[((I.a + T) * V + l) * pstride]););
+        else CHAIN_EACH(T, e, l, A[e] = expf(A[e] - Pm[(I.a * V + l) * pstride]) / Pm[((I.a + T) * V + l) * pstride];);
         break;
     case OP_SMCDOT:
         CHAIN_CASE;
