@@ -35,20 +35,20 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # plain copy of 25 088 KiB reads FETCH_SIZE 12 557 -> units of 1.998 KiB, and WRITE_SIZE 25 088 -> KiB; the dispatches of
 # a run are attributed to the launches of a step by position; commands and tables in profiles/).  The figures are valid
 # only for the kernel sources they were taken on (one hash over the library's source folder), otherwise `traffic` is null.
-TRAFFIC_SHA256 = "0c95bf2cb5087059b3ef527c17d33ab74abbd9bd659eda516057b45870099dae"
+TRAFFIC_SHA256 = "8e421938639fd978f6a91276b051d50575fb67a893047c1943244e723da8e289"
 TRAFFIC_KIB = {  # workload -> launch (phase:name) -> (KiB fetched, KiB written) per launch
-    'shift_residual': {'fwd:sgfc_fwd': (28781.3, 25090.2), 'bwd:sgfc_bwd': (52695.3, 25888.5), 'bwd:sgfc_dw_reduce': (3226.7, 4.0)},
+    'shift_residual': {'fwd:sgfc_fwd': (28773.5, 25090.9), 'bwd:sgfc_bwd': (52695.2, 25890.3), 'bwd:sgfc_dw_reduce': (3226.7, 4.0)},
     'involution': {'fwd:weight_prep': (326.0, 40.0), 'fwd:dyn_fc1_softmax': (6732.3, 882.0), 'fwd:dyn_apply': (7266.3, 6272.0), 'fwd:dyn_fc2': (6990.8, 6272.0), 'bwd:dyn_fc2_wgrad': (15871.7, 6656.0), 'bwd:dyn_fc2_dgrad': (6990.8, 6272.0), 'bwd:dyn_apply_dx_da': (20213.4, 7154.2), 'bwd:dyn_softmax_bwd': (2088.0, 1323.0), 'bwd:dyn_fc1_wgrad': (10051.7, 900.0), 'bwd:dyn_fc1_dgrad': (7235.0, 6272.0), 'bwd:wgrad_reduce': (7617.2, 68.5)},
-    'sampled_c64_h56': {'fwd:weight_prep': (169.0, 44.0), 'fwd:ufc_fc1_unfold': (50563.5, 50176.0), 'fwd:ufc_mid_fwd': (101104.5, 50189.2), 'fwd:ufc_fc2': (50606.7, 50176.0), 'bwd:ufc_fc2_wgrad': (100519.2, 6272.0), 'bwd:ufc_fc2_dgrad': (50606.7, 50176.0), 'bwd:ufc_mid_bwd': (152855.0, 100352.0), 'bwd:ufc_fc1_wgrad_unfold': (105580.2, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (100797.7, 50176.0), 'bwd:wgrad_reduce': (10937.7, 104.0)},
-    'sampled_c128_h28': {'fwd:weight_prep': (531.7, 104.0), 'fwd:ufc_fc1_unfold': (25631.8, 25098.2), 'fwd:ufc_mid_fwd': (50596.6, 25096.1), 'fwd:ufc_fc2': (26279.9, 25093.7), 'bwd:ufc_fc2_wgrad': (65496.2, 6656.0), 'bwd:ufc_fc2_dgrad': (26279.9, 25088.0), 'bwd:ufc_mid_bwd': (76485.9, 50176.0), 'bwd:ufc_fc1_wgrad_unfold': (60958.4, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (50698.8, 25133.0), 'bwd:wgrad_reduce': (11321.3, 416.0)},
-    'sampled_c256_h14': {'fwd:weight_prep': (2214.1, 416.0), 'fwd:ufc_fc1_unfold': (13282.0, 12563.1), 'fwd:ufc_mid_fwd': (25905.1, 12865.7), 'fwd:ufc_fc2': (14591.9, 12592.0), 'bwd:ufc_fc2_wgrad': (25350.4, 8192.0), 'bwd:ufc_fc2_dgrad': (14591.8, 12592.0), 'bwd:ufc_mid_bwd': (38884.9, 25706.6), 'bwd:ufc_fc1_wgrad_unfold': (61697.5, 6624.0), 'bwd:ufc_fc1_dgrad_unfold': (26114.7, 12604.9), 'bwd:wgrad_reduce': (14869.7, 1104.0)},
-    'sampled_c512_h7': {'fwd:weight_prep': (6709.7, 1664.0), 'fwd:ufc_fc1_unfold': (7412.6, 6273.4), 'fwd:ufc_mid_fwd': (13052.4, 6322.5), 'fwd:ufc_fc2': (10616.9, 6272.0), 'bwd:ufc_fc2_wgrad': (12804.6, 8192.0), 'bwd:ufc_fc2_dgrad': (10616.9, 6272.0), 'bwd:ufc_mid_bwd': (19622.7, 12647.9), 'bwd:ufc_fc1_wgrad_unfold': (19711.7, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (13692.3, 6277.2), 'bwd:wgrad_reduce': (12855.8, 6656.0)},
-    'chain_relu': {'fwd:chain_fwd': (50474.2, 57373.7), 'bwd:chain_bwd': (100735.0, 55944.8)},
-    'chain_gate': {'fwd:chain_fwd': (50672.2, 62137.7), 'bwd:chain_bwd': (101129.3, 60244.7)},
-    'chain_shift_residual': {'fwd:chain_fwd': (50645.5, 60019.1), 'bwd:chain_bwd': (100812.6, 57114.3)},
-    'chain_box3': {'fwd:chain_fwd': (54333.9, 50412.8), 'bwd:chain_bwd': (54335.9, 50410.1)},
-    'chain_softmax_c': {'fwd:chain_fwd': (99497.3, 56915.3), 'bwd:chain_bwd': (251294.7, 54495.1)},
-    'fuzz': {'all:chain': (64542.7, 43693.7)},
+    'sampled_c64_h56': {'fwd:weight_prep': (169.0, 44.0), 'fwd:ufc_fc1_unfold': (50562.9, 50176.0), 'fwd:ufc_mid_fwd': (101104.5, 50182.7), 'fwd:ufc_fc2': (50606.7, 50176.0), 'bwd:ufc_fc2_wgrad': (100519.2, 6272.0), 'bwd:ufc_fc2_dgrad': (50606.7, 50176.0), 'bwd:ufc_mid_bwd': (152855.0, 100352.0), 'bwd:ufc_fc1_wgrad_unfold': (105580.2, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (100704.1, 50176.0), 'bwd:wgrad_reduce': (10937.7, 104.0)},
+    'sampled_c128_h28': {'fwd:weight_prep': (531.7, 104.0), 'fwd:ufc_fc1_unfold': (25631.4, 25099.4), 'fwd:ufc_mid_fwd': (50596.6, 25093.1), 'fwd:ufc_fc2': (26279.9, 25094.6), 'bwd:ufc_fc2_wgrad': (65423.1, 6656.0), 'bwd:ufc_fc2_dgrad': (26279.9, 25088.0), 'bwd:ufc_mid_bwd': (76486.0, 50176.0), 'bwd:ufc_fc1_wgrad_unfold': (60974.9, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (50697.8, 25127.5), 'bwd:wgrad_reduce': (11321.3, 416.0)},
+    'sampled_c256_h14': {'fwd:weight_prep': (2214.1, 416.0), 'fwd:ufc_fc1_unfold': (13282.1, 12563.2), 'fwd:ufc_mid_fwd': (25905.1, 12871.0), 'fwd:ufc_fc2': (14591.9, 12592.0), 'bwd:ufc_fc2_wgrad': (25347.3, 8192.0), 'bwd:ufc_fc2_dgrad': (14591.8, 12592.0), 'bwd:ufc_mid_bwd': (38884.8, 25711.9), 'bwd:ufc_fc1_wgrad_unfold': (61701.1, 6624.0), 'bwd:ufc_fc1_dgrad_unfold': (26078.5, 12611.2), 'bwd:wgrad_reduce': (14869.7, 1104.0)},
+    'sampled_c512_h7': {'fwd:weight_prep': (6709.6, 1664.0), 'fwd:ufc_fc1_unfold': (7412.6, 6272.9), 'fwd:ufc_mid_fwd': (13052.4, 6322.7), 'fwd:ufc_fc2': (10617.0, 6272.0), 'bwd:ufc_fc2_wgrad': (12804.6, 8192.0), 'bwd:ufc_fc2_dgrad': (10616.9, 6272.0), 'bwd:ufc_mid_bwd': (19622.7, 12648.0), 'bwd:ufc_fc1_wgrad_unfold': (19711.7, 4608.0), 'bwd:ufc_fc1_dgrad_unfold': (13682.6, 6278.0), 'bwd:wgrad_reduce': (12855.8, 6656.0)},
+    'chain_relu': {'fwd:chain_fwd': (50494.8, 56897.6), 'bwd:chain_bwd': (100764.7, 56030.4)},
+    'chain_gate': {'fwd:chain_fwd': (50662.8, 57627.5), 'bwd:chain_bwd': (101068.1, 57927.8)},
+    'chain_shift_residual': {'fwd:chain_fwd': (50649.2, 59868.6), 'bwd:chain_bwd': (100823.2, 57042.1)},
+    'chain_box3': {'fwd:chain_fwd': (55416.3, 51561.4), 'bwd:chain_bwd': (55409.9, 51586.4)},
+    'chain_softmax_c': {'fwd:chain_fwd': (100595.2, 55565.5), 'bwd:chain_bwd': (251269.7, 53517.8)},
+    'fuzz': {'all:chain': (64858.9, 44338.0)},
 }
 
 
